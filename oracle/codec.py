@@ -1,0 +1,213 @@
+"""ctypes view of the C oracle (ha_rag_oracle.c) plus thin numpy conveniences.
+
+Every array is a numpy array on the host.  BF16 and binary16 values travel as
+uint16 words.  Shapes follow the packed-chunk layout described at the top of
+ha_rag_oracle.c.  Precision tags: bits 16 (BF16 words kept verbatim), 8, 4.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
+            _build.build()
+        L = C.CDLL(path)
+        u8p, u16p, f32p = C.POINTER(C.c_uint8), C.POINTER(C.c_uint16), C.POINTER(C.c_float)
+        L.orc_bf16_to_f32.restype = C.c_float
+        L.orc_bf16_to_f32.argtypes = [C.c_uint16]
+        L.orc_f32_to_bf16_rne.restype = C.c_uint16
+        L.orc_f32_to_bf16_rne.argtypes = [C.c_float]
+        L.orc_fp16_to_f64.restype = C.c_double
+        L.orc_fp16_to_f64.argtypes = [C.c_uint16]
+        L.orc_fp16_round_down.restype = C.c_uint16
+        L.orc_fp16_round_down.argtypes = [C.c_float, C.POINTER(C.c_int)]
+        L.orc_fp16_round_up.restype = C.c_uint16
+        L.orc_fp16_round_up.argtypes = [C.c_float, C.POINTER(C.c_int)]
+        L.orc_quantize_group.restype = C.c_int
+        L.orc_quantize_group.argtypes = [f32p, C.c_int, C.c_int, u16p, u16p, u8p]
+        L.orc_dequant_f32.restype = C.c_float
+        L.orc_dequant_f32.argtypes = [C.c_uint, C.c_uint16, C.c_uint16]
+        L.orc_dequant_bf16.restype = C.c_uint16
+        L.orc_dequant_bf16.argtypes = [C.c_uint, C.c_uint16, C.c_uint16]
+        for name in ("orc_tile_blocks",):
+            getattr(L, name).restype = C.c_size_t
+            getattr(L, name).argtypes = [C.c_int, C.c_int]
+        L.orc_tile_payload_bytes.restype = C.c_size_t
+        L.orc_tile_payload_bytes.argtypes = [C.c_int, C.c_int, C.c_int]
+        L.orc_tile_meta_bytes.restype = C.c_size_t
+        L.orc_tile_meta_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int]
+        L.orc_chunk_bytes.restype = C.c_size_t
+        L.orc_chunk_bytes.argtypes = [C.c_int] * 6
+        L.orc_octet_offset.restype = C.c_size_t
+        L.orc_octet_offset.argtypes = [C.c_size_t, C.c_int]
+        L.orc_meta_offset.restype = C.c_size_t
+        L.orc_meta_offset.argtypes = [C.c_size_t, C.c_int]
+        L.orc_quantize_pack_chunk.restype = C.c_long
+        L.orc_quantize_pack_chunk.argtypes = [u16p] + [C.c_int] * 6 + [u8p]
+        L.orc_dequant_scatter_chunk.restype = C.c_int
+        L.orc_dequant_scatter_chunk.argtypes = [u8p] + [C.c_int] * 6 + [u16p, C.c_size_t, C.c_size_t]
+        L.orc_unpack_chunk.restype = C.c_int
+        L.orc_unpack_chunk.argtypes = [u8p] + [C.c_int] * 6 + [u8p, u16p, u16p, u16p]
+        L.orc_rmse_bf16.restype = C.c_double
+        L.orc_rmse_bf16.argtypes = [u16p, u16p, C.c_size_t]
+        _lib = L
+    return _lib
+
+
+def _p(a, ctype):
+    return a.ctypes.data_as(C.POINTER(ctype))
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+# ---- scalars ---------------------------------------------------------------
+def bf16_to_f32(w):
+    return lib().orc_bf16_to_f32(int(w))
+
+
+def f32_to_bf16_rne(f):
+    return lib().orc_f32_to_bf16_rne(float(np.float32(f)))
+
+
+def fp16_to_f64(h):
+    return lib().orc_fp16_to_f64(int(h))
+
+
+def fp16_round_down(x):
+    sat = C.c_int(0)
+    return lib().orc_fp16_round_down(float(np.float32(x)), C.byref(sat)), bool(sat.value)
+
+
+def fp16_round_up(x):
+    sat = C.c_int(0)
+    return lib().orc_fp16_round_up(float(np.float32(x)), C.byref(sat)), bool(sat.value)
+
+
+def dequant_f32(code, scale_h, zero_h):
+    return lib().orc_dequant_f32(int(code), int(scale_h), int(zero_h))
+
+
+def dequant_bf16(code, scale_h, zero_h):
+    return lib().orc_dequant_bf16(int(code), int(scale_h), int(zero_h))
+
+
+# ---- one group ---------------------------------------------------------------
+def quantize_group(x, bits):
+    """x: float32 values of one group.  Returns (scale_h, zero_h, codes, saturated)."""
+    x = _c(x, np.float32)
+    codes = np.zeros(x.size, np.uint8)
+    sh, zh = C.c_uint16(0), C.c_uint16(0)
+    sat = lib().orc_quantize_group(_p(x, C.c_float), x.size, bits, C.byref(sh), C.byref(zh),
+                                   _p(codes, C.c_uint8))
+    return sh.value, zh.value, codes, bool(sat)
+
+
+# ---- layout ----------------------------------------------------------------
+def chunk_bytes(L, H, D, T, bits, g=128):
+    return lib().orc_chunk_bytes(L, H, D, T, bits, g)
+
+
+def tile_payload_bytes(T, D, bits):
+    return lib().orc_tile_payload_bytes(T, D, bits)
+
+
+def tile_meta_bytes(T, D, bits, g):
+    return lib().orc_tile_meta_bytes(T, D, bits, g)
+
+
+def octet_offset(e, bits):
+    return lib().orc_octet_offset(e, bits)
+
+
+def meta_offset(e, g):
+    return lib().orc_meta_offset(e, g)
+
+
+# ---- chunks ------------------------------------------------------------------
+def quantize_pack_chunk(src, bits, g=128):
+    """src: uint16 BF16 words, shape [L][2][H][T][D].  Returns (packed uint8, n_saturated)."""
+    src = _c(src, np.uint16)
+    L, two, H, T, D = src.shape
+    assert two == 2
+    n = chunk_bytes(L, H, D, T, bits, g)
+    if n == 0 and T > 0:
+        raise ValueError("bad shape/bits/group")
+    dst = np.zeros(n, np.uint8)
+    r = lib().orc_quantize_pack_chunk(_p(src, C.c_uint16), L, H, D, T, bits, g, _p(dst, C.c_uint8))
+    if r < 0:
+        raise ValueError("bad shape/bits/group")
+    return dst, int(r)
+
+
+def dequant_scatter_chunk(packed, shape, T, bits, g, out, tok_off):
+    """out: uint16 [L][2][H][cap][D], written in place."""
+    L, H, D = shape
+    assert out.dtype == np.uint16 and out.flags.c_contiguous
+    assert out.shape[0] == L and out.shape[1] == 2 and out.shape[2] == H and out.shape[4] == D
+    packed = _c(packed, np.uint8)
+    assert packed.size >= chunk_bytes(L, H, D, T, bits, g)
+    r = lib().orc_dequant_scatter_chunk(_p(packed, C.c_uint8), L, H, D, T, bits, g,
+                                        _p(out, C.c_uint16), out.shape[3], tok_off)
+    if r != 0:
+        raise ValueError("bad shape or not enough room in out")
+
+
+def unpack_chunk(packed, shape, T, bits, g=128):
+    """Returns (codes [L,2,H,T,D] uint8 or uint16, scale_h, zero_h [L,2,H,T,D//g])."""
+    L, H, D = shape
+    packed = _c(packed, np.uint8)
+    n = L * 2 * H * T * D
+    codes = np.zeros(n, np.uint8)
+    codes16 = np.zeros(n if bits == 16 else 1, np.uint16)
+    ng = n // g if bits != 16 else 1
+    sh = np.zeros(max(ng, 1), np.uint16)
+    zh = np.zeros(max(ng, 1), np.uint16)
+    r = lib().orc_unpack_chunk(_p(packed, C.c_uint8), L, H, D, T, bits, g, _p(codes, C.c_uint8),
+                               _p(codes16, C.c_uint16), _p(sh, C.c_uint16), _p(zh, C.c_uint16))
+    if r != 0:
+        raise ValueError("bad shape")
+    if bits == 16:
+        return codes16.reshape(L, 2, H, T, D), None, None
+    return (codes.reshape(L, 2, H, T, D), sh.reshape(L, 2, H, T, D // g),
+            zh.reshape(L, 2, H, T, D // g))
+
+
+def load_chunks(packed_list, shape, tokens, bits_list, g_list, order, cap_tokens=None,
+                tok_base=0, out=None):
+    """The whole request: chunks gathered in `order`, dequantised and laid one
+    after another along the token axis of one BF16 cache [L][2][H][cap][D]
+    (Sec. 2.1: load, decompress, concatenate).  Returns (out, tok_off list)."""
+    L, H, D = shape
+    total = sum(tokens[c] for c in order)
+    if cap_tokens is None:
+        cap_tokens = tok_base + total
+    if tok_base + total > cap_tokens:
+        raise ValueError("request does not fit in the cache")
+    if out is None:
+        out = np.zeros((L, 2, H, cap_tokens, D), np.uint16)
+    offs = []
+    off = tok_base
+    for c in order:
+        offs.append(off)
+        dequant_scatter_chunk(packed_list[c], shape, tokens[c], bits_list[c], g_list[c], out, off)
+        off += tokens[c]
+    return out, offs
+
+
+def rmse_bf16(a, b):
+    a = _c(a, np.uint16).ravel()
+    b = _c(b, np.uint16).ravel()
+    assert a.size == b.size
+    return lib().orc_rmse_bf16(_p(a, C.c_uint16), _p(b, C.c_uint16), a.size)
