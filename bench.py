@@ -1,0 +1,297 @@
+#!/usr/bin/env python3
+"""Benchmark of the hotness-aware mixed-precision KV-chunk load on one MI355X.
+
+A step is one request through the whole hot path (`ha_rag_load_chunks`: counters,
+tier lookup, descriptors, gather-dequantize-scatter kernel) over chunks already
+resident in the HBM pool.  Headline workload (`--workload hbm8b`): Llama-3-8B
+shaped KV (32 layers, 8 KV heads, head_dim 128), ten 512-token chunks per request
+with the rank-class mix 2 x 16-bit + 3 x int8 + 5 x int4 (group 128), each step
+taking different chunks of a pool much larger than the caches.
+
+Prints ONE JSON line: the metric (GB/s of packed bytes read + BF16 bytes written),
+KV tokens/s, the roofline object for the gather-dequantize-scatter kernel, and
+the CPU oracle timed on this machine's host cores as a baseline.
+
+Other workloads (`--workload cold8b`, `llama70b`, `zipf`) report the same fields
+for the pinned-host path, the 70B shape and the mixed-tier Zipf batch.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+PCIE_PEAK_GBPS = 63.0           # PCIe Gen5 x16, one direction, theoretical
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def per_token_bytes(L, H, D, bits, g):
+    """Algorithmic HBM bytes per KV token: packed bytes read + BF16 bytes written."""
+    elems = L * 2 * H * D
+    read = elems * 2 if bits == 16 else elems * bits // 8 + 4 * elems // g
+    return read, elems * 2
+
+
+def build_hbm_pool(B, wl, torch, ctx, shape, T, g, counts, seed0):
+    """One slab per tag in HBM; every chunk drawn on the device and quantized by the
+    library straight into its slot.  Returns {prec: [ids]}."""
+    L, H, D = shape
+    ids = {}
+    next_id = 0
+    for prec, n in counts.items():
+        if n == 0:
+            ids[prec] = []
+            continue
+        slot = (ctx.chunk_bytes(prec, T) + 255) // 256 * 256
+        slab = torch.empty(slot * n, dtype=torch.uint8, device="cuda")
+        ctx.register_slab(B.TIER_HBM, prec, slab)
+        ids[prec] = list(range(next_id, next_id + n))
+        next_id += n
+        for cid in ids[prec]:
+            src = wl.kv_chunk_device(L, H, D, T, seed0 + cid)
+            ctx.pool_insert(cid, prec, T, None, B.TIER_HBM)
+            ptr, _ = ctx.pool_slot(cid, B.TIER_HBM)
+            ctx.quantize_chunk(src, T, prec, g, ptr)
+        torch.cuda.synchronize()
+    return ids
+
+
+def cpu_baseline(shape, T, g, mix, layers_sampled, seed):
+    """The oracle's dequantize-scatter, single thread, on the first `layers_sampled`
+    layers of one request of the same mix."""
+    import numpy as np
+    from oracle import codec
+    from paper_2510_20878_amd import workloads as wl
+
+    L, H, D = shape
+    Ls = min(L, layers_sampled)
+    packed, bits_list = [], []
+    for i, bits in enumerate(mix):
+        src = wl.kv_chunk(Ls, H, D, T, seed + i)
+        packed.append(codec.quantize_pack_chunk(src, bits, g)[0])
+        bits_list.append(bits)
+    n = len(mix)
+    out = np.zeros((Ls, 2, H, n * T, D), np.uint16)
+    t0 = time.perf_counter()
+    codec.load_chunks(packed, (Ls, H, D), [T] * n, bits_list, [g] * n, list(range(n)), out=out,
+                      cap_tokens=n * T)
+    dt = time.perf_counter() - t0
+    nbytes = sum(sum(per_token_bytes(Ls, H, D, b, g)) * T for b in mix)
+    return {
+        "value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": f"dequantize-scatter of one request ({n} chunks x {T} tokens, bits {mix}), "
+                  f"first {Ls} of {L} layers, {dt:.1f} s",
+        "kv_tokens_per_s": n * T * (Ls / L) / dt,
+    }
+
+
+def run_hbm(args, B, wl, torch, name):
+    if name == "hbm8b":
+        shape, T, g = (32, 8, 128), 512, 128
+        mix = [16] * 2 + [8] * 3 + [4] * 5
+        frac = {B.PREC_16: 0.2, B.PREC_INT8: 0.3, B.PREC_INT4: 0.5}
+        desc = ("Llama-3-8B KV (32 layers, 8 KV heads, head_dim 128, bf16 source): top-10 chunks x "
+                "512 tokens per request from an HBM pool, 2x16-bit + 3xint8 + 5xint4, group 128")
+    else:  # llama70b
+        shape, T, g = (80, 8, 128), 1024, 128
+        mix = [8, 4] * 8
+        frac = {B.PREC_16: 0.0, B.PREC_INT8: 0.5, B.PREC_INT4: 0.5}
+        desc = ("Llama-3-70B KV (80 layers, 8 KV heads, head_dim 128): 16 chunks x 1024 tokens per "
+                "request, 8xint8 + 8xint4 alternating, group 128")
+    L, H, D = shape
+    n_pool = args.pool_chunks
+    counts = {p: int(round(f * n_pool)) for p, f in frac.items()}
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g)
+    if args.threads:
+        ctx.set_launch_params(args.threads, args.blocks_per_wave, args.nontemporal)
+    t0 = time.time()
+    ids = build_hbm_pool(B, wl, torch, ctx, shape, T, g, counts, seed0=args.seed * 1_000_003)
+    pool_bytes = sum(ctx.chunk_bytes(p, T) * n for p, n in counts.items())
+    log(f"pool: {counts} chunks, {pool_bytes / 2**30:.1f} GiB packed, built in {time.time() - t0:.1f} s")
+
+    import numpy as np
+    rng = np.random.Generator(np.random.PCG64(args.seed))
+    n_req = len(mix)
+    per = {B.PREC_OF_BITS[b]: mix.count(b) for b in set(mix)}
+    cursor = {p: 0 for p in per}
+
+    def next_request():
+        req = []
+        for p, k in per.items():
+            pool = ids[p]
+            for _ in range(k):
+                req.append(pool[cursor[p] % len(pool)])
+                cursor[p] += 1
+        return [req[i] for i in rng.permutation(n_req)]
+
+    cap = n_req * T
+    n_out = args.out_buffers
+    outs = [torch.empty((L, 2, H, cap, D), dtype=torch.bfloat16, device="cuda") for _ in range(n_out)]
+    stream = torch.cuda.Stream()
+    reqs = [next_request() for _ in range(args.warmup + args.steps)]
+
+    step_bytes = sum(sum(per_token_bytes(L, H, D, b, g)) * T for b in mix)
+    step_tokens = n_req * T
+    with torch.cuda.stream(stream):
+        for k in range(args.warmup):
+            ctx.load_chunks(reqs[k], outs[k % n_out], cap, stream=stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for k in range(args.warmup, args.warmup + args.steps):
+            ctx.load_chunks(reqs[k], outs[k % n_out], cap, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = wall * 1e3 / args.steps
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    kernel_ms = ev_ms / args.steps                # one kernel launch per step
+    achieved = step_bytes / (kernel_ms * 1e-3) / 1e9
+    ctx.destroy()
+    res = {
+        "metric": "kv_load_gbps", "value": value, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": desc, "pool_chunks": n_pool, "pool_gib": round(pool_bytes / 2**30, 1),
+                   "tokens_per_step": step_tokens, "bytes_per_step": step_bytes,
+                   "launch": {"threads": args.threads or 256, "blocks_per_wave": args.blocks_per_wave,
+                              "nontemporal": bool(args.nontemporal)}},
+        "kv_tokens_per_s": step_tokens / (ms_per_step * 1e-3),
+        "hbm_fraction_whole_path": value / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "k1_gather_dequant_scatter", "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": args.traffic_bytes, "kernel_ms": kernel_ms,
+                     "algorithmic_bytes_per_launch": step_bytes},
+    }
+    return res, (shape, T, g, mix)
+
+
+def run_cold(args, B, wl, torch):
+    """All chunks int4 (group 64) in pinned host memory, 8B shape, 1024-token chunks,
+    32 chunks per request, 4 requests in flight on 4 streams."""
+    shape, T, g = (32, 8, 128), 1024, 64
+    L, H, D = shape
+    n_streams, per_req = 4, 32
+    prec = B.PREC_INT4
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=0, n_copy_streams=args.copy_streams)
+    cb = ctx.chunk_bytes(prec, T)
+    slot = (cb + 255) // 256 * 256
+    n_pool = n_streams * per_req
+    pinned = torch.empty(slot * n_pool, dtype=torch.uint8).pin_memory()
+    ctx.register_slab(B.TIER_PINNED, prec, pinned)
+    staging = torch.empty(slot * args.staging_slots, dtype=torch.uint8, device="cuda")
+    ctx.register_staging(staging)
+    tmp = torch.empty(cb, dtype=torch.uint8, device="cuda")
+    t0 = time.time()
+    for cid in range(n_pool):
+        src = wl.kv_chunk_device(L, H, D, T, args.seed * 7919 + cid)
+        ctx.quantize_chunk(src, T, prec, g, tmp)
+        ctx.pool_insert(cid, prec, T, tmp, B.TIER_PINNED, packed_is_device=True)
+        torch.cuda.synchronize()
+    log(f"cold pool: {n_pool} chunks, {cb * n_pool / 2**30:.2f} GiB pinned, built in {time.time() - t0:.1f} s")
+    cap = per_req * T
+    outs = [torch.empty((L, 2, H, cap, D), dtype=torch.bfloat16, device="cuda") for _ in range(n_streams)]
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+
+    # bare pinned -> device copy rate of this machine, for reference
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    dst = torch.empty(slot * 8, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(4):
+        dst.copy_(pinned[:slot * 8], non_blocking=True)
+    e1.record()
+    torch.cuda.synchronize()
+    bare = 4 * slot * 8 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    def step():
+        for r in range(n_streams):
+            ctx.load_chunks(list(range(r * per_req, (r + 1) * per_req)), outs[r], cap, stream=streams[r])
+
+    steps, warmup = max(1, min(args.steps, 20)), max(1, min(args.warmup, 2))
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ctx.destroy()
+    link_bytes = cb * n_pool
+    ms = wall * 1e3 / steps
+    link = link_bytes / (ms * 1e-3) / 1e9
+    tokens = n_pool * T
+    return {
+        "metric": "kv_load_gbps", "value": link, "unit": "GB/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "cold path: 4 concurrent requests x 32 int4/g64 chunks x 1024 tokens "
+                               "(Llama-3-8B KV shape), all in pinned host memory",
+                   "staging_slots": args.staging_slots, "copy_streams": args.copy_streams or 2,
+                   "link_bytes_per_step": link_bytes},
+        "kv_tokens_per_s": tokens / (ms * 1e-3),
+        "roofline": {"bound": "pcie", "achieved": link, "peak": PCIE_PEAK_GBPS, "unit": "GB/s",
+                     "frac": link / PCIE_PEAK_GBPS, "bare_pinned_memcpy_gbps": bare,
+                     "frac_of_bare_memcpy": link / bare, "traffic": None},
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="hbm8b", choices=["hbm8b", "llama70b", "cold8b"])
+    ap.add_argument("--pool-chunks", type=int, default=0, help="chunks in the HBM pool (0 = default)")
+    ap.add_argument("--out-buffers", type=int, default=4)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--threads", type=int, default=0, help="kernel launch shape override")
+    ap.add_argument("--blocks-per-wave", type=int, default=4)
+    ap.add_argument("--nontemporal", type=int, default=1)
+    ap.add_argument("--staging-slots", type=int, default=8)
+    ap.add_argument("--copy-streams", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=16)
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per launch from rocprofv3 counters (see profiles/), if known")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+                 "use --gpus 1")
+
+    import torch
+    from paper_2510_20878_amd import binding as B
+    from paper_2510_20878_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the load path has no CPU fallback")
+    B.lib()
+    torch.cuda.set_device(0)
+    if args.workload == "cold8b":
+        res = run_cold(args, B, wl, torch)
+        shape, T, g, mix = (32, 8, 128), 1024, 64, [4] * 8
+    else:
+        if args.pool_chunks == 0:
+            args.pool_chunks = 2000 if args.workload == "hbm8b" else 400
+        res, (shape, T, g, mix) = run_hbm(args, B, wl, torch, args.workload)
+    if not args.no_cpu_baseline:
+        t0 = time.time()
+        res["cpu_baseline"] = cpu_baseline(shape, T, g, mix, args.cpu_layers, seed=12345)
+        log(f"cpu baseline took {time.time() - t0:.1f} s in all")
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,286 @@
+/*
+ * ha_rag.h -- C ABI of the MI355X (gfx950) hotness-aware mixed-precision KV-chunk
+ * load: the hot path of HA-RAG ("HA-RAG: Hotness-Aware RAG Acceleration via Mixed
+ * Precision and Data Placement").
+ *
+ * A *chunk* is the precomputed K and V of one retrieved document (Sec. 1: the
+ * KV of each document chunk is computed once, stored, and loaded on demand),
+ * shape [L layers][2 = K,V][H kv heads][T tokens][D head_dim], BF16 at full
+ * precision (Sec. 2.2.1).  Offline, each chunk is compressed to a precision
+ * chosen from its access-frequency rank (Algorithm 1); online, the chunks a
+ * request retrieved are looked up in a tiered pool (Algorithm 2: GPU memory, then
+ * pinned host memory), moved to the GPU if needed, decompressed and laid one
+ * after another along the token axis of one BF16 KV cache
+ * out[L][2][H][cap_tokens][D] that prefill can consume (Sec. 2.1, Fig. 3).
+ *
+ * Conventions
+ *  - Every function returns HA_RAG_OK (0) or a negative HA_RAG_E* code; nothing
+ *    throws or aborts across this boundary.
+ *  - "device pointer" = HBM address valid on the current HIP device; "host
+ *    pointer" = ordinary host memory; "pinned pointer" = page-locked host memory
+ *    (hipHostMalloc or equivalent).  The CALLER allocates and owns every device
+ *    and pinned buffer; the library allocates host metadata, HIP events and its
+ *    copy streams only, and never calls hipMalloc.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  GPU
+ *    work is enqueued, not awaited: results are valid once the caller has
+ *    synchronised `stream`.
+ *  - Precision tags: HA_RAG_PREC_16 keeps the BF16 words verbatim; INT8 / INT4
+ *    are unsigned codes with one fp16 scale and one fp16 zero per group of
+ *    `group` consecutive head_dim elements (value = code * scale + zero).  The
+ *    paper fixes only the code range of its integer scheme (Sec. 2.2.2); scale,
+ *    zero, group and byte layout are this library's format.
+ *  - Packed byte layout of a chunk: tile records (l*2+kv)*H+h back to back; a tile
+ *    is cut into blocks of 2048 elements (last one zero padded); payload blocks
+ *    (256*bits bytes each) first, then meta blocks (2048/group entries of
+ *    {u16 scale, u16 zero}).  Element r of a block: plane j=r/512, lane i=(r%512)/8,
+ *    position p=r%8; the octet (j,i) starts at byte (j/P)*1024 + i*16 + (j%P)*bits
+ *    of its payload block, P = 16/bits; group G=r/group is meta entry
+ *    (G % (512/group))*4 + G/(512/group).
+ *  - A context is not thread safe against itself: calls on one context are
+ *    serialised by an internal mutex; calls that overlap on the GPU are ordered
+ *    by the streams and events described at each function.
+ */
+#ifndef HA_RAG_H
+#define HA_RAG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HA_RAG_OK 0
+#define HA_RAG_EINVAL (-1)  /* null pointer, bad size, duplicate id, misaligned buffer  */
+#define HA_RAG_ENOENT (-2)  /* unknown chunk id                                          */
+#define HA_RAG_ENOSPC (-3)  /* pool slab full, output cache too small, staging too small */
+#define HA_RAG_EFORMAT (-4) /* tag / group / shape mismatch                              */
+#define HA_RAG_EHIP (-5)    /* a HIP call failed; see ha_rag_last_hip_error              */
+
+#define HA_RAG_PREC_16 0
+#define HA_RAG_PREC_INT8 1
+#define HA_RAG_PREC_INT4 2
+#define HA_RAG_N_PREC 3
+
+#define HA_RAG_TIER_HBM 0    /* queueGPU of Algorithm 2 */
+#define HA_RAG_TIER_PINNED 1 /* queuePIN of Algorithm 2 */
+#define HA_RAG_TIER_NONE 255
+
+#define HA_RAG_NO_CHUNK UINT64_MAX
+#define HA_RAG_MAX_REQUEST_CHUNKS 4096
+
+typedef struct ha_rag_ctx ha_rag_ctx;
+
+typedef struct ha_rag_config {
+    uint32_t n_layers;         /* L                                                        */
+    uint32_t n_kv_heads;       /* H                                                        */
+    uint32_t head_dim;         /* D, multiple of 8                                         */
+    uint32_t max_chunk_tokens; /* slot size of every slab is that of a chunk this long     */
+    uint32_t group_int8;       /* group size of the INT8 tag: 32..512, power of 2, | D     */
+    uint32_t group_int4;       /* group size of the INT4 tag                               */
+    uint32_t tau_gpu_ppm;      /* Algorithm 2 step 1: GPU_LIST = ranks below
+                                  floor(tau_gpu_ppm * N / 1e6), N = chunks in the pool     */
+    uint32_t rerank_interval;  /* recompute ranks after this many load calls; 0 = only in
+                                  ha_rag_rerank                                            */
+    uint32_t n_copy_streams;   /* streams for pinned -> HBM copies (0 = 2, at most 8)      */
+    uint32_t dry_run;          /* 1 = host bookkeeping only: no HIP call is ever made, no
+                                  byte is moved (for host-logic tests without a GPU)      */
+} ha_rag_config;
+
+/* One packed chunk handed to ha_rag_load_packed (no pool involved). */
+typedef struct ha_rag_packed_chunk {
+    const void *packed; /* device pointer, 16-byte aligned, ha_rag_chunk_bytes() bytes */
+    uint32_t n_tokens;
+    uint32_t prec;      /* HA_RAG_PREC_*                                                */
+    uint32_t group;     /* ignored for HA_RAG_PREC_16                                   */
+    uint32_t reserved;
+} ha_rag_packed_chunk;
+
+typedef struct ha_rag_chunk_info {
+    uint32_t prec, group, n_tokens;
+    uint32_t in_hbm, in_pinned; /* 0 / 1                                      */
+    uint32_t rank;              /* 0 = hottest, as of the last rerank         */
+    uint64_t count;             /* accesses so far (Algorithm 1's AF entry)   */
+    uint64_t bytes;             /* packed size                                */
+    const void *hbm_ptr;        /* slot address or NULL                       */
+    const void *pinned_ptr;     /* slot address or NULL                       */
+} ha_rag_chunk_info;
+
+/* What happened to one chunk of a load (Algorithm 2 step 2, per C_i). */
+typedef struct ha_rag_chunk_trace {
+    uint64_t tok_off;     /* first token row of this chunk in the cache        */
+    uint64_t evicted_id;  /* chunk dropped from HBM to make room, or NO_CHUNK  */
+    uint8_t found_tier;   /* HA_RAG_TIER_HBM or HA_RAG_TIER_PINNED             */
+    uint8_t promoted;     /* 1 = copied into the HBM slab by this load         */
+    uint8_t promote_skipped; /* 1 = in GPU_LIST but no slot could be freed     */
+    uint8_t reserved[5];
+} ha_rag_chunk_trace;
+
+typedef struct ha_rag_load_stats {
+    uint32_t n_chunks, n_hbm_hits, n_pinned_hits;
+    uint32_t n_promoted, n_evicted, n_promote_skipped, n_kernel_launches, reserved;
+    uint64_t tokens;
+    uint64_t bytes_h2d;          /* packed bytes copied pinned -> HBM staging        */
+    uint64_t bytes_d2d;          /* packed bytes copied staging -> HBM slab          */
+    uint64_t packed_bytes_read;  /* payload + meta bytes the kernels read            */
+    uint64_t bf16_bytes_written; /* bytes written to the cache                       */
+} ha_rag_load_stats;
+
+/* ---- stateless helpers (no context, no GPU) ------------------------------- */
+
+/* Packed size of a chunk in the layout described above.  `payload`, `meta`,
+ * `total` may each be NULL.  EFORMAT if D % 8, group not in {32..512} power of two
+ * or not dividing D (group is ignored for PREC_16), unknown prec. */
+int ha_rag_chunk_bytes(uint32_t n_layers, uint32_t n_kv_heads, uint32_t head_dim,
+                       uint32_t prec, uint32_t group, uint32_t n_tokens,
+                       size_t *payload, size_t *meta, size_t *total);
+
+/* Algorithm 1 steps 1-2: sort the n chunks by access frequency `af` (descending;
+ * equal counts by ascending index), cut at idx_k = floor(tau_ppm[k] * n / 1e6) +
+ * idx_{k-1}, and write the class (0 = hottest .. n_tau = coldest) of every chunk to
+ * cls_out[n].  rank_out[n] (nullable) receives each chunk's position in the sort.
+ * Host pointers. */
+int ha_rag_alg1_classes(const uint64_t *af, size_t n, const uint32_t *tau_ppm, uint32_t n_tau,
+                        uint8_t *cls_out, uint32_t *rank_out);
+
+const char *ha_rag_strerror(int code);
+const char *ha_rag_version(void);
+
+/* ---- context --------------------------------------------------------------- */
+
+/* Validates the configuration (EINVAL / EFORMAT) and creates a context with empty
+ * pools.  Creates the copy streams unless dry_run. */
+int ha_rag_create(const ha_rag_config *cfg, ha_rag_ctx **out);
+
+/* Destroys events, copy streams and host metadata.  Synchronises the copy streams
+ * first.  The caller's buffers are not touched. */
+int ha_rag_destroy(ha_rag_ctx *ctx);
+
+/* Name of the last failing HIP call and its error string ("" if none). */
+const char *ha_rag_last_hip_error(ha_rag_ctx *ctx);
+
+/* Launch shape of the gather-dequantize-scatter kernel: threads per workgroup
+ * (64..1024, multiple of 64), blocks of 2048 elements each wave handles (1, 2, 4
+ * or 8), nontemporal (streaming) stores on/off.  For tuning sweeps; the defaults
+ * are the measured best. */
+int ha_rag_set_launch_params(ha_rag_ctx *ctx, uint32_t threads, uint32_t blocks_per_wave,
+                             uint32_t nontemporal);
+
+/* ---- offline: quantize + pack (Algorithm 1 step 3, Compression(S_i, chunk)) -- */
+
+/* src  device pointer, BF16 [L][2][H][n_tokens][D] contiguous, 16-byte aligned,
+ *      finite values.
+ * dst  device pointer, 16-byte aligned, ha_rag_chunk_bytes() bytes; every byte is
+ *      written (padding included).  May be a pool slot (ha_rag_pool_slot).
+ * saturated  nullable device pointer to a u32 the kernel adds to: the number of
+ *      groups whose zero or scale left the fp16 range (then stored as +-65504).
+ * Per group: zero = min rounded toward -inf to fp16, scale = (max - zero)/(2^b-1)
+ * in fp32 rounded toward +inf to fp16, code = clamp(rint((x - zero)/scale)) in fp32.
+ * EFORMAT on prec/group/shape; EINVAL on null or misaligned pointers. */
+int ha_rag_quantize_chunk(ha_rag_ctx *ctx, const void *src, uint32_t n_tokens, uint32_t prec,
+                          uint32_t group, void *dst, uint32_t *saturated, void *stream);
+
+/* ---- online, no pool: gather-dequantize-scatter of caller-held packed chunks -- */
+
+/* Chunk i of `chunks[n]` (host array, n <= HA_RAG_MAX_REQUEST_CHUNKS) is
+ * dequantized as bf16_rne(fma(code, scale, zero)) (16-bit tag: copied) into token
+ * rows [tok_base + sum_{j<i} n_tokens_j, ...) of every (layer, K/V, head) tile of
+ * out[L][2][H][cap_tokens][D] (device, BF16, 16-byte aligned).  Rows outside those
+ * ranges are not written.  ENOSPC if the chunks do not fit, before anything is
+ * enqueued.  One kernel launch per 64 chunks. */
+int ha_rag_load_packed(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks, uint32_t n,
+                       void *out, uint64_t cap_tokens, uint64_t tok_base, void *stream);
+
+/* ---- pools (Algorithm 2's queueGPU / queuePIN) ------------------------------ */
+
+/* Gives the context a slab for chunks of tag `prec` in `tier`: `base` is a device
+ * pointer (TIER_HBM) or a pinned pointer (TIER_PINNED), 256-byte aligned.  It is
+ * cut into fixed slots of ha_rag_chunk_bytes(prec, group_of(prec),
+ * max_chunk_tokens) rounded up to 256 bytes.  One slab per (tier, prec); EINVAL if
+ * registered twice or smaller than one slot. */
+int ha_rag_register_slab(ha_rag_ctx *ctx, uint32_t tier, uint32_t prec, void *base, size_t bytes);
+
+/* Device staging area that cold chunks pass through on their way from pinned
+ * memory to the kernel (256-byte aligned).  It is cut into slots as large as the
+ * largest pinned-slab slot registered so far; at least 2 slots are required. */
+int ha_rag_register_staging(ha_rag_ctx *ctx, void *base, size_t bytes);
+
+/* Adds chunk `id` (tag `prec`, group = the context's group for that tag) to
+ * `tier`.  If `packed` is non-NULL its ha_rag_chunk_bytes() bytes are copied into
+ * the slot on `stream` (`packed_is_device` says where they are; host sources
+ * should be pinned); if NULL the slot is only reserved and the caller fills it
+ * (ha_rag_pool_slot + ha_rag_quantize_chunk).  Inserting an id that exists in the
+ * other tier adds the second copy (same tag and n_tokens required, else EFORMAT);
+ * the pinned copy is the master, an HBM-only chunk is never evicted.
+ * EINVAL duplicate in that tier; ENOSPC slab full (pinned), or full of
+ * unevictable chunks (HBM; otherwise the least recently used evictable chunk of
+ * that slab is dropped). */
+int ha_rag_pool_insert(ha_rag_ctx *ctx, uint64_t id, uint32_t prec, uint32_t n_tokens,
+                       const void *packed, int packed_is_device, uint32_t tier, void *stream);
+
+/* Address and size of the slot that holds chunk `id` in `tier` (ENOENT if not
+ * there). */
+int ha_rag_pool_slot(ha_rag_ctx *ctx, uint64_t id, uint32_t tier, void **ptr, size_t *bytes);
+
+/* Copies the pinned master of `id` into an HBM slot on `stream` regardless of its
+ * rank (no-op if already there); LRU eviction as in insert.  ENOENT / ENOSPC. */
+int ha_rag_pool_promote(ha_rag_ctx *ctx, uint64_t id, void *stream);
+
+/* Drops the HBM copy of `id` (EINVAL if it has no pinned master, ENOENT if not in
+ * HBM).  The slot is reused only after the loads that read it have finished. */
+int ha_rag_pool_evict(ha_rag_ctx *ctx, uint64_t id);
+
+int ha_rag_pool_query(ha_rag_ctx *ctx, uint64_t id, ha_rag_chunk_info *info);
+
+/* Ids resident in HBM, least recently used first; returns how many were written
+ * (at most `cap`) through *n. */
+int ha_rag_pool_hbm_lru(ha_rag_ctx *ctx, uint64_t *ids, size_t cap, size_t *n);
+
+/* ---- hotness (Algorithm 1 step 1, Algorithm 2 step 1) ------------------------ */
+
+/* counts[id] += 1 for each listed id (ENOENT if one is unknown; none is counted
+ * then).  ha_rag_load_chunks does this itself. */
+int ha_rag_touch(ha_rag_ctx *ctx, const uint64_t *ids, size_t n);
+
+/* Overwrites the access counts (an offline profile AF). */
+int ha_rag_set_counts(ha_rag_ctx *ctx, const uint64_t *ids, const uint64_t *counts, size_t n);
+
+/* Sorts all chunks by count (descending, ties by ascending id), assigns ranks and
+ * recomputes the GPU_LIST boundary floor(tau_gpu_ppm * N / 1e6). */
+int ha_rag_rerank(ha_rag_ctx *ctx);
+
+int ha_rag_get_rank(ha_rag_ctx *ctx, uint64_t id, uint32_t *rank);
+
+/* ---- online: the load (Algorithm 2 step 2 + decompression + concatenation) --- */
+
+/* For each id in request order: count the access; if the chunk is in HBM, read it
+ * there (refreshing its LRU position); else copy its pinned master into a staging
+ * slot on a copy stream and make `stream` wait for that copy; dequantize-scatter
+ * it to its token rows; and if its rank is in GPU_LIST, copy it from staging into
+ * an HBM slot (evicting the least recently used evictable chunk of that slab if
+ * full; skipped, not an error, if nothing can be evicted).
+ *   tags   nullable host array of HA_RAG_PREC_*; if given, tags[i] must equal the
+ *          stored tag of ids[i] (EFORMAT otherwise)
+ *   out    device BF16 [L][2][H][cap_tokens][D]; chunk i starts at token row
+ *          tok_base + sum of the token counts before it
+ *   stats, trace  nullable host outputs (trace has n entries)
+ * All checks (ENOENT, EFORMAT, ENOSPC for the cache, staging missing while a
+ * chunk is cold) happen before any state changes or work is enqueued.  A slot
+ * that another stream's load may still read is not overwritten before that load
+ * has finished (the library records an event per stream after each load). */
+int ha_rag_load_chunks(ha_rag_ctx *ctx, const uint64_t *ids, const uint8_t *tags, uint32_t n,
+                       void *out, uint64_t cap_tokens, uint64_t tok_base, void *stream,
+                       ha_rag_load_stats *stats, ha_rag_chunk_trace *trace);
+
+/* A batch of requests in one call: request r owns ids[request_starts[r] ..
+ * request_starts[r+1]) and is written to outs[r] (cap_tokens[r], tok_base[r]).
+ * Hot chunks of all requests share kernel launches. */
+int ha_rag_load_batch(ha_rag_ctx *ctx, const uint64_t *ids, const uint8_t *tags,
+                      const uint32_t *request_starts, uint32_t n_requests, void *const *outs,
+                      const uint64_t *cap_tokens, const uint64_t *tok_base, void *stream,
+                      ha_rag_load_stats *stats, ha_rag_chunk_trace *trace);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HA_RAG_H */

@@ -1,0 +1,325 @@
+"""ctypes binding of include/ha_rag.h: same names, argument marshalling only.
+
+Device and pinned buffers are torch tensors (or raw integer addresses); this
+module passes their addresses through and never computes on them.  If the built
+library is missing the import of this module still works, but the first call
+raises: there is no CPU fallback.
+"""
+import ctypes as C
+import os
+
+from . import build as _build
+
+OK, EINVAL, ENOENT, ENOSPC, EFORMAT, EHIP = 0, -1, -2, -3, -4, -5
+PREC_16, PREC_INT8, PREC_INT4 = 0, 1, 2
+TIER_HBM, TIER_PINNED = 0, 1
+NO_CHUNK = 2**64 - 1
+BITS = {PREC_16: 16, PREC_INT8: 8, PREC_INT4: 4}
+PREC_OF_BITS = {16: PREC_16, 8: PREC_INT8, 4: PREC_INT4}
+
+# every function include/ha_rag.h declares
+SYMBOLS = [
+    "ha_rag_chunk_bytes", "ha_rag_alg1_classes", "ha_rag_strerror", "ha_rag_version",
+    "ha_rag_create", "ha_rag_destroy", "ha_rag_last_hip_error", "ha_rag_set_launch_params",
+    "ha_rag_quantize_chunk", "ha_rag_load_packed", "ha_rag_register_slab",
+    "ha_rag_register_staging", "ha_rag_pool_insert", "ha_rag_pool_slot", "ha_rag_pool_promote",
+    "ha_rag_pool_evict", "ha_rag_pool_query", "ha_rag_pool_hbm_lru", "ha_rag_touch",
+    "ha_rag_set_counts", "ha_rag_rerank", "ha_rag_get_rank", "ha_rag_load_chunks",
+    "ha_rag_load_batch",
+]
+
+
+class Config(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in (
+        "n_layers", "n_kv_heads", "head_dim", "max_chunk_tokens", "group_int8", "group_int4",
+        "tau_gpu_ppm", "rerank_interval", "n_copy_streams", "dry_run")]
+
+
+class PackedChunk(C.Structure):
+    _fields_ = [("packed", C.c_void_p), ("n_tokens", C.c_uint32), ("prec", C.c_uint32),
+                ("group", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class ChunkInfo(C.Structure):
+    _fields_ = [("prec", C.c_uint32), ("group", C.c_uint32), ("n_tokens", C.c_uint32),
+                ("in_hbm", C.c_uint32), ("in_pinned", C.c_uint32), ("rank", C.c_uint32),
+                ("count", C.c_uint64), ("bytes", C.c_uint64),
+                ("hbm_ptr", C.c_void_p), ("pinned_ptr", C.c_void_p)]
+
+
+class ChunkTrace(C.Structure):
+    _fields_ = [("tok_off", C.c_uint64), ("evicted_id", C.c_uint64), ("found_tier", C.c_uint8),
+                ("promoted", C.c_uint8), ("promote_skipped", C.c_uint8),
+                ("reserved", C.c_uint8 * 5)]
+
+
+class LoadStats(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in (
+        "n_chunks", "n_hbm_hits", "n_pinned_hits", "n_promoted", "n_evicted",
+        "n_promote_skipped", "n_kernel_launches", "reserved")] + [(n, C.c_uint64) for n in (
+            "tokens", "bytes_h2d", "bytes_d2d", "packed_bytes_read", "bf16_bytes_written")]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}
+
+
+class HaRagError(RuntimeError):
+    def __init__(self, code, where, detail=""):
+        self.code = code
+        msg = f"{where}: {strerror(code)} ({code})"
+        if detail:
+            msg += f" [{detail}]"
+        super().__init__(msg)
+
+
+_lib = None
+
+
+def lib_path():
+    return _build.LIB
+
+
+def lib():
+    """Loads lib/libha_rag.so.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise RuntimeError(
+                f"{path} is missing: build it first (python -m paper_2510_20878_amd.build or "
+                "__graft_entry__.build()); there is no fallback path")
+        L = C.CDLL(path)
+        vp, u32, u64, sz = C.c_void_p, C.c_uint32, C.c_uint64, C.c_size_t
+        P = C.POINTER
+        sig = {
+            "ha_rag_chunk_bytes": (C.c_int, [u32] * 6 + [P(sz)] * 3),
+            "ha_rag_alg1_classes": (C.c_int, [P(u64), sz, P(u32), u32, P(C.c_uint8), P(u32)]),
+            "ha_rag_strerror": (C.c_char_p, [C.c_int]),
+            "ha_rag_version": (C.c_char_p, []),
+            "ha_rag_create": (C.c_int, [P(Config), P(vp)]),
+            "ha_rag_destroy": (C.c_int, [vp]),
+            "ha_rag_last_hip_error": (C.c_char_p, [vp]),
+            "ha_rag_set_launch_params": (C.c_int, [vp, u32, u32, u32]),
+            "ha_rag_quantize_chunk": (C.c_int, [vp, vp, u32, u32, u32, vp, vp, vp]),
+            "ha_rag_load_packed": (C.c_int, [vp, P(PackedChunk), u32, vp, u64, u64, vp]),
+            "ha_rag_register_slab": (C.c_int, [vp, u32, u32, vp, sz]),
+            "ha_rag_register_staging": (C.c_int, [vp, vp, sz]),
+            "ha_rag_pool_insert": (C.c_int, [vp, u64, u32, u32, vp, C.c_int, u32, vp]),
+            "ha_rag_pool_slot": (C.c_int, [vp, u64, u32, P(vp), P(sz)]),
+            "ha_rag_pool_promote": (C.c_int, [vp, u64, vp]),
+            "ha_rag_pool_evict": (C.c_int, [vp, u64]),
+            "ha_rag_pool_query": (C.c_int, [vp, u64, P(ChunkInfo)]),
+            "ha_rag_pool_hbm_lru": (C.c_int, [vp, P(u64), sz, P(sz)]),
+            "ha_rag_touch": (C.c_int, [vp, P(u64), sz]),
+            "ha_rag_set_counts": (C.c_int, [vp, P(u64), P(u64), sz]),
+            "ha_rag_rerank": (C.c_int, [vp]),
+            "ha_rag_get_rank": (C.c_int, [vp, u64, P(u32)]),
+            "ha_rag_load_chunks": (C.c_int, [vp, P(u64), P(C.c_uint8), u32, vp, u64, u64, vp,
+                                             P(LoadStats), P(ChunkTrace)]),
+            "ha_rag_load_batch": (C.c_int, [vp, P(u64), P(C.c_uint8), P(u32), u32, P(vp), P(u64),
+                                            P(u64), vp, P(LoadStats), P(ChunkTrace)]),
+        }
+        for name, (res, args) in sig.items():
+            f = getattr(L, name)
+            f.restype, f.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def strerror(code):
+    return lib().ha_rag_strerror(code).decode()
+
+
+def version():
+    return lib().ha_rag_version().decode()
+
+
+def _addr(x):
+    """Address of a torch tensor / numpy array / int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if hasattr(x, "ctypes"):
+        return x.ctypes.data
+    raise TypeError(type(x))
+
+
+def _stream(s):
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return s
+    return s.cuda_stream  # torch.cuda.Stream
+
+
+def _u64s(ids):
+    return (C.c_uint64 * len(ids))(*[int(i) for i in ids])
+
+
+def ha_rag_chunk_bytes(L, H, D, prec, group, n_tokens):
+    """Returns (payload, meta, total) bytes."""
+    p, m, t = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    rc = lib().ha_rag_chunk_bytes(L, H, D, prec, group, n_tokens, C.byref(p), C.byref(m), C.byref(t))
+    if rc:
+        raise HaRagError(rc, "ha_rag_chunk_bytes")
+    return p.value, m.value, t.value
+
+
+def ha_rag_alg1_classes(af, tau_ppm):
+    """Returns (classes, ranks) lists."""
+    n = len(af)
+    a = _u64s(af)
+    t = (C.c_uint32 * len(tau_ppm))(*tau_ppm)
+    cls = (C.c_uint8 * max(n, 1))()
+    rk = (C.c_uint32 * max(n, 1))()
+    rc = lib().ha_rag_alg1_classes(a, n, t, len(tau_ppm), cls, rk)
+    if rc:
+        raise HaRagError(rc, "ha_rag_alg1_classes")
+    return list(cls[:n]), list(rk[:n])
+
+
+class Context:
+    """Owns one ha_rag_ctx.  Methods carry the C names without the prefix."""
+
+    def __init__(self, n_layers, n_kv_heads, head_dim, max_chunk_tokens, group_int8=128,
+                 group_int4=128, tau_gpu_ppm=50_000, rerank_interval=0, n_copy_streams=0,
+                 dry_run=False):
+        self.cfg = Config(n_layers, n_kv_heads, head_dim, max_chunk_tokens, group_int8, group_int4,
+                          tau_gpu_ppm, rerank_interval, n_copy_streams, 1 if dry_run else 0)
+        self._h = C.c_void_p()
+        rc = lib().ha_rag_create(C.byref(self.cfg), C.byref(self._h))
+        if rc:
+            raise HaRagError(rc, "ha_rag_create")
+        self._keep = []  # tensors registered as slabs stay alive with the context
+
+    def _chk(self, rc, where):
+        if rc:
+            detail = lib().ha_rag_last_hip_error(self._h).decode() if rc == EHIP else ""
+            raise HaRagError(rc, where, detail)
+
+    def destroy(self):
+        if self._h:
+            lib().ha_rag_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def group_of(self, prec):
+        return {PREC_16: 0, PREC_INT8: self.cfg.group_int8, PREC_INT4: self.cfg.group_int4}[prec]
+
+    def chunk_bytes(self, prec, n_tokens, group=None):
+        g = self.group_of(prec) if group is None else group
+        return ha_rag_chunk_bytes(self.cfg.n_layers, self.cfg.n_kv_heads, self.cfg.head_dim, prec,
+                                  g, n_tokens)[2]
+
+    def set_launch_params(self, threads, blocks_per_wave, nontemporal):
+        self._chk(lib().ha_rag_set_launch_params(self._h, threads, blocks_per_wave,
+                                                 1 if nontemporal else 0), "ha_rag_set_launch_params")
+
+    def quantize_chunk(self, src, n_tokens, prec, group, dst, saturated=None, stream=None):
+        self._chk(lib().ha_rag_quantize_chunk(self._h, _addr(src), n_tokens, prec, group, _addr(dst),
+                                              _addr(saturated), _stream(stream)),
+                  "ha_rag_quantize_chunk")
+
+    def load_packed(self, chunks, out, cap_tokens, tok_base=0, stream=None):
+        """chunks: list of (packed, n_tokens, prec, group)."""
+        arr = (PackedChunk * max(len(chunks), 1))()
+        for i, (p, t, prec, g) in enumerate(chunks):
+            arr[i] = PackedChunk(_addr(p), t, prec, g, 0)
+        self._chk(lib().ha_rag_load_packed(self._h, arr, len(chunks), _addr(out), cap_tokens,
+                                           tok_base, _stream(stream)), "ha_rag_load_packed")
+
+    def register_slab(self, tier, prec, base, nbytes=None):
+        if nbytes is None:
+            nbytes = base.numel() * base.element_size()
+        self._chk(lib().ha_rag_register_slab(self._h, tier, prec, _addr(base), nbytes),
+                  "ha_rag_register_slab")
+        self._keep.append(base)
+
+    def register_staging(self, base, nbytes=None):
+        if nbytes is None:
+            nbytes = base.numel() * base.element_size()
+        self._chk(lib().ha_rag_register_staging(self._h, _addr(base), nbytes),
+                  "ha_rag_register_staging")
+        self._keep.append(base)
+
+    def pool_insert(self, cid, prec, n_tokens, packed, tier, packed_is_device=False, stream=None):
+        self._chk(lib().ha_rag_pool_insert(self._h, cid, prec, n_tokens, _addr(packed),
+                                           1 if packed_is_device else 0, tier, _stream(stream)),
+                  "ha_rag_pool_insert")
+
+    def pool_slot(self, cid, tier):
+        p, n = C.c_void_p(), C.c_size_t()
+        self._chk(lib().ha_rag_pool_slot(self._h, cid, tier, C.byref(p), C.byref(n)),
+                  "ha_rag_pool_slot")
+        return p.value, n.value
+
+    def pool_promote(self, cid, stream=None):
+        self._chk(lib().ha_rag_pool_promote(self._h, cid, _stream(stream)), "ha_rag_pool_promote")
+
+    def pool_evict(self, cid):
+        self._chk(lib().ha_rag_pool_evict(self._h, cid), "ha_rag_pool_evict")
+
+    def pool_query(self, cid):
+        info = ChunkInfo()
+        self._chk(lib().ha_rag_pool_query(self._h, cid, C.byref(info)), "ha_rag_pool_query")
+        return info
+
+    def pool_hbm_lru(self, cap=1 << 16):
+        ids = (C.c_uint64 * cap)()
+        n = C.c_size_t()
+        self._chk(lib().ha_rag_pool_hbm_lru(self._h, ids, cap, C.byref(n)), "ha_rag_pool_hbm_lru")
+        return list(ids[:n.value])
+
+    def touch(self, ids):
+        self._chk(lib().ha_rag_touch(self._h, _u64s(ids), len(ids)), "ha_rag_touch")
+
+    def set_counts(self, ids, counts):
+        self._chk(lib().ha_rag_set_counts(self._h, _u64s(ids), _u64s(counts), len(ids)),
+                  "ha_rag_set_counts")
+
+    def rerank(self):
+        self._chk(lib().ha_rag_rerank(self._h), "ha_rag_rerank")
+
+    def get_rank(self, cid):
+        r = C.c_uint32()
+        self._chk(lib().ha_rag_get_rank(self._h, cid, C.byref(r)), "ha_rag_get_rank")
+        return r.value
+
+    def load_chunks(self, ids, out, cap_tokens, tok_base=0, tags=None, stream=None,
+                    want_trace=False):
+        """Returns (stats dict, trace list or None)."""
+        n = len(ids)
+        st = LoadStats()
+        tr = (ChunkTrace * max(n, 1))() if want_trace else None
+        tg = (C.c_uint8 * max(n, 1))(*tags) if tags is not None else None
+        self._chk(lib().ha_rag_load_chunks(self._h, _u64s(ids), tg, n, _addr(out), cap_tokens,
+                                           tok_base, _stream(stream), C.byref(st), tr),
+                  "ha_rag_load_chunks")
+        return st.as_dict(), (list(tr[:n]) if want_trace else None)
+
+    def load_batch(self, requests, outs, cap_tokens, tok_base=None, tags=None, stream=None,
+                   want_trace=False):
+        """requests: list of id lists; outs: one cache per request."""
+        flat = [i for r in requests for i in r]
+        starts = [0]
+        for r in requests:
+            starts.append(starts[-1] + len(r))
+        n, nr = len(flat), len(requests)
+        st = LoadStats()
+        tr = (ChunkTrace * max(n, 1))() if want_trace else None
+        tg = (C.c_uint8 * max(n, 1))(*tags) if tags is not None else None
+        outp = (C.c_void_p * max(nr, 1))(*[_addr(o) for o in outs])
+        caps = _u64s(cap_tokens)
+        base = _u64s(tok_base) if tok_base is not None else None
+        self._chk(lib().ha_rag_load_batch(self._h, _u64s(flat), tg, (C.c_uint32 * (nr + 1))(*starts),
+                                          nr, outp, caps, base, _stream(stream), C.byref(st), tr),
+                  "ha_rag_load_batch")
+        return st.as_dict(), (list(tr[:n]) if want_trace else None)

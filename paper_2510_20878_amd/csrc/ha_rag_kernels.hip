@@ -1,0 +1,378 @@
+// gfx950 kernels of the HA-RAG mixed-precision KV-chunk load.
+//
+//  k1_gather_dequant_scatter  online: packed chunks -> BF16 KV cache (the
+//      "load + decompress + concatenate" stage of Sec. 2.1 / Fig. 3; the
+//      decompression whose cost Table 2 compares)
+//  k2_quantize_pack           offline: BF16 chunk -> packed chunk (Algorithm 1
+//      step 3, Compression(S_i, chunk), for the per-group integer formats)
+//
+// Both kernels are HBM-bound streaming kernels: no matrix cores, no LDS.  The
+// packed layout (see include/ha_rag.h) is built so that lane i of a 64-lane wave
+// reads 16-byte word i of a 1024-byte run and writes 16-byte word i of four
+// 1024-byte runs: every memory instruction of a wave covers one contiguous KiB.
+#include "ha_rag_kernels.h"
+
+namespace ha_rag {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ u32x4 ld16(const uint8_t *p)
+{
+    return *reinterpret_cast<const u32x4 *>(p);
+}
+
+template <bool NT>
+__device__ __forceinline__ void st16(uint8_t *p, u32x4 v)
+{
+    if (NT) __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
+    else *reinterpret_cast<u32x4 *>(p) = v;
+}
+
+__device__ __forceinline__ float h2f(uint32_t h16)
+{
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)h16);
+}
+
+// two fp32 -> one dword of two BF16 (round to nearest even), a in the low half
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b)
+{
+    f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+__device__ __forceinline__ float byte_f(uint32_t w, int k)
+{
+    return (float)((w >> (8 * k)) & 0xFFu);  // one byte-to-float conversion each
+}
+
+// 8 int4 codes (one dword) of one plane -> 8 BF16 (16 bytes)
+__device__ __forceinline__ u32x4 dequant_octet4(uint32_t c, uint32_t m)
+{
+    const float s = h2f(m & 0xFFFFu), z = h2f(m >> 16);
+    const uint32_t ev = c & 0x0F0F0F0Fu;         // codes 0,2,4,6 one per byte
+    const uint32_t od = (c >> 4) & 0x0F0F0F0Fu;  // codes 1,3,5,7
+    u32x4 r;
+    r.x = pack_bf16(__builtin_fmaf(byte_f(ev, 0), s, z), __builtin_fmaf(byte_f(od, 0), s, z));
+    r.y = pack_bf16(__builtin_fmaf(byte_f(ev, 1), s, z), __builtin_fmaf(byte_f(od, 1), s, z));
+    r.z = pack_bf16(__builtin_fmaf(byte_f(ev, 2), s, z), __builtin_fmaf(byte_f(od, 2), s, z));
+    r.w = pack_bf16(__builtin_fmaf(byte_f(ev, 3), s, z), __builtin_fmaf(byte_f(od, 3), s, z));
+    return r;
+}
+
+// 8 int8 codes (two dwords) of one plane -> 8 BF16
+__device__ __forceinline__ u32x4 dequant_octet8(uint32_t c0, uint32_t c1, uint32_t m)
+{
+    const float s = h2f(m & 0xFFFFu), z = h2f(m >> 16);
+    u32x4 r;
+    r.x = pack_bf16(__builtin_fmaf(byte_f(c0, 0), s, z), __builtin_fmaf(byte_f(c0, 1), s, z));
+    r.y = pack_bf16(__builtin_fmaf(byte_f(c0, 2), s, z), __builtin_fmaf(byte_f(c0, 3), s, z));
+    r.z = pack_bf16(__builtin_fmaf(byte_f(c1, 0), s, z), __builtin_fmaf(byte_f(c1, 1), s, z));
+    r.w = pack_bf16(__builtin_fmaf(byte_f(c1, 2), s, z), __builtin_fmaf(byte_f(c1, 3), s, z));
+    return r;
+}
+
+// ---------------------------------------------------------------------------
+// K1.  Grid: x = tile * wg_per_tile + workgroup-in-tile, y = chunk of the launch.
+// A workgroup of W waves owns W*U consecutive blocks of one tile; wave w takes
+// blocks base + u*W + w.  All loads of a wave's U blocks are issued before the
+// first store so that several KiB per wave are in flight.
+// ---------------------------------------------------------------------------
+template <int U, bool NT>
+__global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params p)
+{
+    const K1Chunk &c = p.c[blockIdx.y];
+    const uint32_t n_e = c.n_tokens * p.head_dim;
+    const uint32_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
+    const uint32_t nwaves = blockDim.x >> 6;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    const uint32_t tile = blockIdx.x / p.wg_per_tile;
+    const uint32_t wgi = blockIdx.x - tile * p.wg_per_tile;
+    const uint32_t blk_base = wgi * nwaves * U;
+    if (blk_base >= nblk) return;
+
+    const uint32_t bits = c.fmt & 0xFFu, gsh = c.fmt >> 8;
+    uint8_t *out_tile = c.out + (uint64_t)tile * c.out_tile_stride;
+    const uint32_t lane_e = lane * 8;   // first element of this lane's octets in plane 0
+    const uint32_t lane_b = lane * 16;  // byte of this lane in a 1024-byte run
+
+    if (bits == 4) {
+        const uint32_t meta_blk = 8192u >> gsh;
+        const uint8_t *pay = c.src + (uint64_t)tile * ((uint64_t)nblk * (1024u + meta_blk));
+        const uint8_t *meta = pay + (uint64_t)nblk * 1024u;
+        const uint32_t mword = (lane_e >> gsh) * 16u;
+        u32x4 w[U], m[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t blk = blk_base + u * nwaves + wave;
+            if (blk < nblk) {
+                w[u] = ld16(pay + (uint64_t)blk * 1024u + lane_b);
+                m[u] = ld16(meta + (uint64_t)blk * meta_blk + mword);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t blk = blk_base + u * nwaves + wave;
+            if (blk < nblk) {
+                uint8_t *o = out_tile + (uint64_t)blk * 4096u + lane_b;
+                const uint32_t e = blk * kBlockElems + lane_e;
+                if (e < n_e) st16<NT>(o, dequant_octet4(w[u].x, m[u].x));
+                if (e + 512 < n_e) st16<NT>(o + 1024, dequant_octet4(w[u].y, m[u].y));
+                if (e + 1024 < n_e) st16<NT>(o + 2048, dequant_octet4(w[u].z, m[u].z));
+                if (e + 1536 < n_e) st16<NT>(o + 3072, dequant_octet4(w[u].w, m[u].w));
+            }
+        }
+    } else if (bits == 8) {
+        const uint32_t meta_blk = 8192u >> gsh;
+        const uint8_t *pay = c.src + (uint64_t)tile * ((uint64_t)nblk * (2048u + meta_blk));
+        const uint8_t *meta = pay + (uint64_t)nblk * 2048u;
+        const uint32_t mword = (lane_e >> gsh) * 16u;
+        u32x4 w0[U], w1[U], m[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t blk = blk_base + u * nwaves + wave;
+            if (blk < nblk) {
+                const uint8_t *b = pay + (uint64_t)blk * 2048u + lane_b;
+                w0[u] = ld16(b);
+                w1[u] = ld16(b + 1024);
+                m[u] = ld16(meta + (uint64_t)blk * meta_blk + mword);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t blk = blk_base + u * nwaves + wave;
+            if (blk < nblk) {
+                uint8_t *o = out_tile + (uint64_t)blk * 4096u + lane_b;
+                const uint32_t e = blk * kBlockElems + lane_e;
+                if (e < n_e) st16<NT>(o, dequant_octet8(w0[u].x, w0[u].y, m[u].x));
+                if (e + 512 < n_e) st16<NT>(o + 1024, dequant_octet8(w0[u].z, w0[u].w, m[u].y));
+                if (e + 1024 < n_e) st16<NT>(o + 2048, dequant_octet8(w1[u].x, w1[u].y, m[u].z));
+                if (e + 1536 < n_e) st16<NT>(o + 3072, dequant_octet8(w1[u].z, w1[u].w, m[u].w));
+            }
+        }
+    } else {
+        const uint8_t *pay = c.src + (uint64_t)tile * ((uint64_t)nblk * 4096u);
+        u32x4 w[U][4];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t blk = blk_base + u * nwaves + wave;
+            if (blk < nblk) {
+                const uint8_t *b = pay + (uint64_t)blk * 4096u + lane_b;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) w[u][j] = ld16(b + j * 1024);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t blk = blk_base + u * nwaves + wave;
+            if (blk < nblk) {
+                uint8_t *o = out_tile + (uint64_t)blk * 4096u + lane_b;
+                const uint32_t e = blk * kBlockElems + lane_e;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (e + j * 512 < n_e) st16<NT>(o + j * 1024, w[u][j]);
+            }
+        }
+    }
+}
+
+template <int U>
+static hipError_t launch_k1_u(const K1Params &p, dim3 grid, const K1Launch &cfg, hipStream_t s)
+{
+    if (cfg.nontemporal)
+        hipLaunchKernelGGL((k1_gather_dequant_scatter<U, true>), grid, dim3(cfg.threads), 0, s, p);
+    else
+        hipLaunchKernelGGL((k1_gather_dequant_scatter<U, false>), grid, dim3(cfg.threads), 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_k1(const K1Params &p_in, uint32_t max_tokens, const K1Launch &cfg,
+                     hipStream_t stream)
+{
+    if (p_in.n_chunks == 0 || max_tokens == 0) return hipSuccess;
+    if (p_in.n_chunks > kMaxLaunchChunks || cfg.threads < 64 || cfg.threads > 1024 ||
+        (cfg.threads & 63u))
+        return hipErrorInvalidValue;
+    K1Params p = p_in;
+    const uint64_t n_e = (uint64_t)max_tokens * p.head_dim;
+    if (n_e > 0x7FFFFFFFull) return hipErrorInvalidValue;  // element indices are 32-bit
+    const uint32_t nblk = (uint32_t)((n_e + kBlockElems - 1) / kBlockElems);
+    const uint32_t per_wg = (cfg.threads >> 6) * cfg.blocks_per_wave;
+    p.wg_per_tile = (nblk + per_wg - 1) / per_wg;
+    const uint64_t gx = (uint64_t)p.n_tiles * p.wg_per_tile;
+    if (gx > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    dim3 grid((uint32_t)gx, p.n_chunks);
+    switch (cfg.blocks_per_wave) {
+    case 1: return launch_k1_u<1>(p, grid, cfg, stream);
+    case 2: return launch_k1_u<2>(p, grid, cfg, stream);
+    case 4: return launch_k1_u<4>(p, grid, cfg, stream);
+    case 8: return launch_k1_u<8>(p, grid, cfg, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// K2.  One wave per block of 2048 elements; a workgroup of 4 waves takes 4
+// consecutive blocks of one tile.
+// ---------------------------------------------------------------------------
+
+// fp32 -> fp16 word, largest finite value <= x; sets sat if none exists
+__device__ __forceinline__ uint32_t f16_round_down(float x, bool &sat)
+{
+    uint32_t h = __builtin_bit_cast(uint16_t, (_Float16)x);  // nearest even
+    if (h2f(h) > x) {                                          // one step down the number line
+        if ((h & 0x7FFFu) == 0) h = 0x8001u;
+        else if (h & 0x8000u) h += 1;
+        else h -= 1;
+    }
+    if (h == 0xFC00u) { h = 0xFBFFu; sat = true; }
+    if (h == 0x7C00u) h = 0x7BFFu;
+    if (h == 0x8000u) h = 0;
+    return h;
+}
+
+// fp32 -> fp16 word, smallest finite value >= x; sets sat if none exists
+__device__ __forceinline__ uint32_t f16_round_up(float x, bool &sat)
+{
+    uint32_t h = __builtin_bit_cast(uint16_t, (_Float16)x);
+    if (h2f(h) < x) {
+        if ((h & 0x7FFFu) == 0) h = 0x0001u;
+        else if (h & 0x8000u) h -= 1;
+        else h += 1;
+    }
+    if ((h & 0x7FFFu) >= 0x7C00u && h != 0xFC00u) { h = 0x7BFFu; sat = true; }
+    if (h == 0xFC00u) h = 0xFBFFu;
+    if (h == 0x8000u) h = 0;
+    return h;
+}
+
+template <int BITS>
+__global__ void __launch_bounds__(256) k2_quantize_pack(const uint8_t *__restrict__ src,
+                                                        uint8_t *__restrict__ dst,
+                                                        uint32_t n_tokens, uint32_t head_dim,
+                                                        uint32_t gsh, uint32_t wg_per_tile,
+                                                        uint32_t *saturated)
+{
+    const uint32_t n_e = n_tokens * head_dim;
+    const uint32_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    const uint32_t tile = blockIdx.x / wg_per_tile;
+    const uint32_t blk = (blockIdx.x - tile * wg_per_tile) * 4 + wave;
+    if (blk >= nblk) return;
+
+    const uint8_t *in = src + (uint64_t)tile * n_e * 2u + (uint64_t)blk * 4096u + lane * 16u;
+    const uint32_t e = blk * kBlockElems + lane * 8;
+    u32x4 raw[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        raw[j] = u32x4{0, 0, 0, 0};
+        if (e + j * 512 < n_e) raw[j] = ld16(in + j * 1024);
+    }
+
+    if (BITS == 16) {
+        uint8_t *o = dst + (uint64_t)tile * nblk * 4096u + (uint64_t)blk * 4096u + lane * 16u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) st16<false>(o + j * 1024, raw[j]);
+        return;
+    }
+
+    const uint32_t meta_blk = 8192u >> gsh;
+    const uint32_t pay_blk = 256u * BITS;
+    uint8_t *pay = dst + (uint64_t)tile * nblk * (pay_blk + meta_blk);
+    uint8_t *meta = pay + (uint64_t)nblk * pay_blk;
+    const uint32_t lanes_per_group = (1u << gsh) >> 3;
+    const float qmax = (float)((1 << BITS) - 1);
+
+    u32x4 mrow;      // the four {scale, zero} entries of this lane's planes
+    uint32_t code_lo[4], code_hi[4];  // int8: two dwords per plane; int4: code_lo only
+    uint32_t n_sat = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float x[8];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            x[2 * k] = __builtin_bit_cast(float, raw[j][k] << 16);
+            x[2 * k + 1] = __builtin_bit_cast(float, raw[j][k] & 0xFFFF0000u);
+        }
+        float mn = x[0], mx = x[0];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) {
+            mn = fminf(mn, x[k]);
+            mx = fmaxf(mx, x[k]);
+        }
+        for (uint32_t o = 1; o < lanes_per_group; o <<= 1) {
+            mn = fminf(mn, __shfl_xor(mn, (int)o));
+            mx = fmaxf(mx, __shfl_xor(mx, (int)o));
+        }
+        bool sat = false;
+        const uint32_t zh = f16_round_down(mn, sat);
+        const float z = h2f(zh);
+        const float range = mx - z;
+        const float sc = range / qmax;
+        const uint32_t sh = f16_round_up(sc, sat);
+        const float s = h2f(sh);
+        n_sat += sat ? 1u : 0u;
+        mrow[j] = sh | (zh << 16);
+        uint32_t q[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float d = x[k] - z;
+            const float t = d / s;
+            float r = __builtin_rintf(t);
+            r = fminf(fmaxf(r, 0.0f), qmax);
+            q[k] = (s != 0.0f) ? (uint32_t)r : 0u;
+        }
+        if (BITS == 4) {
+            code_lo[j] = q[0] | (q[1] << 4) | (q[2] << 8) | (q[3] << 12) | (q[4] << 16) |
+                         (q[5] << 20) | (q[6] << 24) | (q[7] << 28);
+        } else {
+            code_lo[j] = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
+            code_hi[j] = q[4] | (q[5] << 8) | (q[6] << 16) | (q[7] << 24);
+        }
+    }
+    if (BITS == 4) {
+        st16<false>(pay + (uint64_t)blk * pay_blk + lane * 16u,
+                    u32x4{code_lo[0], code_lo[1], code_lo[2], code_lo[3]});
+    } else {
+        uint8_t *o = pay + (uint64_t)blk * pay_blk + lane * 16u;
+        st16<false>(o, u32x4{code_lo[0], code_hi[0], code_lo[1], code_hi[1]});
+        st16<false>(o + 1024, u32x4{code_lo[2], code_hi[2], code_lo[3], code_hi[3]});
+    }
+    if ((lane & (lanes_per_group - 1)) == 0) {  // first lane of each group
+        st16<false>(meta + (uint64_t)blk * meta_blk + ((lane * 8u) >> gsh) * 16u, mrow);
+        if (saturated != nullptr && n_sat) atomicAdd(saturated, n_sat);
+    }
+}
+
+hipError_t launch_k2(const void *src, void *dst, uint32_t n_tiles, uint32_t head_dim,
+                     uint32_t n_tokens, uint32_t bits, uint32_t group, uint32_t *saturated,
+                     hipStream_t stream)
+{
+    if (n_tokens == 0 || n_tiles == 0) return hipSuccess;
+    const uint64_t n_e = (uint64_t)n_tokens * head_dim;
+    if (n_e > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const uint32_t nblk = (uint32_t)((n_e + kBlockElems - 1) / kBlockElems);
+    const uint32_t wg_per_tile = (nblk + 3) / 4;
+    const uint64_t gx = (uint64_t)n_tiles * wg_per_tile;
+    if (gx > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    uint32_t gsh = 0;
+    while ((1u << gsh) < group) ++gsh;
+    const uint8_t *s = static_cast<const uint8_t *>(src);
+    uint8_t *d = static_cast<uint8_t *>(dst);
+    dim3 grid((uint32_t)gx), block(256);
+    if (bits == 16)
+        hipLaunchKernelGGL(k2_quantize_pack<16>, grid, block, 0, stream, s, d, n_tokens, head_dim,
+                           gsh, wg_per_tile, saturated);
+    else if (bits == 8)
+        hipLaunchKernelGGL(k2_quantize_pack<8>, grid, block, 0, stream, s, d, n_tokens, head_dim,
+                           gsh, wg_per_tile, saturated);
+    else if (bits == 4)
+        hipLaunchKernelGGL(k2_quantize_pack<4>, grid, block, 0, stream, s, d, n_tokens, head_dim,
+                           gsh, wg_per_tile, saturated);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace ha_rag

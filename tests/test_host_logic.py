@@ -1,0 +1,233 @@
+"""Host logic of the library without a GPU (dry_run contexts: bookkeeping only,
+no HIP call, no byte moved): sizes, Algorithm 1 split, Algorithm 2 lookup /
+promotion / LRU against the oracle's plain-Python simulation, error codes."""
+import numpy as np
+import pytest
+
+from oracle import codec, placement as pl
+from paper_2510_20878_amd import binding as B
+from paper_2510_20878_amd import workloads as wl
+
+FAKE_HBM = 0x7F0000000000     # never dereferenced in dry_run
+FAKE_PIN = 0x7E0000000000
+FAKE_STG = 0x7D0000000000
+
+
+@pytest.mark.parametrize("shape", [(32, 8, 128), (80, 8, 128), (2, 2, 64), (1, 1, 96)])
+@pytest.mark.parametrize("T", [1, 7, 100, 128, 512, 1024])
+def test_chunk_bytes_equals_oracle(shape, T):
+    L, H, D = shape
+    for prec, bits in B.BITS.items():
+        for g in (32, 64, 128):
+            if D % g:
+                with pytest.raises(B.HaRagError) as e:
+                    B.ha_rag_chunk_bytes(L, H, D, B.PREC_INT4, g, T)
+                assert e.value.code == B.EFORMAT
+                continue
+            pay, meta, total = B.ha_rag_chunk_bytes(L, H, D, prec, g, T)
+            assert total == codec.chunk_bytes(L, H, D, T, bits, g)
+            assert pay == L * 2 * H * codec.tile_payload_bytes(T, D, bits)
+            assert pay + meta == total
+
+
+def test_chunk_bytes_rejects_bad_shapes():
+    for args in [(2, 2, 60, B.PREC_INT4, 64, 8), (2, 2, 64, 3, 64, 8), (2, 2, 64, B.PREC_INT8, 48, 8),
+                 (0, 2, 64, B.PREC_16, 0, 8)]:
+        with pytest.raises(B.HaRagError) as e:
+            B.ha_rag_chunk_bytes(*args)
+        assert e.value.code == B.EFORMAT
+
+
+def test_alg1_classes_equal_oracle():
+    rng = np.random.default_rng(0)
+    for n in (1, 2, 9, 10, 38, 257, 1000):
+        af = rng.integers(0, 12, n).tolist()         # many ties
+        for taus in ([100_000, 100_000, 100_000], [200_000, 300_000], [999_999], []):
+            cls, ranks = B.ha_rag_alg1_classes(af, taus)
+            assert cls == pl.classes_by_rank(af, taus)
+            assert ranks == pl.ranks(af)
+
+
+def _ctx(cap_hbm, n_pinned, tau_gpu_ppm, L=2, H=2, D=64, T=128, prec=B.PREC_INT4, staging=4,
+         rerank_interval=0):
+    ctx = B.Context(L, H, D, T, group_int8=64, group_int4=64, tau_gpu_ppm=tau_gpu_ppm,
+                    rerank_interval=rerank_interval, dry_run=True)
+    slot = (ctx.chunk_bytes(prec, T) + 255) // 256 * 256
+    if cap_hbm:
+        ctx.register_slab(B.TIER_HBM, prec, FAKE_HBM, slot * cap_hbm)
+    ctx.register_slab(B.TIER_PINNED, prec, FAKE_PIN, slot * n_pinned)
+    if staging:
+        ctx.register_staging(FAKE_STG, slot * staging)
+    return ctx
+
+
+def test_alg2_two_tier_trace_equals_oracle():
+    """Every chunk has a pinned master; GPU_LIST = hottest 10 %; HBM holds 3."""
+    n, cap = 50, 3
+    ctx = _ctx(cap, n, 100_000)
+    for c in range(n):
+        ctx.pool_insert(c, B.PREC_INT4, 128, None, B.TIER_PINNED)
+    counts = [1000 - c for c in range(n)]            # rank == id
+    ctx.set_counts(list(range(n)), counts)
+    ctx.rerank()
+    assert [ctx.get_rank(c) for c in (0, 7, 49)] == [0, 7, 49]
+    sim = pl.TierSim(list(range(n)), [100_000, 900_000, 0], (cap, None, 0))
+    sim.seed(sim.PIN, range(n))
+    rng = np.random.default_rng(1)
+    seq = [0, 1, 2, 3, 0, 7, 4, 1, 2, 2, 30, 0] + rng.integers(0, 8, 200).tolist()
+    for c in seq:                                     # one chunk per load call
+        st, tr = ctx.load_chunks([c], FAKE_HBM, 128, want_trace=True)
+        tier, placed = sim.access(c)
+        assert tr[0].found_tier == (B.TIER_HBM if tier == sim.GPU else B.TIER_PINNED)
+        assert bool(tr[0].promoted) == bool(placed)
+        exp_ev = placed[0][1] if placed and placed[0][1] is not None else B.NO_CHUNK
+        assert tr[0].evicted_id == exp_ev
+        assert ctx.pool_hbm_lru() == sim.resident(sim.GPU)
+        assert st["n_hbm_hits"] + st["n_pinned_hits"] == 1
+    # counters moved with every access; ranks did not (no rerank since)
+    assert ctx.pool_query(0).count == counts[0] + seq.count(0)
+    assert ctx.get_rank(7) == 7
+
+
+def test_multi_chunk_request_bookkeeping_and_offsets():
+    n = 20
+    ctx = _ctx(8, n, 500_000)
+    toks = [128 - 3 * c for c in range(n)]
+    for c in range(n):
+        ctx.pool_insert(c, B.PREC_INT4, toks[c], None, B.TIER_PINNED)
+    ctx.set_counts(list(range(n)), [100 - c for c in range(n)])
+    ctx.rerank()
+    sim = pl.TierSim(list(range(n)), [500_000, 500_000, 0], (8, None, 0))
+    sim.seed(sim.PIN, range(n))
+    req = [3, 0, 15, 2, 1, 3, 12]
+    st, tr = ctx.load_chunks(req, FAKE_HBM, 1000, tok_base=11, want_trace=True)
+    off = 11
+    for i, c in enumerate(req):
+        tier, placed = sim.access(c)
+        assert tr[i].tok_off == off
+        assert tr[i].found_tier == (B.TIER_HBM if tier == sim.GPU else B.TIER_PINNED)
+        assert bool(tr[i].promoted) == bool(placed)
+        off += toks[c]
+    assert st["tokens"] == sum(toks[c] for c in req)
+    assert st["n_promoted"] == 4 and st["n_hbm_hits"] == 1 and st["n_pinned_hits"] == 6
+    per_tok = 2 * 2 * 2 * 64 * 2
+    assert st["bf16_bytes_written"] == st["tokens"] * per_tok
+    assert st["packed_bytes_read"] == sum(ctx.chunk_bytes(B.PREC_INT4, toks[c]) for c in req)
+    assert st["bytes_h2d"] == sum(ctx.chunk_bytes(B.PREC_INT4, toks[c]) for c in req) - \
+        ctx.chunk_bytes(B.PREC_INT4, toks[3])
+    assert ctx.pool_hbm_lru() == sim.resident(sim.GPU)
+    # launches: one for the early hits (none here), one per cold chunk, one for late hits
+    assert st["n_kernel_launches"] == 6 + 1
+
+
+def test_hbm_only_chunks_are_never_evicted_and_promotion_is_skipped():
+    ctx = _ctx(2, 10, 1_000_000)
+    ctx.pool_insert(100, B.PREC_INT4, 128, None, B.TIER_HBM)       # no pinned master
+    ctx.pool_insert(101, B.PREC_INT4, 128, None, B.TIER_HBM)
+    ctx.pool_insert(5, B.PREC_INT4, 128, None, B.TIER_PINNED)
+    ctx.rerank()
+    st, tr = ctx.load_chunks([5], FAKE_HBM, 128, want_trace=True)
+    assert tr[0].promote_skipped == 1 and tr[0].promoted == 0 and st["n_promote_skipped"] == 1
+    with pytest.raises(B.HaRagError) as e:
+        ctx.pool_insert(102, B.PREC_INT4, 128, None, B.TIER_HBM)
+    assert e.value.code == B.ENOSPC
+    with pytest.raises(B.HaRagError) as e:
+        ctx.pool_evict(100)
+    assert e.value.code == B.EINVAL
+    # once a master exists the copy becomes evictable
+    ctx.pool_insert(100, B.PREC_INT4, 128, None, B.TIER_PINNED)
+    st, tr = ctx.load_chunks([5], FAKE_HBM, 128, want_trace=True)
+    assert tr[0].promoted == 1 and tr[0].evicted_id == 100
+
+
+def test_rerank_interval_and_gpu_list_boundary():
+    n = 10
+    ctx = _ctx(4, n, 200_000, rerank_interval=3)          # GPU_LIST = 2 hottest
+    for c in range(n):
+        ctx.pool_insert(c, B.PREC_INT4, 128, None, B.TIER_PINNED)
+    # no rank yet: nothing is promoted
+    st, _ = ctx.load_chunks([9], FAKE_HBM, 128)
+    assert st["n_promoted"] == 0
+    ctx.load_chunks([9], FAKE_HBM, 128)
+    ctx.load_chunks([8], FAKE_HBM, 128)
+    # 4th call: automatic rerank first -> 9 (2 hits) rank 0, 8 rank 1
+    st, tr = ctx.load_chunks([8], FAKE_HBM, 128, want_trace=True)
+    assert ctx.get_rank(9) == 0 and ctx.get_rank(8) == 1 and ctx.get_rank(0) == 2
+    assert tr[0].promoted == 1
+    st, _ = ctx.load_chunks([0], FAKE_HBM, 128)
+    assert st["n_promoted"] == 0                      # rank 2 is outside GPU_LIST
+
+
+def test_error_paths_change_nothing():
+    ctx = _ctx(2, 4, 1_000_000)
+    for c in range(3):
+        ctx.pool_insert(c, B.PREC_INT4, 128, None, B.TIER_PINNED)
+    ctx.rerank()
+
+    def code(fn, *a, **k):
+        with pytest.raises(B.HaRagError) as e:
+            fn(*a, **k)
+        return e.value.code
+
+    assert code(ctx.load_chunks, [0, 77], FAKE_HBM, 1000) == B.ENOENT
+    assert code(ctx.load_chunks, [0, 1], FAKE_HBM, 255) == B.ENOSPC          # cache too small
+    assert code(ctx.load_chunks, [0, 1], FAKE_HBM, 300, tok_base=50) == B.ENOSPC
+    assert code(ctx.load_chunks, [0], FAKE_HBM, 128, tags=[B.PREC_INT8]) == B.EFORMAT
+    assert code(ctx.load_chunks, [0], FAKE_HBM + 8, 128) == B.EINVAL         # misaligned cache
+    assert code(ctx.pool_insert, 0, B.PREC_INT4, 128, None, B.TIER_PINNED) == B.EINVAL   # duplicate
+    assert code(ctx.pool_insert, 0, B.PREC_INT4, 64, None, B.TIER_HBM) == B.EFORMAT     # other length
+    assert code(ctx.pool_insert, 9, B.PREC_INT8, 128, None, B.TIER_PINNED) == B.ENOSPC  # no such slab
+    assert code(ctx.pool_insert, 9, B.PREC_INT4, 129, None, B.TIER_PINNED) == B.EINVAL  # too long
+    ctx.pool_insert(3, B.PREC_INT4, 128, None, B.TIER_PINNED)
+    assert code(ctx.pool_insert, 4, B.PREC_INT4, 128, None, B.TIER_PINNED) == B.ENOSPC  # slab full
+    assert code(ctx.pool_promote, 77) == B.ENOENT
+    assert code(ctx.pool_slot, 0, B.TIER_HBM) == B.ENOENT
+    assert code(ctx.touch, [0, 77]) == B.ENOENT
+    for c in range(3):
+        q = ctx.pool_query(c)
+        assert q.count == 0 and q.in_hbm == 0         # failed calls counted nothing, moved nothing
+    ptr, nbytes = ctx.pool_slot(1, B.TIER_PINNED)
+    slot = (nbytes + 255) // 256 * 256
+    assert nbytes == codec.chunk_bytes(2, 2, 64, 128, 4, 64) and (ptr - FAKE_PIN) % slot == 0
+    # cold chunk without a staging area
+    ctx2 = _ctx(2, 4, 0, staging=0)
+    ctx2.pool_insert(0, B.PREC_INT4, 128, None, B.TIER_PINNED)
+    assert code(ctx2.load_chunks, [0], FAKE_HBM, 128) == B.ENOSPC
+    assert code(B.Context, 2, 2, 60, 128, dry_run=True) == B.EFORMAT
+    assert code(B.Context, 2, 2, 64, 128, group_int4=128, dry_run=True) == B.EFORMAT
+
+
+def test_batch_load_bookkeeping():
+    n = 12
+    ctx = _ctx(12, n, 1_000_000)
+    for c in range(n):
+        ctx.pool_insert(c, B.PREC_INT4, 128, None, B.TIER_PINNED)
+    ctx.rerank()
+    reqs = [[0, 1, 2], [3, 1], [], [4, 5, 6, 0]]
+    st, tr = ctx.load_batch(reqs, [FAKE_HBM + 4096 * i for i in range(4)], [384, 256, 0, 600],
+                            tok_base=[0, 0, 0, 88], want_trace=True)
+    assert [t.tok_off for t in tr] == [0, 128, 256, 0, 128, 88, 216, 344, 472]
+    assert [t.found_tier for t in tr] == [1, 1, 1, 1, 0, 1, 1, 1, 0]   # repeats hit HBM
+    assert st["n_promoted"] == 7 and st["tokens"] == 9 * 128
+    with pytest.raises(B.HaRagError) as e:
+        ctx.load_batch([[0, 1, 2]], [FAKE_HBM], [383])
+    assert e.value.code == B.ENOSPC
+
+
+def test_zipf_workload_hit_rate_is_high_once_warm():
+    """The placement the paper motivates: with ~1 % of ids drawing most accesses,
+    an HBM tier holding the hottest few percent serves most chunk loads."""
+    n = 2000
+    ctx = _ctx(100, n, 50_000)                      # tau_GPU = 5 % (the paper's setting)
+    for c in range(n):
+        ctx.pool_insert(c, B.PREC_INT4, 128, None, B.TIER_PINNED)
+    reqs = wl.zipf_requests(n, 600, 8, seed=3)
+    for r in reqs[:300]:
+        ctx.load_chunks(r.tolist(), FAKE_HBM, 8 * 128)
+    ctx.rerank()
+    hits = tot = 0
+    for r in reqs[300:]:
+        st, _ = ctx.load_chunks(r.tolist(), FAKE_HBM, 8 * 128)
+        hits += st["n_hbm_hits"]
+        tot += 8
+    assert hits / tot > 0.6
