@@ -156,7 +156,8 @@ int ha_rag_create(const ha_rag_config *cfg, ha_rag_ctx **out);
  * first.  The caller's buffers are not touched. */
 int ha_rag_destroy(ha_rag_ctx *ctx);
 
-/* Name of the last failing HIP call and its error string ("" if none). */
+/* Name of the last failing HIP call and its error string ("" if none).  With
+ * ctx == NULL: the reason the calling thread's last ha_rag_create failed. */
 const char *ha_rag_last_hip_error(ha_rag_ctx *ctx);
 
 /* Launch shape of the gather-dequantize-scatter kernel: threads per workgroup

@@ -88,6 +88,10 @@ def lib():
             raise RuntimeError(
                 f"{path} is missing: build it first (python -m paper_2510_20878_amd.build or "
                 "__graft_entry__.build()); there is no fallback path")
+        # PyTorch ships its own HIP runtime.  Device memory and streams come from
+        # torch, so the library must bind to that same runtime: import torch first,
+        # then the loader resolves libamdhip64 to the copy torch already mapped.
+        import torch  # noqa: F401
         L = C.CDLL(path)
         vp, u32, u64, sz = C.c_void_p, C.c_uint32, C.c_uint64, C.c_size_t
         P = C.POINTER
@@ -192,7 +196,8 @@ class Context:
         self._h = C.c_void_p()
         rc = lib().ha_rag_create(C.byref(self.cfg), C.byref(self._h))
         if rc:
-            raise HaRagError(rc, "ha_rag_create")
+            detail = lib().ha_rag_last_hip_error(None).decode() if rc == EHIP else ""
+            raise HaRagError(rc, "ha_rag_create", detail)
         self._keep = []  # tensors registered as slabs stay alive with the context
 
     def _chk(self, rc, where):

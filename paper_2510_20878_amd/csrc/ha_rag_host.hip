@@ -22,6 +22,7 @@ using namespace ha_rag;
 namespace {
 
 constexpr uint64_t kPPM = 1000000ull;
+thread_local std::string g_create_err;  // why the last ha_rag_create on this thread failed
 constexpr uint32_t kNoRank = UINT32_MAX;
 
 bool valid_group(uint32_t g)
@@ -284,6 +285,8 @@ struct Action {
     uint64_t tok_off;
     enum Kind { HOT_EARLY, HOT_LATE, COLD } kind;
     int32_t promote_slot;  // HBM slot to fill from staging, or -1
+    int32_t hbm_slot;      // slot read by a HOT_* action, as of the moment it was decided
+                           // (a later chunk of the same call may evict this one)
 };
 
 K1Chunk make_desc(const ha_rag_ctx *c, const Chunk &ch, const uint8_t *src, const Request &rq,
@@ -378,7 +381,7 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
             const uint32_t ci = cis[i];
             Chunk &ch = c->chunks[ci];
             ch.count += 1;
-            Action a{ci, r, off, Action::COLD, -1};
+            Action a{ci, r, off, Action::COLD, -1, -1};
             ha_rag_chunk_trace tr;
             std::memset(&tr, 0, sizeof tr);
             tr.tok_off = off;
@@ -386,6 +389,7 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
             if (ch.slot[HA_RAG_TIER_HBM] >= 0) {  // C_i in queueGPU
                 hbm_touch(c, ci);
                 a.kind = written_now[ci] ? Action::HOT_LATE : Action::HOT_EARLY;
+                a.hbm_slot = ch.slot[HA_RAG_TIER_HBM];
                 tr.found_tier = HA_RAG_TIER_HBM;
                 ++st.n_hbm_hits;
             } else {                               // C_i in queuePIN
@@ -460,10 +464,10 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
         if (a.kind != Action::HOT_EARLY) continue;
         const Chunk &ch = c->chunks[a.ci];
         Slab &hs = c->slab[HA_RAG_TIER_HBM][ch.prec];
-        int rc = before_read(c, hs.use[ch.slot[HA_RAG_TIER_HBM]], s);
+        int rc = before_read(c, hs.use[a.hbm_slot], s);
         if (rc) return rc;
-        rc = push(c, batch, make_desc(c, ch, hs.ptr(ch.slot[HA_RAG_TIER_HBM]), reqs[a.req], a.tok_off),
-                  s, &st.n_kernel_launches);
+        rc = push(c, batch, make_desc(c, ch, hs.ptr(a.hbm_slot), reqs[a.req], a.tok_off), s,
+                  &st.n_kernel_launches);
         if (rc) return rc;
     }
     int rc = flush(c, batch, s, &st.n_kernel_launches);
@@ -500,12 +504,13 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     for (const Action &a : acts) {
         if (a.kind != Action::HOT_LATE) continue;
         const Chunk &ch = c->chunks[a.ci];
-        if (ch.slot[HA_RAG_TIER_HBM] < 0) return HA_RAG_EINVAL;  // excluded by `keep` in pass A
+        // `keep` in pass A guarantees the copy written by this call is still in its slot
+        if (ch.slot[HA_RAG_TIER_HBM] != a.hbm_slot) return HA_RAG_EINVAL;
         Slab &hs = c->slab[HA_RAG_TIER_HBM][ch.prec];
-        rc = before_read(c, hs.use[ch.slot[HA_RAG_TIER_HBM]], s);
+        rc = before_read(c, hs.use[a.hbm_slot], s);
         if (rc) return rc;
-        rc = push(c, batch, make_desc(c, ch, hs.ptr(ch.slot[HA_RAG_TIER_HBM]), reqs[a.req], a.tok_off),
-                  s, &st.n_kernel_launches);
+        rc = push(c, batch, make_desc(c, ch, hs.ptr(a.hbm_slot), reqs[a.req], a.tok_off), s,
+                  &st.n_kernel_launches);
         if (rc) return rc;
     }
     rc = flush(c, batch, s, &st.n_kernel_launches);
@@ -591,6 +596,7 @@ int ha_rag_create(const ha_rag_config *cfg, ha_rag_ctx **out)
             hipStream_t s;
             hipError_t e = hipStreamCreateWithFlags(&s, hipStreamNonBlocking);
             if (e != hipSuccess) {
+                g_create_err = std::string("hipStreamCreateWithFlags: ") + hipGetErrorString(e);
                 for (hipStream_t t : c->copy_streams) (void)hipStreamDestroy(t);
                 delete c;
                 return HA_RAG_EHIP;
@@ -620,7 +626,10 @@ int ha_rag_destroy(ha_rag_ctx *c)
     return HA_RAG_OK;
 }
 
-const char *ha_rag_last_hip_error(ha_rag_ctx *c) { return c ? c->hip_err.c_str() : ""; }
+const char *ha_rag_last_hip_error(ha_rag_ctx *c)
+{
+    return c ? c->hip_err.c_str() : g_create_err.c_str();
+}
 
 int ha_rag_set_launch_params(ha_rag_ctx *c, uint32_t threads, uint32_t blocks_per_wave,
                              uint32_t nontemporal)

@@ -231,3 +231,42 @@ def test_zipf_workload_hit_rate_is_high_once_warm():
         hits += st["n_hbm_hits"]
         tot += 8
     assert hits / tot > 0.6
+
+
+def test_chunk_hit_early_in_a_call_may_be_evicted_later_in_the_same_call():
+    """Algorithm 2 handles the chunks of a request one after another: a chunk served
+    from HBM at the start of a request can be the LRU victim of a promotion further
+    down the same request.  The early read keeps the slot it was decided for."""
+    n = 6
+    ctx = _ctx(2, n, 1_000_000)
+    for c in range(n):
+        ctx.pool_insert(c, B.PREC_INT4, 128, None, B.TIER_PINNED)
+    ctx.rerank()
+    ctx.load_chunks([0, 1], FAKE_HBM, 256)               # both promoted, slab full
+    sim = pl.TierSim(list(range(n)), [1_000_000, 0, 0], (2, None, 0))
+    sim.seed(sim.PIN, range(n))
+    for c in (0, 1):
+        sim.access(c)
+    st, tr = ctx.load_chunks([0, 1, 2, 0], FAKE_HBM, 512, want_trace=True)
+    exp = [sim.access(c) for c in (0, 1, 2, 0)]
+    # 2 evicts 0 (least recent); the last 0 is cold again and evicts 1
+    assert [t.found_tier for t in tr] == [0, 0, 1, 1]
+    assert [t.evicted_id for t in tr] == [B.NO_CHUNK, B.NO_CHUNK, 0, 1]
+    assert [e[0] for e in exp] == [sim.GPU, sim.GPU, sim.PIN, sim.PIN]
+    assert ctx.pool_hbm_lru() == sim.resident(sim.GPU) == [2, 0]
+    assert st["n_kernel_launches"] == 1 + 2              # one for the early hits, one per cold chunk
+
+
+def test_copy_made_by_a_call_is_not_dropped_by_the_same_call():
+    """Where this library departs from plain LRU: with fewer slots than a request
+    promotes, the later promotions are skipped instead of evicting copies that the
+    same call has just made (and may still be about to read)."""
+    ctx = _ctx(2, 6, 1_000_000)
+    for c in range(6):
+        ctx.pool_insert(c, B.PREC_INT4, 128, None, B.TIER_PINNED)
+    ctx.rerank()
+    st, tr = ctx.load_chunks([0, 1, 2, 1, 3], FAKE_HBM, 5 * 128, want_trace=True)
+    assert [t.promoted for t in tr] == [1, 1, 0, 0, 0]
+    assert [t.promote_skipped for t in tr] == [0, 0, 1, 0, 1]
+    assert tr[3].found_tier == B.TIER_HBM                # the repeat of 1 reads the new copy
+    assert ctx.pool_hbm_lru() == [0, 1]
