@@ -64,33 +64,46 @@ def build_hbm_pool(B, wl, torch, ctx, shape, T, g, counts, seed0):
     return ids
 
 
-def cpu_baseline(shape, T, g, mix, layers_sampled, seed):
-    """The oracle's dequantize-scatter, single thread, on the first `layers_sampled`
-    layers of one request of the same mix."""
+def cpu_baseline(shape, T, g, mix, min_seconds, seed):
+    """The oracle's dequantize-scatter, single thread, over whole requests of the
+    same shape and mix, repeated until `min_seconds` of CPU time have been spent."""
     import numpy as np
     from oracle import codec
     from paper_2510_20878_amd import workloads as wl
 
     L, H, D = shape
-    Ls = min(L, layers_sampled)
     packed, bits_list = [], []
     for i, bits in enumerate(mix):
-        src = wl.kv_chunk(Ls, H, D, T, seed + i)
+        src = wl.kv_chunk(L, H, D, T, seed + i)
         packed.append(codec.quantize_pack_chunk(src, bits, g)[0])
         bits_list.append(bits)
     n = len(mix)
-    out = np.zeros((Ls, 2, H, n * T, D), np.uint16)
-    t0 = time.perf_counter()
-    codec.load_chunks(packed, (Ls, H, D), [T] * n, bits_list, [g] * n, list(range(n)), out=out,
-                      cap_tokens=n * T)
-    dt = time.perf_counter() - t0
-    nbytes = sum(sum(per_token_bytes(Ls, H, D, b, g)) * T for b in mix)
+    out = np.zeros((L, 2, H, n * T, D), np.uint16)
+    passes, dt = 0, 0.0
+    while dt < min_seconds and passes < 8:
+        t0 = time.perf_counter()
+        codec.load_chunks(packed, (L, H, D), [T] * n, bits_list, [g] * n, list(range(n)), out=out,
+                          cap_tokens=n * T)
+        dt += time.perf_counter() - t0
+        passes += 1
+    nbytes = passes * sum(sum(per_token_bytes(L, H, D, b, g)) * T for b in mix)
     return {
         "value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-        "sample": f"dequantize-scatter of one request ({n} chunks x {T} tokens, bits {mix}), "
-                  f"first {Ls} of {L} layers, {dt:.1f} s",
-        "kv_tokens_per_s": n * T * (Ls / L) / dt,
+        "sample": f"dequantize-scatter of {passes} whole request(s) ({n} chunks x {T} tokens, "
+                  f"bits {mix}, {L} layers), {dt:.1f} s of one host core",
+        "kv_tokens_per_s": passes * n * T / dt,
     }
+
+
+def calibrate(torch, n_bytes=1 << 30, reps=5):
+    """A plain elementwise kernel of known traffic (reads n_bytes, writes n_bytes per
+    launch) so that a counter run can scale FETCH_SIZE / WRITE_SIZE readings."""
+    x = torch.ones(n_bytes // 4, dtype=torch.int32, device="cuda")
+    y = torch.empty_like(x)
+    for _ in range(reps):
+        torch.neg(x, out=y)
+    torch.cuda.synchronize()
+    log(f"calibration: {reps} x torch.neg over {n_bytes} bytes in, {n_bytes} bytes out")
 
 
 def run_hbm(args, B, wl, torch, name):
@@ -110,8 +123,7 @@ def run_hbm(args, B, wl, torch, name):
     n_pool = args.pool_chunks
     counts = {p: int(round(f * n_pool)) for p, f in frac.items()}
     ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g)
-    if args.threads:
-        ctx.set_launch_params(args.threads, args.blocks_per_wave, args.nontemporal)
+    ctx.set_launch_params(args.threads, args.planes16, args.planes8, args.nt_store, args.nt_load)
     t0 = time.time()
     ids = build_hbm_pool(B, wl, torch, ctx, shape, T, g, counts, seed0=args.seed * 1_000_003)
     pool_bytes = sum(ctx.chunk_bytes(p, T) * n for p, n in counts.items())
@@ -165,8 +177,9 @@ def run_hbm(args, B, wl, torch, name):
         "data": "synthetic",
         "config": {"workload": desc, "pool_chunks": n_pool, "pool_gib": round(pool_bytes / 2**30, 1),
                    "tokens_per_step": step_tokens, "bytes_per_step": step_bytes,
-                   "launch": {"threads": args.threads or 256, "blocks_per_wave": args.blocks_per_wave,
-                              "nontemporal": bool(args.nontemporal)}},
+                   "launch": {"threads": args.threads, "planes16": args.planes16,
+                              "planes8": args.planes8, "nt_store": bool(args.nt_store),
+                              "nt_load": bool(args.nt_load)}},
         "kv_tokens_per_s": step_tokens / (ms_per_step * 1e-3),
         "hbm_fraction_whole_path": value / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "kernel": "k1_gather_dequant_scatter", "achieved": achieved,
@@ -257,13 +270,17 @@ def main():
     ap.add_argument("--pool-chunks", type=int, default=0, help="chunks in the HBM pool (0 = default)")
     ap.add_argument("--out-buffers", type=int, default=4)
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--threads", type=int, default=0, help="kernel launch shape override")
-    ap.add_argument("--blocks-per-wave", type=int, default=4)
-    ap.add_argument("--nontemporal", type=int, default=1)
+    ap.add_argument("--threads", type=int, default=64, help="kernel launch shape (see ha_rag.h)")
+    ap.add_argument("--planes16", type=int, default=1)
+    ap.add_argument("--planes8", type=int, default=2)
+    ap.add_argument("--nt-store", type=int, default=1)
+    ap.add_argument("--nt-load", type=int, default=0)
     ap.add_argument("--staging-slots", type=int, default=8)
     ap.add_argument("--copy-streams", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-layers", type=int, default=16)
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also launch a plain elementwise kernel of known size (for counter runs)")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch from rocprofv3 counters (see profiles/), if known")
     args = ap.parse_args()
@@ -279,6 +296,8 @@ def main():
         sys.exit("bench.py: no GPU visible; the load path has no CPU fallback")
     B.lib()
     torch.cuda.set_device(0)
+    if args.calibrate:
+        calibrate(torch)
     if args.workload == "cold8b":
         res = run_cold(args, B, wl, torch)
         shape, T, g, mix = (32, 8, 128), 1024, 64, [4] * 8
@@ -288,7 +307,7 @@ def main():
         res, (shape, T, g, mix) = run_hbm(args, B, wl, torch, args.workload)
     if not args.no_cpu_baseline:
         t0 = time.time()
-        res["cpu_baseline"] = cpu_baseline(shape, T, g, mix, args.cpu_layers, seed=12345)
+        res["cpu_baseline"] = cpu_baseline(shape, T, g, mix, args.cpu_seconds, seed=12345)
         log(f"cpu baseline took {time.time() - t0:.1f} s in all")
     print(json.dumps(res))
 

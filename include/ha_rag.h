@@ -160,12 +160,17 @@ int ha_rag_destroy(ha_rag_ctx *ctx);
  * ctx == NULL: the reason the calling thread's last ha_rag_create failed. */
 const char *ha_rag_last_hip_error(ha_rag_ctx *ctx);
 
-/* Launch shape of the gather-dequantize-scatter kernel: threads per workgroup
- * (64..1024, multiple of 64), blocks of 2048 elements each wave handles (1, 2, 4
- * or 8), nontemporal (streaming) stores on/off.  For tuning sweeps; the defaults
- * are the measured best. */
-int ha_rag_set_launch_params(ha_rag_ctx *ctx, uint32_t threads, uint32_t blocks_per_wave,
-                             uint32_t nontemporal);
+/* Launch shape of the gather-dequantize-scatter kernel, for tuning sweeps; the
+ * defaults are the measured best.  One wave handles one *item*: some of the four
+ * 1024-byte output planes of one 2048-element block. */
+typedef struct ha_rag_launch_params {
+    uint32_t threads;   /* per workgroup: 64..1024, multiple of 64 (one item per wave)  */
+    uint32_t planes16;  /* planes per item for 16-bit chunks: 1, 2 or 4                  */
+    uint32_t planes8;   /* planes per item for int8 chunks: 2 or 4 (int4: always 4)      */
+    uint32_t nt_store;  /* 1 = nontemporal (streaming) stores to the cache              */
+    uint32_t nt_load;   /* 1 = nontemporal loads of the packed payload                  */
+} ha_rag_launch_params;
+int ha_rag_set_launch_params(ha_rag_ctx *ctx, const ha_rag_launch_params *lp);
 
 /* ---- offline: quantize + pack (Algorithm 1 step 3, Compression(S_i, chunk)) -- */
 

@@ -35,6 +35,11 @@ class Config(C.Structure):
         "tau_gpu_ppm", "rerank_interval", "n_copy_streams", "dry_run")]
 
 
+class LaunchParams(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in (
+        "threads", "planes16", "planes8", "nt_store", "nt_load")]
+
+
 class PackedChunk(C.Structure):
     _fields_ = [("packed", C.c_void_p), ("n_tokens", C.c_uint32), ("prec", C.c_uint32),
                 ("group", C.c_uint32), ("reserved", C.c_uint32)]
@@ -103,7 +108,7 @@ def lib():
             "ha_rag_create": (C.c_int, [P(Config), P(vp)]),
             "ha_rag_destroy": (C.c_int, [vp]),
             "ha_rag_last_hip_error": (C.c_char_p, [vp]),
-            "ha_rag_set_launch_params": (C.c_int, [vp, u32, u32, u32]),
+            "ha_rag_set_launch_params": (C.c_int, [vp, P(LaunchParams)]),
             "ha_rag_quantize_chunk": (C.c_int, [vp, vp, u32, u32, u32, vp, vp, vp]),
             "ha_rag_load_packed": (C.c_int, [vp, P(PackedChunk), u32, vp, u64, u64, vp]),
             "ha_rag_register_slab": (C.c_int, [vp, u32, u32, vp, sz]),
@@ -224,9 +229,9 @@ class Context:
         return ha_rag_chunk_bytes(self.cfg.n_layers, self.cfg.n_kv_heads, self.cfg.head_dim, prec,
                                   g, n_tokens)[2]
 
-    def set_launch_params(self, threads, blocks_per_wave, nontemporal):
-        self._chk(lib().ha_rag_set_launch_params(self._h, threads, blocks_per_wave,
-                                                 1 if nontemporal else 0), "ha_rag_set_launch_params")
+    def set_launch_params(self, threads=64, planes16=1, planes8=2, nt_store=1, nt_load=0):
+        lp = LaunchParams(threads, planes16, planes8, int(nt_store), int(nt_load))
+        self._chk(lib().ha_rag_set_launch_params(self._h, C.byref(lp)), "ha_rag_set_launch_params")
 
     def quantize_chunk(self, src, n_tokens, prec, group, dst, saturated=None, stream=None):
         self._chk(lib().ha_rag_quantize_chunk(self._h, _addr(src), n_tokens, prec, group, _addr(dst),

@@ -118,7 +118,7 @@ struct ha_rag_ctx {
     uint64_t copy_rr = 0;
     std::unordered_map<hipStream_t, hipEvent_t> stream_done;
 
-    K1Launch launch{256, 4, true};
+    K1Launch launch{64, 1, 2, true, false};
 
     uint32_t group_of(uint32_t prec) const
     {
@@ -305,23 +305,20 @@ K1Chunk make_desc(const ha_rag_ctx *c, const Chunk &ch, const uint8_t *src, cons
 
 struct Batch {
     K1Params p;
-    uint32_t max_tokens = 0;
 };
 
 int flush(ha_rag_ctx *c, Batch &b, hipStream_t s, uint32_t *launches)
 {
     if (b.p.n_chunks == 0) return HA_RAG_OK;
-    if (!c->dry()) HIPCHK(c, launch_k1(b.p, b.max_tokens, c->launch, s));
+    if (!c->dry()) HIPCHK(c, launch_k1(b.p, c->launch, s));
     if (launches) ++*launches;
     b.p.n_chunks = 0;
-    b.max_tokens = 0;
     return HA_RAG_OK;
 }
 
 int push(ha_rag_ctx *c, Batch &b, const K1Chunk &d, hipStream_t s, uint32_t *launches)
 {
     b.p.c[b.p.n_chunks++] = d;
-    b.max_tokens = std::max(b.max_tokens, d.n_tokens);
     if (b.p.n_chunks == kMaxLaunchChunks) return flush(c, b, s, launches);
     return HA_RAG_OK;
 }
@@ -330,9 +327,8 @@ void init_batch(const ha_rag_ctx *c, Batch &b)
 {
     b.p.n_tiles = c->n_tiles;
     b.p.head_dim = c->cfg.head_dim;
-    b.p.wg_per_tile = 0;
     b.p.n_chunks = 0;
-    b.max_tokens = 0;
+    b.p.total_items = 0;
 }
 
 int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Request *reqs,
@@ -631,14 +627,15 @@ const char *ha_rag_last_hip_error(ha_rag_ctx *c)
     return c ? c->hip_err.c_str() : g_create_err.c_str();
 }
 
-int ha_rag_set_launch_params(ha_rag_ctx *c, uint32_t threads, uint32_t blocks_per_wave,
-                             uint32_t nontemporal)
+int ha_rag_set_launch_params(ha_rag_ctx *c, const ha_rag_launch_params *lp)
 {
-    if (!c) return HA_RAG_EINVAL;
-    if (threads < 64 || threads > 1024 || (threads & 63u)) return HA_RAG_EINVAL;
-    if (blocks_per_wave != 1 && blocks_per_wave != 2 && blocks_per_wave != 4) return HA_RAG_EINVAL;
+    if (!c || !lp) return HA_RAG_EINVAL;
+    if (lp->threads < 64 || lp->threads > 1024 || (lp->threads & 63u)) return HA_RAG_EINVAL;
+    if (lp->planes16 != 1 && lp->planes16 != 2 && lp->planes16 != 4) return HA_RAG_EINVAL;
+    if (lp->planes8 != 2 && lp->planes8 != 4) return HA_RAG_EINVAL;
     std::lock_guard<std::mutex> g(c->mu);
-    c->launch = K1Launch{threads, blocks_per_wave, nontemporal != 0};
+    c->launch = K1Launch{lp->threads, lp->planes16, lp->planes8, lp->nt_store != 0,
+                         lp->nt_load != 0};
     return HA_RAG_OK;
 }
 

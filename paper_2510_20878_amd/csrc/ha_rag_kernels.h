@@ -19,23 +19,28 @@ struct K1Chunk {
     uint32_t fmt;              // bits (16, 8, 4) | log2(group) << 8
 };
 
+// The unit of work of one wave is an *item*: `planes` of the four 1024-byte output
+// planes of one block (int4: always all four, fed by one 16-byte load per lane;
+// int8: two or four; 16-bit: one, two or four).
 struct K1Params {
     uint32_t n_tiles;      // 2 * L * H
     uint32_t head_dim;
-    uint32_t wg_per_tile;  // workgroups that share one tile (from the longest chunk)
     uint32_t n_chunks;
+    uint32_t total_items;
+    uint8_t planes16, planes8, pad[2];
+    uint32_t item_start[kMaxLaunchChunks + 1];  // exclusive prefix sum of items per chunk
     K1Chunk c[kMaxLaunchChunks];
 };
 
 struct K1Launch {
-    uint32_t threads;          // per workgroup, multiple of 64
-    uint32_t blocks_per_wave;  // 1, 2, 4, 8
-    bool nontemporal;
+    uint32_t threads;     // per workgroup, multiple of 64; one item per wave
+    uint32_t planes16;    // 1, 2, 4
+    uint32_t planes8;     // 2, 4
+    bool nt_store, nt_load;
 };
 
-// Enqueues one launch covering p.n_chunks chunks.  max_tokens = longest chunk.
-hipError_t launch_k1(const K1Params &p, uint32_t max_tokens, const K1Launch &cfg,
-                     hipStream_t stream);
+// Enqueues one launch covering p.n_chunks chunks (fills the item fields of p).
+hipError_t launch_k1(K1Params &p, const K1Launch &cfg, hipStream_t stream);
 
 // Quantize + pack one chunk.  src BF16 [n_tiles][n_tokens][D]; dst packed.
 hipError_t launch_k2(const void *src, void *dst, uint32_t n_tiles, uint32_t head_dim,

@@ -74,142 +74,141 @@ __device__ __forceinline__ u32x4 dequant_octet8(uint32_t c0, uint32_t c1, uint32
 }
 
 // ---------------------------------------------------------------------------
-// K1.  Grid: x = tile * wg_per_tile + workgroup-in-tile, y = chunk of the launch.
-// A workgroup of W waves owns W*U consecutive blocks of one tile; wave w takes
-// blocks base + u*W + w.  All loads of a wave's U blocks are issued before the
-// first store so that several KiB per wave are in flight.
+// K1.  One item per wave (see K1Params); 1-D grid over all items of all chunks of
+// the launch, so ragged chunks and mixed tags leave no empty workgroups.  Small
+// items in many short-lived waves measured fastest on MI355X (one 16-byte load per
+// lane feeding one or two 1 KiB stores per wave reaches the rate of a plain copy
+// kernel; four loads then four stores per wave is ~10 % slower).  Items follow the
+// workgroup index linearly: consecutive workgroups, which the hardware deals
+// round robin to the 8 XCDs, touch consecutive KiB; handing each XCD its own
+// contiguous range instead measured slower (nothing is reused, so there is no L2
+// locality to gain, and the XCDs then drift apart).
 // ---------------------------------------------------------------------------
-template <int U, bool NT>
+template <bool NT>
+__device__ __forceinline__ u32x4 ld16s(const uint8_t *p)
+{
+    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return *reinterpret_cast<const u32x4 *>(p);
+}
+
+template <bool NT_ST, bool NT_LD>
 __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params p)
 {
-    const K1Chunk &c = p.c[blockIdx.y];
+    const uint32_t nwaves = blockDim.x >> 6;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t item = blockIdx.x * nwaves + wave;
+    if (item >= p.total_items) return;
+
+    uint32_t lo = 0, hi = p.n_chunks;  // item_start[lo] <= item < item_start[hi]
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (item >= p.item_start[mid]) lo = mid;
+        else hi = mid;
+    }
+    const K1Chunk &c = p.c[lo];
+    const uint32_t it = item - p.item_start[lo];
     const uint32_t n_e = c.n_tokens * p.head_dim;
     const uint32_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
-    const uint32_t nwaves = blockDim.x >> 6;
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
-    const uint32_t tile = blockIdx.x / p.wg_per_tile;
-    const uint32_t wgi = blockIdx.x - tile * p.wg_per_tile;
-    const uint32_t blk_base = wgi * nwaves * U;
-    if (blk_base >= nblk) return;
-
     const uint32_t bits = c.fmt & 0xFFu, gsh = c.fmt >> 8;
-    uint8_t *out_tile = c.out + (uint64_t)tile * c.out_tile_stride;
-    const uint32_t lane_e = lane * 8;   // first element of this lane's octets in plane 0
-    const uint32_t lane_b = lane * 16;  // byte of this lane in a 1024-byte run
+    const uint32_t planes = bits == 4 ? 4u : bits == 8 ? p.planes8 : p.planes16;
+    const uint32_t ipb = 4u / planes;            // items per block
+    const uint32_t per_tile = nblk * ipb;
+    const uint32_t tile = it / per_tile;
+    const uint32_t r = it - tile * per_tile;
+    const uint32_t blk = r / ipb;
+    const uint32_t j0 = (r - blk * ipb) * planes;  // first plane of this item
+
+    const uint32_t lane_b = lane * 16;
+    const uint32_t e = blk * kBlockElems + lane * 8 + j0 * 512;  // element of plane j0
+    uint8_t *o = c.out + (uint64_t)tile * c.out_tile_stride + (uint64_t)blk * 4096u +
+                 j0 * 1024u + lane_b;
 
     if (bits == 4) {
         const uint32_t meta_blk = 8192u >> gsh;
         const uint8_t *pay = c.src + (uint64_t)tile * ((uint64_t)nblk * (1024u + meta_blk));
         const uint8_t *meta = pay + (uint64_t)nblk * 1024u;
-        const uint32_t mword = (lane_e >> gsh) * 16u;
-        u32x4 w[U], m[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t blk = blk_base + u * nwaves + wave;
-            if (blk < nblk) {
-                w[u] = ld16(pay + (uint64_t)blk * 1024u + lane_b);
-                m[u] = ld16(meta + (uint64_t)blk * meta_blk + mword);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t blk = blk_base + u * nwaves + wave;
-            if (blk < nblk) {
-                uint8_t *o = out_tile + (uint64_t)blk * 4096u + lane_b;
-                const uint32_t e = blk * kBlockElems + lane_e;
-                if (e < n_e) st16<NT>(o, dequant_octet4(w[u].x, m[u].x));
-                if (e + 512 < n_e) st16<NT>(o + 1024, dequant_octet4(w[u].y, m[u].y));
-                if (e + 1024 < n_e) st16<NT>(o + 2048, dequant_octet4(w[u].z, m[u].z));
-                if (e + 1536 < n_e) st16<NT>(o + 3072, dequant_octet4(w[u].w, m[u].w));
-            }
-        }
+        const u32x4 w = ld16s<NT_LD>(pay + (uint64_t)blk * 1024u + lane_b);
+        const u32x4 m = ld16(meta + (uint64_t)blk * meta_blk + ((lane * 8) >> gsh) * 16u);
+        if (e < n_e) st16<NT_ST>(o, dequant_octet4(w.x, m.x));
+        if (e + 512 < n_e) st16<NT_ST>(o + 1024, dequant_octet4(w.y, m.y));
+        if (e + 1024 < n_e) st16<NT_ST>(o + 2048, dequant_octet4(w.z, m.z));
+        if (e + 1536 < n_e) st16<NT_ST>(o + 3072, dequant_octet4(w.w, m.w));
     } else if (bits == 8) {
         const uint32_t meta_blk = 8192u >> gsh;
         const uint8_t *pay = c.src + (uint64_t)tile * ((uint64_t)nblk * (2048u + meta_blk));
         const uint8_t *meta = pay + (uint64_t)nblk * 2048u;
-        const uint32_t mword = (lane_e >> gsh) * 16u;
-        u32x4 w0[U], w1[U], m[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t blk = blk_base + u * nwaves + wave;
-            if (blk < nblk) {
-                const uint8_t *b = pay + (uint64_t)blk * 2048u + lane_b;
-                w0[u] = ld16(b);
-                w1[u] = ld16(b + 1024);
-                m[u] = ld16(meta + (uint64_t)blk * meta_blk + mword);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t blk = blk_base + u * nwaves + wave;
-            if (blk < nblk) {
-                uint8_t *o = out_tile + (uint64_t)blk * 4096u + lane_b;
-                const uint32_t e = blk * kBlockElems + lane_e;
-                if (e < n_e) st16<NT>(o, dequant_octet8(w0[u].x, w0[u].y, m[u].x));
-                if (e + 512 < n_e) st16<NT>(o + 1024, dequant_octet8(w0[u].z, w0[u].w, m[u].y));
-                if (e + 1024 < n_e) st16<NT>(o + 2048, dequant_octet8(w1[u].x, w1[u].y, m[u].z));
-                if (e + 1536 < n_e) st16<NT>(o + 3072, dequant_octet8(w1[u].z, w1[u].w, m[u].w));
-            }
+        const uint8_t *b = pay + (uint64_t)blk * 2048u + lane_b;
+        const uint8_t *mp = meta + (uint64_t)blk * meta_blk + ((lane * 8) >> gsh) * 16u;
+        if (planes == 4) {
+            const u32x4 w0 = ld16s<NT_LD>(b), w1 = ld16s<NT_LD>(b + 1024);
+            const u32x4 m = ld16(mp);
+            if (e < n_e) st16<NT_ST>(o, dequant_octet8(w0.x, w0.y, m.x));
+            if (e + 512 < n_e) st16<NT_ST>(o + 1024, dequant_octet8(w0.z, w0.w, m.y));
+            if (e + 1024 < n_e) st16<NT_ST>(o + 2048, dequant_octet8(w1.x, w1.y, m.z));
+            if (e + 1536 < n_e) st16<NT_ST>(o + 3072, dequant_octet8(w1.z, w1.w, m.w));
+        } else {  // two planes: one 16-byte load, the two meta entries of those planes
+            const u32x4 w = ld16s<NT_LD>(b + (j0 >> 1) * 1024u);
+            const uint2 m = *reinterpret_cast<const uint2 *>(mp + j0 * 4u);
+            if (e < n_e) st16<NT_ST>(o, dequant_octet8(w.x, w.y, m.x));
+            if (e + 512 < n_e) st16<NT_ST>(o + 1024, dequant_octet8(w.z, w.w, m.y));
         }
     } else {
-        const uint8_t *pay = c.src + (uint64_t)tile * ((uint64_t)nblk * 4096u);
-        u32x4 w[U][4];
+        const uint8_t *b = c.src + (uint64_t)tile * ((uint64_t)nblk * 4096u) +
+                           (uint64_t)blk * 4096u + j0 * 1024u + lane_b;
+        if (planes == 1) {
+            if (e < n_e) st16<NT_ST>(o, ld16s<NT_LD>(b));
+        } else if (planes == 2) {
+            const u32x4 w0 = ld16s<NT_LD>(b), w1 = ld16s<NT_LD>(b + 1024);
+            if (e < n_e) st16<NT_ST>(o, w0);
+            if (e + 512 < n_e) st16<NT_ST>(o + 1024, w1);
+        } else {
+            u32x4 w[4];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t blk = blk_base + u * nwaves + wave;
-            if (blk < nblk) {
-                const uint8_t *b = pay + (uint64_t)blk * 4096u + lane_b;
+            for (int j = 0; j < 4; ++j) w[j] = ld16s<NT_LD>(b + j * 1024);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) w[u][j] = ld16(b + j * 1024);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t blk = blk_base + u * nwaves + wave;
-            if (blk < nblk) {
-                uint8_t *o = out_tile + (uint64_t)blk * 4096u + lane_b;
-                const uint32_t e = blk * kBlockElems + lane_e;
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (e + j * 512 < n_e) st16<NT>(o + j * 1024, w[u][j]);
-            }
+            for (int j = 0; j < 4; ++j)
+                if (e + j * 512 < n_e) st16<NT_ST>(o + j * 1024, w[j]);
         }
     }
 }
 
-template <int U>
-static hipError_t launch_k1_u(const K1Params &p, dim3 grid, const K1Launch &cfg, hipStream_t s)
+hipError_t launch_k1(K1Params &p, const K1Launch &cfg, hipStream_t stream)
 {
-    if (cfg.nontemporal)
-        hipLaunchKernelGGL((k1_gather_dequant_scatter<U, true>), grid, dim3(cfg.threads), 0, s, p);
-    else
-        hipLaunchKernelGGL((k1_gather_dequant_scatter<U, false>), grid, dim3(cfg.threads), 0, s, p);
-    return hipGetLastError();
-}
-
-hipError_t launch_k1(const K1Params &p_in, uint32_t max_tokens, const K1Launch &cfg,
-                     hipStream_t stream)
-{
-    if (p_in.n_chunks == 0 || max_tokens == 0) return hipSuccess;
-    if (p_in.n_chunks > kMaxLaunchChunks || cfg.threads < 64 || cfg.threads > 1024 ||
+    if (p.n_chunks == 0) return hipSuccess;
+    if (p.n_chunks > kMaxLaunchChunks || cfg.threads < 64 || cfg.threads > 1024 ||
         (cfg.threads & 63u))
         return hipErrorInvalidValue;
-    K1Params p = p_in;
-    const uint64_t n_e = (uint64_t)max_tokens * p.head_dim;
-    if (n_e > 0x7FFFFFFFull) return hipErrorInvalidValue;  // element indices are 32-bit
-    const uint32_t nblk = (uint32_t)((n_e + kBlockElems - 1) / kBlockElems);
-    const uint32_t per_wg = (cfg.threads >> 6) * cfg.blocks_per_wave;
-    p.wg_per_tile = (nblk + per_wg - 1) / per_wg;
-    const uint64_t gx = (uint64_t)p.n_tiles * p.wg_per_tile;
-    if (gx > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    dim3 grid((uint32_t)gx, p.n_chunks);
-    switch (cfg.blocks_per_wave) {
-    case 1: return launch_k1_u<1>(p, grid, cfg, stream);
-    case 2: return launch_k1_u<2>(p, grid, cfg, stream);
-    case 4: return launch_k1_u<4>(p, grid, cfg, stream);
-    case 8: return launch_k1_u<8>(p, grid, cfg, stream);
-    default: return hipErrorInvalidValue;
+    if ((cfg.planes16 != 1 && cfg.planes16 != 2 && cfg.planes16 != 4) ||
+        (cfg.planes8 != 2 && cfg.planes8 != 4))
+        return hipErrorInvalidValue;
+    p.planes16 = (uint8_t)cfg.planes16;
+    p.planes8 = (uint8_t)cfg.planes8;
+    uint64_t total = 0;
+    for (uint32_t i = 0; i < p.n_chunks; ++i) {
+        const uint64_t n_e = (uint64_t)p.c[i].n_tokens * p.head_dim;
+        if (n_e > 0x7FFFFFFFull) return hipErrorInvalidValue;  // element indices are 32-bit
+        const uint64_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
+        const uint32_t bits = p.c[i].fmt & 0xFFu;
+        const uint32_t planes = bits == 4 ? 4u : bits == 8 ? cfg.planes8 : cfg.planes16;
+        p.item_start[i] = (uint32_t)total;
+        total += (uint64_t)p.n_tiles * nblk * (4u / planes);
+        if (total > 0x7FFFFFFFull) return hipErrorInvalidValue;
     }
+    p.item_start[p.n_chunks] = (uint32_t)total;
+    p.total_items = (uint32_t)total;
+    if (total == 0) return hipSuccess;
+    const uint32_t nwaves = cfg.threads >> 6;
+    const uint32_t wgs = (uint32_t)((total + nwaves - 1) / nwaves);
+    dim3 grid(wgs), block(cfg.threads);
+    if (cfg.nt_store) {
+        if (cfg.nt_load) hipLaunchKernelGGL((k1_gather_dequant_scatter<true, true>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((k1_gather_dequant_scatter<true, false>), grid, block, 0, stream, p);
+    } else {
+        if (cfg.nt_load) hipLaunchKernelGGL((k1_gather_dequant_scatter<false, true>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((k1_gather_dequant_scatter<false, false>), grid, block, 0, stream, p);
+    }
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------

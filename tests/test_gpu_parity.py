@@ -154,7 +154,8 @@ def test_tiny_configuration_gather_order_3_0_2_1():
     ctx.destroy()
 
 
-@pytest.mark.parametrize("launch", [None, (64, 1, 0), (256, 2, 1), (512, 4, 0), (1024, 4, 1), (128, 1, 1)])
+@pytest.mark.parametrize("launch", [None, (64, 1, 2, 0, 1), (256, 2, 4, 1, 0), (512, 4, 2, 0, 0),
+                                    (1024, 1, 4, 1, 1), (128, 2, 2, 1, 1), (64, 4, 4, 1, 0)])
 def test_load_mixed_tags_ragged_tokens_all_launch_shapes(launch):
     tokens = [100, 1, 272, 7, 33, 64]
     precs = [B.PREC_INT4, B.PREC_16, B.PREC_INT8, B.PREC_INT4, B.PREC_INT8, B.PREC_16]
