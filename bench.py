@@ -26,6 +26,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+# HBM bytes per launch of the gather-dequantize-scatter kernel on the hbm8b workload, from
+# rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size
+# (profiles/k1_gather_dequant_scatter_hbm8b.md): 1.015 x the algorithmic bytes.
+MEASURED_TRAFFIC = {"hbm8b": 1_013_052_000}
 PCIE_PEAK_GBPS = 63.0           # PCIe Gen5 x16, one direction, theoretical
 
 
@@ -184,7 +188,7 @@ def run_hbm(args, B, wl, torch, name):
         "hbm_fraction_whole_path": value / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "kernel": "k1_gather_dequant_scatter", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": args.traffic_bytes, "kernel_ms": kernel_ms,
+                     "traffic": args.traffic_bytes or MEASURED_TRAFFIC.get(name), "kernel_ms": kernel_ms,
                      "algorithmic_bytes_per_launch": step_bytes},
     }
     return res, (shape, T, g, mix)
