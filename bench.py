@@ -205,7 +205,7 @@ def run_cold(args, B, wl, torch):
     cb = ctx.chunk_bytes(prec, T)
     slot = (cb + 255) // 256 * 256
     n_pool = n_streams * per_req
-    pinned = torch.empty(slot * n_pool, dtype=torch.uint8).pin_memory()
+    pinned = torch.empty(slot * n_pool, dtype=torch.uint8, pin_memory=True)
     ctx.register_slab(B.TIER_PINNED, prec, pinned)
     staging = torch.empty(slot * args.staging_slots, dtype=torch.uint8, device="cuda")
     ctx.register_staging(staging)
@@ -265,12 +265,90 @@ def run_cold(args, B, wl, torch):
     }
 
 
+def run_zipf(args, B, wl, torch):
+    """Mixed-tier batch: ids follow Zipf(1.1); tags by popularity rank (20 % 16-bit, 30 % int8,
+    50 % int4, Algorithm 1); every chunk has a pinned master; the HBM tier holds GPU_LIST
+    (the tau_GPU hottest by the online counters) and fills by promotion (Algorithm 2).  A
+    step is one batch of 32 requests x 8 distinct chunks through ha_rag_load_batch."""
+    import numpy as np
+    shape, T, g = (32, 8, 128), 512, 128
+    L, H, D = shape
+    N = args.pool_chunks or 1000
+    n_req, per_req = 32, 8
+    cls, _ = B.ha_rag_alg1_classes([N - i for i in range(N)], [200_000, 300_000])
+    precs = [(B.PREC_16, B.PREC_INT8, B.PREC_INT4)[c] for c in cls]
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=args.tau_gpu_ppm,
+                    rerank_interval=1, n_copy_streams=args.copy_streams)
+    ctx.set_launch_params(args.threads, args.planes16, args.planes8, args.nt_store, args.nt_load)
+    gpu_list = args.tau_gpu_ppm * N // 1_000_000
+    slot = {p: (ctx.chunk_bytes(p, T) + 255) // 256 * 256 for p in (0, 1, 2)}
+    t0 = time.time()
+    for p in (0, 1, 2):
+        n_p = precs.count(p)
+        ctx.register_slab(B.TIER_PINNED, p, torch.empty(slot[p] * n_p, dtype=torch.uint8, pin_memory=True))
+        # HBM: room for all of GPU_LIST in the class it is expected in, a little elsewhere
+        n_h = max(4, min(n_p, gpu_list if p == B.PREC_16 else gpu_list // 8))
+        ctx.register_slab(B.TIER_HBM, p, torch.empty(slot[p] * n_h, dtype=torch.uint8, device="cuda"))
+    ctx.register_staging(torch.empty(max(slot.values()) * args.staging_slots, dtype=torch.uint8,
+                                     device="cuda"))
+    tmp = torch.empty(max(slot.values()), dtype=torch.uint8, device="cuda")
+    for cid in range(N):
+        src = wl.kv_chunk_device(L, H, D, T, args.seed * 104729 + cid)
+        ctx.quantize_chunk(src, T, precs[cid], g, tmp)
+        ctx.pool_insert(cid, precs[cid], T, tmp, B.TIER_PINNED, packed_is_device=True)
+        torch.cuda.synchronize()
+    pinned_gib = sum(slot[p] * precs.count(p) for p in (0, 1, 2)) / 2**30
+    log(f"zipf pool: {N} ids, {pinned_gib:.1f} GiB pinned, GPU_LIST {gpu_list} ids, built in "
+        f"{time.time() - t0:.1f} s")
+    steps, warmup = max(1, min(args.steps, 40)), max(1, min(args.warmup, 10))
+    draws = wl.zipf_requests(N, (steps + warmup) * n_req, per_req, seed=args.seed + 1)
+    cap = per_req * T
+    outs = [torch.empty((L, 2, H, cap, D), dtype=torch.bfloat16, device="cuda") for _ in range(n_req)]
+    stream = torch.cuda.Stream()
+
+    def batch(k):
+        reqs = [draws[k * n_req + r].tolist() for r in range(n_req)]
+        st, _ = ctx.load_batch(reqs, outs, [cap] * n_req, stream=stream)
+        return st
+
+    for k in range(warmup):
+        batch(k)
+    torch.cuda.synchronize()
+    tot = {}
+    t0 = time.perf_counter()
+    for k in range(warmup, warmup + steps):
+        for key, v in batch(k).items():
+            tot[key] = tot.get(key, 0) + v
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ctx.destroy()
+    ms = wall * 1e3 / steps
+    hbm_bytes = tot["packed_bytes_read"] + tot["bf16_bytes_written"]
+    return {
+        "metric": "kv_load_gbps", "value": hbm_bytes / wall / 1e9, "unit": "GB/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"Zipf(1.1) over {N} chunk ids (the 100k-id pool reduced to what "
+                               "fits in pinned memory), Llama-3-8B KV shape, 512-token chunks, batch "
+                               "of 32 requests x 8 chunks, HBM hot tier + pinned cold tier with "
+                               "promotion", "tau_gpu_ppm": args.tau_gpu_ppm,
+                   "pinned_gib": round(pinned_gib, 1)},
+        "kv_tokens_per_s": tot["tokens"] / wall,
+        "hbm_hit_rate": tot["n_hbm_hits"] / tot["n_chunks"],
+        "promotions": tot["n_promoted"], "evictions": tot["n_evicted"],
+        "link_gbps": tot["bytes_h2d"] / wall / 1e9,
+        "roofline": {"bound": "pcie", "achieved": tot["bytes_h2d"] / wall / 1e9,
+                     "peak": PCIE_PEAK_GBPS, "unit": "GB/s",
+                     "frac": tot["bytes_h2d"] / wall / 1e9 / PCIE_PEAK_GBPS, "traffic": None},
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="hbm8b", choices=["hbm8b", "llama70b", "cold8b"])
+    ap.add_argument("--workload", default="hbm8b", choices=["hbm8b", "llama70b", "cold8b", "zipf"])
     ap.add_argument("--pool-chunks", type=int, default=0, help="chunks in the HBM pool (0 = default)")
     ap.add_argument("--out-buffers", type=int, default=4)
     ap.add_argument("--seed", type=int, default=0)
@@ -281,6 +359,7 @@ def main():
     ap.add_argument("--nt-load", type=int, default=0)
     ap.add_argument("--staging-slots", type=int, default=8)
     ap.add_argument("--copy-streams", type=int, default=0)
+    ap.add_argument("--tau-gpu-ppm", type=int, default=50_000, help="zipf: GPU_LIST fraction (ppm)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--calibrate", action="store_true",
@@ -305,6 +384,9 @@ def main():
     if args.workload == "cold8b":
         res = run_cold(args, B, wl, torch)
         shape, T, g, mix = (32, 8, 128), 1024, 64, [4] * 8
+    elif args.workload == "zipf":
+        res = run_zipf(args, B, wl, torch)
+        shape, T, g, mix = (32, 8, 128), 512, 128, [16] * 2 + [8] * 3 + [4] * 5
     else:
         if args.pool_chunks == 0:
             args.pool_chunks = 2000 if args.workload == "hbm8b" else 400

@@ -26,9 +26,10 @@ struct K1Params {
     uint32_t n_tiles;      // 2 * L * H
     uint32_t head_dim;
     uint32_t n_chunks;
-    uint32_t total_items;
+    uint32_t total_items;     // n_tiles * items_per_tile
+    uint32_t items_per_tile;  // items of all chunks in one tile
     uint8_t planes16, planes8, pad[2];
-    uint32_t item_start[kMaxLaunchChunks + 1];  // exclusive prefix sum of items per chunk
+    uint32_t item_start[kMaxLaunchChunks + 1];  // prefix sum over chunks of items per tile
     K1Chunk c[kMaxLaunchChunks];
 };
 

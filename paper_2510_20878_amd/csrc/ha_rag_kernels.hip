@@ -100,24 +100,25 @@ __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params
     const uint32_t item = blockIdx.x * nwaves + wave;
     if (item >= p.total_items) return;
 
-    uint32_t lo = 0, hi = p.n_chunks;  // item_start[lo] <= item < item_start[hi]
+    // Items are ordered tile by tile, and inside a tile chunk by chunk in request order: the
+    // launch then writes each tile of the cache front to back as one sequential stream.
+    const uint32_t tile = item / p.items_per_tile;
+    const uint32_t rt = item - tile * p.items_per_tile;
+    uint32_t lo = 0, hi = p.n_chunks;  // item_start[lo] <= rt < item_start[hi]
     while (hi - lo > 1) {
         const uint32_t mid = (lo + hi) >> 1;
-        if (item >= p.item_start[mid]) lo = mid;
+        if (rt >= p.item_start[mid]) lo = mid;
         else hi = mid;
     }
     const K1Chunk &c = p.c[lo];
-    const uint32_t it = item - p.item_start[lo];
+    const uint32_t r = rt - p.item_start[lo];
     const uint32_t n_e = c.n_tokens * p.head_dim;
     const uint32_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
     const uint32_t bits = c.fmt & 0xFFu, gsh = c.fmt >> 8;
     const uint32_t planes = bits == 4 ? 4u : bits == 8 ? p.planes8 : p.planes16;
-    const uint32_t ipb = 4u / planes;            // items per block
-    const uint32_t per_tile = nblk * ipb;
-    const uint32_t tile = it / per_tile;
-    const uint32_t r = it - tile * per_tile;
-    const uint32_t blk = r / ipb;
-    const uint32_t j0 = (r - blk * ipb) * planes;  // first plane of this item
+    const uint32_t ipb_sh = planes == 4 ? 0u : planes == 2 ? 1u : 2u;  // log2(items per block)
+    const uint32_t blk = r >> ipb_sh;
+    const uint32_t j0 = (r - (blk << ipb_sh)) * planes;  // first plane of this item
 
     const uint32_t lane_b = lane * 16;
     const uint32_t e = blk * kBlockElems + lane * 8 + j0 * 512;  // element of plane j0
@@ -185,17 +186,21 @@ hipError_t launch_k1(K1Params &p, const K1Launch &cfg, hipStream_t stream)
     p.planes16 = (uint8_t)cfg.planes16;
     p.planes8 = (uint8_t)cfg.planes8;
     uint64_t total = 0;
+    uint64_t per_tile = 0;
     for (uint32_t i = 0; i < p.n_chunks; ++i) {
         const uint64_t n_e = (uint64_t)p.c[i].n_tokens * p.head_dim;
         if (n_e > 0x7FFFFFFFull) return hipErrorInvalidValue;  // element indices are 32-bit
         const uint64_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
         const uint32_t bits = p.c[i].fmt & 0xFFu;
         const uint32_t planes = bits == 4 ? 4u : bits == 8 ? cfg.planes8 : cfg.planes16;
-        p.item_start[i] = (uint32_t)total;
-        total += (uint64_t)p.n_tiles * nblk * (4u / planes);
-        if (total > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        p.item_start[i] = (uint32_t)per_tile;
+        per_tile += nblk * (4u / planes);
+        if (per_tile > 0x7FFFFFFFull) return hipErrorInvalidValue;
     }
-    p.item_start[p.n_chunks] = (uint32_t)total;
+    p.item_start[p.n_chunks] = (uint32_t)per_tile;
+    p.items_per_tile = (uint32_t)per_tile;
+    total = per_tile * p.n_tiles;
+    if (total > 0x7FFFFFFFull) return hipErrorInvalidValue;
     p.total_items = (uint32_t)total;
     if (total == 0) return hipSuccess;
     const uint32_t nwaves = cfg.threads >> 6;
