@@ -356,7 +356,7 @@ def main():
     ap.add_argument("--planes16", type=int, default=1)
     ap.add_argument("--planes8", type=int, default=2)
     ap.add_argument("--nt-store", type=int, default=1)
-    ap.add_argument("--nt-load", type=int, default=0)
+    ap.add_argument("--nt-load", type=int, default=1)
     ap.add_argument("--staging-slots", type=int, default=8)
     ap.add_argument("--copy-streams", type=int, default=0)
     ap.add_argument("--tau-gpu-ppm", type=int, default=50_000, help="zipf: GPU_LIST fraction (ppm)")

@@ -229,7 +229,7 @@ class Context:
         return ha_rag_chunk_bytes(self.cfg.n_layers, self.cfg.n_kv_heads, self.cfg.head_dim, prec,
                                   g, n_tokens)[2]
 
-    def set_launch_params(self, threads=64, planes16=1, planes8=2, nt_store=1, nt_load=0):
+    def set_launch_params(self, threads=64, planes16=1, planes8=2, nt_store=1, nt_load=1):
         lp = LaunchParams(threads, planes16, planes8, int(nt_store), int(nt_load))
         self._chk(lib().ha_rag_set_launch_params(self._h, C.byref(lp)), "ha_rag_set_launch_params")
 

@@ -118,7 +118,7 @@ struct ha_rag_ctx {
     uint64_t copy_rr = 0;
     std::unordered_map<hipStream_t, hipEvent_t> stream_done;
 
-    K1Launch launch{64, 1, 2, true, false};
+    K1Launch launch{64, 1, 2, true, true};
 
     uint32_t group_of(uint32_t prec) const
     {

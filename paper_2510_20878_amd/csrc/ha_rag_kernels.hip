@@ -218,45 +218,81 @@ hipError_t launch_k1(K1Params &p, const K1Launch &cfg, hipStream_t stream)
 
 // ---------------------------------------------------------------------------
 // K2.  One wave per block of 2048 elements; a workgroup of 4 waves takes 4
-// consecutive blocks of one tile.
+// consecutive blocks of one tile.  Bound by VALU issue, not by HBM: every
+// element costs a correctly rounded division.
 // ---------------------------------------------------------------------------
 
 // fp32 -> fp16 word, largest finite value <= x; sets sat if none exists
-__device__ __forceinline__ uint32_t f16_round_down(float x, bool &sat)
+__device__ __forceinline__ uint32_t f16_round_down(float x, uint32_t &sat)
 {
     uint32_t h = __builtin_bit_cast(uint16_t, (_Float16)x);  // nearest even
-    if (h2f(h) > x) {                                          // one step down the number line
-        if ((h & 0x7FFFu) == 0) h = 0x8001u;
-        else if (h & 0x8000u) h += 1;
-        else h -= 1;
-    }
-    if (h == 0xFC00u) { h = 0xFBFFu; sat = true; }
-    if (h == 0x7C00u) h = 0x7BFFu;
-    if (h == 0x8000u) h = 0;
-    return h;
+    const bool step = h2f(h) > x;                              // one step down the number line
+    const uint32_t below = (h & 0x7FFFu) == 0 ? 0x8001u : ((h & 0x8000u) ? h + 1u : h - 1u);
+    h = step ? below : h;
+    sat |= (h == 0xFC00u) ? 1u : 0u;
+    h = (h == 0xFC00u) ? 0xFBFFu : h;
+    h = (h == 0x7C00u) ? 0x7BFFu : h;
+    return (h == 0x8000u) ? 0u : h;
 }
 
 // fp32 -> fp16 word, smallest finite value >= x; sets sat if none exists
-__device__ __forceinline__ uint32_t f16_round_up(float x, bool &sat)
+__device__ __forceinline__ uint32_t f16_round_up(float x, uint32_t &sat)
 {
     uint32_t h = __builtin_bit_cast(uint16_t, (_Float16)x);
-    if (h2f(h) < x) {
-        if ((h & 0x7FFFu) == 0) h = 0x0001u;
-        else if (h & 0x8000u) h -= 1;
-        else h += 1;
-    }
-    if ((h & 0x7FFFu) >= 0x7C00u && h != 0xFC00u) { h = 0x7BFFu; sat = true; }
-    if (h == 0xFC00u) h = 0xFBFFu;
-    if (h == 0x8000u) h = 0;
-    return h;
+    const bool step = h2f(h) < x;
+    const uint32_t above = (h & 0x7FFFu) == 0 ? 0x0001u : ((h & 0x8000u) ? h - 1u : h + 1u);
+    h = step ? above : h;
+    const bool over = (h & 0x7FFFu) >= 0x7C00u && h != 0xFC00u;
+    sat |= over ? 1u : 0u;
+    h = over ? 0x7BFFu : h;
+    h = (h == 0xFC00u) ? 0xFBFFu : h;
+    return (h == 0x8000u) ? 0u : h;
 }
 
-template <int BITS>
+// value of another lane of the same 16-lane row, through the data-parallel-primitive path
+template <int CTRL>
+__device__ __forceinline__ float dpp(float v)
+{
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+// min and max over the 2^(GSH-3) consecutive lanes that share a group; every lane gets both
+template <int GSH>
+__device__ __forceinline__ void group_minmax(float &mn, float &mx)
+{
+    constexpr int LPG = (1 << GSH) >> 3;
+    if (LPG >= 2) {  // lane ^ 1: quad_perm [1,0,3,2]
+        mn = fminf(mn, dpp<0xB1>(mn));
+        mx = fmaxf(mx, dpp<0xB1>(mx));
+    }
+    if (LPG >= 4) {  // lane ^ 2: quad_perm [2,3,0,1]
+        mn = fminf(mn, dpp<0x4E>(mn));
+        mx = fmaxf(mx, dpp<0x4E>(mx));
+    }
+    if (LPG >= 8) {  // row_half_mirror: lane i <-> 7 - i inside each 8 lanes
+        mn = fminf(mn, dpp<0x141>(mn));
+        mx = fmaxf(mx, dpp<0x141>(mx));
+    }
+    if (LPG >= 16) {  // row_mirror: lane i <-> 15 - i inside each 16 lanes
+        mn = fminf(mn, dpp<0x140>(mn));
+        mx = fmaxf(mx, dpp<0x140>(mx));
+    }
+    if (LPG >= 32) {
+        mn = fminf(mn, __shfl_xor(mn, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+    }
+    if (LPG >= 64) {
+        mn = fminf(mn, __shfl_xor(mn, 32));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+    }
+}
+
+template <int BITS, int GSH>
 __global__ void __launch_bounds__(256) k2_quantize_pack(const uint8_t *__restrict__ src,
                                                         uint8_t *__restrict__ dst,
                                                         uint32_t n_tokens, uint32_t head_dim,
-                                                        uint32_t gsh, uint32_t wg_per_tile,
-                                                        uint32_t *saturated)
+                                                        uint32_t wg_per_tile, uint32_t *saturated)
 {
     const uint32_t n_e = n_tokens * head_dim;
     const uint32_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
@@ -271,21 +307,14 @@ __global__ void __launch_bounds__(256) k2_quantize_pack(const uint8_t *__restric
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         raw[j] = u32x4{0, 0, 0, 0};
-        if (e + j * 512 < n_e) raw[j] = ld16(in + j * 1024);
+        if (e + j * 512 < n_e) raw[j] = ld16s<true>(in + j * 1024);
     }
 
-    if (BITS == 16) {
-        uint8_t *o = dst + (uint64_t)tile * nblk * 4096u + (uint64_t)blk * 4096u + lane * 16u;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) st16<false>(o + j * 1024, raw[j]);
-        return;
-    }
-
-    const uint32_t meta_blk = 8192u >> gsh;
-    const uint32_t pay_blk = 256u * BITS;
+    constexpr uint32_t meta_blk = 8192u >> GSH;
+    constexpr uint32_t pay_blk = 256u * BITS;
+    constexpr uint32_t lanes_per_group = (1u << GSH) >> 3;
     uint8_t *pay = dst + (uint64_t)tile * nblk * (pay_blk + meta_blk);
     uint8_t *meta = pay + (uint64_t)nblk * pay_blk;
-    const uint32_t lanes_per_group = (1u << gsh) >> 3;
     const float qmax = (float)((1 << BITS) - 1);
 
     u32x4 mrow;      // the four {scale, zero} entries of this lane's planes
@@ -305,27 +334,41 @@ __global__ void __launch_bounds__(256) k2_quantize_pack(const uint8_t *__restric
             mn = fminf(mn, x[k]);
             mx = fmaxf(mx, x[k]);
         }
-        for (uint32_t o = 1; o < lanes_per_group; o <<= 1) {
-            mn = fminf(mn, __shfl_xor(mn, (int)o));
-            mx = fmaxf(mx, __shfl_xor(mx, (int)o));
-        }
-        bool sat = false;
+        group_minmax<GSH>(mn, mx);
+        uint32_t sat = 0;
         const uint32_t zh = f16_round_down(mn, sat);
         const float z = h2f(zh);
         const float range = mx - z;
         const float sc = range / qmax;
         const uint32_t sh = f16_round_up(sc, sat);
         const float s = h2f(sh);
-        n_sat += sat ? 1u : 0u;
+        n_sat += sat;
         mrow[j] = sh | (zh << 16);
+        // A constant group has scale 0 and every x equal to zero: divide by 1 instead, the
+        // quotient is 0.
+        const float sd = (s != 0.0f) ? s : 1.0f;
+        // d / sd eight times by the same divisor: the reciprocal is refined once (rcp, one
+        // Newton step); each quotient is then a multiply plus one residual correction
+        // (q1 = q0 + (d - sd*q0) * r1).  q1 can differ from the correctly rounded quotient
+        // only when d/sd lies within ~2^-21 ulp of the midpoint of two floats, and the code
+        // depends on the quotient only through its side of a half-integer k + 1/2.  Because
+        // sd has at most 11 significant bits and k < 256, (k + 1/2) * sd is a float: an exact
+        // tie (d equal to it) gives q1 = k + 1/2 exactly, and any other d puts the true
+        // quotient more than 2^-13 ulp away from the float midpoints next to k + 1/2, so q1
+        // falls on the same side as the correctly rounded quotient does.
+        const float r0 = __builtin_amdgcn_rcpf(sd);
+        const float r1 = __builtin_fmaf(__builtin_fmaf(-sd, r0, 1.0f), r0, r0);
+        // Clamping before rounding equals rounding before clamping (the bounds are integers),
+        // and adding 2^23 rounds a float in [0, 2^22) to the nearest integer, ties to even,
+        // leaving that integer in the low mantissa bits.
         uint32_t q[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const float d = x[k] - z;
-            const float t = d / s;
-            float r = __builtin_rintf(t);
-            r = fminf(fmaxf(r, 0.0f), qmax);
-            q[k] = (s != 0.0f) ? (uint32_t)r : 0u;
+            const float q0 = d * r1;
+            const float q1 = __builtin_fmaf(__builtin_fmaf(-sd, q0, d), r1, q0);
+            const float t = __builtin_amdgcn_fmed3f(q1, 0.0f, qmax);
+            q[k] = __builtin_bit_cast(uint32_t, t + 8388608.0f) & 0xFFu;
         }
         if (BITS == 4) {
             code_lo[j] = q[0] | (q[1] << 4) | (q[2] << 8) | (q[3] << 12) | (q[4] << 16) |
@@ -344,8 +387,38 @@ __global__ void __launch_bounds__(256) k2_quantize_pack(const uint8_t *__restric
         st16<false>(o + 1024, u32x4{code_lo[2], code_hi[2], code_lo[3], code_hi[3]});
     }
     if ((lane & (lanes_per_group - 1)) == 0) {  // first lane of each group
-        st16<false>(meta + (uint64_t)blk * meta_blk + ((lane * 8u) >> gsh) * 16u, mrow);
+        st16<false>(meta + (uint64_t)blk * meta_blk + ((lane * 8u) >> GSH) * 16u, mrow);
         if (saturated != nullptr && n_sat) atomicAdd(saturated, n_sat);
+    }
+}
+
+// The 16-bit tag stores the BF16 words verbatim: one 1024-byte plane per wave (the shape
+// that copies fastest), zero fill behind the last element of a tile.
+__global__ void __launch_bounds__(64) k2_pack16(const uint8_t *__restrict__ src,
+                                                uint8_t *__restrict__ dst, uint32_t n_tokens,
+                                                uint32_t head_dim, uint32_t planes_per_tile)
+{
+    const uint32_t n_e = n_tokens * head_dim;
+    const uint32_t tile = blockIdx.x / planes_per_tile;
+    const uint32_t pl = blockIdx.x - tile * planes_per_tile;   // plane = 512 elements
+    const uint32_t e = pl * 512u + threadIdx.x * 8u;
+    u32x4 w = u32x4{0, 0, 0, 0};
+    if (e < n_e) w = ld16s<true>(src + ((uint64_t)tile * n_e + e) * 2u);
+    st16<false>(dst + ((uint64_t)tile * planes_per_tile * 512u + e) * 2u, w);
+}
+
+template <int BITS>
+static void launch_k2_g(uint32_t gsh, dim3 grid, hipStream_t stream, const uint8_t *s, uint8_t *d,
+                        uint32_t n_tokens, uint32_t head_dim, uint32_t wg_per_tile,
+                        uint32_t *saturated)
+{
+    dim3 block(256);
+    switch (gsh) {
+    case 5: hipLaunchKernelGGL((k2_quantize_pack<BITS, 5>), grid, block, 0, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated); break;
+    case 6: hipLaunchKernelGGL((k2_quantize_pack<BITS, 6>), grid, block, 0, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated); break;
+    case 7: hipLaunchKernelGGL((k2_quantize_pack<BITS, 7>), grid, block, 0, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated); break;
+    case 8: hipLaunchKernelGGL((k2_quantize_pack<BITS, 8>), grid, block, 0, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated); break;
+    default: hipLaunchKernelGGL((k2_quantize_pack<BITS, 9>), grid, block, 0, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated); break;
     }
 }
 
@@ -364,18 +437,18 @@ hipError_t launch_k2(const void *src, void *dst, uint32_t n_tiles, uint32_t head
     while ((1u << gsh) < group) ++gsh;
     const uint8_t *s = static_cast<const uint8_t *>(src);
     uint8_t *d = static_cast<uint8_t *>(dst);
-    dim3 grid((uint32_t)gx), block(256);
-    if (bits == 16)
-        hipLaunchKernelGGL(k2_quantize_pack<16>, grid, block, 0, stream, s, d, n_tokens, head_dim,
-                           gsh, wg_per_tile, saturated);
-    else if (bits == 8)
-        hipLaunchKernelGGL(k2_quantize_pack<8>, grid, block, 0, stream, s, d, n_tokens, head_dim,
-                           gsh, wg_per_tile, saturated);
-    else if (bits == 4)
-        hipLaunchKernelGGL(k2_quantize_pack<4>, grid, block, 0, stream, s, d, n_tokens, head_dim,
-                           gsh, wg_per_tile, saturated);
-    else
-        return hipErrorInvalidValue;
+    dim3 grid((uint32_t)gx);
+    if (bits == 16) {
+        const uint64_t planes = (uint64_t)n_tiles * nblk * 4u;
+        if (planes > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(k2_pack16, dim3((uint32_t)planes), dim3(64), 0, stream, s, d, n_tokens,
+                           head_dim, nblk * 4u);
+    } else {
+        if (gsh < 5 || gsh > 9 || (1u << gsh) != group) return hipErrorInvalidValue;
+        if (bits == 8) launch_k2_g<8>(gsh, grid, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated);
+        else if (bits == 4) launch_k2_g<4>(gsh, grid, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated);
+        else return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

@@ -107,6 +107,28 @@ def test_quantize_pack_bytes_equal_oracle(shape, prec):
     ctx.destroy()
 
 
+@pytest.mark.parametrize("prec,g", [(B.PREC_INT8, 128), (B.PREC_INT4, 64), (B.PREC_INT8, 32)])
+def test_quantize_codes_bit_exact_on_tens_of_millions_of_elements(prec, g):
+    """The kernel divides by a shared refined reciprocal; the oracle by IEEE division.
+    Rows get widely different magnitudes and offsets so that scales, zeros and quotients
+    cover many binades and many near-half-integer quotients occur."""
+    L, H, D, T = 16, 8, 128, 1024                      # 33.5 M elements
+    rng = np.random.Generator(np.random.PCG64(99 + prec + g))
+    x = rng.standard_normal((L, 2, H, T, D), dtype=np.float32)
+    x *= np.exp(rng.normal(0, 2.5, (L, 2, H, T, 1))).astype(np.float32)
+    x += (rng.normal(0, 3, (L, 2, H, T, 1)) * np.exp(rng.normal(0, 2, (L, 2, H, T, 1)))).astype(np.float32)
+    # a share of rows on a coarse grid: many exact ties
+    x[:, :, :, ::7] = np.round(x[:, :, :, ::7] * 2) / 2
+    src = wl.f32_to_bf16_words(x)
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g)
+    ref, ref_sat = codec.quantize_pack_chunk(src, B.BITS[prec], g)
+    got, got_sat = gpu_quantize(ctx, src, prec, g)
+    bad = np.flatnonzero(got != ref)
+    assert bad.size == 0, f"{bad.size} bytes differ, first at {bad[:5]}"
+    assert got_sat == ref_sat
+    ctx.destroy()
+
+
 def _load_case(shape, tokens, precs, g, order, seed, cap_extra=0, tok_base=0, launch=None):
     L, H, D = shape
     ctx = B.Context(L, H, D, max(tokens), group_int8=g, group_int4=g)
