@@ -29,7 +29,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the gather-dequantize-scatter kernel on the hbm8b workload, from
 # rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size
 # (profiles/k1_gather_dequant_scatter_hbm8b.md): 1.015 x the algorithmic bytes.
-MEASURED_TRAFFIC = {"hbm8b": 1_013_052_000}
+MEASURED_TRAFFIC = {"hbm8b": 1_013_000_000}
 PCIE_PEAK_GBPS = 63.0           # PCIe Gen5 x16, one direction, theoretical
 
 
