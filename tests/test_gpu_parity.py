@@ -386,47 +386,115 @@ def test_batch_of_requests_one_call():
     ctx.destroy()
 
 
-# ---- the benchmark's own shape and launch configuration ----------------------------
-def test_llama3_8b_request_sampled_tiles_match_oracle():
-    """One request of the headline workload (32 layers, 8 KV heads, head_dim 128, ten
-    512-token chunks: 2 x 16-bit, 3 x int8, 5 x int4, group 128) built and loaded by
-    the GPU in the launch configuration the benchmark times; K/V tile pairs sampled
-    across chunks are recomputed by the oracle from the same source words."""
-    L, H, D, T, g = 32, 8, 128, 512, 128
-    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g)
-    precs = [B.PREC_16] * 2 + [B.PREC_INT8] * 3 + [B.PREC_INT4] * 5
-    order = [4, 9, 0, 6, 2, 8, 1, 5, 3, 7]
-    srcs, packs = [], []
-    for i, p in enumerate(precs):
-        s = wl.kv_chunk_device(L, H, D, T, 500 + i)
-        dst = torch.empty(ctx.chunk_bytes(p, T), dtype=torch.uint8, device="cuda")
-        ctx.quantize_chunk(s, T, p, g, dst)
-        srcs.append(s)
-        packs.append(dst)
-    cap = 10 * T
-    out = torch.empty((L, 2, H, cap, D), dtype=torch.int16, device="cuda")
-    ctx.load_packed([(packs[c], T, precs[c], g) for c in order], out, cap)
-    torch.cuda.synchronize()
-    rng = np.random.default_rng(0)
-    for pos, c in enumerate(order):
+# ---- the benchmark's own shapes and launch configuration ----------------------------
+def _check_sampled_tiles(ctx, shape, T, g, precs, order, srcs, packs, out, n_samples, rng):
+    """K/V tile pairs sampled across the chunks of a request are recomputed by the oracle from
+    the same source words: packed tile records and cache rows must match."""
+    L, H, D = shape
+    pos_of = {}
+    pos = 0
+    for c in order:
+        pos_of.setdefault(c, pos)
+        pos += T
+    for c in sorted(set(order)):
         bits = B.BITS[precs[c]]
         tile_bytes = codec.chunk_bytes(1, 1, D, T, bits, g) // 2
-        for _ in range(3):
+        for _ in range(n_samples):
             l, h = int(rng.integers(L)), int(rng.integers(H))
             src_kv = srcs[c][l, :, h].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
-            mini = src_kv.reshape(1, 2, 1, T, D)
-            ref_pack, _ = codec.quantize_pack_chunk(mini, bits, g)
+            ref_pack, _ = codec.quantize_pack_chunk(src_kv.reshape(1, 2, 1, T, D), bits, g)
             for kv in range(2):
                 tile = (l * 2 + kv) * H + h
                 got = packs[c][tile * tile_bytes:(tile + 1) * tile_bytes].cpu().numpy()
                 assert np.array_equal(got, ref_pack[kv * tile_bytes:(kv + 1) * tile_bytes])
             ref_out = np.zeros((1, 2, 1, T, D), np.uint16)
             codec.dequant_scatter_chunk(ref_pack, (1, 1, D), T, bits, g, ref_out, 0)
-            got_out = host_u16(out[l, :, h, pos * T:(pos + 1) * T])
+            p0 = pos_of[c]
+            got_out = host_u16(out[l, :, h, p0:p0 + T])
             assert ulp_distance(got_out, ref_out[0, :, 0]).max() <= 1
             assert np.array_equal(got_out, ref_out[0, :, 0])
-    # properties that hold at any size: 16-bit chunks are copied word for word
+
+
+def test_llama3_8b_request_sampled_tiles_match_oracle():
+    """One request of the headline workload (32 layers, 8 KV heads, head_dim 128, ten
+    512-token chunks: 2 x 16-bit, 3 x int8, 5 x int4, group 128) built and loaded by
+    the GPU in the launch configuration the benchmark times."""
+    L, H, D, T, g = 32, 8, 128, 512, 128
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g)
+    precs = [B.PREC_16] * 2 + [B.PREC_INT8] * 3 + [B.PREC_INT4] * 5
+    order = [4, 9, 0, 6, 2, 8, 1, 5, 3, 7]
+    srcs, packs = [], []
+    for i, p in enumerate(precs):
+        s_ = wl.kv_chunk_device(L, H, D, T, 500 + i)
+        dst = torch.empty(ctx.chunk_bytes(p, T), dtype=torch.uint8, device="cuda")
+        ctx.quantize_chunk(s_, T, p, g, dst)
+        srcs.append(s_)
+        packs.append(dst)
+    cap = 10 * T
+    out = torch.empty((L, 2, H, cap, D), dtype=torch.int16, device="cuda")
+    ctx.load_packed([(packs[c], T, precs[c], g) for c in order], out, cap)
+    torch.cuda.synchronize()
+    _check_sampled_tiles(ctx, (L, H, D), T, g, precs, order, srcs, packs, out, 3,
+                         np.random.default_rng(0))
+    # a property that holds at any size: 16-bit chunks are copied word for word
     for pos, c in enumerate(order):
         if precs[c] == B.PREC_16:
             assert torch.equal(out[:, :, :, pos * T:(pos + 1) * T], srcs[c].view(torch.int16))
+    ctx.destroy()
+
+
+def test_llama3_70b_request_sampled_tiles_match_oracle():
+    """80 layers, 8 KV heads, head_dim 128, sixteen 1024-token chunks, int8 and int4
+    alternating (group 128): 5 GiB of cache written by one launch."""
+    L, H, D, T, g = 80, 8, 128, 1024, 128
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g)
+    n_distinct = 4                                     # sources are reused: 16 x 320 MiB is a lot
+    precs = [B.PREC_INT8, B.PREC_INT4] * (n_distinct // 2)
+    srcs, packs = [], []
+    for i, p in enumerate(precs):
+        s_ = wl.kv_chunk_device(L, H, D, T, 600 + i)
+        dst = torch.empty(ctx.chunk_bytes(p, T), dtype=torch.uint8, device="cuda")
+        ctx.quantize_chunk(s_, T, p, g, dst)
+        srcs.append(s_)
+        packs.append(dst)
+    order = [i % n_distinct for i in range(16)]
+    cap = 16 * T
+    out = torch.empty((L, 2, H, cap, D), dtype=torch.int16, device="cuda")
+    ctx.load_packed([(packs[c], T, precs[c], g) for c in order], out, cap)
+    torch.cuda.synchronize()
+    _check_sampled_tiles(ctx, (L, H, D), T, g, precs, order[:n_distinct], srcs, packs, out, 2,
+                         np.random.default_rng(1))
+    # every repeat of a chunk must equal its first occurrence, over the whole 5 GiB
+    for pos in range(n_distinct, 16):
+        first = order[pos]
+        assert torch.equal(out[:, :, :, pos * T:(pos + 1) * T], out[:, :, :, first * T:(first + 1) * T])
+    ctx.destroy()
+
+
+def test_cold_stress_shape_through_the_pool():
+    """The cold-path stress shape: 8B KV, 1024-token int4 chunks with group 64, every chunk in
+    pinned memory, two requests on two streams through a 3-slot staging ring."""
+    L, H, D, T, g = 32, 8, 128, 1024, 64
+    n = 6
+    ctx = _pool_ctx(L, H, D, T, g, hbm_slots=0, pin_slots=n, stg_slots=3, tau_gpu_ppm=0,
+                    precs=[B.PREC_INT4])
+    srcs, packs = [], []
+    for i in range(n):
+        s_ = wl.kv_chunk_device(L, H, D, T, 700 + i)
+        dst = torch.empty(ctx.chunk_bytes(B.PREC_INT4, T), dtype=torch.uint8, device="cuda")
+        ctx.quantize_chunk(s_, T, B.PREC_INT4, g, dst)
+        ctx.pool_insert(i, B.PREC_INT4, T, dst, B.TIER_PINNED, packed_is_device=True)
+        srcs.append(s_)
+        packs.append(dst)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    orders = [[2, 0, 1], [5, 3, 4]]
+    outs = [torch.empty((L, 2, H, 3 * T, D), dtype=torch.int16, device="cuda") for _ in range(2)]
+    for r in range(2):
+        st, _ = ctx.load_chunks(orders[r], outs[r], 3 * T, stream=streams[r])
+        assert st["n_pinned_hits"] == 3 and st["bytes_h2d"] == 3 * ctx.chunk_bytes(B.PREC_INT4, T)
+    torch.cuda.synchronize()
+    for r in range(2):
+        _check_sampled_tiles(ctx, (L, H, D), T, g, [B.PREC_INT4] * n, orders[r], srcs, packs,
+                             outs[r], 2, np.random.default_rng(2 + r))
     ctx.destroy()

@@ -270,3 +270,25 @@ def test_copy_made_by_a_call_is_not_dropped_by_the_same_call():
     assert [t.promote_skipped for t in tr] == [0, 0, 1, 0, 1]
     assert tr[3].found_tier == B.TIER_HBM                # the repeat of 1 reads the new copy
     assert ctx.pool_hbm_lru() == [0, 1]
+
+
+def test_limits_are_rejected_not_wrapped():
+    # element indices inside a tile are 32-bit: tokens * head_dim must stay below 2^31
+    with pytest.raises(B.HaRagError) as e:
+        B.ha_rag_chunk_bytes(1, 1, 128, B.PREC_INT4, 128, 2**24)
+    assert e.value.code == B.EINVAL
+    with pytest.raises(B.HaRagError) as e:
+        B.Context(1, 1, 128, 2**24, dry_run=True)
+    assert e.value.code == B.EINVAL
+    pay, meta, total = B.ha_rag_chunk_bytes(1, 1, 128, B.PREC_INT4, 128, 2**24 - 1)
+    assert total == codec.chunk_bytes(1, 1, 128, 2**24 - 1, 4, 128)
+    # a request may list at most 4096 chunks
+    ctx = _ctx(2, 4, 0)
+    ctx.pool_insert(0, B.PREC_INT4, 128, None, B.TIER_HBM)
+    st, _ = ctx.load_chunks([0] * 4096, FAKE_HBM, 4096 * 128)
+    assert st["tokens"] == 4096 * 128 and st["n_kernel_launches"] == 64
+    with pytest.raises(B.HaRagError) as e:
+        ctx.load_chunks([0] * 4097, FAKE_HBM, 4097 * 128)
+    assert e.value.code == B.EINVAL
+    st, _ = ctx.load_chunks([], FAKE_HBM, 0)              # an empty request is legal
+    assert st["n_chunks"] == 0 and st["n_kernel_launches"] == 0
