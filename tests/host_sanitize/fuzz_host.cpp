@@ -1,0 +1,130 @@
+// Random sequences of pool / hotness / load calls on dry_run contexts (host
+// bookkeeping only: no HIP call, no byte moved), meant to be built with
+// -fsanitize=address,undefined on the host side.  Checks a few invariants after
+// every call and exits non-zero on the first violation.
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <set>
+#include <vector>
+
+#include "../../include/ha_rag.h"
+
+static uint64_t rng_state = 0x9E3779B97F4A7C15ull;
+static uint64_t rnd()
+{
+    rng_state ^= rng_state << 13;
+    rng_state ^= rng_state >> 7;
+    rng_state ^= rng_state << 17;
+    return rng_state;
+}
+
+#define REQUIRE(cond)                                                          \
+    do {                                                                       \
+        if (!(cond)) {                                                         \
+            std::fprintf(stderr, "fuzz_host: %s failed at line %d\n", #cond, __LINE__); \
+            std::exit(1);                                                      \
+        }                                                                      \
+    } while (0)
+
+int main(int argc, char **argv)
+{
+    const int rounds = argc > 1 ? std::atoi(argv[1]) : 200;
+    for (int round = 0; round < rounds; ++round) {
+        ha_rag_config cfg;
+        std::memset(&cfg, 0, sizeof cfg);
+        cfg.n_layers = 1 + rnd() % 3;
+        cfg.n_kv_heads = 1 + rnd() % 3;
+        cfg.head_dim = 128;
+        cfg.max_chunk_tokens = 16 + rnd() % 100;
+        cfg.group_int8 = 128;
+        cfg.group_int4 = 64;
+        cfg.tau_gpu_ppm = (uint32_t)(rnd() % 1000001);
+        cfg.rerank_interval = (uint32_t)(rnd() % 4);
+        cfg.dry_run = 1;
+        ha_rag_ctx *ctx = nullptr;
+        REQUIRE(ha_rag_create(&cfg, &ctx) == HA_RAG_OK);
+        const uint32_t hbm_slots = 1 + rnd() % 4, pin_slots = 4 + rnd() % 12;
+        size_t slot[HA_RAG_N_PREC];
+        for (uint32_t p = 0; p < HA_RAG_N_PREC; ++p) {
+            size_t total;
+            const uint32_t g = p == HA_RAG_PREC_INT8 ? 128 : 64;
+            REQUIRE(ha_rag_chunk_bytes(cfg.n_layers, cfg.n_kv_heads, cfg.head_dim, p, g,
+                                       cfg.max_chunk_tokens, nullptr, nullptr, &total) == HA_RAG_OK);
+            slot[p] = (total + 255) & ~(size_t)255;
+            REQUIRE(ha_rag_register_slab(ctx, HA_RAG_TIER_HBM, p, (void *)(0x100000000000ull + p * 0x10000000000ull),
+                                         slot[p] * hbm_slots) == HA_RAG_OK);
+            REQUIRE(ha_rag_register_slab(ctx, HA_RAG_TIER_PINNED, p, (void *)(0x200000000000ull + p * 0x10000000000ull),
+                                         slot[p] * pin_slots) == HA_RAG_OK);
+        }
+        REQUIRE(ha_rag_register_staging(ctx, (void *)0x300000000000ull, slot[0] * (2 + rnd() % 3)) == HA_RAG_OK);
+        std::vector<uint64_t> known;
+        for (int op = 0; op < 400; ++op) {
+            const uint64_t what = rnd() % 100;
+            if (what < 25) {  // insert somewhere
+                const uint64_t id = rnd() % 40;
+                const uint32_t prec = rnd() % 3, tier = rnd() % 2;
+                const uint32_t tok = 1 + rnd() % cfg.max_chunk_tokens;
+                int rc = ha_rag_pool_insert(ctx, id, prec, tok, nullptr, 0, tier, nullptr);
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_EINVAL || rc == HA_RAG_ENOSPC || rc == HA_RAG_EFORMAT);
+                if (rc == HA_RAG_OK) known.push_back(id);
+            } else if (what < 75 && !known.empty()) {  // a request (single or batch)
+                const uint32_t n_req = 1 + rnd() % 3;
+                std::vector<uint64_t> ids;
+                std::vector<uint32_t> starts(1, 0);
+                std::vector<void *> outs;
+                std::vector<uint64_t> caps, bases;
+                for (uint32_t r = 0; r < n_req; ++r) {
+                    const uint32_t k = rnd() % 7;
+                    for (uint32_t i = 0; i < k; ++i)
+                        ids.push_back(rnd() % 50 == 0 ? 999 : known[rnd() % known.size()]);
+                    starts.push_back((uint32_t)ids.size());
+                    outs.push_back((void *)(0x400000000000ull + r * 0x1000000000ull));
+                    caps.push_back(rnd() % 5 == 0 ? 10 : 7 * (uint64_t)cfg.max_chunk_tokens + 5);
+                    bases.push_back(rnd() % 6);
+                }
+                std::vector<ha_rag_chunk_trace> tr(ids.size() + 1);
+                ha_rag_load_stats st;
+                int rc = ha_rag_load_batch(ctx, ids.data(), nullptr, starts.data(), n_req, outs.data(),
+                                           caps.data(), bases.data(), nullptr, &st, tr.data());
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOENT || rc == HA_RAG_ENOSPC);
+                if (rc == HA_RAG_OK) {
+                    REQUIRE(st.n_chunks == ids.size());
+                    REQUIRE(st.n_hbm_hits + st.n_pinned_hits == st.n_chunks);
+                    REQUIRE(st.n_evicted <= st.n_promoted);
+                }
+            } else if (what < 82 && !known.empty()) {
+                int rc = ha_rag_pool_promote(ctx, known[rnd() % known.size()], nullptr);
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOSPC || rc == HA_RAG_ENOENT);
+            } else if (what < 88 && !known.empty()) {
+                int rc = ha_rag_pool_evict(ctx, known[rnd() % known.size()]);
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_EINVAL || rc == HA_RAG_ENOENT);
+            } else if (what < 94) {
+                REQUIRE(ha_rag_rerank(ctx) == HA_RAG_OK);
+            } else if (!known.empty()) {
+                uint64_t ids2[3] = {known[rnd() % known.size()], known[rnd() % known.size()], rnd() % 60};
+                int rc = ha_rag_touch(ctx, ids2, 3);
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOENT);
+            }
+            // invariants: residency lists are consistent with per-chunk queries
+            uint64_t lru[256];
+            size_t n_lru = 0;
+            REQUIRE(ha_rag_pool_hbm_lru(ctx, lru, 256, &n_lru) == HA_RAG_OK);
+            REQUIRE(n_lru <= (size_t)hbm_slots * HA_RAG_N_PREC);
+            std::set<uint64_t> seen;
+            for (size_t i = 0; i < n_lru; ++i) {
+                REQUIRE(seen.insert(lru[i]).second);
+                ha_rag_chunk_info info;
+                REQUIRE(ha_rag_pool_query(ctx, lru[i], &info) == HA_RAG_OK);
+                REQUIRE(info.in_hbm == 1 && info.hbm_ptr != nullptr);
+                void *p = nullptr;
+                size_t nb = 0;
+                REQUIRE(ha_rag_pool_slot(ctx, lru[i], HA_RAG_TIER_HBM, &p, &nb) == HA_RAG_OK);
+                REQUIRE(p == info.hbm_ptr && nb == info.bytes && nb <= slot[info.prec]);
+            }
+        }
+        REQUIRE(ha_rag_destroy(ctx) == HA_RAG_OK);
+    }
+    std::printf("fuzz_host ok: %d rounds\n", rounds);
+    return 0;
+}

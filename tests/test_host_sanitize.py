@@ -1,0 +1,30 @@
+"""The host runtime under AddressSanitizer + UBSan (host code only): a C++ driver
+replays random pool / hotness / load sequences on dry_run contexts."""
+import os
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"),
+                    reason="needs hipcc")
+def test_host_runtime_fuzz_under_asan_ubsan(tmp_path):
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    exe = str(tmp_path / "fuzz_host")
+    csrc = os.path.join(ROOT, "paper_2510_20878_amd", "csrc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17",
+           "-Xarch_host", "-fsanitize=address,undefined", "-Xarch_host", "-fno-omit-frame-pointer",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Wno-unused-command-line-argument",
+           os.path.join(ROOT, "tests", "host_sanitize", "fuzz_host.cpp"),
+           os.path.join(csrc, "ha_rag_host.hip"), os.path.join(csrc, "ha_rag_kernels.hip"),
+           "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-3000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="halt_on_error=1")
+    r = subprocess.run([exe, "150"], capture_output=True, text=True, env=env, timeout=300)
+    assert r.returncode == 0, (r.stdout + r.stderr)[-4000:]
+    assert "fuzz_host ok" in r.stdout
