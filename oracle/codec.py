@@ -2,7 +2,8 @@
 
 Every array is a numpy array on the host.  BF16 and binary16 values travel as
 uint16 words.  Shapes follow the packed-chunk layout described at the top of
-ha_rag_oracle.c.  Precision tags: bits 16 (BF16 words kept verbatim), 8, 4.
+ha_rag_oracle.c.  Precision tags: bits 16 (BF16 words kept verbatim), 8, 4 (integer codes), 43 and 52
+(FP8 E4M3 / E5M2).
 """
 import ctypes as C
 import os
@@ -32,6 +33,10 @@ def lib():
         L.orc_fp16_round_down.argtypes = [C.c_float, C.POINTER(C.c_int)]
         L.orc_fp16_round_up.restype = C.c_uint16
         L.orc_fp16_round_up.argtypes = [C.c_float, C.POINTER(C.c_int)]
+        L.orc_fp8_to_f64.restype = C.c_double
+        L.orc_fp8_to_f64.argtypes = [C.c_uint8, C.c_int]
+        L.orc_f64_to_fp8.restype = C.c_uint8
+        L.orc_f64_to_fp8.argtypes = [C.c_double, C.c_int]
         L.orc_quantize_group.restype = C.c_int
         L.orc_quantize_group.argtypes = [f32p, C.c_int, C.c_int, u16p, u16p, u8p]
         L.orc_dequant_f32.restype = C.c_float
@@ -103,6 +108,15 @@ def dequant_bf16(code, scale_h, zero_h):
     return lib().orc_dequant_bf16(int(code), int(scale_h), int(zero_h))
 
 
+def fp8_to_f64(code, kind):
+    """kind: 43 = E4M3, 52 = E5M2."""
+    return lib().orc_fp8_to_f64(int(code), kind)
+
+
+def f64_to_fp8(x, kind):
+    return lib().orc_f64_to_fp8(float(x), kind)
+
+
 # ---- one group ---------------------------------------------------------------
 def quantize_group(x, bits):
     """x: float32 values of one group.  Returns (scale_h, zero_h, codes, saturated)."""
@@ -171,7 +185,7 @@ def unpack_chunk(packed, shape, T, bits, g=128):
     n = L * 2 * H * T * D
     codes = np.zeros(n, np.uint8)
     codes16 = np.zeros(n if bits == 16 else 1, np.uint16)
-    ng = n // g if bits != 16 else 1
+    ng = n // g if bits in (8, 4) else 1
     sh = np.zeros(max(ng, 1), np.uint16)
     zh = np.zeros(max(ng, 1), np.uint16)
     r = lib().orc_unpack_chunk(_p(packed, C.c_uint8), L, H, D, T, bits, g, _p(codes, C.c_uint8),
@@ -180,6 +194,8 @@ def unpack_chunk(packed, shape, T, bits, g=128):
         raise ValueError("bad shape")
     if bits == 16:
         return codes16.reshape(L, 2, H, T, D), None, None
+    if bits in (43, 52):
+        return codes.reshape(L, 2, H, T, D), None, None
     return (codes.reshape(L, 2, H, T, D), sh.reshape(L, 2, H, T, D // g),
             zh.reshape(L, 2, H, T, D // g))
 

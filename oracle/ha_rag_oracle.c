@@ -133,6 +133,74 @@ uint16_t orc_fp16_round_up(float x, int *sat)
 }
 
 /* ------------------------------------------------------------------ */
+/* 8-bit floating point (the paper's schemes S2 = E4M3 and S3 = E5M2,    */
+/* Sec. 2.2.2, Fig. 6, Sec. 3.2.1)                                       */
+/* ------------------------------------------------------------------ */
+/*
+ * The paper names the two FP8 variants of its reference [FP8 formats for deep
+ * learning] and quotes their ranges (about +-448 and +-57344); it does not say
+ * how values are rounded or what happens beyond the range.  Readings:
+ *   E4M3: 1 sign, 4 exponent (bias 7), 3 fraction bits, no infinities, the only
+ *         NaN is S.1111.111, largest finite 448; subnormals m/8 * 2^-6.
+ *   E5M2: 1 sign, 5 exponent (bias 15), 2 fraction bits, IEEE-like infinities
+ *         and NaNs, largest finite 57344; subnormals m/4 * 2^-14.
+ *   encode: round to nearest, ties to even, on the exact value; anything that
+ *         would land beyond the largest finite value saturates to it; the sign
+ *         of zero is kept.  Inputs are finite.
+ *   decode: exact (every FP8 value is a BF16 value).
+ * kind: 43 = E4M3, 52 = E5M2.
+ */
+static int fp8_params(int kind, int *ebits, int *mbits, int *bias, double *maxv)
+{
+    if (kind == 43) { *ebits = 4; *mbits = 3; *bias = 7; *maxv = 448.0; return 1; }
+    if (kind == 52) { *ebits = 5; *mbits = 2; *bias = 15; *maxv = 57344.0; return 1; }
+    return 0;
+}
+
+/* FP8 code -> value (NaN codes give NAN, E5M2 infinities give INFINITY). */
+double orc_fp8_to_f64(uint8_t c, int kind)
+{
+    int eb, mb, bias;
+    double maxv;
+    if (!fp8_params(kind, &eb, &mb, &bias, &maxv)) return NAN;
+    int sign = c >> 7;
+    int e = (c >> mb) & ((1 << eb) - 1);
+    int m = c & ((1 << mb) - 1);
+    double v;
+    if (kind == 43 && e == 15 && m == 7) v = NAN;
+    else if (kind == 52 && e == 31) v = m ? NAN : INFINITY;
+    else if (e == 0) v = ldexp((double)m, 1 - bias - mb);
+    else v = ldexp((double)((1 << mb) + m), e - bias - mb);
+    return sign ? -v : v;
+}
+
+/* finite value -> FP8 code: nearest, ties to even, saturating. */
+uint8_t orc_f64_to_fp8(double x, int kind)
+{
+    int eb, mb, bias;
+    double maxv;
+    if (!fp8_params(kind, &eb, &mb, &bias, &maxv)) return 0;
+    uint8_t sign = signbit(x) ? 0x80u : 0;
+    double a = fabs(x);
+    if (a == 0.0) return sign;
+    int ex;
+    (void)frexp(a, &ex);
+    int E = ex - 1;                       /* a in [2^E, 2^(E+1)) */
+    if (E < 1 - bias) E = 1 - bias;       /* subnormal spacing below the smallest normal */
+    double q = ldexp(1.0, E - mb);        /* spacing of the FP8 grid around a */
+    double n = nearbyint(a / q);          /* exact quotient; default mode = ties to even */
+    double v = n * q;
+    if (v > maxv) v = maxv;
+    /* encode the grid value v */
+    if (v == 0.0) return sign;
+    (void)frexp(v, &ex);
+    E = ex - 1;
+    if (E < 1 - bias) return (uint8_t)(sign | (uint8_t)ldexp(v, bias - 1 + mb));
+    int m = (int)ldexp(v, mb - E) - (1 << mb);
+    return (uint8_t)(sign | ((E + bias) << mb) | m);
+}
+
+/* ------------------------------------------------------------------ */
 /* one group                                                           */
 /* ------------------------------------------------------------------ */
 
@@ -212,11 +280,17 @@ uint16_t orc_dequant_bf16(unsigned code, uint16_t scale_h, uint16_t zero_h)
  */
 #define ORC_BLOCK 2048
 
+/* `bits` names the storage format: 16 (BF16 verbatim), 8 / 4 (integer codes with
+ * per-group scale and zero), 43 / 52 (FP8 E4M3 / E5M2, one byte per element, no
+ * meta; the payload is laid out like the 8-bit integer payload). */
+static int is_fp8(int bits) { return bits == 43 || bits == 52; }
+static int storage_bits(int bits) { return is_fp8(bits) ? 8 : bits; }
+
 static int valid_shape(int D, int bits, int g)
 {
-    if (bits != 16 && bits != 8 && bits != 4) return 0;
+    if (bits != 16 && bits != 8 && bits != 4 && !is_fp8(bits)) return 0;
     if (D <= 0 || D % 8) return 0;
-    if (bits == 16) return 1;
+    if (bits == 16 || is_fp8(bits)) return 1;
     if (g != 32 && g != 64 && g != 128 && g != 256 && g != 512) return 0;
     return D % g == 0;
 }
@@ -228,12 +302,12 @@ size_t orc_tile_blocks(int T, int D)
 
 size_t orc_tile_payload_bytes(int T, int D, int bits)
 {
-    return orc_tile_blocks(T, D) * 256u * (size_t)bits;
+    return orc_tile_blocks(T, D) * 256u * (size_t)storage_bits(bits);
 }
 
 size_t orc_tile_meta_bytes(int T, int D, int bits, int g)
 {
-    if (bits == 16) return 0;
+    if (bits == 16 || is_fp8(bits)) return 0;
     return orc_tile_blocks(T, D) * (size_t)(ORC_BLOCK / g) * 4u;
 }
 
@@ -315,6 +389,12 @@ long orc_quantize_pack_chunk(const uint16_t *src, int L, int H, int D, int T,
             }
             continue;
         }
+        if (is_fp8(bits)) {
+            for (size_t e = 0; e < n_e; ++e)
+                payload[octet_offset(e, 8) + e % 8] =
+                    orc_f64_to_fp8((double)orc_bf16_to_f32(x[e]), bits);
+            continue;
+        }
         float xs[512];
         uint8_t codes[512];
         for (size_t e0 = 0; e0 < n_e; e0 += (size_t)g) {
@@ -355,6 +435,9 @@ int orc_dequant_scatter_chunk(const uint8_t *packed, int L, int H, int D, int T,
             if (bits == 16) {
                 const uint8_t *o = payload + octet_offset(e, 16) + 2 * (e % 8);
                 y[e] = (uint16_t)(o[0] | (o[1] << 8));
+            } else if (is_fp8(bits)) {
+                uint8_t c = payload[octet_offset(e, 8) + e % 8];
+                y[e] = orc_f32_to_bf16_rne((float)orc_fp8_to_f64(c, bits)); /* exact */
             } else {
                 const uint8_t *m = meta + meta_offset(e, g);
                 uint16_t sh = (uint16_t)(m[0] | (m[1] << 8));
@@ -386,6 +469,8 @@ int orc_unpack_chunk(const uint8_t *packed, int L, int H, int D, int T, int bits
             if (bits == 16) {
                 const uint8_t *o = payload + octet_offset(e, 16) + 2 * (e % 8);
                 codes16[tile * n_e + e] = (uint16_t)(o[0] | (o[1] << 8));
+            } else if (is_fp8(bits)) {
+                codes[tile * n_e + e] = payload[octet_offset(e, 8) + e % 8];
             } else {
                 codes[tile * n_e + e] = (uint8_t)get_code(payload, e, bits);
                 if (e % (size_t)g == 0) {
