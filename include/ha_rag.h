@@ -28,7 +28,11 @@
  *    are unsigned codes with one fp16 scale and one fp16 zero per group of
  *    `group` consecutive head_dim elements (value = code * scale + zero).  The
  *    paper fixes only the code range of its integer scheme (Sec. 2.2.2); scale,
- *    zero, group and byte layout are this library's format.
+ *    zero, group and byte layout are this library's format.  FP8_E4M3 / FP8_E5M2
+ *    store one 8-bit float per element (1-4-3, bias 7, no infinities, largest
+ *    finite 448; 1-5-2, bias 15, largest finite 57344; Sec. 2.2.2, Fig. 6), encoded
+ *    round-to-nearest-even and saturating at the largest finite value, decoded
+ *    exactly; no scale/zero, payload laid out like the INT8 payload.
  *  - Packed byte layout of a chunk: tile records (l*2+kv)*H+h back to back; a tile
  *    is cut into blocks of 2048 elements (last one zero padded); payload blocks
  *    (256*bits bytes each) first, then meta blocks (2048/group entries of
@@ -60,7 +64,9 @@ extern "C" {
 #define HA_RAG_PREC_16 0
 #define HA_RAG_PREC_INT8 1
 #define HA_RAG_PREC_INT4 2
-#define HA_RAG_N_PREC 3
+#define HA_RAG_PREC_FP8_E4M3 3 /* the paper's scheme S2 (Sec. 2.2.2, Sec. 3.2.1) */
+#define HA_RAG_PREC_FP8_E5M2 4 /* the paper's scheme S3                           */
+#define HA_RAG_N_PREC 5
 
 #define HA_RAG_TIER_HBM 0    /* queueGPU of Algorithm 2 */
 #define HA_RAG_TIER_PINNED 1 /* queuePIN of Algorithm 2 */
@@ -182,6 +188,8 @@ int ha_rag_set_launch_params(ha_rag_ctx *ctx, const ha_rag_launch_params *lp);
  *      groups whose zero or scale left the fp16 range (then stored as +-65504).
  * Per group: zero = min rounded toward -inf to fp16, scale = (max - zero)/(2^b-1)
  * in fp32 rounded toward +inf to fp16, code = clamp(rint((x - zero)/scale)) in fp32.
+ * FP8 tags: each element rounded to the nearest FP8 value (ties to even),
+ * saturating; `group` is ignored and `saturated` is not touched.
  * EFORMAT on prec/group/shape; EINVAL on null or misaligned pointers. */
 int ha_rag_quantize_chunk(ha_rag_ctx *ctx, const void *src, uint32_t n_tokens, uint32_t prec,
                           uint32_t group, void *dst, uint32_t *saturated, void *stream);

@@ -11,10 +11,10 @@ import os
 from . import build as _build
 
 OK, EINVAL, ENOENT, ENOSPC, EFORMAT, EHIP = 0, -1, -2, -3, -4, -5
-PREC_16, PREC_INT8, PREC_INT4 = 0, 1, 2
+PREC_16, PREC_INT8, PREC_INT4, PREC_FP8_E4M3, PREC_FP8_E5M2 = 0, 1, 2, 3, 4
 TIER_HBM, TIER_PINNED = 0, 1
 NO_CHUNK = 2**64 - 1
-BITS = {PREC_16: 16, PREC_INT8: 8, PREC_INT4: 4}
+BITS = {PREC_16: 16, PREC_INT8: 8, PREC_INT4: 4, PREC_FP8_E4M3: 8, PREC_FP8_E5M2: 8}  # storage bits
 PREC_OF_BITS = {16: PREC_16, 8: PREC_INT8, 4: PREC_INT4}
 
 # every function include/ha_rag.h declares
@@ -222,7 +222,7 @@ class Context:
             pass
 
     def group_of(self, prec):
-        return {PREC_16: 0, PREC_INT8: self.cfg.group_int8, PREC_INT4: self.cfg.group_int4}[prec]
+        return {PREC_INT8: self.cfg.group_int8, PREC_INT4: self.cfg.group_int4}.get(prec, 0)
 
     def chunk_bytes(self, prec, n_tokens, group=None):
         g = self.group_of(prec) if group is None else group

@@ -30,10 +30,12 @@ bool valid_group(uint32_t g)
     return g == 32 || g == 64 || g == 128 || g == 256 || g == 512;
 }
 
-uint32_t bits_of(uint32_t prec)
+uint32_t bits_of(uint32_t prec)  // storage bits per element
 {
-    return prec == HA_RAG_PREC_16 ? 16u : prec == HA_RAG_PREC_INT8 ? 8u : 4u;
+    return prec == HA_RAG_PREC_16 ? 16u : prec == HA_RAG_PREC_INT4 ? 4u : 8u;
 }
+
+bool has_meta(uint32_t prec) { return prec == HA_RAG_PREC_INT8 || prec == HA_RAG_PREC_INT4; }
 
 uint32_t log2u(uint32_t v)
 {
@@ -46,13 +48,13 @@ int chunk_bytes_impl(uint32_t L, uint32_t H, uint32_t D, uint32_t prec, uint32_t
                      uint32_t T, size_t *payload, size_t *meta, size_t *total)
 {
     if (prec >= HA_RAG_N_PREC || L == 0 || H == 0 || D == 0 || (D % 8u)) return HA_RAG_EFORMAT;
-    if (prec != HA_RAG_PREC_16 && (!valid_group(group) || (D % group))) return HA_RAG_EFORMAT;
+    if (has_meta(prec) && (!valid_group(group) || (D % group))) return HA_RAG_EFORMAT;
     const uint64_t n_e = (uint64_t)T * D;
     if (n_e > 0x7FFFFFFFull) return HA_RAG_EINVAL;
     const uint64_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
     const uint64_t tiles = 2ull * L * H;
     const uint64_t pay = tiles * nblk * 256ull * bits_of(prec);
-    const uint64_t met = prec == HA_RAG_PREC_16 ? 0 : tiles * nblk * (kBlockElems / group) * 4ull;
+    const uint64_t met = has_meta(prec) ? tiles * nblk * (kBlockElems / group) * 4ull : 0;
     if (payload) *payload = (size_t)pay;
     if (meta) *meta = (size_t)met;
     if (total) *total = (size_t)(pay + met);
@@ -299,7 +301,7 @@ K1Chunk make_desc(const ha_rag_ctx *c, const Chunk &ch, const uint8_t *src, cons
     d.out_tile_stride = rq.cap * D * 2ull;
     d.n_tokens = ch.n_tokens;
     const uint32_t g = c->group_of(ch.prec);
-    d.fmt = bits_of(ch.prec) | ((g ? log2u(g) : 0u) << 8);
+    d.fmt = ch.prec | ((g ? log2u(g) : 0u) << 8);
     return d;
 }
 
@@ -650,8 +652,8 @@ int ha_rag_quantize_chunk(ha_rag_ctx *c, const void *src, uint32_t n_tokens, uin
     if (rc) return rc;
     if (c->dry()) return HA_RAG_OK;
     std::lock_guard<std::mutex> g(c->mu);
-    HIPCHK(c, launch_k2(src, dst, c->n_tiles, c->cfg.head_dim, n_tokens, bits_of(prec),
-                        prec == HA_RAG_PREC_16 ? 32u : group, saturated, (hipStream_t)stream));
+    HIPCHK(c, launch_k2(src, dst, c->n_tiles, c->cfg.head_dim, n_tokens, prec,
+                        has_meta(prec) ? group : 32u, saturated, (hipStream_t)stream));
     return HA_RAG_OK;
 }
 
@@ -684,7 +686,7 @@ int ha_rag_load_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, uint32_
         d.out = static_cast<uint8_t *>(out) + off * D * 2ull;
         d.out_tile_stride = cap_tokens * D * 2ull;
         d.n_tokens = pc.n_tokens;
-        d.fmt = bits_of(pc.prec) | ((pc.prec == HA_RAG_PREC_16 ? 0u : log2u(pc.group)) << 8);
+        d.fmt = pc.prec | ((has_meta(pc.prec) ? log2u(pc.group) : 0u) << 8);
         int rc = push(c, batch, d, (hipStream_t)stream, nullptr);
         if (rc) return rc;
         off += pc.n_tokens;

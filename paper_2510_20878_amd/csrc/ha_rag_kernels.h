@@ -7,6 +7,9 @@
 namespace ha_rag {
 
 constexpr uint32_t kBlockElems = 2048;   // elements per layout block
+
+// storage formats (numbered like the HA_RAG_PREC_* tags of the C ABI)
+enum Prec : uint32_t { kP16 = 0, kInt8 = 1, kInt4 = 2, kE4M3 = 3, kE5M2 = 4 };
 constexpr uint32_t kMaxLaunchChunks = 64; // chunk descriptors per kernel launch
 
 // One chunk of a gather-dequantize-scatter launch.  Travels in the kernel
@@ -16,12 +19,12 @@ struct K1Chunk {
     uint8_t *out;              // cache address of tile 0, token row tok_off, dim 0
     uint64_t out_tile_stride;  // bytes between consecutive tiles of the cache
     uint32_t n_tokens;
-    uint32_t fmt;              // bits (16, 8, 4) | log2(group) << 8
+    uint32_t fmt;              // Prec | log2(group) << 8
 };
 
 // The unit of work of one wave is an *item*: `planes` of the four 1024-byte output
 // planes of one block (int4: always all four, fed by one 16-byte load per lane;
-// int8: two or four; 16-bit: one, two or four).
+// int8 and FP8: two or four; 16-bit: one, two or four).
 struct K1Params {
     uint32_t n_tiles;      // 2 * L * H
     uint32_t head_dim;
@@ -45,7 +48,7 @@ hipError_t launch_k1(K1Params &p, const K1Launch &cfg, hipStream_t stream);
 
 // Quantize + pack one chunk.  src BF16 [n_tiles][n_tokens][D]; dst packed.
 hipError_t launch_k2(const void *src, void *dst, uint32_t n_tiles, uint32_t head_dim,
-                     uint32_t n_tokens, uint32_t bits, uint32_t group, uint32_t *saturated,
+                     uint32_t n_tokens, uint32_t prec, uint32_t group, uint32_t *saturated,
                      hipStream_t stream);
 
 }  // namespace ha_rag

@@ -73,6 +73,31 @@ __device__ __forceinline__ u32x4 dequant_octet8(uint32_t c0, uint32_t c1, uint32
     return r;
 }
 
+// 8 FP8 codes (two dwords) of one plane -> 8 BF16.  The hardware conversion to fp32 is
+// exact and every FP8 value is a BF16 value, so the BF16 rounding changes nothing.
+template <bool E5M2>
+__device__ __forceinline__ u32x4 decode_octet_fp8(uint32_t c0, uint32_t c1)
+{
+    f32x2 a, b, c, d;
+    if (E5M2) {
+        a = __builtin_amdgcn_cvt_pk_f32_bf8(c0, false);
+        b = __builtin_amdgcn_cvt_pk_f32_bf8(c0, true);
+        c = __builtin_amdgcn_cvt_pk_f32_bf8(c1, false);
+        d = __builtin_amdgcn_cvt_pk_f32_bf8(c1, true);
+    } else {
+        a = __builtin_amdgcn_cvt_pk_f32_fp8(c0, false);
+        b = __builtin_amdgcn_cvt_pk_f32_fp8(c0, true);
+        c = __builtin_amdgcn_cvt_pk_f32_fp8(c1, false);
+        d = __builtin_amdgcn_cvt_pk_f32_fp8(c1, true);
+    }
+    u32x4 r;
+    r.x = pack_bf16(a.x, a.y);
+    r.y = pack_bf16(b.x, b.y);
+    r.z = pack_bf16(c.x, c.y);
+    r.w = pack_bf16(d.x, d.y);
+    return r;
+}
+
 // ---------------------------------------------------------------------------
 // K1.  One item per wave (see K1Params); 1-D grid over all items of all chunks of
 // the launch, so ragged chunks and mixed tags leave no empty workgroups.  Small
@@ -114,8 +139,8 @@ __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params
     const uint32_t r = rt - p.item_start[lo];
     const uint32_t n_e = c.n_tokens * p.head_dim;
     const uint32_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
-    const uint32_t bits = c.fmt & 0xFFu, gsh = c.fmt >> 8;
-    const uint32_t planes = bits == 4 ? 4u : bits == 8 ? p.planes8 : p.planes16;
+    const uint32_t prec = c.fmt & 0xFFu, gsh = c.fmt >> 8;
+    const uint32_t planes = prec == kInt4 ? 4u : prec == kP16 ? p.planes16 : p.planes8;
     const uint32_t ipb_sh = planes == 4 ? 0u : planes == 2 ? 1u : 2u;  // log2(items per block)
     const uint32_t blk = r >> ipb_sh;
     const uint32_t j0 = (r - (blk << ipb_sh)) * planes;  // first plane of this item
@@ -125,7 +150,7 @@ __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params
     uint8_t *o = c.out + (uint64_t)tile * c.out_tile_stride + (uint64_t)blk * 4096u +
                  j0 * 1024u + lane_b;
 
-    if (bits == 4) {
+    if (prec == kInt4) {
         const uint32_t meta_blk = 8192u >> gsh;
         const uint8_t *pay = c.src + (uint64_t)tile * ((uint64_t)nblk * (1024u + meta_blk));
         const uint8_t *meta = pay + (uint64_t)nblk * 1024u;
@@ -135,7 +160,7 @@ __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params
         if (e + 512 < n_e) st16<NT_ST>(o + 1024, dequant_octet4(w.y, m.y));
         if (e + 1024 < n_e) st16<NT_ST>(o + 2048, dequant_octet4(w.z, m.z));
         if (e + 1536 < n_e) st16<NT_ST>(o + 3072, dequant_octet4(w.w, m.w));
-    } else if (bits == 8) {
+    } else if (prec == kInt8) {
         const uint32_t meta_blk = 8192u >> gsh;
         const uint8_t *pay = c.src + (uint64_t)tile * ((uint64_t)nblk * (2048u + meta_blk));
         const uint8_t *meta = pay + (uint64_t)nblk * 2048u;
@@ -153,6 +178,21 @@ __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params
             const uint2 m = *reinterpret_cast<const uint2 *>(mp + j0 * 4u);
             if (e < n_e) st16<NT_ST>(o, dequant_octet8(w.x, w.y, m.x));
             if (e + 512 < n_e) st16<NT_ST>(o + 1024, dequant_octet8(w.z, w.w, m.y));
+        }
+    } else if (prec == kE4M3 || prec == kE5M2) {
+        const uint8_t *b = c.src + (uint64_t)tile * ((uint64_t)nblk * 2048u) +
+                           (uint64_t)blk * 2048u + lane_b;
+        const bool e5 = prec == kE5M2;
+        if (planes == 4) {
+            const u32x4 w0 = ld16s<NT_LD>(b), w1 = ld16s<NT_LD>(b + 1024);
+            if (e < n_e) st16<NT_ST>(o, e5 ? decode_octet_fp8<true>(w0.x, w0.y) : decode_octet_fp8<false>(w0.x, w0.y));
+            if (e + 512 < n_e) st16<NT_ST>(o + 1024, e5 ? decode_octet_fp8<true>(w0.z, w0.w) : decode_octet_fp8<false>(w0.z, w0.w));
+            if (e + 1024 < n_e) st16<NT_ST>(o + 2048, e5 ? decode_octet_fp8<true>(w1.x, w1.y) : decode_octet_fp8<false>(w1.x, w1.y));
+            if (e + 1536 < n_e) st16<NT_ST>(o + 3072, e5 ? decode_octet_fp8<true>(w1.z, w1.w) : decode_octet_fp8<false>(w1.z, w1.w));
+        } else {
+            const u32x4 w = ld16s<NT_LD>(b + (j0 >> 1) * 1024u);
+            if (e < n_e) st16<NT_ST>(o, e5 ? decode_octet_fp8<true>(w.x, w.y) : decode_octet_fp8<false>(w.x, w.y));
+            if (e + 512 < n_e) st16<NT_ST>(o + 1024, e5 ? decode_octet_fp8<true>(w.z, w.w) : decode_octet_fp8<false>(w.z, w.w));
         }
     } else {
         const uint8_t *b = c.src + (uint64_t)tile * ((uint64_t)nblk * 4096u) +
@@ -191,8 +231,9 @@ hipError_t launch_k1(K1Params &p, const K1Launch &cfg, hipStream_t stream)
         const uint64_t n_e = (uint64_t)p.c[i].n_tokens * p.head_dim;
         if (n_e > 0x7FFFFFFFull) return hipErrorInvalidValue;  // element indices are 32-bit
         const uint64_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
-        const uint32_t bits = p.c[i].fmt & 0xFFu;
-        const uint32_t planes = bits == 4 ? 4u : bits == 8 ? cfg.planes8 : cfg.planes16;
+        const uint32_t prec = p.c[i].fmt & 0xFFu;
+        if (prec > kE5M2) return hipErrorInvalidValue;
+        const uint32_t planes = prec == kInt4 ? 4u : prec == kP16 ? cfg.planes16 : cfg.planes8;
         p.item_start[i] = (uint32_t)per_tile;
         per_tile += nblk * (4u / planes);
         if (per_tile > 0x7FFFFFFFull) return hipErrorInvalidValue;
@@ -407,6 +448,53 @@ __global__ void __launch_bounds__(64) k2_pack16(const uint8_t *__restrict__ src,
     st16<false>(dst + ((uint64_t)tile * planes_per_tile * 512u + e) * 2u, w);
 }
 
+// FP8 tags: every element is rounded on its own (nearest, ties to even, by the hardware
+// conversion) after clamping to the largest finite value; one wave per block.
+template <bool E5M2>
+__global__ void __launch_bounds__(256) k2_pack_fp8(const uint8_t *__restrict__ src,
+                                                   uint8_t *__restrict__ dst, uint32_t n_tokens,
+                                                   uint32_t head_dim, uint32_t wg_per_tile)
+{
+    const uint32_t n_e = n_tokens * head_dim;
+    const uint32_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    const uint32_t tile = blockIdx.x / wg_per_tile;
+    const uint32_t blk = (blockIdx.x - tile * wg_per_tile) * 4 + wave;
+    if (blk >= nblk) return;
+    const uint8_t *in = src + (uint64_t)tile * n_e * 2u + (uint64_t)blk * 4096u + lane * 16u;
+    const uint32_t e = blk * kBlockElems + lane * 8;
+    const float vmax = E5M2 ? 57344.0f : 448.0f;
+    uint32_t code[4][2];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        u32x4 raw = u32x4{0, 0, 0, 0};
+        if (e + j * 512 < n_e) raw = ld16s<true>(in + j * 1024);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {  // four elements -> one dword of codes
+            float x[4];
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                x[2 * k] = __builtin_bit_cast(float, raw[2 * h + k] << 16);
+                x[2 * k + 1] = __builtin_bit_cast(float, raw[2 * h + k] & 0xFFFF0000u);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) x[k] = __builtin_amdgcn_fmed3f(x[k], -vmax, vmax);
+            int w = 0;
+            if (E5M2) {
+                w = __builtin_amdgcn_cvt_pk_bf8_f32(x[0], x[1], w, false);
+                w = __builtin_amdgcn_cvt_pk_bf8_f32(x[2], x[3], w, true);
+            } else {
+                w = __builtin_amdgcn_cvt_pk_fp8_f32(x[0], x[1], w, false);
+                w = __builtin_amdgcn_cvt_pk_fp8_f32(x[2], x[3], w, true);
+            }
+            code[j][h] = (uint32_t)w;
+        }
+    }
+    uint8_t *o = dst + (uint64_t)tile * nblk * 2048u + (uint64_t)blk * 2048u + lane * 16u;
+    st16<false>(o, u32x4{code[0][0], code[0][1], code[1][0], code[1][1]});
+    st16<false>(o + 1024, u32x4{code[2][0], code[2][1], code[3][0], code[3][1]});
+}
+
 template <int BITS>
 static void launch_k2_g(uint32_t gsh, dim3 grid, hipStream_t stream, const uint8_t *s, uint8_t *d,
                         uint32_t n_tokens, uint32_t head_dim, uint32_t wg_per_tile,
@@ -423,9 +511,10 @@ static void launch_k2_g(uint32_t gsh, dim3 grid, hipStream_t stream, const uint8
 }
 
 hipError_t launch_k2(const void *src, void *dst, uint32_t n_tiles, uint32_t head_dim,
-                     uint32_t n_tokens, uint32_t bits, uint32_t group, uint32_t *saturated,
+                     uint32_t n_tokens, uint32_t prec, uint32_t group, uint32_t *saturated,
                      hipStream_t stream)
 {
+    const uint32_t bits = prec == kP16 ? 16u : prec == kInt4 ? 4u : 8u;
     if (n_tokens == 0 || n_tiles == 0) return hipSuccess;
     const uint64_t n_e = (uint64_t)n_tokens * head_dim;
     if (n_e > 0x7FFFFFFFull) return hipErrorInvalidValue;
@@ -438,15 +527,20 @@ hipError_t launch_k2(const void *src, void *dst, uint32_t n_tiles, uint32_t head
     const uint8_t *s = static_cast<const uint8_t *>(src);
     uint8_t *d = static_cast<uint8_t *>(dst);
     dim3 grid((uint32_t)gx);
-    if (bits == 16) {
+    if (prec == kE4M3 || prec == kE5M2) {
+        if (prec == kE5M2)
+            hipLaunchKernelGGL(k2_pack_fp8<true>, grid, dim3(256), 0, stream, s, d, n_tokens, head_dim, wg_per_tile);
+        else
+            hipLaunchKernelGGL(k2_pack_fp8<false>, grid, dim3(256), 0, stream, s, d, n_tokens, head_dim, wg_per_tile);
+    } else if (bits == 16) {
         const uint64_t planes = (uint64_t)n_tiles * nblk * 4u;
         if (planes > 0x7FFFFFFFull) return hipErrorInvalidValue;
         hipLaunchKernelGGL(k2_pack16, dim3((uint32_t)planes), dim3(64), 0, stream, s, d, n_tokens,
                            head_dim, nblk * 4u);
     } else {
         if (gsh < 5 || gsh > 9 || (1u << gsh) != group) return hipErrorInvalidValue;
-        if (bits == 8) launch_k2_g<8>(gsh, grid, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated);
-        else if (bits == 4) launch_k2_g<4>(gsh, grid, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated);
+        if (prec == kInt8) launch_k2_g<8>(gsh, grid, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated);
+        else if (prec == kInt4) launch_k2_g<4>(gsh, grid, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated);
         else return hipErrorInvalidValue;
     }
     return hipGetLastError();

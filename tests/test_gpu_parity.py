@@ -12,6 +12,8 @@ from paper_2510_20878_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 CANARY = 0x7FC1          # a BF16 NaN pattern no kernel output can contain
+# the oracle's name for each storage format
+ORC = {B.PREC_16: 16, B.PREC_INT8: 8, B.PREC_INT4: 4, B.PREC_FP8_E4M3: 43, B.PREC_FP8_E5M2: 52}
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -228,6 +230,74 @@ def test_empty_and_error_calls_touch_nothing():
     assert e.value.code == B.EFORMAT
     torch.cuda.synchronize()
     assert np.all(host_u16(out) == CANARY)
+    ctx.destroy()
+
+
+# ---- FP8 tags (the paper's schemes S2 and S3) ------------------------------------------
+@pytest.mark.parametrize("prec", [B.PREC_FP8_E4M3, B.PREC_FP8_E5M2])
+def test_fp8_encode_every_finite_bf16_value(prec):
+    words = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    f = wl.bf16_words_to_f32(words)
+    words = np.where(np.isfinite(f), words, 0).astype(np.uint16)       # inputs are finite by contract
+    src = words.reshape(1, 2, 1, 256, 128)
+    ctx = B.Context(1, 1, 128, 256)
+    ref, _ = codec.quantize_pack_chunk(src, ORC[prec])
+    got, _ = gpu_quantize(ctx, src, prec, 0)
+    bad = np.flatnonzero(got != ref)
+    assert bad.size == 0, f"{bad.size} codes differ, first at {bad[:8]}"
+    ctx.destroy()
+
+
+@pytest.mark.parametrize("prec", [B.PREC_FP8_E4M3, B.PREC_FP8_E5M2])
+def test_fp8_decode_every_code(prec):
+    kind = ORC[prec]
+    codes = np.arange(256, dtype=np.uint8)
+    finite = np.array([np.isfinite(codec.fp8_to_f64(int(c), kind)) for c in codes])
+    codes = np.where(finite, codes, 0).astype(np.uint8)                 # NaN / inf codes are never written
+    L, H, D, T = 1, 1, 128, 32                                           # 2 blocks per tile
+    per_tile = np.tile(codes, T * D // 256)
+    # build the packed chunk through the oracle's layout: one byte per element
+    packed = np.zeros(codec.chunk_bytes(L, H, D, T, kind), np.uint8)
+    for tile in range(2):
+        for e in range(T * D):
+            packed[tile * 4096 + codec.octet_offset(e, 8) + e % 8] = per_tile[(e + 37 * tile) % per_tile.size]
+    ref = np.zeros((L, 2, H, T, D), np.uint16)
+    codec.dequant_scatter_chunk(packed, (L, H, D), T, kind, 128, ref, 0)
+    ctx = B.Context(L, H, D, T)
+    out = torch.zeros((L, 2, H, T, D), dtype=torch.int16, device="cuda")
+    ctx.load_packed([(dev_u8(packed), T, prec, 0)], out, T)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u16(out), ref)
+    ctx.destroy()
+
+
+def test_all_five_tags_in_one_request_through_the_pool():
+    L, H, D, T, g = 2, 2, 128, 72, 64
+    precs = [B.PREC_FP8_E5M2, B.PREC_INT4, B.PREC_16, B.PREC_FP8_E4M3, B.PREC_INT8, B.PREC_FP8_E4M3]
+    tokens = [72, 40, 9, 72, 33, 1]
+    ctx = _pool_ctx(L, H, D, T, g, hbm_slots=2, pin_slots=3, stg_slots=2, tau_gpu_ppm=400_000,
+                    precs=sorted(set(precs)))
+    srcs = [wl.kv_chunk(L, H, D, t, 900 + i, outlier_channels=1) for i, t in enumerate(tokens)]
+    packed = []
+    for i, (s_, p, t) in enumerate(zip(srcs, precs, tokens)):
+        ref, _ = codec.quantize_pack_chunk(s_, ORC[p], g)
+        got, _ = gpu_quantize(B.Context(L, H, D, t, group_int8=g, group_int4=g), s_, p, g)
+        assert np.array_equal(got, ref), f"chunk {i}"
+        packed.append(ref)
+        ctx.pool_insert(i, p, t, dev_u8(got), B.TIER_PINNED, packed_is_device=True)
+    torch.cuda.synchronize()
+    ctx.set_counts(list(range(6)), [9, 8, 7, 6, 5, 4])
+    ctx.rerank()                                             # GPU_LIST = ids 0, 1
+    for order in ([5, 0, 3, 1, 4, 2], [0, 1, 2, 3, 4, 5, 0]):
+        total = sum(tokens[c] for c in order)
+        out = torch.full((L, 2, H, total + 3, D), CANARY, dtype=torch.int16, device="cuda")
+        st, _ = ctx.load_chunks(order, out, total + 3, tok_base=1, tags=[precs[c] for c in order])
+        torch.cuda.synchronize()
+        ref = np.full((L, 2, H, total + 3, D), CANARY, np.uint16)
+        codec.load_chunks(packed, (L, H, D), tokens, [ORC[p] for p in precs], [g] * 6, order,
+                          cap_tokens=total + 3, tok_base=1, out=ref)
+        assert np.array_equal(host_u16(out), ref), order
+    assert st["n_hbm_hits"] == 3                             # ids 0, 1 promoted by the first request
     ctx.destroy()
 
 

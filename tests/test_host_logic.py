@@ -8,6 +8,8 @@ from oracle import codec, placement as pl
 from paper_2510_20878_amd import binding as B
 from paper_2510_20878_amd import workloads as wl
 
+# the oracle's name for each storage format
+ORC = {B.PREC_16: 16, B.PREC_INT8: 8, B.PREC_INT4: 4, B.PREC_FP8_E4M3: 43, B.PREC_FP8_E5M2: 52}
 FAKE_HBM = 0x7F0000000000     # never dereferenced in dry_run
 FAKE_PIN = 0x7E0000000000
 FAKE_STG = 0x7D0000000000
@@ -17,7 +19,7 @@ FAKE_STG = 0x7D0000000000
 @pytest.mark.parametrize("T", [1, 7, 100, 128, 512, 1024])
 def test_chunk_bytes_equals_oracle(shape, T):
     L, H, D = shape
-    for prec, bits in B.BITS.items():
+    for prec, bits in ORC.items():
         for g in (32, 64, 128):
             if D % g:
                 with pytest.raises(B.HaRagError) as e:
@@ -28,10 +30,11 @@ def test_chunk_bytes_equals_oracle(shape, T):
             assert total == codec.chunk_bytes(L, H, D, T, bits, g)
             assert pay == L * 2 * H * codec.tile_payload_bytes(T, D, bits)
             assert pay + meta == total
+            assert (meta == 0) == (prec in (B.PREC_16, B.PREC_FP8_E4M3, B.PREC_FP8_E5M2))
 
 
 def test_chunk_bytes_rejects_bad_shapes():
-    for args in [(2, 2, 60, B.PREC_INT4, 64, 8), (2, 2, 64, 3, 64, 8), (2, 2, 64, B.PREC_INT8, 48, 8),
+    for args in [(2, 2, 60, B.PREC_INT4, 64, 8), (2, 2, 64, 7, 64, 8), (2, 2, 64, B.PREC_INT8, 48, 8),
                  (0, 2, 64, B.PREC_16, 0, 8)]:
         with pytest.raises(B.HaRagError) as e:
             B.ha_rag_chunk_bytes(*args)
