@@ -37,11 +37,22 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def per_token_bytes(L, H, D, bits, g):
-    """Algorithmic HBM bytes per KV token: packed bytes read + BF16 bytes written."""
+def per_token_bytes(L, H, D, tag, g):
+    """Algorithmic HBM bytes per KV token: packed bytes read + BF16 bytes written.
+    tag: 16, 8, 4 (integer codes with 4 bytes of scale/zero per group) or "e4m3" / "e5m2"."""
     elems = L * 2 * H * D
-    read = elems * 2 if bits == 16 else elems * bits // 8 + 4 * elems // g
+    if tag == 16:
+        read = elems * 2
+    elif tag in ("e4m3", "e5m2"):
+        read = elems
+    else:
+        read = elems * tag // 8 + 4 * elems // g
     return read, elems * 2
+
+
+def prec_of(B, tag):
+    return {16: B.PREC_16, 8: B.PREC_INT8, 4: B.PREC_INT4, "e4m3": B.PREC_FP8_E4M3,
+            "e5m2": B.PREC_FP8_E5M2}[tag]
 
 
 def build_hbm_pool(B, wl, torch, ctx, shape, T, g, counts, seed0):
@@ -77,7 +88,8 @@ def cpu_baseline(shape, T, g, mix, min_seconds, seed):
 
     L, H, D = shape
     packed, bits_list = [], []
-    for i, bits in enumerate(mix):
+    for i, tag in enumerate(mix):
+        bits = {"e4m3": 43, "e5m2": 52}.get(tag, tag)      # the oracle's format names
         src = wl.kv_chunk(L, H, D, T, seed + i)
         packed.append(codec.quantize_pack_chunk(src, bits, g)[0])
         bits_list.append(bits)
@@ -114,9 +126,13 @@ def run_hbm(args, B, wl, torch, name):
     if name == "hbm8b":
         shape, T, g = (32, 8, 128), 512, 128
         mix = [16] * 2 + [8] * 3 + [4] * 5
-        frac = {B.PREC_16: 0.2, B.PREC_INT8: 0.3, B.PREC_INT4: 0.5}
         desc = ("Llama-3-8B KV (32 layers, 8 KV heads, head_dim 128, bf16 source): top-10 chunks x "
                 "512 tokens per request from an HBM pool, 2x16-bit + 3xint8 + 5xint4, group 128")
+        if args.mix:
+            mix = [int(t) if t.isdigit() else t for t in args.mix.split(",")]
+            desc = ("Llama-3-8B KV shape, 512-token chunks from an HBM pool, tags per request "
+                    f"{args.mix}, group 128")
+        frac = {prec_of(B, t): mix.count(t) / len(mix) for t in set(mix)}
     else:  # llama70b
         shape, T, g = (80, 8, 128), 1024, 128
         mix = [8, 4] * 8
@@ -136,7 +152,7 @@ def run_hbm(args, B, wl, torch, name):
     import numpy as np
     rng = np.random.Generator(np.random.PCG64(args.seed))
     n_req = len(mix)
-    per = {B.PREC_OF_BITS[b]: mix.count(b) for b in set(mix)}
+    per = {prec_of(B, b): mix.count(b) for b in set(mix)}
     cursor = {p: 0 for p in per}
 
     def next_request():
@@ -188,7 +204,8 @@ def run_hbm(args, B, wl, torch, name):
         "hbm_fraction_whole_path": value / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "kernel": "k1_gather_dequant_scatter", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": args.traffic_bytes or MEASURED_TRAFFIC.get(name), "kernel_ms": kernel_ms,
+                     "traffic": args.traffic_bytes or (None if args.mix else MEASURED_TRAFFIC.get(name)),
+                     "kernel_ms": kernel_ms,
                      "algorithmic_bytes_per_launch": step_bytes},
     }
     return res, (shape, T, g, mix)
@@ -349,6 +366,7 @@ def main():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="hbm8b", choices=["hbm8b", "llama70b", "cold8b", "zipf"])
+    ap.add_argument("--mix", default="", help="hbm8b: tags of one request, e.g. 8,e4m3,e5m2,4")
     ap.add_argument("--pool-chunks", type=int, default=0, help="chunks in the HBM pool (0 = default)")
     ap.add_argument("--out-buffers", type=int, default=4)
     ap.add_argument("--seed", type=int, default=0)

@@ -3,7 +3,7 @@
 Every array is a numpy array on the host.  BF16 and binary16 values travel as
 uint16 words.  Shapes follow the packed-chunk layout described at the top of
 ha_rag_oracle.c.  Precision tags: bits 16 (BF16 words kept verbatim), 8, 4 (integer codes), 43 and 52
-(FP8 E4M3 / E5M2).
+(FP8 E4M3 / E5M2), 143 (GSE-8 with the 1+4+3 split).
 """
 import ctypes as C
 import os
@@ -37,6 +37,14 @@ def lib():
         L.orc_fp8_to_f64.argtypes = [C.c_uint8, C.c_int]
         L.orc_f64_to_fp8.restype = C.c_uint8
         L.orc_f64_to_fp8.argtypes = [C.c_double, C.c_int]
+        L.orc_gse_shared_exponent.restype = C.c_int
+        L.orc_gse_shared_exponent.argtypes = [C.c_int, C.c_int, C.c_int]
+        L.orc_gse_range.restype = C.c_int
+        L.orc_gse_range.argtypes = [u16p, C.c_size_t, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+        L.orc_gse8_encode.restype = C.c_uint8
+        L.orc_gse8_encode.argtypes = [C.c_uint16, C.c_int, C.c_int]
+        L.orc_gse8_decode.restype = C.c_double
+        L.orc_gse8_decode.argtypes = [C.c_uint8, C.c_int, C.c_int]
         L.orc_quantize_group.restype = C.c_int
         L.orc_quantize_group.argtypes = [f32p, C.c_int, C.c_int, u16p, u16p, u8p]
         L.orc_dequant_f32.restype = C.c_float
@@ -117,6 +125,27 @@ def f64_to_fp8(x, kind):
     return lib().orc_f64_to_fp8(float(x), kind)
 
 
+def gse_shared_exponents(e_lo, e_hi, n=16):
+    """The shared-exponent array of the range (e_lo - 1, e_hi]."""
+    return [lib().orc_gse_shared_exponent(k, e_lo, e_hi) for k in range(n)]
+
+
+def gse_range(words):
+    """(e_lo, e_hi, any_nonzero) of BF16 words."""
+    w = _c(words, np.uint16).ravel()
+    lo, hi = C.c_int(0), C.c_int(0)
+    r = lib().orc_gse_range(_p(w, C.c_uint16), w.size, C.byref(lo), C.byref(hi))
+    return lo.value, hi.value, bool(r)
+
+
+def gse8_encode(word, e_lo, e_hi):
+    return lib().orc_gse8_encode(int(word), e_lo, e_hi)
+
+
+def gse8_decode(code, e_lo, e_hi):
+    return lib().orc_gse8_decode(int(code), e_lo, e_hi)
+
+
 # ---- one group ---------------------------------------------------------------
 def quantize_group(x, bits):
     """x: float32 values of one group.  Returns (scale_h, zero_h, codes, saturated)."""
@@ -194,7 +223,7 @@ def unpack_chunk(packed, shape, T, bits, g=128):
         raise ValueError("bad shape")
     if bits == 16:
         return codes16.reshape(L, 2, H, T, D), None, None
-    if bits in (43, 52):
+    if bits in (43, 52, 143):
         return codes.reshape(L, 2, H, T, D), None, None
     return (codes.reshape(L, 2, H, T, D), sh.reshape(L, 2, H, T, D // g),
             zh.reshape(L, 2, H, T, D // g))

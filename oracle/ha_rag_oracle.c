@@ -201,6 +201,90 @@ uint8_t orc_f64_to_fp8(double x, int kind)
 }
 
 /* ------------------------------------------------------------------ */
+/* GSE-8, the paper's scheme S4 (Sec. 2.2.2, Fig. 7; split 1+4+3 adopted */
+/* in Sec. 3.2.1)                                                        */
+/* ------------------------------------------------------------------ */
+/*
+ * One byte: sign, 4-bit index into an array of shared exponents, 3-bit fraction
+ * field.  The paper's three conversion steps for a BF16 value x with exponent E:
+ * pick the smallest shared exponent G >= E, let d = G - E, shift the fraction
+ * right by d + 1 and set bit d + 1 (counted from the most significant end), i.e.
+ * the field is the bit string 0^d 1 f1 f2 ... cut to 3 bits; the bits that fall
+ * off are discarded (truncation).  Decoding finds the first 1, which gives d and
+ * so E = G - d, and shifts the rest back.  Read as numbers, both directions are
+ *     field = floor(|x| * 2^(2 - G)),     value = +-field * 2^(G - 2),
+ * which is how they are written below.  A field of 0 is the value 0.
+ *
+ * Shared exponents (Sec. 2.2.2, last paragraph): the exponent range of the unit
+ * is cut, from its lower end, into steps of 3 and the right end of every step is
+ * a shared exponent, the last one clipped to the top of the range (the worked
+ * example: range (-10, 10) gives -7, -4, -1, 2, 5, 8, 10).  Readings taken here:
+ * the unit is one tile (one layer, K or V, one head of a chunk); the range is
+ * (e_lo - 1, e_hi] with e_lo, e_hi the smallest and largest unbiased exponent of
+ * the tile's nonzero values; 16 entries at step 3 reach 48 binades, so e_lo is
+ * raised to e_hi - 47 if needed; a value more than 2 binades below the first
+ * shared exponent shifts its leading one out of the field and becomes 0; the
+ * index stored with a zero field is 0.  The array is not stored: the tile record ends with a
+ * 16-byte block {int8 e_lo, int8 e_hi, 14 zero bytes} it is rebuilt from.
+ */
+#define ORC_GSE_STEP 3
+#define ORC_GSE_ENTRIES 16
+
+/* k-th shared exponent of the range (e_lo - 1, e_hi] */
+int orc_gse_shared_exponent(int k, int e_lo, int e_hi)
+{
+    int g = e_lo - 1 + ORC_GSE_STEP * (k + 1);
+    return g < e_hi ? g : e_hi;
+}
+
+/* unbiased exponent of a finite nonzero BF16 value (subnormals: -126) */
+static int bf16_exponent(uint16_t w)
+{
+    int e = (w >> 7) & 0xFF;
+    return e ? e - 127 : -126;
+}
+
+/* smallest / largest exponent over the nonzero values; returns 0 if all are zero.
+ * e_lo is already raised to e_hi - 47. */
+int orc_gse_range(const uint16_t *x, size_t n, int *e_lo, int *e_hi)
+{
+    int lo = 1000, hi = -1000;
+    for (size_t i = 0; i < n; ++i) {
+        if ((x[i] & 0x7FFF) == 0) continue;
+        int e = bf16_exponent(x[i]);
+        if (e < lo) lo = e;
+        if (e > hi) hi = e;
+    }
+    if (hi == -1000) { *e_lo = 0; *e_hi = 0; return 0; }
+    if (lo < hi - (ORC_GSE_STEP * ORC_GSE_ENTRIES - 1)) lo = hi - (ORC_GSE_STEP * ORC_GSE_ENTRIES - 1);
+    *e_lo = lo;
+    *e_hi = hi;
+    return 1;
+}
+
+uint8_t orc_gse8_encode(uint16_t w, int e_lo, int e_hi)
+{
+    uint8_t sign = (uint8_t)((w >> 15) << 7);
+    if ((w & 0x7FFF) == 0) return sign;
+    int E = bf16_exponent(w);
+    int k = 0;
+    while (orc_gse_shared_exponent(k, e_lo, e_hi) < E) ++k; /* smallest shared exponent >= E */
+    int G = orc_gse_shared_exponent(k, e_lo, e_hi);
+    double a = fabs((double)orc_bf16_to_f32(w));
+    int field = (int)floor(ldexp(a, 2 - G));      /* at most 7 because E <= G */
+    if (field == 0) return sign;                  /* E < G - 2: more than 2 places to shift, the
+                                                     leading one falls off the field: value 0 */
+    return (uint8_t)(sign | (k << 3) | field);
+}
+
+double orc_gse8_decode(uint8_t c, int e_lo, int e_hi)
+{
+    int field = c & 7, k = (c >> 3) & 15;
+    double v = ldexp((double)field, orc_gse_shared_exponent(k, e_lo, e_hi) - 2);
+    return (c & 0x80) ? -v : v;
+}
+
+/* ------------------------------------------------------------------ */
 /* one group                                                           */
 /* ------------------------------------------------------------------ */
 
@@ -284,13 +368,14 @@ uint16_t orc_dequant_bf16(unsigned code, uint16_t scale_h, uint16_t zero_h)
  * per-group scale and zero), 43 / 52 (FP8 E4M3 / E5M2, one byte per element, no
  * meta; the payload is laid out like the 8-bit integer payload). */
 static int is_fp8(int bits) { return bits == 43 || bits == 52; }
-static int storage_bits(int bits) { return is_fp8(bits) ? 8 : bits; }
+static int is_gse(int bits) { return bits == 143; }  /* GSE-8 with the 1+4+3 split */
+static int storage_bits(int bits) { return (is_fp8(bits) || is_gse(bits)) ? 8 : bits; }
 
 static int valid_shape(int D, int bits, int g)
 {
-    if (bits != 16 && bits != 8 && bits != 4 && !is_fp8(bits)) return 0;
+    if (bits != 16 && bits != 8 && bits != 4 && !is_fp8(bits) && !is_gse(bits)) return 0;
     if (D <= 0 || D % 8) return 0;
-    if (bits == 16 || is_fp8(bits)) return 1;
+    if (bits == 16 || is_fp8(bits) || is_gse(bits)) return 1;
     if (g != 32 && g != 64 && g != 128 && g != 256 && g != 512) return 0;
     return D % g == 0;
 }
@@ -308,6 +393,7 @@ size_t orc_tile_payload_bytes(int T, int D, int bits)
 size_t orc_tile_meta_bytes(int T, int D, int bits, int g)
 {
     if (bits == 16 || is_fp8(bits)) return 0;
+    if (is_gse(bits)) return T > 0 ? 16 : 0;
     return orc_tile_blocks(T, D) * (size_t)(ORC_BLOCK / g) * 4u;
 }
 
@@ -395,6 +481,15 @@ long orc_quantize_pack_chunk(const uint16_t *src, int L, int H, int D, int T,
                     orc_f64_to_fp8((double)orc_bf16_to_f32(x[e]), bits);
             continue;
         }
+        if (is_gse(bits)) {
+            int e_lo, e_hi;
+            (void)orc_gse_range(x, n_e, &e_lo, &e_hi);
+            for (size_t e = 0; e < n_e; ++e)
+                payload[octet_offset(e, 8) + e % 8] = orc_gse8_encode(x[e], e_lo, e_hi);
+            meta[0] = (uint8_t)(int8_t)e_lo;
+            meta[1] = (uint8_t)(int8_t)e_hi;
+            continue;
+        }
         float xs[512];
         uint8_t codes[512];
         for (size_t e0 = 0; e0 < n_e; e0 += (size_t)g) {
@@ -438,6 +533,10 @@ int orc_dequant_scatter_chunk(const uint8_t *packed, int L, int H, int D, int T,
             } else if (is_fp8(bits)) {
                 uint8_t c = payload[octet_offset(e, 8) + e % 8];
                 y[e] = orc_f32_to_bf16_rne((float)orc_fp8_to_f64(c, bits)); /* exact */
+            } else if (is_gse(bits)) {
+                uint8_t c = payload[octet_offset(e, 8) + e % 8];
+                double v = orc_gse8_decode(c, (int8_t)meta[0], (int8_t)meta[1]);
+                y[e] = orc_f32_to_bf16_rne((float)v);                        /* exact */
             } else {
                 const uint8_t *m = meta + meta_offset(e, g);
                 uint16_t sh = (uint16_t)(m[0] | (m[1] << 8));
@@ -469,7 +568,7 @@ int orc_unpack_chunk(const uint8_t *packed, int L, int H, int D, int T, int bits
             if (bits == 16) {
                 const uint8_t *o = payload + octet_offset(e, 16) + 2 * (e % 8);
                 codes16[tile * n_e + e] = (uint16_t)(o[0] | (o[1] << 8));
-            } else if (is_fp8(bits)) {
+            } else if (is_fp8(bits) || is_gse(bits)) {
                 codes[tile * n_e + e] = payload[octet_offset(e, 8) + e % 8];
             } else {
                 codes[tile * n_e + e] = (uint8_t)get_code(payload, e, bits);
