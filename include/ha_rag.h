@@ -32,7 +32,14 @@
  *    store one 8-bit float per element (1-4-3, bias 7, no infinities, largest
  *    finite 448; 1-5-2, bias 15, largest finite 57344; Sec. 2.2.2, Fig. 6), encoded
  *    round-to-nearest-even and saturating at the largest finite value, decoded
- *    exactly; no scale/zero, payload laid out like the INT8 payload.
+ *    exactly; no scale/zero, payload laid out like the INT8 payload.  GSE8 stores
+ *    sign, a 4-bit index k into the tile's shared exponents and a 3-bit field
+ *    (Sec. 2.2.2, Fig. 7): value = +-field * 2^(G_k - 2), G_k = min(e_lo + 2 + 3k,
+ *    e_hi), field = floor(|x| * 2^(2 - G_k)) for the smallest G_k >= exponent(x)
+ *    (truncating, as the paper's shift does); e_lo / e_hi are the smallest /
+ *    largest exponent of the tile's nonzero values (e_lo raised to e_hi - 47 if
+ *    the tile spans more than 48 binades).  Payload like INT8, and each tile
+ *    record ends with 16 bytes {int8 e_lo, int8 e_hi, 14 zero bytes}.
  *  - Packed byte layout of a chunk: tile records (l*2+kv)*H+h back to back; a tile
  *    is cut into blocks of 2048 elements (last one zero padded); payload blocks
  *    (256*bits bytes each) first, then meta blocks (2048/group entries of
@@ -66,7 +73,8 @@ extern "C" {
 #define HA_RAG_PREC_INT4 2
 #define HA_RAG_PREC_FP8_E4M3 3 /* the paper's scheme S2 (Sec. 2.2.2, Sec. 3.2.1) */
 #define HA_RAG_PREC_FP8_E5M2 4 /* the paper's scheme S3                           */
-#define HA_RAG_N_PREC 5
+#define HA_RAG_PREC_GSE8 5     /* the paper's scheme S4, GSE-8 with the 1+4+3 split */
+#define HA_RAG_N_PREC 6
 
 #define HA_RAG_TIER_HBM 0    /* queueGPU of Algorithm 2 */
 #define HA_RAG_TIER_PINNED 1 /* queuePIN of Algorithm 2 */
@@ -189,7 +197,8 @@ int ha_rag_set_launch_params(ha_rag_ctx *ctx, const ha_rag_launch_params *lp);
  * Per group: zero = min rounded toward -inf to fp16, scale = (max - zero)/(2^b-1)
  * in fp32 rounded toward +inf to fp16, code = clamp(rint((x - zero)/scale)) in fp32.
  * FP8 tags: each element rounded to the nearest FP8 value (ties to even),
- * saturating; `group` is ignored and `saturated` is not touched.
+ * saturating.  GSE8: per tile, exponent range then truncating encode.  For both
+ * `group` is ignored and `saturated` is not touched.
  * EFORMAT on prec/group/shape; EINVAL on null or misaligned pointers. */
 int ha_rag_quantize_chunk(ha_rag_ctx *ctx, const void *src, uint32_t n_tokens, uint32_t prec,
                           uint32_t group, void *dst, uint32_t *saturated, void *stream);

@@ -11,10 +11,11 @@ import os
 from . import build as _build
 
 OK, EINVAL, ENOENT, ENOSPC, EFORMAT, EHIP = 0, -1, -2, -3, -4, -5
-PREC_16, PREC_INT8, PREC_INT4, PREC_FP8_E4M3, PREC_FP8_E5M2 = 0, 1, 2, 3, 4
+PREC_16, PREC_INT8, PREC_INT4, PREC_FP8_E4M3, PREC_FP8_E5M2, PREC_GSE8 = 0, 1, 2, 3, 4, 5
 TIER_HBM, TIER_PINNED = 0, 1
 NO_CHUNK = 2**64 - 1
-BITS = {PREC_16: 16, PREC_INT8: 8, PREC_INT4: 4, PREC_FP8_E4M3: 8, PREC_FP8_E5M2: 8}  # storage bits
+BITS = {PREC_16: 16, PREC_INT8: 8, PREC_INT4: 4, PREC_FP8_E4M3: 8, PREC_FP8_E5M2: 8,
+        PREC_GSE8: 8}  # storage bits
 PREC_OF_BITS = {16: PREC_16, 8: PREC_INT8, 4: PREC_INT4}
 
 # every function include/ha_rag.h declares

@@ -54,7 +54,9 @@ int chunk_bytes_impl(uint32_t L, uint32_t H, uint32_t D, uint32_t prec, uint32_t
     const uint64_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
     const uint64_t tiles = 2ull * L * H;
     const uint64_t pay = tiles * nblk * 256ull * bits_of(prec);
-    const uint64_t met = has_meta(prec) ? tiles * nblk * (kBlockElems / group) * 4ull : 0;
+    const uint64_t met = has_meta(prec)               ? tiles * nblk * (kBlockElems / group) * 4ull
+                         : prec == HA_RAG_PREC_GSE8 ? (nblk ? tiles * 16ull : 0)
+                                                    : 0;
     if (payload) *payload = (size_t)pay;
     if (meta) *meta = (size_t)met;
     if (total) *total = (size_t)(pay + met);

@@ -9,7 +9,7 @@ namespace ha_rag {
 constexpr uint32_t kBlockElems = 2048;   // elements per layout block
 
 // storage formats (numbered like the HA_RAG_PREC_* tags of the C ABI)
-enum Prec : uint32_t { kP16 = 0, kInt8 = 1, kInt4 = 2, kE4M3 = 3, kE5M2 = 4 };
+enum Prec : uint32_t { kP16 = 0, kInt8 = 1, kInt4 = 2, kE4M3 = 3, kE5M2 = 4, kGSE8 = 5 };
 constexpr uint32_t kMaxLaunchChunks = 64; // chunk descriptors per kernel launch
 
 // One chunk of a gather-dequantize-scatter launch.  Travels in the kernel

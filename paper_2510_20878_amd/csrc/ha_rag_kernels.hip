@@ -98,6 +98,29 @@ __device__ __forceinline__ u32x4 decode_octet_fp8(uint32_t c0, uint32_t c1)
     return r;
 }
 
+// 8 GSE-8 codes (two dwords) of one plane -> 8 BF16.  base = e_lo + 2 - 2 and top = e_hi - 2
+// are the tile's exponent bounds already lowered by the 2 fraction places of the field:
+// value = +-field * 2^min(base + 3k, top), exact in BF16.
+__device__ __forceinline__ float decode_gse8(uint32_t w, int b, int base, int top)
+{
+    const uint32_t c = (w >> (8 * b)) & 0xFFu;
+    const float field = (float)(c & 7u);
+    int n = (int)((c >> 3) & 15u) * 3 + base;
+    n = n < top ? n : top;
+    const float v = __builtin_ldexpf(field, n);
+    return __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, v) | ((c & 0x80u) << 24));
+}
+
+__device__ __forceinline__ u32x4 decode_octet_gse8(uint32_t c0, uint32_t c1, int base, int top)
+{
+    u32x4 r;
+    r.x = pack_bf16(decode_gse8(c0, 0, base, top), decode_gse8(c0, 1, base, top));
+    r.y = pack_bf16(decode_gse8(c0, 2, base, top), decode_gse8(c0, 3, base, top));
+    r.z = pack_bf16(decode_gse8(c1, 0, base, top), decode_gse8(c1, 1, base, top));
+    r.w = pack_bf16(decode_gse8(c1, 2, base, top), decode_gse8(c1, 3, base, top));
+    return r;
+}
+
 // ---------------------------------------------------------------------------
 // K1.  One item per wave (see K1Params); 1-D grid over all items of all chunks of
 // the launch, so ragged chunks and mixed tags leave no empty workgroups.  Small
@@ -194,6 +217,23 @@ __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params
             if (e < n_e) st16<NT_ST>(o, e5 ? decode_octet_fp8<true>(w.x, w.y) : decode_octet_fp8<false>(w.x, w.y));
             if (e + 512 < n_e) st16<NT_ST>(o + 1024, e5 ? decode_octet_fp8<true>(w.z, w.w) : decode_octet_fp8<false>(w.z, w.w));
         }
+    } else if (prec == kGSE8) {
+        const uint8_t *rec = c.src + (uint64_t)tile * ((uint64_t)nblk * 2048u + 16u);
+        const uint8_t *b = rec + (uint64_t)blk * 2048u + lane_b;
+        const uint32_t range = *reinterpret_cast<const uint32_t *>(rec + (uint64_t)nblk * 2048u);
+        const int base = (int)(int8_t)(range & 0xFFu);              // e_lo + 2 - 2
+        const int top = (int)(int8_t)((range >> 8) & 0xFFu) - 2;    // e_hi - 2
+        if (planes == 4) {
+            const u32x4 w0 = ld16s<NT_LD>(b), w1 = ld16s<NT_LD>(b + 1024);
+            if (e < n_e) st16<NT_ST>(o, decode_octet_gse8(w0.x, w0.y, base, top));
+            if (e + 512 < n_e) st16<NT_ST>(o + 1024, decode_octet_gse8(w0.z, w0.w, base, top));
+            if (e + 1024 < n_e) st16<NT_ST>(o + 2048, decode_octet_gse8(w1.x, w1.y, base, top));
+            if (e + 1536 < n_e) st16<NT_ST>(o + 3072, decode_octet_gse8(w1.z, w1.w, base, top));
+        } else {
+            const u32x4 w = ld16s<NT_LD>(b + (j0 >> 1) * 1024u);
+            if (e < n_e) st16<NT_ST>(o, decode_octet_gse8(w.x, w.y, base, top));
+            if (e + 512 < n_e) st16<NT_ST>(o + 1024, decode_octet_gse8(w.z, w.w, base, top));
+        }
     } else {
         const uint8_t *b = c.src + (uint64_t)tile * ((uint64_t)nblk * 4096u) +
                            (uint64_t)blk * 4096u + j0 * 1024u + lane_b;
@@ -232,7 +272,7 @@ hipError_t launch_k1(K1Params &p, const K1Launch &cfg, hipStream_t stream)
         if (n_e > 0x7FFFFFFFull) return hipErrorInvalidValue;  // element indices are 32-bit
         const uint64_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
         const uint32_t prec = p.c[i].fmt & 0xFFu;
-        if (prec > kE5M2) return hipErrorInvalidValue;
+        if (prec > kGSE8) return hipErrorInvalidValue;
         const uint32_t planes = prec == kInt4 ? 4u : prec == kP16 ? cfg.planes16 : cfg.planes8;
         p.item_start[i] = (uint32_t)per_tile;
         per_tile += nblk * (4u / planes);
@@ -495,6 +535,102 @@ __global__ void __launch_bounds__(256) k2_pack_fp8(const uint8_t *__restrict__ s
     st16<false>(o + 1024, u32x4{code[2][0], code[2][1], code[3][0], code[3][1]});
 }
 
+// GSE-8: one workgroup per tile.  Pass 1 finds the smallest and largest exponent of the
+// tile's nonzero values (BF16 subnormals count as exponent -126), pass 2 encodes.
+// Exponents are handled in biased form (field value, 1..254).
+__global__ void __launch_bounds__(256) k2_pack_gse8(const uint8_t *__restrict__ src,
+                                                    uint8_t *__restrict__ dst, uint32_t n_tokens,
+                                                    uint32_t head_dim)
+{
+    __shared__ uint32_t s_lo[4], s_hi[4];
+    const uint32_t n_e = n_tokens * head_dim;
+    const uint32_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    const uint32_t tile = blockIdx.x;
+    const uint8_t *in = src + (uint64_t)tile * n_e * 2u;
+    uint8_t *rec = dst + (uint64_t)tile * ((uint64_t)nblk * 2048u + 16u);
+
+    uint32_t lo = 255, hi = 0;  // biased exponents; lo > hi means "no nonzero value yet"
+    for (uint32_t blk = wave; blk < nblk; blk += 4) {
+        const uint32_t e = blk * kBlockElems + lane * 8;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (e + j * 512 >= n_e) continue;
+            const u32x4 raw = ld16(in + (uint64_t)blk * 4096u + j * 1024 + lane * 16u);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t w = (raw[k] >> (16 * h)) & 0x7FFFu;
+                    uint32_t eb = w >> 7;
+                    eb = eb ? eb : 1u;
+                    if (w) {
+                        lo = eb < lo ? eb : lo;
+                        hi = eb > hi ? eb : hi;
+                    }
+                }
+            }
+        }
+    }
+    for (int o = 32; o >= 1; o >>= 1) {
+        const uint32_t l2 = (uint32_t)__shfl_xor((int)lo, o), h2 = (uint32_t)__shfl_xor((int)hi, o);
+        lo = l2 < lo ? l2 : lo;
+        hi = h2 > hi ? h2 : hi;
+    }
+    if (lane == 0) {
+        s_lo[wave] = lo;
+        s_hi[wave] = hi;
+    }
+    __syncthreads();
+    lo = s_lo[0];
+    hi = s_hi[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+        lo = s_lo[w] < lo ? s_lo[w] : lo;
+        hi = s_hi[w] > hi ? s_hi[w] : hi;
+    }
+    if (lo > hi) lo = hi = 127;          // all zero: range (e_lo, e_hi) = (0, 0)
+    if (lo + 47 < hi) lo = hi - 47;      // 16 shared exponents, 3 apart, reach 48 binades
+
+    for (uint32_t blk = wave; blk < nblk; blk += 4) {
+        const uint32_t e = blk * kBlockElems + lane * 8;
+        uint32_t code[4][2];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            u32x4 raw = u32x4{0, 0, 0, 0};
+            if (e + j * 512 < n_e) raw = ld16(in + (uint64_t)blk * 4096u + j * 1024 + lane * 16u);
+#pragma unroll
+            for (int d = 0; d < 2; ++d) {  // four elements -> one dword of codes
+                uint32_t cw = 0;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t w = (raw[2 * d + (q >> 1)] >> (16 * (q & 1))) & 0xFFFFu;
+                    const uint32_t mag = w & 0x7FFFu;
+                    uint32_t eb = mag >> 7;
+                    eb = eb ? eb : 1u;
+                    const uint32_t rel = eb > lo ? eb - lo : 0u;     // exponent above e_lo
+                    const uint32_t k = (rel * 171u) >> 9;            // rel / 3 for rel < 128
+                    uint32_t g = lo + 2u + 3u * k;                   // k-th shared exponent, biased
+                    g = g < hi ? g : hi;
+                    const float a = __builtin_bit_cast(float, mag << 16);
+                    // |x| * 2^(2 - G), truncated: 0..7 (0 when the leading one is shifted out)
+                    const uint32_t field = (uint32_t)__builtin_ldexpf(a, 2 + 127 - (int)g);
+                    const uint32_t c8 = ((w >> 8) & 0x80u) | (field ? ((k << 3) | field) : 0u);
+                    cw |= c8 << (8 * q);
+                }
+                code[j][d] = cw;
+            }
+        }
+        uint8_t *o = rec + (uint64_t)blk * 2048u + lane * 16u;
+        st16<false>(o, u32x4{code[0][0], code[0][1], code[1][0], code[1][1]});
+        st16<false>(o + 1024, u32x4{code[2][0], code[2][1], code[3][0], code[3][1]});
+    }
+    if (threadIdx.x == 0) {
+        const uint32_t e_lo = (lo - 127u) & 0xFFu, e_hi = (hi - 127u) & 0xFFu;
+        st16<false>(rec + (uint64_t)nblk * 2048u, u32x4{e_lo | (e_hi << 8), 0, 0, 0});
+    }
+}
+
 template <int BITS>
 static void launch_k2_g(uint32_t gsh, dim3 grid, hipStream_t stream, const uint8_t *s, uint8_t *d,
                         uint32_t n_tokens, uint32_t head_dim, uint32_t wg_per_tile,
@@ -527,7 +663,9 @@ hipError_t launch_k2(const void *src, void *dst, uint32_t n_tiles, uint32_t head
     const uint8_t *s = static_cast<const uint8_t *>(src);
     uint8_t *d = static_cast<uint8_t *>(dst);
     dim3 grid((uint32_t)gx);
-    if (prec == kE4M3 || prec == kE5M2) {
+    if (prec == kGSE8) {
+        hipLaunchKernelGGL(k2_pack_gse8, dim3(n_tiles), dim3(256), 0, stream, s, d, n_tokens, head_dim);
+    } else if (prec == kE4M3 || prec == kE5M2) {
         if (prec == kE5M2)
             hipLaunchKernelGGL(k2_pack_fp8<true>, grid, dim3(256), 0, stream, s, d, n_tokens, head_dim, wg_per_tile);
         else

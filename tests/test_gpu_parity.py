@@ -13,7 +13,8 @@ pytestmark = pytest.mark.gpu
 
 CANARY = 0x7FC1          # a BF16 NaN pattern no kernel output can contain
 # the oracle's name for each storage format
-ORC = {B.PREC_16: 16, B.PREC_INT8: 8, B.PREC_INT4: 4, B.PREC_FP8_E4M3: 43, B.PREC_FP8_E5M2: 52}
+ORC = {B.PREC_16: 16, B.PREC_INT8: 8, B.PREC_INT4: 4, B.PREC_FP8_E4M3: 43, B.PREC_FP8_E5M2: 52,
+       B.PREC_GSE8: 143}
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -271,9 +272,49 @@ def test_fp8_decode_every_code(prec):
     ctx.destroy()
 
 
-def test_all_five_tags_in_one_request_through_the_pool():
+# ---- GSE-8 (the paper's scheme S4) -------------------------------------------------------
+def _gse_roundtrip(src, T):
+    L, _, H, _, D = src.shape
+    ctx = B.Context(L, H, D, T, group_int8=32, group_int4=32)
+    ref, _ = codec.quantize_pack_chunk(src, 143)
+    got, _ = gpu_quantize(ctx, src, B.PREC_GSE8, 0)
+    bad = np.flatnonzero(got != ref)
+    assert bad.size == 0, f"{bad.size} bytes differ, first at {bad[:8]}"
+    ref_out = np.full((L, 2, H, T + 2, D), CANARY, np.uint16)
+    codec.dequant_scatter_chunk(ref, (L, H, D), T, 143, 0, ref_out, 1)
+    out = torch.full((L, 2, H, T + 2, D), CANARY, dtype=torch.int16, device="cuda")
+    ctx.load_packed([(dev_u8(got), T, B.PREC_GSE8, 0)], out, T + 2, 1)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u16(out), ref_out)
+    ctx.destroy()
+
+
+def test_gse8_every_finite_bf16_value_in_tiles_of_different_ranges():
+    words = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    f = wl.bf16_words_to_f32(words)
+    words = np.where(np.isfinite(f), words, 0).astype(np.uint16)
+    tiles = []
+    # tile 0: everything (range clipped to 48 binades below the top); the others: slices of
+    # the exponent axis, among them BF16 subnormals only, and an all-zero tile
+    for lo_e, hi_e in [(0, 255), (100, 140), (120, 128), (0, 1), (1, 30), (126, 127), (200, 254), (0, 0)]:
+        e = (words >> 7) & 0xFF
+        keep = (e >= lo_e) & (e <= hi_e) if hi_e else (words & 0x7FFF) == 0
+        tiles.append(np.where(keep, words, 0).astype(np.uint16))
+    src = np.stack(tiles).reshape(2, 2, 2, 512, 128)
+    _gse_roundtrip(src, 512)
+
+
+@pytest.mark.parametrize("shape", [(2, 2, 64, 128), (1, 2, 128, 100), (1, 1, 128, 1), (2, 1, 96, 40),
+                                   (1, 2, 128, 272)])
+def test_gse8_shapes(shape):
+    L, H, D, T = shape
+    _gse_roundtrip(wl.kv_chunk(L, H, D, T, 77, outlier_channels=1), T)
+    _gse_roundtrip(special_values_chunk(L, H, D, T, 78), T)
+
+
+def test_all_six_tags_in_one_request_through_the_pool():
     L, H, D, T, g = 2, 2, 128, 72, 64
-    precs = [B.PREC_FP8_E5M2, B.PREC_INT4, B.PREC_16, B.PREC_FP8_E4M3, B.PREC_INT8, B.PREC_FP8_E4M3]
+    precs = [B.PREC_FP8_E5M2, B.PREC_INT4, B.PREC_16, B.PREC_FP8_E4M3, B.PREC_INT8, B.PREC_GSE8]
     tokens = [72, 40, 9, 72, 33, 1]
     ctx = _pool_ctx(L, H, D, T, g, hbm_slots=2, pin_slots=3, stg_slots=2, tau_gpu_ppm=400_000,
                     precs=sorted(set(precs)))

@@ -9,7 +9,8 @@ from paper_2510_20878_amd import binding as B
 from paper_2510_20878_amd import workloads as wl
 
 # the oracle's name for each storage format
-ORC = {B.PREC_16: 16, B.PREC_INT8: 8, B.PREC_INT4: 4, B.PREC_FP8_E4M3: 43, B.PREC_FP8_E5M2: 52}
+ORC = {B.PREC_16: 16, B.PREC_INT8: 8, B.PREC_INT4: 4, B.PREC_FP8_E4M3: 43, B.PREC_FP8_E5M2: 52,
+       B.PREC_GSE8: 143}
 FAKE_HBM = 0x7F0000000000     # never dereferenced in dry_run
 FAKE_PIN = 0x7E0000000000
 FAKE_STG = 0x7D0000000000
@@ -31,6 +32,8 @@ def test_chunk_bytes_equals_oracle(shape, T):
             assert pay == L * 2 * H * codec.tile_payload_bytes(T, D, bits)
             assert pay + meta == total
             assert (meta == 0) == (prec in (B.PREC_16, B.PREC_FP8_E4M3, B.PREC_FP8_E5M2))
+            if prec == B.PREC_GSE8:
+                assert meta == 16 * L * 2 * H
 
 
 def test_chunk_bytes_rejects_bad_shapes():
