@@ -101,23 +101,32 @@ __device__ __forceinline__ u32x4 decode_octet_fp8(uint32_t c0, uint32_t c1)
 // 8 GSE-8 codes (two dwords) of one plane -> 8 BF16.  base = e_lo + 2 - 2 and top = e_hi - 2
 // are the tile's exponent bounds already lowered by the 2 fraction places of the field:
 // value = +-field * 2^min(base + 3k, top), exact in BF16.
-__device__ __forceinline__ float decode_gse8(uint32_t w, int b, int base, int top)
+__device__ __forceinline__ float decode_gse8(uint32_t w, uint32_t fields, int b, int base, int top)
 {
-    const uint32_t c = (w >> (8 * b)) & 0xFFu;
-    const float field = (float)(c & 7u);
-    int n = (int)((c >> 3) & 15u) * 3 + base;
+    int n = (int)((w >> (8 * b + 3)) & 15u) * 3 + base;
     n = n < top ? n : top;
-    const float v = __builtin_ldexpf(field, n);
-    return __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, v) | ((c & 0x80u) << 24));
+    return __builtin_ldexpf(byte_f(fields, b), n);
+}
+
+// two codes (bytes b, b+1 of w) -> one dword of two BF16; the sign bits are moved from bit 7
+// of each code to bit 15 of each half by one byte permute
+template <int B>
+__device__ __forceinline__ uint32_t decode_pair_gse8(uint32_t w, uint32_t fields, int base, int top)
+{
+    const uint32_t mag = pack_bf16(decode_gse8(w, fields, B, base, top),
+                                   decode_gse8(w, fields, B + 1, base, top));
+    constexpr uint32_t sel = 0x0Cu | (uint32_t(B) << 8) | (0x0Cu << 16) | (uint32_t(B + 1) << 24);
+    return mag | (__builtin_amdgcn_perm(0u, w, sel) & 0x80008000u);
 }
 
 __device__ __forceinline__ u32x4 decode_octet_gse8(uint32_t c0, uint32_t c1, int base, int top)
 {
+    const uint32_t f0 = c0 & 0x07070707u, f1 = c1 & 0x07070707u;
     u32x4 r;
-    r.x = pack_bf16(decode_gse8(c0, 0, base, top), decode_gse8(c0, 1, base, top));
-    r.y = pack_bf16(decode_gse8(c0, 2, base, top), decode_gse8(c0, 3, base, top));
-    r.z = pack_bf16(decode_gse8(c1, 0, base, top), decode_gse8(c1, 1, base, top));
-    r.w = pack_bf16(decode_gse8(c1, 2, base, top), decode_gse8(c1, 3, base, top));
+    r.x = decode_pair_gse8<0>(c0, f0, base, top);
+    r.y = decode_pair_gse8<2>(c0, f0, base, top);
+    r.z = decode_pair_gse8<0>(c1, f1, base, top);
+    r.w = decode_pair_gse8<2>(c1, f1, base, top);
     return r;
 }
 
