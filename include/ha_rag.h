@@ -67,6 +67,7 @@ extern "C" {
 #define HA_RAG_ENOSPC (-3)  /* pool slab full, output cache too small, staging too small */
 #define HA_RAG_EFORMAT (-4) /* tag / group / shape mismatch                              */
 #define HA_RAG_EHIP (-5)    /* a HIP call failed; see ha_rag_last_hip_error              */
+#define HA_RAG_EIO (-6)     /* a file operation failed; see ha_rag_last_hip_error        */
 
 #define HA_RAG_PREC_16 0
 #define HA_RAG_PREC_INT8 1
@@ -76,8 +77,11 @@ extern "C" {
 #define HA_RAG_PREC_GSE8 5     /* the paper's scheme S4, GSE-8 with the 1+4+3 split */
 #define HA_RAG_N_PREC 6
 
-#define HA_RAG_TIER_HBM 0    /* queueGPU of Algorithm 2 */
-#define HA_RAG_TIER_PINNED 1 /* queuePIN of Algorithm 2 */
+#define HA_RAG_TIER_HBM 0      /* queueGPU of Algorithm 2                                  */
+#define HA_RAG_TIER_PINNED 1   /* queuePIN: page-locked host memory, copied straight to HBM */
+#define HA_RAG_TIER_PAGEABLE 2 /* queuePAGE: ordinary host memory; goes through a pinned
+                                  bounce buffer on its way to HBM (Sec. 2.3, Fig. 8)       */
+#define HA_RAG_TIER_DISK 3     /* a file; read into a pinned bounce buffer first           */
 #define HA_RAG_TIER_NONE 255
 
 #define HA_RAG_NO_CHUNK UINT64_MAX
@@ -93,12 +97,21 @@ typedef struct ha_rag_config {
     uint32_t group_int8;       /* group size of the INT8 tag: 32..512, power of 2, | D     */
     uint32_t group_int4;       /* group size of the INT4 tag                               */
     uint32_t tau_gpu_ppm;      /* Algorithm 2 step 1: GPU_LIST = ranks below
-                                  floor(tau_gpu_ppm * N / 1e6), N = chunks in the pool     */
+                                  idx1 = floor(tau_gpu_ppm * N / 1e6), N = chunks in the pool */
     uint32_t rerank_interval;  /* recompute ranks after this many load calls; 0 = only in
                                   ha_rag_rerank                                            */
     uint32_t n_copy_streams;   /* streams for pinned -> HBM copies (0 = 2, at most 8)      */
     uint32_t dry_run;          /* 1 = host bookkeeping only: no HIP call is ever made, no
                                   byte is moved (for host-logic tests without a GPU)      */
+    uint32_t tau_pin_ppm;      /* PIN_LIST = ranks [idx1, idx2), idx2 = idx1 +
+                                  floor(tau_pin_ppm * N / 1e6)                             */
+    uint32_t tau_page_ppm;     /* PAGE_LIST = ranks [idx2, idx3), idx3 = idx2 +
+                                  floor(tau_page_ppm * N / 1e6); DISK_LIST = the rest      */
+    uint32_t disk_o_direct;    /* 1 = open pool files with O_DIRECT (bypasses the OS page
+                                  cache; transfers are rounded up to 4096 bytes and pass
+                                  through one page-aligned host buffer that the library
+                                  allocates in ha_rag_register_bounce, because direct I/O
+                                  cannot target GPU-pinned memory)                         */
 } ha_rag_config;
 
 /* One packed chunk handed to ha_rag_load_packed (no pool involved). */
@@ -114,6 +127,7 @@ typedef struct ha_rag_chunk_info {
     uint32_t prec, group, n_tokens;
     uint32_t in_hbm, in_pinned; /* 0 / 1                                      */
     uint32_t rank;              /* 0 = hottest, as of the last rerank         */
+    uint32_t in_pageable, on_disk; /* 0 / 1                                   */
     uint64_t count;             /* accesses so far (Algorithm 1's AF entry)   */
     uint64_t bytes;             /* packed size                                */
     const void *hbm_ptr;        /* slot address or NULL                       */
@@ -124,20 +138,27 @@ typedef struct ha_rag_chunk_info {
 typedef struct ha_rag_chunk_trace {
     uint64_t tok_off;     /* first token row of this chunk in the cache        */
     uint64_t evicted_id;  /* chunk dropped from HBM to make room, or NO_CHUNK  */
-    uint8_t found_tier;   /* HA_RAG_TIER_HBM or HA_RAG_TIER_PINNED             */
+    uint8_t found_tier;   /* fastest tier that held the chunk (HA_RAG_TIER_*)   */
     uint8_t promoted;     /* 1 = copied into the HBM slab by this load         */
-    uint8_t promote_skipped; /* 1 = in GPU_LIST but no slot could be freed     */
-    uint8_t reserved[5];
+    uint8_t promote_skipped; /* 1 = its list asked for a faster copy but no slot could be freed */
+    uint8_t placed_tier;  /* tier a new copy was placed into, or HA_RAG_TIER_NONE */
+    uint8_t reserved[4];
 } ha_rag_chunk_trace;
 
 typedef struct ha_rag_load_stats {
     uint32_t n_chunks, n_hbm_hits, n_pinned_hits;
-    uint32_t n_promoted, n_evicted, n_promote_skipped, n_kernel_launches, reserved;
+    uint32_t n_promoted;         /* copies placed into HBM                           */
+    uint32_t n_evicted, n_promote_skipped, n_kernel_launches;
+    uint32_t n_pageable_hits, n_disk_hits;
+    uint32_t n_placed_host;      /* copies placed into pinned or pageable memory     */
+    uint32_t reserved[2];
     uint64_t tokens;
-    uint64_t bytes_h2d;          /* packed bytes copied pinned -> HBM staging        */
+    uint64_t bytes_h2d;          /* packed bytes copied host -> HBM staging          */
     uint64_t bytes_d2d;          /* packed bytes copied staging -> HBM slab          */
     uint64_t packed_bytes_read;  /* payload + meta bytes the kernels read            */
     uint64_t bf16_bytes_written; /* bytes written to the cache                       */
+    uint64_t bytes_disk_read;    /* packed bytes read from files                     */
+    uint64_t bytes_host_copied;  /* packed bytes copied host -> host                 */
 } ha_rag_load_stats;
 
 /* ---- stateless helpers (no context, no GPU) ------------------------------- */
@@ -170,8 +191,8 @@ int ha_rag_create(const ha_rag_config *cfg, ha_rag_ctx **out);
  * first.  The caller's buffers are not touched. */
 int ha_rag_destroy(ha_rag_ctx *ctx);
 
-/* Name of the last failing HIP call and its error string ("" if none).  With
- * ctx == NULL: the reason the calling thread's last ha_rag_create failed. */
+/* Name of the last failing HIP or file call and its error string ("" if none).
+ * With ctx == NULL: the reason the calling thread's last ha_rag_create failed. */
 const char *ha_rag_last_hip_error(ha_rag_ctx *ctx);
 
 /* Launch shape of the gather-dequantize-scatter kernel, for tuning sweeps; the
@@ -214,30 +235,43 @@ int ha_rag_quantize_chunk(ha_rag_ctx *ctx, const void *src, uint32_t n_tokens, u
 int ha_rag_load_packed(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks, uint32_t n,
                        void *out, uint64_t cap_tokens, uint64_t tok_base, void *stream);
 
-/* ---- pools (Algorithm 2's queueGPU / queuePIN) ------------------------------ */
+/* ---- pools (Algorithm 2's queueGPU / queuePIN / queuePAGE and the files) ------- */
 
-/* Gives the context a slab for chunks of tag `prec` in `tier`: `base` is a device
- * pointer (TIER_HBM) or a pinned pointer (TIER_PINNED), 256-byte aligned.  It is
- * cut into fixed slots of ha_rag_chunk_bytes(prec, group_of(prec),
- * max_chunk_tokens) rounded up to 256 bytes.  One slab per (tier, prec); EINVAL if
- * registered twice or smaller than one slot. */
+/* Gives the context a slab for chunks of tag `prec` in a memory tier: `base` is a
+ * device pointer (TIER_HBM) or a pinned pointer (TIER_PINNED), 256-byte aligned, or
+ * a host pointer (TIER_PAGEABLE), 16-byte aligned.  It is cut into fixed slots of
+ * ha_rag_chunk_bytes(prec, group_of(prec), max_chunk_tokens) rounded up to 256
+ * bytes.  One slab per (tier, prec); EINVAL if registered twice or smaller than
+ * one slot. */
 int ha_rag_register_slab(ha_rag_ctx *ctx, uint32_t tier, uint32_t prec, void *base, size_t bytes);
 
-/* Device staging area that cold chunks pass through on their way from pinned
- * memory to the kernel (256-byte aligned).  It is cut into slots as large as the
- * largest pinned-slab slot registered so far; at least 2 slots are required. */
+/* The disk tier for tag `prec`: the file `path` (created and grown if needed) cut
+ * into slots rounded up to 4096 bytes.  It is kept open until ha_rag_destroy and
+ * is not deleted.  EIO if it cannot be opened or grown. */
+int ha_rag_register_disk(ha_rag_ctx *ctx, uint32_t prec, const char *path, size_t bytes);
+
+/* Device staging area that cold chunks pass through on their way from host memory
+ * to the kernel (256-byte aligned).  It is cut into slots as large as the largest
+ * host-side slot registered so far; at least 2 slots are required. */
 int ha_rag_register_staging(ha_rag_ctx *ctx, void *base, size_t bytes);
+
+/* Pinned bounce buffers that pageable and disk chunks are copied / read into before
+ * they are copied to the device (4096-byte aligned pinned pointer).  Cut into slots
+ * as large as the largest pageable / disk slot registered so far; at least 2. */
+int ha_rag_register_bounce(ha_rag_ctx *ctx, void *base, size_t bytes);
 
 /* Adds chunk `id` (tag `prec`, group = the context's group for that tag) to
  * `tier`.  If `packed` is non-NULL its ha_rag_chunk_bytes() bytes are copied into
  * the slot on `stream` (`packed_is_device` says where they are; host sources
  * should be pinned); if NULL the slot is only reserved and the caller fills it
- * (ha_rag_pool_slot + ha_rag_quantize_chunk).  Inserting an id that exists in the
- * other tier adds the second copy (same tag and n_tokens required, else EFORMAT);
- * the pinned copy is the master, an HBM-only chunk is never evicted.
- * EINVAL duplicate in that tier; ENOSPC slab full (pinned), or full of
- * unevictable chunks (HBM; otherwise the least recently used evictable chunk of
- * that slab is dropped). */
+ * (ha_rag_pool_slot + ha_rag_quantize_chunk).  Pageable and disk targets are written
+ * by the calling thread before the call returns (device sources and O_DIRECT files
+ * go through a bounce buffer and `stream` is synchronised).  Inserting an id that
+ * exists in another tier adds a further copy (same tag and n_tokens required, else
+ * EFORMAT).  The copy in the slowest tier is the master: a copy is evictable only
+ * if a slower tier also holds the chunk.  EINVAL duplicate in that tier; ENOSPC
+ * slab full of unevictable chunks (otherwise the least recently used evictable
+ * chunk of that slab is dropped), file slab full, or bounce buffer missing. */
 int ha_rag_pool_insert(ha_rag_ctx *ctx, uint64_t id, uint32_t prec, uint32_t n_tokens,
                        const void *packed, int packed_is_device, uint32_t tier, void *stream);
 
@@ -249,14 +283,17 @@ int ha_rag_pool_slot(ha_rag_ctx *ctx, uint64_t id, uint32_t tier, void **ptr, si
  * rank (no-op if already there); LRU eviction as in insert.  ENOENT / ENOSPC. */
 int ha_rag_pool_promote(ha_rag_ctx *ctx, uint64_t id, void *stream);
 
-/* Drops the HBM copy of `id` (EINVAL if it has no pinned master, ENOENT if not in
- * HBM).  The slot is reused only after the loads that read it have finished. */
-int ha_rag_pool_evict(ha_rag_ctx *ctx, uint64_t id);
+/* Drops the copy of `id` in `tier` (HBM, pinned or pageable; EINVAL if no slower
+ * tier holds the chunk, ENOENT if it is not in that tier).  The slot is reused only
+ * after the transfers and loads that read it have finished. */
+int ha_rag_pool_evict(ha_rag_ctx *ctx, uint64_t id, uint32_t tier);
 
 int ha_rag_pool_query(ha_rag_ctx *ctx, uint64_t id, ha_rag_chunk_info *info);
 
-/* Ids resident in HBM, least recently used first; returns how many were written
- * (at most `cap`) through *n. */
+/* Ids resident in `tier` (HBM, pinned or pageable), least recently used first;
+ * returns how many were written (at most `cap`) through *n.  ha_rag_pool_hbm_lru is
+ * the same for TIER_HBM. */
+int ha_rag_pool_lru(ha_rag_ctx *ctx, uint32_t tier, uint64_t *ids, size_t cap, size_t *n);
 int ha_rag_pool_hbm_lru(ha_rag_ctx *ctx, uint64_t *ids, size_t cap, size_t *n);
 
 /* ---- hotness (Algorithm 1 step 1, Algorithm 2 step 1) ------------------------ */
@@ -269,26 +306,32 @@ int ha_rag_touch(ha_rag_ctx *ctx, const uint64_t *ids, size_t n);
 int ha_rag_set_counts(ha_rag_ctx *ctx, const uint64_t *ids, const uint64_t *counts, size_t n);
 
 /* Sorts all chunks by count (descending, ties by ascending id), assigns ranks and
- * recomputes the GPU_LIST boundary floor(tau_gpu_ppm * N / 1e6). */
+ * recomputes the list boundaries idx1, idx2, idx3 of Algorithm 2 step 1. */
 int ha_rag_rerank(ha_rag_ctx *ctx);
 
 int ha_rag_get_rank(ha_rag_ctx *ctx, uint64_t id, uint32_t *rank);
 
 /* ---- online: the load (Algorithm 2 step 2 + decompression + concatenation) --- */
 
-/* For each id in request order: count the access; if the chunk is in HBM, read it
- * there (refreshing its LRU position); else copy its pinned master into a staging
- * slot on a copy stream and make `stream` wait for that copy; dequantize-scatter
- * it to its token rows; and if its rank is in GPU_LIST, copy it from staging into
- * an HBM slot (evicting the least recently used evictable chunk of that slab if
- * full; skipped, not an error, if nothing can be evicted).
+/* For each id in request order: count the access; find the fastest tier that holds
+ * the chunk and refresh its LRU position there; if that is HBM, read it in place;
+ * else bring the packed bytes into a staging slot (pinned: a host -> HBM copy on a
+ * copy stream; pageable / disk: the calling thread first copies / reads them into a
+ * bounce buffer) and make `stream` wait for that copy; dequantize-scatter the chunk
+ * to its token rows; and if the list its rank belongs to (GPU_LIST, PIN_LIST,
+ * PAGE_LIST) names a faster tier than the one it was found in, place a copy there
+ * (HBM: copied from staging on `stream`; pinned / pageable: copied from the bounce
+ * buffer by the calling thread), evicting the least recently used evictable chunk
+ * of that slab if full (skipped, not an error, if nothing can be evicted).
  *   tags   nullable host array of HA_RAG_PREC_*; if given, tags[i] must equal the
  *          stored tag of ids[i] (EFORMAT otherwise)
  *   out    device BF16 [L][2][H][cap_tokens][D]; chunk i starts at token row
  *          tok_base + sum of the token counts before it
  *   stats, trace  nullable host outputs (trace has n entries)
- * All checks (ENOENT, EFORMAT, ENOSPC for the cache, staging missing while a
- * chunk is cold) happen before any state changes or work is enqueued.  A slot
+ * All checks (ENOENT, EFORMAT, ENOSPC for the cache, staging or bounce buffers
+ * missing for a chunk that needs them) happen before any state changes or work is
+ * enqueued; EIO can occur midway (a file read failed): work enqueued so far stays
+ * valid, the bookkeeping of the call is kept.  A slot
  * that another stream's load may still read is not overwritten before that load
  * has finished (the library records an event per stream after each load). */
 int ha_rag_load_chunks(ha_rag_ctx *ctx, const uint64_t *ids, const uint8_t *tags, uint32_t n,

@@ -10,9 +10,9 @@ import os
 
 from . import build as _build
 
-OK, EINVAL, ENOENT, ENOSPC, EFORMAT, EHIP = 0, -1, -2, -3, -4, -5
+OK, EINVAL, ENOENT, ENOSPC, EFORMAT, EHIP, EIO = 0, -1, -2, -3, -4, -5, -6
 PREC_16, PREC_INT8, PREC_INT4, PREC_FP8_E4M3, PREC_FP8_E5M2, PREC_GSE8 = 0, 1, 2, 3, 4, 5
-TIER_HBM, TIER_PINNED = 0, 1
+TIER_HBM, TIER_PINNED, TIER_PAGEABLE, TIER_DISK, TIER_NONE = 0, 1, 2, 3, 255
 NO_CHUNK = 2**64 - 1
 BITS = {PREC_16: 16, PREC_INT8: 8, PREC_INT4: 4, PREC_FP8_E4M3: 8, PREC_FP8_E5M2: 8,
         PREC_GSE8: 8}  # storage bits
@@ -26,14 +26,15 @@ SYMBOLS = [
     "ha_rag_register_staging", "ha_rag_pool_insert", "ha_rag_pool_slot", "ha_rag_pool_promote",
     "ha_rag_pool_evict", "ha_rag_pool_query", "ha_rag_pool_hbm_lru", "ha_rag_touch",
     "ha_rag_set_counts", "ha_rag_rerank", "ha_rag_get_rank", "ha_rag_load_chunks",
-    "ha_rag_load_batch",
+    "ha_rag_load_batch", "ha_rag_register_disk", "ha_rag_register_bounce", "ha_rag_pool_lru",
 ]
 
 
 class Config(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in (
         "n_layers", "n_kv_heads", "head_dim", "max_chunk_tokens", "group_int8", "group_int4",
-        "tau_gpu_ppm", "rerank_interval", "n_copy_streams", "dry_run")]
+        "tau_gpu_ppm", "rerank_interval", "n_copy_streams", "dry_run", "tau_pin_ppm",
+        "tau_page_ppm", "disk_o_direct")]
 
 
 class LaunchParams(C.Structure):
@@ -49,24 +50,26 @@ class PackedChunk(C.Structure):
 class ChunkInfo(C.Structure):
     _fields_ = [("prec", C.c_uint32), ("group", C.c_uint32), ("n_tokens", C.c_uint32),
                 ("in_hbm", C.c_uint32), ("in_pinned", C.c_uint32), ("rank", C.c_uint32),
-                ("count", C.c_uint64), ("bytes", C.c_uint64),
+                ("in_pageable", C.c_uint32), ("on_disk", C.c_uint32), ("count", C.c_uint64), ("bytes", C.c_uint64),
                 ("hbm_ptr", C.c_void_p), ("pinned_ptr", C.c_void_p)]
 
 
 class ChunkTrace(C.Structure):
     _fields_ = [("tok_off", C.c_uint64), ("evicted_id", C.c_uint64), ("found_tier", C.c_uint8),
                 ("promoted", C.c_uint8), ("promote_skipped", C.c_uint8),
-                ("reserved", C.c_uint8 * 5)]
+                ("placed_tier", C.c_uint8), ("reserved", C.c_uint8 * 4)]
 
 
 class LoadStats(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in (
         "n_chunks", "n_hbm_hits", "n_pinned_hits", "n_promoted", "n_evicted",
-        "n_promote_skipped", "n_kernel_launches", "reserved")] + [(n, C.c_uint64) for n in (
-            "tokens", "bytes_h2d", "bytes_d2d", "packed_bytes_read", "bf16_bytes_written")]
+        "n_promote_skipped", "n_kernel_launches", "n_pageable_hits", "n_disk_hits",
+        "n_placed_host", "reserved0", "reserved1")] + [(n, C.c_uint64) for n in (
+            "tokens", "bytes_h2d", "bytes_d2d", "packed_bytes_read", "bf16_bytes_written",
+            "bytes_disk_read", "bytes_host_copied")]
 
     def as_dict(self):
-        return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}
+        return {n: getattr(self, n) for n, _ in self._fields_ if not n.startswith("reserved")}
 
 
 class HaRagError(RuntimeError):
@@ -114,10 +117,13 @@ def lib():
             "ha_rag_load_packed": (C.c_int, [vp, P(PackedChunk), u32, vp, u64, u64, vp]),
             "ha_rag_register_slab": (C.c_int, [vp, u32, u32, vp, sz]),
             "ha_rag_register_staging": (C.c_int, [vp, vp, sz]),
+            "ha_rag_register_bounce": (C.c_int, [vp, vp, sz]),
+            "ha_rag_register_disk": (C.c_int, [vp, u32, C.c_char_p, sz]),
+            "ha_rag_pool_lru": (C.c_int, [vp, u32, P(u64), sz, P(sz)]),
             "ha_rag_pool_insert": (C.c_int, [vp, u64, u32, u32, vp, C.c_int, u32, vp]),
             "ha_rag_pool_slot": (C.c_int, [vp, u64, u32, P(vp), P(sz)]),
             "ha_rag_pool_promote": (C.c_int, [vp, u64, vp]),
-            "ha_rag_pool_evict": (C.c_int, [vp, u64]),
+            "ha_rag_pool_evict": (C.c_int, [vp, u64, u32]),
             "ha_rag_pool_query": (C.c_int, [vp, u64, P(ChunkInfo)]),
             "ha_rag_pool_hbm_lru": (C.c_int, [vp, P(u64), sz, P(sz)]),
             "ha_rag_touch": (C.c_int, [vp, P(u64), sz]),
@@ -196,9 +202,10 @@ class Context:
 
     def __init__(self, n_layers, n_kv_heads, head_dim, max_chunk_tokens, group_int8=128,
                  group_int4=128, tau_gpu_ppm=50_000, rerank_interval=0, n_copy_streams=0,
-                 dry_run=False):
+                 dry_run=False, tau_pin_ppm=0, tau_page_ppm=0, disk_o_direct=False):
         self.cfg = Config(n_layers, n_kv_heads, head_dim, max_chunk_tokens, group_int8, group_int4,
-                          tau_gpu_ppm, rerank_interval, n_copy_streams, 1 if dry_run else 0)
+                          tau_gpu_ppm, rerank_interval, n_copy_streams, 1 if dry_run else 0,
+                          tau_pin_ppm, tau_page_ppm, 1 if disk_o_direct else 0)
         self._h = C.c_void_p()
         rc = lib().ha_rag_create(C.byref(self.cfg), C.byref(self._h))
         if rc:
@@ -208,7 +215,7 @@ class Context:
 
     def _chk(self, rc, where):
         if rc:
-            detail = lib().ha_rag_last_hip_error(self._h).decode() if rc == EHIP else ""
+            detail = lib().ha_rag_last_hip_error(self._h).decode() if rc in (EHIP, EIO) else ""
             raise HaRagError(rc, where, detail)
 
     def destroy(self):
@@ -261,6 +268,17 @@ class Context:
                   "ha_rag_register_staging")
         self._keep.append(base)
 
+    def register_bounce(self, base, nbytes=None):
+        if nbytes is None:
+            nbytes = base.numel() * base.element_size()
+        self._chk(lib().ha_rag_register_bounce(self._h, _addr(base), nbytes),
+                  "ha_rag_register_bounce")
+        self._keep.append(base)
+
+    def register_disk(self, prec, path, nbytes):
+        self._chk(lib().ha_rag_register_disk(self._h, prec, os.fsencode(path), nbytes),
+                  "ha_rag_register_disk")
+
     def pool_insert(self, cid, prec, n_tokens, packed, tier, packed_is_device=False, stream=None):
         self._chk(lib().ha_rag_pool_insert(self._h, cid, prec, n_tokens, _addr(packed),
                                            1 if packed_is_device else 0, tier, _stream(stream)),
@@ -275,13 +293,19 @@ class Context:
     def pool_promote(self, cid, stream=None):
         self._chk(lib().ha_rag_pool_promote(self._h, cid, _stream(stream)), "ha_rag_pool_promote")
 
-    def pool_evict(self, cid):
-        self._chk(lib().ha_rag_pool_evict(self._h, cid), "ha_rag_pool_evict")
+    def pool_evict(self, cid, tier=TIER_HBM):
+        self._chk(lib().ha_rag_pool_evict(self._h, cid, tier), "ha_rag_pool_evict")
 
     def pool_query(self, cid):
         info = ChunkInfo()
         self._chk(lib().ha_rag_pool_query(self._h, cid, C.byref(info)), "ha_rag_pool_query")
         return info
+
+    def pool_lru(self, tier, cap=1 << 16):
+        ids = (C.c_uint64 * cap)()
+        n = C.c_size_t()
+        self._chk(lib().ha_rag_pool_lru(self._h, tier, ids, cap, C.byref(n)), "ha_rag_pool_lru")
+        return list(ids[:n.value])
 
     def pool_hbm_lru(self, cap=1 << 16):
         ids = (C.c_uint64 * cap)()

@@ -1,11 +1,18 @@
-// Host runtime behind include/ha_rag.h: pool slabs, hotness counters and ranks
-// (Algorithm 1 steps 1-2), the tier lookup / promotion / LRU of Algorithm 2 for
-// the two fast tiers (GPU memory and pinned host memory), and the stream/event
-// pipeline that overlaps pinned -> HBM copies with the dequantize kernel.
+// Host runtime behind include/ha_rag.h: pool slabs in four tiers (GPU memory, pinned
+// host memory, pageable host memory, files), hotness counters and ranks (Algorithm 1
+// steps 1-2), the tier lookup / placement / LRU of Algorithm 2, and the stream/event
+// pipeline that overlaps file reads, host copies and host -> HBM copies with the
+// dequantize kernel.
 #include <hip/hip_runtime.h>
 
+#include <fcntl.h>
+#include <sys/stat.h>
+#include <unistd.h>
+
 #include <algorithm>
+#include <cerrno>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <list>
 #include <mutex>
@@ -22,8 +29,11 @@ using namespace ha_rag;
 namespace {
 
 constexpr uint64_t kPPM = 1000000ull;
-thread_local std::string g_create_err;  // why the last ha_rag_create on this thread failed
 constexpr uint32_t kNoRank = UINT32_MAX;
+constexpr uint32_t kTiers = 4;        // HBM, pinned, pageable, disk
+constexpr uint32_t kCacheTiers = 3;   // tiers with a capacity and an LRU order
+constexpr size_t kDirectAlign = 4096; // offset / size / buffer alignment of O_DIRECT I/O
+thread_local std::string g_create_err;  // why the last ha_rag_create on this thread failed
 
 bool valid_group(uint32_t g)
 {
@@ -67,35 +77,59 @@ struct Chunk {
     uint64_t id = 0;
     uint32_t prec = 0, n_tokens = 0;
     uint64_t bytes = 0;
-    int32_t slot[2] = {-1, -1};  // per tier
+    int32_t slot[kTiers] = {-1, -1, -1, -1};
     uint64_t count = 0;
     uint32_t rank = kNoRank;
-    uint64_t last_use = 0;       // global sequence number of the last HBM access
-    std::list<uint32_t>::iterator lru_it;
+    uint64_t last_use[kCacheTiers] = {0, 0, 0};  // sequence number of the last access per tier
+    std::list<uint32_t>::iterator lru_it[kCacheTiers];
+
+    int fastest() const
+    {
+        for (uint32_t t = 0; t < kTiers; ++t)
+            if (slot[t] >= 0) return (int)t;
+        return -1;
+    }
+    bool has_slower_copy(uint32_t tier) const
+    {
+        for (uint32_t t = tier + 1; t < kTiers; ++t)
+            if (slot[t] >= 0) return true;
+        return false;
+    }
 };
 
-// Which streams touched a slot last, so that a different stream can be made to
-// wait before it overwrites (or first reads) the slot.
+// Who touched a slot last.  HBM slots: the streams that wrote / read it, so that a
+// different stream can be made to wait.  Pinned slots: the stream that wrote it (a
+// device -> host copy) and the events of host -> device copies that read it, which the
+// host waits for before it overwrites the slot.
 struct SlotUse {
     hipStream_t writer = nullptr;
     bool has_writer = false;
     std::vector<hipStream_t> readers;
+    std::vector<hipEvent_t> read_events;
 };
 
 struct Slab {
-    uint8_t *base = nullptr;
+    uint8_t *base = nullptr;  // memory tiers
+    int fd = -1;              // disk tier
     size_t slot_bytes = 0;
     uint32_t n_slots = 0;
+    bool reg = false;
     std::vector<uint32_t> free_slots;  // stack
     std::vector<SlotUse> use;
     std::list<uint32_t> lru;           // chunk indices resident here, least recent first
-    bool registered() const { return base != nullptr; }
+    bool registered() const { return reg; }
     uint8_t *ptr(int32_t s) const { return base + (size_t)s * slot_bytes; }
+    off_t offset(int32_t s) const { return (off_t)((size_t)s * slot_bytes); }
 };
 
 struct StagingSlot {
     hipEvent_t filled = nullptr, consumed = nullptr;
     bool consumed_valid = false;
+};
+
+struct BounceSlot {
+    hipEvent_t h2d_done = nullptr;
+    bool busy = false;
 };
 
 }  // namespace
@@ -104,19 +138,26 @@ struct ha_rag_ctx {
     ha_rag_config cfg{};
     uint32_t n_tiles = 0;
     std::mutex mu;
-    std::string hip_err;
+    std::string err;  // last failing HIP or I/O call
 
     std::vector<Chunk> chunks;
     std::unordered_map<uint64_t, uint32_t> index;
-    Slab slab[2][HA_RAG_N_PREC];
+    Slab slab[kTiers][HA_RAG_N_PREC];
 
-    uint32_t gpu_bound = 0;  // ranks below this are GPU_LIST
+    uint32_t bound[3] = {0, 0, 0};  // ranks below bound[t] belong to the list of tier <= t
     uint64_t n_loads = 0, use_seq = 0;
 
     uint8_t *staging = nullptr;
     size_t staging_slot_bytes = 0;
     std::vector<StagingSlot> stg;
     uint64_t stg_next = 0;
+
+    uint8_t *bounce = nullptr;  // pinned buffers that pageable / disk chunks pass through
+    size_t bounce_slot_bytes = 0;
+    uint8_t *dio = nullptr;     // page-aligned ordinary memory for O_DIRECT transfers: the
+                                // kernel cannot do direct I/O on GPU-pinned host memory
+    std::vector<BounceSlot> bnc;
+    uint64_t bnc_next = 0;
 
     std::vector<hipStream_t> copy_streams;
     uint64_t copy_rr = 0;
@@ -129,18 +170,71 @@ struct ha_rag_ctx {
         return prec == HA_RAG_PREC_INT8 ? cfg.group_int8 : prec == HA_RAG_PREC_INT4 ? cfg.group_int4 : 0;
     }
     bool dry() const { return cfg.dry_run != 0; }
+    bool direct() const { return cfg.disk_o_direct != 0; }
+    size_t io_bytes(uint64_t bytes) const  // what a file transfer of `bytes` moves
+    {
+        return direct() ? (size_t)((bytes + kDirectAlign - 1) / kDirectAlign * kDirectAlign) : (size_t)bytes;
+    }
+    // Algorithm 2 step 1: which list a rank belongs to
+    uint32_t list_of(uint32_t rank) const
+    {
+        return rank < bound[0] ? HA_RAG_TIER_HBM
+               : rank < bound[1] ? HA_RAG_TIER_PINNED
+               : rank < bound[2] ? HA_RAG_TIER_PAGEABLE
+                                 : HA_RAG_TIER_DISK;
+    }
 };
 
 namespace {
 
-#define HIPCHK(ctx, call)                                                              \
-    do {                                                                               \
-        hipError_t e_ = (call);                                                        \
-        if (e_ != hipSuccess) {                                                        \
-            (ctx)->hip_err = std::string(#call) + ": " + hipGetErrorString(e_);        \
-            return HA_RAG_EHIP;                                                        \
-        }                                                                              \
+#define HIPCHK(ctx, call)                                                      \
+    do {                                                                       \
+        hipError_t e_ = (call);                                                \
+        if (e_ != hipSuccess) {                                                \
+            (ctx)->err = std::string(#call) + ": " + hipGetErrorString(e_);    \
+            return HA_RAG_EHIP;                                                \
+        }                                                                      \
     } while (0)
+
+int io_error(ha_rag_ctx *c, const char *what)
+{
+    c->err = std::string(what) + ": " + std::strerror(errno);
+    return HA_RAG_EIO;
+}
+
+int read_full(ha_rag_ctx *c, int fd, uint8_t *dst, size_t n, off_t off)
+{
+    while (n) {
+        const ssize_t r = pread(fd, dst, n, off);
+        if (r < 0) {
+            if (errno == EINTR) continue;
+            return io_error(c, "pread");
+        }
+        if (r == 0) {
+            c->err = "pread: unexpected end of file";
+            return HA_RAG_EIO;
+        }
+        dst += r;
+        off += r;
+        n -= (size_t)r;
+    }
+    return HA_RAG_OK;
+}
+
+int write_full(ha_rag_ctx *c, int fd, const uint8_t *src, size_t n, off_t off)
+{
+    while (n) {
+        const ssize_t r = pwrite(fd, src, n, off);
+        if (r < 0) {
+            if (errno == EINTR) continue;
+            return io_error(c, "pwrite");
+        }
+        src += r;
+        off += r;
+        n -= (size_t)r;
+    }
+    return HA_RAG_OK;
+}
 
 int stream_event(ha_rag_ctx *c, hipStream_t s, hipEvent_t *out)
 {
@@ -200,6 +294,27 @@ int before_write(ha_rag_ctx *c, SlotUse &u, hipStream_t s)
     return HA_RAG_OK;
 }
 
+// The host is about to overwrite a host-memory slot: wait until every device copy that
+// reads or writes it has finished.
+int before_host_write(ha_rag_ctx *c, SlotUse &u)
+{
+    if (!c->dry()) {
+        for (hipEvent_t ev : u.read_events) HIPCHK(c, hipEventSynchronize(ev));
+        if (u.has_writer) {
+            auto it = c->stream_done.find(u.writer);
+            if (it != c->stream_done.end()) HIPCHK(c, hipEventSynchronize(it->second));
+        }
+        for (hipStream_t r : u.readers) {
+            auto it = c->stream_done.find(r);
+            if (it != c->stream_done.end()) HIPCHK(c, hipEventSynchronize(it->second));
+        }
+    }
+    u.read_events.clear();
+    u.readers.clear();
+    u.has_writer = false;
+    return HA_RAG_OK;
+}
+
 Chunk *find_chunk(ha_rag_ctx *c, uint64_t id, uint32_t *idx = nullptr)
 {
     auto it = c->index.find(id);
@@ -208,55 +323,57 @@ Chunk *find_chunk(ha_rag_ctx *c, uint64_t id, uint32_t *idx = nullptr)
     return &c->chunks[it->second];
 }
 
-void hbm_touch(ha_rag_ctx *c, uint32_t ci)
+void tier_touch(ha_rag_ctx *c, uint32_t tier, uint32_t ci)  // queueX.get(C_i)
 {
+    if (tier >= kCacheTiers) return;
     Chunk &ch = c->chunks[ci];
-    Slab &sl = c->slab[HA_RAG_TIER_HBM][ch.prec];
-    sl.lru.splice(sl.lru.end(), sl.lru, ch.lru_it);  // most recent at the back
-    ch.last_use = ++c->use_seq;
+    Slab &sl = c->slab[tier][ch.prec];
+    sl.lru.splice(sl.lru.end(), sl.lru, ch.lru_it[tier]);  // most recent at the back
+    ch.last_use[tier] = ++c->use_seq;
 }
 
-void hbm_attach(ha_rag_ctx *c, uint32_t ci, int32_t slot)
+void tier_attach(ha_rag_ctx *c, uint32_t tier, uint32_t ci, int32_t slot)
 {
     Chunk &ch = c->chunks[ci];
-    Slab &sl = c->slab[HA_RAG_TIER_HBM][ch.prec];
-    ch.slot[HA_RAG_TIER_HBM] = slot;
-    ch.lru_it = sl.lru.insert(sl.lru.end(), ci);
-    ch.last_use = ++c->use_seq;
+    ch.slot[tier] = slot;
+    if (tier >= kCacheTiers) return;
+    Slab &sl = c->slab[tier][ch.prec];
+    ch.lru_it[tier] = sl.lru.insert(sl.lru.end(), ci);
+    ch.last_use[tier] = ++c->use_seq;
 }
 
-void hbm_detach(ha_rag_ctx *c, uint32_t ci)
+void tier_detach(ha_rag_ctx *c, uint32_t tier, uint32_t ci)
 {
     Chunk &ch = c->chunks[ci];
-    Slab &sl = c->slab[HA_RAG_TIER_HBM][ch.prec];
-    sl.lru.erase(ch.lru_it);
-    sl.free_slots.push_back((uint32_t)ch.slot[HA_RAG_TIER_HBM]);
-    ch.slot[HA_RAG_TIER_HBM] = -1;
+    Slab &sl = c->slab[tier][ch.prec];
+    if (tier < kCacheTiers) sl.lru.erase(ch.lru_it[tier]);
+    sl.free_slots.push_back((uint32_t)ch.slot[tier]);
+    ch.slot[tier] = -1;
 }
 
-// A free HBM slot of the slab for `prec`, evicting the least recently used chunk
-// that has a pinned master if the slab is full ("put C_i in queueGPU with LRU").
-// Returns -1 if nothing can be freed.  *evicted receives the dropped id.  Chunks
-// flagged in `keep` (indexed like ctx->chunks) are passed over: a copy that the
-// running call has itself just created is not dropped again by the same call,
-// because a later read of it may already be planned.
-int32_t hbm_acquire(ha_rag_ctx *c, uint32_t prec, uint64_t *evicted,
-                    const std::vector<uint8_t> *keep = nullptr)
+// A free slot of the slab (tier, prec); if the slab is full the least recently used chunk
+// that also lives in a slower tier is dropped ("put C_i in queueX with LRU").  Returns -1 if
+// nothing can be freed.  *evicted receives the dropped id.  Chunks flagged in `keep`
+// (indexed like ctx->chunks) are passed over: a copy that the running call has itself
+// just created is not dropped again by the same call, because a later read of it may
+// already be planned.
+int32_t tier_acquire(ha_rag_ctx *c, uint32_t tier, uint32_t prec, uint64_t *evicted,
+                     const std::vector<uint8_t> *keep = nullptr)
 {
-    Slab &sl = c->slab[HA_RAG_TIER_HBM][prec];
+    Slab &sl = c->slab[tier][prec];
     *evicted = HA_RAG_NO_CHUNK;
     if (!sl.registered()) return -1;
-    if (sl.free_slots.empty()) {
+    if (sl.free_slots.empty() && tier < kCacheTiers) {
         for (uint32_t ci : sl.lru) {
             if (keep && (*keep)[ci]) continue;
-            if (c->chunks[ci].slot[HA_RAG_TIER_PINNED] >= 0) {
+            if (c->chunks[ci].has_slower_copy(tier)) {
                 *evicted = c->chunks[ci].id;
-                hbm_detach(c, ci);
+                tier_detach(c, tier, ci);
                 break;
             }
         }
-        if (sl.free_slots.empty()) return -1;
     }
+    if (sl.free_slots.empty()) return -1;
     const int32_t s = (int32_t)sl.free_slots.back();
     sl.free_slots.pop_back();
     return s;
@@ -273,7 +390,13 @@ void rerank_locked(ha_rag_ctx *c)
         return x.id < y.id;
     });
     for (size_t r = 0; r < n; ++r) c->chunks[order[r]].rank = (uint32_t)r;
-    c->gpu_bound = (uint32_t)std::min<uint64_t>(n, ((uint64_t)c->cfg.tau_gpu_ppm * n) / kPPM);
+    // idx_1 = tau_GPU * N, idx_2 = tau_PIN * N + idx_1, idx_3 = tau_PAGE * N + idx_2
+    const uint32_t tau[3] = {c->cfg.tau_gpu_ppm, c->cfg.tau_pin_ppm, c->cfg.tau_page_ppm};
+    uint64_t acc = 0;
+    for (int t = 0; t < 3; ++t) {
+        acc = std::min<uint64_t>(n, acc + ((uint64_t)tau[t] * n) / kPPM);
+        c->bound[t] = (uint32_t)acc;
+    }
 }
 
 struct Request {
@@ -288,9 +411,11 @@ struct Action {
     uint32_t req;
     uint64_t tok_off;
     enum Kind { HOT_EARLY, HOT_LATE, COLD } kind;
-    int32_t promote_slot;  // HBM slot to fill from staging, or -1
-    int32_t hbm_slot;      // slot read by a HOT_* action, as of the moment it was decided
-                           // (a later chunk of the same call may evict this one)
+    uint8_t src_tier;      // tier the bytes come from
+    int32_t src_slot;      // slot in that tier, as of the moment the action was decided (a
+                           // later chunk of the same call may evict this copy)
+    uint8_t place_tier;    // tier a new copy is placed into, or HA_RAG_TIER_NONE
+    int32_t place_slot;
 };
 
 K1Chunk make_desc(const ha_rag_ctx *c, const Chunk &ch, const uint8_t *src, const Request &rq,
@@ -335,6 +460,35 @@ void init_batch(const ha_rag_ctx *c, Batch &b)
     b.p.total_items = 0;
 }
 
+// Next bounce buffer, once the host -> device copy that last read it has finished.
+int acquire_bounce(ha_rag_ctx *c, size_t *idx)
+{
+    const size_t b = (size_t)(c->bnc_next++ % c->bnc.size());
+    if (!c->dry() && c->bnc[b].busy) {
+        HIPCHK(c, hipEventSynchronize(c->bnc[b].h2d_done));
+        c->bnc[b].busy = false;
+    }
+    *idx = b;
+    return HA_RAG_OK;
+}
+
+// Packed bytes of a chunk from its pageable or disk copy into a bounce buffer (host work,
+// synchronous).
+int fill_bounce(ha_rag_ctx *c, const Chunk &ch, uint32_t tier, int32_t slot, uint8_t *dst)
+{
+    if (c->dry()) return HA_RAG_OK;
+    const Slab &sl = c->slab[tier][ch.prec];
+    if (tier == HA_RAG_TIER_PAGEABLE) {
+        std::memcpy(dst, sl.ptr(slot), ch.bytes);
+        return HA_RAG_OK;
+    }
+    if (!c->direct()) return read_full(c, sl.fd, dst, ch.bytes, sl.offset(slot));
+    int rc = read_full(c, sl.fd, c->dio, c->io_bytes(ch.bytes), sl.offset(slot));
+    if (rc) return rc;
+    std::memcpy(dst, c->dio, ch.bytes);
+    return HA_RAG_OK;
+}
+
 int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Request *reqs,
               uint32_t n_req, uint32_t n, hipStream_t s, ha_rag_load_stats *stats,
               ha_rag_chunk_trace *trace)
@@ -342,7 +496,6 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     const uint64_t D = c->cfg.head_dim;
     // ---- checks: nothing changes before all of them pass --------------------
     std::vector<uint32_t> cis(n);
-    bool any_cold = false;
     for (uint32_t r = 0; r < n_req; ++r) {
         const Request &rq = reqs[r];
         if (rq.end < rq.begin || rq.end > n) return HA_RAG_EINVAL;
@@ -352,15 +505,18 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
             Chunk *ch = find_chunk(c, ids[i], &cis[i]);
             if (!ch) return HA_RAG_ENOENT;
             if (tags && tags[i] != ch->prec) return HA_RAG_EFORMAT;
-            if (ch->slot[HA_RAG_TIER_HBM] < 0) {
-                any_cold = true;
-                if (c->stg.size() < 2 || ch->bytes > c->staging_slot_bytes) return HA_RAG_ENOSPC;
-            }
+            const int f = ch->fastest();
+            if (f < 0) return HA_RAG_ENOENT;
+            if (f >= (int)HA_RAG_TIER_PINNED &&
+                (c->stg.size() < 2 || ch->bytes > c->staging_slot_bytes))
+                return HA_RAG_ENOSPC;
+            if (f >= (int)HA_RAG_TIER_PAGEABLE &&
+                (c->bnc.size() < 2 || c->io_bytes(ch->bytes) > c->bounce_slot_bytes))
+                return HA_RAG_ENOSPC;
             tok += ch->n_tokens;
         }
         if (rq.base > rq.cap || tok > rq.cap - rq.base) return HA_RAG_ENOSPC;
     }
-    (void)any_cold;
 
     if (c->cfg.rerank_interval && c->n_loads && (c->n_loads % c->cfg.rerank_interval) == 0)
         rerank_locked(c);
@@ -373,7 +529,9 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     // ---- pass A: Algorithm 2 step 2, chunk by chunk, in request order ---------
     std::vector<Action> acts;
     acts.reserve(n);
-    std::vector<uint8_t> written_now(c->chunks.size(), 0);  // HBM copy created by this call
+    // copies created by this call, per cache tier: not evicted again by this call
+    std::vector<uint8_t> made[kCacheTiers];
+    for (auto &m : made) m.assign(c->chunks.size(), 0);
     for (uint32_t r = 0; r < n_req; ++r) {
         const Request &rq = reqs[r];
         uint64_t off = rq.base;
@@ -381,33 +539,54 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
             const uint32_t ci = cis[i];
             Chunk &ch = c->chunks[ci];
             ch.count += 1;
-            Action a{ci, r, off, Action::COLD, -1, -1};
+            const uint32_t found = (uint32_t)ch.fastest();
+            Action a{ci, r, off, Action::COLD, (uint8_t)found, ch.slot[found], HA_RAG_TIER_NONE, -1};
             ha_rag_chunk_trace tr;
             std::memset(&tr, 0, sizeof tr);
             tr.tok_off = off;
             tr.evicted_id = HA_RAG_NO_CHUNK;
-            if (ch.slot[HA_RAG_TIER_HBM] >= 0) {  // C_i in queueGPU
-                hbm_touch(c, ci);
-                a.kind = written_now[ci] ? Action::HOT_LATE : Action::HOT_EARLY;
-                a.hbm_slot = ch.slot[HA_RAG_TIER_HBM];
-                tr.found_tier = HA_RAG_TIER_HBM;
+            tr.found_tier = (uint8_t)found;
+            tr.placed_tier = HA_RAG_TIER_NONE;
+            tier_touch(c, found, ci);
+            switch (found) {
+            case HA_RAG_TIER_HBM:
+                a.kind = made[HA_RAG_TIER_HBM][ci] ? Action::HOT_LATE : Action::HOT_EARLY;
                 ++st.n_hbm_hits;
-            } else {                               // C_i in queuePIN
-                tr.found_tier = HA_RAG_TIER_PINNED;
-                ++st.n_pinned_hits;
+                break;
+            case HA_RAG_TIER_PINNED: ++st.n_pinned_hits; break;
+            case HA_RAG_TIER_PAGEABLE:
+                ++st.n_pageable_hits;
+                st.bytes_host_copied += ch.bytes;
+                break;
+            default:
+                ++st.n_disk_hits;
+                st.bytes_disk_read += ch.bytes;
+                break;
+            }
+            if (found != HA_RAG_TIER_HBM) {
                 st.bytes_h2d += ch.bytes;
-                if (ch.rank < c->gpu_bound && c->slab[HA_RAG_TIER_HBM][ch.prec].registered()) {
+                // the list the chunk's rank belongs to says where a copy should be kept;
+                // only a tier faster than the one it was found in gets one
+                const uint32_t want = ch.rank == kNoRank ? HA_RAG_TIER_DISK : c->list_of(ch.rank);
+                if (want < found && c->slab[want][ch.prec].registered()) {
                     uint64_t ev;
-                    const int32_t slot = hbm_acquire(c, ch.prec, &ev, &written_now);
+                    const int32_t slot = tier_acquire(c, want, ch.prec, &ev, &made[want]);
                     if (slot >= 0) {
-                        hbm_attach(c, ci, slot);
-                        written_now[ci] = 1;
-                        a.promote_slot = slot;
-                        tr.promoted = 1;
+                        tier_attach(c, want, ci, slot);
+                        made[want][ci] = 1;
+                        a.place_tier = (uint8_t)want;
+                        a.place_slot = slot;
+                        tr.placed_tier = (uint8_t)want;
                         tr.evicted_id = ev;
-                        ++st.n_promoted;
-                        st.bytes_d2d += ch.bytes;
                         if (ev != HA_RAG_NO_CHUNK) ++st.n_evicted;
+                        if (want == HA_RAG_TIER_HBM) {
+                            tr.promoted = 1;
+                            ++st.n_promoted;
+                            st.bytes_d2d += ch.bytes;
+                        } else {
+                            ++st.n_placed_host;
+                            st.bytes_host_copied += ch.bytes;
+                        }
                     } else {
                         tr.promote_skipped = 1;
                         ++st.n_promote_skipped;
@@ -424,37 +603,69 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     }
 
     // ---- pass B: enqueue ---------------------------------------------------------
-    // 1. copies of the first cold chunks (as many as there are staging slots)
+    // 1. transfers of the first cold chunks (as many as there are staging slots)
     // 2. one kernel over every chunk that was already resident in HBM
-    // 3. per cold chunk: wait for its copy, kernel, promotion copy, release the
-    //    staging slot, start the copy of the cold chunk that reuses it
+    // 3. per cold chunk: wait for its transfer, kernel, copy into the HBM slab if it was
+    //    placed there, release the staging slot, start the transfer that reuses it
     // 4. one kernel over chunks whose HBM copy was written in step 3
+    // A transfer is a host -> HBM copy from the pinned slot, or, for pageable and disk
+    // chunks, a host copy / file read into a pinned bounce buffer (synchronous, on this
+    // thread; also the moment a pinned / pageable copy is written) followed by that copy.
     std::vector<uint32_t> cold;
     for (uint32_t k = 0; k < acts.size(); ++k)
         if (acts[k].kind == Action::COLD) cold.push_back(k);
     const size_t n_stg = c->stg.size();
     std::vector<size_t> cold_slot(cold.size());
 
-    auto start_copy = [&](size_t k) -> int {
+    auto start_transfer = [&](size_t k) -> int {
         const Action &a = acts[cold[k]];
         const Chunk &ch = c->chunks[a.ci];
         const size_t sidx = (size_t)(c->stg_next++ % n_stg);
         cold_slot[k] = sidx;
+        const uint8_t *src = nullptr;
+        size_t bidx = 0;
+        if (a.src_tier == HA_RAG_TIER_PINNED) {
+            src = c->slab[HA_RAG_TIER_PINNED][ch.prec].ptr(a.src_slot);
+        } else {
+            int rc = acquire_bounce(c, &bidx);
+            if (rc) return rc;
+            uint8_t *bp = c->bounce + bidx * c->bounce_slot_bytes;
+            rc = fill_bounce(c, ch, a.src_tier, a.src_slot, bp);
+            if (rc) return rc;
+            if (a.place_tier == HA_RAG_TIER_PINNED || a.place_tier == HA_RAG_TIER_PAGEABLE) {
+                Slab &ds = c->slab[a.place_tier][ch.prec];
+                rc = before_host_write(c, ds.use[a.place_slot]);
+                if (rc) return rc;
+                if (!c->dry()) std::memcpy(ds.ptr(a.place_slot), bp, ch.bytes);
+            }
+            src = bp;
+        }
         if (c->dry()) return HA_RAG_OK;
         StagingSlot &ss = c->stg[sidx];
         hipStream_t cs = c->copy_streams[c->copy_rr++ % c->copy_streams.size()];
         if (ss.consumed_valid) HIPCHK(c, hipStreamWaitEvent(cs, ss.consumed, 0));
-        const Slab &ps = c->slab[HA_RAG_TIER_PINNED][ch.prec];
-        HIPCHK(c, hipMemcpyAsync(c->staging + sidx * c->staging_slot_bytes,
-                                 ps.ptr(ch.slot[HA_RAG_TIER_PINNED]), ch.bytes,
+        if (a.src_tier == HA_RAG_TIER_PINNED) {
+            SlotUse &u = c->slab[HA_RAG_TIER_PINNED][ch.prec].use[a.src_slot];
+            if (u.has_writer) {  // a device -> host copy may still be filling the slot
+                int rc = wait_for(c, cs, u.writer);
+                if (rc) return rc;
+            }
+            u.read_events.push_back(ss.filled);
+            if (u.read_events.size() > 8) u.read_events.erase(u.read_events.begin());
+        }
+        HIPCHK(c, hipMemcpyAsync(c->staging + sidx * c->staging_slot_bytes, src, ch.bytes,
                                  hipMemcpyHostToDevice, cs));
         HIPCHK(c, hipEventRecord(ss.filled, cs));
+        if (a.src_tier != HA_RAG_TIER_PINNED) {
+            HIPCHK(c, hipEventRecord(c->bnc[bidx].h2d_done, cs));
+            c->bnc[bidx].busy = true;
+        }
         return HA_RAG_OK;
     };
 
-    size_t copies_started = 0;
-    for (; copies_started < cold.size() && copies_started < n_stg; ++copies_started) {
-        int rc = start_copy(copies_started);
+    size_t started = 0;
+    for (; started < cold.size() && started < n_stg; ++started) {
+        int rc = start_transfer(started);
         if (rc) return rc;
     }
 
@@ -464,9 +675,9 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
         if (a.kind != Action::HOT_EARLY) continue;
         const Chunk &ch = c->chunks[a.ci];
         Slab &hs = c->slab[HA_RAG_TIER_HBM][ch.prec];
-        int rc = before_read(c, hs.use[a.hbm_slot], s);
+        int rc = before_read(c, hs.use[a.src_slot], s);
         if (rc) return rc;
-        rc = push(c, batch, make_desc(c, ch, hs.ptr(a.hbm_slot), reqs[a.req], a.tok_off), s,
+        rc = push(c, batch, make_desc(c, ch, hs.ptr(a.src_slot), reqs[a.req], a.tok_off), s,
                   &st.n_kernel_launches);
         if (rc) return rc;
     }
@@ -483,20 +694,20 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
         if (rc) return rc;
         rc = flush(c, batch, s, &st.n_kernel_launches);
         if (rc) return rc;
-        if (a.promote_slot >= 0) {
+        if (a.place_tier == HA_RAG_TIER_HBM) {
             Slab &hs = c->slab[HA_RAG_TIER_HBM][ch.prec];
-            rc = before_write(c, hs.use[a.promote_slot], s);
+            rc = before_write(c, hs.use[a.place_slot], s);
             if (rc) return rc;
             if (!c->dry())
-                HIPCHK(c, hipMemcpyAsync(hs.ptr(a.promote_slot), sp, ch.bytes,
+                HIPCHK(c, hipMemcpyAsync(hs.ptr(a.place_slot), sp, ch.bytes,
                                          hipMemcpyDeviceToDevice, s));
         }
         if (!c->dry()) {
             HIPCHK(c, hipEventRecord(c->stg[sidx].consumed, s));
             c->stg[sidx].consumed_valid = true;
         }
-        if (copies_started < cold.size()) {
-            rc = start_copy(copies_started++);
+        if (started < cold.size()) {
+            rc = start_transfer(started++);
             if (rc) return rc;
         }
     }
@@ -504,12 +715,12 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     for (const Action &a : acts) {
         if (a.kind != Action::HOT_LATE) continue;
         const Chunk &ch = c->chunks[a.ci];
-        // `keep` in pass A guarantees the copy written by this call is still in its slot
-        if (ch.slot[HA_RAG_TIER_HBM] != a.hbm_slot) return HA_RAG_EINVAL;
+        // `made` in pass A guarantees the copy written by this call is still in its slot
+        if (ch.slot[HA_RAG_TIER_HBM] != a.src_slot) return HA_RAG_EINVAL;
         Slab &hs = c->slab[HA_RAG_TIER_HBM][ch.prec];
-        rc = before_read(c, hs.use[a.hbm_slot], s);
+        rc = before_read(c, hs.use[a.src_slot], s);
         if (rc) return rc;
-        rc = push(c, batch, make_desc(c, ch, hs.ptr(a.hbm_slot), reqs[a.req], a.tok_off), s,
+        rc = push(c, batch, make_desc(c, ch, hs.ptr(a.src_slot), reqs[a.req], a.tok_off), s,
                   &st.n_kernel_launches);
         if (rc) return rc;
     }
@@ -518,6 +729,25 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     rc = mark_stream(c, s);
     if (rc) return rc;
     if (stats) *stats = st;
+    return HA_RAG_OK;
+}
+
+int register_slab_common(ha_rag_ctx *c, Slab &sl, uint32_t prec, size_t bytes, size_t align)
+{
+    size_t total;
+    int rc = chunk_bytes_impl(c->cfg.n_layers, c->cfg.n_kv_heads, c->cfg.head_dim, prec,
+                              c->group_of(prec), c->cfg.max_chunk_tokens, nullptr, nullptr, &total);
+    if (rc) return rc;
+    const size_t slot = (total + align - 1) / align * align;
+    if (bytes < slot) return HA_RAG_EINVAL;
+    const size_t n_slots = bytes / slot;
+    if (n_slots > 0x7FFFFFFFu) return HA_RAG_EINVAL;
+    sl.slot_bytes = slot;
+    sl.n_slots = (uint32_t)n_slots;
+    sl.use.assign(n_slots, SlotUse());
+    sl.free_slots.resize(n_slots);
+    for (size_t i = 0; i < n_slots; ++i) sl.free_slots[i] = (uint32_t)(n_slots - 1 - i);  // slot 0 first
+    sl.reg = true;
     return HA_RAG_OK;
 }
 
@@ -567,14 +797,15 @@ const char *ha_rag_strerror(int code)
     case HA_RAG_OK: return "ok";
     case HA_RAG_EINVAL: return "invalid argument";
     case HA_RAG_ENOENT: return "unknown chunk id";
-    case HA_RAG_ENOSPC: return "no space (pool slab, staging or output cache)";
+    case HA_RAG_ENOSPC: return "no space (pool slab, staging, bounce buffer or output cache)";
     case HA_RAG_EFORMAT: return "precision tag / group / shape mismatch";
     case HA_RAG_EHIP: return "HIP call failed";
+    case HA_RAG_EIO: return "file I/O failed";
     default: return "unknown error code";
     }
 }
 
-const char *ha_rag_version(void) { return "ha_rag 0.1 (gfx950)"; }
+const char *ha_rag_version(void) { return "ha_rag 0.2 (gfx950)"; }
 
 int ha_rag_create(const ha_rag_config *cfg, ha_rag_ctx **out)
 {
@@ -584,7 +815,9 @@ int ha_rag_create(const ha_rag_config *cfg, ha_rag_ctx **out)
     if (cfg->head_dim == 0 || (cfg->head_dim % 8u)) return HA_RAG_EFORMAT;
     if (!valid_group(cfg->group_int8) || !valid_group(cfg->group_int4)) return HA_RAG_EFORMAT;
     if ((cfg->head_dim % cfg->group_int8) || (cfg->head_dim % cfg->group_int4)) return HA_RAG_EFORMAT;
-    if (cfg->tau_gpu_ppm > kPPM || cfg->n_copy_streams > 8) return HA_RAG_EINVAL;
+    if (cfg->tau_gpu_ppm > kPPM || cfg->tau_pin_ppm > kPPM || cfg->tau_page_ppm > kPPM ||
+        cfg->n_copy_streams > 8)
+        return HA_RAG_EINVAL;
     if ((uint64_t)cfg->max_chunk_tokens * cfg->head_dim > 0x7FFFFFFFull) return HA_RAG_EINVAL;
     ha_rag_ctx *c = new (std::nothrow) ha_rag_ctx();
     if (!c) return HA_RAG_EINVAL;
@@ -621,14 +854,19 @@ int ha_rag_destroy(ha_rag_ctx *c)
             if (s.filled) (void)hipEventDestroy(s.filled);
             if (s.consumed) (void)hipEventDestroy(s.consumed);
         }
+        for (BounceSlot &b : c->bnc)
+            if (b.h2d_done) (void)hipEventDestroy(b.h2d_done);
     }
+    for (uint32_t p = 0; p < HA_RAG_N_PREC; ++p)
+        if (c->slab[HA_RAG_TIER_DISK][p].fd >= 0) (void)close(c->slab[HA_RAG_TIER_DISK][p].fd);
+    std::free(c->dio);
     delete c;
     return HA_RAG_OK;
 }
 
 const char *ha_rag_last_hip_error(ha_rag_ctx *c)
 {
-    return c ? c->hip_err.c_str() : g_create_err.c_str();
+    return c ? c->err.c_str() : g_create_err.c_str();
 }
 
 int ha_rag_set_launch_params(ha_rag_ctx *c, const ha_rag_launch_params *lp)
@@ -698,25 +936,44 @@ int ha_rag_load_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, uint32_
 
 int ha_rag_register_slab(ha_rag_ctx *c, uint32_t tier, uint32_t prec, void *base, size_t bytes)
 {
-    if (!c || !base || tier > HA_RAG_TIER_PINNED || prec >= HA_RAG_N_PREC) return HA_RAG_EINVAL;
-    if ((uintptr_t)base & 255u) return HA_RAG_EINVAL;
+    if (!c || !base || tier > HA_RAG_TIER_PAGEABLE || prec >= HA_RAG_N_PREC) return HA_RAG_EINVAL;
+    if ((uintptr_t)base & (tier == HA_RAG_TIER_PAGEABLE ? 15u : 255u)) return HA_RAG_EINVAL;
     std::lock_guard<std::mutex> g(c->mu);
     Slab &sl = c->slab[tier][prec];
     if (sl.registered()) return HA_RAG_EINVAL;
-    size_t total;
-    int rc = chunk_bytes_impl(c->cfg.n_layers, c->cfg.n_kv_heads, c->cfg.head_dim, prec,
-                              c->group_of(prec), c->cfg.max_chunk_tokens, nullptr, nullptr, &total);
+    int rc = register_slab_common(c, sl, prec, bytes, 256);
     if (rc) return rc;
-    const size_t slot = (total + 255u) & ~(size_t)255u;
-    if (bytes < slot) return HA_RAG_EINVAL;
-    const size_t n_slots = bytes / slot;
-    if (n_slots > 0x7FFFFFFFu) return HA_RAG_EINVAL;
     sl.base = static_cast<uint8_t *>(base);
-    sl.slot_bytes = slot;
-    sl.n_slots = (uint32_t)n_slots;
-    sl.use.assign(n_slots, SlotUse());
-    sl.free_slots.resize(n_slots);
-    for (size_t i = 0; i < n_slots; ++i) sl.free_slots[i] = (uint32_t)(n_slots - 1 - i);  // slot 0 first
+    return HA_RAG_OK;
+}
+
+int ha_rag_register_disk(ha_rag_ctx *c, uint32_t prec, const char *path, size_t bytes)
+{
+    if (!c || !path || prec >= HA_RAG_N_PREC) return HA_RAG_EINVAL;
+    std::lock_guard<std::mutex> g(c->mu);
+    Slab &sl = c->slab[HA_RAG_TIER_DISK][prec];
+    if (sl.registered()) return HA_RAG_EINVAL;
+    int rc = register_slab_common(c, sl, prec, bytes, kDirectAlign);
+    if (rc) return rc;
+    if (!c->dry()) {
+        int flags = O_RDWR | O_CREAT;
+        if (c->direct()) flags |= O_DIRECT;
+        sl.fd = open(path, flags, 0600);
+        if (sl.fd < 0) {
+            sl.reg = false;
+            return io_error(c, "open");
+        }
+        struct stat stt;
+        if (fstat(sl.fd, &stt) != 0 ||
+            ((size_t)stt.st_size < (size_t)sl.n_slots * sl.slot_bytes &&
+             ftruncate(sl.fd, (off_t)((size_t)sl.n_slots * sl.slot_bytes)) != 0)) {
+            rc = io_error(c, "ftruncate");
+            (void)close(sl.fd);
+            sl.fd = -1;
+            sl.reg = false;
+            return rc;
+        }
+    }
     return HA_RAG_OK;
 }
 
@@ -726,9 +983,9 @@ int ha_rag_register_staging(ha_rag_ctx *c, void *base, size_t bytes)
     std::lock_guard<std::mutex> g(c->mu);
     if (c->staging) return HA_RAG_EINVAL;
     size_t slot = 0;
-    for (uint32_t p = 0; p < HA_RAG_N_PREC; ++p)
-        slot = std::max(slot, c->slab[HA_RAG_TIER_PINNED][p].slot_bytes);
-    if (slot == 0) return HA_RAG_EINVAL;  // register the pinned slabs first
+    for (uint32_t t = HA_RAG_TIER_PINNED; t < kTiers; ++t)
+        for (uint32_t p = 0; p < HA_RAG_N_PREC; ++p) slot = std::max(slot, c->slab[t][p].slot_bytes);
+    if (slot == 0) return HA_RAG_EINVAL;  // register the host-side slabs first
     const size_t n = bytes / slot;
     if (n < 2) return HA_RAG_ENOSPC;
     c->stg.resize(n);
@@ -743,10 +1000,35 @@ int ha_rag_register_staging(ha_rag_ctx *c, void *base, size_t bytes)
     return HA_RAG_OK;
 }
 
+int ha_rag_register_bounce(ha_rag_ctx *c, void *base, size_t bytes)
+{
+    if (!c || !base || ((uintptr_t)base & (kDirectAlign - 1))) return HA_RAG_EINVAL;
+    std::lock_guard<std::mutex> g(c->mu);
+    if (c->bounce) return HA_RAG_EINVAL;
+    size_t slot = 0;
+    for (uint32_t t = HA_RAG_TIER_PAGEABLE; t < kTiers; ++t)
+        for (uint32_t p = 0; p < HA_RAG_N_PREC; ++p) slot = std::max(slot, c->slab[t][p].slot_bytes);
+    if (slot == 0) return HA_RAG_EINVAL;  // register the pageable / disk slabs first
+    slot = (slot + kDirectAlign - 1) / kDirectAlign * kDirectAlign;
+    const size_t n = bytes / slot;
+    if (n < 2) return HA_RAG_ENOSPC;
+    if (c->direct() && !c->dry()) {
+        void *p = nullptr;
+        if (posix_memalign(&p, kDirectAlign, slot) != 0) return HA_RAG_ENOSPC;
+        c->dio = static_cast<uint8_t *>(p);
+    }
+    c->bnc.resize(n);
+    if (!c->dry())
+        for (BounceSlot &b : c->bnc) HIPCHK(c, hipEventCreateWithFlags(&b.h2d_done, hipEventDisableTiming));
+    c->bounce = static_cast<uint8_t *>(base);
+    c->bounce_slot_bytes = slot;
+    return HA_RAG_OK;
+}
+
 int ha_rag_pool_insert(ha_rag_ctx *c, uint64_t id, uint32_t prec, uint32_t n_tokens,
                        const void *packed, int packed_is_device, uint32_t tier, void *stream)
 {
-    if (!c || tier > HA_RAG_TIER_PINNED || prec >= HA_RAG_N_PREC || id == HA_RAG_NO_CHUNK) return HA_RAG_EINVAL;
+    if (!c || tier >= kTiers || prec >= HA_RAG_N_PREC || id == HA_RAG_NO_CHUNK) return HA_RAG_EINVAL;
     if (n_tokens == 0 || n_tokens > c->cfg.max_chunk_tokens) return HA_RAG_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     std::lock_guard<std::mutex> g(c->mu);
@@ -762,16 +1044,13 @@ int ha_rag_pool_insert(ha_rag_ctx *c, uint64_t id, uint32_t prec, uint32_t n_tok
         if (ch->slot[tier] >= 0) return HA_RAG_EINVAL;
         if (ch->prec != prec || ch->n_tokens != n_tokens) return HA_RAG_EFORMAT;
     }
-    int32_t slot;
-    if (tier == HA_RAG_TIER_HBM) {
-        uint64_t ev;
-        slot = hbm_acquire(c, prec, &ev);
-        if (slot < 0) return HA_RAG_ENOSPC;
-    } else {
-        if (sl.free_slots.empty()) return HA_RAG_ENOSPC;
-        slot = (int32_t)sl.free_slots.back();
-        sl.free_slots.pop_back();
-    }
+    // pageable / disk targets fed from device memory or through O_DIRECT need a bounce buffer
+    const bool via_bounce = packed && tier >= HA_RAG_TIER_PAGEABLE && packed_is_device;
+    if (packed && tier == HA_RAG_TIER_DISK && c->direct() && !c->dry() && !c->dio) return HA_RAG_ENOSPC;
+    if (via_bounce && (c->bnc.size() < 2 || c->io_bytes(total) > c->bounce_slot_bytes)) return HA_RAG_ENOSPC;
+    uint64_t ev;
+    const int32_t slot = tier_acquire(c, tier, prec, &ev);
+    if (slot < 0) return HA_RAG_ENOSPC;
     if (!ch) {
         ci = (uint32_t)c->chunks.size();
         c->chunks.emplace_back();
@@ -782,28 +1061,55 @@ int ha_rag_pool_insert(ha_rag_ctx *c, uint64_t id, uint32_t prec, uint32_t n_tok
         ch->bytes = total;
         c->index.emplace(id, ci);
     }
-    if (tier == HA_RAG_TIER_HBM) hbm_attach(c, ci, slot);
-    else ch->slot[tier] = slot;
-    if (packed && !c->dry()) {
+    tier_attach(c, tier, ci, slot);
+    if (!packed || c->dry()) return HA_RAG_OK;
+    if (tier == HA_RAG_TIER_HBM) {
         rc = before_write(c, sl.use[slot], s);
         if (rc) return rc;
-        if (tier == HA_RAG_TIER_HBM) {
-            HIPCHK(c, hipMemcpyAsync(sl.ptr(slot), packed, total,
-                                     packed_is_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, s));
-        } else if (packed_is_device) {
-            HIPCHK(c, hipMemcpyAsync(sl.ptr(slot), packed, total, hipMemcpyDeviceToHost, s));
-        } else {
-            std::memcpy(sl.ptr(slot), packed, total);
-        }
-        rc = mark_stream(c, s);
-        if (rc) return rc;
+        HIPCHK(c, hipMemcpyAsync(sl.ptr(slot), packed, total,
+                                 packed_is_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, s));
+        return mark_stream(c, s);
     }
-    return HA_RAG_OK;
+    if (tier == HA_RAG_TIER_PINNED) {
+        rc = before_host_write(c, sl.use[slot]);
+        if (rc) return rc;
+        if (packed_is_device) {
+            HIPCHK(c, hipMemcpyAsync(sl.ptr(slot), packed, total, hipMemcpyDeviceToHost, s));
+            sl.use[slot].writer = s;
+            sl.use[slot].has_writer = true;
+            return mark_stream(c, s);
+        }
+        std::memcpy(sl.ptr(slot), packed, total);
+        return HA_RAG_OK;
+    }
+    // pageable or disk: the bytes have to be in host memory first
+    const uint8_t *host = static_cast<const uint8_t *>(packed);
+    if (via_bounce) {
+        size_t bidx;
+        rc = acquire_bounce(c, &bidx);
+        if (rc) return rc;
+        uint8_t *bp = c->bounce + bidx * c->bounce_slot_bytes;
+        if (packed_is_device) {
+            HIPCHK(c, hipMemcpyAsync(bp, packed, total, hipMemcpyDeviceToHost, s));
+            HIPCHK(c, hipStreamSynchronize(s));
+        } else {
+            std::memcpy(bp, packed, total);
+        }
+        host = bp;
+    }
+    if (tier == HA_RAG_TIER_PAGEABLE) {
+        std::memcpy(sl.ptr(slot), host, total);
+        return HA_RAG_OK;
+    }
+    if (!c->direct()) return write_full(c, sl.fd, host, total, sl.offset(slot));
+    std::memcpy(c->dio, host, total);
+    std::memset(c->dio + total, 0, c->io_bytes(total) - total);
+    return write_full(c, sl.fd, c->dio, c->io_bytes(total), sl.offset(slot));
 }
 
 int ha_rag_pool_slot(ha_rag_ctx *c, uint64_t id, uint32_t tier, void **ptr, size_t *bytes)
 {
-    if (!c || tier > HA_RAG_TIER_PINNED) return HA_RAG_EINVAL;
+    if (!c || tier > HA_RAG_TIER_PAGEABLE) return HA_RAG_EINVAL;
     std::lock_guard<std::mutex> g(c->mu);
     Chunk *ch = find_chunk(c, id);
     if (!ch || ch->slot[tier] < 0) return HA_RAG_ENOENT;
@@ -823,31 +1129,37 @@ int ha_rag_pool_promote(ha_rag_ctx *c, uint64_t id, void *stream)
     if (ch->slot[HA_RAG_TIER_HBM] >= 0) return HA_RAG_OK;
     if (ch->slot[HA_RAG_TIER_PINNED] < 0) return HA_RAG_ENOENT;
     uint64_t ev;
-    const int32_t slot = hbm_acquire(c, ch->prec, &ev);
+    const int32_t slot = tier_acquire(c, HA_RAG_TIER_HBM, ch->prec, &ev);
     if (slot < 0) return HA_RAG_ENOSPC;
-    hbm_attach(c, ci, slot);
+    tier_attach(c, HA_RAG_TIER_HBM, ci, slot);
     if (!c->dry()) {
         Slab &hs = c->slab[HA_RAG_TIER_HBM][ch->prec];
+        Slab &ps = c->slab[HA_RAG_TIER_PINNED][ch->prec];
         int rc = before_write(c, hs.use[slot], s);
         if (rc) return rc;
-        HIPCHK(c, hipMemcpyAsync(hs.ptr(slot),
-                                 c->slab[HA_RAG_TIER_PINNED][ch->prec].ptr(ch->slot[HA_RAG_TIER_PINNED]),
-                                 ch->bytes, hipMemcpyHostToDevice, s));
+        SlotUse &pu = ps.use[ch->slot[HA_RAG_TIER_PINNED]];
+        if (pu.has_writer) {
+            rc = wait_for(c, s, pu.writer);
+            if (rc) return rc;
+        }
+        if (std::find(pu.readers.begin(), pu.readers.end(), s) == pu.readers.end()) pu.readers.push_back(s);
+        HIPCHK(c, hipMemcpyAsync(hs.ptr(slot), ps.ptr(ch->slot[HA_RAG_TIER_PINNED]), ch->bytes,
+                                 hipMemcpyHostToDevice, s));
         rc = mark_stream(c, s);
         if (rc) return rc;
     }
     return HA_RAG_OK;
 }
 
-int ha_rag_pool_evict(ha_rag_ctx *c, uint64_t id)
+int ha_rag_pool_evict(ha_rag_ctx *c, uint64_t id, uint32_t tier)
 {
-    if (!c) return HA_RAG_EINVAL;
+    if (!c || tier >= kCacheTiers) return HA_RAG_EINVAL;
     std::lock_guard<std::mutex> g(c->mu);
     uint32_t ci;
     Chunk *ch = find_chunk(c, id, &ci);
-    if (!ch || ch->slot[HA_RAG_TIER_HBM] < 0) return HA_RAG_ENOENT;
-    if (ch->slot[HA_RAG_TIER_PINNED] < 0) return HA_RAG_EINVAL;
-    hbm_detach(c, ci);
+    if (!ch || ch->slot[tier] < 0) return HA_RAG_ENOENT;
+    if (!ch->has_slower_copy(tier)) return HA_RAG_EINVAL;
+    tier_detach(c, tier, ci);
     return HA_RAG_OK;
 }
 
@@ -863,6 +1175,8 @@ int ha_rag_pool_query(ha_rag_ctx *c, uint64_t id, ha_rag_chunk_info *info)
     info->n_tokens = ch->n_tokens;
     info->in_hbm = ch->slot[HA_RAG_TIER_HBM] >= 0;
     info->in_pinned = ch->slot[HA_RAG_TIER_PINNED] >= 0;
+    info->in_pageable = ch->slot[HA_RAG_TIER_PAGEABLE] >= 0;
+    info->on_disk = ch->slot[HA_RAG_TIER_DISK] >= 0;
     info->rank = ch->rank;
     info->count = ch->count;
     info->bytes = ch->bytes;
@@ -872,17 +1186,23 @@ int ha_rag_pool_query(ha_rag_ctx *c, uint64_t id, ha_rag_chunk_info *info)
     return HA_RAG_OK;
 }
 
-int ha_rag_pool_hbm_lru(ha_rag_ctx *c, uint64_t *ids, size_t cap, size_t *n)
+int ha_rag_pool_lru(ha_rag_ctx *c, uint32_t tier, uint64_t *ids, size_t cap, size_t *n)
 {
-    if (!c || !n || (cap && !ids)) return HA_RAG_EINVAL;
+    if (!c || !n || (cap && !ids) || tier >= kCacheTiers) return HA_RAG_EINVAL;
     std::lock_guard<std::mutex> g(c->mu);
     std::vector<const Chunk *> v;
     for (const Chunk &ch : c->chunks)
-        if (ch.slot[HA_RAG_TIER_HBM] >= 0) v.push_back(&ch);
-    std::sort(v.begin(), v.end(), [](const Chunk *a, const Chunk *b) { return a->last_use < b->last_use; });
+        if (ch.slot[tier] >= 0) v.push_back(&ch);
+    std::sort(v.begin(), v.end(),
+              [tier](const Chunk *a, const Chunk *b) { return a->last_use[tier] < b->last_use[tier]; });
     *n = std::min(cap, v.size());
     for (size_t i = 0; i < *n; ++i) ids[i] = v[i]->id;
     return HA_RAG_OK;
+}
+
+int ha_rag_pool_hbm_lru(ha_rag_ctx *c, uint64_t *ids, size_t cap, size_t *n)
+{
+    return ha_rag_pool_lru(c, HA_RAG_TIER_HBM, ids, cap, n);
 }
 
 int ha_rag_touch(ha_rag_ctx *c, const uint64_t *ids, size_t n)

@@ -41,6 +41,9 @@ int main(int argc, char **argv)
         cfg.group_int4 = 64;
         cfg.tau_gpu_ppm = (uint32_t)(rnd() % 1000001);
         cfg.rerank_interval = (uint32_t)(rnd() % 4);
+        cfg.tau_pin_ppm = (uint32_t)(rnd() % 400001);
+        cfg.tau_page_ppm = (uint32_t)(rnd() % 400001);
+        cfg.disk_o_direct = (uint32_t)(rnd() % 2);
         cfg.dry_run = 1;
         ha_rag_ctx *ctx = nullptr;
         REQUIRE(ha_rag_create(&cfg, &ctx) == HA_RAG_OK);
@@ -56,14 +59,18 @@ int main(int argc, char **argv)
                                          slot[p] * hbm_slots) == HA_RAG_OK);
             REQUIRE(ha_rag_register_slab(ctx, HA_RAG_TIER_PINNED, p, (void *)(0x200000000000ull + p * 0x10000000000ull),
                                          slot[p] * pin_slots) == HA_RAG_OK);
+            REQUIRE(ha_rag_register_slab(ctx, HA_RAG_TIER_PAGEABLE, p, (void *)(0x500000000000ull + p * 0x10000000000ull),
+                                         slot[p] * (1 + rnd() % 4)) == HA_RAG_OK);
+            REQUIRE(ha_rag_register_disk(ctx, p, "/nonexistent/dry-run", (slot[p] + 4096) * 24) == HA_RAG_OK);
         }
-        REQUIRE(ha_rag_register_staging(ctx, (void *)0x300000000000ull, slot[0] * (2 + rnd() % 3)) == HA_RAG_OK);
+        REQUIRE(ha_rag_register_staging(ctx, (void *)0x300000000000ull, (slot[0] + 4096) * (2 + rnd() % 3)) == HA_RAG_OK);
+        REQUIRE(ha_rag_register_bounce(ctx, (void *)0x600000000000ull, (slot[0] + 8192) * (2 + rnd() % 2)) == HA_RAG_OK);
         std::vector<uint64_t> known;
         for (int op = 0; op < 400; ++op) {
             const uint64_t what = rnd() % 100;
             if (what < 25) {  // insert somewhere
                 const uint64_t id = rnd() % 40;
-                const uint32_t prec = rnd() % 3, tier = rnd() % 2;
+                const uint32_t prec = rnd() % HA_RAG_N_PREC, tier = rnd() % 4;
                 const uint32_t tok = 1 + rnd() % cfg.max_chunk_tokens;
                 int rc = ha_rag_pool_insert(ctx, id, prec, tok, nullptr, 0, tier, nullptr);
                 REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_EINVAL || rc == HA_RAG_ENOSPC || rc == HA_RAG_EFORMAT);
@@ -90,14 +97,14 @@ int main(int argc, char **argv)
                 REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOENT || rc == HA_RAG_ENOSPC);
                 if (rc == HA_RAG_OK) {
                     REQUIRE(st.n_chunks == ids.size());
-                    REQUIRE(st.n_hbm_hits + st.n_pinned_hits == st.n_chunks);
-                    REQUIRE(st.n_evicted <= st.n_promoted);
+                    REQUIRE(st.n_hbm_hits + st.n_pinned_hits + st.n_pageable_hits + st.n_disk_hits == st.n_chunks);
+                    REQUIRE(st.n_evicted <= st.n_promoted + st.n_placed_host);
                 }
             } else if (what < 82 && !known.empty()) {
                 int rc = ha_rag_pool_promote(ctx, known[rnd() % known.size()], nullptr);
                 REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOSPC || rc == HA_RAG_ENOENT);
             } else if (what < 88 && !known.empty()) {
-                int rc = ha_rag_pool_evict(ctx, known[rnd() % known.size()]);
+                int rc = ha_rag_pool_evict(ctx, known[rnd() % known.size()], (uint32_t)(rnd() % 3));
                 REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_EINVAL || rc == HA_RAG_ENOENT);
             } else if (what < 94) {
                 REQUIRE(ha_rag_rerank(ctx) == HA_RAG_OK);

@@ -27,13 +27,13 @@ def test_every_declared_symbol_is_exported():
 def test_strerror_and_version():
     assert B.version().startswith("ha_rag")
     assert B.strerror(B.OK) == "ok"
-    for code in (B.EINVAL, B.ENOENT, B.ENOSPC, B.EFORMAT, B.EHIP):
+    for code in (B.EINVAL, B.ENOENT, B.ENOSPC, B.EFORMAT, B.EHIP, B.EIO):
         assert B.strerror(code) and B.strerror(code) != "unknown error code"
 
 
 def test_struct_sizes_match_the_header_layout():
-    assert ctypes.sizeof(B.Config) == 40
+    assert ctypes.sizeof(B.Config) == 52
     assert ctypes.sizeof(B.PackedChunk) == 24
     assert ctypes.sizeof(B.ChunkTrace) == 24
-    assert ctypes.sizeof(B.LoadStats) == 8 * 4 + 5 * 8
-    assert ctypes.sizeof(B.ChunkInfo) == 6 * 4 + 2 * 8 + 2 * 8
+    assert ctypes.sizeof(B.LoadStats) == 12 * 4 + 7 * 8
+    assert ctypes.sizeof(B.ChunkInfo) == 8 * 4 + 2 * 8 + 2 * 8

@@ -497,6 +497,78 @@ def test_batch_of_requests_one_call():
     ctx.destroy()
 
 
+# ---- four tiers: HBM, pinned, pageable, files -----------------------------------------
+@pytest.mark.parametrize("o_direct", [False, True])
+def test_four_tier_placement_end_to_end(tmp_path, o_direct):
+    """Every chunk starts in a file.  Requests pull chunks through bounce buffers and the
+    staging ring; Algorithm 2 leaves copies in HBM / pinned / pageable memory according to
+    rank; whatever tier serves a chunk, the cache must equal the oracle's."""
+    L, H, D, T, g = 2, 2, 64, 128, 64
+    n = 12
+    precs_all = [B.PREC_INT4, B.PREC_FP8_E4M3]
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=170_000,
+                    tau_pin_ppm=170_000, tau_page_ppm=250_000, disk_o_direct=o_direct)
+    biggest = 0
+    for p in precs_all:
+        slot = (ctx.chunk_bytes(p, T) + 4095) // 4096 * 4096
+        biggest = max(biggest, slot)
+        ctx.register_slab(B.TIER_HBM, p, torch.zeros(slot * 1, dtype=torch.uint8, device="cuda"))
+        ctx.register_slab(B.TIER_PINNED, p, torch.zeros(slot * 1, dtype=torch.uint8).pin_memory())
+        ctx.register_slab(B.TIER_PAGEABLE, p, torch.zeros(slot * 2, dtype=torch.uint8))
+        try:
+            ctx.register_disk(p, str(tmp_path / f"pool_{p}.bin"), slot * n)
+        except B.HaRagError as e:
+            if o_direct and e.code == B.EIO:
+                pytest.skip("this filesystem refuses O_DIRECT")
+            raise
+    ctx.register_staging(torch.zeros(biggest * 2, dtype=torch.uint8, device="cuda"))
+    ctx.register_bounce(torch.zeros(biggest * 2, dtype=torch.uint8).pin_memory())
+    tokens = [T - 7 * (i % 3) for i in range(n)]
+    precs = [precs_all[i % 2] for i in range(n)]
+    srcs = [wl.kv_chunk(L, H, D, tokens[i], 1200 + i) for i in range(n)]
+    packed = [codec.quantize_pack_chunk(s_, ORC[p], g)[0] for s_, p in zip(srcs, precs)]
+    for i in range(n):
+        if i % 3 == 0:      # device bytes -> file (through a bounce buffer)
+            ctx.pool_insert(i, precs[i], tokens[i], dev_u8(packed[i]), B.TIER_DISK, packed_is_device=True)
+        else:               # host bytes -> file
+            ctx.pool_insert(i, precs[i], tokens[i], packed[i], B.TIER_DISK)
+    ctx.set_counts(list(range(n)), [100 - i for i in range(n)])
+    ctx.rerank()            # lists: GPU {0,1}, PIN {2,3}, PAGE {4,5,6}, DISK the rest
+
+    def run(req):
+        total = sum(tokens[c] for c in req)
+        out = torch.full((L, 2, H, total + 2, D), CANARY, dtype=torch.int16, device="cuda")
+        st, tr = ctx.load_chunks(req, out, total + 2, tok_base=1, want_trace=True)
+        torch.cuda.synchronize()
+        ref = np.full((L, 2, H, total + 2, D), CANARY, np.uint16)
+        codec.load_chunks(packed, (L, H, D), tokens, [ORC[p] for p in precs], [g] * n, req,
+                          cap_tokens=total + 2, tok_base=1, out=ref)
+        assert np.array_equal(host_u16(out), ref), req
+        return st, tr
+
+    st, tr = run([0, 2, 4, 9, 1, 3, 5, 6])
+    assert [t.found_tier for t in tr] == [3] * 8
+    assert [t.placed_tier for t in tr] == [0, 1, 2, 255, 0, 1, 2, 2]
+    assert st["bytes_disk_read"] == sum(len(packed[c]) for c in [0, 2, 4, 9, 1, 3, 5, 6])
+    # now served from where Algorithm 2 left them (one slot per tag in HBM / pinned, two in pageable)
+    st, tr = run([0, 1, 2, 3, 4, 5, 6, 9, 0])
+    assert [t.found_tier for t in tr] == [0, 0, 1, 1, 2, 2, 2, 3, 0]
+    assert st["n_disk_hits"] == 1 and st["n_pageable_hits"] == 3
+    # 8 and 10 are int4, 7 is e4m3: give 10 a GPU rank -> it evicts 0 from HBM (same tag slab)
+    ctx.set_counts([10], [1000])
+    ctx.rerank()
+    st, tr = run([10, 7, 0, 10])
+    assert tr[0].found_tier == 3 and tr[0].placed_tier == 0 and tr[0].evicted_id == 0
+    assert tr[2].found_tier == 3                              # 0 lost its only fast copy
+    assert tr[3].found_tier == 0
+    # pageable insert from the host and from the device, then load
+    ctx.pool_evict(4, B.TIER_PAGEABLE)
+    ctx.pool_insert(4, precs[4], tokens[4], packed[4], B.TIER_PAGEABLE)
+    st, tr = run([4, 11, 8])
+    assert tr[0].found_tier == 2
+    ctx.destroy()
+
+
 # ---- the benchmark's own shapes and launch configuration ----------------------------
 def _check_sampled_tiles(ctx, shape, T, g, precs, order, srcs, packs, out, n_samples, rng):
     """K/V tile pairs sampled across the chunks of a request are recomputed by the oracle from

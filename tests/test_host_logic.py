@@ -298,3 +298,106 @@ def test_limits_are_rejected_not_wrapped():
     assert e.value.code == B.EINVAL
     st, _ = ctx.load_chunks([], FAKE_HBM, 0)              # an empty request is legal
     assert st["n_chunks"] == 0 and st["n_kernel_launches"] == 0
+
+
+# ---- four tiers (Algorithm 2 in full) -------------------------------------------------
+FAKE_PAGE = 0x7C0000000000
+FAKE_BNC = 0x7B0000000000
+
+
+def _ctx4(n, caps, taus, prec=B.PREC_INT4, T=128, rerank_interval=0):
+    """Every chunk lives on disk; HBM / pinned / pageable hold caps[0..2] chunks."""
+    ctx = B.Context(2, 2, 64, T, group_int8=64, group_int4=64, tau_gpu_ppm=taus[0],
+                    tau_pin_ppm=taus[1], tau_page_ppm=taus[2], rerank_interval=rerank_interval,
+                    dry_run=True)
+    slot = (ctx.chunk_bytes(prec, T) + 255) // 256 * 256
+    dslot = (ctx.chunk_bytes(prec, T) + 4095) // 4096 * 4096
+    for tier, base, cap in ((B.TIER_HBM, FAKE_HBM, caps[0]), (B.TIER_PINNED, FAKE_PIN, caps[1]),
+                            (B.TIER_PAGEABLE, FAKE_PAGE, caps[2])):
+        if cap:
+            ctx.register_slab(tier, prec, base, slot * cap)
+    ctx.register_disk(prec, "/nonexistent/never-opened-in-dry-run", dslot * n)
+    ctx.register_staging(FAKE_STG, dslot * 3)
+    ctx.register_bounce(FAKE_BNC, dslot * 2)
+    for c in range(n):
+        ctx.pool_insert(c, prec, T, None, B.TIER_DISK)
+    return ctx
+
+
+def test_alg2_four_tier_trace_equals_oracle(golden_dir):
+    import json
+    import os
+    gold = json.load(open(os.path.join(golden_dir, "paper_values.json")))["alg2_thresholds_percent"]
+    taus = [gold["tau_gpu"] * 10_000, gold["tau_pin"] * 10_000, gold["tau_page"] * 10_000]
+    n, caps = 100, (3, 4, 6)                    # lists of 5 / 5 / 10 chunks, smaller queues
+    ctx = _ctx4(n, caps, taus)
+    ctx.set_counts(list(range(n)), [1000 - c for c in range(n)])     # rank == id
+    ctx.rerank()
+    sim = pl.TierSim(list(range(n)), taus, caps)
+    assert sim.bounds == (5, 10, 20)
+    rng = np.random.default_rng(5)
+    hot = rng.integers(0, 25, 600)
+    cold = rng.integers(0, n, 600)
+    seq = np.where(rng.random(600) < 0.8, hot, cold).tolist()
+    tiers = (B.TIER_HBM, B.TIER_PINNED, B.TIER_PAGEABLE)
+    seen = set()
+    for c in seq:
+        st, tr = ctx.load_chunks([c], FAKE_HBM, 128, want_trace=True)
+        found, placed = sim.access(c)
+        assert tr[0].found_tier == found, (c, tr[0].found_tier, found)
+        if placed:
+            assert tr[0].placed_tier == placed[0][0]
+            assert tr[0].evicted_id == (placed[0][1] if placed[0][1] is not None else B.NO_CHUNK)
+        else:
+            assert tr[0].placed_tier == B.TIER_NONE and tr[0].evicted_id == B.NO_CHUNK
+        for t in tiers:
+            assert ctx.pool_lru(t) == sim.resident(t), (c, t)
+        seen.add((found, placed[0][0] if placed else None))
+        assert st["n_hbm_hits"] + st["n_pinned_hits"] + st["n_pageable_hits"] + st["n_disk_hits"] == 1
+    # the sequence exercised every branch of the lookup cascade
+    assert {(3, 0), (3, 1), (3, 2), (3, None), (0, None), (1, None), (2, None)} <= seen
+    q = ctx.pool_query(0)
+    assert q.on_disk == 1 and q.count == 1000 + seq.count(0)
+
+
+def test_four_tier_multi_chunk_request_and_stats():
+    n = 40
+    ctx = _ctx4(n, (4, 4, 8), [100_000, 100_000, 200_000])    # lists: 4 / 4 / 8 chunks
+    ctx.set_counts(list(range(n)), [1000 - c for c in range(n)])
+    ctx.rerank()
+    req = [0, 5, 9, 30, 1, 5, 0]
+    st, tr = ctx.load_chunks(req, FAKE_HBM, 7 * 128, want_trace=True)
+    assert [t.found_tier for t in tr] == [3, 3, 3, 3, 3, 1, 0]      # repeats find the new copies
+    assert [t.placed_tier for t in tr] == [0, 1, 2, 255, 0, 255, 255]
+    cb = ctx.chunk_bytes(B.PREC_INT4, 128)
+    assert st["n_disk_hits"] == 5 and st["n_pinned_hits"] == 1 and st["n_hbm_hits"] == 1
+    assert st["n_promoted"] == 2 and st["n_placed_host"] == 2
+    assert st["bytes_disk_read"] == 5 * cb and st["bytes_h2d"] == 6 * cb
+    assert st["bytes_host_copied"] == 2 * cb and st["bytes_d2d"] == 2 * cb
+    # kernels: none for early hits, six cold chunks one by one, one for the late HBM hit
+    assert st["n_kernel_launches"] == 7
+    assert ctx.pool_lru(B.TIER_HBM) == [1, 0] and ctx.pool_lru(B.TIER_PINNED) == [5]
+    assert ctx.pool_lru(B.TIER_PAGEABLE) == [9]
+    # eviction by hand: only copies that have a slower copy can go
+    ctx.pool_evict(5, B.TIER_PINNED)
+    with pytest.raises(B.HaRagError) as e:
+        ctx.pool_evict(5, B.TIER_PINNED)
+    assert e.value.code == B.ENOENT
+    assert ctx.pool_query(5).in_pinned == 0 and ctx.pool_query(5).on_disk == 1
+
+
+def test_slow_tiers_need_bounce_buffers():
+    ctx = B.Context(2, 2, 64, 128, group_int8=64, group_int4=64, dry_run=True)
+    slot = (ctx.chunk_bytes(B.PREC_INT4, 128) + 4095) // 4096 * 4096
+    ctx.register_slab(B.TIER_PAGEABLE, B.PREC_INT4, FAKE_PAGE, slot * 4)
+    ctx.register_staging(FAKE_STG, slot * 2)
+    ctx.pool_insert(1, B.PREC_INT4, 128, None, B.TIER_PAGEABLE)
+    with pytest.raises(B.HaRagError) as e:
+        ctx.load_chunks([1], FAKE_HBM, 128)
+    assert e.value.code == B.ENOSPC                   # no bounce buffers registered
+    with pytest.raises(B.HaRagError) as e:
+        ctx.register_bounce(FAKE_BNC + 8, slot * 2)   # not 4096-byte aligned
+    assert e.value.code == B.EINVAL
+    ctx.register_bounce(FAKE_BNC, slot * 2)
+    st, _ = ctx.load_chunks([1], FAKE_HBM, 128)
+    assert st["n_pageable_hits"] == 1 and st["bytes_host_copied"] == ctx.chunk_bytes(B.PREC_INT4, 128)
