@@ -330,8 +330,9 @@ int ha_rag_get_rank(ha_rag_ctx *ctx, uint64_t id, uint32_t *rank);
  *   stats, trace  nullable host outputs (trace has n entries)
  * All checks (ENOENT, EFORMAT, ENOSPC for the cache, staging or bounce buffers
  * missing for a chunk that needs them) happen before any state changes or work is
- * enqueued; EIO can occur midway (a file read failed): work enqueued so far stays
- * valid, the bookkeeping of the call is kept.  A slot
+ * enqueued; EIO / EHIP can occur midway (a file read failed): chunks enqueued so
+ * far are still loaded, access counts and evictions of the call stand, and copies
+ * the call had booked but not yet written are taken out of the books again.  A slot
  * that another stream's load may still read is not overwritten before that load
  * has finished (the library records an event per stream after each load). */
 int ha_rag_load_chunks(ha_rag_ctx *ctx, const uint64_t *ids, const uint8_t *tags, uint32_t n,

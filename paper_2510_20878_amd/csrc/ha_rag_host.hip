@@ -617,6 +617,24 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     const size_t n_stg = c->stg.size();
     std::vector<size_t> cold_slot(cold.size());
 
+    // If a HIP or file call fails midway, copies that pass A booked but that were never
+    // written must not stay in the books.
+    struct Undo {
+        ha_rag_ctx *c;
+        std::vector<Action> &acts;
+        std::vector<uint8_t> written;  // per action: its placed copy has been written / enqueued
+        bool ok = false;
+        ~Undo()
+        {
+            if (ok) return;
+            for (size_t k = 0; k < acts.size(); ++k) {
+                const Action &a = acts[k];
+                if (a.place_tier == HA_RAG_TIER_NONE || written[k]) continue;
+                if (c->chunks[a.ci].slot[a.place_tier] == a.place_slot) tier_detach(c, a.place_tier, a.ci);
+            }
+        }
+    } undo{c, acts, std::vector<uint8_t>(acts.size(), 0)};
+
     auto start_transfer = [&](size_t k) -> int {
         const Action &a = acts[cold[k]];
         const Chunk &ch = c->chunks[a.ci];
@@ -637,6 +655,7 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
                 rc = before_host_write(c, ds.use[a.place_slot]);
                 if (rc) return rc;
                 if (!c->dry()) std::memcpy(ds.ptr(a.place_slot), bp, ch.bytes);
+                undo.written[cold[k]] = 1;
             }
             src = bp;
         }
@@ -650,8 +669,8 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
                 int rc = wait_for(c, cs, u.writer);
                 if (rc) return rc;
             }
-            u.read_events.push_back(ss.filled);
-            if (u.read_events.size() > 8) u.read_events.erase(u.read_events.begin());
+            if (std::find(u.read_events.begin(), u.read_events.end(), ss.filled) == u.read_events.end())
+                u.read_events.push_back(ss.filled);  // at most one per staging slot
         }
         HIPCHK(c, hipMemcpyAsync(c->staging + sidx * c->staging_slot_bytes, src, ch.bytes,
                                  hipMemcpyHostToDevice, cs));
@@ -701,6 +720,7 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
             if (!c->dry())
                 HIPCHK(c, hipMemcpyAsync(hs.ptr(a.place_slot), sp, ch.bytes,
                                          hipMemcpyDeviceToDevice, s));
+            undo.written[cold[k]] = 1;
         }
         if (!c->dry()) {
             HIPCHK(c, hipEventRecord(c->stg[sidx].consumed, s));
@@ -728,6 +748,7 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     if (rc) return rc;
     rc = mark_stream(c, s);
     if (rc) return rc;
+    undo.ok = true;
     if (stats) *stats = st;
     return HA_RAG_OK;
 }

@@ -569,6 +569,41 @@ def test_four_tier_placement_end_to_end(tmp_path, o_direct):
     ctx.destroy()
 
 
+def test_file_read_failure_is_reported_and_rolled_back(tmp_path):
+    L, H, D, T, g = 1, 2, 64, 64, 64
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=1_000_000)
+    p = B.PREC_INT8
+    slot = (ctx.chunk_bytes(p, T) + 4095) // 4096 * 4096
+    ctx.register_slab(B.TIER_HBM, p, torch.zeros(slot * 4, dtype=torch.uint8, device="cuda"))
+    path = tmp_path / "pool.bin"
+    ctx.register_disk(p, str(path), slot * 4)
+    ctx.register_staging(torch.zeros(slot * 2, dtype=torch.uint8, device="cuda"))
+    ctx.register_bounce(torch.zeros(slot * 2, dtype=torch.uint8).pin_memory())
+    srcs = [wl.kv_chunk(L, H, D, T, 1300 + i) for i in range(3)]
+    packed = [codec.quantize_pack_chunk(s_, 8, g)[0] for s_ in srcs]
+    for i in range(3):
+        ctx.pool_insert(i, p, T, packed[i], B.TIER_DISK)
+    ctx.rerank()                                       # everything belongs to GPU_LIST
+    out = torch.zeros((L, 2, H, 3 * T, D), dtype=torch.int16, device="cuda")
+    st, _ = ctx.load_chunks([0], out, 3 * T)
+    assert st["n_promoted"] == 1 and ctx.pool_query(0).in_hbm == 1
+    with open(path, "r+b") as f:                       # the pool file loses chunks 1 and 2
+        f.truncate(slot)
+    with pytest.raises(B.HaRagError) as e:
+        ctx.load_chunks([0, 1, 2], out, 3 * T)
+    assert e.value.code == B.EIO and "pread" in str(e.value)
+    torch.cuda.synchronize()
+    assert ctx.pool_query(1).in_hbm == 0 and ctx.pool_query(2).in_hbm == 0   # booked copies undone
+    assert ctx.pool_query(1).count == 1                # the access itself was counted
+    # the context keeps working: chunk 0 is still served from HBM, correctly
+    out.fill_(0)
+    st, _ = ctx.load_chunks([0], out, 3 * T)
+    torch.cuda.synchronize()
+    ref, _ = codec.load_chunks(packed, (L, H, D), [T] * 3, [8] * 3, [g] * 3, [0], cap_tokens=3 * T)
+    assert st["n_hbm_hits"] == 1 and np.array_equal(host_u16(out), ref)
+    ctx.destroy()
+
+
 # ---- the benchmark's own shapes and launch configuration ----------------------------
 def _check_sampled_tiles(ctx, shape, T, g, precs, order, srcs, packs, out, n_samples, rng):
     """K/V tile pairs sampled across the chunks of a request are recomputed by the oracle from
