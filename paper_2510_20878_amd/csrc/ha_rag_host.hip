@@ -11,6 +11,7 @@
 
 #include <algorithm>
 #include <cerrno>
+#include <condition_variable>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -18,6 +19,7 @@
 #include <mutex>
 #include <new>
 #include <string>
+#include <thread>
 #include <unordered_map>
 #include <vector>
 
@@ -156,6 +158,7 @@ struct ha_rag_ctx {
     size_t bounce_slot_bytes = 0;
     uint8_t *dio = nullptr;     // page-aligned ordinary memory for O_DIRECT transfers: the
                                 // kernel cannot do direct I/O on GPU-pinned host memory
+    size_t dio_bytes = 0;
     std::vector<BounceSlot> bnc;
     uint64_t bnc_next = 0;
 
@@ -472,6 +475,81 @@ int acquire_bounce(ha_rag_ctx *c, size_t *idx)
     return HA_RAG_OK;
 }
 
+// O_DIRECT read of `bytes` at `off` into `dst` (GPU-pinned memory, which direct I/O cannot
+// target): a helper thread reads pieces into the two halves of the page-aligned buffer
+// c->dio while this thread copies the previous piece to dst, so the file read and the
+// host copy overlap.
+int read_direct(ha_rag_ctx *c, int fd, uint8_t *dst, size_t bytes, off_t off)
+{
+    const size_t half = c->dio_bytes / 2 / kDirectAlign * kDirectAlign;
+    const size_t total = c->io_bytes(bytes);
+    if (half == 0 || total <= half) {  // small: one read, one copy
+        int rc = read_full(c, fd, c->dio, total, off);
+        if (rc) return rc;
+        std::memcpy(dst, c->dio, bytes);
+        return HA_RAG_OK;
+    }
+    const size_t piece = std::min<size_t>(half, 4u << 20);
+    const size_t n_pieces = (total + piece - 1) / piece;
+    std::mutex mu;
+    std::condition_variable cv;
+    size_t produced = 0, consumed = 0;  // pieces read / pieces copied out
+    int rc_reader = HA_RAG_OK;
+    std::string err_reader;
+    std::thread reader([&] {
+        for (size_t i = 0; i < n_pieces; ++i) {
+            {
+                std::unique_lock<std::mutex> lk(mu);
+                cv.wait(lk, [&] { return i < consumed + 2; });  // a free half
+            }
+            const size_t n = std::min(piece, total - i * piece);
+            uint8_t *buf = c->dio + (i & 1) * half;
+            size_t done = 0;
+            int rc = HA_RAG_OK;
+            while (done < n) {
+                const ssize_t r = pread(fd, buf + done, n - done, off + (off_t)(i * piece + done));
+                if (r < 0 && errno == EINTR) continue;
+                if (r <= 0) {
+                    err_reader = r < 0 ? std::string("pread: ") + std::strerror(errno)
+                                       : std::string("pread: unexpected end of file");
+                    rc = HA_RAG_EIO;
+                    break;
+                }
+                done += (size_t)r;
+            }
+            std::lock_guard<std::mutex> lk(mu);
+            if (rc) rc_reader = rc;
+            produced = i + 1;
+            cv.notify_all();
+            if (rc) return;
+        }
+    });
+    int rc = HA_RAG_OK;
+    for (size_t i = 0; i < n_pieces; ++i) {
+        {
+            std::unique_lock<std::mutex> lk(mu);
+            cv.wait(lk, [&] { return produced > i || rc_reader; });
+            if (rc_reader) {
+                rc = rc_reader;
+                break;
+            }
+        }
+        const size_t lo = i * piece;
+        if (lo < bytes) std::memcpy(dst + lo, c->dio + (i & 1) * half, std::min(piece, bytes - lo));
+        std::lock_guard<std::mutex> lk(mu);
+        consumed = i + 1;
+        cv.notify_all();
+    }
+    {
+        std::lock_guard<std::mutex> lk(mu);
+        consumed = n_pieces + 2;  // lets a reader that is still waiting run to its end
+        cv.notify_all();
+    }
+    reader.join();
+    if (rc) c->err = err_reader;
+    return rc;
+}
+
 // Packed bytes of a chunk from its pageable or disk copy into a bounce buffer (host work,
 // synchronous).
 int fill_bounce(ha_rag_ctx *c, const Chunk &ch, uint32_t tier, int32_t slot, uint8_t *dst)
@@ -483,10 +561,7 @@ int fill_bounce(ha_rag_ctx *c, const Chunk &ch, uint32_t tier, int32_t slot, uin
         return HA_RAG_OK;
     }
     if (!c->direct()) return read_full(c, sl.fd, dst, ch.bytes, sl.offset(slot));
-    int rc = read_full(c, sl.fd, c->dio, c->io_bytes(ch.bytes), sl.offset(slot));
-    if (rc) return rc;
-    std::memcpy(dst, c->dio, ch.bytes);
-    return HA_RAG_OK;
+    return read_direct(c, sl.fd, dst, ch.bytes, sl.offset(slot));
 }
 
 int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Request *reqs,
@@ -1037,6 +1112,7 @@ int ha_rag_register_bounce(ha_rag_ctx *c, void *base, size_t bytes)
         void *p = nullptr;
         if (posix_memalign(&p, kDirectAlign, slot) != 0) return HA_RAG_ENOSPC;
         c->dio = static_cast<uint8_t *>(p);
+        c->dio_bytes = slot;
     }
     c->bnc.resize(n);
     if (!c->dry())
