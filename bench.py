@@ -27,8 +27,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the gather-dequantize-scatter kernel on the hbm8b workload, from
-# rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size
-# (profiles/k1_gather_dequant_scatter_hbm8b.md): 1.015 x the algorithmic bytes.
+# rocprofv3 FETCH_SIZE / WRITE_SIZE runs (one counter per run) scaled by an elementwise
+# kernel of known size (--calibrate): 1.015 x the algorithmic bytes.
 MEASURED_TRAFFIC = {"hbm8b": 1_013_000_000}
 PCIE_PEAK_GBPS = 63.0           # PCIe Gen5 x16, one direction, theoretical
 
@@ -490,7 +490,7 @@ def main():
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch a plain elementwise kernel of known size (for counter runs)")
     ap.add_argument("--traffic-bytes", type=float, default=None,
-                    help="HBM bytes per launch from rocprofv3 counters (see profiles/), if known")
+                    help="HBM bytes per launch from rocprofv3 counters, if known")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); "

@@ -13,12 +13,12 @@
  * compresses each chunk, as a whole, to a precision chosen from its access
  * frequency rank (Algorithm 1).  For its integer scheme it gives the code
  * range only (Sec. 2.2.2); it defines no scale, zero point, group or byte
- * layout.  The readings used here (unsigned codes, asymmetric, one fp16 scale
- * and one fp16 zero per group of g consecutive head_dim elements, directed
- * rounding of scale and zero, round-half-even codes, the block-permuted byte
- * layout) are this build's and are listed in the design notes of the
- * repository.  Because the encoding is lossy, the oracle is the algorithm taken
- * step by step; it is pinned by the tests in tests/test_oracle_*.py against
+ * layout.  The readings used here are this build's own and are stated where they
+ * are applied below: unsigned codes, asymmetric, one fp16 scale and one fp16 zero
+ * per group of g consecutive head_dim elements, directed rounding of scale and
+ * zero, round-half-even codes, the block-permuted byte layout; for the paper's
+ * FP8 and GSE-8 schemes see their sections.  Because the encoding is lossy, the
+ * oracle is the algorithm taken step by step; every function is pinned by the tests in tests/test_oracle_*.py against
  * closed forms, invariants, exhaustive enumeration and library conversions.
  *
  * Arithmetic: the decision of a code is taken in IEEE binary32 (subtract,
