@@ -351,11 +351,9 @@ uint16_t orc_dequant_bf16(unsigned code, uint16_t scale_h, uint16_t zero_h)
  * (element index e = t*D + d).  A tile is cut into blocks of 2048 elements;
  * the last block is padded with zero bytes.  Inside a block, element r is
  *   plane j = r / 512, lane i = (r % 512) / 8, position p = r % 8,
- * and the 8 elements sharing (j, i) form an octet of `bits` bytes.  A lane's
- * octets are stored in words of P octets (P = 1 for 16-bit elements, else 2; a
- * word is W = P*bits bytes: 16, 16 or 8), 64 words to a run: octet (j, i) starts
- * at byte
- *   (j / P) * 64 * W + i * W + (j % P) * bits
+ * and the 8 elements sharing (j, i) form an octet of `bits` bytes.  With
+ * P = 16/bits octets per 16-byte word, octet (j, i) starts at byte
+ *   (j / P) * 1024 + i * 16 + (j % P) * bits
  * of the block's payload (256*bits bytes).  Inside the octet: 16-bit elements
  * are little-endian words in order; 8-bit codes one per byte; 4-bit codes two
  * per byte, even position in the low nibble.
@@ -411,9 +409,8 @@ static size_t octet_offset(size_t e, int bits)
 {
     size_t k = e / ORC_BLOCK, r = e % ORC_BLOCK;
     size_t j = r / 512, i = (r % 512) / 8;
-    size_t P = bits == 16 ? 1 : 2;
-    size_t W = P * (size_t)bits;
-    return k * 256u * (size_t)bits + (j / P) * 64u * W + i * W + (j % P) * (size_t)bits;
+    size_t P = 16 / (size_t)bits;
+    return k * 256u * (size_t)bits + (j / P) * 1024u + i * 16u + (j % P) * (size_t)bits;
 }
 
 /* byte offset, inside the tile's meta area, of the entry of element e's group */

@@ -65,10 +65,10 @@ def test_ragged_tile_is_padded_to_whole_blocks():
     packed, _ = codec.quantize_pack_chunk(src, 4, 64)
     tile = packed.reshape(8, 4096 + 512)
     used = 6400 - 3 * 2048                                     # elements in the last block: 256
-    last = tile[:, 3 * 1024:4 * 1024].reshape(8, 2, 64, 8)     # [run][lane][8 bytes = 2 planes x 4 B]
+    last = tile[:, 3 * 1024:4 * 1024].reshape(8, 64, 16)       # [lane][16 bytes = 4 planes x 4 B]
     # plane 0 holds elements 0..511 of the block: lanes 0..31 used, the rest and planes 1..3 zero
     assert used == 256
-    assert not last[:, 1].any() and not last[:, 0, 32:, :].any() and not last[:, 0, :, 4:].any()
+    assert not last[:, 32:, :].any() and not last[:, :, 4:].any()
     meta_last = tile[:, 4096 + 3 * 128:].reshape(8, 8, 4, 4)    # [rho][plane][4 bytes]
     assert not meta_last[:, :, 1:, :].any() and not meta_last[:, 4:, 0, :].any()
     out = np.zeros((2, 2, 2, 100, 64), np.uint16)
@@ -81,9 +81,8 @@ def test_ragged_tile_is_padded_to_whole_blocks():
 def _octet_offset(e, bits):
     k, r = divmod(e, 2048)
     j, i = r // 512, (r % 512) // 8
-    P = 1 if bits == 16 else 2             # octets per word
-    W = P * bits                           # bytes per word: 16, 16, 8
-    return k * 256 * bits + (j // P) * 64 * W + i * W + (j % P) * bits
+    P = 16 // bits
+    return k * 256 * bits + (j // P) * 1024 + i * 16 + (j % P) * bits
 
 
 @pytest.mark.parametrize("bits", [4, 8, 16])
@@ -122,12 +121,11 @@ def _coded_chunk(bits, g, T, D, rng):
 @pytest.mark.parametrize("bits,g,D", [(4, 64, 64), (4, 128, 128), (8, 64, 128), (8, 32, 64),
                                       (8, 256, 256), (4, 32, 96)])
 def test_wave_view_consecutive_words_give_consecutive_stores(bits, g, D):
-    """Simulate what the layout is for.  Lane i of a 64-lane wave reads word i (two
-    octets: 16 bytes for int8, 8 bytes for int4) of each run of 64 words of a block;
-    octet number w of what the lane has read so far belongs to plane j = w, whose
-    16-byte store goes to byte j*1024 + i*16 of the block's 4096 output bytes.  The
-    scale/zero the lane needs for plane j is entry j of the 16-byte meta word number
-    (8*i) // g."""
+    """Simulate what the layout is for.  Lane i of a 64-lane wave reads 16-byte
+    word i of each 1024-byte slab of a block; octet number w of what the lane has
+    read so far belongs to plane j = w, whose 16-byte store goes to byte
+    j*1024 + i*16 of the block's 4096 output bytes.  The scale/zero the lane needs
+    for plane j is entry j of the 16-byte meta word number (8*i) // g."""
     rng = np.random.default_rng(bits * 100 + g)
     T = 48 if D != 96 else 64
     vals = _coded_chunk(bits, g, T, D, rng)
@@ -140,7 +138,7 @@ def test_wave_view_consecutive_words_give_consecutive_stores(bits, g, D):
     n_e = T * D
     nblk = -(-n_e // 2048)
     pay, met = nblk * 256 * bits, nblk * (2048 // g) * 4
-    P, W = 2, 2 * bits
+    P = 16 // bits
     for tile in range(2):
         rec = packed[tile * (pay + met):(tile + 1) * (pay + met)]
         out = np.zeros(nblk * 2048, np.float32)
@@ -149,8 +147,8 @@ def test_wave_view_consecutive_words_give_consecutive_stores(bits, g, D):
             mblk = rec[pay + k * (2048 // g) * 4: pay + (k + 1) * (2048 // g) * 4]
             for i in range(64):
                 mword = mblk[((8 * i) // g) * 16:((8 * i) // g) * 16 + 16] if g <= 512 else None
-                for a in range(4 // P):                       # word loads of this lane
-                    word = blk[a * 64 * W + i * W: a * 64 * W + i * W + W]
+                for a in range(4 // P):                       # 16-byte loads of this lane
+                    word = blk[a * 1024 + i * 16: a * 1024 + i * 16 + 16]
                     for w in range(P):
                         j = a * P + w
                         octet = word[w * bits:(w + 1) * bits]
@@ -188,13 +186,12 @@ def test_pack_unpack_every_byte_value_and_nibble_position():
     for pos in range(32):
         v4 = np.zeros((1, 2, 1, 16, 128), np.float32)
         v4[..., 1] = 15                                        # every group: min 0, max 15
-        # element whose code lands in nibble `pos` of lane 0's two words (planes 0,1 in the
-        # first run of 512 bytes, planes 2,3 in the second): plane pos//8, position pos%8
+        # element whose code lands in nibble `pos` of lane 0's word: plane pos//8, position pos%8
         e = (pos // 8) * 512 + pos % 8
         t, d = divmod(e, 128)
         if d != 1:
             v4[0, 0, 0, t, d] = 9
         packed, _ = codec.quantize_pack_chunk(wl.f32_to_bf16_words(v4), 4, 128)
-        word = np.concatenate([packed[:8], packed[512:520]])
+        word = packed[:16]
         nib = (word[pos // 2] >> (4 * (pos % 2))) & 15
         assert nib == (15 if d == 1 else 9), pos
