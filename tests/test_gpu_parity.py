@@ -716,3 +716,44 @@ def test_cold_stress_shape_through_the_pool():
         _check_sampled_tiles(ctx, (L, H, D), T, g, [B.PREC_INT4] * n, orders[r], srcs, packs,
                              outs[r], 2, np.random.default_rng(2 + r))
     ctx.destroy()
+
+
+def test_mixed_tier_batch_at_the_8b_shape_sampled_tiles_match_oracle():
+    """The Zipf batch workload in small: 4 requests x 8 chunks of the 8B shape in one
+    ha_rag_load_batch call, chunks split between the HBM pool and pinned memory, tags by
+    rank class, promotion on; tiles sampled from every request are recomputed by the oracle."""
+    L, H, D, T, g = 32, 8, 128, 512, 128
+    n = 16
+    precs = [B.PREC_16] * 3 + [B.PREC_INT8] * 5 + [B.PREC_INT4] * 8
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=500_000)
+    keep = []
+    for p in (B.PREC_16, B.PREC_INT8, B.PREC_INT4):
+        slot = (ctx.chunk_bytes(p, T) + 255) // 256 * 256
+        ctx.register_slab(B.TIER_HBM, p, torch.empty(slot * 4, dtype=torch.uint8, device="cuda"))
+        ctx.register_slab(B.TIER_PINNED, p, torch.empty(slot * precs.count(p), dtype=torch.uint8,
+                                                        pin_memory=True))
+    ctx.register_staging(torch.empty(((ctx.chunk_bytes(B.PREC_16, T) + 255) // 256 * 256) * 3,
+                                     dtype=torch.uint8, device="cuda"))
+    srcs, packs = [], []
+    for i, p in enumerate(precs):
+        s_ = wl.kv_chunk_device(L, H, D, T, 800 + i)
+        dst = torch.empty(ctx.chunk_bytes(p, T), dtype=torch.uint8, device="cuda")
+        ctx.quantize_chunk(s_, T, p, g, dst)
+        ctx.pool_insert(i, p, T, dst, B.TIER_PINNED, packed_is_device=True)
+        if i % 4 == 0:
+            ctx.pool_insert(i, p, T, dst, B.TIER_HBM, packed_is_device=True)
+        srcs.append(s_)
+        packs.append(dst)
+    torch.cuda.synchronize()
+    ctx.set_counts(list(range(n)), [100 - i for i in range(n)])
+    ctx.rerank()
+    rng = np.random.default_rng(7)
+    reqs = [rng.permutation(n)[:8].tolist() for _ in range(4)]
+    outs = [torch.empty((L, 2, H, 8 * T, D), dtype=torch.int16, device="cuda") for _ in reqs]
+    st, tr = ctx.load_batch(reqs, outs, [8 * T] * 4, want_trace=True)
+    torch.cuda.synchronize()
+    assert st["n_chunks"] == 32 and st["n_hbm_hits"] + st["n_pinned_hits"] == 32
+    assert st["n_promoted"] >= 1 and st["n_hbm_hits"] >= 4
+    for r, o in zip(reqs, outs):
+        _check_sampled_tiles(ctx, (L, H, D), T, g, precs, r, srcs, packs, o, 1, rng)
+    ctx.destroy()
