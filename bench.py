@@ -57,6 +57,29 @@ def prec_of(B, tag):
             "e5m2": B.PREC_FP8_E5M2, "gse8": B.PREC_GSE8}[tag]
 
 
+def pcie_link():
+    """Link speed / width of the AMD display-class PCI functions as sysfs reports them
+    (best effort; a virtual machine may not expose the physical link)."""
+    out = []
+    root = "/sys/bus/pci/devices"
+    try:
+        for dev in sorted(os.listdir(root)):
+            d = os.path.join(root, dev)
+            try:
+                if open(os.path.join(d, "vendor")).read().strip() != "0x1002":
+                    continue
+                if not open(os.path.join(d, "class")).read().strip().startswith(("0x03", "0x12")):
+                    continue
+                out.append({"device": dev,
+                            "speed": open(os.path.join(d, "current_link_speed")).read().strip(),
+                            "width": open(os.path.join(d, "current_link_width")).read().strip()})
+            except OSError:
+                continue
+    except OSError:
+        pass
+    return out
+
+
 def build_hbm_pool(B, wl, torch, ctx, shape, T, g, counts, seed0):
     """One slab per tag in HBM; every chunk drawn on the device and quantized by the
     library straight into its slot.  Returns {prec: [ids]}."""
@@ -231,6 +254,17 @@ def run_hbm(args, B, wl, torch, name):
     ev_ms = e0.elapsed_time(e1)
     ms_per_step = wall * 1e3 / args.steps
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    # a second, untimed-for-the-metric pass with an event pair around every launch
+    n_evt = min(args.steps, 100)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(n_evt)]
+    with torch.cuda.stream(stream):
+        for k in range(n_evt):
+            evs[k][0].record(stream)
+            ctx.load_chunks(reqs[args.warmup + k], outs[k % n_out], cap, stream=stream)
+            evs[k][1].record(stream)
+        torch.cuda.synchronize()
+    per = sorted(a.elapsed_time(b) for a, b in evs)
     k2 = time_quantize(B, wl, torch, ctx, shape, T, g, sorted(set(mix), key=str))
     kernel_ms = ev_ms / args.steps                # one kernel launch per step
     achieved = step_bytes / (kernel_ms * 1e-3) / 1e9
@@ -251,7 +285,8 @@ def run_hbm(args, B, wl, torch, name):
         "roofline": {"bound": "hbm", "kernel": "k1_gather_dequant_scatter", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": args.traffic_bytes or (None if args.mix else MEASURED_TRAFFIC.get(name)),
-                     "kernel_ms": kernel_ms,
+                     "kernel_ms": kernel_ms, "kernel_ms_median": per[len(per) // 2],
+                     "kernel_ms_best": per[0],
                      "algorithmic_bytes_per_launch": step_bytes},
     }
     return res, (shape, T, g, mix)
@@ -282,7 +317,7 @@ def run_cold(args, B, wl, torch):
     log(f"cold pool: {n_pool} chunks, {cb * n_pool / 2**30:.2f} GiB pinned, built in {time.time() - t0:.1f} s")
     cap = per_req * T
     outs = [torch.empty((L, 2, H, cap, D), dtype=torch.bfloat16, device="cuda") for _ in range(n_streams)]
-    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+    streams = [torch.cuda.Stream() for _ in range(max(1, args.cold_streams))]
 
     # bare pinned -> device copy rate of this machine, for reference
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -297,7 +332,8 @@ def run_cold(args, B, wl, torch):
 
     def step():
         for r in range(n_streams):
-            ctx.load_chunks(list(range(r * per_req, (r + 1) * per_req)), outs[r], cap, stream=streams[r])
+            ctx.load_chunks(list(range(r * per_req, (r + 1) * per_req)), outs[r], cap,
+                            stream=streams[r % len(streams)])
 
     steps, warmup = max(1, min(args.steps, 20)), max(1, min(args.warmup, 2))
     for _ in range(warmup):
@@ -306,6 +342,7 @@ def run_cold(args, B, wl, torch):
     t0 = time.perf_counter()
     for _ in range(steps):
         step()
+    host_enqueue = time.perf_counter() - t0      # all calls returned; the GPU is still working
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ctx.destroy()
@@ -320,11 +357,13 @@ def run_cold(args, B, wl, torch):
         "config": {"workload": "cold path: 4 concurrent requests x 32 int4/g64 chunks x 1024 tokens "
                                "(Llama-3-8B KV shape), all in pinned host memory",
                    "staging_slots": args.staging_slots, "copy_streams": args.copy_streams or 2,
-                   "link_bytes_per_step": link_bytes},
+                   "link_bytes_per_step": link_bytes,
+                   "host_enqueue_ms_per_step": host_enqueue * 1e3 / steps},
         "kv_tokens_per_s": tokens / (ms * 1e-3),
         "roofline": {"bound": "pcie", "achieved": link, "peak": PCIE_PEAK_GBPS, "unit": "GB/s",
                      "frac": link / PCIE_PEAK_GBPS, "bare_pinned_memcpy_gbps": bare,
-                     "frac_of_bare_memcpy": link / bare, "traffic": None},
+                     "frac_of_bare_memcpy": link / bare, "traffic": None,
+                     "pcie_link_sysfs": pcie_link()},
     }
 
 
@@ -522,10 +561,14 @@ def main():
     ap.add_argument("--nt-load", type=int, default=1)
     ap.add_argument("--staging-slots", type=int, default=8)
     ap.add_argument("--copy-streams", type=int, default=0)
+    ap.add_argument("--cold-streams", type=int, default=4,
+                    help="cold8b: caller streams the 4 concurrent requests are spread over")
     ap.add_argument("--tau-gpu-ppm", type=int, default=50_000, help="zipf: GPU_LIST fraction (ppm)")
     ap.add_argument("--o-direct", type=int, default=1, help="tiers: open pool files with O_DIRECT")
     ap.add_argument("--disk-dir", default="", help="tiers: directory for the pool files")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cold", action="store_true",
+                    help="hbm8b: skip the short pinned-host measurement appended to the line")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch a plain elementwise kernel of known size (for counter runs)")
@@ -559,6 +602,16 @@ def main():
         if args.pool_chunks == 0:
             args.pool_chunks = 2000 if args.workload == "hbm8b" else 400
         res, (shape, T, g, mix) = run_hbm(args, B, wl, torch, args.workload)
+    if args.workload == "hbm8b" and not args.no_cold:
+        # the same build's pinned-host path, so that the default line carries the PCIe figure too
+        torch.cuda.empty_cache()
+        a2 = argparse.Namespace(**vars(args))
+        a2.steps, a2.warmup = 5, 1
+        cold = run_cold(a2, B, wl, torch)
+        res["cold_path"] = {"workload": cold["config"]["workload"], "link_gbps": cold["value"],
+                            "ms_per_step": cold["ms_per_step"], "steps": cold["steps"],
+                            "kv_tokens_per_s": cold["kv_tokens_per_s"],
+                            "roofline": cold["roofline"]}
     res["paper_context"] = {
         "note": "context only, not a target: the paper reports end-to-end TTFT ratios, no GB/s",
         "ttft_speedup_vs_turborag": {"average": 2.10, "max": 10.49},
