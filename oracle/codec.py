@@ -68,6 +68,12 @@ def lib():
         L.orc_quantize_pack_chunk.argtypes = [u16p] + [C.c_int] * 6 + [u8p]
         L.orc_dequant_scatter_chunk.restype = C.c_int
         L.orc_dequant_scatter_chunk.argtypes = [u8p] + [C.c_int] * 6 + [u16p, C.c_size_t, C.c_size_t]
+        L.orc_quantize_pack_half.restype = C.c_long
+        L.orc_quantize_pack_half.argtypes = [u16p] + [C.c_int] * 6 + [u8p]
+        L.orc_half_bytes.restype = C.c_size_t
+        L.orc_half_bytes.argtypes = [C.c_int] * 6
+        L.orc_dequant_scatter_half.restype = C.c_int
+        L.orc_dequant_scatter_half.argtypes = [u8p] + [C.c_int] * 7 + [u16p, C.c_size_t, C.c_size_t]
         L.orc_unpack_chunk.restype = C.c_int
         L.orc_unpack_chunk.argtypes = [u8p] + [C.c_int] * 6 + [u8p, u16p, u16p, u16p]
         L.orc_rmse_bf16.restype = C.c_double
@@ -162,6 +168,11 @@ def chunk_bytes(L, H, D, T, bits, g=128):
     return lib().orc_chunk_bytes(L, H, D, T, bits, g)
 
 
+def half_bytes(L, H, D, T, bits, g=128):
+    """Bytes of a keys-only or values-only chunk."""
+    return lib().orc_half_bytes(L, H, D, T, bits, g)
+
+
 def tile_payload_bytes(T, D, bits):
     return lib().orc_tile_payload_bytes(T, D, bits)
 
@@ -192,6 +203,34 @@ def quantize_pack_chunk(src, bits, g=128):
     if r < 0:
         raise ValueError("bad shape/bits/group")
     return dst, int(r)
+
+
+def quantize_pack_half(src, bits, g=128):
+    """src: uint16 BF16 words of one half of a document's KV, shape [L][H][T][D]
+    (Algorithm 1 treats key chunks and value chunks as separate units)."""
+    src = _c(src, np.uint16)
+    L, H, T, D = src.shape
+    n = half_bytes(L, H, D, T, bits, g)
+    if n == 0 and T > 0:
+        raise ValueError("bad shape/bits/group")
+    dst = np.zeros(n, np.uint8)
+    r = lib().orc_quantize_pack_half(_p(src, C.c_uint16), L, H, D, T, bits, g, _p(dst, C.c_uint8))
+    if r < 0:
+        raise ValueError("bad shape/bits/group")
+    return dst, int(r)
+
+
+def dequant_scatter_half(packed, shape, T, bits, g, kv, out, tok_off):
+    """A keys-only (kv=0) or values-only (kv=1) chunk into plane kv of out [L][2][H][cap][D]."""
+    L, H, D = shape
+    assert out.dtype == np.uint16 and out.flags.c_contiguous
+    assert out.shape[0] == L and out.shape[1] == 2 and out.shape[2] == H and out.shape[4] == D
+    packed = _c(packed, np.uint8)
+    assert packed.size >= half_bytes(L, H, D, T, bits, g)
+    r = lib().orc_dequant_scatter_half(_p(packed, C.c_uint8), L, H, D, T, bits, g, kv,
+                                       _p(out, C.c_uint16), out.shape[3], tok_off)
+    if r != 0:
+        raise ValueError("bad shape, plane or not enough room in out")
 
 
 def dequant_scatter_chunk(packed, shape, T, bits, g, out, tok_off):
@@ -230,11 +269,18 @@ def unpack_chunk(packed, shape, T, bits, g=128):
 
 
 def load_chunks(packed_list, shape, tokens, bits_list, g_list, order, cap_tokens=None,
-                tok_base=0, out=None):
+                tok_base=0, out=None, parts=None):
     """The whole request: chunks gathered in `order`, dequantised and laid one
     after another along the token axis of one BF16 cache [L][2][H][cap][D]
-    (Sec. 2.1: load, decompress, concatenate).  Returns (out, tok_off list)."""
+    (Sec. 2.1: load, decompress, concatenate).  Returns (out, tok_off list).
+
+    parts[c] (optional) is 0 for a chunk holding keys and values, 1 keys only, 2 values
+    only: the key plane and the value plane then fill independently, each in list order,
+    and must end at the same length."""
     L, H, D = shape
+    if parts is not None:
+        return _load_parts(packed_list, shape, tokens, bits_list, g_list, order, cap_tokens,
+                           tok_base, out, parts)
     total = sum(tokens[c] for c in order)
     if cap_tokens is None:
         cap_tokens = tok_base + total
@@ -248,6 +294,37 @@ def load_chunks(packed_list, shape, tokens, bits_list, g_list, order, cap_tokens
         offs.append(off)
         dequant_scatter_chunk(packed_list[c], shape, tokens[c], bits_list[c], g_list[c], out, off)
         off += tokens[c]
+    return out, offs
+
+
+def _load_parts(packed_list, shape, tokens, bits_list, g_list, order, cap_tokens, tok_base,
+                out, parts):
+    L, H, D = shape
+    need = [sum(tokens[c] for c in order if parts[c] in (0, 1 + kv)) for kv in (0, 1)]
+    if need[0] != need[1]:
+        raise ValueError("key plane and value plane end at different lengths")
+    if cap_tokens is None:
+        cap_tokens = tok_base + need[0]
+    if tok_base + need[0] > cap_tokens:
+        raise ValueError("request does not fit in the cache")
+    if out is None:
+        out = np.zeros((L, 2, H, cap_tokens, D), np.uint16)
+    off = [tok_base, tok_base]
+    offs = []
+    for c in order:
+        if parts[c] == 0:
+            if off[0] != off[1]:
+                raise ValueError("a whole chunk needs both planes at the same length")
+            offs.append(off[0])
+            dequant_scatter_chunk(packed_list[c], shape, tokens[c], bits_list[c], g_list[c], out, off[0])
+            off[0] += tokens[c]
+            off[1] += tokens[c]
+        else:
+            kv = parts[c] - 1
+            offs.append(off[kv])
+            dequant_scatter_half(packed_list[c], shape, tokens[c], bits_list[c], g_list[c], kv,
+                                 out, off[kv])
+            off[kv] += tokens[c]
     return out, offs
 
 

@@ -447,17 +447,11 @@ static unsigned get_code(const uint8_t *payload, size_t e, int bits)
     return (p & 1) ? (unsigned)(o[p / 2] >> 4) : (unsigned)(o[p / 2] & 0x0Fu);
 }
 
-/*
- * Quantise and pack one chunk (Algorithm 1 step 3 for one chunk).
- *   src   BF16 words, [L][2][H][T][D] contiguous
- *   dst   orc_chunk_bytes() bytes, fully written (padding included)
- * Returns <0 on a bad shape, else the number of groups that saturated.
- */
-long orc_quantize_pack_chunk(const uint16_t *src, int L, int H, int D, int T,
-                             int bits, int g, uint8_t *dst)
+/* n_tiles tiles of [T][D] BF16 words -> n_tiles tile records, back to back */
+static long pack_tiles(const uint16_t *src, size_t n_tiles, int D, int T,
+                       int bits, int g, uint8_t *dst)
 {
     if (!valid_shape(D, bits, g) || T < 0) return -1;
-    const size_t n_tiles = (size_t)L * 2 * H;
     const size_t n_e = (size_t)T * D;
     const size_t pay = orc_tile_payload_bytes(T, D, bits);
     const size_t met = orc_tile_meta_bytes(T, D, bits, g);
@@ -506,26 +500,62 @@ long orc_quantize_pack_chunk(const uint16_t *src, int L, int H, int D, int T,
 }
 
 /*
+ * Quantise and pack one chunk (Algorithm 1 step 3 for one chunk).
+ *   src   BF16 words, [L][2][H][T][D] contiguous
+ *   dst   orc_chunk_bytes() bytes, fully written (padding included)
+ * Returns <0 on a bad shape, else the number of groups that saturated.
+ */
+long orc_quantize_pack_chunk(const uint16_t *src, int L, int H, int D, int T,
+                             int bits, int g, uint8_t *dst)
+{
+    return pack_tiles(src, (size_t)L * 2 * H, D, T, bits, g, dst);
+}
+
+/*
+ * The same for a chunk that holds only the keys or only the values of a
+ * document: Algorithm 1 takes the n key chunks and the n value chunks as 2n
+ * units, each with its own access frequency and so its own precision.
+ *   src   BF16 words, [L][H][T][D] contiguous (one half of the document's KV)
+ *   dst   orc_half_bytes() bytes: the tile records (l, h) in that order
+ */
+long orc_quantize_pack_half(const uint16_t *src, int L, int H, int D, int T,
+                            int bits, int g, uint8_t *dst)
+{
+    return pack_tiles(src, (size_t)L * H, D, T, bits, g, dst);
+}
+
+size_t orc_half_bytes(int L, int H, int D, int T, int bits, int g)
+{
+    if (!valid_shape(D, bits, g) || T < 0) return 0;
+    return (size_t)L * H *
+           (orc_tile_payload_bytes(T, D, bits) + orc_tile_meta_bytes(T, D, bits, g));
+}
+
+/*
  * Dequantise one packed chunk and scatter it into the request's KV cache
  * (the "load + decompress + concatenate" step of Sec. 2.1).
  *   out      BF16 words, [L][2][H][cap_tokens][D]
  *   tok_off  first token row this chunk occupies in every tile of `out`
  * Returns 0, or -1 on a bad shape / not enough room.
  */
-int orc_dequant_scatter_chunk(const uint8_t *packed, int L, int H, int D, int T,
-                              int bits, int g,
-                              uint16_t *out, size_t cap_tokens, size_t tok_off)
+/* kv < 0: the chunk holds keys and values; kv = 0 / 1: only the keys / only the values */
+static int scatter_tiles(const uint8_t *packed, int L, int H, int D, int T,
+                         int bits, int g, int kv,
+                         uint16_t *out, size_t cap_tokens, size_t tok_off)
 {
     if (!valid_shape(D, bits, g) || T < 0) return -1;
     if (tok_off + (size_t)T > cap_tokens) return -1;
-    const size_t n_tiles = (size_t)L * 2 * H;
+    const size_t n_tiles = (size_t)L * (kv < 0 ? 2 : 1) * H;
     const size_t n_e = (size_t)T * D;
     const size_t pay = orc_tile_payload_bytes(T, D, bits);
     const size_t met = orc_tile_meta_bytes(T, D, bits, g);
     for (size_t tile = 0; tile < n_tiles; ++tile) {
         const uint8_t *payload = packed + tile * (pay + met);
         const uint8_t *meta = payload + pay;
-        uint16_t *y = out + (tile * cap_tokens + tok_off) * (size_t)D;
+        /* tile of the cache [L][2][H]: a half chunk's tile (l, h) lands in plane kv */
+        const size_t out_tile = kv < 0 ? tile
+            : ((tile / (size_t)H) * 2 + (size_t)kv) * (size_t)H + tile % (size_t)H;
+        uint16_t *y = out + (out_tile * cap_tokens + tok_off) * (size_t)D;
         for (size_t e = 0; e < n_e; ++e) {
             if (bits == 16) {
                 const uint8_t *o = payload + octet_offset(e, 16) + 2 * (e % 8);
@@ -546,6 +576,22 @@ int orc_dequant_scatter_chunk(const uint8_t *packed, int L, int H, int D, int T,
         }
     }
     return 0;
+}
+
+int orc_dequant_scatter_chunk(const uint8_t *packed, int L, int H, int D, int T,
+                              int bits, int g,
+                              uint16_t *out, size_t cap_tokens, size_t tok_off)
+{
+    return scatter_tiles(packed, L, H, D, T, bits, g, -1, out, cap_tokens, tok_off);
+}
+
+/* A keys-only (kv = 0) or values-only (kv = 1) chunk into its plane of the cache. */
+int orc_dequant_scatter_half(const uint8_t *packed, int L, int H, int D, int T,
+                             int bits, int g, int kv,
+                             uint16_t *out, size_t cap_tokens, size_t tok_off)
+{
+    if (kv != 0 && kv != 1) return -1;
+    return scatter_tiles(packed, L, H, D, T, bits, g, kv, out, cap_tokens, tok_off);
 }
 
 /*
