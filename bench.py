@@ -12,7 +12,7 @@ Prints ONE JSON line: the metric (GB/s of packed bytes read + BF16 bytes written
 KV tokens/s, the roofline object for the gather-dequantize-scatter kernel, and
 the CPU oracle timed on this machine's host cores as a baseline.
 
-Other workloads (`--workload cold8b`, `llama70b`, `zipf`) report the same fields
+Other workloads (`--workload cold8b`, `llama70b`, `zipf`, `tiers`, `units8b`) report the same fields
 for the pinned-host path, the 70B shape and the mixed-tier Zipf batch.
 """
 import argparse
@@ -304,6 +304,92 @@ def run_hbm(args, B, wl, torch, name):
     return res, (shape, T, g, mix)
 
 
+def run_units(args, B, wl, torch):
+    """The 8B shape with every document stored as a key chunk and a value chunk of their own
+    (the 2n units of Algorithm 1), keys one step hotter than values: per request ten
+    512-token documents, keys 2x16-bit + 5xint8 + 3xint4, values 1x16-bit + 2xint8 + 7xint4."""
+    import numpy as np
+    shape, T, g = (32, 8, 128), 512, 128
+    L, H, D = shape
+    kmix = [16] * 2 + [8] * 5 + [4] * 3
+    vmix = [16] * 1 + [8] * 2 + [4] * 7
+    n_pool = args.pool_chunks or 2000                      # units
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, half_slots=True)
+    ctx.set_launch_params(args.threads, args.planes16, args.planes8, args.nt_store, args.nt_load)
+    ids = {}                                               # (part, prec) -> unit ids
+    next_id, pool_bytes = 0, 0
+    t0 = time.time()
+    for tag in (16, 8, 4):
+        prec = prec_of(B, tag)
+        share = {B.PART_K: kmix.count(tag), B.PART_V: vmix.count(tag)}
+        n = {part: max(4, n_pool * k // 20) for part, k in share.items()}
+        nb = ctx.chunk_bytes(prec, T, part=B.PART_K)
+        slot = (nb + 255) // 256 * 256
+        slab = torch.empty(slot * sum(n.values()), dtype=torch.uint8, device="cuda")
+        ctx.register_slab(B.TIER_HBM, prec, slab)
+        pool_bytes += nb * sum(n.values())
+        for part, cnt in n.items():
+            ids[(part, prec)] = list(range(next_id, next_id + cnt))
+            next_id += cnt
+            for cid in ids[(part, prec)]:
+                src = wl.kv_chunk_device(L, H, D, T, args.seed * 1_000_003 + cid)
+                ctx.pool_insert_half(cid, part, prec, T, None, B.TIER_HBM)
+                ptr, _ = ctx.pool_slot(cid, B.TIER_HBM)
+                ctx.quantize_half(src[:, part - 1].contiguous(), T, prec, g, ptr)
+            torch.cuda.synchronize()
+    log(f"unit pool: {next_id} key / value chunks, {pool_bytes / 2**30:.1f} GiB packed, "
+        f"built in {time.time() - t0:.1f} s")
+    rng = np.random.Generator(np.random.PCG64(args.seed))
+    cursor = {k: 0 for k in ids}
+
+    def next_request():
+        req = []
+        for part, mix in ((B.PART_K, kmix), (B.PART_V, vmix)):
+            for tag in mix:
+                key = (part, prec_of(B, tag))
+                req.append(ids[key][cursor[key] % len(ids[key])])
+                cursor[key] += 1
+        return [req[i] for i in rng.permutation(len(req))]
+
+    cap = 10 * T
+    outs = [torch.empty((L, 2, H, cap, D), dtype=torch.bfloat16, device="cuda")
+            for _ in range(args.out_buffers)]
+    stream = torch.cuda.Stream()
+    reqs = [next_request() for _ in range(args.warmup + args.steps)]
+    step_bytes = int(sum(sum(per_token_bytes(L, H, D, b, g)) * T for b in kmix + vmix)) // 2
+    with torch.cuda.stream(stream):
+        for k in range(args.warmup):
+            ctx.load_chunks(reqs[k], outs[k % len(outs)], cap, stream=stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for k in range(args.warmup, args.warmup + args.steps):
+            ctx.load_chunks(reqs[k], outs[k % len(outs)], cap, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    kernel_ms = e0.elapsed_time(e1) / args.steps
+    ms = wall * 1e3 / args.steps
+    ctx.destroy()
+    achieved = step_bytes / (kernel_ms * 1e-3) / 1e9
+    return {
+        "metric": "kv_load_gbps", "value": step_bytes / (ms * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "Llama-3-8B KV shape, ten 512-token documents per request, each stored "
+                               "as a key chunk and a value chunk with their own tag (keys 2x16-bit + "
+                               "5xint8 + 3xint4, values 1x16-bit + 2xint8 + 7xint4, group 128), HBM pool",
+                   "pool_units": next_id, "pool_gib": round(pool_bytes / 2**30, 1),
+                   "tokens_per_step": 10 * T, "bytes_per_step": step_bytes},
+        "kv_tokens_per_s": 10 * T / (ms * 1e-3),
+        "roofline": {"bound": "hbm", "kernel": "k1_gather_dequant_scatter", "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": None, "kernel_ms": kernel_ms,
+                     "algorithmic_bytes_per_launch": step_bytes},
+    }, (shape, T, g, kmix)
+
+
 def run_cold(args, B, wl, torch):
     """All chunks int4 (group 64) in pinned host memory, 8B shape, 1024-token chunks,
     32 chunks per request, 4 requests in flight on 4 streams."""
@@ -561,7 +647,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="hbm8b", choices=["hbm8b", "llama70b", "cold8b", "zipf", "tiers"])
+    ap.add_argument("--workload", default="hbm8b", choices=["hbm8b", "llama70b", "cold8b", "zipf", "tiers", "units8b"])
     ap.add_argument("--mix", default="", help="hbm8b: tags of one request, e.g. 8,e4m3,e5m2,4")
     ap.add_argument("--pool-chunks", type=int, default=0, help="chunks in the HBM pool (0 = default)")
     ap.add_argument("--out-buffers", type=int, default=4)
@@ -610,6 +696,8 @@ def main():
     elif args.workload == "zipf":
         res = run_zipf(args, B, wl, torch)
         shape, T, g, mix = (32, 8, 128), 512, 128, [16] * 2 + [8] * 3 + [4] * 5
+    elif args.workload == "units8b":
+        res, (shape, T, g, mix) = run_units(args, B, wl, torch)
     else:
         if args.pool_chunks == 0:
             args.pool_chunks = 2000 if args.workload == "hbm8b" else 400

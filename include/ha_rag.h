@@ -84,6 +84,14 @@ extern "C" {
 #define HA_RAG_TIER_DISK 3     /* a file; read into a pinned bounce buffer first           */
 #define HA_RAG_TIER_NONE 255
 
+/* What a chunk holds.  Algorithm 1 ranks the n key chunks and the n value chunks of a
+ * knowledge base as 2n units, each with its own access frequency and precision; a
+ * keys-only or values-only chunk is such a unit: shape [L][H][T][D], tile records
+ * (l, h) back to back, exactly half the bytes of a whole chunk of the same length. */
+#define HA_RAG_PART_KV 0 /* keys and values of a document under one id and one tag */
+#define HA_RAG_PART_K 1
+#define HA_RAG_PART_V 2
+
 #define HA_RAG_NO_CHUNK UINT64_MAX
 #define HA_RAG_MAX_REQUEST_CHUNKS 4096
 
@@ -112,6 +120,10 @@ typedef struct ha_rag_config {
                                   through one page-aligned host buffer that the library
                                   allocates in ha_rag_register_bounce, because direct I/O
                                   cannot target GPU-pinned memory)                         */
+    uint32_t half_slots;       /* 1 = every slab slot is sized for a keys-only or values-only
+                                  chunk of max_chunk_tokens (a pool that stores the 2n units
+                                  of Algorithm 1); whole chunks are then refused (EFORMAT).
+                                  0 = slots are sized for whole chunks; halves fit too     */
 } ha_rag_config;
 
 /* One packed chunk handed to ha_rag_load_packed (no pool involved). */
@@ -120,7 +132,7 @@ typedef struct ha_rag_packed_chunk {
     uint32_t n_tokens;
     uint32_t prec;      /* HA_RAG_PREC_*                                                */
     uint32_t group;     /* ignored for HA_RAG_PREC_16                                   */
-    uint32_t reserved;
+    uint32_t part;      /* HA_RAG_PART_*; a half has half the bytes of a whole chunk    */
 } ha_rag_packed_chunk;
 
 typedef struct ha_rag_chunk_info {
@@ -128,6 +140,8 @@ typedef struct ha_rag_chunk_info {
     uint32_t in_hbm, in_pinned; /* 0 / 1                                      */
     uint32_t rank;              /* 0 = hottest, as of the last rerank         */
     uint32_t in_pageable, on_disk; /* 0 / 1                                   */
+    uint32_t part;              /* HA_RAG_PART_*                              */
+    uint32_t reserved;
     uint64_t count;             /* accesses so far (Algorithm 1's AF entry)   */
     uint64_t bytes;             /* packed size                                */
     const void *hbm_ptr;        /* slot address or NULL                       */
@@ -136,7 +150,8 @@ typedef struct ha_rag_chunk_info {
 
 /* What happened to one chunk of a load (Algorithm 2 step 2, per C_i). */
 typedef struct ha_rag_chunk_trace {
-    uint64_t tok_off;     /* first token row of this chunk in the cache        */
+    uint64_t tok_off;     /* first token row of this chunk in the cache (of its plane,
+                             for a keys-only or values-only chunk)             */
     uint64_t evicted_id;  /* chunk dropped from HBM to make room, or NO_CHUNK  */
     uint8_t found_tier;   /* fastest tier that held the chunk (HA_RAG_TIER_*)   */
     uint8_t promoted;     /* 1 = copied into the HBM slab by this load         */
@@ -224,6 +239,12 @@ int ha_rag_set_launch_params(ha_rag_ctx *ctx, const ha_rag_launch_params *lp);
 int ha_rag_quantize_chunk(ha_rag_ctx *ctx, const void *src, uint32_t n_tokens, uint32_t prec,
                           uint32_t group, void *dst, uint32_t *saturated, void *stream);
 
+/* The same for a keys-only or values-only chunk: src is BF16 [L][H][n_tokens][D] (one
+ * plane of a document's KV), dst takes half of ha_rag_chunk_bytes().  The bytes do not
+ * depend on which of the two planes the chunk is. */
+int ha_rag_quantize_half(ha_rag_ctx *ctx, const void *src, uint32_t n_tokens, uint32_t prec,
+                         uint32_t group, void *dst, uint32_t *saturated, void *stream);
+
 /* ---- online, no pool: gather-dequantize-scatter of caller-held packed chunks -- */
 
 /* Chunk i of `chunks[n]` (host array, n <= HA_RAG_MAX_REQUEST_CHUNKS) is
@@ -231,7 +252,12 @@ int ha_rag_quantize_chunk(ha_rag_ctx *ctx, const void *src, uint32_t n_tokens, u
  * rows [tok_base + sum_{j<i} n_tokens_j, ...) of every (layer, K/V, head) tile of
  * out[L][2][H][cap_tokens][D] (device, BF16, 16-byte aligned).  Rows outside those
  * ranges are not written.  ENOSPC if the chunks do not fit, before anything is
- * enqueued.  One kernel launch per 64 chunks. */
+ * enqueued.  One kernel launch per 64 chunks.
+ * Keys-only and values-only chunks (`part`) fill only their plane: the key plane and
+ * the value plane each advance in list order by the chunks that hold them, so the keys
+ * and the values of a document may sit anywhere in the list and differ in precision.
+ * EINVAL, before anything is enqueued, if a whole chunk arrives while the two planes
+ * differ in length, or if they differ at the end of the list. */
 int ha_rag_load_packed(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks, uint32_t n,
                        void *out, uint64_t cap_tokens, uint64_t tok_base, void *stream);
 
@@ -274,6 +300,15 @@ int ha_rag_register_bounce(ha_rag_ctx *ctx, void *base, size_t bytes);
  * chunk of that slab is dropped), file slab full, or bounce buffer missing. */
 int ha_rag_pool_insert(ha_rag_ctx *ctx, uint64_t id, uint32_t prec, uint32_t n_tokens,
                        const void *packed, int packed_is_device, uint32_t tier, void *stream);
+
+/* The same for a keys-only (HA_RAG_PART_K) or values-only (HA_RAG_PART_V) chunk: one of
+ * the 2n units of Algorithm 1, with an id, an access count, a rank and a tag of its own.
+ * `packed` holds half of ha_rag_chunk_bytes().  In a load (ha_rag_load_chunks,
+ * ha_rag_load_batch) such chunks follow the rule given at ha_rag_load_packed, per
+ * request.  EINVAL for any other `part`; EFORMAT if the id exists with another part. */
+int ha_rag_pool_insert_half(ha_rag_ctx *ctx, uint64_t id, uint32_t part, uint32_t prec,
+                            uint32_t n_tokens, const void *packed, int packed_is_device,
+                            uint32_t tier, void *stream);
 
 /* Address and size of the slot that holds chunk `id` in `tier` (ENOENT if not
  * there). */

@@ -13,6 +13,7 @@ from . import build as _build
 OK, EINVAL, ENOENT, ENOSPC, EFORMAT, EHIP, EIO = 0, -1, -2, -3, -4, -5, -6
 PREC_16, PREC_INT8, PREC_INT4, PREC_FP8_E4M3, PREC_FP8_E5M2, PREC_GSE8 = 0, 1, 2, 3, 4, 5
 TIER_HBM, TIER_PINNED, TIER_PAGEABLE, TIER_DISK, TIER_NONE = 0, 1, 2, 3, 255
+PART_KV, PART_K, PART_V = 0, 1, 2
 NO_CHUNK = 2**64 - 1
 BITS = {PREC_16: 16, PREC_INT8: 8, PREC_INT4: 4, PREC_FP8_E4M3: 8, PREC_FP8_E5M2: 8,
         PREC_GSE8: 8}  # storage bits
@@ -27,6 +28,7 @@ SYMBOLS = [
     "ha_rag_pool_evict", "ha_rag_pool_query", "ha_rag_pool_hbm_lru", "ha_rag_touch",
     "ha_rag_set_counts", "ha_rag_rerank", "ha_rag_get_rank", "ha_rag_load_chunks",
     "ha_rag_load_batch", "ha_rag_register_disk", "ha_rag_register_bounce", "ha_rag_pool_lru",
+    "ha_rag_quantize_half", "ha_rag_pool_insert_half",
 ]
 
 
@@ -34,7 +36,7 @@ class Config(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in (
         "n_layers", "n_kv_heads", "head_dim", "max_chunk_tokens", "group_int8", "group_int4",
         "tau_gpu_ppm", "rerank_interval", "n_copy_streams", "dry_run", "tau_pin_ppm",
-        "tau_page_ppm", "disk_o_direct")]
+        "tau_page_ppm", "disk_o_direct", "half_slots")]
 
 
 class LaunchParams(C.Structure):
@@ -44,13 +46,14 @@ class LaunchParams(C.Structure):
 
 class PackedChunk(C.Structure):
     _fields_ = [("packed", C.c_void_p), ("n_tokens", C.c_uint32), ("prec", C.c_uint32),
-                ("group", C.c_uint32), ("reserved", C.c_uint32)]
+                ("group", C.c_uint32), ("part", C.c_uint32)]
 
 
 class ChunkInfo(C.Structure):
     _fields_ = [("prec", C.c_uint32), ("group", C.c_uint32), ("n_tokens", C.c_uint32),
                 ("in_hbm", C.c_uint32), ("in_pinned", C.c_uint32), ("rank", C.c_uint32),
-                ("in_pageable", C.c_uint32), ("on_disk", C.c_uint32), ("count", C.c_uint64), ("bytes", C.c_uint64),
+                ("in_pageable", C.c_uint32), ("on_disk", C.c_uint32),
+                ("part", C.c_uint32), ("reserved", C.c_uint32), ("count", C.c_uint64), ("bytes", C.c_uint64),
                 ("hbm_ptr", C.c_void_p), ("pinned_ptr", C.c_void_p)]
 
 
@@ -64,7 +67,7 @@ class LoadStats(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in (
         "n_chunks", "n_hbm_hits", "n_pinned_hits", "n_promoted", "n_evicted",
         "n_promote_skipped", "n_kernel_launches", "n_pageable_hits", "n_disk_hits",
-        "n_placed_host", "reserved0", "reserved1")] + [(n, C.c_uint64) for n in (
+        "n_placed_host")] + [("reserved", C.c_uint32 * 2)] + [(n, C.c_uint64) for n in (
             "tokens", "bytes_h2d", "bytes_d2d", "packed_bytes_read", "bf16_bytes_written",
             "bytes_disk_read", "bytes_host_copied")]
 
@@ -114,6 +117,8 @@ def lib():
             "ha_rag_last_hip_error": (C.c_char_p, [vp]),
             "ha_rag_set_launch_params": (C.c_int, [vp, P(LaunchParams)]),
             "ha_rag_quantize_chunk": (C.c_int, [vp, vp, u32, u32, u32, vp, vp, vp]),
+            "ha_rag_quantize_half": (C.c_int, [vp, vp, u32, u32, u32, vp, vp, vp]),
+            "ha_rag_pool_insert_half": (C.c_int, [vp, u64, u32, u32, u32, vp, C.c_int, u32, vp]),
             "ha_rag_load_packed": (C.c_int, [vp, P(PackedChunk), u32, vp, u64, u64, vp]),
             "ha_rag_register_slab": (C.c_int, [vp, u32, u32, vp, sz]),
             "ha_rag_register_staging": (C.c_int, [vp, vp, sz]),
@@ -202,10 +207,12 @@ class Context:
 
     def __init__(self, n_layers, n_kv_heads, head_dim, max_chunk_tokens, group_int8=128,
                  group_int4=128, tau_gpu_ppm=50_000, rerank_interval=0, n_copy_streams=0,
-                 dry_run=False, tau_pin_ppm=0, tau_page_ppm=0, disk_o_direct=False):
+                 dry_run=False, tau_pin_ppm=0, tau_page_ppm=0, disk_o_direct=False,
+                 half_slots=False):
         self.cfg = Config(n_layers, n_kv_heads, head_dim, max_chunk_tokens, group_int8, group_int4,
                           tau_gpu_ppm, rerank_interval, n_copy_streams, 1 if dry_run else 0,
-                          tau_pin_ppm, tau_page_ppm, 1 if disk_o_direct else 0)
+                          tau_pin_ppm, tau_page_ppm, 1 if disk_o_direct else 0,
+                          1 if half_slots else 0)
         self._h = C.c_void_p()
         rc = lib().ha_rag_create(C.byref(self.cfg), C.byref(self._h))
         if rc:
@@ -232,10 +239,11 @@ class Context:
     def group_of(self, prec):
         return {PREC_INT8: self.cfg.group_int8, PREC_INT4: self.cfg.group_int4}.get(prec, 0)
 
-    def chunk_bytes(self, prec, n_tokens, group=None):
+    def chunk_bytes(self, prec, n_tokens, group=None, part=PART_KV):
         g = self.group_of(prec) if group is None else group
-        return ha_rag_chunk_bytes(self.cfg.n_layers, self.cfg.n_kv_heads, self.cfg.head_dim, prec,
-                                  g, n_tokens)[2]
+        whole = ha_rag_chunk_bytes(self.cfg.n_layers, self.cfg.n_kv_heads, self.cfg.head_dim, prec,
+                                   g, n_tokens)[2]
+        return whole if part == PART_KV else whole // 2
 
     def set_launch_params(self, threads=64, planes16=1, planes8=2, nt_store=1, nt_load=1):
         lp = LaunchParams(threads, planes16, planes8, int(nt_store), int(nt_load))
@@ -246,11 +254,17 @@ class Context:
                                               _addr(saturated), _stream(stream)),
                   "ha_rag_quantize_chunk")
 
+    def quantize_half(self, src, n_tokens, prec, group, dst, saturated=None, stream=None):
+        self._chk(lib().ha_rag_quantize_half(self._h, _addr(src), n_tokens, prec, group, _addr(dst),
+                                             _addr(saturated), _stream(stream)),
+                  "ha_rag_quantize_half")
+
     def load_packed(self, chunks, out, cap_tokens, tok_base=0, stream=None):
-        """chunks: list of (packed, n_tokens, prec, group)."""
+        """chunks: list of (packed, n_tokens, prec, group[, part])."""
         arr = (PackedChunk * max(len(chunks), 1))()
-        for i, (p, t, prec, g) in enumerate(chunks):
-            arr[i] = PackedChunk(_addr(p), t, prec, g, 0)
+        for i, ch in enumerate(chunks):
+            p, t, prec, g = ch[:4]
+            arr[i] = PackedChunk(_addr(p), t, prec, g, ch[4] if len(ch) > 4 else PART_KV)
         self._chk(lib().ha_rag_load_packed(self._h, arr, len(chunks), _addr(out), cap_tokens,
                                            tok_base, _stream(stream)), "ha_rag_load_packed")
 
@@ -283,6 +297,12 @@ class Context:
         self._chk(lib().ha_rag_pool_insert(self._h, cid, prec, n_tokens, _addr(packed),
                                            1 if packed_is_device else 0, tier, _stream(stream)),
                   "ha_rag_pool_insert")
+
+    def pool_insert_half(self, cid, part, prec, n_tokens, packed, tier, packed_is_device=False,
+                         stream=None):
+        self._chk(lib().ha_rag_pool_insert_half(self._h, cid, part, prec, n_tokens, _addr(packed),
+                                                1 if packed_is_device else 0, tier, _stream(stream)),
+                  "ha_rag_pool_insert_half")
 
     def pool_slot(self, cid, tier):
         p, n = C.c_void_p(), C.c_size_t()

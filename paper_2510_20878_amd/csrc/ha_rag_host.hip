@@ -57,14 +57,16 @@ uint32_t log2u(uint32_t v)
 }
 
 int chunk_bytes_impl(uint32_t L, uint32_t H, uint32_t D, uint32_t prec, uint32_t group,
-                     uint32_t T, size_t *payload, size_t *meta, size_t *total)
+                     uint32_t T, size_t *payload, size_t *meta, size_t *total,
+                     uint32_t part = kPartKV)
 {
     if (prec >= HA_RAG_N_PREC || L == 0 || H == 0 || D == 0 || (D % 8u)) return HA_RAG_EFORMAT;
     if (has_meta(prec) && (!valid_group(group) || (D % group))) return HA_RAG_EFORMAT;
     const uint64_t n_e = (uint64_t)T * D;
     if (n_e > 0x7FFFFFFFull) return HA_RAG_EINVAL;
     const uint64_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
-    const uint64_t tiles = 2ull * L * H;
+    if (part > kPartV) return HA_RAG_EINVAL;
+    const uint64_t tiles = (part == kPartKV ? 2ull : 1ull) * L * H;
     const uint64_t pay = tiles * nblk * 256ull * bits_of(prec);
     const uint64_t met = has_meta(prec)               ? tiles * nblk * (kBlockElems / group) * 4ull
                          : prec == HA_RAG_PREC_GSE8 ? (nblk ? tiles * 16ull : 0)
@@ -78,6 +80,7 @@ int chunk_bytes_impl(uint32_t L, uint32_t H, uint32_t D, uint32_t prec, uint32_t
 struct Chunk {
     uint64_t id = 0;
     uint32_t prec = 0, n_tokens = 0;
+    uint32_t part = kPartKV;  // keys and values, or one of the two
     uint64_t bytes = 0;
     int32_t slot[kTiers] = {-1, -1, -1, -1};
     uint64_t count = 0;
@@ -402,6 +405,28 @@ void rerank_locked(ha_rag_ctx *c)
     }
 }
 
+// Token rows of the key plane and of the value plane of one request's cache, as its chunks
+// fill them in list order.  A whole chunk needs both planes at the same length.
+struct PlaneCursor {
+    uint64_t off[2];
+    explicit PlaneCursor(uint64_t base) : off{base, base} {}
+    bool place(uint32_t part, uint64_t n_tokens, uint64_t *at)
+    {
+        if (part == kPartKV) {
+            if (off[0] != off[1]) return false;
+            *at = off[0];
+            off[0] += n_tokens;
+            off[1] += n_tokens;
+        } else {
+            *at = off[part - kPartK];
+            off[part - kPartK] += n_tokens;
+        }
+        return true;
+    }
+    bool closed() const { return off[0] == off[1]; }
+    uint64_t end() const { return std::max(off[0], off[1]); }
+};
+
 struct Request {
     uint32_t begin, end;
     uint8_t *out;
@@ -431,7 +456,7 @@ K1Chunk make_desc(const ha_rag_ctx *c, const Chunk &ch, const uint8_t *src, cons
     d.out_tile_stride = rq.cap * D * 2ull;
     d.n_tokens = ch.n_tokens;
     const uint32_t g = c->group_of(ch.prec);
-    d.fmt = ch.prec | ((g ? log2u(g) : 0u) << 8);
+    d.fmt = ch.prec | ((g ? log2u(g) : 0u) << 8) | (ch.part << 16);
     return d;
 }
 
@@ -457,7 +482,8 @@ int push(ha_rag_ctx *c, Batch &b, const K1Chunk &d, hipStream_t s, uint32_t *lau
 
 void init_batch(const ha_rag_ctx *c, Batch &b)
 {
-    b.p.n_tiles = c->n_tiles;
+    b.p.n_layers = c->cfg.n_layers;
+    b.p.n_kv_heads = c->cfg.n_kv_heads;
     b.p.head_dim = c->cfg.head_dim;
     b.p.n_chunks = 0;
     b.p.total_items = 0;
@@ -575,7 +601,7 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
         const Request &rq = reqs[r];
         if (rq.end < rq.begin || rq.end > n) return HA_RAG_EINVAL;
         if (rq.end > rq.begin && (rq.out == nullptr || ((uintptr_t)rq.out & 15u))) return HA_RAG_EINVAL;
-        uint64_t tok = 0;
+        PlaneCursor cur(0);
         for (uint32_t i = rq.begin; i < rq.end; ++i) {
             Chunk *ch = find_chunk(c, ids[i], &cis[i]);
             if (!ch) return HA_RAG_ENOENT;
@@ -588,9 +614,11 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
             if (f >= (int)HA_RAG_TIER_PAGEABLE &&
                 (c->bnc.size() < 2 || c->io_bytes(ch->bytes) > c->bounce_slot_bytes))
                 return HA_RAG_ENOSPC;
-            tok += ch->n_tokens;
+            uint64_t at;
+            if (!cur.place(ch->part, ch->n_tokens, &at)) return HA_RAG_EINVAL;
         }
-        if (rq.base > rq.cap || tok > rq.cap - rq.base) return HA_RAG_ENOSPC;
+        if (!cur.closed()) return HA_RAG_EINVAL;  // keys without their values, or the reverse
+        if (rq.base > rq.cap || cur.end() > rq.cap - rq.base) return HA_RAG_ENOSPC;
     }
 
     if (c->cfg.rerank_interval && c->n_loads && (c->n_loads % c->cfg.rerank_interval) == 0)
@@ -609,11 +637,13 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     for (auto &m : made) m.assign(c->chunks.size(), 0);
     for (uint32_t r = 0; r < n_req; ++r) {
         const Request &rq = reqs[r];
-        uint64_t off = rq.base;
+        PlaneCursor cur(rq.base);
         for (uint32_t i = rq.begin; i < rq.end; ++i) {
             const uint32_t ci = cis[i];
             Chunk &ch = c->chunks[ci];
             ch.count += 1;
+            uint64_t off = 0;
+            (void)cur.place(ch.part, ch.n_tokens, &off);  // checked above
             const uint32_t found = (uint32_t)ch.fastest();
             Action a{ci, r, off, Action::COLD, (uint8_t)found, ch.slot[found], HA_RAG_TIER_NONE, -1};
             ha_rag_chunk_trace tr;
@@ -668,10 +698,10 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
                     }
                 }
             }
-            st.tokens += ch.n_tokens;
+            if (ch.part != kPartV) st.tokens += ch.n_tokens;  // rows of the key plane
             st.packed_bytes_read += ch.bytes;
-            st.bf16_bytes_written += (uint64_t)ch.n_tokens * c->n_tiles * D * 2ull;
-            off += ch.n_tokens;
+            st.bf16_bytes_written +=
+                (uint64_t)ch.n_tokens * (ch.part == kPartKV ? c->n_tiles : c->n_tiles / 2) * D * 2ull;
             acts.push_back(a);
             if (trace) trace[i] = tr;
         }
@@ -832,7 +862,8 @@ int register_slab_common(ha_rag_ctx *c, Slab &sl, uint32_t prec, size_t bytes, s
 {
     size_t total;
     int rc = chunk_bytes_impl(c->cfg.n_layers, c->cfg.n_kv_heads, c->cfg.head_dim, prec,
-                              c->group_of(prec), c->cfg.max_chunk_tokens, nullptr, nullptr, &total);
+                              c->group_of(prec), c->cfg.max_chunk_tokens, nullptr, nullptr, &total,
+                              c->cfg.half_slots ? kPartK : kPartKV);
     if (rc) return rc;
     const size_t slot = (total + align - 1) / align * align;
     if (bytes < slot) return HA_RAG_EINVAL;
@@ -977,20 +1008,34 @@ int ha_rag_set_launch_params(ha_rag_ctx *c, const ha_rag_launch_params *lp)
     return HA_RAG_OK;
 }
 
-int ha_rag_quantize_chunk(ha_rag_ctx *c, const void *src, uint32_t n_tokens, uint32_t prec,
-                          uint32_t group, void *dst, uint32_t *saturated, void *stream)
+static int quantize_impl(ha_rag_ctx *c, const void *src, uint32_t n_tokens, uint32_t prec,
+                         uint32_t group, void *dst, uint32_t *saturated, void *stream, uint32_t part)
 {
     if (!c || !src || !dst) return HA_RAG_EINVAL;
     if (((uintptr_t)src & 15u) || ((uintptr_t)dst & 15u) || ((uintptr_t)saturated & 3u)) return HA_RAG_EINVAL;
     size_t total;
     int rc = chunk_bytes_impl(c->cfg.n_layers, c->cfg.n_kv_heads, c->cfg.head_dim, prec, group,
-                              n_tokens, nullptr, nullptr, &total);
+                              n_tokens, nullptr, nullptr, &total, part);
     if (rc) return rc;
     if (c->dry()) return HA_RAG_OK;
     std::lock_guard<std::mutex> g(c->mu);
-    HIPCHK(c, launch_k2(src, dst, c->n_tiles, c->cfg.head_dim, n_tokens, prec,
-                        has_meta(prec) ? group : 32u, saturated, (hipStream_t)stream));
+    HIPCHK(c, launch_k2(src, dst, part == kPartKV ? c->n_tiles : c->n_tiles / 2, c->cfg.head_dim,
+                        n_tokens, prec, has_meta(prec) ? group : 32u, saturated,
+                        (hipStream_t)stream));
     return HA_RAG_OK;
+}
+
+int ha_rag_quantize_chunk(ha_rag_ctx *c, const void *src, uint32_t n_tokens, uint32_t prec,
+                          uint32_t group, void *dst, uint32_t *saturated, void *stream)
+{
+    return quantize_impl(c, src, n_tokens, prec, group, dst, saturated, stream, kPartKV);
+}
+
+int ha_rag_quantize_half(ha_rag_ctx *c, const void *src, uint32_t n_tokens, uint32_t prec,
+                         uint32_t group, void *dst, uint32_t *saturated, void *stream)
+{
+    // the tile records of a half do not depend on which plane it is
+    return quantize_impl(c, src, n_tokens, prec, group, dst, saturated, stream, kPartK);
 }
 
 int ha_rag_load_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, uint32_t n, void *out,
@@ -999,33 +1044,36 @@ int ha_rag_load_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, uint32_
     if (!c || (n && (!chunks || !out)) || n > HA_RAG_MAX_REQUEST_CHUNKS) return HA_RAG_EINVAL;
     if ((uintptr_t)out & 15u) return HA_RAG_EINVAL;
     const uint64_t D = c->cfg.head_dim;
-    uint64_t tok = 0;
+    PlaneCursor chk(0);
     for (uint32_t i = 0; i < n; ++i) {
         const ha_rag_packed_chunk &pc = chunks[i];
         int rc = chunk_bytes_impl(c->cfg.n_layers, c->cfg.n_kv_heads, c->cfg.head_dim, pc.prec,
-                                  pc.group, pc.n_tokens, nullptr, nullptr, nullptr);
+                                  pc.group, pc.n_tokens, nullptr, nullptr, nullptr, pc.part);
         if (rc) return rc;
         if (pc.n_tokens && (!pc.packed || ((uintptr_t)pc.packed & 15u))) return HA_RAG_EINVAL;
-        tok += pc.n_tokens;
+        uint64_t at;
+        if (!chk.place(pc.part, pc.n_tokens, &at)) return HA_RAG_EINVAL;
     }
-    if (tok_base > cap_tokens || tok > cap_tokens - tok_base) return HA_RAG_ENOSPC;
+    if (!chk.closed()) return HA_RAG_EINVAL;
+    if (tok_base > cap_tokens || chk.end() > cap_tokens - tok_base) return HA_RAG_ENOSPC;
     if (cap_tokens * D > 0x7FFFFFFFFFFFull) return HA_RAG_EINVAL;
     std::lock_guard<std::mutex> g(c->mu);
     Batch batch;
     init_batch(c, batch);
-    uint64_t off = tok_base;
+    PlaneCursor cur(tok_base);
     for (uint32_t i = 0; i < n; ++i) {
         const ha_rag_packed_chunk &pc = chunks[i];
         if (pc.n_tokens == 0) continue;
+        uint64_t off = 0;
+        (void)cur.place(pc.part, pc.n_tokens, &off);  // checked above
         K1Chunk d;
         d.src = static_cast<const uint8_t *>(pc.packed);
         d.out = static_cast<uint8_t *>(out) + off * D * 2ull;
         d.out_tile_stride = cap_tokens * D * 2ull;
         d.n_tokens = pc.n_tokens;
-        d.fmt = pc.prec | ((has_meta(pc.prec) ? log2u(pc.group) : 0u) << 8);
+        d.fmt = pc.prec | ((has_meta(pc.prec) ? log2u(pc.group) : 0u) << 8) | (pc.part << 16);
         int rc = push(c, batch, d, (hipStream_t)stream, nullptr);
         if (rc) return rc;
-        off += pc.n_tokens;
     }
     return flush(c, batch, (hipStream_t)stream, nullptr);
 }
@@ -1122,24 +1170,26 @@ int ha_rag_register_bounce(ha_rag_ctx *c, void *base, size_t bytes)
     return HA_RAG_OK;
 }
 
-int ha_rag_pool_insert(ha_rag_ctx *c, uint64_t id, uint32_t prec, uint32_t n_tokens,
+static int insert_impl(ha_rag_ctx *c, uint64_t id, uint32_t part, uint32_t prec, uint32_t n_tokens,
                        const void *packed, int packed_is_device, uint32_t tier, void *stream)
 {
     if (!c || tier >= kTiers || prec >= HA_RAG_N_PREC || id == HA_RAG_NO_CHUNK) return HA_RAG_EINVAL;
+    if (part > kPartV) return HA_RAG_EINVAL;
     if (n_tokens == 0 || n_tokens > c->cfg.max_chunk_tokens) return HA_RAG_EINVAL;
+    if (part == kPartKV && c->cfg.half_slots) return HA_RAG_EFORMAT;  // slots hold halves only
     hipStream_t s = (hipStream_t)stream;
     std::lock_guard<std::mutex> g(c->mu);
     Slab &sl = c->slab[tier][prec];
     if (!sl.registered()) return HA_RAG_ENOSPC;
     size_t total;
     int rc = chunk_bytes_impl(c->cfg.n_layers, c->cfg.n_kv_heads, c->cfg.head_dim, prec,
-                              c->group_of(prec), n_tokens, nullptr, nullptr, &total);
+                              c->group_of(prec), n_tokens, nullptr, nullptr, &total, part);
     if (rc) return rc;
     uint32_t ci;
     Chunk *ch = find_chunk(c, id, &ci);
     if (ch) {
         if (ch->slot[tier] >= 0) return HA_RAG_EINVAL;
-        if (ch->prec != prec || ch->n_tokens != n_tokens) return HA_RAG_EFORMAT;
+        if (ch->prec != prec || ch->n_tokens != n_tokens || ch->part != part) return HA_RAG_EFORMAT;
     }
     // pageable / disk targets fed from device memory or through O_DIRECT need a bounce buffer
     const bool via_bounce = packed && tier >= HA_RAG_TIER_PAGEABLE && packed_is_device;
@@ -1155,6 +1205,7 @@ int ha_rag_pool_insert(ha_rag_ctx *c, uint64_t id, uint32_t prec, uint32_t n_tok
         ch->id = id;
         ch->prec = prec;
         ch->n_tokens = n_tokens;
+        ch->part = part;
         ch->bytes = total;
         c->index.emplace(id, ci);
     }
@@ -1202,6 +1253,20 @@ int ha_rag_pool_insert(ha_rag_ctx *c, uint64_t id, uint32_t prec, uint32_t n_tok
     std::memcpy(c->dio, host, total);
     std::memset(c->dio + total, 0, c->io_bytes(total) - total);
     return write_full(c, sl.fd, c->dio, c->io_bytes(total), sl.offset(slot));
+}
+
+int ha_rag_pool_insert(ha_rag_ctx *c, uint64_t id, uint32_t prec, uint32_t n_tokens,
+                       const void *packed, int packed_is_device, uint32_t tier, void *stream)
+{
+    return insert_impl(c, id, kPartKV, prec, n_tokens, packed, packed_is_device, tier, stream);
+}
+
+int ha_rag_pool_insert_half(ha_rag_ctx *c, uint64_t id, uint32_t part, uint32_t prec,
+                            uint32_t n_tokens, const void *packed, int packed_is_device,
+                            uint32_t tier, void *stream)
+{
+    if (part != kPartK && part != kPartV) return HA_RAG_EINVAL;
+    return insert_impl(c, id, part, prec, n_tokens, packed, packed_is_device, tier, stream);
 }
 
 int ha_rag_pool_slot(ha_rag_ctx *c, uint64_t id, uint32_t tier, void **ptr, size_t *bytes)
@@ -1270,6 +1335,7 @@ int ha_rag_pool_query(ha_rag_ctx *c, uint64_t id, ha_rag_chunk_info *info)
     info->prec = ch->prec;
     info->group = c->group_of(ch->prec);
     info->n_tokens = ch->n_tokens;
+    info->part = ch->part;
     info->in_hbm = ch->slot[HA_RAG_TIER_HBM] >= 0;
     info->in_pinned = ch->slot[HA_RAG_TIER_PINNED] >= 0;
     info->in_pageable = ch->slot[HA_RAG_TIER_PAGEABLE] >= 0;

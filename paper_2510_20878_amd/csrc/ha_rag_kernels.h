@@ -19,20 +19,30 @@ struct K1Chunk {
     uint8_t *out;              // cache address of tile 0, token row tok_off, dim 0
     uint64_t out_tile_stride;  // bytes between consecutive tiles of the cache
     uint32_t n_tokens;
-    uint32_t fmt;              // Prec | log2(group) << 8
+    uint32_t fmt;              // Prec | log2(group) << 8 | part << 16
 };
+
+// what a chunk holds (numbered like HA_RAG_PART_* of the C ABI): keys and values of a
+// document (tile records (l, kv, h)), or only its keys / only its values (records (l, h))
+enum Part : uint32_t { kPartKV = 0, kPartK = 1, kPartV = 2 };
 
 // The unit of work of one wave is an *item*: `planes` of the four 1024-byte output
 // planes of one block (int4: always all four, fed by one 16-byte load per lane;
 // int8 and FP8: two or four; 16-bit: one, two or four).
 struct K1Params {
-    uint32_t n_tiles;      // 2 * L * H
+    uint32_t n_layers;     // the cache has n_layers * 2 * n_kv_heads tiles
+    uint32_t n_kv_heads;
     uint32_t head_dim;
     uint32_t n_chunks;
-    uint32_t total_items;     // n_tiles * items_per_tile
-    uint32_t items_per_tile;  // items of all chunks in one tile
-    uint8_t planes16, planes8, pad[2];
-    uint32_t item_start[kMaxLaunchChunks + 1];  // prefix sum over chunks of items per tile
+    uint32_t total_items;        // n_layers * items_per_layer
+    uint32_t items_per_layer;    // n_kv_heads * (items_per_tile[0] + items_per_tile[1])
+    uint32_t items_per_tile[2];  // items of all chunks in one key tile / one value tile
+    uint8_t planes16, planes8;
+    uint8_t any_half;  // 1 = some chunk of the launch holds only keys or only values
+    uint8_t pad;
+    // per plane (keys, values): prefix sum over chunks of the items a chunk has in one
+    // tile of that plane (none if the chunk does not hold that plane)
+    uint32_t item_start[2][kMaxLaunchChunks + 1];
     K1Chunk c[kMaxLaunchChunks];
 };
 

@@ -157,21 +157,41 @@ __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params
     const uint32_t item = blockIdx.x * nwaves + wave;
     if (item >= p.total_items) return;
 
-    // Items are ordered tile by tile, and inside a tile chunk by chunk in request order: the
-    // launch then writes each tile of the cache front to back as one sequential stream.
-    const uint32_t tile = item / p.items_per_tile;
-    const uint32_t rt = item - tile * p.items_per_tile;
-    uint32_t lo = 0, hi = p.n_chunks;  // item_start[lo] <= rt < item_start[hi]
+    // Items are ordered tile by tile of the cache ([layer][keys, values][head]), and inside a
+    // tile chunk by chunk in request order: the launch then writes each tile front to back
+    // as one sequential stream.  Key tiles and value tiles may hold different item counts
+    // (a keys-only chunk has no items in a value tile).
+    uint32_t layer, kv, head, rt, out_tile;
+    if (!p.any_half) {
+        // whole chunks only: every tile holds the same items, one division finds the tile
+        out_tile = item / p.items_per_tile[0];
+        rt = item - out_tile * p.items_per_tile[0];
+        layer = head = kv = 0;  // not needed: tile records are numbered like cache tiles
+    } else {
+        layer = item / p.items_per_layer;
+        uint32_t rl = item - layer * p.items_per_layer;
+        const uint32_t k_items = p.n_kv_heads * p.items_per_tile[0];
+        kv = rl >= k_items ? 1u : 0u;
+        rl -= kv ? k_items : 0u;
+        const uint32_t ipt = p.items_per_tile[kv];
+        head = rl / ipt;
+        rt = rl - head * ipt;
+        out_tile = (layer * 2u + kv) * p.n_kv_heads + head;
+    }
+    const uint32_t *start = p.item_start[kv];
+    uint32_t lo = 0, hi = p.n_chunks;  // start[lo] <= rt < start[hi]
     while (hi - lo > 1) {
         const uint32_t mid = (lo + hi) >> 1;
-        if (rt >= p.item_start[mid]) lo = mid;
+        if (rt >= start[mid]) lo = mid;
         else hi = mid;
     }
     const K1Chunk &c = p.c[lo];
-    const uint32_t r = rt - p.item_start[lo];
+    const uint32_t r = rt - start[lo];
+    // tile record inside the chunk: (l, kv, h) for a whole chunk, (l, h) for a half
+    const uint32_t tile = ((c.fmt >> 16) & 3u) ? layer * p.n_kv_heads + head : out_tile;
     const uint32_t n_e = c.n_tokens * p.head_dim;
     const uint32_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
-    const uint32_t prec = c.fmt & 0xFFu, gsh = c.fmt >> 8;
+    const uint32_t prec = c.fmt & 0xFFu, gsh = (c.fmt >> 8) & 0xFFu;
     const uint32_t planes = prec == kInt4 ? 4u : prec == kP16 ? p.planes16 : p.planes8;
     const uint32_t ipb_sh = planes == 4 ? 0u : planes == 2 ? 1u : 2u;  // log2(items per block)
     const uint32_t blk = r >> ipb_sh;
@@ -179,7 +199,7 @@ __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params
 
     const uint32_t lane_b = lane * 16;
     const uint32_t e = blk * kBlockElems + lane * 8 + j0 * 512;  // element of plane j0
-    uint8_t *o = c.out + (uint64_t)tile * c.out_tile_stride + (uint64_t)blk * 4096u +
+    uint8_t *o = c.out + (uint64_t)out_tile * c.out_tile_stride + (uint64_t)blk * 4096u +
                  j0 * 1024u + lane_b;
 
     if (prec == kInt4) {
@@ -274,23 +294,31 @@ hipError_t launch_k1(K1Params &p, const K1Launch &cfg, hipStream_t stream)
         return hipErrorInvalidValue;
     p.planes16 = (uint8_t)cfg.planes16;
     p.planes8 = (uint8_t)cfg.planes8;
-    uint64_t total = 0;
-    uint64_t per_tile = 0;
+    uint64_t per_tile[2] = {0, 0};
+    p.any_half = 0;
+    p.pad = 0;
     for (uint32_t i = 0; i < p.n_chunks; ++i) {
         const uint64_t n_e = (uint64_t)p.c[i].n_tokens * p.head_dim;
         if (n_e > 0x7FFFFFFFull) return hipErrorInvalidValue;  // element indices are 32-bit
         const uint64_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
-        const uint32_t prec = p.c[i].fmt & 0xFFu;
-        if (prec > kGSE8) return hipErrorInvalidValue;
+        const uint32_t prec = p.c[i].fmt & 0xFFu, part = (p.c[i].fmt >> 16) & 0xFFu;
+        if (prec > kGSE8 || part > kPartV) return hipErrorInvalidValue;
+        if (part != kPartKV) p.any_half = 1;
         const uint32_t planes = prec == kInt4 ? 4u : prec == kP16 ? cfg.planes16 : cfg.planes8;
-        p.item_start[i] = (uint32_t)per_tile;
-        per_tile += nblk * (4u / planes);
-        if (per_tile > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        for (uint32_t kv = 0; kv < 2; ++kv) {
+            p.item_start[kv][i] = (uint32_t)per_tile[kv];
+            if (part == kPartKV || part == kPartK + kv) per_tile[kv] += nblk * (4u / planes);
+            if (per_tile[kv] > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        }
     }
-    p.item_start[p.n_chunks] = (uint32_t)per_tile;
-    p.items_per_tile = (uint32_t)per_tile;
-    total = per_tile * p.n_tiles;
+    for (uint32_t kv = 0; kv < 2; ++kv) {
+        p.item_start[kv][p.n_chunks] = (uint32_t)per_tile[kv];
+        p.items_per_tile[kv] = (uint32_t)per_tile[kv];
+    }
+    const uint64_t per_layer = (per_tile[0] + per_tile[1]) * p.n_kv_heads;
+    const uint64_t total = per_layer * p.n_layers;
     if (total > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    p.items_per_layer = (uint32_t)per_layer;
     p.total_items = (uint32_t)total;
     if (total == 0) return hipSuccess;
     const uint32_t nwaves = cfg.threads >> 6;

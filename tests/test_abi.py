@@ -31,9 +31,29 @@ def test_strerror_and_version():
         assert B.strerror(code) and B.strerror(code) != "unknown error code"
 
 
-def test_struct_sizes_match_the_header_layout():
-    assert ctypes.sizeof(B.Config) == 52
-    assert ctypes.sizeof(B.PackedChunk) == 24
-    assert ctypes.sizeof(B.ChunkTrace) == 24
-    assert ctypes.sizeof(B.LoadStats) == 12 * 4 + 7 * 8
-    assert ctypes.sizeof(B.ChunkInfo) == 8 * 4 + 2 * 8 + 2 * 8
+def test_struct_sizes_match_the_header_layout(tmp_path):
+    """sizeof and field offsets as a C compiler sees include/ha_rag.h against the ctypes
+    mirror in the binding."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pairs = [("ha_rag_config", B.Config), ("ha_rag_packed_chunk", B.PackedChunk),
+             ("ha_rag_chunk_trace", B.ChunkTrace), ("ha_rag_load_stats", B.LoadStats),
+             ("ha_rag_chunk_info", B.ChunkInfo), ("ha_rag_launch_params", B.LaunchParams)]
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "ha_rag.h"', 'int main(void){']
+    for cname, cls in pairs:
+        lines.append(f'printf("{cname} %zu\\n", sizeof({cname}));')
+        for fname, _ in cls._fields_:
+            lines.append(f'printf("{cname}.{fname} %zu\\n", offsetof({cname}, {fname}));')
+    lines.append('return 0;}')
+    src = tmp_path / "sizes.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "sizes"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(root, "include"), str(src), "-o", str(exe)],
+                   check=True)
+    seen = dict(l.split() for l in subprocess.run([str(exe)], check=True, capture_output=True,
+                                                  text=True).stdout.splitlines())
+    for cname, cls in pairs:
+        assert int(seen[cname]) == ctypes.sizeof(cls), cname
+        for fname, _ in cls._fields_:
+            assert int(seen[f"{cname}.{fname}"]) == getattr(cls, fname).offset, (cname, fname)

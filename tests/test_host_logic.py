@@ -401,3 +401,102 @@ def test_slow_tiers_need_bounce_buffers():
     ctx.register_bounce(FAKE_BNC, slot * 2)
     st, _ = ctx.load_chunks([1], FAKE_HBM, 128)
     assert st["n_pageable_hits"] == 1 and st["bytes_host_copied"] == ctx.chunk_bytes(B.PREC_INT4, 128)
+
+
+# ---- keys-only / values-only chunks: Algorithm 1's 2n units --------------------------
+def _half_ctx(half_slots, n_slots=16, T=128):
+    ctx = B.Context(2, 2, 64, T, group_int8=64, group_int4=64, tau_gpu_ppm=500_000, dry_run=True,
+                    half_slots=half_slots)
+    for prec in (B.PREC_INT8, B.PREC_INT4):
+        whole = (ctx.chunk_bytes(prec, T) + 255) // 256 * 256
+        half = (ctx.chunk_bytes(prec, T, part=B.PART_K) + 255) // 256 * 256
+        slot = half if half_slots else whole
+        ctx.register_slab(B.TIER_HBM, prec, FAKE_HBM + prec * (1 << 32), slot * n_slots)
+        ctx.register_slab(B.TIER_PINNED, prec, FAKE_PIN + prec * (1 << 32), slot * n_slots)
+    ctx.register_staging(FAKE_STG, (ctx.chunk_bytes(B.PREC_INT8, T) + 255) // 256 * 256 * 4)
+    return ctx
+
+
+def test_half_chunk_sizes_are_half_the_oracle_whole():
+    ctx = _half_ctx(False)
+    for prec, bits in ((B.PREC_INT8, 8), (B.PREC_INT4, 4)):
+        for T in (1, 37, 128):
+            assert ctx.chunk_bytes(prec, T, part=B.PART_V) == codec.half_bytes(2, 2, 64, T, bits, 64)
+    ctx.destroy()
+
+
+def test_planes_fill_independently_and_must_close():
+    ctx = _half_ctx(False)
+    # documents 0..2: keys int8 under id 10+d, values int4 under id 20+d; document 3 whole (id 3)
+    toks = [100, 128, 64]
+    for d, t in enumerate(toks):
+        ctx.pool_insert_half(10 + d, B.PART_K, B.PREC_INT8, t, None, B.TIER_PINNED)
+        ctx.pool_insert_half(20 + d, B.PART_V, B.PREC_INT4, t, None, B.TIER_PINNED)
+    ctx.pool_insert(3, B.PREC_INT4, 50, None, B.TIER_PINNED)
+    info = ctx.pool_query(21)
+    assert info.part == B.PART_V and info.bytes == codec.half_bytes(2, 2, 64, 128, 4, 64)
+    assert ctx.pool_query(3).part == B.PART_KV
+
+    req = [10, 11, 20, 21, 3, 22, 12]             # K0 K1 V0 V1 whole V2 K2
+    st, tr = ctx.load_chunks(req, FAKE_HBM, 1000, tok_base=5, want_trace=True)
+    assert [t.tok_off for t in tr] == [5, 105, 5, 105, 233, 283, 283]
+    assert st["tokens"] == 100 + 128 + 50 + 64
+    assert st["bf16_bytes_written"] == st["tokens"] * 2 * 2 * 2 * 64 * 2
+    assert st["packed_bytes_read"] == sum(ctx.pool_query(c).bytes for c in req)
+    # every unit has its own access count (the AF entries of Algorithm 1)
+    assert ctx.pool_query(10).count == 1 and ctx.pool_query(20).count == 1
+
+    def refused(req, code, cap=1000):
+        before = [ctx.pool_query(c).count for c in (10, 20, 3)]
+        with pytest.raises(B.HaRagError) as e:
+            ctx.load_chunks(req, FAKE_HBM, cap)
+        assert e.value.code == code
+        assert [ctx.pool_query(c).count for c in (10, 20, 3)] == before   # nothing happened
+
+    refused([10], B.EINVAL)                        # keys without values
+    refused([10, 21], B.EINVAL)                    # planes end at different lengths (100 vs 128)
+    refused([10, 3, 20], B.EINVAL)                 # a whole chunk while the planes differ
+    refused([10, 20], B.ENOSPC, cap=99)
+    ctx.load_chunks([20, 10], FAKE_HBM, 100)       # values first is fine
+    # the same id cannot be a key chunk here and a value chunk there
+    with pytest.raises(B.HaRagError) as e:
+        ctx.pool_insert_half(10, B.PART_V, B.PREC_INT8, 100, None, B.TIER_HBM)
+    assert e.value.code == B.EFORMAT
+    for bad in (B.PART_KV, 3):
+        with pytest.raises(B.HaRagError) as e:
+            ctx.pool_insert_half(99, bad, B.PREC_INT8, 100, None, B.TIER_PINNED)
+        assert e.value.code == B.EINVAL
+    ctx.destroy()
+
+
+def test_batch_of_requests_with_halves_checks_each_request():
+    ctx = _half_ctx(False)
+    for d in range(2):
+        ctx.pool_insert_half(10 + d, B.PART_K, B.PREC_INT8, 64, None, B.TIER_PINNED)
+        ctx.pool_insert_half(20 + d, B.PART_V, B.PREC_INT4, 64, None, B.TIER_PINNED)
+    st, tr = ctx.load_batch([[10, 20], [21, 11, 10, 20]], [FAKE_HBM, FAKE_HBM + (1 << 30)], [64, 200],
+                            tok_base=[0, 7], want_trace=True)
+    assert [t.tok_off for t in tr] == [0, 0, 7, 7, 71, 71]
+    with pytest.raises(B.HaRagError) as e:         # second request leaves the value plane short
+        ctx.load_batch([[10, 20], [11, 10, 20]], [FAKE_HBM, FAKE_HBM + (1 << 30)], [64, 200])
+    assert e.value.code == B.EINVAL
+    ctx.destroy()
+
+
+def test_half_slots_pool_refuses_whole_chunks_and_promotes_units_on_their_own():
+    ctx = _half_ctx(True, n_slots=4)
+    with pytest.raises(B.HaRagError) as e:
+        ctx.pool_insert(1, B.PREC_INT4, 128, None, B.TIER_PINNED)
+    assert e.value.code == B.EFORMAT
+    # keys hot, values cold: only the key chunks are in GPU_LIST (top half of 4 units)
+    for d in range(2):
+        ctx.pool_insert_half(10 + d, B.PART_K, B.PREC_INT8, 128, None, B.TIER_PINNED)
+        ctx.pool_insert_half(20 + d, B.PART_V, B.PREC_INT4, 128, None, B.TIER_PINNED)
+    ctx.set_counts([10, 11, 20, 21], [50, 40, 3, 2])
+    ctx.rerank()
+    st, tr = ctx.load_chunks([10, 20, 11, 21], FAKE_HBM, 256, want_trace=True)
+    assert [t.promoted for t in tr] == [1, 0, 1, 0]
+    assert ctx.pool_query(10).in_hbm and not ctx.pool_query(20).in_hbm
+    st, tr = ctx.load_chunks([10, 20], FAKE_HBM, 256, want_trace=True)
+    assert [t.found_tier for t in tr] == [B.TIER_HBM, B.TIER_PINNED]
+    ctx.destroy()
