@@ -333,3 +333,38 @@ def rmse_bf16(a, b):
     b = _c(b, np.uint16).ravel()
     assert a.size == b.size
     return lib().orc_rmse_bf16(_p(a, C.c_uint16), _p(b, C.c_uint16), a.size)
+
+
+# ---- paged cache ---------------------------------------------------------------
+def paged_view(pages, layout, L, H, P, D):
+    """The physical page pool as an array indexed [page][l][kv][h][row in page][d].
+
+    pages is a flat uint16 array holding n_pages pages of P token rows.  layout
+    "page_major": each page is one contiguous [L][2][H][P][D] block; "tile_major": the pool
+    is [L][2][H][n_pages][P][D] (every tile's pages side by side).  Returns a view (writes
+    through)."""
+    n_pages = pages.size // (L * 2 * H * P * D)
+    if layout == "page_major":
+        return pages.reshape(n_pages, L, 2, H, P, D)
+    if layout == "tile_major":
+        return pages.reshape(L, 2, H, n_pages, P, D).transpose(3, 0, 1, 2, 4, 5)
+    raise ValueError(layout)
+
+
+def load_chunks_paged(packed_list, shape, tokens, bits_list, g_list, order, pages, layout, P,
+                      page_table, tok_base=0, parts=None):
+    """The request of load_chunks, written into a paged cache: token row r of the request
+    (r counted from 0, the chunks starting at tok_base) lives in physical page
+    page_table[r // P] at row r % P.  Rows the request does not cover are left alone.
+    Built from load_chunks itself: the contiguous cache is computed first and its rows are
+    then copied to their pages one by one."""
+    L, H, D = shape
+    virt, offs = load_chunks(packed_list, shape, tokens, bits_list, g_list, order,
+                             tok_base=tok_base, parts=parts)
+    end = virt.shape[3]
+    if end > len(page_table) * P:
+        raise ValueError("request does not fit in the page table")
+    view = paged_view(pages, layout, L, H, P, D)
+    for r in range(tok_base, end):
+        view[page_table[r // P], :, :, :, r % P, :] = virt[:, :, :, r, :]
+    return offs
