@@ -248,18 +248,34 @@ def run_hbm(args, B, wl, torch, name):
     outs = [torch.empty((L, 2, H, cap, D), dtype=torch.bfloat16, device="cuda") for _ in range(n_out)]
     stream = torch.cuda.Stream()
     reqs = [next_request() for _ in range(args.warmup + args.steps)]
+    if args.paged:
+        # the same bytes as n_out page pools; a fresh random page table per buffer
+        P = args.paged
+        n_pages = cap // P
+        tables = [torch.from_numpy(rng.permutation(n_pages).astype(np.int32)).cuda() for _ in range(n_out)]
+        caches = [B.paged_cache(outs[i], tables[i], P, n_pages, "page_major", L, H, D) for i in range(n_out)]
+        desc += f"; paged cache, {P}-token pages, page-major pool, random page table"
+
+        cache_of = {o.data_ptr(): c for o, c in zip(outs, caches)}
+
+        class _Paged:
+            def load_chunks(self, req, out, cap, stream=None):
+                ctx.load_chunks_paged(req, cache_of[out.data_ptr()], stream=stream)
+        loader = _Paged()
+    else:
+        loader = ctx
 
     step_bytes = int(sum(sum(per_token_bytes(L, H, D, b, g)) * T for b in mix))
     step_tokens = n_req * T
     with torch.cuda.stream(stream):
         for k in range(args.warmup):
-            ctx.load_chunks(reqs[k], outs[k % n_out], cap, stream=stream)
+            loader.load_chunks(reqs[k], outs[k % n_out], cap, stream=stream)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         e0.record(stream)
         for k in range(args.warmup, args.warmup + args.steps):
-            ctx.load_chunks(reqs[k], outs[k % n_out], cap, stream=stream)
+            loader.load_chunks(reqs[k], outs[k % n_out], cap, stream=stream)
         e1.record(stream)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
@@ -273,7 +289,7 @@ def run_hbm(args, B, wl, torch, name):
     with torch.cuda.stream(stream):
         for k in range(n_evt):
             evs[k][0].record(stream)
-            ctx.load_chunks(reqs[args.warmup + k], outs[k % n_out], cap, stream=stream)
+            loader.load_chunks(reqs[args.warmup + k], outs[k % n_out], cap, stream=stream)
             evs[k][1].record(stream)
         torch.cuda.synchronize()
     per = sorted(a.elapsed_time(b) for a, b in evs)
@@ -296,7 +312,7 @@ def run_hbm(args, B, wl, torch, name):
         "quantize_pack_kernel": k2,
         "roofline": {"bound": "hbm", "kernel": "k1_gather_dequant_scatter", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": args.traffic_bytes or (None if args.mix else MEASURED_TRAFFIC.get(name)),
+                     "traffic": args.traffic_bytes or (None if (args.mix or args.paged) else MEASURED_TRAFFIC.get(name)),
                      "kernel_ms": kernel_ms, "kernel_ms_median": per[len(per) // 2],
                      "kernel_ms_best": per[0],
                      "algorithmic_bytes_per_launch": step_bytes},
@@ -647,6 +663,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--paged", type=int, default=0, metavar="P",
+                    help="hbm8b / llama70b: write into a page-major paged cache of P-token pages "
+                         "(random page table) instead of the contiguous cache")
     ap.add_argument("--workload", default="hbm8b", choices=["hbm8b", "llama70b", "cold8b", "zipf", "tiers", "units8b"])
     ap.add_argument("--mix", default="", help="hbm8b: tags of one request, e.g. 8,e4m3,e5m2,4")
     ap.add_argument("--pool-chunks", type=int, default=0, help="chunks in the HBM pool (0 = default)")

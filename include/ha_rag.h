@@ -148,6 +148,35 @@ typedef struct ha_rag_chunk_info {
     const void *pinned_ptr;     /* slot address or NULL                       */
 } ha_rag_chunk_info;
 
+/* A paged KV cache as serving engines keep it: the request's token rows are cut into
+ * pages of `page_tokens` rows, and row r lives in physical page page_table[r /
+ * page_tokens] at row r % page_tokens.  The BF16 word of (layer l, K/V kv, head h, row r,
+ * dim d) is at
+ *   base + page * page_stride + ((l*2+kv)*H + h) * tile_stride
+ *        + (r % page_tokens) * D * 2 + d * 2            (all strides in bytes).
+ * Two common pools: every page one contiguous [L][2][H][page_tokens][D] block
+ * (page_stride = 2*L*H*page_tokens*D*2, tile_stride = page_tokens*D*2), or the pool as
+ * [L][2][H][n_pages][page_tokens][D] (tile_stride = n_pages*page_tokens*D*2,
+ * page_stride = page_tokens*D*2).  The paper hands the loaded chunks to prefill as one
+ * concatenated cache (Sec. 2.1); this is the same cache in the layout a paged attention
+ * kernel reads. */
+typedef struct ha_rag_paged_cache {
+    void *base;                 /* device pointer, 16-byte aligned                           */
+    const uint32_t *page_table; /* DEVICE pointer to n_table page ids, request order         */
+    uint32_t *bad_pages;        /* nullable device pointer to a u32 the kernel adds to: the
+                                   number of 16-byte stores it dropped because the table
+                                   named a page >= n_pages                                   */
+    uint64_t page_stride;       /* multiples of 16                                           */
+    uint64_t tile_stride;
+    uint32_t page_tokens;       /* page_tokens * D * 2 >= 1024 bytes                         */
+    uint32_t n_table;           /* table entries: the request may hold n_table * page_tokens
+                                   rows; n_table * page_tokens * D * 2 < 2^32                */
+    uint32_t n_pages;           /* physical pages in the pool (page ids are checked against
+                                   it on the device; the table itself is never read by the
+                                   host)                                                     */
+    uint32_t reserved;
+} ha_rag_paged_cache;
+
 /* What happened to one chunk of a load (Algorithm 2 step 2, per C_i). */
 typedef struct ha_rag_chunk_trace {
     uint64_t tok_off;     /* first token row of this chunk in the cache (of its plane,
@@ -260,6 +289,12 @@ int ha_rag_quantize_half(ha_rag_ctx *ctx, const void *src, uint32_t n_tokens, ui
  * differ in length, or if they differ at the end of the list. */
 int ha_rag_load_packed(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks, uint32_t n,
                        void *out, uint64_t cap_tokens, uint64_t tok_base, void *stream);
+
+/* The same into a paged cache.  Capacity is n_table * page_tokens rows; rows the chunks do
+ * not cover, and pages the table does not name, are not written.  EINVAL for a cache
+ * description that breaks the limits stated at ha_rag_paged_cache. */
+int ha_rag_load_packed_paged(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks, uint32_t n,
+                             const ha_rag_paged_cache *cache, uint64_t tok_base, void *stream);
 
 /* ---- pools (Algorithm 2's queueGPU / queuePIN / queuePAGE and the files) ------- */
 
@@ -381,6 +416,12 @@ int ha_rag_load_batch(ha_rag_ctx *ctx, const uint64_t *ids, const uint8_t *tags,
                       const uint32_t *request_starts, uint32_t n_requests, void *const *outs,
                       const uint64_t *cap_tokens, const uint64_t *tok_base, void *stream,
                       ha_rag_load_stats *stats, ha_rag_chunk_trace *trace);
+
+/* ha_rag_load_chunks with a paged cache as the destination (one request per call).
+ * Everything else -- lookup, placement, statistics, trace -- is the same. */
+int ha_rag_load_chunks_paged(ha_rag_ctx *ctx, const uint64_t *ids, const uint8_t *tags, uint32_t n,
+                             const ha_rag_paged_cache *cache, uint64_t tok_base, void *stream,
+                             ha_rag_load_stats *stats, ha_rag_chunk_trace *trace);
 
 #ifdef __cplusplus
 }

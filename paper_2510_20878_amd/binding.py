@@ -28,7 +28,8 @@ SYMBOLS = [
     "ha_rag_pool_evict", "ha_rag_pool_query", "ha_rag_pool_hbm_lru", "ha_rag_touch",
     "ha_rag_set_counts", "ha_rag_rerank", "ha_rag_get_rank", "ha_rag_load_chunks",
     "ha_rag_load_batch", "ha_rag_register_disk", "ha_rag_register_bounce", "ha_rag_pool_lru",
-    "ha_rag_quantize_half", "ha_rag_pool_insert_half",
+    "ha_rag_quantize_half", "ha_rag_pool_insert_half", "ha_rag_load_packed_paged",
+    "ha_rag_load_chunks_paged",
 ]
 
 
@@ -47,6 +48,13 @@ class LaunchParams(C.Structure):
 class PackedChunk(C.Structure):
     _fields_ = [("packed", C.c_void_p), ("n_tokens", C.c_uint32), ("prec", C.c_uint32),
                 ("group", C.c_uint32), ("part", C.c_uint32)]
+
+
+class PagedCache(C.Structure):
+    _fields_ = [("base", C.c_void_p), ("page_table", C.c_void_p), ("bad_pages", C.c_void_p),
+                ("page_stride", C.c_uint64), ("tile_stride", C.c_uint64),
+                ("page_tokens", C.c_uint32), ("n_table", C.c_uint32), ("n_pages", C.c_uint32),
+                ("reserved", C.c_uint32)]
 
 
 class ChunkInfo(C.Structure):
@@ -120,6 +128,9 @@ def lib():
             "ha_rag_quantize_half": (C.c_int, [vp, vp, u32, u32, u32, vp, vp, vp]),
             "ha_rag_pool_insert_half": (C.c_int, [vp, u64, u32, u32, u32, vp, C.c_int, u32, vp]),
             "ha_rag_load_packed": (C.c_int, [vp, P(PackedChunk), u32, vp, u64, u64, vp]),
+            "ha_rag_load_packed_paged": (C.c_int, [vp, P(PackedChunk), u32, P(PagedCache), u64, vp]),
+            "ha_rag_load_chunks_paged": (C.c_int, [vp, P(u64), P(C.c_uint8), u32, P(PagedCache), u64, vp,
+                                                   P(LoadStats), P(ChunkTrace)]),
             "ha_rag_register_slab": (C.c_int, [vp, u32, u32, vp, sz]),
             "ha_rag_register_staging": (C.c_int, [vp, vp, sz]),
             "ha_rag_register_bounce": (C.c_int, [vp, vp, sz]),
@@ -145,6 +156,25 @@ def lib():
             f.restype, f.argtypes = res, args
         _lib = L
     return _lib
+
+
+def paged_cache(base, page_table, page_tokens, n_pages, layout, n_layers, n_kv_heads, head_dim,
+                bad_pages=None, n_table=None):
+    """A PagedCache for one of the two pool layouts the header describes: "page_major"
+    (every page one [L][2][H][P][D] block) or "tile_major" ([L][2][H][n_pages][P][D])."""
+    row = head_dim * 2
+    if layout == "page_major":
+        tile_stride = page_tokens * row
+        page_stride = 2 * n_layers * n_kv_heads * tile_stride
+    elif layout == "tile_major":
+        page_stride = page_tokens * row
+        tile_stride = n_pages * page_stride
+    else:
+        raise ValueError(layout)
+    if n_table is None:
+        n_table = page_table.numel() if hasattr(page_table, "numel") else len(page_table)
+    return PagedCache(_addr(base), _addr(page_table), _addr(bad_pages), page_stride, tile_stride,
+                      page_tokens, n_table, n_pages, 0)
 
 
 def strerror(code):
@@ -267,6 +297,25 @@ class Context:
             arr[i] = PackedChunk(_addr(p), t, prec, g, ch[4] if len(ch) > 4 else PART_KV)
         self._chk(lib().ha_rag_load_packed(self._h, arr, len(chunks), _addr(out), cap_tokens,
                                            tok_base, _stream(stream)), "ha_rag_load_packed")
+
+    def load_packed_paged(self, chunks, cache, tok_base=0, stream=None):
+        """chunks as in load_packed; cache: a PagedCache (see paged_cache())."""
+        arr = (PackedChunk * max(len(chunks), 1))()
+        for i, ch in enumerate(chunks):
+            p, t, prec, g = ch[:4]
+            arr[i] = PackedChunk(_addr(p), t, prec, g, ch[4] if len(ch) > 4 else PART_KV)
+        self._chk(lib().ha_rag_load_packed_paged(self._h, arr, len(chunks), C.byref(cache), tok_base,
+                                                 _stream(stream)), "ha_rag_load_packed_paged")
+
+    def load_chunks_paged(self, ids, cache, tok_base=0, tags=None, stream=None, want_trace=False):
+        n = len(ids)
+        st = LoadStats()
+        tr = (ChunkTrace * max(n, 1))() if want_trace else None
+        tg = (C.c_uint8 * max(n, 1))(*tags) if tags is not None else None
+        self._chk(lib().ha_rag_load_chunks_paged(self._h, _u64s(ids), tg, n, C.byref(cache), tok_base,
+                                                 _stream(stream), C.byref(st), tr),
+                  "ha_rag_load_chunks_paged")
+        return st.as_dict(), (list(tr[:n]) if want_trace else None)
 
     def register_slab(self, tier, prec, base, nbytes=None):
         if nbytes is None:

@@ -431,7 +431,22 @@ struct Request {
     uint32_t begin, end;
     uint8_t *out;
     uint64_t cap, base;
+    const ha_rag_paged_cache *paged = nullptr;  // set: `out` is unused, cap = table entries * P
 };
+
+// Checks a paged-cache description and returns the token rows its table covers.
+int check_paged(const ha_rag_ctx *c, const ha_rag_paged_cache *pg, uint64_t *cap_tokens)
+{
+    if (!pg || !pg->base || !pg->page_table || pg->page_tokens == 0 || pg->n_pages == 0) return HA_RAG_EINVAL;
+    if (((uintptr_t)pg->base & 15u) || ((uintptr_t)pg->page_table & 3u) || ((uintptr_t)pg->bad_pages & 3u))
+        return HA_RAG_EINVAL;
+    if ((pg->page_stride & 15u) || (pg->tile_stride & 15u)) return HA_RAG_EINVAL;
+    const uint64_t page_bytes = (uint64_t)pg->page_tokens * c->cfg.head_dim * 2ull;
+    if (page_bytes < 1024u) return HA_RAG_EINVAL;  // a wave's KiB may cross one page boundary only
+    if ((uint64_t)pg->n_table * page_bytes > 0xFFFFFFFFull) return HA_RAG_EINVAL;
+    *cap_tokens = (uint64_t)pg->n_table * pg->page_tokens;
+    return HA_RAG_OK;
+}
 
 // What pass A decided for one chunk of a load.
 struct Action {
@@ -452,8 +467,13 @@ K1Chunk make_desc(const ha_rag_ctx *c, const Chunk &ch, const uint8_t *src, cons
     K1Chunk d;
     const uint64_t D = c->cfg.head_dim;
     d.src = src;
-    d.out = rq.out + tok_off * D * 2ull;
-    d.out_tile_stride = rq.cap * D * 2ull;
+    if (rq.paged) {  // the row's byte offset in the request's virtual tile rides in the pointer
+        d.out = reinterpret_cast<uint8_t *>((uintptr_t)(tok_off * D * 2ull));
+        d.out_tile_stride = 0;
+    } else {
+        d.out = rq.out + tok_off * D * 2ull;
+        d.out_tile_stride = rq.cap * D * 2ull;
+    }
     d.n_tokens = ch.n_tokens;
     const uint32_t g = c->group_of(ch.prec);
     d.fmt = ch.prec | ((g ? log2u(g) : 0u) << 8) | (ch.part << 16);
@@ -480,13 +500,26 @@ int push(ha_rag_ctx *c, Batch &b, const K1Chunk &d, hipStream_t s, uint32_t *lau
     return HA_RAG_OK;
 }
 
-void init_batch(const ha_rag_ctx *c, Batch &b)
+void init_batch(const ha_rag_ctx *c, Batch &b, const ha_rag_paged_cache *pg = nullptr)
 {
     b.p.n_layers = c->cfg.n_layers;
     b.p.n_kv_heads = c->cfg.n_kv_heads;
     b.p.head_dim = c->cfg.head_dim;
     b.p.n_chunks = 0;
     b.p.total_items = 0;
+    std::memset(&b.p.paged, 0, sizeof b.p.paged);
+    if (pg) {
+        K1Paged &k = b.p.paged;
+        k.enabled = 1;
+        k.base = static_cast<uint8_t *>(pg->base);
+        k.page_table = pg->page_table;
+        k.bad_pages = pg->bad_pages;
+        k.page_stride = pg->page_stride;
+        k.tile_stride = pg->tile_stride;
+        k.page_bytes = pg->page_tokens * c->cfg.head_dim * 2u;
+        k.n_table = pg->n_table;
+        k.n_pages = pg->n_pages;
+    }
 }
 
 // Next bounce buffer, once the host -> device copy that last read it has finished.
@@ -600,7 +633,8 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     for (uint32_t r = 0; r < n_req; ++r) {
         const Request &rq = reqs[r];
         if (rq.end < rq.begin || rq.end > n) return HA_RAG_EINVAL;
-        if (rq.end > rq.begin && (rq.out == nullptr || ((uintptr_t)rq.out & 15u))) return HA_RAG_EINVAL;
+        if (rq.end > rq.begin && !rq.paged && (rq.out == nullptr || ((uintptr_t)rq.out & 15u)))
+            return HA_RAG_EINVAL;
         PlaneCursor cur(0);
         for (uint32_t i = rq.begin; i < rq.end; ++i) {
             Chunk *ch = find_chunk(c, ids[i], &cis[i]);
@@ -794,7 +828,7 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     }
 
     Batch batch;
-    init_batch(c, batch);
+    init_batch(c, batch, n_req == 1 ? reqs[0].paged : nullptr);
     for (const Action &a : acts) {
         if (a.kind != Action::HOT_EARLY) continue;
         const Chunk &ch = c->chunks[a.ci];
@@ -1038,11 +1072,17 @@ int ha_rag_quantize_half(ha_rag_ctx *c, const void *src, uint32_t n_tokens, uint
     return quantize_impl(c, src, n_tokens, prec, group, dst, saturated, stream, kPartK);
 }
 
-int ha_rag_load_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, uint32_t n, void *out,
-                       uint64_t cap_tokens, uint64_t tok_base, void *stream)
+static int load_packed_impl(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, uint32_t n, void *out,
+                            uint64_t cap_tokens, uint64_t tok_base, void *stream,
+                            const ha_rag_paged_cache *paged)
 {
-    if (!c || (n && (!chunks || !out)) || n > HA_RAG_MAX_REQUEST_CHUNKS) return HA_RAG_EINVAL;
-    if ((uintptr_t)out & 15u) return HA_RAG_EINVAL;
+    if (!c || (n && !chunks) || n > HA_RAG_MAX_REQUEST_CHUNKS) return HA_RAG_EINVAL;
+    if (paged) {
+        int rc = check_paged(c, paged, &cap_tokens);
+        if (rc) return rc;
+    } else if ((n && !out) || ((uintptr_t)out & 15u)) {
+        return HA_RAG_EINVAL;
+    }
     const uint64_t D = c->cfg.head_dim;
     PlaneCursor chk(0);
     for (uint32_t i = 0; i < n; ++i) {
@@ -1059,7 +1099,7 @@ int ha_rag_load_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, uint32_
     if (cap_tokens * D > 0x7FFFFFFFFFFFull) return HA_RAG_EINVAL;
     std::lock_guard<std::mutex> g(c->mu);
     Batch batch;
-    init_batch(c, batch);
+    init_batch(c, batch, paged);
     PlaneCursor cur(tok_base);
     for (uint32_t i = 0; i < n; ++i) {
         const ha_rag_packed_chunk &pc = chunks[i];
@@ -1068,14 +1108,32 @@ int ha_rag_load_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, uint32_
         (void)cur.place(pc.part, pc.n_tokens, &off);  // checked above
         K1Chunk d;
         d.src = static_cast<const uint8_t *>(pc.packed);
-        d.out = static_cast<uint8_t *>(out) + off * D * 2ull;
-        d.out_tile_stride = cap_tokens * D * 2ull;
+        if (paged) {
+            d.out = reinterpret_cast<uint8_t *>((uintptr_t)(off * D * 2ull));
+            d.out_tile_stride = 0;
+        } else {
+            d.out = static_cast<uint8_t *>(out) + off * D * 2ull;
+            d.out_tile_stride = cap_tokens * D * 2ull;
+        }
         d.n_tokens = pc.n_tokens;
         d.fmt = pc.prec | ((has_meta(pc.prec) ? log2u(pc.group) : 0u) << 8) | (pc.part << 16);
         int rc = push(c, batch, d, (hipStream_t)stream, nullptr);
         if (rc) return rc;
     }
     return flush(c, batch, (hipStream_t)stream, nullptr);
+}
+
+int ha_rag_load_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, uint32_t n, void *out,
+                       uint64_t cap_tokens, uint64_t tok_base, void *stream)
+{
+    return load_packed_impl(c, chunks, n, out, cap_tokens, tok_base, stream, nullptr);
+}
+
+int ha_rag_load_packed_paged(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, uint32_t n,
+                             const ha_rag_paged_cache *cache, uint64_t tok_base, void *stream)
+{
+    if (!cache) return HA_RAG_EINVAL;
+    return load_packed_impl(c, chunks, n, nullptr, 0, tok_base, stream, cache);
 }
 
 int ha_rag_register_slab(ha_rag_ctx *c, uint32_t tier, uint32_t prec, void *base, size_t bytes)
@@ -1413,7 +1471,20 @@ int ha_rag_load_chunks(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, 
     if (!c || (n && !ids) || n > HA_RAG_MAX_REQUEST_CHUNKS) return HA_RAG_EINVAL;
     if (cap_tokens * (uint64_t)c->cfg.head_dim > 0x7FFFFFFFFFFFull) return HA_RAG_EINVAL;
     std::lock_guard<std::mutex> g(c->mu);
-    Request rq{0, n, static_cast<uint8_t *>(out), cap_tokens, tok_base};
+    Request rq{0, n, static_cast<uint8_t *>(out), cap_tokens, tok_base, nullptr};
+    return load_impl(c, ids, tags, &rq, 1, n, (hipStream_t)stream, stats, trace);
+}
+
+int ha_rag_load_chunks_paged(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, uint32_t n,
+                             const ha_rag_paged_cache *cache, uint64_t tok_base, void *stream,
+                             ha_rag_load_stats *stats, ha_rag_chunk_trace *trace)
+{
+    if (!c || !cache || (n && !ids) || n > HA_RAG_MAX_REQUEST_CHUNKS) return HA_RAG_EINVAL;
+    uint64_t cap = 0;
+    int rc = check_paged(c, cache, &cap);
+    if (rc) return rc;
+    std::lock_guard<std::mutex> g(c->mu);
+    Request rq{0, n, nullptr, cap, tok_base, cache};
     return load_impl(c, ids, tags, &rq, 1, n, (hipStream_t)stream, stats, trace);
 }
 
@@ -1430,7 +1501,7 @@ int ha_rag_load_batch(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags,
         if (request_starts[r + 1] < request_starts[r]) return HA_RAG_EINVAL;
         if (cap_tokens[r] * (uint64_t)c->cfg.head_dim > 0x7FFFFFFFFFFFull) return HA_RAG_EINVAL;
         reqs[r] = Request{request_starts[r], request_starts[r + 1], static_cast<uint8_t *>(outs[r]),
-                          cap_tokens[r], tok_base ? tok_base[r] : 0};
+                          cap_tokens[r], tok_base ? tok_base[r] : 0, nullptr};
     }
     std::lock_guard<std::mutex> g(c->mu);
     return load_impl(c, ids, tags, reqs.data(), n_requests, n, (hipStream_t)stream, stats, trace);

@@ -16,8 +16,10 @@ constexpr uint32_t kMaxLaunchChunks = 64; // chunk descriptors per kernel launch
 // argument buffer, so no device-side descriptor table exists.
 struct K1Chunk {
     const uint8_t *src;        // packed chunk (tile records back to back)
-    uint8_t *out;              // cache address of tile 0, token row tok_off, dim 0
-    uint64_t out_tile_stride;  // bytes between consecutive tiles of the cache
+    uint8_t *out;              // cache address of tile 0, token row tok_off, dim 0; for a paged
+                               // launch: byte offset of row tok_off in the request's virtual
+                               // tile (tok_off * head_dim * 2), carried in the pointer
+    uint64_t out_tile_stride;  // bytes between consecutive tiles of the cache (unused if paged)
     uint32_t n_tokens;
     uint32_t fmt;              // Prec | log2(group) << 8 | part << 16
 };
@@ -29,6 +31,21 @@ enum Part : uint32_t { kPartKV = 0, kPartK = 1, kPartV = 2 };
 // The unit of work of one wave is an *item*: `planes` of the four 1024-byte output
 // planes of one block (int4: always all four, fed by one 16-byte load per lane;
 // int8 and FP8: two or four; 16-bit: one, two or four).
+// A paged cache: token row r of the request lives in physical page page_table[r / P] at row
+// r % P; byte address of (cache tile, row, dim 0) =
+// base + page * page_stride + tile * tile_stride + (r % P) * head_dim * 2.
+struct K1Paged {
+    uint8_t *base;
+    const uint32_t *page_table;  // device
+    uint32_t *bad_pages;         // device counter of stores dropped for a page id >= n_pages, or null
+    uint64_t page_stride, tile_stride;
+    uint32_t page_bytes;         // P * head_dim * 2: one tile's rows of one page, >= 1024
+    uint32_t n_table, n_pages;
+    uint32_t enabled;
+    uint32_t page_shift;         // log2(page_bytes) if that is a power of two, else 0 (set by launch_k1)
+    uint32_t pad;
+};
+
 struct K1Params {
     uint32_t n_layers;     // the cache has n_layers * 2 * n_kv_heads tiles
     uint32_t n_kv_heads;
@@ -43,6 +60,7 @@ struct K1Params {
     // per plane (keys, values): prefix sum over chunks of the items a chunk has in one
     // tile of that plane (none if the chunk does not hold that plane)
     uint32_t item_start[2][kMaxLaunchChunks + 1];
+    K1Paged paged;
     K1Chunk c[kMaxLaunchChunks];
 };
 

@@ -148,7 +148,7 @@ __device__ __forceinline__ u32x4 ld16s(const uint8_t *p)
     return *reinterpret_cast<const u32x4 *>(p);
 }
 
-template <bool NT_ST, bool NT_LD>
+template <bool NT_ST, bool NT_LD, bool PAGED>
 __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params p)
 {
     const uint32_t nwaves = blockDim.x >> 6;
@@ -199,8 +199,54 @@ __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params
 
     const uint32_t lane_b = lane * 16;
     const uint32_t e = blk * kBlockElems + lane * 8 + j0 * 512;  // element of plane j0
-    uint8_t *o = c.out + (uint64_t)out_tile * c.out_tile_stride + (uint64_t)blk * 4096u +
-                 j0 * 1024u + lane_b;
+    // where plane k of this item goes: one contiguous KiB per wave in a plain cache
+    uint8_t *o = nullptr;
+    uint8_t *op[4] = {nullptr, nullptr, nullptr, nullptr};
+    uint32_t dropped = 0;  // paged: stores of this lane that had no valid page
+    if (!PAGED) {
+        o = c.out + (uint64_t)out_tile * c.out_tile_stride + (uint64_t)blk * 4096u + j0 * 1024u +
+            lane_b;
+    }
+    // Paged cache: called once per item after its payload loads have been issued, so that the
+    // page-table reads overlap them.
+    auto locate = [&]() {
+        if (!PAGED) return;
+        // In a paged cache the KiB of a wave may straddle one page boundary (page_bytes >= 1024).
+        // The wave's first byte is located with one division; the next planes step by 1024.
+        const K1Paged &pc = p.paged;
+        const uint32_t vb = (uint32_t)(uintptr_t)c.out + blk * 4096u + j0 * 1024u;
+        uint32_t pg = pc.page_shift ? vb >> pc.page_shift : vb / pc.page_bytes;
+        uint32_t within = vb - pg * pc.page_bytes;
+        uint8_t *tile_base = pc.base + (uint64_t)out_tile * pc.tile_stride;
+        const uint32_t last = pc.n_table - 1u;
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) {
+            if (k >= planes) break;
+            // the two pages this KiB can touch: wave-uniform table reads and base addresses
+            const uint32_t id0 = pc.page_table[pg < last ? pg : last];
+            const uint32_t id1 = pc.page_table[pg + 1u < last ? pg + 1u : last];
+            uint8_t *b0 = tile_base + (uint64_t)id0 * pc.page_stride;
+            uint8_t *b1 = tile_base + (uint64_t)id1 * pc.page_stride - pc.page_bytes;
+            const uint32_t w = within + lane_b;
+            const bool cross = w >= pc.page_bytes;
+            const bool live = e + k * 512u < n_e;  // rows past the chunk's end have no page
+            const bool ok = pg + (cross ? 1u : 0u) <= last && (cross ? id1 : id0) < pc.n_pages;
+            if (live && ok) op[k] = (cross ? b1 : b0) + w;
+            else if (live) ++dropped;
+            within += 1024u;
+            if (within >= pc.page_bytes) {
+                within -= pc.page_bytes;
+                ++pg;
+            }
+        }
+    };
+    auto put = [&](uint32_t k, u32x4 v) {
+        if (PAGED) {
+            if (op[k]) st16<NT_ST>(op[k], v);
+        } else if (e + k * 512u < n_e) {
+            st16<NT_ST>(o + k * 1024u, v);
+        }
+    };
 
     if (prec == kInt4) {
         const uint32_t meta_blk = 8192u >> gsh;
@@ -208,10 +254,11 @@ __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params
         const uint8_t *meta = pay + (uint64_t)nblk * 1024u;
         const u32x4 w = ld16s<NT_LD>(pay + (uint64_t)blk * 1024u + lane_b);
         const u32x4 m = ld16(meta + (uint64_t)blk * meta_blk + ((lane * 8) >> gsh) * 16u);
-        if (e < n_e) st16<NT_ST>(o, dequant_octet4(w.x, m.x));
-        if (e + 512 < n_e) st16<NT_ST>(o + 1024, dequant_octet4(w.y, m.y));
-        if (e + 1024 < n_e) st16<NT_ST>(o + 2048, dequant_octet4(w.z, m.z));
-        if (e + 1536 < n_e) st16<NT_ST>(o + 3072, dequant_octet4(w.w, m.w));
+        locate();
+        put(0, dequant_octet4(w.x, m.x));
+        put(1, dequant_octet4(w.y, m.y));
+        put(2, dequant_octet4(w.z, m.z));
+        put(3, dequant_octet4(w.w, m.w));
     } else if (prec == kInt8) {
         const uint32_t meta_blk = 8192u >> gsh;
         const uint8_t *pay = c.src + (uint64_t)tile * ((uint64_t)nblk * (2048u + meta_blk));
@@ -221,15 +268,17 @@ __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params
         if (planes == 4) {
             const u32x4 w0 = ld16s<NT_LD>(b), w1 = ld16s<NT_LD>(b + 1024);
             const u32x4 m = ld16(mp);
-            if (e < n_e) st16<NT_ST>(o, dequant_octet8(w0.x, w0.y, m.x));
-            if (e + 512 < n_e) st16<NT_ST>(o + 1024, dequant_octet8(w0.z, w0.w, m.y));
-            if (e + 1024 < n_e) st16<NT_ST>(o + 2048, dequant_octet8(w1.x, w1.y, m.z));
-            if (e + 1536 < n_e) st16<NT_ST>(o + 3072, dequant_octet8(w1.z, w1.w, m.w));
+            locate();
+            put(0, dequant_octet8(w0.x, w0.y, m.x));
+            put(1, dequant_octet8(w0.z, w0.w, m.y));
+            put(2, dequant_octet8(w1.x, w1.y, m.z));
+            put(3, dequant_octet8(w1.z, w1.w, m.w));
         } else {  // two planes: one 16-byte load, the two meta entries of those planes
             const u32x4 w = ld16s<NT_LD>(b + (j0 >> 1) * 1024u);
             const uint2 m = *reinterpret_cast<const uint2 *>(mp + j0 * 4u);
-            if (e < n_e) st16<NT_ST>(o, dequant_octet8(w.x, w.y, m.x));
-            if (e + 512 < n_e) st16<NT_ST>(o + 1024, dequant_octet8(w.z, w.w, m.y));
+            locate();
+            put(0, dequant_octet8(w.x, w.y, m.x));
+            put(1, dequant_octet8(w.z, w.w, m.y));
         }
     } else if (prec == kE4M3 || prec == kE5M2) {
         const uint8_t *b = c.src + (uint64_t)tile * ((uint64_t)nblk * 2048u) +
@@ -237,14 +286,16 @@ __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params
         const bool e5 = prec == kE5M2;
         if (planes == 4) {
             const u32x4 w0 = ld16s<NT_LD>(b), w1 = ld16s<NT_LD>(b + 1024);
-            if (e < n_e) st16<NT_ST>(o, e5 ? decode_octet_fp8<true>(w0.x, w0.y) : decode_octet_fp8<false>(w0.x, w0.y));
-            if (e + 512 < n_e) st16<NT_ST>(o + 1024, e5 ? decode_octet_fp8<true>(w0.z, w0.w) : decode_octet_fp8<false>(w0.z, w0.w));
-            if (e + 1024 < n_e) st16<NT_ST>(o + 2048, e5 ? decode_octet_fp8<true>(w1.x, w1.y) : decode_octet_fp8<false>(w1.x, w1.y));
-            if (e + 1536 < n_e) st16<NT_ST>(o + 3072, e5 ? decode_octet_fp8<true>(w1.z, w1.w) : decode_octet_fp8<false>(w1.z, w1.w));
+            locate();
+            put(0, e5 ? decode_octet_fp8<true>(w0.x, w0.y) : decode_octet_fp8<false>(w0.x, w0.y));
+            put(1, e5 ? decode_octet_fp8<true>(w0.z, w0.w) : decode_octet_fp8<false>(w0.z, w0.w));
+            put(2, e5 ? decode_octet_fp8<true>(w1.x, w1.y) : decode_octet_fp8<false>(w1.x, w1.y));
+            put(3, e5 ? decode_octet_fp8<true>(w1.z, w1.w) : decode_octet_fp8<false>(w1.z, w1.w));
         } else {
             const u32x4 w = ld16s<NT_LD>(b + (j0 >> 1) * 1024u);
-            if (e < n_e) st16<NT_ST>(o, e5 ? decode_octet_fp8<true>(w.x, w.y) : decode_octet_fp8<false>(w.x, w.y));
-            if (e + 512 < n_e) st16<NT_ST>(o + 1024, e5 ? decode_octet_fp8<true>(w.z, w.w) : decode_octet_fp8<false>(w.z, w.w));
+            locate();
+            put(0, e5 ? decode_octet_fp8<true>(w.x, w.y) : decode_octet_fp8<false>(w.x, w.y));
+            put(1, e5 ? decode_octet_fp8<true>(w.z, w.w) : decode_octet_fp8<false>(w.z, w.w));
         }
     } else if (prec == kGSE8) {
         const uint8_t *rec = c.src + (uint64_t)tile * ((uint64_t)nblk * 2048u + 16u);
@@ -254,33 +305,41 @@ __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params
         const int top = (int)(int8_t)((range >> 8) & 0xFFu) - 2;    // e_hi - 2
         if (planes == 4) {
             const u32x4 w0 = ld16s<NT_LD>(b), w1 = ld16s<NT_LD>(b + 1024);
-            if (e < n_e) st16<NT_ST>(o, decode_octet_gse8(w0.x, w0.y, base, top));
-            if (e + 512 < n_e) st16<NT_ST>(o + 1024, decode_octet_gse8(w0.z, w0.w, base, top));
-            if (e + 1024 < n_e) st16<NT_ST>(o + 2048, decode_octet_gse8(w1.x, w1.y, base, top));
-            if (e + 1536 < n_e) st16<NT_ST>(o + 3072, decode_octet_gse8(w1.z, w1.w, base, top));
+            locate();
+            put(0, decode_octet_gse8(w0.x, w0.y, base, top));
+            put(1, decode_octet_gse8(w0.z, w0.w, base, top));
+            put(2, decode_octet_gse8(w1.x, w1.y, base, top));
+            put(3, decode_octet_gse8(w1.z, w1.w, base, top));
         } else {
             const u32x4 w = ld16s<NT_LD>(b + (j0 >> 1) * 1024u);
-            if (e < n_e) st16<NT_ST>(o, decode_octet_gse8(w.x, w.y, base, top));
-            if (e + 512 < n_e) st16<NT_ST>(o + 1024, decode_octet_gse8(w.z, w.w, base, top));
+            locate();
+            put(0, decode_octet_gse8(w.x, w.y, base, top));
+            put(1, decode_octet_gse8(w.z, w.w, base, top));
         }
     } else {
         const uint8_t *b = c.src + (uint64_t)tile * ((uint64_t)nblk * 4096u) +
                            (uint64_t)blk * 4096u + j0 * 1024u + lane_b;
         if (planes == 1) {
-            if (e < n_e) st16<NT_ST>(o, ld16s<NT_LD>(b));
+            const u32x4 w0 = ld16s<NT_LD>(b);
+            locate();
+            put(0, w0);
         } else if (planes == 2) {
             const u32x4 w0 = ld16s<NT_LD>(b), w1 = ld16s<NT_LD>(b + 1024);
-            if (e < n_e) st16<NT_ST>(o, w0);
-            if (e + 512 < n_e) st16<NT_ST>(o + 1024, w1);
+            locate();
+            put(0, w0);
+            put(1, w1);
         } else {
             u32x4 w[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) w[j] = ld16s<NT_LD>(b + j * 1024);
+            locate();
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (e + j * 512 < n_e) st16<NT_ST>(o + j * 1024, w[j]);
+            for (int j = 0; j < 4; ++j) put(j, w[j]);
         }
     }
+    // reported last, so that no store precedes the page-table reads above (they can then be
+    // scalar loads)
+    if (PAGED && dropped && p.paged.bad_pages) atomicAdd(p.paged.bad_pages, dropped);
 }
 
 hipError_t launch_k1(K1Params &p, const K1Launch &cfg, hipStream_t stream)
@@ -292,6 +351,16 @@ hipError_t launch_k1(K1Params &p, const K1Launch &cfg, hipStream_t stream)
     if ((cfg.planes16 != 1 && cfg.planes16 != 2 && cfg.planes16 != 4) ||
         (cfg.planes8 != 2 && cfg.planes8 != 4))
         return hipErrorInvalidValue;
+    if (p.paged.enabled) {
+        const K1Paged &pc = p.paged;
+        if (!pc.base || !pc.page_table || pc.n_table == 0 || pc.page_bytes < 1024u || (pc.page_bytes & 15u) ||
+            ((uintptr_t)pc.base & 15u) || (pc.page_stride & 15u) || (pc.tile_stride & 15u) ||
+            (uint64_t)pc.n_table * pc.page_bytes > 0xFFFFFFFFull)
+            return hipErrorInvalidValue;
+        p.paged.page_shift = 0;
+        if ((pc.page_bytes & (pc.page_bytes - 1u)) == 0)
+            while ((1u << p.paged.page_shift) < pc.page_bytes) ++p.paged.page_shift;
+    }
     p.planes16 = (uint8_t)cfg.planes16;
     p.planes8 = (uint8_t)cfg.planes8;
     uint64_t per_tile[2] = {0, 0};
@@ -324,12 +393,16 @@ hipError_t launch_k1(K1Params &p, const K1Launch &cfg, hipStream_t stream)
     const uint32_t nwaves = cfg.threads >> 6;
     const uint32_t wgs = (uint32_t)((total + nwaves - 1) / nwaves);
     dim3 grid(wgs), block(cfg.threads);
-    if (cfg.nt_store) {
-        if (cfg.nt_load) hipLaunchKernelGGL((k1_gather_dequant_scatter<true, true>), grid, block, 0, stream, p);
-        else hipLaunchKernelGGL((k1_gather_dequant_scatter<true, false>), grid, block, 0, stream, p);
-    } else {
-        if (cfg.nt_load) hipLaunchKernelGGL((k1_gather_dequant_scatter<false, true>), grid, block, 0, stream, p);
-        else hipLaunchKernelGGL((k1_gather_dequant_scatter<false, false>), grid, block, 0, stream, p);
+    const int variant = (cfg.nt_store ? 4 : 0) | (cfg.nt_load ? 2 : 0) | (p.paged.enabled ? 1 : 0);
+    switch (variant) {
+    case 0: hipLaunchKernelGGL((k1_gather_dequant_scatter<false, false, false>), grid, block, 0, stream, p); break;
+    case 1: hipLaunchKernelGGL((k1_gather_dequant_scatter<false, false, true>), grid, block, 0, stream, p); break;
+    case 2: hipLaunchKernelGGL((k1_gather_dequant_scatter<false, true, false>), grid, block, 0, stream, p); break;
+    case 3: hipLaunchKernelGGL((k1_gather_dequant_scatter<false, true, true>), grid, block, 0, stream, p); break;
+    case 4: hipLaunchKernelGGL((k1_gather_dequant_scatter<true, false, false>), grid, block, 0, stream, p); break;
+    case 5: hipLaunchKernelGGL((k1_gather_dequant_scatter<true, false, true>), grid, block, 0, stream, p); break;
+    case 6: hipLaunchKernelGGL((k1_gather_dequant_scatter<true, true, false>), grid, block, 0, stream, p); break;
+    default: hipLaunchKernelGGL((k1_gather_dequant_scatter<true, true, true>), grid, block, 0, stream, p); break;
     }
     return hipGetLastError();
 }

@@ -500,3 +500,35 @@ def test_half_slots_pool_refuses_whole_chunks_and_promotes_units_on_their_own():
     st, tr = ctx.load_chunks([10, 20], FAKE_HBM, 256, want_trace=True)
     assert [t.found_tier for t in tr] == [B.TIER_HBM, B.TIER_PINNED]
     ctx.destroy()
+
+
+# ---- paged destination ------------------------------------------------------------------
+def test_paged_cache_description_is_checked():
+    ctx = _ctx(2, 8, 500_000)                     # L2 H2 D64, int4 chunks of up to 128 tokens
+    for c in range(4):
+        ctx.pool_insert(c, B.PREC_INT4, 100, None, B.TIER_PINNED)
+
+    def cache(**kw):
+        a = dict(base=FAKE_HBM, page_table=FAKE_HBM + (1 << 20), page_tokens=16, n_pages=64,
+                 layout="page_major", n_layers=2, n_kv_heads=2, head_dim=64, n_table=16)
+        a.update(kw)
+        return B.paged_cache(**a)
+
+    st, tr = ctx.load_chunks_paged([0, 1], cache(), tok_base=3, want_trace=True)
+    assert [t.tok_off for t in tr] == [3, 103] and st["tokens"] == 200
+    for bad, code in [(cache(n_table=12), B.ENOSPC),              # 192 rows < 3 + 200
+                      (cache(page_tokens=4), B.EINVAL),            # 4 * 64 * 2 = 512 B < 1 KiB
+                      (cache(base=FAKE_HBM + 8), B.EINVAL),
+                      (cache(page_table=0), B.EINVAL),
+                      (cache(n_pages=0), B.EINVAL),
+                      (cache(page_tokens=1 << 16, n_table=1 << 10), B.EINVAL)]:   # virtual tile >= 4 GiB
+        with pytest.raises(B.HaRagError) as e:
+            ctx.load_chunks_paged([0, 1], bad, tok_base=3)
+        assert e.value.code == code
+    c2 = cache()
+    c2.page_stride += 8
+    with pytest.raises(B.HaRagError) as e:
+        ctx.load_chunks_paged([0], c2)
+    assert e.value.code == B.EINVAL
+    assert ctx.pool_query(0).count == 1           # refused calls changed nothing
+    ctx.destroy()
