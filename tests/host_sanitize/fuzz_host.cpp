@@ -44,6 +44,7 @@ int main(int argc, char **argv)
         cfg.tau_pin_ppm = (uint32_t)(rnd() % 400001);
         cfg.tau_page_ppm = (uint32_t)(rnd() % 400001);
         cfg.disk_o_direct = (uint32_t)(rnd() % 2);
+        cfg.half_slots = (uint32_t)(rnd() % 3 == 0);
         cfg.dry_run = 1;
         ha_rag_ctx *ctx = nullptr;
         REQUIRE(ha_rag_create(&cfg, &ctx) == HA_RAG_OK);
@@ -54,6 +55,7 @@ int main(int argc, char **argv)
             const uint32_t g = p == HA_RAG_PREC_INT8 ? 128 : 64;
             REQUIRE(ha_rag_chunk_bytes(cfg.n_layers, cfg.n_kv_heads, cfg.head_dim, p, g,
                                        cfg.max_chunk_tokens, nullptr, nullptr, &total) == HA_RAG_OK);
+            if (cfg.half_slots) total /= 2;
             slot[p] = (total + 255) & ~(size_t)255;
             REQUIRE(ha_rag_register_slab(ctx, HA_RAG_TIER_HBM, p, (void *)(0x100000000000ull + p * 0x10000000000ull),
                                          slot[p] * hbm_slots) == HA_RAG_OK);
@@ -72,7 +74,10 @@ int main(int argc, char **argv)
                 const uint64_t id = rnd() % 40;
                 const uint32_t prec = rnd() % HA_RAG_N_PREC, tier = rnd() % 4;
                 const uint32_t tok = 1 + rnd() % cfg.max_chunk_tokens;
-                int rc = ha_rag_pool_insert(ctx, id, prec, tok, nullptr, 0, tier, nullptr);
+                const uint32_t part = rnd() % 3;  // whole chunks, key units, value units
+                int rc = part == HA_RAG_PART_KV
+                             ? ha_rag_pool_insert(ctx, id, prec, tok, nullptr, 0, tier, nullptr)
+                             : ha_rag_pool_insert_half(ctx, id, part, prec, tok, nullptr, 0, tier, nullptr);
                 REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_EINVAL || rc == HA_RAG_ENOSPC || rc == HA_RAG_EFORMAT);
                 if (rc == HA_RAG_OK) known.push_back(id);
             } else if (what < 75 && !known.empty()) {  // a request (single or batch)
@@ -94,12 +99,30 @@ int main(int argc, char **argv)
                 ha_rag_load_stats st;
                 int rc = ha_rag_load_batch(ctx, ids.data(), nullptr, starts.data(), n_req, outs.data(),
                                            caps.data(), bases.data(), nullptr, &st, tr.data());
-                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOENT || rc == HA_RAG_ENOSPC);
+                // EINVAL: key and value planes of a request that do not line up
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOENT || rc == HA_RAG_ENOSPC || rc == HA_RAG_EINVAL);
                 if (rc == HA_RAG_OK) {
                     REQUIRE(st.n_chunks == ids.size());
                     REQUIRE(st.n_hbm_hits + st.n_pinned_hits + st.n_pageable_hits + st.n_disk_hits == st.n_chunks);
                     REQUIRE(st.n_evicted <= st.n_promoted + st.n_placed_host);
                 }
+            } else if (what < 79 && !known.empty()) {  // one request into a paged cache
+                std::vector<uint64_t> ids;
+                const uint32_t k = rnd() % 6;
+                for (uint32_t i = 0; i < k; ++i) ids.push_back(known[rnd() % known.size()]);
+                ha_rag_paged_cache pc;
+                std::memset(&pc, 0, sizeof pc);
+                pc.base = (void *)0x700000000000ull;
+                pc.page_table = (const uint32_t *)0x710000000000ull;
+                pc.page_tokens = 4u << (rnd() % 4);
+                pc.n_table = (uint32_t)(rnd() % 64);
+                pc.n_pages = 1 + (uint32_t)(rnd() % 100);
+                pc.page_stride = 16 * (1 + rnd() % 1000);
+                pc.tile_stride = 16 * (1 + rnd() % 1000);
+                ha_rag_load_stats st;
+                int rc = ha_rag_load_chunks_paged(ctx, ids.data(), nullptr, (uint32_t)ids.size(), &pc,
+                                                  rnd() % 4, nullptr, &st, nullptr);
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOSPC || rc == HA_RAG_EINVAL);
             } else if (what < 82 && !known.empty()) {
                 int rc = ha_rag_pool_promote(ctx, known[rnd() % known.size()], nullptr);
                 REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOSPC || rc == HA_RAG_ENOENT);
