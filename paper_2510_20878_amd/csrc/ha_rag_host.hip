@@ -86,6 +86,7 @@ struct Chunk {
     uint64_t count = 0;
     uint32_t rank = kNoRank;
     uint64_t last_use[kCacheTiers] = {0, 0, 0};  // sequence number of the last access per tier
+    uint64_t made_by[kCacheTiers] = {0, 0, 0};   // load call that created this tier's copy (0: none)
     std::list<uint32_t>::iterator lru_it[kCacheTiers];
 
     int fastest() const
@@ -150,7 +151,7 @@ struct ha_rag_ctx {
     Slab slab[kTiers][HA_RAG_N_PREC];
 
     uint32_t bound[3] = {0, 0, 0};  // ranks below bound[t] belong to the list of tier <= t
-    uint64_t n_loads = 0, use_seq = 0;
+    uint64_t n_loads = 0, use_seq = 0, call_seq = 0;
 
     uint8_t *staging = nullptr;
     size_t staging_slot_bytes = 0;
@@ -359,19 +360,19 @@ void tier_detach(ha_rag_ctx *c, uint32_t tier, uint32_t ci)
 
 // A free slot of the slab (tier, prec); if the slab is full the least recently used chunk
 // that also lives in a slower tier is dropped ("put C_i in queueX with LRU").  Returns -1 if
-// nothing can be freed.  *evicted receives the dropped id.  Chunks flagged in `keep`
-// (indexed like ctx->chunks) are passed over: a copy that the running call has itself
-// just created is not dropped again by the same call, because a later read of it may
-// already be planned.
+// nothing can be freed.  *evicted receives the dropped id.  Copies created by load call
+// `keep_call` (non-zero) are passed over: a copy that the running call has itself just
+// created is not dropped again by the same call, because a later read of it may already
+// be planned.
 int32_t tier_acquire(ha_rag_ctx *c, uint32_t tier, uint32_t prec, uint64_t *evicted,
-                     const std::vector<uint8_t> *keep = nullptr)
+                     uint64_t keep_call = 0)
 {
     Slab &sl = c->slab[tier][prec];
     *evicted = HA_RAG_NO_CHUNK;
     if (!sl.registered()) return -1;
     if (sl.free_slots.empty() && tier < kCacheTiers) {
         for (uint32_t ci : sl.lru) {
-            if (keep && (*keep)[ci]) continue;
+            if (keep_call && c->chunks[ci].made_by[tier] == keep_call) continue;
             if (c->chunks[ci].has_slower_copy(tier)) {
                 *evicted = c->chunks[ci].id;
                 tier_detach(c, tier, ci);
@@ -666,9 +667,8 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     // ---- pass A: Algorithm 2 step 2, chunk by chunk, in request order ---------
     std::vector<Action> acts;
     acts.reserve(n);
-    // copies created by this call, per cache tier: not evicted again by this call
-    std::vector<uint8_t> made[kCacheTiers];
-    for (auto &m : made) m.assign(c->chunks.size(), 0);
+    // copies created by this call carry its number: they are not evicted again by this call
+    const uint64_t call = ++c->call_seq;
     for (uint32_t r = 0; r < n_req; ++r) {
         const Request &rq = reqs[r];
         PlaneCursor cur(rq.base);
@@ -689,7 +689,7 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
             tier_touch(c, found, ci);
             switch (found) {
             case HA_RAG_TIER_HBM:
-                a.kind = made[HA_RAG_TIER_HBM][ci] ? Action::HOT_LATE : Action::HOT_EARLY;
+                a.kind = ch.made_by[HA_RAG_TIER_HBM] == call ? Action::HOT_LATE : Action::HOT_EARLY;
                 ++st.n_hbm_hits;
                 break;
             case HA_RAG_TIER_PINNED: ++st.n_pinned_hits; break;
@@ -709,10 +709,10 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
                 const uint32_t want = ch.rank == kNoRank ? HA_RAG_TIER_DISK : c->list_of(ch.rank);
                 if (want < found && c->slab[want][ch.prec].registered()) {
                     uint64_t ev;
-                    const int32_t slot = tier_acquire(c, want, ch.prec, &ev, &made[want]);
+                    const int32_t slot = tier_acquire(c, want, ch.prec, &ev, call);
                     if (slot >= 0) {
                         tier_attach(c, want, ci, slot);
-                        made[want][ci] = 1;
+                        ch.made_by[want] = call;
                         a.place_tier = (uint8_t)want;
                         a.place_slot = slot;
                         tr.placed_tier = (uint8_t)want;
@@ -874,7 +874,7 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     for (const Action &a : acts) {
         if (a.kind != Action::HOT_LATE) continue;
         const Chunk &ch = c->chunks[a.ci];
-        // `made` in pass A guarantees the copy written by this call is still in its slot
+        // `made_by` in pass A guarantees the copy written by this call is still in its slot
         if (ch.slot[HA_RAG_TIER_HBM] != a.src_slot) return HA_RAG_EINVAL;
         Slab &hs = c->slab[HA_RAG_TIER_HBM][ch.prec];
         rc = before_read(c, hs.use[a.src_slot], s);

@@ -532,3 +532,44 @@ def test_paged_cache_description_is_checked():
     assert e.value.code == B.EINVAL
     assert ctx.pool_query(0).count == 1           # refused calls changed nothing
     ctx.destroy()
+
+
+def test_hundred_thousand_ids_ranks_lists_and_trace_equal_oracle():
+    """The id count of the Zipf configuration (100k logical ids): ranks after a rerank equal
+    Algorithm 1's sort, list boundaries equal the floors, and 600 Zipf requests of 8 ids
+    through four tiers leave the same trace as the plain simulation."""
+    N = 100_000
+    taus = [10_000, 40_000, 100_000]
+    caps = (50, 300, 2000)
+    ctx = B.Context(2, 2, 64, 128, group_int8=64, group_int4=64, tau_gpu_ppm=taus[0], tau_pin_ppm=taus[1],
+                    tau_page_ppm=taus[2], dry_run=True)
+    nb = ctx.chunk_bytes(B.PREC_INT4, 128)
+    slot = (nb + 255) // 256 * 256
+    ctx.register_slab(B.TIER_HBM, B.PREC_INT4, FAKE_HBM, slot * caps[0])
+    ctx.register_slab(B.TIER_PINNED, B.PREC_INT4, FAKE_PIN, slot * caps[1])
+    ctx.register_slab(B.TIER_PAGEABLE, B.PREC_INT4, 0x7A0000000000, slot * caps[2])
+    ctx.register_disk(B.PREC_INT4, "/nonexistent/dry-run", (nb + 4095) // 4096 * 4096 * N)
+    ctx.register_staging(FAKE_STG, slot * 4)
+    ctx.register_bounce(0x790000000000, ((nb + 4095) // 4096 * 4096) * 2)
+    for c in range(N):
+        ctx.pool_insert(c, B.PREC_INT4, 128, None, B.TIER_DISK)
+    rng = np.random.default_rng(7)
+    counts = rng.multinomial(2_000_000, wl.zipf_pmf(N, 1.1))[rng.permutation(N)].tolist()   # many ties
+    ctx.set_counts(list(range(N)), counts)
+    ctx.rerank()
+    ranks = pl.ranks(counts)
+    probe = rng.integers(0, N, 500).tolist() + [0, N - 1]
+    assert [ctx.get_rank(c) for c in probe] == [ranks[c] for c in probe]
+    sim = pl.TierSim(ranks, taus, caps)
+    order = pl.rank_order(counts)
+    for req in wl.zipf_requests(N, 600, 8, 3):
+        ids = [order[int(r)] for r in req]            # rank r -> the chunk id holding it
+        st, tr = ctx.load_chunks(ids, FAKE_HBM, 8 * 128, want_trace=True)
+        for c, t in zip(ids, tr):
+            tier, placed = sim.access(c)
+            assert t.found_tier == tier
+            assert t.placed_tier == (placed[0][0] if placed else B.TIER_NONE)
+            assert t.evicted_id == (placed[0][1] if placed and placed[0][1] is not None else B.NO_CHUNK)
+    for tier in (B.TIER_HBM, B.TIER_PINNED, B.TIER_PAGEABLE):
+        assert ctx.pool_lru(tier) == sim.resident(tier)
+    ctx.destroy()
