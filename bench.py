@@ -127,8 +127,13 @@ def time_quantize(B, wl, torch, ctx, shape, T, g, tags, reps=40):
             e1.record(stream)
             torch.cuda.synchronize()
         us = e0.elapsed_time(e1) * 1e3 / reps
+        # Eq. 1 on the synthetic chunk: RMSE between the source and its round trip
+        acc = torch.zeros(1, dtype=torch.float64, device="cuda")
+        ctx.chunk_sq_error(srcs[0], dst[0], T, prec, g, acc)
+        torch.cuda.synchronize()
         out[str(tag)] = {"us_per_chunk": us, "gbps": (elems * 2 + nb) / us / 1e3,
-                         "bytes_per_chunk": elems * 2 + nb}
+                         "bytes_per_chunk": elems * 2 + nb,
+                         "rmse": (float(acc.item()) / elems) ** 0.5}
     return out
 
 

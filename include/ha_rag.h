@@ -274,6 +274,16 @@ int ha_rag_quantize_chunk(ha_rag_ctx *ctx, const void *src, uint32_t n_tokens, u
 int ha_rag_quantize_half(ha_rag_ctx *ctx, const void *src, uint32_t n_tokens, uint32_t prec,
                          uint32_t group, void *dst, uint32_t *saturated, void *stream);
 
+/* Squared error of a packed chunk against its source: adds to *sum_sq (device pointer to a
+ * binary64, 8-byte aligned, which the caller has set, usually to 0) the sum over all elements
+ * of (x - y)^2, x the source BF16 value and y the BF16 value a load would write for it.  The
+ * paper's RMSE (Eq. 1; Sec. 3.2.1 orders the schemes S1..S4 by it) is sqrt(sum_sq / elements).
+ * src as in ha_rag_quantize_chunk (part = HA_RAG_PART_KV) or ha_rag_quantize_half (PART_K or
+ * PART_V); `packed` a device pointer to that chunk's packed bytes.  The sum is accumulated in
+ * binary64 with one atomic add per 2048 elements, so its last bits depend on the order. */
+int ha_rag_chunk_sq_error(ha_rag_ctx *ctx, const void *src, const void *packed, uint32_t n_tokens,
+                          uint32_t prec, uint32_t group, uint32_t part, double *sum_sq, void *stream);
+
 /* ---- online, no pool: gather-dequantize-scatter of caller-held packed chunks -- */
 
 /* Chunk i of `chunks[n]` (host array, n <= HA_RAG_MAX_REQUEST_CHUNKS) is

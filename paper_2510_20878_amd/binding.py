@@ -29,7 +29,7 @@ SYMBOLS = [
     "ha_rag_set_counts", "ha_rag_rerank", "ha_rag_get_rank", "ha_rag_load_chunks",
     "ha_rag_load_batch", "ha_rag_register_disk", "ha_rag_register_bounce", "ha_rag_pool_lru",
     "ha_rag_quantize_half", "ha_rag_pool_insert_half", "ha_rag_load_packed_paged",
-    "ha_rag_load_chunks_paged",
+    "ha_rag_load_chunks_paged", "ha_rag_chunk_sq_error",
 ]
 
 
@@ -128,6 +128,7 @@ def lib():
             "ha_rag_quantize_half": (C.c_int, [vp, vp, u32, u32, u32, vp, vp, vp]),
             "ha_rag_pool_insert_half": (C.c_int, [vp, u64, u32, u32, u32, vp, C.c_int, u32, vp]),
             "ha_rag_load_packed": (C.c_int, [vp, P(PackedChunk), u32, vp, u64, u64, vp]),
+            "ha_rag_chunk_sq_error": (C.c_int, [vp, vp, vp, u32, u32, u32, u32, vp, vp]),
             "ha_rag_load_packed_paged": (C.c_int, [vp, P(PackedChunk), u32, P(PagedCache), u64, vp]),
             "ha_rag_load_chunks_paged": (C.c_int, [vp, P(u64), P(C.c_uint8), u32, P(PagedCache), u64, vp,
                                                    P(LoadStats), P(ChunkTrace)]),
@@ -288,6 +289,11 @@ class Context:
         self._chk(lib().ha_rag_quantize_half(self._h, _addr(src), n_tokens, prec, group, _addr(dst),
                                              _addr(saturated), _stream(stream)),
                   "ha_rag_quantize_half")
+
+    def chunk_sq_error(self, src, packed, n_tokens, prec, group, sum_sq, part=PART_KV, stream=None):
+        self._chk(lib().ha_rag_chunk_sq_error(self._h, _addr(src), _addr(packed), n_tokens, prec, group,
+                                              part, _addr(sum_sq), _stream(stream)),
+                  "ha_rag_chunk_sq_error")
 
     def load_packed(self, chunks, out, cap_tokens, tok_base=0, stream=None):
         """chunks: list of (packed, n_tokens, prec, group[, part])."""

@@ -1072,6 +1072,21 @@ int ha_rag_quantize_half(ha_rag_ctx *c, const void *src, uint32_t n_tokens, uint
     return quantize_impl(c, src, n_tokens, prec, group, dst, saturated, stream, kPartK);
 }
 
+int ha_rag_chunk_sq_error(ha_rag_ctx *c, const void *src, const void *packed, uint32_t n_tokens,
+                          uint32_t prec, uint32_t group, uint32_t part, double *sum_sq, void *stream)
+{
+    if (!c || !src || !packed || !sum_sq) return HA_RAG_EINVAL;
+    if (((uintptr_t)src & 15u) || ((uintptr_t)packed & 15u) || ((uintptr_t)sum_sq & 7u)) return HA_RAG_EINVAL;
+    int rc = chunk_bytes_impl(c->cfg.n_layers, c->cfg.n_kv_heads, c->cfg.head_dim, prec, group,
+                              n_tokens, nullptr, nullptr, nullptr, part);
+    if (rc) return rc;
+    if (c->dry()) return HA_RAG_OK;
+    std::lock_guard<std::mutex> g(c->mu);
+    HIPCHK(c, launch_k3(src, packed, part == kPartKV ? c->n_tiles : c->n_tiles / 2, c->cfg.head_dim,
+                        n_tokens, prec, has_meta(prec) ? group : 32u, sum_sq, (hipStream_t)stream));
+    return HA_RAG_OK;
+}
+
 static int load_packed_impl(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, uint32_t n, void *out,
                             uint64_t cap_tokens, uint64_t tok_base, void *stream,
                             const ha_rag_paged_cache *paged)

@@ -79,4 +79,10 @@ hipError_t launch_k2(const void *src, void *dst, uint32_t n_tiles, uint32_t head
                      uint32_t n_tokens, uint32_t prec, uint32_t group, uint32_t *saturated,
                      hipStream_t stream);
 
+// Adds to *sum_sq (device, binary64) the squared error between src (BF16 [n_tiles][n_tokens][D])
+// and what `packed` decodes to.
+hipError_t launch_k3(const void *src, const void *packed, uint32_t n_tiles, uint32_t head_dim,
+                     uint32_t n_tokens, uint32_t prec, uint32_t group, double *sum_sq,
+                     hipStream_t stream);
+
 }  // namespace ha_rag

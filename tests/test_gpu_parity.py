@@ -211,6 +211,59 @@ def test_more_chunks_than_one_launch_holds():
     assert np.array_equal(got, ref)
 
 
+def test_the_most_chunks_one_call_takes_and_one_more():
+    """HA_RAG_MAX_REQUEST_CHUNKS = 4096 descriptors (64 launches), every tag, 1..3 tokens each,
+    some of them empty; 4097 is refused before anything is enqueued."""
+    L, H, D, g = 1, 1, 64, 32
+    precs_all = sorted(ORC)
+    n = 4096
+    rng = np.random.default_rng(12)
+    tokens = rng.integers(0, 4, n).tolist()
+    precs = [precs_all[i % 6] for i in range(n)]
+    base = {}
+    for p in precs_all:                       # one source per (tag, length): contents repeat, slots do not
+        for t in range(4):
+            src = wl.kv_chunk(L, H, D, t, 300 + 7 * p + t) if t else np.zeros((L, 2, H, 0, D), np.uint16)
+            base[(p, t)] = codec.quantize_pack_chunk(src, ORC[p], g)[0]
+    packed = [base[(precs[i], tokens[i])] for i in range(n)]
+    cap = sum(tokens) + 1
+    ref = np.full((L, 2, H, cap, D), CANARY, np.uint16)
+    codec.load_chunks(packed, (L, H, D), tokens, [ORC[p] for p in precs], [g] * n, list(range(n)),
+                      cap_tokens=cap, out=ref)
+    ctx = B.Context(L, H, D, 4, group_int8=g, group_int4=g)
+    dev = {k: dev_u8(np.concatenate([v, np.zeros(16, np.uint8)])) for k, v in base.items()}
+    chunks = [(dev[(precs[i], tokens[i])], tokens[i], precs[i], g) for i in range(n)]
+    out = torch.full((L, 2, H, cap, D), CANARY, dtype=torch.int16, device="cuda")
+    ctx.load_packed(chunks, out, cap)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u16(out), ref)
+    out.fill_(CANARY)
+    with pytest.raises(B.HaRagError) as e:
+        ctx.load_packed(chunks + [chunks[0]], out, cap + 8)
+    assert e.value.code == B.EINVAL
+    torch.cuda.synchronize()
+    assert bool((out == CANARY).all())
+    ctx.destroy()
+
+
+@pytest.mark.parametrize("prec", [B.PREC_INT4, B.PREC_16])
+def test_one_very_long_chunk(prec):
+    """100,003 tokens in one chunk: 3,126 blocks per tile and a ragged last block."""
+    L, H, D, g, T = 1, 1, 64, 64, 100_003
+    src = wl.kv_chunk(L, H, D, T, 77)
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g)
+    got_pack, _ = gpu_quantize(ctx, src, prec, g)
+    ref_pack, _ = codec.quantize_pack_chunk(src, ORC[prec], g)
+    assert np.array_equal(got_pack, ref_pack)
+    ref = np.full((L, 2, H, T + 2, D), CANARY, np.uint16)
+    codec.dequant_scatter_chunk(ref_pack, (L, H, D), T, ORC[prec], g, ref, 1)
+    out = torch.full((L, 2, H, T + 2, D), CANARY, dtype=torch.int16, device="cuda")
+    ctx.load_packed([(dev_u8(got_pack), T, prec, g)], out, T + 2, 1)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u16(out), ref)
+    ctx.destroy()
+
+
 def test_empty_and_error_calls_touch_nothing():
     ctx = B.Context(2, 2, 64, 128, group_int8=64, group_int4=64)
     out = torch.full((2, 2, 2, 64, 64), CANARY, dtype=torch.int16, device="cuda")

@@ -1,0 +1,78 @@
+"""The squared-error kernel (Eq. 1) against the oracle's RMSE of the oracle's own round trip."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import codec
+from paper_2510_20878_amd import binding as B
+from paper_2510_20878_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+ORC = {B.PREC_16: 16, B.PREC_INT8: 8, B.PREC_INT4: 4, B.PREC_FP8_E4M3: 43, B.PREC_FP8_E5M2: 52,
+       B.PREC_GSE8: 143}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    B.lib()
+    yield
+    torch.cuda.synchronize()
+
+
+def dev_u16(a):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+
+
+@pytest.mark.parametrize("prec", sorted(ORC))
+@pytest.mark.parametrize("shape", [(2, 2, 64, 128, 64), (1, 3, 96, 37, 32), (3, 1, 128, 1000, 128)])
+def test_sq_error_equals_oracle_rmse(prec, shape):
+    L, H, D, T, g = shape
+    src = wl.kv_chunk(L, H, D, T, 21)
+    packed, _ = codec.quantize_pack_chunk(src, ORC[prec], g)
+    back = np.zeros((L, 2, H, T, D), np.uint16)
+    codec.dequant_scatter_chunk(packed, (L, H, D), T, ORC[prec], g, back, 0)
+    rmse = codec.rmse_bf16(src, back)
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g)
+    acc = torch.zeros(1, dtype=torch.float64, device="cuda")
+    pk = torch.from_numpy(packed).cuda()
+    s_dev = dev_u16(src)
+    ctx.chunk_sq_error(s_dev, pk, T, prec, g, acc)
+    ctx.chunk_sq_error(s_dev, pk, T, prec, g, acc)              # it adds
+    torch.cuda.synchronize()
+    got = float(acc.item()) / 2
+    n = src.size
+    assert got == pytest.approx(rmse * rmse * n, rel=1e-10, abs=1e-300)
+    if prec == B.PREC_16:
+        assert got == 0.0
+    # a half chunk: the value plane alone
+    half = np.ascontiguousarray(src[:, 1])
+    hp, _ = codec.quantize_pack_half(half, ORC[prec], g)
+    acc.zero_()
+    h_dev, hp_dev = dev_u16(half), torch.from_numpy(hp).cuda()
+    ctx.chunk_sq_error(h_dev, hp_dev, T, prec, g, acc, part=B.PART_V)
+    torch.cuda.synchronize()
+    r_half = codec.rmse_bf16(src[:, 1], back[:, 1])
+    assert float(acc.item()) == pytest.approx(r_half * r_half * half.size, rel=1e-10, abs=1e-300)
+    ctx.destroy()
+
+
+def test_scheme_order_on_the_synthetic_kv():
+    """Fig. 9's order on data of the paper's value ranges: INT8 < E4M3 < E5M2 < GSE-8, and
+    int4 above int8 by about 255/15."""
+    L, H, D, T, g = 4, 8, 128, 512, 128
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g)
+    src = wl.kv_chunk_device(L, H, D, T, 5)
+    rm = {}
+    for prec in sorted(ORC):
+        dst = torch.empty(ctx.chunk_bytes(prec, T), dtype=torch.uint8, device="cuda")
+        ctx.quantize_chunk(src, T, prec, g, dst)
+        acc = torch.zeros(1, dtype=torch.float64, device="cuda")
+        ctx.chunk_sq_error(src, dst, T, prec, g, acc)
+        torch.cuda.synchronize()
+        rm[prec] = (float(acc.item()) / src.numel()) ** 0.5
+    assert rm[B.PREC_16] == 0.0
+    assert rm[B.PREC_INT8] < rm[B.PREC_FP8_E4M3] < rm[B.PREC_FP8_E5M2] < rm[B.PREC_GSE8]
+    assert 12 < rm[B.PREC_INT4] / rm[B.PREC_INT8] < 22
+    ctx.destroy()
