@@ -296,7 +296,10 @@ int ha_rag_chunk_sq_error(ha_rag_ctx *ctx, const void *src, const void *packed, 
  * the value plane each advance in list order by the chunks that hold them, so the keys
  * and the values of a document may sit anywhere in the list and differ in precision.
  * EINVAL, before anything is enqueued, if a whole chunk arrives while the two planes
- * differ in length, or if they differ at the end of the list. */
+ * differ in length, or if they differ at the end of the list.
+ * The call makes no allocation, no copy and no synchronisation: it only launches kernels
+ * on `stream`, so it may be recorded into a HIP graph (stream capture) and replayed; a
+ * replay reads whatever the packed buffers hold at that time. */
 int ha_rag_load_packed(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks, uint32_t n,
                        void *out, uint64_t cap_tokens, uint64_t tok_base, void *stream);
 

@@ -810,3 +810,41 @@ def test_mixed_tier_batch_at_the_8b_shape_sampled_tiles_match_oracle():
     for r, o in zip(reqs, outs):
         _check_sampled_tiles(ctx, (L, H, D), T, g, precs, r, srcs, packs, o, 1, rng)
     ctx.destroy()
+
+
+def test_load_packed_can_be_captured_in_a_hip_graph_and_replayed():
+    """ha_rag_load_packed only launches kernels (descriptors travel in the kernel arguments),
+    so a serving loop may capture it once per request shape.  Replays see the packed bytes
+    that are in the buffers at replay time; eager work runs between the replays."""
+    L, H, D, g = 2, 2, 64, 64
+    tokens = [40, 128, 7]
+    precs = [B.PREC_INT4, B.PREC_INT8, B.PREC_16]
+    ctx = B.Context(L, H, D, 128, group_int8=g, group_int4=g)
+    cap = sum(tokens) + 3
+    bufs = [torch.zeros(ctx.chunk_bytes(p, t) + 16, dtype=torch.uint8, device="cuda")
+            for p, t in zip(precs, tokens)]
+    out = torch.full((L, 2, H, cap, D), CANARY, dtype=torch.int16, device="cuda")
+    chunks = [(bufs[i], tokens[i], precs[i], g) for i in (2, 0, 1)]
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ctx.load_packed(chunks, out, cap, 2, stream=side)          # warm-up outside the capture
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            ctx.load_packed(chunks, out, cap, 2, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for rnd in range(3):
+        packed = [codec.quantize_pack_chunk(wl.kv_chunk(L, H, D, t, 900 + 10 * rnd + i), B.BITS[p], g)[0]
+                  for i, (p, t) in enumerate(zip(precs, tokens))]
+        for b, pk in zip(bufs, packed):
+            b[:pk.size].copy_(torch.from_numpy(pk))
+        ref = np.full((L, 2, H, cap, D), CANARY, np.uint16)
+        codec.load_chunks(packed, (L, H, D), tokens, [B.BITS[p] for p in precs], [g] * 3, [2, 0, 1],
+                          cap_tokens=cap, tok_base=2, out=ref)
+        out.fill_(CANARY)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(host_u16(out), ref), rnd
+    ctx.destroy()
