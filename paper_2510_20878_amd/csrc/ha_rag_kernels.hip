@@ -222,17 +222,22 @@ __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params
 #pragma unroll
         for (uint32_t k = 0; k < 4; ++k) {
             if (k >= planes) break;
-            // the two pages this KiB can touch: wave-uniform table reads and base addresses
-            const uint32_t id0 = pc.page_table[pg < last ? pg : last];
-            const uint32_t id1 = pc.page_table[pg + 1u < last ? pg + 1u : last];
-            uint8_t *b0 = tile_base + (uint64_t)id0 * pc.page_stride;
-            uint8_t *b1 = tile_base + (uint64_t)id1 * pc.page_stride - pc.page_bytes;
             const uint32_t w = within + lane_b;
-            const bool cross = w >= pc.page_bytes;
             const bool live = e + k * 512u < n_e;  // rows past the chunk's end have no page
-            const bool ok = pg + (cross ? 1u : 0u) <= last && (cross ? id1 : id0) < pc.n_pages;
-            if (live && ok) op[k] = (cross ? b1 : b0) + w;
-            else if (live) ++dropped;
+            // wave-uniform table reads and base addresses; most KiB lie inside one page
+            const uint32_t id0 = pc.page_table[pg < last ? pg : last];
+            uint8_t *b0 = tile_base + (uint64_t)id0 * pc.page_stride;
+            if (within + 1024u <= pc.page_bytes) {
+                if (live && pg <= last && id0 < pc.n_pages) op[k] = b0 + w;
+                else if (live) ++dropped;
+            } else {
+                const uint32_t id1 = pc.page_table[pg + 1u < last ? pg + 1u : last];
+                uint8_t *b1 = tile_base + (uint64_t)id1 * pc.page_stride - pc.page_bytes;
+                const bool cross = w >= pc.page_bytes;
+                const bool ok = pg + (cross ? 1u : 0u) <= last && (cross ? id1 : id0) < pc.n_pages;
+                if (live && ok) op[k] = (cross ? b1 : b0) + w;
+                else if (live) ++dropped;
+            }
             within += 1024u;
             if (within >= pc.page_bytes) {
                 within -= pc.page_bytes;
