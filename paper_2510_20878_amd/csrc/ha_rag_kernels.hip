@@ -414,34 +414,54 @@ hipError_t launch_k1(K1Params &p, const K1Launch &cfg, hipStream_t stream)
 
 // ---------------------------------------------------------------------------
 // K2.  One wave per block of 2048 elements; a workgroup of 4 waves takes 4
-// consecutive blocks of one tile.  Bound by VALU issue, not by HBM: every
-// element costs a correctly rounded division.
+// consecutive blocks of one tile.  Every element costs a correctly rounded division, so
+// the kernel is kept short on vector instructions (about 14 per element): hardware directed
+// rounding for scale and zero, one shared reciprocal per group, a hardware float -> byte
+// conversion for the codes.
 // ---------------------------------------------------------------------------
 
-// fp32 -> fp16 word, largest finite value <= x; sets sat if none exists
+// fp32 -> fp16 with the rounding direction taken from the MODE register: bits [3:2] are the
+// round mode of the half / double precision pipe, which v_cvt_f16_f32 obeys (1 = toward
+// +inf, 2 = toward -inf; checked against a software reference on every finite fp32 value).
+// The switch, the conversion and the switch back are one asm statement, so nothing can be
+// scheduled in between; fp32 arithmetic is governed by bits [1:0] and is not affected.
+__device__ __forceinline__ uint32_t cvt_f16_toward_neg_inf(float x)
+{
+    uint32_t h;
+    asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 2, 2), 2\n\t"
+                 "v_cvt_f16_f32 %0, %1\n\t"
+                 "s_setreg_imm32_b32 hwreg(HW_REG_MODE, 2, 2), 0"
+                 : "=v"(h)
+                 : "v"(x));
+    return h & 0xFFFFu;
+}
+
+__device__ __forceinline__ uint32_t cvt_f16_toward_pos_inf(float x)
+{
+    uint32_t h;
+    asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 2, 2), 1\n\t"
+                 "v_cvt_f16_f32 %0, %1\n\t"
+                 "s_setreg_imm32_b32 hwreg(HW_REG_MODE, 2, 2), 0"
+                 : "=v"(h)
+                 : "v"(x));
+    return h & 0xFFFFu;
+}
+
+// fp32 (finite) -> fp16 word, largest finite value <= x; sets sat if none exists
 __device__ __forceinline__ uint32_t f16_round_down(float x, uint32_t &sat)
 {
-    uint32_t h = __builtin_bit_cast(uint16_t, (_Float16)x);  // nearest even
-    const bool step = h2f(h) > x;                              // one step down the number line
-    const uint32_t below = (h & 0x7FFFu) == 0 ? 0x8001u : ((h & 0x8000u) ? h + 1u : h - 1u);
-    h = step ? below : h;
+    uint32_t h = cvt_f16_toward_neg_inf(x);  // -inf below -65504; never +inf
     sat |= (h == 0xFC00u) ? 1u : 0u;
     h = (h == 0xFC00u) ? 0xFBFFu : h;
-    h = (h == 0x7C00u) ? 0x7BFFu : h;
     return (h == 0x8000u) ? 0u : h;
 }
 
-// fp32 -> fp16 word, smallest finite value >= x; sets sat if none exists
+// fp32 (finite) -> fp16 word, smallest finite value >= x; sets sat if none exists
 __device__ __forceinline__ uint32_t f16_round_up(float x, uint32_t &sat)
 {
-    uint32_t h = __builtin_bit_cast(uint16_t, (_Float16)x);
-    const bool step = h2f(h) < x;
-    const uint32_t above = (h & 0x7FFFu) == 0 ? 0x0001u : ((h & 0x8000u) ? h - 1u : h + 1u);
-    h = step ? above : h;
-    const bool over = (h & 0x7FFFu) >= 0x7C00u && h != 0xFC00u;
-    sat |= over ? 1u : 0u;
-    h = over ? 0x7BFFu : h;
-    h = (h == 0xFC00u) ? 0xFBFFu : h;
+    uint32_t h = cvt_f16_toward_pos_inf(x);  // +inf above 65504; never -inf
+    sat |= (h == 0x7C00u) ? 1u : 0u;
+    h = (h == 0x7C00u) ? 0x7BFFu : h;
     return (h == 0x8000u) ? 0u : h;
 }
 
@@ -535,7 +555,13 @@ __global__ void __launch_bounds__(256) k2_quantize_pack(const uint8_t *__restric
         const uint32_t zh = f16_round_down(mn, sat);
         const float z = h2f(zh);
         const float range = mx - z;
-        const float sc = range / qmax;
+        // range / qmax, correctly rounded, without the division sequence: with r the rounded
+        // reciprocal of the constant, q0 = range * r is within an ulp and one exact residual
+        // step lands on the IEEE quotient (checked on every non-negative finite fp32 value for
+        // 15 and for 255).
+        constexpr float rq = 1.0f / (float)((1 << BITS) - 1);
+        const float sc0 = range * rq;
+        const float sc = __builtin_fmaf(__builtin_fmaf(-qmax, sc0, range), rq, sc0);
         const uint32_t sh = f16_round_up(sc, sat);
         const float s = h2f(sh);
         n_sat += sat;
@@ -554,24 +580,27 @@ __global__ void __launch_bounds__(256) k2_quantize_pack(const uint8_t *__restric
         // falls on the same side as the correctly rounded quotient does.
         const float r0 = __builtin_amdgcn_rcpf(sd);
         const float r1 = __builtin_fmaf(__builtin_fmaf(-sd, r0, 1.0f), r0, r0);
-        // Clamping before rounding equals rounding before clamping (the bounds are integers),
-        // and adding 2^23 rounds a float in [0, 2^22) to the nearest integer, ties to even,
-        // leaving that integer in the low mantissa bits.
-        uint32_t q[8];
+        // v_cvt_pk_u8_f32 rounds to the nearest integer, ties to even, clamps to 0..255 and
+        // drops the byte into a dword (checked on every finite fp32 value); clamping before
+        // rounding equals rounding before clamping because the bounds are integers.
+        uint32_t lo = 0, hi = 0;
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const float d = x[k] - z;
             const float q0 = d * r1;
-            const float q1 = __builtin_fmaf(__builtin_fmaf(-sd, q0, d), r1, q0);
-            const float t = __builtin_amdgcn_fmed3f(q1, 0.0f, qmax);
-            q[k] = __builtin_bit_cast(uint32_t, t + 8388608.0f) & 0xFFu;
+            float q1 = __builtin_fmaf(__builtin_fmaf(-sd, q0, d), r1, q0);
+            if (BITS == 4) q1 = fminf(q1, qmax);
+            if (k < 4) lo = __builtin_amdgcn_cvt_pk_u8_f32(q1, k, lo);
+            else hi = __builtin_amdgcn_cvt_pk_u8_f32(q1, k - 4, hi);
         }
         if (BITS == 4) {
-            code_lo[j] = q[0] | (q[1] << 4) | (q[2] << 8) | (q[3] << 12) | (q[4] << 16) |
-                         (q[5] << 20) | (q[6] << 24) | (q[7] << 28);
+            // bytes 0 and 2 of x | x >> 4 hold two codes each; gather them from both dwords
+            lo |= lo >> 4;
+            hi |= hi >> 4;
+            code_lo[j] = __builtin_amdgcn_perm(hi, lo, 0x06040200u);
         } else {
-            code_lo[j] = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
-            code_hi[j] = q[4] | (q[5] << 8) | (q[6] << 16) | (q[7] << 24);
+            code_lo[j] = lo;
+            code_hi[j] = hi;
         }
     }
     if (BITS == 4) {
