@@ -280,7 +280,7 @@ int ha_rag_quantize_half(ha_rag_ctx *ctx, const void *src, uint32_t n_tokens, ui
  * paper's RMSE (Eq. 1; Sec. 3.2.1 orders the schemes S1..S4 by it) is sqrt(sum_sq / elements).
  * src as in ha_rag_quantize_chunk (part = HA_RAG_PART_KV) or ha_rag_quantize_half (PART_K or
  * PART_V); `packed` a device pointer to that chunk's packed bytes.  The sum is accumulated in
- * binary64 with one atomic add per 2048 elements, so its last bits depend on the order. */
+ * binary64 with one atomic add per workgroup, so its last bits depend on the order. */
 int ha_rag_chunk_sq_error(ha_rag_ctx *ctx, const void *src, const void *packed, uint32_t n_tokens,
                           uint32_t prec, uint32_t group, uint32_t part, double *sum_sq, void *stream);
 

@@ -833,8 +833,8 @@ hipError_t launch_k2(const void *src, void *dst, uint32_t n_tiles, uint32_t head
 // decodes to (Eq. 1 before the mean and the root; Sec. 3.2.1 orders the
 // compression schemes by this figure).  One wave per block of 2048 elements:
 // the block is decoded exactly as k1 decodes it, compared with the source
-// plane by plane, summed in binary64, reduced over the wave and added to the
-// caller's accumulator with one atomic per wave.
+// plane by plane and summed in binary64; the grid strides over the blocks, and
+// each workgroup adds its total to the caller's accumulator with one atomic.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ double sq_err8(u32x4 a, u32x4 b)
 {
@@ -855,77 +855,87 @@ __device__ __forceinline__ double sq_err8(u32x4 a, u32x4 b)
 __global__ void __launch_bounds__(256) k3_sq_error(const uint8_t *__restrict__ src,
                                                    const uint8_t *__restrict__ packed,
                                                    uint32_t n_tokens, uint32_t head_dim,
-                                                   uint32_t wg_per_tile, uint32_t prec, uint32_t gsh,
+                                                   uint32_t n_tiles, uint32_t prec, uint32_t gsh,
                                                    double *sum_sq)
 {
+    __shared__ double part[4];
     const uint32_t n_e = n_tokens * head_dim;
     const uint32_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
-    const uint32_t tile = blockIdx.x / wg_per_tile;
-    const uint32_t blk = (blockIdx.x - tile * wg_per_tile) * 4 + wave;
-    if (blk >= nblk) return;
     const uint32_t lane_b = lane * 16u;
-    const uint32_t e = blk * kBlockElems + lane * 8u;
-
-    u32x4 dec[4];  // the four planes of this block as BF16 words, as k1 would store them
-    if (prec == kInt4) {
-        const uint32_t meta_blk = 8192u >> gsh;
-        const uint8_t *pay = packed + (uint64_t)tile * ((uint64_t)nblk * (1024u + meta_blk));
-        const uint8_t *meta = pay + (uint64_t)nblk * 1024u;
-        const u32x4 w = ld16(pay + (uint64_t)blk * 1024u + lane_b);
-        const u32x4 m = ld16(meta + (uint64_t)blk * meta_blk + ((lane * 8) >> gsh) * 16u);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) dec[j] = dequant_octet4(w[j], m[j]);
-    } else if (prec == kInt8) {
-        const uint32_t meta_blk = 8192u >> gsh;
-        const uint8_t *pay = packed + (uint64_t)tile * ((uint64_t)nblk * (2048u + meta_blk));
-        const uint8_t *meta = pay + (uint64_t)nblk * 2048u;
-        const uint8_t *b = pay + (uint64_t)blk * 2048u + lane_b;
-        const u32x4 w0 = ld16(b), w1 = ld16(b + 1024);
-        const u32x4 m = ld16(meta + (uint64_t)blk * meta_blk + ((lane * 8) >> gsh) * 16u);
-        dec[0] = dequant_octet8(w0.x, w0.y, m.x);
-        dec[1] = dequant_octet8(w0.z, w0.w, m.y);
-        dec[2] = dequant_octet8(w1.x, w1.y, m.z);
-        dec[3] = dequant_octet8(w1.z, w1.w, m.w);
-    } else if (prec == kE4M3 || prec == kE5M2) {
-        const uint8_t *b = packed + (uint64_t)tile * ((uint64_t)nblk * 2048u) + (uint64_t)blk * 2048u + lane_b;
-        const u32x4 w0 = ld16(b), w1 = ld16(b + 1024);
-        if (prec == kE5M2) {
-            dec[0] = decode_octet_fp8<true>(w0.x, w0.y);
-            dec[1] = decode_octet_fp8<true>(w0.z, w0.w);
-            dec[2] = decode_octet_fp8<true>(w1.x, w1.y);
-            dec[3] = decode_octet_fp8<true>(w1.z, w1.w);
-        } else {
-            dec[0] = decode_octet_fp8<false>(w0.x, w0.y);
-            dec[1] = decode_octet_fp8<false>(w0.z, w0.w);
-            dec[2] = decode_octet_fp8<false>(w1.x, w1.y);
-            dec[3] = decode_octet_fp8<false>(w1.z, w1.w);
-        }
-    } else if (prec == kGSE8) {
-        const uint8_t *rec = packed + (uint64_t)tile * ((uint64_t)nblk * 2048u + 16u);
-        const uint8_t *b = rec + (uint64_t)blk * 2048u + lane_b;
-        const uint32_t range = *reinterpret_cast<const uint32_t *>(rec + (uint64_t)nblk * 2048u);
-        const int base = (int)(int8_t)(range & 0xFFu);
-        const int top = (int)(int8_t)((range >> 8) & 0xFFu) - 2;
-        const u32x4 w0 = ld16(b), w1 = ld16(b + 1024);
-        dec[0] = decode_octet_gse8(w0.x, w0.y, base, top);
-        dec[1] = decode_octet_gse8(w0.z, w0.w, base, top);
-        dec[2] = decode_octet_gse8(w1.x, w1.y, base, top);
-        dec[3] = decode_octet_gse8(w1.z, w1.w, base, top);
-    } else {
-        const uint8_t *b = packed + (uint64_t)tile * ((uint64_t)nblk * 4096u) + (uint64_t)blk * 4096u + lane_b;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) dec[j] = ld16(b + j * 1024);
-    }
-
-    const uint8_t *in = src + (uint64_t)tile * n_e * 2u + (uint64_t)blk * 4096u + lane_b;
     double acc = 0.0;
+    // the grid strides over all (tile, block) pairs: few workgroups, one atomic each
+    const uint64_t n_items = (uint64_t)n_tiles * nblk;
+    for (uint64_t item = (uint64_t)blockIdx.x * 4u + wave; item < n_items;
+         item += (uint64_t)gridDim.x * 4u) {
+        const uint32_t tile = (uint32_t)(item / nblk);
+        const uint32_t blk = (uint32_t)(item - (uint64_t)tile * nblk);
+        const uint32_t e = blk * kBlockElems + lane * 8u;
+
+        u32x4 dec[4];  // the four planes of this block as BF16 words, as k1 would store them
+        if (prec == kInt4) {
+            const uint32_t meta_blk = 8192u >> gsh;
+            const uint8_t *pay = packed + (uint64_t)tile * ((uint64_t)nblk * (1024u + meta_blk));
+            const uint8_t *meta = pay + (uint64_t)nblk * 1024u;
+            const u32x4 w = ld16(pay + (uint64_t)blk * 1024u + lane_b);
+            const u32x4 m = ld16(meta + (uint64_t)blk * meta_blk + ((lane * 8) >> gsh) * 16u);
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-        if (e + j * 512 < n_e) acc += sq_err8(ld16(in + j * 1024), dec[j]);
+            for (int j = 0; j < 4; ++j) dec[j] = dequant_octet4(w[j], m[j]);
+        } else if (prec == kInt8) {
+            const uint32_t meta_blk = 8192u >> gsh;
+            const uint8_t *pay = packed + (uint64_t)tile * ((uint64_t)nblk * (2048u + meta_blk));
+            const uint8_t *meta = pay + (uint64_t)nblk * 2048u;
+            const uint8_t *b = pay + (uint64_t)blk * 2048u + lane_b;
+            const u32x4 w0 = ld16(b), w1 = ld16(b + 1024);
+            const u32x4 m = ld16(meta + (uint64_t)blk * meta_blk + ((lane * 8) >> gsh) * 16u);
+            dec[0] = dequant_octet8(w0.x, w0.y, m.x);
+            dec[1] = dequant_octet8(w0.z, w0.w, m.y);
+            dec[2] = dequant_octet8(w1.x, w1.y, m.z);
+            dec[3] = dequant_octet8(w1.z, w1.w, m.w);
+        } else if (prec == kE4M3 || prec == kE5M2) {
+            const uint8_t *b = packed + (uint64_t)tile * ((uint64_t)nblk * 2048u) + (uint64_t)blk * 2048u + lane_b;
+            const u32x4 w0 = ld16(b), w1 = ld16(b + 1024);
+            if (prec == kE5M2) {
+                dec[0] = decode_octet_fp8<true>(w0.x, w0.y);
+                dec[1] = decode_octet_fp8<true>(w0.z, w0.w);
+                dec[2] = decode_octet_fp8<true>(w1.x, w1.y);
+                dec[3] = decode_octet_fp8<true>(w1.z, w1.w);
+            } else {
+                dec[0] = decode_octet_fp8<false>(w0.x, w0.y);
+                dec[1] = decode_octet_fp8<false>(w0.z, w0.w);
+                dec[2] = decode_octet_fp8<false>(w1.x, w1.y);
+                dec[3] = decode_octet_fp8<false>(w1.z, w1.w);
+            }
+        } else if (prec == kGSE8) {
+            const uint8_t *rec = packed + (uint64_t)tile * ((uint64_t)nblk * 2048u + 16u);
+            const uint8_t *b = rec + (uint64_t)blk * 2048u + lane_b;
+            const uint32_t range = *reinterpret_cast<const uint32_t *>(rec + (uint64_t)nblk * 2048u);
+            const int base = (int)(int8_t)(range & 0xFFu);
+            const int top = (int)(int8_t)((range >> 8) & 0xFFu) - 2;
+            const u32x4 w0 = ld16(b), w1 = ld16(b + 1024);
+            dec[0] = decode_octet_gse8(w0.x, w0.y, base, top);
+            dec[1] = decode_octet_gse8(w0.z, w0.w, base, top);
+            dec[2] = decode_octet_gse8(w1.x, w1.y, base, top);
+            dec[3] = decode_octet_gse8(w1.z, w1.w, base, top);
+        } else {
+            const uint8_t *b = packed + (uint64_t)tile * ((uint64_t)nblk * 4096u) + (uint64_t)blk * 4096u + lane_b;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dec[j] = ld16(b + j * 1024);
+        }
+
+        const uint8_t *in = src + (uint64_t)tile * n_e * 2u + (uint64_t)blk * 4096u + lane_b;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (e + j * 512 < n_e) acc += sq_err8(ld16(in + j * 1024), dec[j]);
+    }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
-    if (lane == 0 && acc != 0.0) atomicAdd(sum_sq, acc);
+    if (lane == 0) part[wave] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const double total = (part[0] + part[1]) + (part[2] + part[3]);
+        if (total != 0.0) atomicAdd(sum_sq, total);
+    }
 }
 
 hipError_t launch_k3(const void *src, const void *packed, uint32_t n_tiles, uint32_t head_dim,
@@ -937,17 +947,16 @@ hipError_t launch_k3(const void *src, const void *packed, uint32_t n_tiles, uint
     const uint64_t n_e = (uint64_t)n_tokens * head_dim;
     if (n_e > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const uint32_t nblk = (uint32_t)((n_e + kBlockElems - 1) / kBlockElems);
-    const uint32_t wg_per_tile = (nblk + 3) / 4;
-    const uint64_t gx = (uint64_t)n_tiles * wg_per_tile;
-    if (gx > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const uint64_t wgs = ((uint64_t)n_tiles * nblk + 3) / 4;
+    const uint32_t gx = (uint32_t)(wgs < 2048u ? wgs : 2048u);  // 8 workgroups per compute unit
     uint32_t gsh = 0;
     if (prec == kInt8 || prec == kInt4) {
         while ((1u << gsh) < group) ++gsh;
         if (gsh < 5 || gsh > 9 || (1u << gsh) != group) return hipErrorInvalidValue;
     }
-    hipLaunchKernelGGL(k3_sq_error, dim3((uint32_t)gx), dim3(256), 0, stream,
+    hipLaunchKernelGGL(k3_sq_error, dim3(gx), dim3(256), 0, stream,
                        static_cast<const uint8_t *>(src), static_cast<const uint8_t *>(packed),
-                       n_tokens, head_dim, wg_per_tile, prec, gsh, sum_sq);
+                       n_tokens, head_dim, n_tiles, prec, gsh, sum_sq);
     return hipGetLastError();
 }
 
