@@ -679,23 +679,25 @@ __global__ void __launch_bounds__(256) k2_pack_fp8(const uint8_t *__restrict__ s
     st16<false>(o + 1024, u32x4{code[2][0], code[2][1], code[3][0], code[3][1]});
 }
 
-// GSE-8: one workgroup per tile.  Pass 1 finds the smallest and largest exponent of the
+// GSE-8: one workgroup of up to 16 waves per tile (a tile is the unit that shares an exponent
+// range, and 16 waves per tile keep a 512-tile chunk at full occupancy).  Pass 1 finds the smallest and largest exponent of the
 // tile's nonzero values (BF16 subnormals count as exponent -126), pass 2 encodes.
 // Exponents are handled in biased form (field value, 1..254).
-__global__ void __launch_bounds__(256) k2_pack_gse8(const uint8_t *__restrict__ src,
+__global__ void __launch_bounds__(1024) k2_pack_gse8(const uint8_t *__restrict__ src,
                                                     uint8_t *__restrict__ dst, uint32_t n_tokens,
                                                     uint32_t head_dim)
 {
-    __shared__ uint32_t s_lo[4], s_hi[4];
+    __shared__ uint32_t s_lo[16], s_hi[16];
     const uint32_t n_e = n_tokens * head_dim;
     const uint32_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    const uint32_t n_waves = blockDim.x >> 6;
     const uint32_t tile = blockIdx.x;
     const uint8_t *in = src + (uint64_t)tile * n_e * 2u;
     uint8_t *rec = dst + (uint64_t)tile * ((uint64_t)nblk * 2048u + 16u);
 
     uint32_t lo = 255, hi = 0;  // biased exponents; lo > hi means "no nonzero value yet"
-    for (uint32_t blk = wave; blk < nblk; blk += 4) {
+    for (uint32_t blk = wave; blk < nblk; blk += n_waves) {
         const uint32_t e = blk * kBlockElems + lane * 8;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -728,15 +730,14 @@ __global__ void __launch_bounds__(256) k2_pack_gse8(const uint8_t *__restrict__ 
     __syncthreads();
     lo = s_lo[0];
     hi = s_hi[0];
-#pragma unroll
-    for (int w = 1; w < 4; ++w) {
+    for (uint32_t w = 1; w < n_waves; ++w) {
         lo = s_lo[w] < lo ? s_lo[w] : lo;
         hi = s_hi[w] > hi ? s_hi[w] : hi;
     }
     if (lo > hi) lo = hi = 127;          // all zero: range (e_lo, e_hi) = (0, 0)
     if (lo + 47 < hi) lo = hi - 47;      // 16 shared exponents, 3 apart, reach 48 binades
 
-    for (uint32_t blk = wave; blk < nblk; blk += 4) {
+    for (uint32_t blk = wave; blk < nblk; blk += n_waves) {
         const uint32_t e = blk * kBlockElems + lane * 8;
         uint32_t code[4][2];
 #pragma unroll
@@ -808,7 +809,9 @@ hipError_t launch_k2(const void *src, void *dst, uint32_t n_tiles, uint32_t head
     uint8_t *d = static_cast<uint8_t *>(dst);
     dim3 grid((uint32_t)gx);
     if (prec == kGSE8) {
-        hipLaunchKernelGGL(k2_pack_gse8, dim3(n_tiles), dim3(256), 0, stream, s, d, n_tokens, head_dim);
+        const uint32_t waves = nblk < 16u ? (nblk < 1u ? 1u : nblk) : 16u;  // one block per wave and pass
+        hipLaunchKernelGGL(k2_pack_gse8, dim3(n_tiles), dim3(waves * 64u), 0, stream, s, d, n_tokens,
+                           head_dim);
     } else if (prec == kE4M3 || prec == kE5M2) {
         if (prec == kE5M2)
             hipLaunchKernelGGL(k2_pack_fp8<true>, grid, dim3(256), 0, stream, s, d, n_tokens, head_dim, wg_per_tile);
