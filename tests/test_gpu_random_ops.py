@@ -1,0 +1,123 @@
+"""Seeded random sequences of pool operations and requests on a small four-tier pool, issued
+on several streams without waiting in between; every request's cache is compared with the
+oracle afterwards.  Aimed at what single-scenario tests miss: slot reuse while earlier work
+is still queued, staging and bounce buffers shared by requests on different streams, copies
+made and evicted in quick succession, key / value units mixed with whole chunks."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import codec
+from paper_2510_20878_amd import binding as B
+from paper_2510_20878_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+CANARY = 0x7FC1
+ORC = {B.PREC_16: 16, B.PREC_INT8: 8, B.PREC_INT4: 4, B.PREC_FP8_E4M3: 43, B.PREC_FP8_E5M2: 52,
+       B.PREC_GSE8: 143}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    B.lib()
+    yield
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3, 4, 5, 6])
+def test_random_operations_match_oracle(tmp_path, seed):
+    rng = np.random.default_rng(seed)
+    L, H, D, T, g = 1, 2, 64, 48, 32
+    precs_all = [B.PREC_INT4, B.PREC_INT8, B.PREC_GSE8]
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=250_000, tau_pin_ppm=250_000,
+                    tau_page_ppm=250_000, rerank_interval=int(rng.integers(0, 4)),
+                    n_copy_streams=int(rng.integers(1, 4)))
+    n_ids = 30
+    keep = []
+    biggest = 0
+    for p in precs_all:
+        slot = (ctx.chunk_bytes(p, T) + 4095) // 4096 * 4096
+        biggest = max(biggest, slot)
+        for tier, n_slots, mk in ((B.TIER_HBM, 2, lambda n: torch.zeros(n, dtype=torch.uint8, device="cuda")),
+                                  (B.TIER_PINNED, 3, lambda n: torch.zeros(n, dtype=torch.uint8).pin_memory()),
+                                  (B.TIER_PAGEABLE, 3, lambda n: torch.zeros(n, dtype=torch.uint8))):
+            ctx.register_slab(tier, p, mk(slot * n_slots))
+        ctx.register_disk(p, str(tmp_path / f"pool_{p}.bin"), slot * n_ids)
+    ctx.register_staging(torch.zeros(biggest * int(rng.integers(2, 5)), dtype=torch.uint8, device="cuda"))
+    ctx.register_bounce(torch.zeros(biggest * 2, dtype=torch.uint8).pin_memory())
+
+    # ids 0..19 whole chunks, 20..29 key / value units of documents 0..4
+    spec, packed = [], []
+    for i in range(n_ids):
+        t = int(rng.integers(1, T + 1))
+        prec = precs_all[int(rng.integers(3))]
+        part = B.PART_KV if i < 20 else (B.PART_K if i % 2 == 0 else B.PART_V)
+        if part == B.PART_V:
+            t = spec[i - 1][2]                      # the values of a document are as long as its keys
+        doc = wl.kv_chunk(L, H, D, t, seed * 1000 + i)
+        pk = (codec.quantize_pack_chunk(doc, ORC[prec], g)[0] if part == B.PART_KV else
+              codec.quantize_pack_half(np.ascontiguousarray(doc[:, part - 1]), ORC[prec], g)[0])
+        spec.append((part, prec, t))
+        packed.append(pk)
+        if part == B.PART_KV:
+            ctx.pool_insert(i, prec, t, pk, B.TIER_DISK)
+        else:
+            ctx.pool_insert_half(i, part, prec, t, pk, B.TIER_DISK)
+    ctx.set_counts(list(range(n_ids)), rng.integers(0, 50, n_ids).tolist())
+    ctx.rerank()
+
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    pending = []                                    # (out tensor, reference)
+    tokens = [s[2] for s in spec]
+
+    def random_request():
+        req = []
+        for _ in range(int(rng.integers(1, 7))):
+            if rng.random() < 0.3:
+                d = int(rng.integers(5))
+                pair = [20 + 2 * d, 21 + 2 * d]
+                req += pair if rng.random() < 0.5 else pair[::-1]
+            else:
+                req.append(int(rng.integers(20)))
+        return req
+
+    for step in range(60):
+        op = rng.random()
+        if op < 0.70:
+            req = random_request()
+            base = int(rng.integers(0, 3))
+            rows = base + sum(tokens[c] for c in req if spec[c][0] != B.PART_V)
+            cap = rows + 1
+            ref = np.full((L, 2, H, cap, D), CANARY, np.uint16)
+            codec.load_chunks(packed, (L, H, D), tokens, [ORC[s[1]] for s in spec], [g] * n_ids, req,
+                              cap_tokens=cap, tok_base=base, out=ref, parts=[s[0] for s in spec])
+            s_ = streams[int(rng.integers(3))]
+            with torch.cuda.stream(s_):
+                out = torch.full((L, 2, H, cap, D), CANARY, dtype=torch.int16, device="cuda")
+                ctx.load_chunks(req, out, cap, tok_base=base, stream=s_)
+            pending.append((out, ref, req))
+        elif op < 0.80:
+            cid = int(rng.integers(n_ids))
+            try:
+                ctx.pool_evict(cid, int(rng.integers(3)))
+            except B.HaRagError as e:
+                assert e.code in (B.ENOENT, B.EINVAL)
+        elif op < 0.88:
+            cid = int(rng.integers(n_ids))
+            try:
+                ctx.pool_promote(cid, stream=streams[int(rng.integers(3))])
+            except B.HaRagError as e:
+                assert e.code in (B.ENOENT, B.ENOSPC)
+        elif op < 0.95:
+            ctx.set_counts([int(rng.integers(n_ids))], [int(rng.integers(0, 200))])
+            ctx.rerank()
+        else:
+            torch.cuda.synchronize()
+        if len(pending) >= 8 or step == 59:
+            torch.cuda.synchronize()
+            for out, ref, req in pending:
+                assert np.array_equal(out.cpu().numpy().view(np.uint16), ref), (seed, step, req)
+            pending.clear()
+    ctx.destroy()
