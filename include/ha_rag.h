@@ -124,6 +124,15 @@ typedef struct ha_rag_config {
                                   chunk of max_chunk_tokens (a pool that stores the 2n units
                                   of Algorithm 1); whole chunks are then refused (EFORMAT).
                                   0 = slots are sized for whole chunks; halves fit too     */
+    uint32_t pinned_dma;       /* how a chunk served from pinned memory that gets no faster copy
+                                  reaches the kernel.  0 = the dequantize kernel reads it
+                                  straight over the link (pinned memory is device-visible):
+                                  no staging slot, no copy stream, one launch per 64 chunks
+                                  (measured faster, and insensitive to host load).  1 = it
+                                  is copied to the staging area by DMA first, which keeps
+                                  the compute units free while the link is busy.  Chunks
+                                  that are promoted, or come from pageable memory or a
+                                  file, always take the DMA route                         */
 } ha_rag_config;
 
 /* One packed chunk handed to ha_rag_load_packed (no pool involved). */

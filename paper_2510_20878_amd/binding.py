@@ -37,7 +37,7 @@ class Config(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in (
         "n_layers", "n_kv_heads", "head_dim", "max_chunk_tokens", "group_int8", "group_int4",
         "tau_gpu_ppm", "rerank_interval", "n_copy_streams", "dry_run", "tau_pin_ppm",
-        "tau_page_ppm", "disk_o_direct", "half_slots")]
+        "tau_page_ppm", "disk_o_direct", "half_slots", "pinned_dma")]
 
 
 class LaunchParams(C.Structure):
@@ -239,11 +239,11 @@ class Context:
     def __init__(self, n_layers, n_kv_heads, head_dim, max_chunk_tokens, group_int8=128,
                  group_int4=128, tau_gpu_ppm=50_000, rerank_interval=0, n_copy_streams=0,
                  dry_run=False, tau_pin_ppm=0, tau_page_ppm=0, disk_o_direct=False,
-                 half_slots=False):
+                 half_slots=False, pinned_dma=False):
         self.cfg = Config(n_layers, n_kv_heads, head_dim, max_chunk_tokens, group_int8, group_int4,
                           tau_gpu_ppm, rerank_interval, n_copy_streams, 1 if dry_run else 0,
                           tau_pin_ppm, tau_page_ppm, 1 if disk_o_direct else 0,
-                          1 if half_slots else 0)
+                          1 if half_slots else 0, 1 if pinned_dma else 0)
         self._h = C.c_void_p()
         rc = lib().ha_rag_create(C.byref(self.cfg), C.byref(self._h))
         if rc:

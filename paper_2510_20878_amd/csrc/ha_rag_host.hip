@@ -463,7 +463,7 @@ struct Action {
 };
 
 K1Chunk make_desc(const ha_rag_ctx *c, const Chunk &ch, const uint8_t *src, const Request &rq,
-                  uint64_t tok_off)
+                  uint64_t tok_off, bool src_in_host_memory = false)
 {
     K1Chunk d;
     const uint64_t D = c->cfg.head_dim;
@@ -478,6 +478,7 @@ K1Chunk make_desc(const ha_rag_ctx *c, const Chunk &ch, const uint8_t *src, cons
     d.n_tokens = ch.n_tokens;
     const uint32_t g = c->group_of(ch.prec);
     d.fmt = ch.prec | ((g ? log2u(g) : 0u) << 8) | (ch.part << 16);
+    if (src_in_host_memory) d.fmt |= kWholeBlockItems;
     return d;
 }
 
@@ -643,8 +644,13 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
             if (tags && tags[i] != ch->prec) return HA_RAG_EFORMAT;
             const int f = ch->fastest();
             if (f < 0) return HA_RAG_ENOENT;
-            if (f >= (int)HA_RAG_TIER_PINNED &&
-                (c->stg.size() < 2 || ch->bytes > c->staging_slot_bytes))
+            // staging is needed by every DMA route: always from pageable memory and files,
+            // from pinned memory if pinned_dma is set or a promotion into HBM is possible
+            const bool via_staging =
+                f >= (int)HA_RAG_TIER_PAGEABLE ||
+                (f == (int)HA_RAG_TIER_PINNED &&
+                 (c->cfg.pinned_dma || c->slab[HA_RAG_TIER_HBM][ch->prec].registered()));
+            if (via_staging && (c->stg.size() < 2 || ch->bytes > c->staging_slot_bytes))
                 return HA_RAG_ENOSPC;
             if (f >= (int)HA_RAG_TIER_PAGEABLE &&
                 (c->bnc.size() < 2 || c->io_bytes(ch->bytes) > c->bounce_slot_bytes))
@@ -732,6 +738,11 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
                     }
                 }
             }
+            // Pinned copy that stays where it is: unless pinned_dma is set the kernel reads it
+            // over the link itself (no staging, no copy stream).  A pinned copy written by this very
+            // call is read after the transfers, which is when its bytes are in place.
+            if (found == HA_RAG_TIER_PINNED && !c->cfg.pinned_dma && a.place_tier == HA_RAG_TIER_NONE)
+                a.kind = ch.made_by[HA_RAG_TIER_PINNED] == call ? Action::HOT_LATE : Action::HOT_EARLY;
             if (ch.part != kPartV) st.tokens += ch.n_tokens;  // rows of the key plane
             st.packed_bytes_read += ch.bytes;
             st.bf16_bytes_written +=
@@ -742,11 +753,12 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     }
 
     // ---- pass B: enqueue ---------------------------------------------------------
-    // 1. transfers of the first cold chunks (as many as there are staging slots)
-    // 2. one kernel over every chunk that was already resident in HBM
+    // 1. one kernel over every chunk that is read where it lies: copies already resident in
+    //    HBM, and pinned copies when the kernel reads pinned memory itself
+    // 2. transfers of the first cold chunks (as many as there are staging slots)
     // 3. per cold chunk: wait for its transfer, kernel, copy into the HBM slab if it was
     //    placed there, release the staging slot, start the transfer that reuses it
-    // 4. one kernel over chunks whose HBM copy was written in step 3
+    // 4. one kernel over chunks whose copy was written in step 2 or 3
     // A transfer is a host -> HBM copy from the pinned slot, or, for pageable and disk
     // chunks, a host copy / file read into a pinned bounce buffer (synchronous, on this
     // thread; also the moment a pinned / pageable copy is written) followed by that copy.
@@ -821,26 +833,36 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
         return HA_RAG_OK;
     };
 
-    size_t started = 0;
-    for (; started < cold.size() && started < n_stg; ++started) {
-        int rc = start_transfer(started);
-        if (rc) return rc;
-    }
-
+    // Chunks read where they lie (HBM copies, and pinned copies unless pinned_dma is set) go
+    // first: their slots may be handed to other chunks by the transfers below.
     Batch batch;
     init_batch(c, batch, n_req == 1 ? reqs[0].paged : nullptr);
+    bool reads_pinned = false;
     for (const Action &a : acts) {
         if (a.kind != Action::HOT_EARLY) continue;
         const Chunk &ch = c->chunks[a.ci];
-        Slab &hs = c->slab[HA_RAG_TIER_HBM][ch.prec];
+        Slab &hs = c->slab[a.src_tier][ch.prec];
         int rc = before_read(c, hs.use[a.src_slot], s);
         if (rc) return rc;
-        rc = push(c, batch, make_desc(c, ch, hs.ptr(a.src_slot), reqs[a.req], a.tok_off), s,
-                  &st.n_kernel_launches);
+        reads_pinned |= a.src_tier == HA_RAG_TIER_PINNED;
+        rc = push(c, batch,
+                  make_desc(c, ch, hs.ptr(a.src_slot), reqs[a.req], a.tok_off,
+                            a.src_tier == HA_RAG_TIER_PINNED),
+                  s, &st.n_kernel_launches);
         if (rc) return rc;
     }
     int rc = flush(c, batch, s, &st.n_kernel_launches);
     if (rc) return rc;
+    if (reads_pinned) {  // a host write into one of those pinned slots waits for this point
+        rc = mark_stream(c, s);
+        if (rc) return rc;
+    }
+
+    size_t started = 0;
+    for (; started < cold.size() && started < n_stg; ++started) {
+        rc = start_transfer(started);
+        if (rc) return rc;
+    }
 
     for (size_t k = 0; k < cold.size(); ++k) {
         const Action &a = acts[cold[k]];
@@ -875,12 +897,14 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
         if (a.kind != Action::HOT_LATE) continue;
         const Chunk &ch = c->chunks[a.ci];
         // `made_by` in pass A guarantees the copy written by this call is still in its slot
-        if (ch.slot[HA_RAG_TIER_HBM] != a.src_slot) return HA_RAG_EINVAL;
-        Slab &hs = c->slab[HA_RAG_TIER_HBM][ch.prec];
+        if (ch.slot[a.src_tier] != a.src_slot) return HA_RAG_EINVAL;
+        Slab &hs = c->slab[a.src_tier][ch.prec];
         rc = before_read(c, hs.use[a.src_slot], s);
         if (rc) return rc;
-        rc = push(c, batch, make_desc(c, ch, hs.ptr(a.src_slot), reqs[a.req], a.tok_off), s,
-                  &st.n_kernel_launches);
+        rc = push(c, batch,
+                  make_desc(c, ch, hs.ptr(a.src_slot), reqs[a.req], a.tok_off,
+                            a.src_tier == HA_RAG_TIER_PINNED),
+                  s, &st.n_kernel_launches);
         if (rc) return rc;
     }
     rc = flush(c, batch, s, &st.n_kernel_launches);

@@ -21,8 +21,13 @@ struct K1Chunk {
                                // tile (tok_off * head_dim * 2), carried in the pointer
     uint64_t out_tile_stride;  // bytes between consecutive tiles of the cache (unused if paged)
     uint32_t n_tokens;
-    uint32_t fmt;              // Prec | log2(group) << 8 | part << 16
+    uint32_t fmt;              // Prec | log2(group) << 8 | part << 16 | kWholeBlockItems
 };
+
+// fmt flag: 8-bit formats of this chunk are decoded a whole block (four planes) per item
+// whatever K1Launch::planes8 says.  For sources in host memory, which no cache holds: a
+// two-plane item re-reads the scale/zero words its sibling item already fetched.
+constexpr uint32_t kWholeBlockItems = 1u << 18;
 
 // what a chunk holds (numbered like HA_RAG_PART_* of the C ABI): keys and values of a
 // document (tile records (l, kv, h)), or only its keys / only its values (records (l, h))

@@ -192,7 +192,8 @@ __global__ void __launch_bounds__(1024) k1_gather_dequant_scatter(const K1Params
     const uint32_t n_e = c.n_tokens * p.head_dim;
     const uint32_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
     const uint32_t prec = c.fmt & 0xFFu, gsh = (c.fmt >> 8) & 0xFFu;
-    const uint32_t planes = prec == kInt4 ? 4u : prec == kP16 ? p.planes16 : p.planes8;
+    const uint32_t planes = prec == kInt4 ? 4u : prec == kP16 ? p.planes16
+                            : (c.fmt & kWholeBlockItems) ? 4u : p.planes8;
     const uint32_t ipb_sh = planes == 4 ? 0u : planes == 2 ? 1u : 2u;  // log2(items per block)
     const uint32_t blk = r >> ipb_sh;
     const uint32_t j0 = (r - (blk << ipb_sh)) * planes;  // first plane of this item
@@ -375,10 +376,11 @@ hipError_t launch_k1(K1Params &p, const K1Launch &cfg, hipStream_t stream)
         const uint64_t n_e = (uint64_t)p.c[i].n_tokens * p.head_dim;
         if (n_e > 0x7FFFFFFFull) return hipErrorInvalidValue;  // element indices are 32-bit
         const uint64_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
-        const uint32_t prec = p.c[i].fmt & 0xFFu, part = (p.c[i].fmt >> 16) & 0xFFu;
+        const uint32_t prec = p.c[i].fmt & 0xFFu, part = (p.c[i].fmt >> 16) & 3u;
         if (prec > kGSE8 || part > kPartV) return hipErrorInvalidValue;
         if (part != kPartKV) p.any_half = 1;
-        const uint32_t planes = prec == kInt4 ? 4u : prec == kP16 ? cfg.planes16 : cfg.planes8;
+        const uint32_t planes = prec == kInt4 ? 4u : prec == kP16 ? cfg.planes16
+                                : (p.c[i].fmt & kWholeBlockItems) ? 4u : cfg.planes8;
         for (uint32_t kv = 0; kv < 2; ++kv) {
             p.item_start[kv][i] = (uint32_t)per_tile[kv];
             if (part == kPartKV || part == kPartK + kv) per_tile[kv] += nblk * (4u / planes);

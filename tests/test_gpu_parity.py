@@ -468,6 +468,51 @@ def test_pool_cold_path_promotion_and_hits_match_oracle():
     ctx.destroy()
 
 
+def test_pinned_chunks_read_by_the_kernel_itself():
+    """Chunks that stay in pinned memory are dequantized straight from it (one launch, no staging
+    traffic) unless pinned_dma is set; chunks that are promoted pass through staging; the
+    result is the same either way."""
+    L, H, D, T, g = 2, 2, 64, 96, 32
+    n = 10
+    precs_all = [B.PREC_INT4, B.PREC_INT8, B.PREC_FP8_E5M2]
+    tokens = [T - 11 * (i % 4) for i in range(n)]
+    precs = [precs_all[i % 3] for i in range(n)]
+    packed = [codec.quantize_pack_chunk(wl.kv_chunk(L, H, D, tokens[i], 700 + i), ORC[precs[i]], g)[0]
+              for i in range(n)]
+    req = [7, 0, 3, 9, 1, 4, 8, 0]
+    cap = sum(tokens[c] for c in req) + 1
+    ref = np.full((L, 2, H, cap, D), CANARY, np.uint16)
+    codec.load_chunks(packed, (L, H, D), tokens, [ORC[p] for p in precs], [g] * n, req, cap_tokens=cap,
+                      out=ref)
+    for zero_copy in (True, False):
+        ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=300_000,
+                        pinned_dma=not zero_copy)
+        big = 0
+        for p in precs_all:
+            slot = (ctx.chunk_bytes(p, T) + 255) // 256 * 256
+            big = max(big, slot)
+            ctx.register_slab(B.TIER_HBM, p, torch.zeros(slot * 2, dtype=torch.uint8, device="cuda"))
+            ctx.register_slab(B.TIER_PINNED, p, torch.zeros(slot * n, dtype=torch.uint8).pin_memory())
+        ctx.register_staging(torch.zeros(big * 2, dtype=torch.uint8, device="cuda"))
+        for i in range(n):
+            ctx.pool_insert(i, precs[i], tokens[i], packed[i], B.TIER_PINNED)
+        ctx.set_counts(list(range(n)), [100 - i for i in range(n)])
+        ctx.rerank()                                   # GPU_LIST = ids 0, 1, 2
+        out = torch.full((L, 2, H, cap, D), CANARY, dtype=torch.int16, device="cuda")
+        st, tr = ctx.load_chunks(req, out, cap, want_trace=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(host_u16(out), ref), zero_copy
+        assert [t.promoted for t in tr] == [0, 1, 0, 0, 1, 0, 0, 0]
+        # promoted chunks go through staging (one launch each); the others share one launch
+        assert st["n_kernel_launches"] == (4 if zero_copy else 8)
+        out.fill_(CANARY)
+        st, tr = ctx.load_chunks(req, out, cap, want_trace=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(host_u16(out), ref), zero_copy
+        assert st["n_kernel_launches"] == (1 if zero_copy else 6)
+        ctx.destroy()
+
+
 def test_explicit_promote_evict_and_insert_from_device():
     L, H, D, T, g = 1, 2, 128, 64, 128
     ctx = _pool_ctx(L, H, D, T, g, hbm_slots=2, pin_slots=4, stg_slots=2, tau_gpu_ppm=0,

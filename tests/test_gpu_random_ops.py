@@ -26,14 +26,15 @@ def _need_gpu():
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("pinned_dma", [False, True])
 @pytest.mark.parametrize("seed", [1, 2, 3, 4, 5, 6])
-def test_random_operations_match_oracle(tmp_path, seed):
+def test_random_operations_match_oracle(tmp_path, seed, pinned_dma):
     rng = np.random.default_rng(seed)
     L, H, D, T, g = 1, 2, 64, 48, 32
     precs_all = [B.PREC_INT4, B.PREC_INT8, B.PREC_GSE8]
     ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=250_000, tau_pin_ppm=250_000,
                     tau_page_ppm=250_000, rerank_interval=int(rng.integers(0, 4)),
-                    n_copy_streams=int(rng.integers(1, 4)))
+                    n_copy_streams=int(rng.integers(1, 4)), pinned_dma=pinned_dma)
     n_ids = 30
     keep = []
     biggest = 0
