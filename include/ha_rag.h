@@ -206,7 +206,7 @@ typedef struct ha_rag_load_stats {
     uint32_t n_placed_host;      /* copies placed into pinned or pageable memory     */
     uint32_t reserved[2];
     uint64_t tokens;
-    uint64_t bytes_h2d;          /* packed bytes copied host -> HBM staging          */
+    uint64_t bytes_h2d;          /* packed bytes that crossed the host link          */
     uint64_t bytes_d2d;          /* packed bytes copied staging -> HBM slab          */
     uint64_t packed_bytes_read;  /* payload + meta bytes the kernels read            */
     uint64_t bf16_bytes_written; /* bytes written to the cache                       */
@@ -333,8 +333,10 @@ int ha_rag_register_slab(ha_rag_ctx *ctx, uint32_t tier, uint32_t prec, void *ba
  * is not deleted.  EIO if it cannot be opened or grown. */
 int ha_rag_register_disk(ha_rag_ctx *ctx, uint32_t prec, const char *path, size_t bytes);
 
-/* Device staging area that cold chunks pass through on their way from host memory
- * to the kernel (256-byte aligned).  It is cut into slots as large as the largest
+/* Device staging area that chunks on the DMA route pass through on their way from
+ * host memory to the kernel (256-byte aligned): chunks from pageable memory and
+ * files, pinned chunks that are promoted to HBM, every pinned chunk under pinned_dma.
+ * A pool whose pinned chunks are only ever read in place needs none.  It is cut into slots as large as the largest
  * host-side slot registered so far; at least 2 slots are required. */
 int ha_rag_register_staging(ha_rag_ctx *ctx, void *base, size_t bytes);
 
@@ -406,11 +408,13 @@ int ha_rag_get_rank(ha_rag_ctx *ctx, uint64_t id, uint32_t *rank);
 /* ---- online: the load (Algorithm 2 step 2 + decompression + concatenation) --- */
 
 /* For each id in request order: count the access; find the fastest tier that holds
- * the chunk and refresh its LRU position there; if that is HBM, read it in place;
- * else bring the packed bytes into a staging slot (pinned: a host -> HBM copy on a
- * copy stream; pageable / disk: the calling thread first copies / reads them into a
- * bounce buffer) and make `stream` wait for that copy; dequantize-scatter the chunk
- * to its token rows; and if the list its rank belongs to (GPU_LIST, PIN_LIST,
+ * the chunk and refresh its LRU position there; if that is HBM, read it in place,
+ * and so for a pinned copy that gets no faster copy (the kernel reads pinned memory
+ * over the link; see pinned_dma in ha_rag_config); else bring the packed bytes into
+ * a staging slot (pinned: a host -> HBM copy on a copy stream; pageable / disk: the
+ * calling thread first copies / reads them into a bounce buffer) and make `stream`
+ * wait for that copy; dequantize-scatter the chunk to its token rows; and if the
+ * list its rank belongs to (GPU_LIST, PIN_LIST,
  * PAGE_LIST) names a faster tier than the one it was found in, place a copy there
  * (HBM: copied from staging on `stream`; pinned / pageable: copied from the bounce
  * buffer by the calling thread), evicting the least recently used evictable chunk
