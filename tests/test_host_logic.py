@@ -575,3 +575,31 @@ def test_hundred_thousand_ids_ranks_lists_and_trace_equal_oracle():
     for tier in (B.TIER_HBM, B.TIER_PINNED, B.TIER_PAGEABLE):
         assert ctx.pool_lru(tier) == sim.resident(tier)
     ctx.destroy()
+
+
+def test_pinned_only_pool_needs_no_staging_unless_dma_is_asked_for():
+    for dma in (False, True):
+        ctx = B.Context(2, 2, 64, 128, group_int8=64, group_int4=64, tau_gpu_ppm=500_000, dry_run=True,
+                        pinned_dma=dma)
+        slot = (ctx.chunk_bytes(B.PREC_INT4, 128) + 255) // 256 * 256
+        ctx.register_slab(B.TIER_PINNED, B.PREC_INT4, FAKE_PIN, slot * 4)
+        for c in range(4):
+            ctx.pool_insert(c, B.PREC_INT4, 100, None, B.TIER_PINNED)
+        if dma:
+            with pytest.raises(B.HaRagError) as e:
+                ctx.load_chunks([0, 1, 2], FAKE_HBM, 300)
+            assert e.value.code == B.ENOSPC               # DMA needs the staging area
+            ctx.register_staging(FAKE_STG, slot * 2)
+            st, _ = ctx.load_chunks([0, 1, 2], FAKE_HBM, 300)
+            assert st["n_kernel_launches"] == 3           # one per transferred chunk
+        else:
+            st, _ = ctx.load_chunks([0, 1, 2], FAKE_HBM, 300)
+            assert st["n_kernel_launches"] == 1           # read in place, one launch
+        assert st["n_pinned_hits"] == 3 and st["bytes_h2d"] == 3 * ctx.chunk_bytes(B.PREC_INT4, 100)
+        # once an HBM slab exists a promotion may need the staging area
+        ctx.register_slab(B.TIER_HBM, B.PREC_INT4, FAKE_HBM, slot * 2)
+        if not dma:
+            with pytest.raises(B.HaRagError) as e:
+                ctx.load_chunks([3], FAKE_HBM, 300)
+            assert e.value.code == B.ENOSPC
+        ctx.destroy()
