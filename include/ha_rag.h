@@ -150,7 +150,8 @@ typedef struct ha_rag_chunk_info {
     uint32_t rank;              /* 0 = hottest, as of the last rerank         */
     uint32_t in_pageable, on_disk; /* 0 / 1                                   */
     uint32_t part;              /* HA_RAG_PART_*                              */
-    uint32_t reserved;
+    uint32_t disk_slot;         /* slot index in the tag's pool file, or
+                                   UINT32_MAX if the chunk has no file copy   */
     uint64_t count;             /* accesses so far (Algorithm 1's AF entry)   */
     uint64_t bytes;             /* packed size                                */
     const void *hbm_ptr;        /* slot address or NULL                       */
@@ -383,6 +384,20 @@ int ha_rag_pool_promote(ha_rag_ctx *ctx, uint64_t id, void *stream);
 int ha_rag_pool_evict(ha_rag_ctx *ctx, uint64_t id, uint32_t tier);
 
 int ha_rag_pool_query(ha_rag_ctx *ctx, uint64_t id, ha_rag_chunk_info *info);
+
+/* The knowledge base is files (Sec. 2.1: the precomputed KV is stored and loaded on demand);
+ * these two calls let it outlive the process.  save_index writes, for every chunk that
+ * has a copy in the file tier, {id, access count, tag, part, n_tokens, file slot} plus the
+ * shape, groups and slot sizes of the context to `path` (a small binary file, native byte
+ * order).  load_index, on a fresh context with the same shape and groups and with the same
+ * pool files registered again (ha_rag_register_disk keeps their contents), adds those
+ * chunks back as file-tier masters with their counts; ranks follow the next ha_rag_rerank.
+ * Faster tiers start empty and fill through Algorithm 2 as before.  Nothing changes unless
+ * every entry fits.  EIO: file missing, truncated or not an index; EFORMAT: shape, group,
+ * slot size or an entry does not match this context; EINVAL: an id already exists or a
+ * slot is in use. */
+int ha_rag_pool_save_index(ha_rag_ctx *ctx, const char *path);
+int ha_rag_pool_load_index(ha_rag_ctx *ctx, const char *path, size_t *n_loaded);
 
 /* Ids resident in `tier` (HBM, pinned or pageable), least recently used first;
  * returns how many were written (at most `cap`) through *n.  ha_rag_pool_hbm_lru is

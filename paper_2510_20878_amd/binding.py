@@ -29,7 +29,8 @@ SYMBOLS = [
     "ha_rag_set_counts", "ha_rag_rerank", "ha_rag_get_rank", "ha_rag_load_chunks",
     "ha_rag_load_batch", "ha_rag_register_disk", "ha_rag_register_bounce", "ha_rag_pool_lru",
     "ha_rag_quantize_half", "ha_rag_pool_insert_half", "ha_rag_load_packed_paged",
-    "ha_rag_load_chunks_paged", "ha_rag_chunk_sq_error",
+    "ha_rag_load_chunks_paged", "ha_rag_chunk_sq_error", "ha_rag_pool_save_index",
+    "ha_rag_pool_load_index",
 ]
 
 
@@ -61,7 +62,7 @@ class ChunkInfo(C.Structure):
     _fields_ = [("prec", C.c_uint32), ("group", C.c_uint32), ("n_tokens", C.c_uint32),
                 ("in_hbm", C.c_uint32), ("in_pinned", C.c_uint32), ("rank", C.c_uint32),
                 ("in_pageable", C.c_uint32), ("on_disk", C.c_uint32),
-                ("part", C.c_uint32), ("reserved", C.c_uint32), ("count", C.c_uint64), ("bytes", C.c_uint64),
+                ("part", C.c_uint32), ("disk_slot", C.c_uint32), ("count", C.c_uint64), ("bytes", C.c_uint64),
                 ("hbm_ptr", C.c_void_p), ("pinned_ptr", C.c_void_p)]
 
 
@@ -136,6 +137,8 @@ def lib():
             "ha_rag_register_staging": (C.c_int, [vp, vp, sz]),
             "ha_rag_register_bounce": (C.c_int, [vp, vp, sz]),
             "ha_rag_register_disk": (C.c_int, [vp, u32, C.c_char_p, sz]),
+            "ha_rag_pool_save_index": (C.c_int, [vp, C.c_char_p]),
+            "ha_rag_pool_load_index": (C.c_int, [vp, C.c_char_p, P(sz)]),
             "ha_rag_pool_lru": (C.c_int, [vp, u32, P(u64), sz, P(sz)]),
             "ha_rag_pool_insert": (C.c_int, [vp, u64, u32, u32, vp, C.c_int, u32, vp]),
             "ha_rag_pool_slot": (C.c_int, [vp, u64, u32, P(vp), P(sz)]),
@@ -375,6 +378,15 @@ class Context:
         info = ChunkInfo()
         self._chk(lib().ha_rag_pool_query(self._h, cid, C.byref(info)), "ha_rag_pool_query")
         return info
+
+    def pool_save_index(self, path):
+        self._chk(lib().ha_rag_pool_save_index(self._h, os.fsencode(path)), "ha_rag_pool_save_index")
+
+    def pool_load_index(self, path):
+        n = C.c_size_t()
+        self._chk(lib().ha_rag_pool_load_index(self._h, os.fsencode(path), C.byref(n)),
+                  "ha_rag_pool_load_index")
+        return n.value
 
     def pool_lru(self, tier, cap=1 << 16):
         ids = (C.c_uint64 * cap)()

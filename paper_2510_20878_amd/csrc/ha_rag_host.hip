@@ -1433,6 +1433,7 @@ int ha_rag_pool_query(ha_rag_ctx *c, uint64_t id, ha_rag_chunk_info *info)
     info->group = c->group_of(ch->prec);
     info->n_tokens = ch->n_tokens;
     info->part = ch->part;
+    info->disk_slot = ch->slot[HA_RAG_TIER_DISK] >= 0 ? (uint32_t)ch->slot[HA_RAG_TIER_DISK] : UINT32_MAX;
     info->in_hbm = ch->slot[HA_RAG_TIER_HBM] >= 0;
     info->in_pinned = ch->slot[HA_RAG_TIER_PINNED] >= 0;
     info->in_pageable = ch->slot[HA_RAG_TIER_PAGEABLE] >= 0;
@@ -1463,6 +1464,145 @@ int ha_rag_pool_lru(ha_rag_ctx *c, uint32_t tier, uint64_t *ids, size_t cap, siz
 int ha_rag_pool_hbm_lru(ha_rag_ctx *c, uint64_t *ids, size_t cap, size_t *n)
 {
     return ha_rag_pool_lru(c, HA_RAG_TIER_HBM, ids, cap, n);
+}
+
+// ---- the knowledge base survives the process: index of the file tier ---------------
+namespace {
+
+struct IndexHeader {
+    char magic[8];  // "HARAGIX1"
+    uint32_t n_layers, n_kv_heads, head_dim, max_chunk_tokens, group_int8, group_int4, half_slots;
+    uint32_t n_prec;
+    uint64_t slot_bytes[HA_RAG_N_PREC];  // of the file slab per tag, 0 = none registered
+    uint64_t n_entries;
+};
+
+struct IndexEntry {
+    uint64_t id, count;
+    uint32_t prec, part, n_tokens;
+    int32_t slot;
+};
+
+const char kIndexMagic[8] = {'H', 'A', 'R', 'A', 'G', 'I', 'X', '1'};
+
+}  // namespace
+
+int ha_rag_pool_save_index(ha_rag_ctx *c, const char *path)
+{
+    if (!c || !path) return HA_RAG_EINVAL;
+    std::lock_guard<std::mutex> g(c->mu);
+    IndexHeader h;
+    std::memset(&h, 0, sizeof h);
+    std::memcpy(h.magic, kIndexMagic, 8);
+    h.n_layers = c->cfg.n_layers;
+    h.n_kv_heads = c->cfg.n_kv_heads;
+    h.head_dim = c->cfg.head_dim;
+    h.max_chunk_tokens = c->cfg.max_chunk_tokens;
+    h.group_int8 = c->cfg.group_int8;
+    h.group_int4 = c->cfg.group_int4;
+    h.half_slots = c->cfg.half_slots;
+    h.n_prec = HA_RAG_N_PREC;
+    for (uint32_t p = 0; p < HA_RAG_N_PREC; ++p)
+        h.slot_bytes[p] = c->slab[HA_RAG_TIER_DISK][p].registered() ? c->slab[HA_RAG_TIER_DISK][p].slot_bytes : 0;
+    std::vector<IndexEntry> entries;
+    for (const Chunk &ch : c->chunks) {
+        if (ch.slot[HA_RAG_TIER_DISK] < 0) continue;
+        IndexEntry e;
+        std::memset(&e, 0, sizeof e);
+        e.id = ch.id;
+        e.count = ch.count;
+        e.prec = ch.prec;
+        e.part = ch.part;
+        e.n_tokens = ch.n_tokens;
+        e.slot = ch.slot[HA_RAG_TIER_DISK];
+        entries.push_back(e);
+    }
+    h.n_entries = entries.size();
+    FILE *f = std::fopen(path, "wb");
+    if (!f) return io_error(c, "fopen");
+    bool ok = std::fwrite(&h, sizeof h, 1, f) == 1;
+    if (ok && !entries.empty())
+        ok = std::fwrite(entries.data(), sizeof(IndexEntry), entries.size(), f) == entries.size();
+    if (std::fclose(f) != 0) ok = false;
+    if (!ok) return io_error(c, "fwrite");
+    return HA_RAG_OK;
+}
+
+int ha_rag_pool_load_index(ha_rag_ctx *c, const char *path, size_t *n_loaded)
+{
+    if (!c || !path) return HA_RAG_EINVAL;
+    std::lock_guard<std::mutex> g(c->mu);
+    FILE *f = std::fopen(path, "rb");
+    if (!f) return io_error(c, "fopen");
+    IndexHeader h;
+    std::vector<IndexEntry> entries;
+    bool ok = std::fread(&h, sizeof h, 1, f) == 1;
+    if (ok && h.n_entries <= 0x7FFFFFFFull && std::memcmp(h.magic, kIndexMagic, 8) == 0) {
+        entries.resize((size_t)h.n_entries);
+        if (!entries.empty())
+            ok = std::fread(entries.data(), sizeof(IndexEntry), entries.size(), f) == entries.size();
+    } else {
+        ok = false;
+    }
+    std::fclose(f);
+    if (!ok) {
+        c->err = "index file: truncated or not an index";
+        return HA_RAG_EIO;
+    }
+    // the files hold bytes of one shape and one slot grid: both must be the ones of this context
+    if (h.n_layers != c->cfg.n_layers || h.n_kv_heads != c->cfg.n_kv_heads ||
+        h.head_dim != c->cfg.head_dim || h.max_chunk_tokens != c->cfg.max_chunk_tokens ||
+        h.group_int8 != c->cfg.group_int8 || h.group_int4 != c->cfg.group_int4 ||
+        h.half_slots != c->cfg.half_slots || h.n_prec != HA_RAG_N_PREC)
+        return HA_RAG_EFORMAT;
+    // checks first: nothing changes unless every entry fits
+    std::vector<std::vector<uint8_t>> taken(HA_RAG_N_PREC);
+    for (const IndexEntry &e : entries) {
+        if (e.prec >= HA_RAG_N_PREC || e.part > kPartV || e.id == HA_RAG_NO_CHUNK) return HA_RAG_EFORMAT;
+        const Slab &sl = c->slab[HA_RAG_TIER_DISK][e.prec];
+        if (!sl.registered() || sl.slot_bytes != h.slot_bytes[e.prec]) return HA_RAG_EFORMAT;
+        if (e.slot < 0 || (uint32_t)e.slot >= sl.n_slots) return HA_RAG_EFORMAT;
+        if (e.n_tokens == 0 || e.n_tokens > c->cfg.max_chunk_tokens) return HA_RAG_EFORMAT;
+        if (e.part == kPartKV && c->cfg.half_slots) return HA_RAG_EFORMAT;
+        if (c->index.count(e.id)) return HA_RAG_EINVAL;
+        if (taken[e.prec].empty()) {
+            taken[e.prec].assign(sl.n_slots, 1);
+            for (uint32_t fs : sl.free_slots) taken[e.prec][fs] = 0;
+        }
+        if (taken[e.prec][e.slot]) return HA_RAG_EINVAL;  // slot in use, or named twice
+        taken[e.prec][e.slot] = 1;
+    }
+    {
+        std::vector<uint64_t> ids(entries.size());
+        for (size_t i = 0; i < entries.size(); ++i) ids[i] = entries[i].id;
+        std::sort(ids.begin(), ids.end());
+        if (std::adjacent_find(ids.begin(), ids.end()) != ids.end()) return HA_RAG_EINVAL;
+    }
+    for (const IndexEntry &e : entries) {
+        size_t total = 0;
+        (void)chunk_bytes_impl(c->cfg.n_layers, c->cfg.n_kv_heads, c->cfg.head_dim, e.prec,
+                               c->group_of(e.prec), e.n_tokens, nullptr, nullptr, &total, e.part);
+        const uint32_t ci = (uint32_t)c->chunks.size();
+        c->chunks.emplace_back();
+        Chunk &ch = c->chunks.back();
+        ch.id = e.id;
+        ch.prec = e.prec;
+        ch.part = e.part;
+        ch.n_tokens = e.n_tokens;
+        ch.bytes = total;
+        ch.count = e.count;
+        ch.slot[HA_RAG_TIER_DISK] = e.slot;
+        c->index.emplace(e.id, ci);
+    }
+    for (uint32_t p = 0; p < HA_RAG_N_PREC; ++p) {
+        if (taken[p].empty()) continue;
+        Slab &sl = c->slab[HA_RAG_TIER_DISK][p];
+        sl.free_slots.clear();
+        for (uint32_t i = sl.n_slots; i-- > 0;)
+            if (!taken[p][i]) sl.free_slots.push_back(i);  // lowest slot on top of the stack
+    }
+    if (n_loaded) *n_loaded = entries.size();
+    return HA_RAG_OK;
 }
 
 int ha_rag_touch(ha_rag_ctx *c, const uint64_t *ids, size_t n)

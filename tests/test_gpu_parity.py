@@ -893,3 +893,63 @@ def test_load_packed_can_be_captured_in_a_hip_graph_and_replayed():
         torch.cuda.synchronize()
         assert np.array_equal(host_u16(out), ref), rnd
     ctx.destroy()
+
+
+def test_knowledge_base_files_survive_the_context(tmp_path):
+    """Pool files plus the saved index are the knowledge base: a second context that registers
+    the same files and loads the index serves the same bytes (whole chunks and key / value
+    units, buffered and O_DIRECT files)."""
+    L, H, D, T, g = 2, 2, 64, 64, 32
+    for o_direct in (False, True):
+        def make():
+            ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=300_000,
+                            disk_o_direct=o_direct)
+            big = 0
+            for p in (B.PREC_INT4, B.PREC_GSE8):
+                slot = (ctx.chunk_bytes(p, T) + 4095) // 4096 * 4096
+                big = max(big, slot)
+                ctx.register_slab(B.TIER_HBM, p, torch.zeros(slot * 2, dtype=torch.uint8, device="cuda"))
+                ctx.register_disk(p, str(tmp_path / f"kb_{int(o_direct)}_{p}.bin"), slot * 8)
+            ctx.register_staging(torch.zeros(big * 2, dtype=torch.uint8, device="cuda"))
+            ctx.register_bounce(torch.zeros(big * 2, dtype=torch.uint8).pin_memory())
+            return ctx
+        try:
+            a = make()
+        except B.HaRagError as e:
+            if o_direct and e.code == B.EIO:
+                pytest.skip("this filesystem refuses O_DIRECT")
+            raise
+        spec = [(B.PART_KV, B.PREC_INT4, 64), (B.PART_K, B.PREC_GSE8, 40), (B.PART_V, B.PREC_INT4, 40),
+                (B.PART_KV, B.PREC_GSE8, 17), (B.PART_KV, B.PREC_INT4, 33)]
+        packed = []
+        for i, (part, prec, t) in enumerate(spec):
+            doc = wl.kv_chunk(L, H, D, t, 2100 + i)
+            if part == B.PART_KV:
+                pk = codec.quantize_pack_chunk(doc, ORC[prec], g)[0]
+                a.pool_insert(50 + i, prec, t, pk, B.TIER_DISK)
+            else:
+                pk = codec.quantize_pack_half(np.ascontiguousarray(doc[:, part - 1]), ORC[prec], g)[0]
+                a.pool_insert_half(50 + i, part, prec, t, pk, B.TIER_DISK)
+            packed.append(pk)
+        a.set_counts([50, 51, 52, 53, 54], [5, 4, 3, 2, 1])
+        idx = str(tmp_path / f"kb_{int(o_direct)}.idx")
+        a.pool_save_index(idx)
+        a.destroy()
+
+        b = make()
+        assert b.pool_load_index(idx) == 5
+        b.rerank()
+        req = [4, 1, 2, 0, 3]
+        tokens = [s_[2] for s_ in spec]
+        cap = 33 + 40 + 64 + 17
+        ref = np.full((L, 2, H, cap, D), CANARY, np.uint16)
+        codec.load_chunks(packed, (L, H, D), tokens, [ORC[s_[1]] for s_ in spec], [g] * 5, req,
+                          cap_tokens=cap, out=ref, parts=[s_[0] for s_ in spec])
+        for rnd in range(2):          # first from the files, then partly from the HBM copies made
+            out = torch.full((L, 2, H, cap, D), CANARY, dtype=torch.int16, device="cuda")
+            st, tr = b.load_chunks([50 + c for c in req], out, cap, want_trace=True)
+            torch.cuda.synchronize()
+            assert np.array_equal(host_u16(out), ref), (o_direct, rnd)
+            if rnd == 0:
+                assert st["n_disk_hits"] == 5
+        b.destroy()

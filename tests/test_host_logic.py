@@ -603,3 +603,105 @@ def test_pinned_only_pool_needs_no_staging_unless_dma_is_asked_for():
                 ctx.load_chunks([3], FAKE_HBM, 300)
             assert e.value.code == B.ENOSPC
         ctx.destroy()
+
+
+# ---- the file tier's index outlives the context -------------------------------------------
+def _disk_ctx(n_slots, half_slots=False, T=128, group4=64):
+    ctx = B.Context(2, 2, 64, T, group_int8=64, group_int4=group4, tau_gpu_ppm=200_000, dry_run=True,
+                    half_slots=half_slots)
+    for prec in (B.PREC_INT4, B.PREC_INT8):
+        nb = ctx.chunk_bytes(prec, T, part=B.PART_K if half_slots else B.PART_KV)
+        ctx.register_disk(prec, "/nonexistent/dry-run", (nb + 4095) // 4096 * 4096 * n_slots)
+        ctx.register_slab(B.TIER_HBM, prec, FAKE_HBM + prec * (1 << 32), (nb + 255) // 256 * 256 * 2)
+    big = (ctx.chunk_bytes(B.PREC_INT8, T) + 4095) // 4096 * 4096
+    ctx.register_staging(FAKE_STG, big * 2)
+    ctx.register_bounce(FAKE_BNC, big * 2)
+    return ctx
+
+
+def test_index_round_trip_restores_masters_counts_and_slots(tmp_path):
+    path = str(tmp_path / "kb.idx")
+    a = _disk_ctx(8)
+    ids = [7, 3, 900, 12, 5]
+    for k, cid in enumerate(ids):
+        a.pool_insert(cid, B.PREC_INT4 if k % 2 else B.PREC_INT8, 100 + k, None, B.TIER_DISK)
+    a.pool_insert(77, B.PREC_INT4, 50, None, B.TIER_HBM)          # no file copy: not in the index
+    a.set_counts(ids, [10, 40, 30, 20, 50])
+    a.rerank()
+    a.load_chunks([3, 5], FAKE_HBM, 400)                          # counts move, 5 and 3 get HBM copies
+    a.pool_save_index(path)
+    before = {cid: a.pool_query(cid) for cid in ids}
+    slots = {cid: before[cid].disk_slot for cid in ids}
+    assert len({(before[c].prec, slots[c]) for c in ids}) == len(ids)
+    a.destroy()
+
+    b = _disk_ctx(8)
+    assert b.pool_load_index(path) == len(ids)
+    for cid in ids:
+        q = b.pool_query(cid)
+        assert (q.prec, q.n_tokens, q.part, q.count, q.bytes) == \
+            (before[cid].prec, before[cid].n_tokens, before[cid].part, before[cid].count, before[cid].bytes)
+        assert q.on_disk == 1 and q.in_hbm == 0                   # faster tiers start empty
+        assert q.disk_slot == slots[cid]
+    with pytest.raises(B.HaRagError) as e:
+        b.pool_query(77)
+    assert e.value.code == B.ENOENT
+    b.rerank()
+    assert sorted(ids, key=lambda c: b.get_rank(c)) == sorted(ids, key=lambda c: (-before[c].count, c))
+    # restored slots are taken: new chunks get other slots, and a full file slab says so
+    used = {slots[c] for c in ids if before[c].prec == B.PREC_INT4}
+    b.pool_insert(1000, B.PREC_INT4, 10, None, B.TIER_DISK)
+    assert b.pool_query(1000).disk_slot not in used
+    st, tr = b.load_chunks([5, 3, 12], FAKE_HBM, 400, want_trace=True)
+    assert [t.found_tier for t in tr] == [B.TIER_DISK] * 3
+    with pytest.raises(B.HaRagError) as e:                        # the same index twice: ids exist
+        b.pool_load_index(path)
+    assert e.value.code == B.EINVAL
+    b.destroy()
+
+
+def test_index_is_refused_by_a_context_that_does_not_match(tmp_path):
+    path = str(tmp_path / "kb.idx")
+    a = _disk_ctx(4)
+    a.pool_insert(1, B.PREC_INT4, 100, None, B.TIER_DISK)
+    a.pool_save_index(path)
+    a.destroy()
+    for make, code in ((lambda: _disk_ctx(4, T=64), B.EFORMAT),          # other slot size / max tokens
+                       (lambda: _disk_ctx(4, group4=32), B.EFORMAT),
+                       (lambda: _disk_ctx(4, half_slots=True), B.EFORMAT)):
+        c = make()
+        with pytest.raises(B.HaRagError) as e:
+            c.pool_load_index(path)
+        assert e.value.code == code
+        with pytest.raises(B.HaRagError):
+            c.pool_query(1)                                               # nothing was added
+        c.destroy()
+    c = _disk_ctx(4)
+    with pytest.raises(B.HaRagError) as e:
+        c.pool_load_index(str(tmp_path / "missing.idx"))
+    assert e.value.code == B.EIO
+    bad = tmp_path / "bad.idx"
+    bad.write_bytes(open(path, "rb").read()[:40])
+    with pytest.raises(B.HaRagError) as e:
+        c.pool_load_index(str(bad))
+    assert e.value.code == B.EIO
+    c.pool_insert(1, B.PREC_INT8, 10, None, B.TIER_DISK)                  # id 1 exists already
+    with pytest.raises(B.HaRagError) as e:
+        c.pool_load_index(path)
+    assert e.value.code == B.EINVAL
+    c.destroy()
+
+
+def test_index_with_key_and_value_units(tmp_path):
+    path = str(tmp_path / "kb.idx")
+    a = _disk_ctx(6, half_slots=True)
+    a.pool_insert_half(10, B.PART_K, B.PREC_INT8, 90, None, B.TIER_DISK)
+    a.pool_insert_half(20, B.PART_V, B.PREC_INT4, 90, None, B.TIER_DISK)
+    a.pool_save_index(path)
+    a.destroy()
+    b = _disk_ctx(6, half_slots=True)
+    assert b.pool_load_index(path) == 2
+    assert b.pool_query(10).part == B.PART_K and b.pool_query(20).part == B.PART_V
+    st, tr = b.load_chunks([20, 10], FAKE_HBM, 90, want_trace=True)
+    assert [t.tok_off for t in tr] == [0, 0]
+    b.destroy()
