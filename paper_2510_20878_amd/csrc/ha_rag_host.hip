@@ -1537,7 +1537,13 @@ int ha_rag_pool_load_index(ha_rag_ctx *c, const char *path, size_t *n_loaded)
     IndexHeader h;
     std::vector<IndexEntry> entries;
     bool ok = std::fread(&h, sizeof h, 1, f) == 1;
-    if (ok && h.n_entries <= 0x7FFFFFFFull && std::memcmp(h.magic, kIndexMagic, 8) == 0) {
+    long file_bytes = -1;
+    if (ok && std::fseek(f, 0, SEEK_END) == 0) file_bytes = std::ftell(f);
+    ok = ok && file_bytes >= 0 && std::fseek(f, (long)sizeof h, SEEK_SET) == 0;
+    // the entry count has to be the one the file's size implies before anything is allocated
+    if (ok && std::memcmp(h.magic, kIndexMagic, 8) == 0 &&
+        h.n_entries == ((uint64_t)file_bytes - sizeof h) / sizeof(IndexEntry) &&
+        ((uint64_t)file_bytes - sizeof h) % sizeof(IndexEntry) == 0) {
         entries.resize((size_t)h.n_entries);
         if (!entries.empty())
             ok = std::fread(entries.data(), sizeof(IndexEntry), entries.size(), f) == entries.size();

@@ -123,6 +123,32 @@ int main(int argc, char **argv)
                 int rc = ha_rag_load_chunks_paged(ctx, ids.data(), nullptr, (uint32_t)ids.size(), &pc,
                                                   rnd() % 4, nullptr, &st, nullptr);
                 REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOSPC || rc == HA_RAG_EINVAL);
+            } else if (what < 80) {  // save the index, damage a copy of it at random, load both
+                const char *good = "/tmp/ha_rag_fuzz.idx", *bad = "/tmp/ha_rag_fuzz_bad.idx";
+                REQUIRE(ha_rag_pool_save_index(ctx, good) == HA_RAG_OK);
+                std::vector<unsigned char> bytes;
+                if (FILE *f = std::fopen(good, "rb")) {
+                    int ch;
+                    while ((ch = std::fgetc(f)) != EOF) bytes.push_back((unsigned char)ch);
+                    std::fclose(f);
+                }
+                REQUIRE(bytes.size() >= 64);
+                const uint64_t how = rnd() % 3;
+                if (how == 0) bytes.resize(rnd() % bytes.size());            // truncated
+                else for (int k = 0; k < 4; ++k) bytes[rnd() % bytes.size()] ^= (unsigned char)(1u << (rnd() % 8));
+                if (FILE *f = std::fopen(bad, "wb")) {
+                    if (!bytes.empty()) std::fwrite(bytes.data(), 1, bytes.size(), f);
+                    std::fclose(f);
+                }
+                ha_rag_ctx *other = nullptr;
+                REQUIRE(ha_rag_create(&cfg, &other) == HA_RAG_OK);
+                for (uint32_t p = 0; p < HA_RAG_N_PREC; ++p)
+                    REQUIRE(ha_rag_register_disk(other, p, "/nonexistent/dry-run", (slot[p] + 4096) * 24) == HA_RAG_OK);
+                size_t n_loaded = 0;
+                int rc = ha_rag_pool_load_index(other, bad, &n_loaded);      // any verdict, no crash
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_EIO || rc == HA_RAG_EFORMAT || rc == HA_RAG_EINVAL);
+                if (rc != HA_RAG_OK) REQUIRE(ha_rag_pool_load_index(other, good, &n_loaded) == HA_RAG_OK);
+                REQUIRE(ha_rag_destroy(other) == HA_RAG_OK);
             } else if (what < 82 && !known.empty()) {
                 int rc = ha_rag_pool_promote(ctx, known[rnd() % known.size()], nullptr);
                 REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOSPC || rc == HA_RAG_ENOENT);
