@@ -61,6 +61,11 @@
 extern "C" {
 #endif
 
+/* the functions declared here are the only symbols the library exports */
+#if defined(__GNUC__) || defined(__clang__)
+#pragma GCC visibility push(default)
+#endif
+
 #define HA_RAG_OK 0
 #define HA_RAG_EINVAL (-1)  /* null pointer, bad size, duplicate id, misaligned buffer  */
 #define HA_RAG_ENOENT (-2)  /* unknown chunk id                                          */
@@ -463,6 +468,10 @@ int ha_rag_load_batch(ha_rag_ctx *ctx, const uint64_t *ids, const uint8_t *tags,
 int ha_rag_load_chunks_paged(ha_rag_ctx *ctx, const uint64_t *ids, const uint8_t *tags, uint32_t n,
                              const ha_rag_paged_cache *cache, uint64_t tok_base, void *stream,
                              ha_rag_load_stats *stats, ha_rag_chunk_trace *trace);
+
+#if defined(__GNUC__) || defined(__clang__)
+#pragma GCC visibility pop
+#endif
 
 #ifdef __cplusplus
 }

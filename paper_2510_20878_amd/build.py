@@ -6,14 +6,15 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIBDIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIBDIR, "libha_rag.so")
-SOURCES = ["ha_rag_kernels.hip", "ha_rag_host.hip"]
-HEADERS = [os.path.join(CSRC, "ha_rag_kernels.h"),
+SOURCES = ["ha_rag_kernels.hip", "ha_rag_api.hip", "ha_rag_pool.hip", "ha_rag_load.hip", "ha_rag_io.hip"]
+HEADERS = [os.path.join(CSRC, "ha_rag_kernels.h"), os.path.join(CSRC, "ha_rag_internal.h"),
            os.path.join(os.path.dirname(HERE), "include", "ha_rag.h")]
 
 # Packed fp32 instructions are switched off for every device compilation.  Inputs are finite
 # by contract, so min/max need not quiet signalling NaNs first (-fno-honor-nans); nothing else
 # of fast-math is enabled: divisions, fmas and conversions keep their IEEE results.
-HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
+               "-ffp-contract=off",
                "-fno-fast-math", "-fno-honor-nans", "-Xclang", "-target-feature", "-Xclang",
                "-packed-fp32-ops",
                "-Wall", "-Wno-unused-command-line-argument"]

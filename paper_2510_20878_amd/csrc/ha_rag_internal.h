@@ -1,0 +1,201 @@
+// Shared by the host sources behind include/ha_rag.h: the context, the pool bookkeeping
+// structures and the helpers that more than one of those sources use.  Not installed, not
+// part of the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <list>
+#include <mutex>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/ha_rag.h"
+#include "ha_rag_kernels.h"
+
+namespace ha_rag_host {
+
+using namespace ha_rag;
+
+constexpr uint64_t kPPM = 1000000ull;
+constexpr uint32_t kNoRank = UINT32_MAX;
+constexpr uint32_t kTiers = 4;        // HBM, pinned, pageable, disk
+constexpr uint32_t kCacheTiers = 3;   // tiers with a capacity and an LRU order
+constexpr size_t kDirectAlign = 4096; // offset / size / buffer alignment of O_DIRECT I/O
+
+inline bool valid_group(uint32_t g)
+{
+    return g == 32 || g == 64 || g == 128 || g == 256 || g == 512;
+}
+
+inline uint32_t bits_of(uint32_t prec)  // storage bits per element
+{
+    return prec == HA_RAG_PREC_16 ? 16u : prec == HA_RAG_PREC_INT4 ? 4u : 8u;
+}
+
+inline bool has_meta(uint32_t prec) { return prec == HA_RAG_PREC_INT8 || prec == HA_RAG_PREC_INT4; }
+
+inline uint32_t log2u(uint32_t v)
+{
+    uint32_t s = 0;
+    while ((1u << s) < v) ++s;
+    return s;
+}
+
+struct Chunk {
+    uint64_t id = 0;
+    uint32_t prec = 0, n_tokens = 0;
+    uint32_t part = kPartKV;  // keys and values, or one of the two
+    uint64_t bytes = 0;
+    int32_t slot[kTiers] = {-1, -1, -1, -1};
+    uint64_t count = 0;
+    uint32_t rank = kNoRank;
+    uint64_t last_use[kCacheTiers] = {0, 0, 0};  // sequence number of the last access per tier
+    uint64_t made_by[kCacheTiers] = {0, 0, 0};   // load call that created this tier's copy (0: none)
+    std::list<uint32_t>::iterator lru_it[kCacheTiers];
+
+    int fastest() const
+    {
+        for (uint32_t t = 0; t < kTiers; ++t)
+            if (slot[t] >= 0) return (int)t;
+        return -1;
+    }
+    bool has_slower_copy(uint32_t tier) const
+    {
+        for (uint32_t t = tier + 1; t < kTiers; ++t)
+            if (slot[t] >= 0) return true;
+        return false;
+    }
+};
+
+// Who touched a slot last.  HBM slots: the streams that wrote / read it, so that a
+// different stream can be made to wait.  Pinned slots: the stream that wrote it (a
+// device -> host copy) and the events of host -> device copies that read it, which the
+// host waits for before it overwrites the slot.
+struct SlotUse {
+    hipStream_t writer = nullptr;
+    bool has_writer = false;
+    std::vector<hipStream_t> readers;
+    std::vector<hipEvent_t> read_events;
+};
+
+struct Slab {
+    uint8_t *base = nullptr;  // memory tiers
+    int fd = -1;              // disk tier
+    size_t slot_bytes = 0;
+    uint32_t n_slots = 0;
+    bool reg = false;
+    std::vector<uint32_t> free_slots;  // stack
+    std::vector<SlotUse> use;
+    std::list<uint32_t> lru;           // chunk indices resident here, least recent first
+    bool registered() const { return reg; }
+    uint8_t *ptr(int32_t s) const { return base + (size_t)s * slot_bytes; }
+    off_t offset(int32_t s) const { return (off_t)((size_t)s * slot_bytes); }
+};
+
+struct StagingSlot {
+    hipEvent_t filled = nullptr, consumed = nullptr;
+    bool consumed_valid = false;
+};
+
+struct BounceSlot {
+    hipEvent_t h2d_done = nullptr;
+    bool busy = false;
+};
+
+}  // namespace ha_rag_host
+
+struct ha_rag_ctx {
+    ha_rag_config cfg{};
+    uint32_t n_tiles = 0;
+    std::mutex mu;
+    std::string err;  // last failing HIP or I/O call
+
+    std::vector<ha_rag_host::Chunk> chunks;
+    std::unordered_map<uint64_t, uint32_t> index;
+    ha_rag_host::Slab slab[ha_rag_host::kTiers][HA_RAG_N_PREC];
+
+    uint32_t bound[3] = {0, 0, 0};  // ranks below bound[t] belong to the list of tier <= t
+    uint64_t n_loads = 0, use_seq = 0, call_seq = 0;
+
+    uint8_t *staging = nullptr;
+    size_t staging_slot_bytes = 0;
+    std::vector<ha_rag_host::StagingSlot> stg;
+    uint64_t stg_next = 0;
+
+    uint8_t *bounce = nullptr;  // pinned buffers that pageable / disk chunks pass through
+    size_t bounce_slot_bytes = 0;
+    uint8_t *dio = nullptr;     // page-aligned ordinary memory for O_DIRECT transfers: the
+                                // kernel cannot do direct I/O on GPU-pinned host memory
+    size_t dio_bytes = 0;
+    std::vector<ha_rag_host::BounceSlot> bnc;
+    uint64_t bnc_next = 0;
+
+    std::vector<hipStream_t> copy_streams;
+    uint64_t copy_rr = 0;
+    std::unordered_map<hipStream_t, hipEvent_t> stream_done;
+
+    ha_rag::K1Launch launch{64, 1, 2, true, true};
+
+    uint32_t group_of(uint32_t prec) const
+    {
+        return prec == HA_RAG_PREC_INT8 ? cfg.group_int8 : prec == HA_RAG_PREC_INT4 ? cfg.group_int4 : 0;
+    }
+    bool dry() const { return cfg.dry_run != 0; }
+    bool direct() const { return cfg.disk_o_direct != 0; }
+    size_t io_bytes(uint64_t bytes) const  // what a file transfer of `bytes` moves
+    {
+        return direct() ? (size_t)((bytes + ha_rag_host::kDirectAlign - 1) / ha_rag_host::kDirectAlign * ha_rag_host::kDirectAlign) : (size_t)bytes;
+    }
+    // Algorithm 2 step 1: which list a rank belongs to
+    uint32_t list_of(uint32_t rank) const
+    {
+        return rank < bound[0] ? HA_RAG_TIER_HBM
+               : rank < bound[1] ? HA_RAG_TIER_PINNED
+               : rank < bound[2] ? HA_RAG_TIER_PAGEABLE
+                                 : HA_RAG_TIER_DISK;
+    }
+};
+
+#define HIPCHK(ctx, call)                                                      \
+    do {                                                                       \
+        hipError_t e_ = (call);                                                \
+        if (e_ != hipSuccess) {                                                \
+            (ctx)->err = std::string(#call) + ": " + hipGetErrorString(e_);    \
+            return HA_RAG_EHIP;                                                \
+        }                                                                      \
+    } while (0)
+
+namespace ha_rag_host {
+
+// why the last ha_rag_create on this thread failed
+extern thread_local std::string g_create_err;
+
+// ---- sizes (ha_rag_pool.hip) ----
+int chunk_bytes_impl(uint32_t L, uint32_t H, uint32_t D, uint32_t prec, uint32_t group, uint32_t T,
+                     size_t *payload, size_t *meta, size_t *total, uint32_t part = kPartKV);
+
+// ---- files (ha_rag_io.hip) ----
+int io_error(ha_rag_ctx *c, const char *what);
+int read_full(ha_rag_ctx *c, int fd, uint8_t *dst, size_t n, off_t off);
+int write_full(ha_rag_ctx *c, int fd, const uint8_t *src, size_t n, off_t off);
+int read_direct(ha_rag_ctx *c, int fd, uint8_t *dst, size_t bytes, off_t off);
+
+// ---- streams, slots, tiers, ranks (ha_rag_pool.hip) ----
+int stream_event(ha_rag_ctx *c, hipStream_t s, hipEvent_t *out);
+int mark_stream(ha_rag_ctx *c, hipStream_t s);
+int wait_for(ha_rag_ctx *c, hipStream_t s, hipStream_t other);
+int before_read(ha_rag_ctx *c, SlotUse &u, hipStream_t s);
+int before_write(ha_rag_ctx *c, SlotUse &u, hipStream_t s);
+int before_host_write(ha_rag_ctx *c, SlotUse &u);
+Chunk *find_chunk(ha_rag_ctx *c, uint64_t id, uint32_t *idx = nullptr);
+void tier_touch(ha_rag_ctx *c, uint32_t tier, uint32_t ci);
+void tier_attach(ha_rag_ctx *c, uint32_t tier, uint32_t ci, int32_t slot);
+void tier_detach(ha_rag_ctx *c, uint32_t tier, uint32_t ci);
+int32_t tier_acquire(ha_rag_ctx *c, uint32_t tier, uint32_t prec, uint64_t *evicted,
+                     uint64_t keep_call = 0);
+void rerank_locked(ha_rag_ctx *c);
+int acquire_bounce(ha_rag_ctx *c, size_t *idx);
+
+}  // namespace ha_rag_host

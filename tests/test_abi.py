@@ -24,6 +24,20 @@ def test_every_declared_symbol_is_exported():
     assert sorted(B.SYMBOLS) == names
 
 
+def test_nothing_else_is_exported():
+    """The dynamic symbol table holds the declared functions and no internal helper."""
+    import shutil
+    import subprocess
+    nm = shutil.which("nm")
+    if nm is None:
+        import pytest
+        pytest.skip("nm not available")
+    out = subprocess.run([nm, "-D", "--defined-only", B.lib_path()], check=True, capture_output=True,
+                         text=True).stdout
+    funcs = sorted(l.split()[-1] for l in out.splitlines() if " T " in l)
+    assert funcs == _declared()
+
+
 def test_strerror_and_version():
     assert B.version().startswith("ha_rag")
     assert B.strerror(B.OK) == "ok"

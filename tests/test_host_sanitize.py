@@ -20,7 +20,9 @@ def test_host_runtime_fuzz_under_asan_ubsan(tmp_path):
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wno-unused-command-line-argument",
            os.path.join(ROOT, "tests", "host_sanitize", "fuzz_host.cpp"),
-           os.path.join(csrc, "ha_rag_host.hip"), os.path.join(csrc, "ha_rag_kernels.hip"),
+           os.path.join(csrc, "ha_rag_api.hip"), os.path.join(csrc, "ha_rag_pool.hip"),
+           os.path.join(csrc, "ha_rag_load.hip"), os.path.join(csrc, "ha_rag_io.hip"),
+           os.path.join(csrc, "ha_rag_kernels.hip"),
            "-o", exe]
     r = subprocess.run(cmd, capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-3000:]
