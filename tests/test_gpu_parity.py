@@ -396,8 +396,9 @@ def test_all_six_tags_in_one_request_through_the_pool():
 
 
 # ---- pools, cold path, promotion -------------------------------------------------
-def _pool_ctx(L, H, D, T, g, hbm_slots, pin_slots, stg_slots, tau_gpu_ppm, precs):
-    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=tau_gpu_ppm)
+def _pool_ctx(L, H, D, T, g, hbm_slots, pin_slots, stg_slots, tau_gpu_ppm, precs, pinned_dma=False):
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=tau_gpu_ppm,
+                    pinned_dma=pinned_dma)
     keep = []
     biggest = 0
     for p in precs:
@@ -787,13 +788,15 @@ def test_llama3_70b_request_sampled_tiles_match_oracle():
     ctx.destroy()
 
 
-def test_cold_stress_shape_through_the_pool():
+@pytest.mark.parametrize("pinned_dma", [False, True])
+def test_cold_stress_shape_through_the_pool(pinned_dma):
     """The cold-path stress shape: 8B KV, 1024-token int4 chunks with group 64, every chunk in
-    pinned memory, two requests on two streams through a 3-slot staging ring."""
+    pinned memory, two requests on two streams; read by the kernel straight from pinned memory
+    (the default) or copied through a 3-slot staging ring (pinned_dma)."""
     L, H, D, T, g = 32, 8, 128, 1024, 64
     n = 6
     ctx = _pool_ctx(L, H, D, T, g, hbm_slots=0, pin_slots=n, stg_slots=3, tau_gpu_ppm=0,
-                    precs=[B.PREC_INT4])
+                    precs=[B.PREC_INT4], pinned_dma=pinned_dma)
     srcs, packs = [], []
     for i in range(n):
         s_ = wl.kv_chunk_device(L, H, D, T, 700 + i)
@@ -809,6 +812,7 @@ def test_cold_stress_shape_through_the_pool():
     for r in range(2):
         st, _ = ctx.load_chunks(orders[r], outs[r], 3 * T, stream=streams[r])
         assert st["n_pinned_hits"] == 3 and st["bytes_h2d"] == 3 * ctx.chunk_bytes(B.PREC_INT4, T)
+        assert st["n_kernel_launches"] == (3 if pinned_dma else 1)
     torch.cuda.synchronize()
     for r in range(2):
         _check_sampled_tiles(ctx, (L, H, D), T, g, [B.PREC_INT4] * n, orders[r], srcs, packs,
@@ -816,14 +820,15 @@ def test_cold_stress_shape_through_the_pool():
     ctx.destroy()
 
 
-def test_mixed_tier_batch_at_the_8b_shape_sampled_tiles_match_oracle():
+@pytest.mark.parametrize("pinned_dma", [False, True])
+def test_mixed_tier_batch_at_the_8b_shape_sampled_tiles_match_oracle(pinned_dma):
     """The Zipf batch workload in small: 4 requests x 8 chunks of the 8B shape in one
     ha_rag_load_batch call, chunks split between the HBM pool and pinned memory, tags by
     rank class, promotion on; tiles sampled from every request are recomputed by the oracle."""
     L, H, D, T, g = 32, 8, 128, 512, 128
     n = 16
     precs = [B.PREC_16] * 3 + [B.PREC_INT8] * 5 + [B.PREC_INT4] * 8
-    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=500_000)
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=500_000, pinned_dma=pinned_dma)
     keep = []
     for p in (B.PREC_16, B.PREC_INT8, B.PREC_INT4):
         slot = (ctx.chunk_bytes(p, T) + 255) // 256 * 256
