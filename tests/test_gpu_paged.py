@@ -124,29 +124,37 @@ def test_page_ids_outside_the_pool_are_dropped_and_counted():
     ctx.destroy()
 
 
-def test_pool_load_into_a_paged_cache():
-    """ha_rag_load_chunks_paged: hot and cold chunks, promotion, then the same request again."""
+@pytest.mark.parametrize("pinned_dma", [False, True])
+def test_pool_load_into_a_paged_cache(pinned_dma):
+    """ha_rag_load_chunks_paged: hot and cold chunks of three tags (pinned chunks read in place or
+    through staging), promotion, then the same request again."""
     L, H, D, T, g, P = 2, 2, 64, 64, 64, 16
-    n = 8
-    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=500_000)
-    slot = (ctx.chunk_bytes(B.PREC_INT4, T) + 255) // 256 * 256
-    ctx.register_slab(B.TIER_HBM, B.PREC_INT4, torch.zeros(slot * 3, dtype=torch.uint8, device="cuda"))
-    ctx.register_slab(B.TIER_PINNED, B.PREC_INT4, torch.zeros(slot * n, dtype=torch.uint8).pin_memory())
-    ctx.register_staging(torch.zeros(slot * 2, dtype=torch.uint8, device="cuda"))
+    n = 9
+    precs_all = [B.PREC_INT4, B.PREC_INT8, B.PREC_FP8_E4M3]
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=500_000, pinned_dma=pinned_dma)
+    big = 0
+    for p in precs_all:
+        slot = (ctx.chunk_bytes(p, T) + 255) // 256 * 256
+        big = max(big, slot)
+        ctx.register_slab(B.TIER_HBM, p, torch.zeros(slot * 2, dtype=torch.uint8, device="cuda"))
+        ctx.register_slab(B.TIER_PINNED, p, torch.zeros(slot * n, dtype=torch.uint8).pin_memory())
+    ctx.register_staging(torch.zeros(big * 2, dtype=torch.uint8, device="cuda"))
     tokens = [T - 7 * (i % 3) for i in range(n)]
-    packed = [codec.quantize_pack_chunk(wl.kv_chunk(L, H, D, tokens[i], 60 + i), 4, g)[0] for i in range(n)]
+    precs = [precs_all[i % 3] for i in range(n)]
+    packed = [codec.quantize_pack_chunk(wl.kv_chunk(L, H, D, tokens[i], 60 + i), ORC[precs[i]], g)[0]
+              for i in range(n)]
     for i in range(n):
-        ctx.pool_insert(i, B.PREC_INT4, tokens[i], torch.from_numpy(packed[i]).pin_memory(), B.TIER_PINNED)
+        ctx.pool_insert(i, precs[i], tokens[i], torch.from_numpy(packed[i]).pin_memory(), B.TIER_PINNED)
     ctx.set_counts(list(range(n)), [100 - i for i in range(n)])
-    ctx.rerank()
-    req = [5, 0, 2, 7, 1]
+    ctx.rerank()                                     # GPU_LIST = ids 0..3
+    req = [5, 0, 2, 7, 1, 8]
     total = sum(tokens[c] for c in req)
     need = -(-total // P)
     n_pages = need + 2
     table = np.random.default_rng(0).permutation(n_pages)[:need].astype(np.uint32)
     ref = np.full(L * 2 * H * n_pages * P * D, CANARY, np.uint16)
-    codec.load_chunks_paged(packed, (L, H, D), tokens, [4] * n, [g] * n, req, ref, "tile_major", P,
-                            table.tolist())
+    codec.load_chunks_paged(packed, (L, H, D), tokens, [ORC[p] for p in precs], [g] * n, req, ref,
+                            "tile_major", P, table.tolist())
     tab = torch.from_numpy(table.view(np.int32)).cuda()
     for rnd in range(2):
         pool = torch.full((ref.size,), CANARY, dtype=torch.int16, device="cuda")
@@ -155,10 +163,10 @@ def test_pool_load_into_a_paged_cache():
         torch.cuda.synchronize()
         assert np.array_equal(host_u16(pool), ref), rnd
         if rnd == 0:
-            assert st["n_pinned_hits"] == 5 and [t.promoted for t in tr] == [0, 1, 1, 0, 1]
+            assert st["n_pinned_hits"] == 6 and [t.promoted for t in tr] == [0, 1, 1, 0, 1, 0]
         else:
             assert [t.found_tier for t in tr] == [B.TIER_PINNED, B.TIER_HBM, B.TIER_HBM, B.TIER_PINNED,
-                                                  B.TIER_HBM]
+                                                  B.TIER_HBM, B.TIER_PINNED]
     ctx.destroy()
 
 
