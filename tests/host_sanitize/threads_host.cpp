@@ -1,0 +1,113 @@
+// Several threads call into one dry_run context at once (host bookkeeping only: no HIP call,
+// no byte moved).  Meant to be built with -fsanitize=thread on the host side: the library
+// promises that calls on one context are serialised by its own mutex, so the sanitizer must
+// stay silent, and the pool must be consistent afterwards.
+#include <atomic>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+#include "../../include/ha_rag.h"
+
+#define REQUIRE(cond)                                                          \
+    do {                                                                       \
+        if (!(cond)) {                                                         \
+            std::fprintf(stderr, "threads_host: %s failed at line %d\n", #cond, __LINE__); \
+            std::exit(1);                                                      \
+        }                                                                      \
+    } while (0)
+
+static uint64_t next(uint64_t &s)
+{
+    s ^= s << 13;
+    s ^= s >> 7;
+    s ^= s << 17;
+    return s;
+}
+
+int main(int argc, char **argv)
+{
+    const int ops = argc > 1 ? std::atoi(argv[1]) : 3000;
+    ha_rag_config cfg;
+    std::memset(&cfg, 0, sizeof cfg);
+    cfg.n_layers = 2;
+    cfg.n_kv_heads = 2;
+    cfg.head_dim = 64;
+    cfg.max_chunk_tokens = 64;
+    cfg.group_int8 = 64;
+    cfg.group_int4 = 64;
+    cfg.tau_gpu_ppm = 300000;
+    cfg.tau_pin_ppm = 300000;
+    cfg.rerank_interval = 5;
+    cfg.dry_run = 1;
+    ha_rag_ctx *ctx = nullptr;
+    REQUIRE(ha_rag_create(&cfg, &ctx) == HA_RAG_OK);
+    size_t total = 0;
+    REQUIRE(ha_rag_chunk_bytes(2, 2, 64, HA_RAG_PREC_INT4, 64, 64, nullptr, nullptr, &total) == HA_RAG_OK);
+    const size_t slot = (total + 4095) & ~(size_t)4095;   // file slots
+    const size_t mslot = (total + 255) & ~(size_t)255;     // memory slots
+    REQUIRE(ha_rag_register_slab(ctx, HA_RAG_TIER_HBM, HA_RAG_PREC_INT4, (void *)0x100000000000ull, mslot * 6) == HA_RAG_OK);
+    REQUIRE(ha_rag_register_slab(ctx, HA_RAG_TIER_PINNED, HA_RAG_PREC_INT4, (void *)0x200000000000ull, mslot * 12) == HA_RAG_OK);
+    REQUIRE(ha_rag_register_disk(ctx, HA_RAG_PREC_INT4, "/nonexistent/dry-run", slot * 256) == HA_RAG_OK);
+    REQUIRE(ha_rag_register_staging(ctx, (void *)0x300000000000ull, slot * 4) == HA_RAG_OK);
+    REQUIRE(ha_rag_register_bounce(ctx, (void *)0x400000000000ull, slot * 2) == HA_RAG_OK);
+    for (uint64_t id = 0; id < 32; ++id)
+        REQUIRE(ha_rag_pool_insert(ctx, id, HA_RAG_PREC_INT4, 48, nullptr, 0, HA_RAG_TIER_DISK, nullptr) == HA_RAG_OK);
+
+    std::atomic<uint64_t> loads{0}, chunks{0};
+    auto worker = [&](int t) {
+        uint64_t s = 0x9E3779B97F4A7C15ull * (uint64_t)(t + 1);
+        for (int op = 0; op < ops; ++op) {
+            const uint64_t what = next(s) % 100;
+            if (what < 60) {
+                uint64_t ids[6];
+                const uint32_t n = 1 + (uint32_t)(next(s) % 6);
+                for (uint32_t i = 0; i < n; ++i) ids[i] = next(s) % 32;
+                ha_rag_load_stats st;
+                int rc = ha_rag_load_chunks(ctx, ids, nullptr, n, (void *)(0x500000000000ull + (uint64_t)t * 0x10000000ull),
+                                            6 * 64, 0, nullptr, &st, nullptr);
+                REQUIRE(rc == HA_RAG_OK);
+                REQUIRE(st.n_chunks == n);
+                loads.fetch_add(1);
+                chunks.fetch_add(n);
+            } else if (what < 70) {
+                const uint64_t id = 100 + (uint64_t)t * 1000 + next(s) % 40;   // ids of this thread only
+                int rc = ha_rag_pool_insert(ctx, id, HA_RAG_PREC_INT4, 1 + (uint32_t)(next(s) % 64), nullptr, 0,
+                                            HA_RAG_TIER_DISK, nullptr);
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_EINVAL || rc == HA_RAG_ENOSPC || rc == HA_RAG_EFORMAT);
+            } else if (what < 78) {
+                int rc = ha_rag_pool_evict(ctx, next(s) % 32, (uint32_t)(next(s) % 2));
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOENT || rc == HA_RAG_EINVAL);
+            } else if (what < 84) {
+                REQUIRE(ha_rag_rerank(ctx) == HA_RAG_OK);
+            } else if (what < 92) {
+                ha_rag_chunk_info info;
+                REQUIRE(ha_rag_pool_query(ctx, next(s) % 32, &info) == HA_RAG_OK);
+                REQUIRE(info.on_disk == 1);
+            } else {
+                uint64_t lru[64];
+                size_t n = 0;
+                REQUIRE(ha_rag_pool_lru(ctx, (uint32_t)(next(s) % 2), lru, 64, &n) == HA_RAG_OK);
+                REQUIRE(n <= 12);
+            }
+        }
+    };
+    std::vector<std::thread> th;
+    for (int t = 0; t < 4; ++t) th.emplace_back(worker, t);
+    for (auto &x : th) x.join();
+
+    // every access was counted exactly once
+    uint64_t counted = 0;
+    for (uint64_t id = 0; id < 32; ++id) {
+        ha_rag_chunk_info info;
+        REQUIRE(ha_rag_pool_query(ctx, id, &info) == HA_RAG_OK);
+        counted += info.count;
+    }
+    REQUIRE(counted == chunks.load());
+    REQUIRE(ha_rag_destroy(ctx) == HA_RAG_OK);
+    std::printf("threads_host ok: %llu loads, %llu chunks\n", (unsigned long long)loads.load(),
+                (unsigned long long)chunks.load());
+    return 0;
+}

@@ -30,3 +30,26 @@ def test_host_runtime_fuzz_under_asan_ubsan(tmp_path):
     r = subprocess.run([exe, "150"], capture_output=True, text=True, env=env, timeout=300)
     assert r.returncode == 0, (r.stdout + r.stderr)[-4000:]
     assert "fuzz_host ok" in r.stdout
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"),
+                    reason="needs hipcc")
+def test_host_runtime_from_four_threads_under_tsan(tmp_path):
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    exe = str(tmp_path / "threads_host")
+    csrc = os.path.join(ROOT, "paper_2510_20878_amd", "csrc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17",
+           "-Xarch_host", "-fsanitize=thread", "-Xarch_host", "-fno-omit-frame-pointer",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Wno-unused-command-line-argument",
+           os.path.join(ROOT, "tests", "host_sanitize", "threads_host.cpp"),
+           os.path.join(csrc, "ha_rag_api.hip"), os.path.join(csrc, "ha_rag_pool.hip"),
+           os.path.join(csrc, "ha_rag_load.hip"), os.path.join(csrc, "ha_rag_io.hip"),
+           os.path.join(csrc, "ha_rag_kernels.hip"),
+           "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-3000:]
+    env = dict(os.environ, TSAN_OPTIONS="halt_on_error=1:exitcode=66")
+    r = subprocess.run([exe, "2000"], capture_output=True, text=True, env=env, timeout=300)
+    assert r.returncode == 0, (r.stdout + r.stderr)[-4000:]
+    assert "threads_host ok" in r.stdout
