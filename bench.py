@@ -12,8 +12,12 @@ Prints ONE JSON line: the metric (GB/s of packed bytes read + BF16 bytes written
 KV tokens/s, the roofline object for the gather-dequantize-scatter kernel, and
 the CPU oracle timed on this machine's host cores as a baseline.
 
-Other workloads (`--workload cold8b`, `llama70b`, `zipf`, `tiers`, `units8b`) report the same fields
-for the pinned-host path, the 70B shape and the mixed-tier Zipf batch.
+The default line also carries `cold_path`: the same build serving chunks from pinned host
+memory (both ways: the kernel reading pinned memory itself, and DMA through staging) against
+the PCIe peak.  Other workloads (`--workload cold8b`, `llama70b`, `zipf`, `tiers`, `units8b`;
+`--paged P`, `--mix`) report the same fields for the pinned-host path, the 70B shape, the
+mixed-tier Zipf batch, all four tiers on files, separate key / value units, a paged cache and
+other tag mixes.
 """
 import argparse
 import json
