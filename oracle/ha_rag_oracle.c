@@ -268,7 +268,10 @@ uint8_t orc_gse8_encode(uint16_t w, int e_lo, int e_hi)
     if ((w & 0x7FFF) == 0) return sign;
     int E = bf16_exponent(w);
     int k = 0;
-    while (orc_gse_shared_exponent(k, e_lo, e_hi) < E) ++k; /* smallest shared exponent >= E */
+    /* smallest shared exponent >= E; the index has 4 bits (Sec. 2.2.2), and a value whose
+       exponent lies above e_hi is outside the contract (the range comes from the values
+       themselves): it stops at the last index instead of searching for ever */
+    while (k < 15 && orc_gse_shared_exponent(k, e_lo, e_hi) < E) ++k;
     int G = orc_gse_shared_exponent(k, e_lo, e_hi);
     double a = fabs((double)orc_bf16_to_f32(w));
     int field = (int)floor(ldexp(a, 2 - G));      /* at most 7 because E <= G */
