@@ -260,7 +260,8 @@ const char *ha_rag_last_hip_error(ha_rag_ctx *ctx);
 typedef struct ha_rag_launch_params {
     uint32_t threads;   /* per workgroup: 64..1024, multiple of 64 (one item per wave)  */
     uint32_t planes16;  /* planes per item for 16-bit chunks: 1, 2 or 4                  */
-    uint32_t planes8;   /* planes per item for int8 chunks: 2 or 4 (int4: always 4)      */
+    uint32_t planes8;   /* planes per item for the 8-bit tags (INT8, FP8, GSE8): 2 or 4;
+                           INT4, and any chunk read from host memory: always 4          */
     uint32_t nt_store;  /* 1 = nontemporal (streaming) stores to the cache              */
     uint32_t nt_load;   /* 1 = nontemporal loads of the packed payload                  */
 } ha_rag_launch_params;
