@@ -107,8 +107,10 @@ typedef struct ha_rag_config {
     uint32_t n_kv_heads;       /* H                                                        */
     uint32_t head_dim;         /* D, multiple of 8                                         */
     uint32_t max_chunk_tokens; /* slot size of every slab is that of a chunk this long     */
-    uint32_t group_int8;       /* group size of the INT8 tag: 32..512, power of 2, | D     */
-    uint32_t group_int4;       /* group size of the INT4 tag                               */
+    uint32_t group_int8;       /* group size of the INT8 tag: 32..512, power of 2, | D; 0 = the
+                                  tag is not used by this context (EFORMAT wherever it is
+                                  named), e.g. when no group size divides head_dim        */
+    uint32_t group_int4;       /* the same for the INT4 tag                                */
     uint32_t tau_gpu_ppm;      /* Algorithm 2 step 1: GPU_LIST = ranks below
                                   idx1 = floor(tau_gpu_ppm * N / 1e6), N = chunks in the pool */
     uint32_t rerank_interval;  /* recompute ranks after this many load calls; 0 = only in

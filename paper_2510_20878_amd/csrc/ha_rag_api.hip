@@ -72,8 +72,10 @@ int ha_rag_create(const ha_rag_config *cfg, ha_rag_ctx **out)
     *out = nullptr;
     if (cfg->n_layers == 0 || cfg->n_kv_heads == 0 || cfg->max_chunk_tokens == 0) return HA_RAG_EINVAL;
     if (cfg->head_dim == 0 || (cfg->head_dim % 8u)) return HA_RAG_EFORMAT;
-    if (!valid_group(cfg->group_int8) || !valid_group(cfg->group_int4)) return HA_RAG_EFORMAT;
-    if ((cfg->head_dim % cfg->group_int8) || (cfg->head_dim % cfg->group_int4)) return HA_RAG_EFORMAT;
+    // group 0 = the context does not use that integer tag (a head_dim that no group size divides
+    // can still hold 16-bit, FP8 and GSE-8 chunks)
+    for (uint32_t grp : {cfg->group_int8, cfg->group_int4})
+        if (grp != 0 && (!valid_group(grp) || (cfg->head_dim % grp))) return HA_RAG_EFORMAT;
     if (cfg->tau_gpu_ppm > kPPM || cfg->tau_pin_ppm > kPPM || cfg->tau_page_ppm > kPPM ||
         cfg->n_copy_streams > 8)
         return HA_RAG_EINVAL;

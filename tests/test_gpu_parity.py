@@ -958,3 +958,37 @@ def test_knowledge_base_files_survive_the_context(tmp_path):
             if rnd == 0:
                 assert st["n_disk_hits"] == 5
         b.destroy()
+
+
+@pytest.mark.parametrize("D", [8, 24, 40])
+def test_smallest_head_dims_without_groups(D):
+    """head_dim only has to be a multiple of 8 for the tags that carry no per-group meta
+    (16-bit, FP8, GSE-8); a context for such a shape names no integer group (0), and the
+    integer tags are refused there."""
+    L, H, g = 2, 3, 32
+    tokens = [1, 300, 7]
+    precs = [B.PREC_16, B.PREC_FP8_E4M3, B.PREC_GSE8]
+    with pytest.raises(B.HaRagError) as e:
+        B.Context(L, H, D, max(tokens), group_int8=32, group_int4=32)
+    assert e.value.code == B.EFORMAT
+    ctx = B.Context(L, H, D, max(tokens), group_int8=0, group_int4=0)
+    with pytest.raises(B.HaRagError) as e:
+        ctx.chunk_bytes(B.PREC_INT4, 7)
+    assert e.value.code == B.EFORMAT
+    srcs = [wl.kv_chunk(L, H, D, t, 3100 + i) for i, t in enumerate(tokens)]
+    packed_ref = [codec.quantize_pack_chunk(s_, ORC[p], g)[0] for s_, p in zip(srcs, precs)]
+    dev = []
+    for s_, p, ref in zip(srcs, precs, packed_ref):
+        got, _ = gpu_quantize(ctx, s_, p, g)
+        assert np.array_equal(got, ref)
+        dev.append(dev_u8(got))
+    order = [1, 0, 2, 1]
+    cap = sum(tokens[c] for c in order) + 2
+    ref = np.full((L, 2, H, cap, D), CANARY, np.uint16)
+    codec.load_chunks(packed_ref, (L, H, D), tokens, [ORC[p] for p in precs], [g] * 3, order,
+                      cap_tokens=cap, tok_base=1, out=ref)
+    out = torch.full((L, 2, H, cap, D), CANARY, dtype=torch.int16, device="cuda")
+    ctx.load_packed([(dev[c], tokens[c], precs[c], g) for c in order], out, cap, 1)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u16(out), ref)
+    ctx.destroy()

@@ -705,3 +705,29 @@ def test_index_with_key_and_value_units(tmp_path):
     st, tr = b.load_chunks([20, 10], FAKE_HBM, 90, want_trace=True)
     assert [t.tok_off for t in tr] == [0, 0]
     b.destroy()
+
+
+def test_context_without_integer_tags_for_head_dims_no_group_divides():
+    for D in (8, 24, 80):
+        with pytest.raises(B.HaRagError) as e:
+            B.Context(2, 2, D, 64, group_int8=32, group_int4=64, dry_run=True)
+        assert e.value.code == B.EFORMAT
+        ctx = B.Context(2, 2, D, 64, group_int8=0, group_int4=0, dry_run=True)
+        for prec, bits in ((B.PREC_16, 16), (B.PREC_FP8_E5M2, 52), (B.PREC_GSE8, 143)):
+            assert ctx.chunk_bytes(prec, 37) == codec.chunk_bytes(2, 2, D, 37, bits, 32)
+            slot = (ctx.chunk_bytes(prec, 64) + 255) // 256 * 256
+            ctx.register_slab(B.TIER_PINNED, prec, FAKE_PIN + prec * (1 << 32), slot * 2)
+            ctx.pool_insert(prec, prec, 37, None, B.TIER_PINNED)
+        for prec in (B.PREC_INT8, B.PREC_INT4):
+            with pytest.raises(B.HaRagError) as e:
+                ctx.register_slab(B.TIER_PINNED, prec, FAKE_PIN + prec * (1 << 32), 1 << 20)
+            assert e.value.code == B.EFORMAT
+        st, _ = ctx.load_chunks([B.PREC_16, B.PREC_GSE8], FAKE_HBM, 100)
+        assert st["tokens"] == 74
+        ctx.destroy()
+    # one integer tag may be off while the other is on
+    ctx = B.Context(2, 2, 96, 64, group_int8=32, group_int4=0, dry_run=True)
+    assert ctx.chunk_bytes(B.PREC_INT8, 10) == codec.chunk_bytes(2, 2, 96, 10, 8, 32)
+    with pytest.raises(B.HaRagError):
+        ctx.chunk_bytes(B.PREC_INT4, 10)
+    ctx.destroy()
