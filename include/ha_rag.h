@@ -391,6 +391,13 @@ int ha_rag_pool_promote(ha_rag_ctx *ctx, uint64_t id, void *stream);
  * after the transfers and loads that read it have finished. */
 int ha_rag_pool_evict(ha_rag_ctx *ctx, uint64_t id, uint32_t tier);
 
+/* Takes chunk `id` out of the knowledge base: every copy is dropped, its slots (file slot
+ * included; the file's bytes are left as they are) become free, its count is forgotten and
+ * the id may be inserted again.  N of Algorithm 2 step 1 shrinks with the next rerank.
+ * Slots are handed on under the same stream / event rules as after an eviction.  ENOENT
+ * unknown id. */
+int ha_rag_pool_remove(ha_rag_ctx *ctx, uint64_t id);
+
 int ha_rag_pool_query(ha_rag_ctx *ctx, uint64_t id, ha_rag_chunk_info *info);
 
 /* The knowledge base is files (Sec. 2.1: the precomputed KV is stored and loaded on demand);

@@ -30,7 +30,7 @@ SYMBOLS = [
     "ha_rag_load_batch", "ha_rag_register_disk", "ha_rag_register_bounce", "ha_rag_pool_lru",
     "ha_rag_quantize_half", "ha_rag_pool_insert_half", "ha_rag_load_packed_paged",
     "ha_rag_load_chunks_paged", "ha_rag_chunk_sq_error", "ha_rag_pool_save_index",
-    "ha_rag_pool_load_index",
+    "ha_rag_pool_load_index", "ha_rag_pool_remove",
 ]
 
 
@@ -144,6 +144,7 @@ def lib():
             "ha_rag_pool_slot": (C.c_int, [vp, u64, u32, P(vp), P(sz)]),
             "ha_rag_pool_promote": (C.c_int, [vp, u64, vp]),
             "ha_rag_pool_evict": (C.c_int, [vp, u64, u32]),
+            "ha_rag_pool_remove": (C.c_int, [vp, u64]),
             "ha_rag_pool_query": (C.c_int, [vp, u64, P(ChunkInfo)]),
             "ha_rag_pool_hbm_lru": (C.c_int, [vp, P(u64), sz, P(sz)]),
             "ha_rag_touch": (C.c_int, [vp, P(u64), sz]),
@@ -373,6 +374,9 @@ class Context:
 
     def pool_evict(self, cid, tier=TIER_HBM):
         self._chk(lib().ha_rag_pool_evict(self._h, cid, tier), "ha_rag_pool_evict")
+
+    def pool_remove(self, cid):
+        self._chk(lib().ha_rag_pool_remove(self._h, cid), "ha_rag_pool_remove")
 
     def pool_query(self, cid):
         info = ChunkInfo()

@@ -112,7 +112,8 @@ struct ha_rag_ctx {
     std::mutex mu;
     std::string err;  // last failing HIP or I/O call
 
-    std::vector<ha_rag_host::Chunk> chunks;
+    std::vector<ha_rag_host::Chunk> chunks;   // entries of removed chunks keep id HA_RAG_NO_CHUNK
+    std::vector<uint32_t> dead;                // ... and wait here to be used again
     std::unordered_map<uint64_t, uint32_t> index;
     ha_rag_host::Slab slab[ha_rag_host::kTiers][HA_RAG_N_PREC];
 
@@ -196,6 +197,7 @@ void tier_detach(ha_rag_ctx *c, uint32_t tier, uint32_t ci);
 int32_t tier_acquire(ha_rag_ctx *c, uint32_t tier, uint32_t prec, uint64_t *evicted,
                      uint64_t keep_call = 0);
 void rerank_locked(ha_rag_ctx *c);
+uint32_t new_chunk_entry(ha_rag_ctx *c);  // index of a fresh entry of ctx->chunks
 int acquire_bounce(ha_rag_ctx *c, size_t *idx);
 
 }  // namespace ha_rag_host

@@ -179,11 +179,25 @@ int32_t tier_acquire(ha_rag_ctx *c, uint32_t tier, uint32_t prec, uint64_t *evic
     return s;
 }
 
+uint32_t new_chunk_entry(ha_rag_ctx *c)
+{
+    if (!c->dead.empty()) {
+        const uint32_t ci = c->dead.back();
+        c->dead.pop_back();
+        c->chunks[ci] = Chunk();
+        return ci;
+    }
+    c->chunks.emplace_back();
+    return (uint32_t)(c->chunks.size() - 1);
+}
+
 void rerank_locked(ha_rag_ctx *c)
 {
-    const size_t n = c->chunks.size();
-    std::vector<uint32_t> order(n);
-    for (size_t i = 0; i < n; ++i) order[i] = (uint32_t)i;
+    std::vector<uint32_t> order;
+    order.reserve(c->chunks.size());
+    for (size_t i = 0; i < c->chunks.size(); ++i)
+        if (c->chunks[i].id != HA_RAG_NO_CHUNK) order.push_back((uint32_t)i);
+    const size_t n = order.size();  // N of Algorithm 2 step 1: the chunks that exist
     std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
         const Chunk &x = c->chunks[a], &y = c->chunks[b];
         if (x.count != y.count) return x.count > y.count;
@@ -362,9 +376,8 @@ static int insert_impl(ha_rag_ctx *c, uint64_t id, uint32_t part, uint32_t prec,
     const int32_t slot = tier_acquire(c, tier, prec, &ev);
     if (slot < 0) return HA_RAG_ENOSPC;
     if (!ch) {
-        ci = (uint32_t)c->chunks.size();
-        c->chunks.emplace_back();
-        ch = &c->chunks.back();
+        ci = new_chunk_entry(c);
+        ch = &c->chunks[ci];
         ch->id = id;
         ch->prec = prec;
         ch->n_tokens = n_tokens;
@@ -485,6 +498,22 @@ int ha_rag_pool_evict(ha_rag_ctx *c, uint64_t id, uint32_t tier)
     if (!ch || ch->slot[tier] < 0) return HA_RAG_ENOENT;
     if (!ch->has_slower_copy(tier)) return HA_RAG_EINVAL;
     tier_detach(c, tier, ci);
+    return HA_RAG_OK;
+}
+
+int ha_rag_pool_remove(ha_rag_ctx *c, uint64_t id)
+{
+    if (!c) return HA_RAG_EINVAL;
+    std::lock_guard<std::mutex> g(c->mu);
+    uint32_t ci;
+    Chunk *ch = find_chunk(c, id, &ci);
+    if (!ch) return HA_RAG_ENOENT;
+    for (uint32_t t = 0; t < kTiers; ++t)
+        if (ch->slot[t] >= 0) tier_detach(c, t, ci);
+    c->index.erase(id);
+    *ch = Chunk();
+    ch->id = HA_RAG_NO_CHUNK;
+    c->dead.push_back(ci);
     return HA_RAG_OK;
 }
 
@@ -654,9 +683,8 @@ int ha_rag_pool_load_index(ha_rag_ctx *c, const char *path, size_t *n_loaded)
         size_t total = 0;
         (void)chunk_bytes_impl(c->cfg.n_layers, c->cfg.n_kv_heads, c->cfg.head_dim, e.prec,
                                c->group_of(e.prec), e.n_tokens, nullptr, nullptr, &total, e.part);
-        const uint32_t ci = (uint32_t)c->chunks.size();
-        c->chunks.emplace_back();
-        Chunk &ch = c->chunks.back();
+        const uint32_t ci = new_chunk_entry(c);
+        Chunk &ch = c->chunks[ci];
         ch.id = e.id;
         ch.prec = e.prec;
         ch.part = e.part;

@@ -122,7 +122,7 @@ int main(int argc, char **argv)
                 ha_rag_load_stats st;
                 int rc = ha_rag_load_chunks_paged(ctx, ids.data(), nullptr, (uint32_t)ids.size(), &pc,
                                                   rnd() % 4, nullptr, &st, nullptr);
-                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOSPC || rc == HA_RAG_EINVAL);
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOSPC || rc == HA_RAG_EINVAL || rc == HA_RAG_ENOENT);
             } else if (what < 80) {  // save the index, damage a copy of it at random, load both
                 const char *good = "/tmp/ha_rag_fuzz.idx", *bad = "/tmp/ha_rag_fuzz_bad.idx";
                 REQUIRE(ha_rag_pool_save_index(ctx, good) == HA_RAG_OK);
@@ -155,6 +155,9 @@ int main(int argc, char **argv)
             } else if (what < 88 && !known.empty()) {
                 int rc = ha_rag_pool_evict(ctx, known[rnd() % known.size()], (uint32_t)(rnd() % 3));
                 REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_EINVAL || rc == HA_RAG_ENOENT);
+            } else if (what < 90 && !known.empty()) {
+                int rc = ha_rag_pool_remove(ctx, known[rnd() % known.size()]);
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOENT);
             } else if (what < 94) {
                 REQUIRE(ha_rag_rerank(ctx) == HA_RAG_OK);
             } else if (!known.empty()) {

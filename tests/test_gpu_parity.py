@@ -992,3 +992,48 @@ def test_smallest_head_dims_without_groups(D):
     torch.cuda.synchronize()
     assert np.array_equal(host_u16(out), ref)
     ctx.destroy()
+
+
+def test_a_removed_chunk_is_gone_and_its_id_and_slots_serve_new_content():
+    L, H, D, T, g = 2, 2, 64, 128, 64
+    n = 4
+    ctx = _pool_ctx(L, H, D, T, g, hbm_slots=2, pin_slots=n, stg_slots=2, tau_gpu_ppm=500_000,
+                    precs=[B.PREC_INT4])                 # GPU_LIST holds two of the four chunks
+    tokens = [T, T - 3, T - 17, 40]
+    srcs = [wl.kv_chunk(L, H, D, tokens[i], 900 + i) for i in range(n)]
+    packed = [codec.quantize_pack_chunk(s, 4, g)[0] for s in srcs]
+    for i in range(n):
+        ctx.pool_insert(i, B.PREC_INT4, tokens[i], packed[i], B.TIER_PINNED)
+    ctx.set_counts(list(range(n)), [10, 9, 8, 7])
+    ctx.rerank()
+
+    def run(req):
+        cap = sum(tokens[c] for c in req) + 2
+        out = torch.full((L, 2, H, cap, D), CANARY, dtype=torch.int16, device="cuda")
+        st, tr = ctx.load_chunks(req, out, cap, want_trace=True)
+        torch.cuda.synchronize()
+        ref = np.full((L, 2, H, cap, D), CANARY, np.uint16)
+        codec.load_chunks(packed, (L, H, D), tokens, [4] * n, [g] * n, req, cap_tokens=cap, out=ref)
+        assert np.array_equal(host_u16(out), ref), req
+        return st, tr
+
+    st, tr = run([0, 1])                                  # both promoted: the HBM slab is full
+    assert [t.promoted for t in tr] == [1, 1]
+    ctx.pool_remove(0)
+    with pytest.raises(B.HaRagError) as e:
+        ctx.load_chunks([0], torch.zeros(1, device="cuda"), 1)
+    assert e.value.code == B.ENOENT
+    # the same id comes back with other content and length, into the freed pinned slot; the
+    # freed HBM slot takes its promotion without evicting chunk 1
+    tokens[0] = 77
+    srcs[0] = wl.kv_chunk(L, H, D, 77, 990)
+    packed[0] = codec.quantize_pack_chunk(srcs[0], 4, g)[0]
+    ctx.pool_insert(0, B.PREC_INT4, 77, packed[0], B.TIER_PINNED)
+    ctx.set_counts([0], [100])
+    ctx.rerank()
+    st, tr = run([1, 0, 2])
+    assert [t.found_tier for t in tr] == [B.TIER_HBM, B.TIER_PINNED, B.TIER_PINNED]
+    assert tr[1].promoted == 1 and tr[1].evicted_id == B.NO_CHUNK
+    st, tr = run([0, 1])
+    assert st["n_hbm_hits"] == 2
+    ctx.destroy()

@@ -731,3 +731,40 @@ def test_context_without_integer_tags_for_head_dims_no_group_divides():
     with pytest.raises(B.HaRagError):
         ctx.chunk_bytes(B.PREC_INT4, 10)
     ctx.destroy()
+
+
+def test_remove_takes_a_chunk_out_of_every_tier_and_frees_its_slots():
+    n = 6
+    ctx = _ctx4(n, (2, 2, 2), [340_000, 340_000, 0])        # lists of 2 / 2 chunks of 6
+    ctx.set_counts(list(range(n)), [100 - c for c in range(n)])
+    ctx.rerank()
+    ctx.load_chunks([0, 1, 2, 3], FAKE_HBM, 4 * 128)         # 0, 1 -> HBM; 2, 3 -> pinned
+    assert ctx.pool_hbm_lru() == [0, 1] and ctx.pool_lru(B.TIER_PINNED) == [2, 3]
+    ctx.pool_remove(0)
+    ctx.pool_remove(2)
+    for cid in (0, 2):
+        with pytest.raises(B.HaRagError) as e:
+            ctx.pool_query(cid)
+        assert e.value.code == B.ENOENT
+        with pytest.raises(B.HaRagError) as e:
+            ctx.load_chunks([cid], FAKE_HBM, 128)
+        assert e.value.code == B.ENOENT
+    with pytest.raises(B.HaRagError) as e:
+        ctx.pool_remove(0)
+    assert e.value.code == B.ENOENT
+    assert ctx.pool_hbm_lru() == [1] and ctx.pool_lru(B.TIER_PINNED) == [3]
+    # N is now 4: lists of floor(0.34 * 4) = 1 / 1 chunk; ranks close up
+    ctx.rerank()
+    assert [ctx.get_rank(c) for c in (1, 3, 4, 5)] == [0, 1, 2, 3]
+    st, tr = ctx.load_chunks([4, 5], FAKE_HBM, 256, want_trace=True)
+    assert [t.placed_tier for t in tr] == [B.TIER_NONE, B.TIER_NONE]       # ranks 2, 3: DISK_LIST
+    # the file slab was full (6 slots, 6 chunks): the freed slots take new chunks, the old id may return
+    used = {ctx.pool_query(c).disk_slot for c in (1, 3, 4, 5)}
+    ctx.pool_insert(0, B.PREC_INT4, 77, None, B.TIER_DISK)
+    ctx.pool_insert(99, B.PREC_INT4, 128, None, B.TIER_DISK)
+    assert ctx.pool_query(0).n_tokens == 77 and ctx.pool_query(0).count == 0
+    assert len(used | {ctx.pool_query(0).disk_slot, ctx.pool_query(99).disk_slot}) == 6
+    with pytest.raises(B.HaRagError) as e:
+        ctx.pool_insert(100, B.PREC_INT4, 128, None, B.TIER_DISK)
+    assert e.value.code == B.ENOSPC
+    ctx.destroy()
