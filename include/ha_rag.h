@@ -327,6 +327,55 @@ int ha_rag_load_packed(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks, uint3
 int ha_rag_load_packed_paged(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks, uint32_t n,
                              const ha_rag_paged_cache *cache, uint64_t tok_base, void *stream);
 
+/* ---- online, no cache: attention straight over packed chunks ------------------ */
+
+#define HA_RAG_MAX_ATTEND_REQUESTS 1024
+#define HA_RAG_MAX_ATTEND_Q 4096
+
+/* One request of ha_rag_attend_packed: the query vectors of its question tokens for one
+ * layer, and where the result goes.  Its chunks are the next n_chunks entries of the call's
+ * chunk list (requests take their chunks in order). */
+typedef struct ha_rag_attend_request {
+    const void *q;     /* device, BF16 [n_q][n_q_heads][D], 16-byte aligned                 */
+    float *out;        /* device, binary32 [n_q][n_q_heads][D], 16-byte aligned             */
+    float *lse;        /* device, binary32 [n_q][n_q_heads], or NULL                        */
+    uint32_t n_q;      /* query tokens, 1..HA_RAG_MAX_ATTEND_Q                              */
+    uint32_t n_chunks; /* chunks of this request                                            */
+} ha_rag_attend_request;
+
+/* The prefill of Sec. 2.1 attends from the question's tokens to the concatenated KV of the
+ * retrieved chunks.  This call computes that attention for one layer without building the
+ * BF16 cache: it reads the packed chunks (Sec. 2.2) and decodes them in registers to the
+ * very values a load would write.  For every request r, query token i and query head hq
+ * (which reads KV head hq / (n_q_heads / H)), over the tokens t of all chunks of r:
+ *     s[t]   = sm_scale * sum_d q[i][hq][d] * K[t][d]
+ *     out[i][hq][d] = sum_t softmax(s)[t] * V[t][d],   lse[i][hq] = log(sum_t exp(s[t]))
+ * Every chunk token is visible to every query token (the question follows the chunks); out
+ * and lse are what a caller needs to merge this with attention over other keys.  A request
+ * whose chunks hold no token gets out = 0 and lse = -inf.
+ * K and V values are exact; the softmax weights are rounded to BF16 before they multiply V
+ * and sums are accumulated in binary32, so out differs from the exact result by about
+ * 2^-8 * sum_t softmax(s)[t] * |V[t][d]| at most.
+ * chunks[]: host array of whole chunks (part = HA_RAG_PART_KV) in device memory, any mix of
+ * tags; reqs[n_reqs]: host array, n_reqs <= HA_RAG_MAX_ATTEND_REQUESTS, all chunks together
+ * <= HA_RAG_MAX_REQUEST_CHUNKS.  n_q_heads a multiple of H, at most 64 H.  sm_scale > 0.
+ * workspace: device memory, 16-byte aligned, of at least the size
+ * ha_rag_attend_workspace_bytes returns for the same lists (it holds partial results and
+ * may be reused by the next call on the same stream); ENOSPC if smaller.
+ * EFORMAT unless head_dim is 128, and for keys-only / values-only chunks.
+ * Like ha_rag_load_packed the call only launches kernels on `stream`: one per 64 chunks
+ * plus one per 64 requests. */
+int ha_rag_attend_packed(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks,
+                         const ha_rag_attend_request *reqs, uint32_t n_reqs, uint32_t layer,
+                         uint32_t n_q_heads, float sm_scale, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
+/* Workspace size for that call: reads only n_tokens, prec, group, part of the chunks and
+ * n_q, n_chunks of the requests. */
+int ha_rag_attend_workspace_bytes(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks,
+                                  const ha_rag_attend_request *reqs, uint32_t n_reqs,
+                                  uint32_t n_q_heads, size_t *bytes);
+
 /* ---- pools (Algorithm 2's queueGPU / queuePIN / queuePAGE and the files) ------- */
 
 /* Gives the context a slab for chunks of tag `prec` in a memory tier: `base` is a

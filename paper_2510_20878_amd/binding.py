@@ -30,7 +30,8 @@ SYMBOLS = [
     "ha_rag_load_batch", "ha_rag_register_disk", "ha_rag_register_bounce", "ha_rag_pool_lru",
     "ha_rag_quantize_half", "ha_rag_pool_insert_half", "ha_rag_load_packed_paged",
     "ha_rag_load_chunks_paged", "ha_rag_chunk_sq_error", "ha_rag_pool_save_index",
-    "ha_rag_pool_load_index", "ha_rag_pool_remove",
+    "ha_rag_pool_load_index", "ha_rag_pool_remove", "ha_rag_attend_packed",
+    "ha_rag_attend_workspace_bytes",
 ]
 
 
@@ -49,6 +50,11 @@ class LaunchParams(C.Structure):
 class PackedChunk(C.Structure):
     _fields_ = [("packed", C.c_void_p), ("n_tokens", C.c_uint32), ("prec", C.c_uint32),
                 ("group", C.c_uint32), ("part", C.c_uint32)]
+
+
+class AttendRequest(C.Structure):
+    _fields_ = [("q", C.c_void_p), ("out", C.c_void_p), ("lse", C.c_void_p), ("n_q", C.c_uint32),
+                ("n_chunks", C.c_uint32)]
 
 
 class PagedCache(C.Structure):
@@ -131,6 +137,10 @@ def lib():
             "ha_rag_load_packed": (C.c_int, [vp, P(PackedChunk), u32, vp, u64, u64, vp]),
             "ha_rag_chunk_sq_error": (C.c_int, [vp, vp, vp, u32, u32, u32, u32, vp, vp]),
             "ha_rag_load_packed_paged": (C.c_int, [vp, P(PackedChunk), u32, P(PagedCache), u64, vp]),
+            "ha_rag_attend_packed": (C.c_int, [vp, P(PackedChunk), P(AttendRequest), u32, u32, u32,
+                                               C.c_float, vp, C.c_size_t, vp]),
+            "ha_rag_attend_workspace_bytes": (C.c_int, [vp, P(PackedChunk), P(AttendRequest), u32, u32,
+                                                        P(C.c_size_t)]),
             "ha_rag_load_chunks_paged": (C.c_int, [vp, P(u64), P(C.c_uint8), u32, P(PagedCache), u64, vp,
                                                    P(LoadStats), P(ChunkTrace)]),
             "ha_rag_register_slab": (C.c_int, [vp, u32, u32, vp, sz]),
@@ -316,6 +326,37 @@ class Context:
             arr[i] = PackedChunk(_addr(p), t, prec, g, ch[4] if len(ch) > 4 else PART_KV)
         self._chk(lib().ha_rag_load_packed_paged(self._h, arr, len(chunks), C.byref(cache), tok_base,
                                                  _stream(stream)), "ha_rag_load_packed_paged")
+
+    @staticmethod
+    def _attend_lists(requests):
+        """requests: list of (chunks, q, out, lse, n_q) with chunks as in load_packed."""
+        n_chunks = sum(len(r[0]) for r in requests)
+        arr = (PackedChunk * max(n_chunks, 1))()
+        reqs = (AttendRequest * max(len(requests), 1))()
+        k = 0
+        for i, (chunks, q, out, lse, n_q) in enumerate(requests):
+            for ch in chunks:
+                p, t, prec, g = ch[:4]
+                arr[k] = PackedChunk(_addr(p), t, prec, g, ch[4] if len(ch) > 4 else PART_KV)
+                k += 1
+            reqs[i] = AttendRequest(_addr(q), _addr(out), _addr(lse), n_q, len(chunks))
+        return arr, reqs
+
+    def attend_workspace_bytes(self, requests, n_q_heads):
+        arr, reqs = self._attend_lists(requests)
+        n = C.c_size_t(0)
+        self._chk(lib().ha_rag_attend_workspace_bytes(self._h, arr, reqs, len(requests), n_q_heads,
+                                                      C.byref(n)), "ha_rag_attend_workspace_bytes")
+        return n.value
+
+    def attend_packed(self, requests, layer, n_q_heads, sm_scale, workspace, workspace_bytes=None,
+                      stream=None):
+        arr, reqs = self._attend_lists(requests)
+        if workspace_bytes is None:
+            workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+        self._chk(lib().ha_rag_attend_packed(self._h, arr, reqs, len(requests), layer, n_q_heads,
+                                             sm_scale, _addr(workspace), workspace_bytes,
+                                             _stream(stream)), "ha_rag_attend_packed")
 
     def load_chunks_paged(self, ids, cache, tok_base=0, tags=None, stream=None, want_trace=False):
         n = len(ids)

@@ -6,8 +6,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIBDIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIBDIR, "libha_rag.so")
-SOURCES = ["ha_rag_kernels.hip", "ha_rag_api.hip", "ha_rag_pool.hip", "ha_rag_load.hip", "ha_rag_io.hip"]
+SOURCES = ["ha_rag_kernels.hip", "ha_rag_attend_kernels.hip", "ha_rag_api.hip", "ha_rag_pool.hip",
+           "ha_rag_load.hip", "ha_rag_attend.hip", "ha_rag_io.hip"]
 HEADERS = [os.path.join(CSRC, "ha_rag_kernels.h"), os.path.join(CSRC, "ha_rag_internal.h"),
+           os.path.join(CSRC, "ha_rag_decode.h"),
            os.path.join(os.path.dirname(HERE), "include", "ha_rag.h")]
 
 # Packed fp32 instructions are switched off for every device compilation.  Inputs are finite

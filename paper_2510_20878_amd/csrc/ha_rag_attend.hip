@@ -1,0 +1,147 @@
+// Host side of attention over packed chunks: argument checks, the workspace layout, and the
+// launches (one partial-attention launch per 64 chunks, one merge launch per 64 requests).
+#include "ha_rag_internal.h"
+
+using namespace ha_rag_host;
+
+namespace {
+
+struct Plan {               // one request
+    uint32_t first = 0;     // its first chunk in the list
+    uint32_t n_live = 0;    // chunks with tokens
+    uint32_t n_split = 1, n_mt = 1;
+    uint64_t part_floats = 0;  // offset of its records in the workspace
+};
+
+// Checks everything and lays the workspace out.  *floats = workspace size in binary32 words.
+int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_attend_request *reqs,
+                uint32_t n_reqs, uint32_t n_q_heads, std::vector<Plan> *plans, uint64_t *floats,
+                bool need_buffers)
+{
+    if (!c || !reqs || n_reqs == 0 || n_reqs > HA_RAG_MAX_ATTEND_REQUESTS) return HA_RAG_EINVAL;
+    if (c->cfg.head_dim != kAttendHeadDim) return HA_RAG_EFORMAT;
+    const uint32_t H = c->cfg.n_kv_heads;
+    if (n_q_heads == 0 || n_q_heads % H || n_q_heads / H > 64) return HA_RAG_EINVAL;
+    const uint32_t G = n_q_heads / H;
+    uint64_t total = 0, n_chunks = 0;
+    plans->assign(n_reqs, Plan());
+    for (uint32_t r = 0; r < n_reqs; ++r) {
+        const ha_rag_attend_request &rq = reqs[r];
+        Plan &pl = (*plans)[r];
+        if (rq.n_q == 0 || rq.n_q > HA_RAG_MAX_ATTEND_Q) return HA_RAG_EINVAL;
+        if (need_buffers && (!rq.q || !rq.out || ((uintptr_t)rq.q & 15u) || ((uintptr_t)rq.out & 15u)))
+            return HA_RAG_EINVAL;
+        if (n_chunks + rq.n_chunks > HA_RAG_MAX_REQUEST_CHUNKS || (rq.n_chunks && !chunks))
+            return HA_RAG_EINVAL;
+        pl.first = (uint32_t)n_chunks;
+        pl.n_mt = (rq.n_q * G + 15u) / 16u;
+        uint32_t max_tokens = 0;
+        for (uint32_t i = 0; i < rq.n_chunks; ++i) {
+            const ha_rag_packed_chunk &pc = chunks[pl.first + i];
+            if (pc.part != HA_RAG_PART_KV) return HA_RAG_EFORMAT;
+            int rc = chunk_bytes_impl(c->cfg.n_layers, H, c->cfg.head_dim, pc.prec, pc.group,
+                                      pc.n_tokens, nullptr, nullptr, nullptr, pc.part);
+            if (rc) return rc;
+            if (pc.n_tokens == 0) continue;
+            if (need_buffers && (!pc.packed || ((uintptr_t)pc.packed & 15u))) return HA_RAG_EINVAL;
+            ++pl.n_live;
+            if (pc.n_tokens > max_tokens) max_tokens = pc.n_tokens;
+        }
+        const uint32_t nblk = (max_tokens + 15u) / 16u;
+        pl.n_split = nblk ? (nblk + kAttendSplitBlocks - 1u) / kAttendSplitBlocks : 1u;
+        pl.part_floats = total;
+        total += (uint64_t)pl.n_live * H * pl.n_split * pl.n_mt * kAttendRecFloats;
+        n_chunks += rq.n_chunks;
+    }
+    if (total * 4ull > (1ull << 40)) return HA_RAG_EINVAL;
+    *floats = total;
+    return HA_RAG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ha_rag_attend_workspace_bytes(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
+                                  const ha_rag_attend_request *reqs, uint32_t n_reqs,
+                                  uint32_t n_q_heads, size_t *bytes)
+{
+    if (!bytes) return HA_RAG_EINVAL;
+    std::vector<Plan> plans;
+    uint64_t floats = 0;
+    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, &plans, &floats, false);
+    if (rc) return rc;
+    *bytes = (size_t)(floats * 4ull);
+    return HA_RAG_OK;
+}
+
+int ha_rag_attend_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
+                         const ha_rag_attend_request *reqs, uint32_t n_reqs, uint32_t layer,
+                         uint32_t n_q_heads, float sm_scale, void *workspace, size_t workspace_bytes,
+                         void *stream)
+{
+    std::vector<Plan> plans;
+    uint64_t floats = 0;
+    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, &plans, &floats, true);
+    if (rc) return rc;
+    if (layer >= c->cfg.n_layers || !(sm_scale > 0.0f) || !(sm_scale < 1e30f)) return HA_RAG_EINVAL;
+    if (floats && (!workspace || ((uintptr_t)workspace & 15u))) return HA_RAG_EINVAL;
+    if (floats * 4ull > workspace_bytes) return HA_RAG_ENOSPC;
+    if (c->dry()) return HA_RAG_OK;
+    std::lock_guard<std::mutex> g(c->mu);
+    hipStream_t st = (hipStream_t)stream;
+    const uint32_t H = c->cfg.n_kv_heads;
+    float *ws = static_cast<float *>(workspace);
+
+    K4Params kp{};
+    kp.n_kv_heads = H;
+    kp.n_q_heads = n_q_heads;
+    kp.layer = layer;
+    kp.scale_log2 = sm_scale * 1.44269504088896341f;
+    for (uint32_t r = 0; r < n_reqs; ++r) {
+        const ha_rag_attend_request &rq = reqs[r];
+        const Plan &pl = plans[r];
+        const uint64_t per_chunk = (uint64_t)H * pl.n_split * pl.n_mt * kAttendRecFloats;
+        uint32_t live = 0;
+        for (uint32_t i = 0; i < rq.n_chunks; ++i) {
+            const ha_rag_packed_chunk &pc = chunks[pl.first + i];
+            if (pc.n_tokens == 0) continue;
+            K4Chunk &d = kp.c[kp.n_chunks++];
+            d.src = static_cast<const uint8_t *>(pc.packed);
+            d.q = static_cast<const uint16_t *>(rq.q);
+            d.part = ws + pl.part_floats + live * per_chunk;
+            d.n_tokens = pc.n_tokens;
+            d.fmt = pc.prec | ((has_meta(pc.prec) ? log2u(pc.group) : 0u) << 8);
+            d.n_q = rq.n_q;
+            d.n_split = pl.n_split;
+            ++live;
+            if (kp.n_chunks == kMaxLaunchChunks) {
+                HIPCHK(c, launch_k4(kp, st));
+                kp.n_chunks = 0;
+            }
+        }
+    }
+    if (kp.n_chunks) HIPCHK(c, launch_k4(kp, st));
+
+    K5Params mp{};
+    mp.n_kv_heads = H;
+    mp.n_q_heads = n_q_heads;
+    for (uint32_t r = 0; r < n_reqs; ++r) {
+        K5Req &d = mp.r[mp.n_reqs++];
+        d.part = ws + plans[r].part_floats;
+        d.out = reqs[r].out;
+        d.lse = reqs[r].lse;
+        d.n_q = reqs[r].n_q;
+        d.n_chunks = plans[r].n_live;
+        d.n_split = plans[r].n_split;
+        d.pad = 0;
+        if (mp.n_reqs == kMaxMergeReqs) {
+            HIPCHK(c, launch_k5(mp, st));
+            mp.n_reqs = 0;
+        }
+    }
+    if (mp.n_reqs) HIPCHK(c, launch_k5(mp, st));
+    return HA_RAG_OK;
+}
+
+}  // extern "C"

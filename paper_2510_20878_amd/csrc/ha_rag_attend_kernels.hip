@@ -1,0 +1,401 @@
+// gfx950 kernels for attention of a request's query tokens over its packed chunks, without
+// building the BF16 cache first (the prefill of Sec. 2.1 consumes the concatenated chunk KV;
+// here the consumer reads the compressed chunks of Sec. 2.2 itself).
+//
+//  k4_attend_partial   one wave per (chunk, KV head, token split, group of query rows):
+//      decodes K and V blocks to BF16 in registers (the values a load would write), scores
+//      them with MFMA, keeps a running softmax, writes an unnormalised partial result
+//  k5_attend_merge     one workgroup per (query token, query head): merges the partial
+//      results of the request's chunks and splits into out and the log-sum-exp
+//
+// head_dim 128 only: a layout block is then 16 tokens x 128 dims, and lane (a = lane/16,
+// o = lane%16) of the wave that reads it holds, in plane j, token 4j + a, dims 8o .. 8o+7.
+//
+// V needs no rearrangement: for the product P V the 16x16x16 MFMA contracts 16 tokens, lane
+// group a supplies 4 of them from its 4 planes, and lane column o supplies dim 8o + p, so
+// MFMA number p (0..7) takes from each lane the p-th value of each of its 4 planes.
+// K is contracted over dims, 8 per lane, with tokens across the 16 lane columns: the raw
+// words go through LDS once (as codes, before decoding) and come back with token and dim
+// roles of the lane index exchanged.  The score tile is computed transposed (tokens x query
+// rows) so that its register layout is already the one P needs as an MFMA operand.
+#include "ha_rag_kernels.h"
+#include "ha_rag_decode.h"
+
+namespace ha_rag {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <uint32_t PREC>
+struct Fmt {
+    static constexpr uint32_t kWords = PREC == kInt4 ? 1u : PREC == kP16 ? 4u : 2u;  // 16-byte words per lane and block
+    static constexpr uint32_t kPayload = 1024u * kWords;
+    static constexpr bool kMeta = PREC == kInt4 || PREC == kInt8;
+};
+
+// the raw codes of one octet (x: int4; x, y: 8-bit formats; all four: 16-bit) -> 8 BF16
+template <uint32_t PREC>
+__device__ __forceinline__ u32x4 decode_octet(u32x4 raw, uint32_t meta, int base, int top)
+{
+    if (PREC == kInt4) return dequant_octet4(raw.x, meta);
+    if (PREC == kInt8) return dequant_octet8(raw.x, raw.y, meta);
+    if (PREC == kE4M3) return decode_octet_fp8<false>(raw.x, raw.y);
+    if (PREC == kE5M2) return decode_octet_fp8<true>(raw.x, raw.y);
+    if (PREC == kGSE8) return decode_octet_gse8(raw.x, raw.y, base, top);
+    return raw;
+}
+
+// plane j of the words a lane loaded from a payload block
+template <uint32_t PREC>
+__device__ __forceinline__ u32x4 plane_raw(const u32x4 *w, int j)
+{
+    u32x4 r = {0u, 0u, 0u, 0u};
+    if (PREC == kInt4) r.x = w[0][j];
+    else if (PREC == kP16) r = w[j];
+    else {
+        r.x = w[j >> 1][(j & 1) * 2];
+        r.y = w[j >> 1][(j & 1) * 2 + 1];
+    }
+    return r;
+}
+
+__device__ __forceinline__ float neg_inf() { return -__builtin_huge_valf(); }
+
+template <uint32_t PREC, int MTW>
+__device__ __forceinline__ void attend_unit(const K4Params &p, const K4Chunk &c, uint32_t h,
+                                            uint32_t s, uint32_t mtg, uint8_t *lds)
+{
+    typedef Fmt<PREC> F;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t c_ = lane >> 4, n_ = lane & 15u;  // MFMA coordinates: lane group, lane column
+    const uint32_t a_ = n_ >> 2, x_ = n_ & 3u;
+    const uint32_t H = p.n_kv_heads, G = p.n_q_heads / H, M = c.n_q * G;
+    const uint32_t n_mt = (M + 15u) >> 4;
+    const uint32_t T = c.n_tokens, nblk = (T + 15u) >> 4;
+    const uint32_t gsh = (c.fmt >> 8) & 0xFFu;
+    const uint32_t meta_blk = F::kMeta ? 8192u >> gsh : 0u;
+    const uint64_t tile_bytes = (uint64_t)nblk * (F::kPayload + meta_blk) + (PREC == kGSE8 ? 16u : 0u);
+    const uint8_t *kt = c.src + (uint64_t)((p.layer * 2u) * H + h) * tile_bytes;
+    const uint8_t *vt = c.src + (uint64_t)((p.layer * 2u + 1u) * H + h) * tile_bytes;
+    const uint8_t *kmeta = kt + (uint64_t)nblk * F::kPayload;
+    const uint8_t *vmeta = vt + (uint64_t)nblk * F::kPayload;
+    float *rec0 = c.part + (uint64_t)((h * c.n_split + s) * n_mt) * kAttendRecFloats;
+
+    const uint32_t b0 = s * kAttendSplitBlocks;
+    const uint32_t b1 = b0 + kAttendSplitBlocks < nblk ? b0 + kAttendSplitBlocks : nblk;
+    if (b0 >= b1) {  // nothing of this chunk in this split: an empty record (l = 0)
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt) {
+            const uint32_t mtile = mtg * MTW + mt;
+            if (mtile < n_mt && c_ == 0) {
+                float *rec = rec0 + (uint64_t)mtile * kAttendRecFloats;
+                rec[2048 + n_] = neg_inf();
+                rec[2048 + 16 + n_] = 0.0f;
+            }
+        }
+        return;
+    }
+
+    int kbase = 0, ktop = 0, vbase = 0, vtop = 0;
+    if (PREC == kGSE8) {
+        const uint32_t kr = *reinterpret_cast<const uint32_t *>(kt + (uint64_t)nblk * 2048u);
+        const uint32_t vr = *reinterpret_cast<const uint32_t *>(vt + (uint64_t)nblk * 2048u);
+        kbase = (int)(int8_t)(kr & 0xFFu);
+        ktop = (int)(int8_t)((kr >> 8) & 0xFFu) - 2;
+        vbase = (int)(int8_t)(vr & 0xFFu);
+        vtop = (int)(int8_t)((vr >> 8) & 0xFFu) - 2;
+    }
+
+    // Q as the B operand of S^T = K Q^T: lane (c_, n_) holds, for MFMA y, dims
+    // 32 c_ + 8 y .. + 7 of query row n_ of the tile (zero rows beyond M)
+    bf16x8 qb[MTW][4];
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt) {
+        const uint32_t row = (mtg * MTW + mt) * 16u + n_;
+        u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int y = 0; y < 4; ++y) qb[mt][y] = __builtin_bit_cast(bf16x8, z);
+        if (row < M) {
+            const uint32_t qt = row / G, gq = row - qt * G;
+            const uint8_t *qp = reinterpret_cast<const uint8_t *>(c.q) +
+                                ((uint64_t)(qt * p.n_q_heads + h * G + gq) * 128u + 32u * c_) * 2u;
+#pragma unroll
+            for (int y = 0; y < 4; ++y) qb[mt][y] = __builtin_bit_cast(bf16x8, ld16(qp + 16 * y));
+        }
+    }
+
+    float m_run[MTW], l_run[MTW];
+    f32x4 O[MTW][8];
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt) {
+        m_run[mt] = neg_inf();
+        l_run[mt] = 0.0f;
+#pragma unroll
+        for (int pp = 0; pp < 8; ++pp) O[mt][pp] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // K after the exchange: this lane holds token tk = 4 x_ + a_ of the block and, for MFMA y,
+    // the octet 4 c_ + y, which lane 16 a_ + 4 c_ + y loaded as its plane x_
+    const uint32_t src_lane0 = 16u * a_ + 4u * c_;
+    uint32_t k_entry = 0;  // scale/zero entry of (token tk, dims 32 c_ ..) in a meta block
+    if (F::kMeta) {
+        const uint32_t grp = ((4u * x_ + a_) * 128u + 32u * c_) >> gsh;
+        k_entry = (grp & ((512u >> gsh) - 1u)) * 4u + (grp >> (9u - gsh));
+    }
+    u32x4 *lds_w = reinterpret_cast<u32x4 *>(lds);
+
+    for (uint32_t b = b0; b < b1; ++b) {
+        // ---- loads of this block: K words, V words, metas
+        u32x4 kw[F::kWords], vw[F::kWords];
+#pragma unroll
+        for (uint32_t a = 0; a < F::kWords; ++a) {
+            kw[a] = ld16(kt + (uint64_t)b * F::kPayload + a * 1024u + lane * 16u);
+            vw[a] = ld16(vt + (uint64_t)b * F::kPayload + a * 1024u + lane * 16u);
+        }
+        uint32_t km = 0;
+        u32x4 vm = {0u, 0u, 0u, 0u};
+        if (F::kMeta) {
+            km = *reinterpret_cast<const uint32_t *>(kmeta + (uint64_t)b * meta_blk + 4u * k_entry);
+            vm = ld16(vmeta + (uint64_t)b * meta_blk + ((lane * 8u) >> gsh) * 16u);
+        }
+
+        // ---- K: exchange through LDS, decode, S^T = K Q^T
+#pragma unroll
+        for (uint32_t a = 0; a < F::kWords; ++a) lds_w[a * 64u + lane] = kw[a];
+        __syncthreads();
+        bf16x8 ka[4];
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+            const uint32_t i_src = src_lane0 + y;
+            u32x4 raw = {0u, 0u, 0u, 0u};
+            if (PREC == kInt4) {
+                raw.x = *reinterpret_cast<const uint32_t *>(lds + 16u * i_src + 4u * x_);
+            } else if (PREC == kP16) {
+                raw = *reinterpret_cast<const u32x4 *>(lds + 1024u * x_ + 16u * i_src);
+            } else {
+                const u32x2 t = *reinterpret_cast<const u32x2 *>(lds + 1024u * (x_ >> 1) + 16u * i_src + 8u * (x_ & 1u));
+                raw.x = t.x;
+                raw.y = t.y;
+            }
+            ka[y] = __builtin_bit_cast(bf16x8, decode_octet<PREC>(raw, km, kbase, ktop));
+        }
+        __syncthreads();
+
+        s16x4 pa[MTW];
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt) {
+            f32x4 S = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int y = 0; y < 4; ++y)
+                S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[y], qb[mt][y], S, 0, 0, 0);
+            // S[jj] = score of token 4 jj + c_ of the block against query row n_
+            float sc[4];
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                sc[jj] = (b * 16u + 4u * jj + c_ < T) ? S[jj] * p.scale_log2 : neg_inf();
+            float mx = __builtin_fmaxf(__builtin_fmaxf(sc[0], sc[1]), __builtin_fmaxf(sc[2], sc[3]));
+            mx = __builtin_fmaxf(mx, __shfl_xor(mx, 16));
+            mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = __builtin_fmaxf(m_run[mt], mx);
+            if (__any(m_new > m_run[mt])) {  // rare after the first blocks: rescale what is accumulated
+                const float alpha = __builtin_amdgcn_exp2f(m_run[mt] - m_new);  // 0 at the first block
+                l_run[mt] *= alpha;
+                m_run[mt] = m_new;
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    const float ar = __shfl(alpha, (int)(4u * c_ + jj));  // factor of output row 4 c_ + jj
+#pragma unroll
+                    for (int pp = 0; pp < 8; ++pp) O[mt][pp][jj] *= ar;
+                }
+            }
+            float pr[4];
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) pr[jj] = __builtin_amdgcn_exp2f(sc[jj] - m_run[mt]);
+            l_run[mt] += (pr[0] + pr[1]) + (pr[2] + pr[3]);
+            const u32x2 pk = {pack_bf16(pr[0], pr[1]), pack_bf16(pr[2], pr[3])};
+            pa[mt] = __builtin_bit_cast(s16x4, pk);
+        }
+
+        // ---- V: decode the lane's four planes, regroup by position, O += P V
+        u32x4 vr[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            vr[j] = decode_octet<PREC>(plane_raw<PREC>(vw, j), vm[j], vbase, vtop);
+            if (b * 16u + 4u * j + c_ >= T) vr[j] = u32x4{0u, 0u, 0u, 0u};  // rows past the chunk's end
+        }
+#pragma unroll
+        for (int pp = 0; pp < 8; ++pp) {
+            const uint32_t sel = (pp & 1) ? 0x07060302u : 0x05040100u;
+            const u32x2 t = {__builtin_amdgcn_perm(vr[1][pp >> 1], vr[0][pp >> 1], sel),
+                             __builtin_amdgcn_perm(vr[3][pp >> 1], vr[2][pp >> 1], sel)};
+            const s16x4 vb = __builtin_bit_cast(s16x4, t);
+#pragma unroll
+            for (int mt = 0; mt < MTW; ++mt)
+                O[mt][pp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa[mt], vb, O[mt][pp], 0, 0, 0);
+        }
+    }
+
+    // ---- the record: O[row 4 c_ + jj][dim 8 n_ + pp], m and l per row
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt) {
+        const uint32_t mtile = mtg * MTW + mt;
+        float l_tot = l_run[mt];
+        l_tot += __shfl_xor(l_tot, 16);
+        l_tot += __shfl_xor(l_tot, 32);
+        if (mtile >= n_mt) continue;
+        float *rec = rec0 + (uint64_t)mtile * kAttendRecFloats;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            float *dst = rec + (4u * c_ + jj) * 128u + 8u * n_;
+            *reinterpret_cast<f32x4 *>(dst) = f32x4{O[mt][0][jj], O[mt][1][jj], O[mt][2][jj], O[mt][3][jj]};
+            *reinterpret_cast<f32x4 *>(dst + 4) = f32x4{O[mt][4][jj], O[mt][5][jj], O[mt][6][jj], O[mt][7][jj]};
+        }
+        if (c_ == 0) {
+            rec[2048 + n_] = m_run[mt];
+            rec[2048 + 16 + n_] = l_tot;
+        }
+    }
+}
+
+template <int MTW>
+__global__ void __launch_bounds__(64) k4_attend_partial(const K4Params p)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds[4096];
+    const uint32_t unit = blockIdx.x;
+    if (unit >= p.total_units) return;
+    uint32_t lo = 0, hi = p.n_chunks;  // unit_start[lo] <= unit < unit_start[hi]
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (unit >= p.unit_start[mid]) lo = mid;
+        else hi = mid;
+    }
+    const K4Chunk &c = p.c[lo];
+    const uint32_t u = unit - p.unit_start[lo];
+    const uint32_t G = p.n_q_heads / p.n_kv_heads;
+    const uint32_t n_mt = (c.n_q * G + 15u) >> 4;
+    const uint32_t n_mtg = (n_mt + MTW - 1u) / MTW;
+    const uint32_t mtg = u % n_mtg;
+    const uint32_t hs = u / n_mtg;
+    const uint32_t s = hs % c.n_split, h = hs / c.n_split;
+    switch (c.fmt & 0xFFu) {
+    case kP16: attend_unit<kP16, MTW>(p, c, h, s, mtg, lds); break;
+    case kInt8: attend_unit<kInt8, MTW>(p, c, h, s, mtg, lds); break;
+    case kInt4: attend_unit<kInt4, MTW>(p, c, h, s, mtg, lds); break;
+    case kE4M3: attend_unit<kE4M3, MTW>(p, c, h, s, mtg, lds); break;
+    case kE5M2: attend_unit<kE5M2, MTW>(p, c, h, s, mtg, lds); break;
+    default: attend_unit<kGSE8, MTW>(p, c, h, s, mtg, lds); break;
+    }
+}
+
+hipError_t launch_k4(K4Params &p, hipStream_t stream)
+{
+    if (p.n_chunks == 0) return hipSuccess;
+    if (p.n_chunks > kMaxLaunchChunks || p.n_kv_heads == 0 || p.n_q_heads % p.n_kv_heads)
+        return hipErrorInvalidValue;
+    const uint32_t G = p.n_q_heads / p.n_kv_heads;
+    uint32_t max_mt = 1;
+    for (uint32_t i = 0; i < p.n_chunks; ++i) {
+        const K4Chunk &c = p.c[i];
+        const uint32_t prec = c.fmt & 0xFFu, gsh = (c.fmt >> 8) & 0xFFu;
+        if (prec > kGSE8 || !c.src || !c.q || !c.part || c.n_q == 0 || c.n_split == 0 ||
+            ((uintptr_t)c.src & 15u) || ((uintptr_t)c.q & 15u) || ((uintptr_t)c.part & 15u))
+            return hipErrorInvalidValue;
+        if ((prec == kInt4 || prec == kInt8) && (gsh < 5 || gsh > 7)) return hipErrorInvalidValue;
+        if ((uint64_t)c.n_q * G > 0xFFFFFFull || c.n_tokens > 0x7FFFFFFu) return hipErrorInvalidValue;
+        // every block of the chunk must belong to one of its splits
+        if ((uint64_t)c.n_split * kAttendSplitBlocks * 16u < c.n_tokens) return hipErrorInvalidValue;
+        const uint32_t n_mt = (c.n_q * G + 15u) >> 4;
+        if (n_mt > max_mt) max_mt = n_mt;
+    }
+    p.mtw = max_mt >= 4 ? 4u : max_mt >= 2 ? 2u : 1u;
+    uint64_t total = 0;
+    for (uint32_t i = 0; i < p.n_chunks; ++i) {
+        const uint32_t n_mt = (p.c[i].n_q * G + 15u) >> 4;
+        p.unit_start[i] = (uint32_t)total;
+        total += (uint64_t)p.n_kv_heads * p.c[i].n_split * ((n_mt + p.mtw - 1u) / p.mtw);
+        if (total > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    }
+    p.unit_start[p.n_chunks] = (uint32_t)total;
+    p.total_units = (uint32_t)total;
+    p.pad = 0;
+    dim3 grid((uint32_t)total), block(64);
+    switch (p.mtw) {
+    case 1: hipLaunchKernelGGL((k4_attend_partial<1>), grid, block, 0, stream, p); break;
+    case 2: hipLaunchKernelGGL((k4_attend_partial<2>), grid, block, 0, stream, p); break;
+    default: hipLaunchKernelGGL((k4_attend_partial<4>), grid, block, 0, stream, p); break;
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// K5.  One workgroup of 128 threads (one per dim) per (query token, query head).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(128) k5_attend_merge(const K5Params p)
+{
+    const uint32_t row = blockIdx.x;
+    if (row >= p.total_rows) return;
+    uint32_t lo = 0, hi = p.n_reqs;
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (row >= p.row_start[mid]) lo = mid;
+        else hi = mid;
+    }
+    const K5Req &r = p.r[lo];
+    const uint32_t rr = row - p.row_start[lo];
+    const uint32_t qt = rr / p.n_q_heads, hq = rr - qt * p.n_q_heads;
+    const uint32_t G = p.n_q_heads / p.n_kv_heads;
+    const uint32_t h = hq / G, gq = hq - h * G;
+    const uint32_t mrow = qt * G + gq, mt = mrow >> 4, ri = mrow & 15u;
+    const uint32_t n_mt = (r.n_q * G + 15u) >> 4;
+    const uint32_t d = threadIdx.x;
+    const uint64_t chunk_stride = (uint64_t)p.n_kv_heads * r.n_split * n_mt * kAttendRecFloats;
+    const float *first = r.part + ((uint64_t)(h * r.n_split) * n_mt + mt) * kAttendRecFloats;
+    const uint64_t split_stride = (uint64_t)n_mt * kAttendRecFloats;
+
+    float m_max = neg_inf();
+    for (uint32_t ci = 0; ci < r.n_chunks; ++ci)
+        for (uint32_t s = 0; s < r.n_split; ++s) {
+            const float *rec = first + ci * chunk_stride + s * split_stride;
+            if (rec[2048 + 16 + ri] > 0.0f) m_max = __builtin_fmaxf(m_max, rec[2048 + ri]);
+        }
+    float acc = 0.0f, l_sum = 0.0f;
+    for (uint32_t ci = 0; ci < r.n_chunks; ++ci)
+        for (uint32_t s = 0; s < r.n_split; ++s) {
+            const float *rec = first + ci * chunk_stride + s * split_stride;
+            const float l = rec[2048 + 16 + ri];
+            if (l > 0.0f) {
+                const float w = __builtin_amdgcn_exp2f(rec[2048 + ri] - m_max);
+                acc = __builtin_fmaf(w, rec[ri * 128u + d], acc);
+                l_sum = __builtin_fmaf(w, l, l_sum);
+            }
+        }
+    const uint64_t o = (uint64_t)qt * p.n_q_heads + hq;
+    r.out[o * 128u + d] = l_sum > 0.0f ? acc / l_sum : 0.0f;
+    if (d == 0 && r.lse)
+        r.lse[o] = l_sum > 0.0f ? (m_max + __builtin_log2f(l_sum)) * 0.69314718055994531f : neg_inf();
+}
+
+hipError_t launch_k5(K5Params &p, hipStream_t stream)
+{
+    if (p.n_reqs == 0) return hipSuccess;
+    if (p.n_reqs > kMaxMergeReqs || p.n_kv_heads == 0 || p.n_q_heads % p.n_kv_heads)
+        return hipErrorInvalidValue;
+    uint64_t total = 0;
+    for (uint32_t i = 0; i < p.n_reqs; ++i) {
+        const K5Req &r = p.r[i];
+        // a request without a token to attend to (n_chunks 0) gets zeros and lse = -inf
+        if ((r.n_chunks && !r.part) || !r.out || r.n_q == 0 || r.n_split == 0)
+            return hipErrorInvalidValue;
+        p.row_start[i] = (uint32_t)total;
+        total += (uint64_t)r.n_q * p.n_q_heads;
+        if (total > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    }
+    p.row_start[p.n_reqs] = (uint32_t)total;
+    p.total_rows = (uint32_t)total;
+    hipLaunchKernelGGL(k5_attend_merge, dim3((uint32_t)total), dim3(128), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace ha_rag

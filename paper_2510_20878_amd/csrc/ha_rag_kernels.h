@@ -90,4 +90,51 @@ hipError_t launch_k3(const void *src, const void *packed, uint32_t n_tiles, uint
                      uint32_t n_tokens, uint32_t prec, uint32_t group, double *sum_sq,
                      hipStream_t stream);
 
+// ---- attention over packed chunks (head_dim 128 only) ------------------------------------
+// A partial result of one (chunk, KV head, token split, 16 query rows): unnormalised
+// output [16][128] binary32, then the running maximum m[16] (base-2 exponent units) and the
+// sum l[16] of 2^(score - m).
+constexpr uint32_t kAttendHeadDim = 128;
+constexpr uint32_t kAttendRecFloats = 16 * 128 + 32;
+constexpr uint32_t kAttendSplitBlocks = 32;  // layout blocks (16 tokens each) per split
+
+struct K4Chunk {
+    const uint8_t *src;   // packed whole chunk
+    const uint16_t *q;    // BF16 [n_q][n_q_heads][128] of the chunk's request
+    float *part;          // this chunk's records [n_kv_heads][n_split][n_mtiles]
+    uint32_t n_tokens;
+    uint32_t fmt;         // Prec | log2(group) << 8
+    uint32_t n_q;         // query tokens of the request
+    uint32_t n_split;     // token splits of the request (the same for all its chunks)
+};
+
+struct K4Params {
+    uint32_t n_kv_heads, n_q_heads, layer, n_chunks;
+    uint32_t total_units;
+    uint32_t mtw;          // 16-row query tiles per wave: 1, 2 or 4 (set by launch_k4)
+    float scale_log2;      // sm_scale * log2(e)
+    uint32_t pad;
+    uint32_t unit_start[kMaxLaunchChunks + 1];  // prefix sum of units (one wave each) per chunk
+    K4Chunk c[kMaxLaunchChunks];
+};
+
+struct K5Req {
+    const float *part;    // records [n_chunks][n_kv_heads][n_split][n_mtiles]
+    float *out;           // binary32 [n_q][n_q_heads][128]
+    float *lse;           // binary32 [n_q][n_q_heads] or null
+    uint32_t n_q, n_chunks, n_split, pad;
+};
+
+constexpr uint32_t kMaxMergeReqs = 64;
+struct K5Params {
+    uint32_t n_kv_heads, n_q_heads, n_reqs, total_rows;
+    uint32_t row_start[kMaxMergeReqs + 1];  // prefix sum of n_q * n_q_heads per request
+    K5Req r[kMaxMergeReqs];
+};
+
+// Partial attention of every chunk of the launch (fills unit_start, total_units, mtw).
+hipError_t launch_k4(K4Params &p, hipStream_t stream);
+// Merges the partial results of each request into out and lse.
+hipError_t launch_k5(K5Params &p, hipStream_t stream);
+
 }  // namespace ha_rag

@@ -54,7 +54,7 @@ def test_struct_sizes_match_the_header_layout(tmp_path):
     pairs = [("ha_rag_config", B.Config), ("ha_rag_packed_chunk", B.PackedChunk),
              ("ha_rag_chunk_trace", B.ChunkTrace), ("ha_rag_load_stats", B.LoadStats),
              ("ha_rag_chunk_info", B.ChunkInfo), ("ha_rag_launch_params", B.LaunchParams),
-             ("ha_rag_paged_cache", B.PagedCache)]
+             ("ha_rag_paged_cache", B.PagedCache), ("ha_rag_attend_request", B.AttendRequest)]
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "ha_rag.h"', 'int main(void){']
     for cname, cls in pairs:
         lines.append(f'printf("{cname} %zu\\n", sizeof({cname}));')

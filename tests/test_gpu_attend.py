@@ -1,0 +1,192 @@
+"""Attention straight over packed chunks (HIP, through the C ABI) against the CPU oracle:
+binary64 softmax attention over the BF16 cache the load oracle builds from the same packed
+bytes.
+
+Tolerance (derived from the kernel's arithmetic; K and V values are exact on both sides):
+  * the softmax weights are rounded to BF16 (8 significant bits: relative 2^-8 each at worst)
+    before they multiply V while the normaliser keeps them in binary32: |out error| <=
+    2^-8 * spread, spread = sum_t softmax(s)[t] |V[t][d]| (the oracle returns it);
+  * scores are sums of 128 exact products accumulated in binary32: |s error| <= 2^-17 * sabs,
+    sabs = sm_scale * sum_d |q[d] K[t][d]| (max over t); it shifts lse by as much and the
+    weights by that relative amount.  The bar adds 2^-15 * (1 + sabs) (times spread for out),
+    which also covers the hardware exp2 / log2 (about 1 ulp of binary32).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attend as A
+from oracle import codec
+from paper_2510_20878_amd import binding as B
+from paper_2510_20878_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    B.lib()
+    yield
+    torch.cuda.synchronize()
+
+
+def dev_u8(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint8)).cuda()
+
+
+def q_words(n_q, n_qh, D, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return wl.f32_to_bf16_words(rng.standard_normal((n_q, n_qh, D), dtype=np.float32))
+
+
+def check(out, lse, ref_out, ref_lse, spread, sabs):
+    """sabs: [n_q][n_qh] bound on sum |q k| * scale."""
+    slack = 2.0 ** -15 * (1.0 + sabs)
+    err = np.abs(out.astype(np.float64) - ref_out)
+    bar = 2.0 ** -8 * spread + slack[..., None] * spread + 1e-30
+    assert np.all(err <= bar), (float((err / bar).max()), float(err.max()))
+    lerr = np.abs(lse.astype(np.float64) - ref_lse)
+    assert np.all(lerr <= slack), (float((lerr / slack).max()), float(lerr.max()))
+    return float((err / bar).max()), float((lerr / slack).max())
+
+
+def score_bound(cache, layer, n_kv, qw, scale, H):
+    q = np.abs(A.bf16_words_to_f64(qw))
+    n_q, n_qh, D = q.shape
+    G = n_qh // H
+    out = np.zeros((n_q, n_qh))
+    for hq in range(n_qh):
+        K = np.abs(A.bf16_words_to_f64(cache[layer, 0, hq // G, :n_kv]))
+        out[:, hq] = scale * (q[:, hq] @ K.T).max(axis=1)
+    return out
+
+
+def run_case(shape, reqs, layer, n_qh, scale, seed, g8=128, g4=128, max_tokens=None):
+    """reqs: list of (tokens list, precs list, n_q).  Chunk i of a request is drawn from seed."""
+    L, H, D = shape
+    T_max = max_tokens or max([t for r in reqs for t in r[0]] + [16])
+    ctx = B.Context(L, H, D, T_max, group_int8=g8, group_int4=g4)
+    grp = {B.PREC_INT8: g8, B.PREC_INT4: g4}
+    ORC = {B.PREC_16: 16, B.PREC_INT8: 8, B.PREC_INT4: 4, B.PREC_FP8_E4M3: 43, B.PREC_FP8_E5M2: 52,
+           B.PREC_GSE8: 143}
+    keep, call, refs = [], [], []
+    k = 0
+    for ri, (tokens, precs, n_q) in enumerate(reqs):
+        packs = []
+        for t, p in zip(tokens, precs):
+            src = wl.kv_chunk(L, H, D, t, seed + k) if t else np.zeros((L, 2, H, 0, D), np.uint16)
+            k += 1
+            packs.append(codec.quantize_pack_chunk(src, ORC[p], grp.get(p, 128))[0] if t
+                         else np.zeros(0, np.uint8))
+        qw = q_words(n_q, n_qh, D, seed + 1000 + ri)
+        q_d = torch.from_numpy(qw.view(np.int16)).cuda()
+        out_d = torch.full((n_q, n_qh, D), float("nan"), dtype=torch.float32, device="cuda")
+        lse_d = torch.full((n_q, n_qh), float("nan"), dtype=torch.float32, device="cuda")
+        packs_d = [dev_u8(p) if len(p) else None for p in packs]
+        keep += [q_d, out_d, lse_d, packs_d]
+        call.append(([(pd, t, p, grp.get(p, 0)) for pd, t, p in zip(packs_d, tokens, precs)],
+                     q_d, out_d, lse_d, n_q))
+        refs.append((packs, tokens, precs, qw, out_d, lse_d))
+    nbytes = ctx.attend_workspace_bytes(call, n_qh)
+    ws = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.attend_packed(call, layer, n_qh, scale, ws, nbytes)
+    torch.cuda.synchronize()
+    worst = (0.0, 0.0)
+    for packs, tokens, precs, qw, out_d, lse_d in refs:
+        n_kv = sum(tokens)
+        out, lse = out_d.cpu().numpy(), lse_d.cpu().numpy()
+        if n_kv == 0:
+            assert np.all(out == 0) and np.all(np.isneginf(lse))
+            continue
+        live = [i for i, t in enumerate(tokens) if t]
+        cache, _ = codec.load_chunks(packs, shape, tokens, [ORC[p] for p in precs],
+                                     [grp.get(p, 128) for p in precs], live)
+        ref_out, ref_lse, spread = A.attend(cache, layer, n_kv, qw, scale)
+        w = check(out, lse, ref_out, ref_lse, spread, score_bound(cache, layer, n_kv, qw, scale, H))
+        worst = (max(worst[0], w[0]), max(worst[1], w[1]))
+    ctx.destroy()
+    return worst
+
+
+ALL = [B.PREC_16, B.PREC_INT8, B.PREC_INT4, B.PREC_FP8_E4M3, B.PREC_FP8_E5M2, B.PREC_GSE8]
+
+
+def test_all_six_tags_ragged_chunks_one_request():
+    tokens = [40, 16, 77, 1, 33, 128]
+    print("worst error / bar:", run_case((2, 2, 128), [(tokens, ALL, 3)], 1, 8, 128 ** -0.5, 10))
+
+
+@pytest.mark.parametrize("prec", ALL)
+@pytest.mark.parametrize("n_q,n_qh", [(1, 2), (1, 8), (5, 8), (16, 8), (21, 8), (3, 32)])
+def test_each_tag_and_query_tile_count(prec, n_q, n_qh):
+    run_case((2, 2, 128), [([50, 96], [prec, prec], n_q)], 0, n_qh, 0.1, 20 + n_q)
+
+
+@pytest.mark.parametrize("g", [32, 64])
+def test_smaller_groups(g):
+    run_case((1, 2, 128), [([70, 30], [B.PREC_INT4, B.PREC_INT8], 2)], 0, 4, 0.09, 30, g8=g, g4=g)
+
+
+def test_a_chunk_longer_than_one_split_and_a_sharp_softmax():
+    # 1100 tokens = 3 splits; a large scale makes few keys dominate, so the running maximum
+    # keeps moving and accumulated sums are rescaled many times
+    run_case((1, 1, 128), [([1100, 513], [B.PREC_INT4, B.PREC_INT8], 4)], 0, 4, 0.5, 40)
+
+
+def test_batch_of_requests_with_different_shapes_empty_chunks_and_an_empty_request():
+    reqs = [([30, 0, 65], [B.PREC_INT4, B.PREC_16, B.PREC_INT8], 1),
+            ([], [], 2),
+            ([16], [B.PREC_GSE8], 17),
+            ([0], [B.PREC_INT4], 1),
+            ([600, 20, 48, 48], [B.PREC_FP8_E4M3, B.PREC_INT4, B.PREC_INT4, B.PREC_FP8_E5M2], 6)]
+    run_case((2, 2, 128), reqs, 1, 4, 0.088, 50)
+
+
+def test_more_chunks_and_requests_than_one_launch_holds():
+    reqs = [([16 + (3 * i + j) % 20 for j in range(3)], [ALL[(i + j) % 6] for j in range(3)], 1 + i % 3)
+            for i in range(70)]                      # 210 chunks, 70 requests
+    run_case((1, 1, 128), reqs, 0, 2, 0.1, 60)
+
+
+def test_llama3_8b_request_sampled_heads_match_oracle():
+    """One request of the headline workload (32 layers, 8 KV heads, head_dim 128, ten
+    512-token chunks: 2 x 16-bit, 3 x int8, 5 x int4, group 128; 32 query heads, one and
+    sixteen query tokens) in the launch configuration the benchmark times; (layer, KV head)
+    pairs are sampled and recomputed by the oracle from the same source words."""
+    L, H, D, T, g, n_qh = 32, 8, 128, 512, 128, 32
+    G = n_qh // H
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g)
+    precs = [B.PREC_16] * 2 + [B.PREC_INT8] * 3 + [B.PREC_INT4] * 5
+    order = [4, 9, 0, 6, 2, 8, 1, 5, 3, 7]
+    srcs, packs = [], []
+    for i, p in enumerate(precs):
+        s_ = wl.kv_chunk_device(L, H, D, T, 700 + i)
+        dst = torch.empty(ctx.chunk_bytes(p, T), dtype=torch.uint8, device="cuda")
+        ctx.quantize_chunk(s_, T, p, g, dst)
+        srcs.append(s_)
+        packs.append(dst)
+    rng = np.random.default_rng(1)
+    scale = D ** -0.5
+    for n_q in (1, 16):
+        qw = q_words(n_q, n_qh, D, 800 + n_q)
+        q_d = torch.from_numpy(qw.view(np.int16)).cuda()
+        out_d = torch.full((n_q, n_qh, D), float("nan"), dtype=torch.float32, device="cuda")
+        lse_d = torch.full((n_q, n_qh), float("nan"), dtype=torch.float32, device="cuda")
+        call = [([(packs[c], T, precs[c], g) for c in order], q_d, out_d, lse_d, n_q)]
+        nbytes = ctx.attend_workspace_bytes(call, n_qh)
+        ws = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda")
+        for layer, h in [(0, 0), (31, 7)] + [(int(rng.integers(L)), int(rng.integers(H))) for _ in range(2)]:
+            ctx.attend_packed(call, layer, n_qh, scale, ws, nbytes)
+            torch.cuda.synchronize()
+            cache = np.zeros((1, 2, 1, len(order) * T, D), np.uint16)
+            for pos, c in enumerate(order):
+                bits = B.BITS[precs[c]]
+                src_kv = srcs[c][layer, :, h].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+                ref_pack, _ = codec.quantize_pack_chunk(src_kv.reshape(1, 2, 1, T, D), bits, g)
+                codec.dequant_scatter_chunk(ref_pack, (1, 1, D), T, bits, g, cache, pos * T)
+            qh = np.ascontiguousarray(qw[:, h * G:(h + 1) * G])
+            ref_out, ref_lse, spread = A.attend(cache, 0, len(order) * T, qh, scale)
+            check(out_d[:, h * G:(h + 1) * G].cpu().numpy(), lse_d[:, h * G:(h + 1) * G].cpu().numpy(),
+                  ref_out, ref_lse, spread, score_bound(cache, 0, len(order) * T, qh, scale, 1))
+    ctx.destroy()

@@ -768,3 +768,55 @@ def test_remove_takes_a_chunk_out_of_every_tier_and_frees_its_slots():
         ctx.pool_insert(100, B.PREC_INT4, 128, None, B.TIER_DISK)
     assert e.value.code == B.ENOSPC
     ctx.destroy()
+
+
+def _attend_ctx(D=128, L=4, H=2):
+    return B.Context(L, H, D, 512, group_int8=min(D, 128), group_int4=min(D, 64), dry_run=True)
+
+
+def test_attend_workspace_size_and_argument_checks():
+    ctx = _attend_ctx()
+    P = 0x7F0000001000
+    ch = lambda t, p=B.PREC_INT4, g=64, part=B.PART_KV: (P, t, p, g, part)
+    req = lambda chunks, n_q: (chunks, P, P, None, n_q)
+    REC = (16 * 128 + 32) * 4
+    # records: live chunks x KV heads x splits (of 512 tokens) x 16-row query tiles
+    assert ctx.attend_workspace_bytes([req([ch(512), ch(100)], 1)], 8) == 2 * 2 * 1 * 1 * REC
+    assert ctx.attend_workspace_bytes([req([ch(512), ch(0)], 5)], 8) == 1 * 2 * 1 * 2 * REC
+    c2 = B.Context(4, 2, 128, 2000, group_int8=128, group_int4=64, dry_run=True)
+    assert c2.attend_workspace_bytes([req([ch(1100), ch(10)], 4), req([], 1), req([ch(16)], 9)], 4) == \
+        (2 * 2 * 3 * 1 + 0 + 1 * 2 * 1 * 2) * REC
+    c2.destroy()
+    ok = [req([ch(512), ch(100, B.PREC_16, 0)], 3)]
+    n = ctx.attend_workspace_bytes(ok, 8)
+    ctx.attend_packed(ok, 3, 8, 0.1, P, n)
+
+    def fails(code, reqs, layer=0, n_qh=8, scale=0.1, ws=P, ws_bytes=n):
+        with pytest.raises(B.HaRagError) as e:
+            ctx.attend_packed(reqs, layer, n_qh, scale, ws, ws_bytes)
+        assert e.value.code == code, e.value.code
+
+    fails(B.EINVAL, ok, layer=4)
+    fails(B.EINVAL, ok, n_qh=7)
+    fails(B.EINVAL, ok, n_qh=0)
+    fails(B.EINVAL, ok, n_qh=2 * 65)
+    fails(B.EINVAL, ok, scale=0.0)
+    fails(B.EINVAL, ok, scale=float("nan"))
+    fails(B.EINVAL, ok, ws=P + 4)
+    fails(B.EINVAL, ok, ws=None)
+    fails(B.ENOSPC, ok, ws_bytes=n - 1)
+    fails(B.EINVAL, [])
+    fails(B.EINVAL, [req([ch(16)], 0)])
+    fails(B.EINVAL, [req([ch(16)], 4097)])
+    fails(B.EINVAL, [(([ch(16)]), P + 2, P, None, 1)])              # q misaligned
+    fails(B.EINVAL, [(([ch(16)]), P, None, None, 1)])               # no out
+    fails(B.EINVAL, [req([(P + 8, 16, B.PREC_INT4, 64, B.PART_KV)], 1)])
+    fails(B.EFORMAT, [req([ch(16, part=B.PART_K)], 1)])
+    fails(B.EFORMAT, [req([ch(16, g=48)], 1)])
+    fails(B.EFORMAT, [req([ch(16, p=9)], 1)])
+    ctx.destroy()
+    other = _attend_ctx(D=64)
+    with pytest.raises(B.HaRagError) as e:
+        other.attend_workspace_bytes([req([ch(16, g=64)], 1)], 2)
+    assert e.value.code == B.EFORMAT
+    other.destroy()
