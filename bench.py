@@ -329,6 +329,110 @@ def run_hbm(args, B, wl, torch, name):
     return res, (shape, T, g, mix)
 
 
+def run_attend(args, B, wl, torch):
+    """Attention of a batch of requests' query tokens over their packed chunks, layer by
+    layer, without building the BF16 cache: the 8B shape and request mix of the headline
+    workload, `--batch` requests per step, `--n-q` query tokens each, 32 query heads.  One
+    step = all 32 layers (one call per layer).  Bytes counted: the packed K and V bytes read
+    plus the query and result vectors."""
+    import numpy as np
+    shape, T, g, n_qh = (32, 8, 128), args.chunk_tokens, 128, 32
+    L, H, D = shape
+    mix = [16] * 2 + [8] * 3 + [4] * 5
+    R, n_q, n_sets = args.batch, args.n_q, 2
+    counts = {prec_of(B, b): mix.count(b) * R * n_sets for b in sorted(set(mix), key=str)}
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g)
+    t0 = time.time()
+    ids = build_hbm_pool(B, wl, torch, ctx, shape, T, g, counts, seed0=args.seed * 1_000_003)
+    pool_bytes = sum(ctx.chunk_bytes(p, T) * n for p, n in counts.items())
+    log(f"pool: {counts} chunks, {pool_bytes / 2**30:.1f} GiB packed, built in {time.time() - t0:.1f} s")
+    rng = np.random.Generator(np.random.PCG64(args.seed))
+    gq = torch.Generator(device="cuda")
+    gq.manual_seed(args.seed + 99)
+    q = torch.randn((R, n_q, n_qh, D), generator=gq, device="cuda").to(torch.bfloat16)
+    out = torch.empty((R, n_q, n_qh, D), dtype=torch.float32, device="cuda")
+    lse = torch.empty((R, n_q, n_qh), dtype=torch.float32, device="cuda")
+    cursor = {p: 0 for p in counts}
+    sets = []
+    for _ in range(n_sets):
+        reqs = []
+        for r in range(R):
+            chunks = []
+            for b in mix:
+                p = prec_of(B, b)
+                cid = ids[p][cursor[p]]
+                cursor[p] += 1
+                info = ctx.pool_query(cid)
+                chunks.append((info.hbm_ptr, T, p, g if p in (B.PREC_INT8, B.PREC_INT4) else 0))
+            chunks = [chunks[i] for i in rng.permutation(len(mix))]
+            reqs.append((chunks, q[r], out[r], lse[r], n_q))
+        sets.append(ctx.attend_lists(reqs))
+    ws_bytes = ctx.attend_workspace_bytes(sets[0], n_qh)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    scale = D ** -0.5
+    packed_bytes = sum(ctx.chunk_bytes(prec_of(B, b), T) for b in mix) * R
+    io_bytes = L * (q.numel() * 2 + out.numel() * 4 + lse.numel() * 4)
+    step_bytes = packed_bytes + io_bytes
+    step_tokens = R * len(mix) * T
+    stream = torch.cuda.Stream()
+
+    def step(k):
+        for layer in range(L):
+            ctx.attend_packed(sets[k % n_sets], layer, n_qh, scale, ws, ws_bytes, stream=stream)
+
+    with torch.cuda.stream(stream):
+        for k in range(args.warmup):
+            step(k)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for k in range(args.warmup, args.warmup + args.steps):
+            step(k)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = wall * 1e3 / args.steps
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    # an event pair around every call (one layer: the partial-attention launches and the merge)
+    n_evt = min(args.steps, 4) * L
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_evt)]
+    with torch.cuda.stream(stream):
+        for k in range(n_evt):
+            evs[k][0].record(stream)
+            ctx.attend_packed(sets[(k // L) % n_sets], k % L, n_qh, scale, ws, ws_bytes, stream=stream)
+            evs[k][1].record(stream)
+        torch.cuda.synchronize()
+    per = sorted(a.elapsed_time(b) for a, b in evs)
+    call_ms = ev_ms / (args.steps * L)
+    achieved = step_bytes / L / (call_ms * 1e-3) / 1e9
+    ctx.destroy()
+    desc = (f"attention over packed chunks, Llama-3-8B KV (32 layers, 8 KV heads, 32 query heads, head_dim 128): "
+            f"{R} requests x 10 chunks x {T} tokens (2x16-bit + 3xint8 + 5xint4, group 128), "
+            f"{n_q} query token(s) per request, all 32 layers per step, no BF16 cache built")
+    res = {
+        "metric": "kv_load_gbps", "value": value, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": desc, "pool_gib": round(pool_bytes / 2**30, 1), "batch": R, "n_q": n_q,
+                   "tokens_per_step": step_tokens, "bytes_per_step": step_bytes,
+                   "workspace_mib": round(ws_bytes / 2**20, 1)},
+        "kv_tokens_per_s": step_tokens / (ms_per_step * 1e-3),
+        "hbm_fraction_whole_path": value / HBM_PEAK_GBPS,
+        # what the same step costs through the cache: write the BF16 cache once per request
+        # (2 B/element) and let an attention kernel read it back every step
+        "bf16_cache_bytes_per_step": step_tokens * L * 2 * H * D * 2,
+        "roofline": {"bound": "hbm", "kernel": "k4_attend_partial (+ k5_attend_merge), one call = one layer",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": args.traffic_bytes,
+                     "kernel_ms": call_ms, "kernel_ms_median": per[len(per) // 2], "kernel_ms_best": per[0],
+                     "algorithmic_bytes_per_launch": step_bytes // L},
+    }
+    return res, (shape, T, g, mix)
+
+
 def run_units(args, B, wl, torch):
     """The 8B shape with every document stored as a key chunk and a value chunk of their own
     (the 2n units of Algorithm 1), keys one step hotter than values: per request ten
@@ -681,7 +785,10 @@ def main():
     ap.add_argument("--paged", type=int, default=0, metavar="P",
                     help="hbm8b / llama70b: write into a page-major paged cache of P-token pages "
                          "(random page table) instead of the contiguous cache")
-    ap.add_argument("--workload", default="hbm8b", choices=["hbm8b", "llama70b", "cold8b", "zipf", "tiers", "units8b"])
+    ap.add_argument("--workload", default="hbm8b", choices=["hbm8b", "llama70b", "cold8b", "zipf", "tiers", "units8b", "attend8b"])
+    ap.add_argument("--batch", type=int, default=32, help="attend8b: requests per step")
+    ap.add_argument("--n-q", type=int, default=1, help="attend8b: query tokens per request")
+    ap.add_argument("--chunk-tokens", type=int, default=512, help="attend8b: tokens per chunk")
     ap.add_argument("--mix", default="", help="hbm8b: tags of one request, e.g. 8,e4m3,e5m2,4")
     ap.add_argument("--pool-chunks", type=int, default=0, help="chunks in the HBM pool (0 = default)")
     ap.add_argument("--out-buffers", type=int, default=4)
@@ -737,6 +844,10 @@ def main():
         shape, T, g, mix = (32, 8, 128), 512, 128, [16] * 2 + [8] * 3 + [4] * 5
     elif args.workload == "units8b":
         res, (shape, T, g, mix) = run_units(args, B, wl, torch)
+    elif args.workload == "attend8b":
+        if args.steps == 400:
+            args.steps, args.warmup = 20, 2
+        res, (shape, T, g, mix) = run_attend(args, B, wl, torch)
     else:
         if args.pool_chunks == 0:
             args.pool_chunks = 2000 if args.workload == "hbm8b" else 400

@@ -328,8 +328,12 @@ class Context:
                                                  _stream(stream)), "ha_rag_load_packed_paged")
 
     @staticmethod
-    def _attend_lists(requests):
-        """requests: list of (chunks, q, out, lse, n_q) with chunks as in load_packed."""
+    def attend_lists(requests):
+        """requests: list of (chunks, q, out, lse, n_q) with chunks as in load_packed.  Returns
+        the marshalled lists, which attend_packed accepts in place of `requests` (a caller that
+        repeats a call layer after layer marshals once)."""
+        if isinstance(requests, tuple) and len(requests) == 3 and isinstance(requests[2], int):
+            return requests
         n_chunks = sum(len(r[0]) for r in requests)
         arr = (PackedChunk * max(n_chunks, 1))()
         reqs = (AttendRequest * max(len(requests), 1))()
@@ -340,21 +344,21 @@ class Context:
                 arr[k] = PackedChunk(_addr(p), t, prec, g, ch[4] if len(ch) > 4 else PART_KV)
                 k += 1
             reqs[i] = AttendRequest(_addr(q), _addr(out), _addr(lse), n_q, len(chunks))
-        return arr, reqs
+        return arr, reqs, len(requests)
 
     def attend_workspace_bytes(self, requests, n_q_heads):
-        arr, reqs = self._attend_lists(requests)
+        arr, reqs, n_reqs = self.attend_lists(requests)
         n = C.c_size_t(0)
-        self._chk(lib().ha_rag_attend_workspace_bytes(self._h, arr, reqs, len(requests), n_q_heads,
+        self._chk(lib().ha_rag_attend_workspace_bytes(self._h, arr, reqs, n_reqs, n_q_heads,
                                                       C.byref(n)), "ha_rag_attend_workspace_bytes")
         return n.value
 
     def attend_packed(self, requests, layer, n_q_heads, sm_scale, workspace, workspace_bytes=None,
                       stream=None):
-        arr, reqs = self._attend_lists(requests)
+        arr, reqs, n_reqs = self.attend_lists(requests)
         if workspace_bytes is None:
             workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-        self._chk(lib().ha_rag_attend_packed(self._h, arr, reqs, len(requests), layer, n_q_heads,
+        self._chk(lib().ha_rag_attend_packed(self._h, arr, reqs, n_reqs, layer, n_q_heads,
                                              sm_scale, _addr(workspace), workspace_bytes,
                                              _stream(stream)), "ha_rag_attend_packed")
 

@@ -1,5 +1,5 @@
 // Host side of attention over packed chunks: argument checks, the workspace layout, and the
-// launches (one partial-attention launch per 64 chunks, one merge launch per 64 requests).
+// launches (one partial-attention launch per 512 chunks, one merge launch per 64 requests).
 #include "ha_rag_internal.h"
 
 using namespace ha_rag_host;
@@ -9,14 +9,14 @@ namespace {
 struct Plan {               // one request
     uint32_t first = 0;     // its first chunk in the list
     uint32_t n_live = 0;    // chunks with tokens
-    uint32_t n_split = 1, n_mt = 1;
+    uint32_t n_split = 1, n_mt = 1, max_blocks = 0;
     uint64_t part_floats = 0;  // offset of its records in the workspace
 };
 
 // Checks everything and lays the workspace out.  *floats = workspace size in binary32 words.
 int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_attend_request *reqs,
                 uint32_t n_reqs, uint32_t n_q_heads, std::vector<Plan> *plans, uint64_t *floats,
-                bool need_buffers)
+                uint32_t *split_blocks, bool need_buffers)
 {
     if (!c || !reqs || n_reqs == 0 || n_reqs > HA_RAG_MAX_ATTEND_REQUESTS) return HA_RAG_EINVAL;
     if (c->cfg.head_dim != kAttendHeadDim) return HA_RAG_EFORMAT;
@@ -47,11 +47,24 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
             ++pl.n_live;
             if (pc.n_tokens > max_tokens) max_tokens = pc.n_tokens;
         }
-        const uint32_t nblk = (max_tokens + 15u) / 16u;
-        pl.n_split = nblk ? (nblk + kAttendSplitBlocks - 1u) / kAttendSplitBlocks : 1u;
+        pl.max_blocks = (max_tokens + 15u) / 16u;
+        n_chunks += rq.n_chunks;
+    }
+    // Tokens per workgroup: as many as possible (every workgroup pays for fetching the queries
+    // and for writing a record), but fine enough that the launch fills the chip a few times
+    // over, since workgroups of one size finish in rounds.
+    uint32_t sb = kAttendMaxSplitBlocks;
+    for (;; sb >>= 1) {
+        uint64_t groups = 0;
+        for (const Plan &pl : *plans)
+            groups += (uint64_t)pl.n_live * H * ((pl.max_blocks + sb - 1u) / sb) * ((pl.n_mt + 3u) / 4u);
+        if (groups >= kAttendTargetGroups || sb == kAttendMinSplitBlocks) break;
+    }
+    *split_blocks = sb;
+    for (Plan &pl : *plans) {
+        pl.n_split = pl.max_blocks ? (pl.max_blocks + sb - 1u) / sb : 1u;
         pl.part_floats = total;
         total += (uint64_t)pl.n_live * H * pl.n_split * pl.n_mt * kAttendRecFloats;
-        n_chunks += rq.n_chunks;
     }
     if (total * 4ull > (1ull << 40)) return HA_RAG_EINVAL;
     *floats = total;
@@ -69,7 +82,8 @@ int ha_rag_attend_workspace_bytes(ha_rag_ctx *c, const ha_rag_packed_chunk *chun
     if (!bytes) return HA_RAG_EINVAL;
     std::vector<Plan> plans;
     uint64_t floats = 0;
-    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, &plans, &floats, false);
+    uint32_t split_blocks = 0;
+    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, &plans, &floats, &split_blocks, false);
     if (rc) return rc;
     *bytes = (size_t)(floats * 4ull);
     return HA_RAG_OK;
@@ -82,7 +96,8 @@ int ha_rag_attend_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
 {
     std::vector<Plan> plans;
     uint64_t floats = 0;
-    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, &plans, &floats, true);
+    uint32_t split_blocks = 0;
+    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, &plans, &floats, &split_blocks, true);
     if (rc) return rc;
     if (layer >= c->cfg.n_layers || !(sm_scale > 0.0f) || !(sm_scale < 1e30f)) return HA_RAG_EINVAL;
     if (floats && (!workspace || ((uintptr_t)workspace & 15u))) return HA_RAG_EINVAL;
@@ -98,6 +113,7 @@ int ha_rag_attend_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
     kp.n_q_heads = n_q_heads;
     kp.layer = layer;
     kp.scale_log2 = sm_scale * 1.44269504088896341f;
+    kp.split_blocks = split_blocks;
     for (uint32_t r = 0; r < n_reqs; ++r) {
         const ha_rag_attend_request &rq = reqs[r];
         const Plan &pl = plans[r];
@@ -111,11 +127,11 @@ int ha_rag_attend_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
             d.q = static_cast<const uint16_t *>(rq.q);
             d.part = ws + pl.part_floats + live * per_chunk;
             d.n_tokens = pc.n_tokens;
-            d.fmt = pc.prec | ((has_meta(pc.prec) ? log2u(pc.group) : 0u) << 8);
+            d.info = pc.prec | ((has_meta(pc.prec) ? log2u(pc.group) : 0u) << 4);
             d.n_q = rq.n_q;
             d.n_split = pl.n_split;
             ++live;
-            if (kp.n_chunks == kMaxLaunchChunks) {
+            if (kp.n_chunks == kAttendLaunchChunks) {
                 HIPCHK(c, launch_k4(kp, st));
                 kp.n_chunks = 0;
             }

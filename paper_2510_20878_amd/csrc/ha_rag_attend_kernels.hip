@@ -2,9 +2,10 @@
 // building the BF16 cache first (the prefill of Sec. 2.1 consumes the concatenated chunk KV;
 // here the consumer reads the compressed chunks of Sec. 2.2 itself).
 //
-//  k4_attend_partial   one wave per (chunk, KV head, token split, group of query rows):
-//      decodes K and V blocks to BF16 in registers (the values a load would write), scores
-//      them with MFMA, keeps a running softmax, writes an unnormalised partial result
+//  k4_attend_partial   one workgroup of four waves per (chunk, KV head, token split, group of
+//      query rows); the waves take the layout blocks in turn: each decodes K and V blocks to
+//      BF16 in registers (the values a load would write), scores them with MFMA and keeps a
+//      running softmax; the four are summed in LDS into one unnormalised partial result
 //  k5_attend_merge     one workgroup per (query token, query head): merges the partial
 //      results of the request's chunks and splits into out and the log-sum-exp
 //
@@ -35,12 +36,50 @@ struct Fmt {
     static constexpr bool kMeta = PREC == kInt4 || PREC == kInt8;
 };
 
+// byte K of a dword -> float in one instruction.  Written as asm because the compiler
+// otherwise folds the nibble mask into a bit-field extract per code and then converts byte 0
+// (two instructions per code instead of one).
+template <int K>
+__device__ __forceinline__ float ubyte_f(uint32_t w)
+{
+    float r;
+    if (K == 0) asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(r) : "v"(w));
+    else if (K == 1) asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(r) : "v"(w));
+    else if (K == 2) asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(r) : "v"(w));
+    else asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(r) : "v"(w));
+    return r;
+}
+
+// the same values as dequant_octet4 / dequant_octet8: bf16_rne(fma(code, scale, zero))
+__device__ __forceinline__ u32x4 attend_octet4(uint32_t c, uint32_t m)
+{
+    const float s = h2f(m & 0xFFFFu), z = h2f(m >> 16);
+    const uint32_t ev = c & 0x0F0F0F0Fu, od = (c >> 4) & 0x0F0F0F0Fu;
+    u32x4 r;
+    r.x = pack_bf16(__builtin_fmaf(ubyte_f<0>(ev), s, z), __builtin_fmaf(ubyte_f<0>(od), s, z));
+    r.y = pack_bf16(__builtin_fmaf(ubyte_f<1>(ev), s, z), __builtin_fmaf(ubyte_f<1>(od), s, z));
+    r.z = pack_bf16(__builtin_fmaf(ubyte_f<2>(ev), s, z), __builtin_fmaf(ubyte_f<2>(od), s, z));
+    r.w = pack_bf16(__builtin_fmaf(ubyte_f<3>(ev), s, z), __builtin_fmaf(ubyte_f<3>(od), s, z));
+    return r;
+}
+
+__device__ __forceinline__ u32x4 attend_octet8(uint32_t c0, uint32_t c1, uint32_t m)
+{
+    const float s = h2f(m & 0xFFFFu), z = h2f(m >> 16);
+    u32x4 r;
+    r.x = pack_bf16(__builtin_fmaf(ubyte_f<0>(c0), s, z), __builtin_fmaf(ubyte_f<1>(c0), s, z));
+    r.y = pack_bf16(__builtin_fmaf(ubyte_f<2>(c0), s, z), __builtin_fmaf(ubyte_f<3>(c0), s, z));
+    r.z = pack_bf16(__builtin_fmaf(ubyte_f<0>(c1), s, z), __builtin_fmaf(ubyte_f<1>(c1), s, z));
+    r.w = pack_bf16(__builtin_fmaf(ubyte_f<2>(c1), s, z), __builtin_fmaf(ubyte_f<3>(c1), s, z));
+    return r;
+}
+
 // the raw codes of one octet (x: int4; x, y: 8-bit formats; all four: 16-bit) -> 8 BF16
 template <uint32_t PREC>
 __device__ __forceinline__ u32x4 decode_octet(u32x4 raw, uint32_t meta, int base, int top)
 {
-    if (PREC == kInt4) return dequant_octet4(raw.x, meta);
-    if (PREC == kInt8) return dequant_octet8(raw.x, raw.y, meta);
+    if (PREC == kInt4) return attend_octet4(raw.x, meta);
+    if (PREC == kInt8) return attend_octet8(raw.x, raw.y, meta);
     if (PREC == kE4M3) return decode_octet_fp8<false>(raw.x, raw.y);
     if (PREC == kE5M2) return decode_octet_fp8<true>(raw.x, raw.y);
     if (PREC == kGSE8) return decode_octet_gse8(raw.x, raw.y, base, top);
@@ -63,18 +102,63 @@ __device__ __forceinline__ u32x4 plane_raw(const u32x4 *w, int j)
 
 __device__ __forceinline__ float neg_inf() { return -__builtin_huge_valf(); }
 
+// orders the LDS accesses of one wave: what its lanes wrote before is visible to all its
+// lanes after (LDS instructions of a wave execute in issue order; this keeps the compiler
+// from moving them and waits for the writes)
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// the launch-wide scalars a workgroup needs, read from the argument buffer once
+struct AttendHdr {
+    uint32_t n_kv_heads, n_q_heads, layer, split_blocks;
+    float scale_log2;
+};
+
+// keeps a value in a scalar register from here on: everything pinned at the top of the kernel
+// is fetched from the argument buffer by loads issued together, not one by one where the
+// values are first used
+__device__ __forceinline__ void pin(uint32_t &v) { asm volatile("" : "+s"(v)); }
+__device__ __forceinline__ void pin(float &v) { asm volatile("" : "+s"(v)); }
+template <class T>
+__device__ __forceinline__ void pin(T *&v)
+{
+    uint64_t a = reinterpret_cast<uint64_t>(v);
+    asm volatile("" : "+s"(a));
+    v = reinterpret_cast<T *>(a);
+}
+
+template <uint32_t PREC>
+struct BlockRegs {  // what a lane loads for one block
+    u32x4 kw[Fmt<PREC>::kWords], vw[Fmt<PREC>::kWords];
+    u32x4 vm;
+    uint32_t km;
+};
+
+template <int MTW>
+struct AttendLds {
+    static constexpr uint32_t kExchange = kAttendWaves * 4096u;  // one 4 KiB region per wave
+    static constexpr uint32_t kCombine = kAttendWaves * 16u * 128u * 4u;  // one output tile per wave, aliases it
+    static constexpr uint32_t kBytes = kExchange > kCombine ? kExchange : kCombine;
+};
+
 template <uint32_t PREC, int MTW>
-__device__ __forceinline__ void attend_unit(const K4Params &p, const K4Chunk &c, uint32_t h,
-                                            uint32_t s, uint32_t mtg, uint8_t *lds)
+__device__ __forceinline__ void attend_unit(const AttendHdr &p, const K4Chunk &c,
+                                            uint32_t h, uint32_t s, uint32_t mtg, uint8_t *lds_all,
+                                            float (*sm)[MTW * 16], float (*sl)[MTW * 16])
 {
     typedef Fmt<PREC> F;
     const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t c_ = lane >> 4, n_ = lane & 15u;  // MFMA coordinates: lane group, lane column
     const uint32_t a_ = n_ >> 2, x_ = n_ & 3u;
     const uint32_t H = p.n_kv_heads, G = p.n_q_heads / H, M = c.n_q * G;
     const uint32_t n_mt = (M + 15u) >> 4;
     const uint32_t T = c.n_tokens, nblk = (T + 15u) >> 4;
-    const uint32_t gsh = (c.fmt >> 8) & 0xFFu;
+    const uint32_t gsh = (c.info >> 4) & 0xFu;
     const uint32_t meta_blk = F::kMeta ? 8192u >> gsh : 0u;
     const uint64_t tile_bytes = (uint64_t)nblk * (F::kPayload + meta_blk) + (PREC == kGSE8 ? 16u : 0u);
     const uint8_t *kt = c.src + (uint64_t)((p.layer * 2u) * H + h) * tile_bytes;
@@ -83,13 +167,12 @@ __device__ __forceinline__ void attend_unit(const K4Params &p, const K4Chunk &c,
     const uint8_t *vmeta = vt + (uint64_t)nblk * F::kPayload;
     float *rec0 = c.part + (uint64_t)((h * c.n_split + s) * n_mt) * kAttendRecFloats;
 
-    const uint32_t b0 = s * kAttendSplitBlocks;
-    const uint32_t b1 = b0 + kAttendSplitBlocks < nblk ? b0 + kAttendSplitBlocks : nblk;
-    if (b0 >= b1) {  // nothing of this chunk in this split: an empty record (l = 0)
-#pragma unroll
-        for (int mt = 0; mt < MTW; ++mt) {
-            const uint32_t mtile = mtg * MTW + mt;
-            if (mtile < n_mt && c_ == 0) {
+    const uint32_t b0 = s * p.split_blocks;
+    const uint32_t b1 = b0 + p.split_blocks < nblk ? b0 + p.split_blocks : nblk;
+    if (b0 >= b1) {  // nothing of this chunk in this split: empty records (l = 0)
+        if (threadIdx.x < MTW * 16u) {
+            const uint32_t mtile = mtg * MTW + (threadIdx.x >> 4);
+            if (mtile < n_mt) {
                 float *rec = rec0 + (uint64_t)mtile * kAttendRecFloats;
                 rec[2048 + n_] = neg_inf();
                 rec[2048 + 16 + n_] = 0.0f;
@@ -144,27 +227,32 @@ __device__ __forceinline__ void attend_unit(const K4Params &p, const K4Chunk &c,
         const uint32_t grp = ((4u * x_ + a_) * 128u + 32u * c_) >> gsh;
         k_entry = (grp & ((512u >> gsh) - 1u)) * 4u + (grp >> (9u - gsh));
     }
+    uint8_t *lds = lds_all + wave * 4096u;
     u32x4 *lds_w = reinterpret_cast<u32x4 *>(lds);
 
-    for (uint32_t b = b0; b < b1; ++b) {
-        // ---- loads of this block: K words, V words, metas
-        u32x4 kw[F::kWords], vw[F::kWords];
+    auto load_block = [&](uint32_t b, BlockRegs<PREC> &r) {
 #pragma unroll
         for (uint32_t a = 0; a < F::kWords; ++a) {
-            kw[a] = ld16(kt + (uint64_t)b * F::kPayload + a * 1024u + lane * 16u);
-            vw[a] = ld16(vt + (uint64_t)b * F::kPayload + a * 1024u + lane * 16u);
+            r.kw[a] = ld16(kt + (uint64_t)b * F::kPayload + a * 1024u + lane * 16u);
+            r.vw[a] = ld16(vt + (uint64_t)b * F::kPayload + a * 1024u + lane * 16u);
         }
-        uint32_t km = 0;
-        u32x4 vm = {0u, 0u, 0u, 0u};
+        r.km = 0;
+        r.vm = u32x4{0u, 0u, 0u, 0u};
         if (F::kMeta) {
-            km = *reinterpret_cast<const uint32_t *>(kmeta + (uint64_t)b * meta_blk + 4u * k_entry);
-            vm = ld16(vmeta + (uint64_t)b * meta_blk + ((lane * 8u) >> gsh) * 16u);
+            r.km = *reinterpret_cast<const uint32_t *>(kmeta + (uint64_t)b * meta_blk + 4u * k_entry);
+            r.vm = ld16(vmeta + (uint64_t)b * meta_blk + ((lane * 8u) >> gsh) * 16u);
         }
+    };
+
+    // the waves of the workgroup take the blocks of the split in turn; each wave fetches its
+    // next block before it works on the current one
+    auto process = [&](uint32_t b, const BlockRegs<PREC> &cur) {
+        const bool ragged = b * 16u + 16u > T;  // only the chunk's last block can be
 
         // ---- K: exchange through LDS, decode, S^T = K Q^T
 #pragma unroll
-        for (uint32_t a = 0; a < F::kWords; ++a) lds_w[a * 64u + lane] = kw[a];
-        __syncthreads();
+        for (uint32_t a = 0; a < F::kWords; ++a) lds_w[a * 64u + lane] = cur.kw[a];
+        wave_lds_sync();
         bf16x8 ka[4];
 #pragma unroll
         for (int y = 0; y < 4; ++y) {
@@ -179,9 +267,9 @@ __device__ __forceinline__ void attend_unit(const K4Params &p, const K4Chunk &c,
                 raw.x = t.x;
                 raw.y = t.y;
             }
-            ka[y] = __builtin_bit_cast(bf16x8, decode_octet<PREC>(raw, km, kbase, ktop));
+            ka[y] = __builtin_bit_cast(bf16x8, decode_octet<PREC>(raw, cur.km, kbase, ktop));
         }
-        __syncthreads();
+        wave_lds_sync();
 
         s16x4 pa[MTW];
 #pragma unroll
@@ -193,8 +281,12 @@ __device__ __forceinline__ void attend_unit(const K4Params &p, const K4Chunk &c,
             // S[jj] = score of token 4 jj + c_ of the block against query row n_
             float sc[4];
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj)
-                sc[jj] = (b * 16u + 4u * jj + c_ < T) ? S[jj] * p.scale_log2 : neg_inf();
+            for (int jj = 0; jj < 4; ++jj) sc[jj] = S[jj] * p.scale_log2;
+            if (ragged) {
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+                    if (b * 16u + 4u * jj + c_ >= T) sc[jj] = neg_inf();
+            }
             float mx = __builtin_fmaxf(__builtin_fmaxf(sc[0], sc[1]), __builtin_fmaxf(sc[2], sc[3]));
             mx = __builtin_fmaxf(mx, __shfl_xor(mx, 16));
             mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));
@@ -221,9 +313,12 @@ __device__ __forceinline__ void attend_unit(const K4Params &p, const K4Chunk &c,
         // ---- V: decode the lane's four planes, regroup by position, O += P V
         u32x4 vr[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            vr[j] = decode_octet<PREC>(plane_raw<PREC>(vw, j), vm[j], vbase, vtop);
-            if (b * 16u + 4u * j + c_ >= T) vr[j] = u32x4{0u, 0u, 0u, 0u};  // rows past the chunk's end
+        for (int j = 0; j < 4; ++j)
+            vr[j] = decode_octet<PREC>(plane_raw<PREC>(cur.vw, j), cur.vm[j], vbase, vtop);
+        if (ragged) {  // rows past the chunk's end
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (b * 16u + 4u * j + c_ >= T) vr[j] = u32x4{0u, 0u, 0u, 0u};
         }
 #pragma unroll
         for (int pp = 0; pp < 8; ++pp) {
@@ -235,92 +330,161 @@ __device__ __forceinline__ void attend_unit(const K4Params &p, const K4Chunk &c,
             for (int mt = 0; mt < MTW; ++mt)
                 O[mt][pp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa[mt], vb, O[mt][pp], 0, 0, 0);
         }
+    };
+    // A ring of kStages register sets: while a block is worked on, the loads of the next
+    // kStages - 1 blocks of this wave are in flight.  What is in flight per compute unit has
+    // to cover the memory latency at full bandwidth, and a block of a 4-bit chunk is a quarter
+    // of the bytes of a 16-bit one, so narrow formats get a deeper ring.  The loop is unrolled
+    // over the ring so that no block is copied from one set to another.
+    constexpr int kStages = MTW > 1 ? 2 : PREC == kInt4 ? 4 : PREC == kP16 ? 2 : 3;
+    BlockRegs<PREC> ring[kStages];
+    uint32_t b = b0 + wave;
+#pragma unroll
+    for (int i = 0; i < kStages - 1; ++i)
+        if (b + i * kAttendWaves < b1) load_block(b + i * kAttendWaves, ring[i]);
+    if (b < b1) {
+        for (;;) {
+#pragma unroll
+            for (int i = 0; i < kStages; ++i) {
+                const uint32_t ahead = b + (kStages - 1) * kAttendWaves;
+                if (ahead < b1) load_block(ahead, ring[(i + kStages - 1) % kStages]);
+                process(b, ring[i]);
+                b += kAttendWaves;
+                if (b >= b1) goto blocks_done;
+            }
+        }
     }
+blocks_done:
 
-    // ---- the record: O[row 4 c_ + jj][dim 8 n_ + pp], m and l per row
+    // ---- the four waves' results: each wave leaves its rows, maxima and sums in LDS; then all
+    // threads bring them to one maximum per row, add them up and write the record
 #pragma unroll
     for (int mt = 0; mt < MTW; ++mt) {
-        const uint32_t mtile = mtg * MTW + mt;
         float l_tot = l_run[mt];
         l_tot += __shfl_xor(l_tot, 16);
         l_tot += __shfl_xor(l_tot, 32);
+        if (c_ == 0) {
+            sm[wave][mt * 16 + n_] = m_run[mt];
+            sl[wave][mt * 16 + n_] = l_tot;
+        }
+    }
+    float *acc = reinterpret_cast<float *>(lds_all);  // [wave][16 rows][128]
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt) {
+        __syncthreads();  // the exchange areas (first tile) or the previous tile's sums are done with
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            f32x4 *dst = reinterpret_cast<f32x4 *>(acc + wave * 2048u + (4u * c_ + jj) * 128u + 8u * n_);
+            dst[0] = f32x4{O[mt][0][jj], O[mt][1][jj], O[mt][2][jj], O[mt][3][jj]};
+            dst[1] = f32x4{O[mt][4][jj], O[mt][5][jj], O[mt][6][jj], O[mt][7][jj]};
+        }
+        __syncthreads();
+        const uint32_t mtile = mtg * MTW + mt;
         if (mtile >= n_mt) continue;
         float *rec = rec0 + (uint64_t)mtile * kAttendRecFloats;
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            float *dst = rec + (4u * c_ + jj) * 128u + 8u * n_;
-            *reinterpret_cast<f32x4 *>(dst) = f32x4{O[mt][0][jj], O[mt][1][jj], O[mt][2][jj], O[mt][3][jj]};
-            *reinterpret_cast<f32x4 *>(dst + 4) = f32x4{O[mt][4][jj], O[mt][5][jj], O[mt][6][jj], O[mt][7][jj]};
+        for (uint32_t k = 0; k < 512u / (64u * kAttendWaves); ++k) {  // 512 16-byte words of output per tile
+            const uint32_t i = threadIdx.x + 64u * kAttendWaves * k, row = mt * 16u + (i >> 5);
+            float m_all = sm[0][row];
+#pragma unroll
+            for (uint32_t w = 1; w < kAttendWaves; ++w) m_all = __builtin_fmaxf(m_all, sm[w][row]);
+            f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (uint32_t w = 0; w < kAttendWaves; ++w) {
+                // a wave that had no block has m = -inf and l = 0: nothing to add
+                const float f = sl[w][row] > 0.0f ? __builtin_amdgcn_exp2f(sm[w][row] - m_all) : 0.0f;
+                sum += reinterpret_cast<const f32x4 *>(acc + w * 2048u)[i] * f;
+            }
+            reinterpret_cast<f32x4 *>(rec)[i] = sum;
         }
-        if (c_ == 0) {
-            rec[2048 + n_] = m_run[mt];
-            rec[2048 + 16 + n_] = l_tot;
+        if (threadIdx.x < 16u) {
+            const uint32_t row = mt * 16u + threadIdx.x;
+            float m_all = sm[0][row];
+#pragma unroll
+            for (uint32_t w = 1; w < kAttendWaves; ++w) m_all = __builtin_fmaxf(m_all, sm[w][row]);
+            float l_all = 0.0f;
+#pragma unroll
+            for (uint32_t w = 0; w < kAttendWaves; ++w)
+                if (sl[w][row] > 0.0f) l_all += sl[w][row] * __builtin_amdgcn_exp2f(sm[w][row] - m_all);
+            rec[2048 + threadIdx.x] = m_all;
+            rec[2048 + 16 + threadIdx.x] = l_all;
         }
     }
 }
 
+// (the second bound is waves per SIMD: two keep the accumulators of the one-tile variant in
+// ordinary vector registers, with no copies to and from the accumulation registers)
 template <int MTW>
-__global__ void __launch_bounds__(64) k4_attend_partial(const K4Params p)
+__global__ void __launch_bounds__(64 * kAttendWaves, MTW == 1 ? 2 : 1) k4_attend_partial(const K4Params p)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[4096];
-    const uint32_t unit = blockIdx.x;
-    if (unit >= p.total_units) return;
-    uint32_t lo = 0, hi = p.n_chunks;  // unit_start[lo] <= unit < unit_start[hi]
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (unit >= p.unit_start[mid]) lo = mid;
-        else hi = mid;
-    }
-    const K4Chunk &c = p.c[lo];
-    const uint32_t u = unit - p.unit_start[lo];
-    const uint32_t G = p.n_q_heads / p.n_kv_heads;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[AttendLds<MTW>::kBytes];
+    __shared__ float sm[kAttendWaves][MTW * 16], sl[kAttendWaves][MTW * 16];
+    // the whole descriptor and the header at once, before anything depends on a part of them
+    K4Chunk c = p.c[blockIdx.y];
+    AttendHdr hdr = {p.n_kv_heads, p.n_q_heads, p.layer, p.split_blocks, p.scale_log2};
+    pin(c.src);
+    pin(c.q);
+    pin(c.part);
+    pin(c.n_tokens);
+    pin(c.info);
+    pin(c.n_q);
+    pin(c.n_split);
+    pin(hdr.n_kv_heads);
+    pin(hdr.n_q_heads);
+    pin(hdr.layer);
+    pin(hdr.split_blocks);
+    pin(hdr.scale_log2);
+    const uint32_t G = hdr.n_q_heads / hdr.n_kv_heads;
     const uint32_t n_mt = (c.n_q * G + 15u) >> 4;
     const uint32_t n_mtg = (n_mt + MTW - 1u) / MTW;
+    const uint32_t u = blockIdx.x;
+    if (u >= hdr.n_kv_heads * c.n_split * n_mtg) return;  // the grid is as wide as the widest chunk
     const uint32_t mtg = u % n_mtg;
     const uint32_t hs = u / n_mtg;
     const uint32_t s = hs % c.n_split, h = hs / c.n_split;
-    switch (c.fmt & 0xFFu) {
-    case kP16: attend_unit<kP16, MTW>(p, c, h, s, mtg, lds); break;
-    case kInt8: attend_unit<kInt8, MTW>(p, c, h, s, mtg, lds); break;
-    case kInt4: attend_unit<kInt4, MTW>(p, c, h, s, mtg, lds); break;
-    case kE4M3: attend_unit<kE4M3, MTW>(p, c, h, s, mtg, lds); break;
-    case kE5M2: attend_unit<kE5M2, MTW>(p, c, h, s, mtg, lds); break;
-    default: attend_unit<kGSE8, MTW>(p, c, h, s, mtg, lds); break;
+    switch (c.info & 0xFu) {
+    case kP16: attend_unit<kP16, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    case kInt8: attend_unit<kInt8, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    case kInt4: attend_unit<kInt4, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    case kE4M3: attend_unit<kE4M3, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    case kE5M2: attend_unit<kE5M2, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    default: attend_unit<kGSE8, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;
     }
 }
 
 hipError_t launch_k4(K4Params &p, hipStream_t stream)
 {
     if (p.n_chunks == 0) return hipSuccess;
-    if (p.n_chunks > kMaxLaunchChunks || p.n_kv_heads == 0 || p.n_q_heads % p.n_kv_heads)
+    if (p.n_chunks > kAttendLaunchChunks || p.n_kv_heads == 0 || p.n_q_heads % p.n_kv_heads ||
+        p.split_blocks < kAttendMinSplitBlocks || p.split_blocks > kAttendMaxSplitBlocks ||
+        (p.split_blocks & (p.split_blocks - 1u)))
         return hipErrorInvalidValue;
     const uint32_t G = p.n_q_heads / p.n_kv_heads;
     uint32_t max_mt = 1;
     for (uint32_t i = 0; i < p.n_chunks; ++i) {
         const K4Chunk &c = p.c[i];
-        const uint32_t prec = c.fmt & 0xFFu, gsh = (c.fmt >> 8) & 0xFFu;
+        const uint32_t prec = c.info & 0xFu, gsh = (c.info >> 4) & 0xFu;
         if (prec > kGSE8 || !c.src || !c.q || !c.part || c.n_q == 0 || c.n_split == 0 ||
-            ((uintptr_t)c.src & 15u) || ((uintptr_t)c.q & 15u) || ((uintptr_t)c.part & 15u))
+            ((uintptr_t)c.src & 15u) || ((uintptr_t)c.q & 15u) || ((uintptr_t)c.part & 15u) ||
+            (uint64_t)c.n_q * G > 0xFFFFFFull || c.n_tokens > 0x7FFFFFFu)
             return hipErrorInvalidValue;
         if ((prec == kInt4 || prec == kInt8) && (gsh < 5 || gsh > 7)) return hipErrorInvalidValue;
-        if ((uint64_t)c.n_q * G > 0xFFFFFFull || c.n_tokens > 0x7FFFFFFu) return hipErrorInvalidValue;
-        // every block of the chunk must belong to one of its splits
-        if ((uint64_t)c.n_split * kAttendSplitBlocks * 16u < c.n_tokens) return hipErrorInvalidValue;
+        // every block of the chunk must belong to one of the request's splits
+        if ((uint64_t)c.n_split * p.split_blocks * 16u < c.n_tokens) return hipErrorInvalidValue;
         const uint32_t n_mt = (c.n_q * G + 15u) >> 4;
         if (n_mt > max_mt) max_mt = n_mt;
     }
     p.mtw = max_mt >= 4 ? 4u : max_mt >= 2 ? 2u : 1u;
-    uint64_t total = 0;
+    uint64_t width = 0;
     for (uint32_t i = 0; i < p.n_chunks; ++i) {
-        const uint32_t n_mt = (p.c[i].n_q * G + 15u) >> 4;
-        p.unit_start[i] = (uint32_t)total;
-        total += (uint64_t)p.n_kv_heads * p.c[i].n_split * ((n_mt + p.mtw - 1u) / p.mtw);
-        if (total > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        const K4Chunk &c = p.c[i];
+        const uint32_t n_mt = (c.n_q * G + 15u) >> 4;
+        const uint64_t w = (uint64_t)p.n_kv_heads * c.n_split * ((n_mt + p.mtw - 1u) / p.mtw);
+        if (w > width) width = w;
     }
-    p.unit_start[p.n_chunks] = (uint32_t)total;
-    p.total_units = (uint32_t)total;
+    if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
     p.pad = 0;
-    dim3 grid((uint32_t)total), block(64);
+    dim3 grid((uint32_t)width, p.n_chunks), block(64 * kAttendWaves);
     switch (p.mtw) {
     case 1: hipLaunchKernelGGL((k4_attend_partial<1>), grid, block, 0, stream, p); break;
     case 2: hipLaunchKernelGGL((k4_attend_partial<2>), grid, block, 0, stream, p); break;
@@ -334,44 +498,59 @@ hipError_t launch_k4(K4Params &p, hipStream_t stream)
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(128) k5_attend_merge(const K5Params p)
 {
-    const uint32_t row = blockIdx.x;
-    if (row >= p.total_rows) return;
-    uint32_t lo = 0, hi = p.n_reqs;
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (row >= p.row_start[mid]) lo = mid;
-        else hi = mid;
-    }
-    const K5Req &r = p.r[lo];
-    const uint32_t rr = row - p.row_start[lo];
-    const uint32_t qt = rr / p.n_q_heads, hq = rr - qt * p.n_q_heads;
-    const uint32_t G = p.n_q_heads / p.n_kv_heads;
+    // grid: x = row of the request (the grid is as wide as the largest), y = request; the
+    // descriptor is fetched at once
+    K5Req r = p.r[blockIdx.y];
+    uint32_t n_kv_heads = p.n_kv_heads, n_q_heads = p.n_q_heads;
+    pin(r.part);
+    pin(r.out);
+    pin(r.lse);
+    pin(r.n_q);
+    pin(r.n_chunks);
+    pin(r.n_split);
+    pin(n_kv_heads);
+    pin(n_q_heads);
+    const uint32_t rr = blockIdx.x;
+    if (rr >= r.n_q * n_q_heads) return;
+    const uint32_t qt = rr / n_q_heads, hq = rr - qt * n_q_heads;
+    const uint32_t G = n_q_heads / n_kv_heads;
     const uint32_t h = hq / G, gq = hq - h * G;
     const uint32_t mrow = qt * G + gq, mt = mrow >> 4, ri = mrow & 15u;
     const uint32_t n_mt = (r.n_q * G + 15u) >> 4;
     const uint32_t d = threadIdx.x;
-    const uint64_t chunk_stride = (uint64_t)p.n_kv_heads * r.n_split * n_mt * kAttendRecFloats;
+    const uint64_t chunk_stride = (uint64_t)n_kv_heads * r.n_split * n_mt * kAttendRecFloats;
     const float *first = r.part + ((uint64_t)(h * r.n_split) * n_mt + mt) * kAttendRecFloats;
     const uint64_t split_stride = (uint64_t)n_mt * kAttendRecFloats;
 
-    float m_max = neg_inf();
-    for (uint32_t ci = 0; ci < r.n_chunks; ++ci)
-        for (uint32_t s = 0; s < r.n_split; ++s) {
-            const float *rec = first + ci * chunk_stride + s * split_stride;
-            if (rec[2048 + 16 + ri] > 0.0f) m_max = __builtin_fmaxf(m_max, rec[2048 + ri]);
+    // One pass, eight records at a time: their maxima, sums and this thread's dim are fetched
+    // together (every thread reads the same m and l: broadcast loads), then folded into a
+    // running maximum like the blocks inside a record were.
+    const uint32_t n_units = r.n_chunks * r.n_split;  // records are [chunk][head][split][tile]
+    float m_max = neg_inf(), acc = 0.0f, l_sum = 0.0f;
+    for (uint32_t u0 = 0; u0 < n_units; u0 += 8u) {
+        float m[8], l[8], o[8];
+#pragma unroll
+        for (uint32_t k = 0; k < 8; ++k) {
+            const uint32_t u = u0 + k < n_units ? u0 + k : n_units - 1u;
+            const uint32_t ci = u / r.n_split, sp = u - ci * r.n_split;
+            const float *rec = first + ci * chunk_stride + sp * split_stride;
+            m[k] = rec[2048 + ri];
+            l[k] = u0 + k < n_units ? rec[2048 + 16 + ri] : 0.0f;
+            o[k] = rec[ri * 128u + d];
         }
-    float acc = 0.0f, l_sum = 0.0f;
-    for (uint32_t ci = 0; ci < r.n_chunks; ++ci)
-        for (uint32_t s = 0; s < r.n_split; ++s) {
-            const float *rec = first + ci * chunk_stride + s * split_stride;
-            const float l = rec[2048 + 16 + ri];
-            if (l > 0.0f) {
-                const float w = __builtin_amdgcn_exp2f(rec[2048 + ri] - m_max);
-                acc = __builtin_fmaf(w, rec[ri * 128u + d], acc);
-                l_sum = __builtin_fmaf(w, l, l_sum);
+#pragma unroll
+        for (uint32_t k = 0; k < 8; ++k) {
+            if (l[k] > 0.0f) {  // the same for all threads; an empty record holds no output rows
+                const float m_new = __builtin_fmaxf(m_max, m[k]);
+                const float fa = __builtin_amdgcn_exp2f(m_max - m_new);  // 0 at the first record
+                const float fb = __builtin_amdgcn_exp2f(m[k] - m_new);
+                acc = __builtin_fmaf(o[k], fb, acc * fa);
+                l_sum = __builtin_fmaf(l[k], fb, l_sum * fa);
+                m_max = m_new;
             }
         }
-    const uint64_t o = (uint64_t)qt * p.n_q_heads + hq;
+    }
+    const uint64_t o = (uint64_t)qt * n_q_heads + hq;
     r.out[o * 128u + d] = l_sum > 0.0f ? acc / l_sum : 0.0f;
     if (d == 0 && r.lse)
         r.lse[o] = l_sum > 0.0f ? (m_max + __builtin_log2f(l_sum)) * 0.69314718055994531f : neg_inf();
@@ -382,19 +561,17 @@ hipError_t launch_k5(K5Params &p, hipStream_t stream)
     if (p.n_reqs == 0) return hipSuccess;
     if (p.n_reqs > kMaxMergeReqs || p.n_kv_heads == 0 || p.n_q_heads % p.n_kv_heads)
         return hipErrorInvalidValue;
-    uint64_t total = 0;
+    uint64_t width = 0;
     for (uint32_t i = 0; i < p.n_reqs; ++i) {
         const K5Req &r = p.r[i];
         // a request without a token to attend to (n_chunks 0) gets zeros and lse = -inf
         if ((r.n_chunks && !r.part) || !r.out || r.n_q == 0 || r.n_split == 0)
             return hipErrorInvalidValue;
-        p.row_start[i] = (uint32_t)total;
-        total += (uint64_t)r.n_q * p.n_q_heads;
-        if (total > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        const uint64_t rows = (uint64_t)r.n_q * p.n_q_heads;
+        if (rows > width) width = rows;
     }
-    p.row_start[p.n_reqs] = (uint32_t)total;
-    p.total_rows = (uint32_t)total;
-    hipLaunchKernelGGL(k5_attend_merge, dim3((uint32_t)total), dim3(128), 0, stream, p);
+    if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k5_attend_merge, dim3((uint32_t)width, p.n_reqs), dim3(128), 0, stream, p);
     return hipGetLastError();
 }
 

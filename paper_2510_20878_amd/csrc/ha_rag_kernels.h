@@ -96,26 +96,33 @@ hipError_t launch_k3(const void *src, const void *packed, uint32_t n_tiles, uint
 // sum l[16] of 2^(score - m).
 constexpr uint32_t kAttendHeadDim = 128;
 constexpr uint32_t kAttendRecFloats = 16 * 128 + 32;
-constexpr uint32_t kAttendSplitBlocks = 32;  // layout blocks (16 tokens each) per split
+constexpr uint32_t kAttendMinSplitBlocks = 8;   // a workgroup takes split_blocks layout blocks (16
+constexpr uint32_t kAttendMaxSplitBlocks = 128; // tokens each) of one chunk: a power of two in this range
+constexpr uint32_t kAttendTargetGroups = 2048;  // the host splits finer while a launch has fewer workgroups
+constexpr uint32_t kAttendWaves = 2;          // waves of a workgroup; they interleave its blocks
+// Descriptors travel in the kernel argument buffer (about 20 KiB when full; launches with
+// arguments of 32 KiB were checked to work on this runtime).  A workgroup needs exactly one
+// descriptor, which it fetches in one go: the argument buffer may live in host memory, where
+// every dependent read costs a trip over the link.
+constexpr uint32_t kAttendLaunchChunks = 512;  // chunk descriptors per launch
 
 struct K4Chunk {
     const uint8_t *src;   // packed whole chunk
     const uint16_t *q;    // BF16 [n_q][n_q_heads][128] of the chunk's request
     float *part;          // this chunk's records [n_kv_heads][n_split][n_mtiles]
     uint32_t n_tokens;
-    uint32_t fmt;         // Prec | log2(group) << 8
+    uint32_t info;        // Prec | log2(group) << 4
     uint32_t n_q;         // query tokens of the request
     uint32_t n_split;     // token splits of the request (the same for all its chunks)
 };
 
 struct K4Params {
     uint32_t n_kv_heads, n_q_heads, layer, n_chunks;
-    uint32_t total_units;
-    uint32_t mtw;          // 16-row query tiles per wave: 1, 2 or 4 (set by launch_k4)
+    uint32_t mtw;          // 16-row query tiles per workgroup: 1, 2 or 4 (set by launch_k4)
     float scale_log2;      // sm_scale * log2(e)
+    uint32_t split_blocks; // layout blocks per token split
     uint32_t pad;
-    uint32_t unit_start[kMaxLaunchChunks + 1];  // prefix sum of units (one wave each) per chunk
-    K4Chunk c[kMaxLaunchChunks];
+    K4Chunk c[kAttendLaunchChunks];
 };
 
 struct K5Req {
@@ -127,12 +134,11 @@ struct K5Req {
 
 constexpr uint32_t kMaxMergeReqs = 64;
 struct K5Params {
-    uint32_t n_kv_heads, n_q_heads, n_reqs, total_rows;
-    uint32_t row_start[kMaxMergeReqs + 1];  // prefix sum of n_q * n_q_heads per request
+    uint32_t n_kv_heads, n_q_heads, n_reqs, pad;
     K5Req r[kMaxMergeReqs];
 };
 
-// Partial attention of every chunk of the launch (fills unit_start, total_units, mtw).
+// Partial attention of every chunk of the launch (sets mtw).
 hipError_t launch_k4(K4Params &p, hipStream_t stream);
 // Merges the partial results of each request into out and lse.
 hipError_t launch_k5(K5Params &p, hipStream_t stream);

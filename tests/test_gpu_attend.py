@@ -129,9 +129,15 @@ def test_smaller_groups(g):
 
 
 def test_a_chunk_longer_than_one_split_and_a_sharp_softmax():
-    # 1100 tokens = 3 splits; a large scale makes few keys dominate, so the running maximum
+    # 1100 tokens = 9 splits of 128 tokens (few workgroups, so the finest split); a large scale makes few keys dominate, so the running maximum
     # keeps moving and accumulated sums are rescaled many times
     run_case((1, 1, 128), [([1100, 513], [B.PREC_INT4, B.PREC_INT8], 4)], 0, 4, 0.5, 40)
+
+
+def test_many_long_chunks_take_coarse_splits():
+    # 40 chunks x 8 heads: 1300 tokens in 2 splits of 1024 give 640 workgroups, 4 of 512 give 1280, 6 of 256 2560
+    reqs = [([1300, 700], [B.PREC_INT4, B.PREC_INT8], 2) for _ in range(20)]
+    run_case((1, 8, 128), reqs, 0, 16, 0.09, 45)
 
 
 def test_batch_of_requests_with_different_shapes_empty_chunks_and_an_empty_request():
@@ -144,8 +150,8 @@ def test_batch_of_requests_with_different_shapes_empty_chunks_and_an_empty_reque
 
 
 def test_more_chunks_and_requests_than_one_launch_holds():
-    reqs = [([16 + (3 * i + j) % 20 for j in range(3)], [ALL[(i + j) % 6] for j in range(3)], 1 + i % 3)
-            for i in range(70)]                      # 210 chunks, 70 requests
+    reqs = [([16 + (3 * i + j) % 20 for j in range(8)], [ALL[(i + j) % 6] for j in range(8)], 1 + i % 3)
+            for i in range(140)]                     # 1120 chunks, 140 requests: two launches each
     run_case((1, 1, 128), reqs, 0, 2, 0.1, 60)
 
 

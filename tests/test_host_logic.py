@@ -780,12 +780,17 @@ def test_attend_workspace_size_and_argument_checks():
     ch = lambda t, p=B.PREC_INT4, g=64, part=B.PART_KV: (P, t, p, g, part)
     req = lambda chunks, n_q: (chunks, P, P, None, n_q)
     REC = (16 * 128 + 32) * 4
-    # records: live chunks x KV heads x splits (of 512 tokens) x 16-row query tiles
-    assert ctx.attend_workspace_bytes([req([ch(512), ch(100)], 1)], 8) == 2 * 2 * 1 * 1 * REC
-    assert ctx.attend_workspace_bytes([req([ch(512), ch(0)], 5)], 8) == 1 * 2 * 1 * 2 * REC
+    # records: live chunks x KV heads x token splits x 16-row query tiles.  A split is 2048
+    # tokens at most; it is halved (down to 128 tokens) while the call has fewer than 2048
+    # workgroups (live chunks x KV heads x splits x groups of 4 query tiles)
+    assert ctx.attend_workspace_bytes([req([ch(512), ch(100)], 1)], 8) == 2 * 2 * 4 * 1 * REC
+    assert ctx.attend_workspace_bytes([req([ch(512), ch(0)], 5)], 8) == 1 * 2 * 4 * 2 * REC
     c2 = B.Context(4, 2, 128, 2000, group_int8=128, group_int4=64, dry_run=True)
     assert c2.attend_workspace_bytes([req([ch(1100), ch(10)], 4), req([], 1), req([ch(16)], 9)], 4) == \
-        (2 * 2 * 3 * 1 + 0 + 1 * 2 * 1 * 2) * REC
+        (2 * 2 * 9 * 1 + 0 + 1 * 2 * 1 * 2) * REC
+    # 300 chunks x 2 heads x 4 splits of 512 tokens make 2400 workgroups: no finer split
+    big = [req([ch(2000)] * 100, 1) for _ in range(3)]
+    assert c2.attend_workspace_bytes(big, 4) == 300 * 2 * 4 * 1 * REC
     c2.destroy()
     ok = [req([ch(512), ch(100, B.PREC_16, 0)], 3)]
     n = ctx.attend_workspace_bytes(ok, 8)
