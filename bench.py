@@ -33,7 +33,11 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the gather-dequantize-scatter kernel on the hbm8b workload, from
 # rocprofv3 FETCH_SIZE / WRITE_SIZE runs (one counter per run) scaled by an elementwise
 # kernel of known size (--calibrate): 1.015 x the algorithmic bytes.
-MEASURED_TRAFFIC = {"hbm8b": 1_013_000_000}
+MEASURED_TRAFFIC = {"hbm8b": 1_013_000_000,
+                    # attention over packed chunks, default batch and one query token, per call
+                    # (one layer): partial kernel 328.5 MB read (= the packed bytes) + 21.3 MB of
+                    # records written, merge kernel 6.6 MB read + 0.6 MB written
+                    "attend8b": 357_000_000}
 PCIE_PEAK_GBPS = 63.0           # PCIe Gen5 x16, one direction, theoretical
 
 
@@ -193,6 +197,35 @@ def cpu_baseline(shape, T, g, mix, min_seconds, seed):
                   f"bits {mix}, {L} layers), {dt:.1f} s of one host core",
         "kv_tokens_per_s": passes * n * T / dt,
     }
+
+
+def cpu_baseline_attend(T, g, mix, n_q, n_qh, H, min_seconds, seed):
+    """The oracles of the same path on one host core: dequantize the request's K and V tiles of
+    one (layer, KV head) and run the attention oracle over them for that head's query heads;
+    repeated over fresh (layer, head) slices until `min_seconds` have been spent."""
+    import numpy as np
+    from oracle import attend as A
+    from oracle import codec
+    from paper_2510_20878_amd import workloads as wl
+
+    D, G, n = 128, n_qh // H, len(mix)
+    slices, dt, nbytes = 0, 0.0, 0
+    rng = np.random.Generator(np.random.PCG64(seed))
+    while dt < min_seconds and slices < 64:
+        packed = [codec.quantize_pack_chunk(wl.kv_chunk(1, 1, D, T, seed + 100 * slices + i), b, g)[0]
+                  for i, b in enumerate(mix)]                       # not timed: the offline step
+        q = wl.f32_to_bf16_words(rng.standard_normal((n_q, G, D), dtype=np.float32))
+        t0 = time.perf_counter()
+        cache, _ = codec.load_chunks(packed, (1, 1, D), [T] * n, list(mix), [g] * n, list(range(n)))
+        A.attend(cache, 0, n * T, q, D ** -0.5)
+        dt += time.perf_counter() - t0
+        nbytes += sum(len(p) for p in packed) + q.size * 2 + n_q * G * (D + 1) * 4
+        slices += 1
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{slices} (layer, KV head) slices of one request ({n} chunks x {T} tokens, bits {mix}): "
+                      f"oracle dequantize + oracle attention for {G} query heads x {n_q} token(s), "
+                      f"{dt:.1f} s of one host core (numpy may use more for its products)",
+            "kv_tokens_per_s": slices * n * T / (H * 32) / dt}
 
 
 def calibrate(torch, n_bytes=1 << 30, reps=5):
@@ -424,9 +457,14 @@ def run_attend(args, B, wl, torch):
         # what the same step costs through the cache: write the BF16 cache once per request
         # (2 B/element) and let an attention kernel read it back every step
         "bf16_cache_bytes_per_step": step_tokens * L * 2 * H * D * 2,
+        # the rate at which an attention kernel over that BF16 cache would have to read it to
+        # finish the step in the same time
+        "equivalent_bf16_cache_read_gbps": step_tokens * L * 2 * H * D * 2 / (ms_per_step * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "kernel": "k4_attend_partial (+ k5_attend_merge), one call = one layer",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": args.traffic_bytes,
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": args.traffic_bytes or (MEASURED_TRAFFIC["attend8b"]
+                                                       if (R, n_q, T) == (32, 1, 512) else None),
                      "kernel_ms": call_ms, "kernel_ms_median": per[len(per) // 2], "kernel_ms_best": per[0],
                      "algorithmic_bytes_per_launch": step_bytes // L},
     }
@@ -876,7 +914,10 @@ def main():
                     "(Sec. 3.1, Table 1; Sec. 3.3)"}
     if not args.no_cpu_baseline:
         t0 = time.time()
-        res["cpu_baseline"] = cpu_baseline(shape, T, g, mix, args.cpu_seconds, seed=12345)
+        if args.workload == "attend8b":
+            res["cpu_baseline"] = cpu_baseline_attend(T, g, mix, args.n_q, 32, shape[1], args.cpu_seconds, seed=12345)
+        else:
+            res["cpu_baseline"] = cpu_baseline(shape, T, g, mix, args.cpu_seconds, seed=12345)
         log(f"cpu baseline took {time.time() - t0:.1f} s in all")
     print(json.dumps(res))
 

@@ -2,10 +2,10 @@
 // building the BF16 cache first (the prefill of Sec. 2.1 consumes the concatenated chunk KV;
 // here the consumer reads the compressed chunks of Sec. 2.2 itself).
 //
-//  k4_attend_partial   one workgroup of four waves per (chunk, KV head, token split, group of
+//  k4_attend_partial   one workgroup of kAttendWaves waves per (chunk, KV head, token split, group of
 //      query rows); the waves take the layout blocks in turn: each decodes K and V blocks to
 //      BF16 in registers (the values a load would write), scores them with MFMA and keeps a
-//      running softmax; the four are summed in LDS into one unnormalised partial result
+//      running softmax; the waves' results are summed in LDS into one unnormalised partial result
 //  k5_attend_merge     one workgroup per (query token, query head): merges the partial
 //      results of the request's chunks and splits into out and the log-sum-exp
 //
@@ -356,7 +356,7 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K4Chunk &c
     }
 blocks_done:
 
-    // ---- the four waves' results: each wave leaves its rows, maxima and sums in LDS; then all
+    // ---- the waves' results: each wave leaves its rows, maxima and sums in LDS; then all
     // threads bring them to one maximum per row, add them up and write the record
 #pragma unroll
     for (int mt = 0; mt < MTW; ++mt) {
