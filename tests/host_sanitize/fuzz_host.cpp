@@ -123,6 +123,38 @@ int main(int argc, char **argv)
                 int rc = ha_rag_load_chunks_paged(ctx, ids.data(), nullptr, (uint32_t)ids.size(), &pc,
                                                   rnd() % 4, nullptr, &st, nullptr);
                 REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOSPC || rc == HA_RAG_EINVAL || rc == HA_RAG_ENOENT);
+            } else if (what < 80 && rnd() % 2) {  // attention over packed chunks: lists of random shape
+                const uint32_t n_reqs = (uint32_t)(rnd() % 5);
+                std::vector<ha_rag_attend_request> rq(n_reqs + 1);
+                std::vector<ha_rag_packed_chunk> ch;
+                for (uint32_t r = 0; r < n_reqs; ++r) {
+                    std::memset(&rq[r], 0, sizeof rq[r]);
+                    rq[r].q = (const void *)(0x720000000000ull + (rnd() % 8 == 0 ? 2 : 0));
+                    rq[r].out = rnd() % 9 == 0 ? nullptr : (float *)0x730000000000ull;
+                    rq[r].lse = rnd() % 2 ? nullptr : (float *)0x740000000000ull;
+                    rq[r].n_q = (uint32_t)(rnd() % 10 == 0 ? 5000 : rnd() % 70);
+                    rq[r].n_chunks = (uint32_t)(rnd() % 6);
+                    for (uint32_t i = 0; i < rq[r].n_chunks; ++i) {
+                        ha_rag_packed_chunk pc;
+                        pc.packed = (const void *)(0x750000000000ull + 16 * (rnd() % 1000) + (rnd() % 16 == 0 ? 4 : 0));
+                        pc.n_tokens = (uint32_t)(rnd() % 12 == 0 ? 0 : rnd() % 5000);
+                        pc.prec = (uint32_t)(rnd() % (HA_RAG_N_PREC + 1));
+                        pc.group = 32u << (rnd() % 4);
+                        pc.part = (uint32_t)(rnd() % 8 == 0 ? rnd() % 4 : 0);
+                        ch.push_back(pc);
+                    }
+                }
+                const uint32_t n_qh = cfg.n_kv_heads * (uint32_t)(rnd() % 6) + (rnd() % 9 == 0 ? 1 : 0);
+                size_t need = 0;
+                int rc = ha_rag_attend_workspace_bytes(ctx, ch.data(), rq.data(), n_reqs, n_qh, &need);
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_EINVAL || rc == HA_RAG_EFORMAT);
+                const size_t have = rnd() % 4 == 0 ? need / 2 : need;
+                int rc2 = ha_rag_attend_packed(ctx, ch.data(), rq.data(), n_reqs, (uint32_t)(rnd() % 4), n_qh,
+                                               rnd() % 10 == 0 ? -1.0f : 0.1f, (void *)0x760000000000ull, have,
+                                               nullptr);
+                REQUIRE(rc2 == HA_RAG_OK || rc2 == HA_RAG_EINVAL || rc2 == HA_RAG_EFORMAT || rc2 == HA_RAG_ENOSPC);
+                if (rc != HA_RAG_OK) REQUIRE(rc2 != HA_RAG_OK);
+                if (rc2 == HA_RAG_ENOSPC) REQUIRE(have < need);
             } else if (what < 80) {  // save the index, damage a copy of it at random, load both
                 const char *good = "/tmp/ha_rag_fuzz.idx", *bad = "/tmp/ha_rag_fuzz_bad.idx";
                 REQUIRE(ha_rag_pool_save_index(ctx, good) == HA_RAG_OK);

@@ -6,6 +6,8 @@ import subprocess
 
 import pytest
 
+from paper_2510_20878_amd.build import SOURCES       # every source of the library
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
@@ -20,9 +22,7 @@ def test_host_runtime_fuzz_under_asan_ubsan(tmp_path):
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wno-unused-command-line-argument",
            os.path.join(ROOT, "tests", "host_sanitize", "fuzz_host.cpp"),
-           os.path.join(csrc, "ha_rag_api.hip"), os.path.join(csrc, "ha_rag_pool.hip"),
-           os.path.join(csrc, "ha_rag_load.hip"), os.path.join(csrc, "ha_rag_io.hip"),
-           os.path.join(csrc, "ha_rag_kernels.hip"),
+           *[os.path.join(csrc, f) for f in SOURCES],
            "-o", exe]
     r = subprocess.run(cmd, capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-3000:]
@@ -43,9 +43,7 @@ def test_host_runtime_from_four_threads_under_tsan(tmp_path):
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wno-unused-command-line-argument",
            os.path.join(ROOT, "tests", "host_sanitize", "threads_host.cpp"),
-           os.path.join(csrc, "ha_rag_api.hip"), os.path.join(csrc, "ha_rag_pool.hip"),
-           os.path.join(csrc, "ha_rag_load.hip"), os.path.join(csrc, "ha_rag_io.hip"),
-           os.path.join(csrc, "ha_rag_kernels.hip"),
+           *[os.path.join(csrc, f) for f in SOURCES],
            "-o", exe]
     r = subprocess.run(cmd, capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-3000:]
