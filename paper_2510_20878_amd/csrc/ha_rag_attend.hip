@@ -57,7 +57,7 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
     for (;; sb >>= 1) {
         uint64_t groups = 0;
         for (const Plan &pl : *plans)
-            groups += (uint64_t)pl.n_live * H * ((pl.max_blocks + sb - 1u) / sb) * ((pl.n_mt + 3u) / 4u);
+            groups += (uint64_t)pl.n_live * H * ((pl.max_blocks + sb - 1u) / sb) * ((pl.n_mt + 1u) / 2u);
         if (groups >= kAttendTargetGroups || sb == kAttendMinSplitBlocks) break;
     }
     *split_blocks = sb;

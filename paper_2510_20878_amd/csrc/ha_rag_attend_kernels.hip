@@ -336,7 +336,7 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K4Chunk &c
     // to cover the memory latency at full bandwidth, and a block of a 4-bit chunk is a quarter
     // of the bytes of a 16-bit one, so narrow formats get a deeper ring.  The loop is unrolled
     // over the ring so that no block is copied from one set to another.
-    constexpr int kStages = MTW > 1 ? 2 : PREC == kInt4 ? 4 : PREC == kP16 ? 2 : 3;
+    constexpr int kStages = MTW > 1 ? 2 : PREC == kInt4 ? 4 : PREC == kP16 ? 2 : 3;  // MTW 2: registers are short
     BlockRegs<PREC> ring[kStages];
     uint32_t b = b0 + wave;
 #pragma unroll
@@ -412,10 +412,10 @@ blocks_done:
     }
 }
 
-// (the second bound is waves per SIMD: two keep the accumulators of the one-tile variant in
-// ordinary vector registers, with no copies to and from the accumulation registers)
+// (the second bound is waves per SIMD: with two the accumulators stay in ordinary vector
+// registers, with no copies to and from the accumulation registers around the rescale branch)
 template <int MTW>
-__global__ void __launch_bounds__(64 * kAttendWaves, MTW == 1 ? 2 : 1) k4_attend_partial(const K4Params p)
+__global__ void __launch_bounds__(64 * kAttendWaves, 2) k4_attend_partial(const K4Params p)
 {
     __shared__ __attribute__((aligned(16))) uint8_t lds[AttendLds<MTW>::kBytes];
     __shared__ float sm[kAttendWaves][MTW * 16], sl[kAttendWaves][MTW * 16];
@@ -474,7 +474,10 @@ hipError_t launch_k4(K4Params &p, hipStream_t stream)
         const uint32_t n_mt = (c.n_q * G + 15u) >> 4;
         if (n_mt > max_mt) max_mt = n_mt;
     }
-    p.mtw = max_mt >= 4 ? 4u : max_mt >= 2 ? 2u : 1u;
+    // Two tiles (32 query rows) per workgroup is the most that still runs two waves per SIMD
+    // (241 vector registers); four tiles at one wave per SIMD measured 35 % slower than two
+    // passes of two.
+    p.mtw = max_mt >= 2 ? 2u : 1u;
     uint64_t width = 0;
     for (uint32_t i = 0; i < p.n_chunks; ++i) {
         const K4Chunk &c = p.c[i];
@@ -485,11 +488,8 @@ hipError_t launch_k4(K4Params &p, hipStream_t stream)
     if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
     p.pad = 0;
     dim3 grid((uint32_t)width, p.n_chunks), block(64 * kAttendWaves);
-    switch (p.mtw) {
-    case 1: hipLaunchKernelGGL((k4_attend_partial<1>), grid, block, 0, stream, p); break;
-    case 2: hipLaunchKernelGGL((k4_attend_partial<2>), grid, block, 0, stream, p); break;
-    default: hipLaunchKernelGGL((k4_attend_partial<4>), grid, block, 0, stream, p); break;
-    }
+    if (p.mtw == 1) hipLaunchKernelGGL((k4_attend_partial<1>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((k4_attend_partial<2>), grid, block, 0, stream, p);
     return hipGetLastError();
 }
 

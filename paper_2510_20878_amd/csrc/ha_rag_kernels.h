@@ -118,7 +118,7 @@ struct K4Chunk {
 
 struct K4Params {
     uint32_t n_kv_heads, n_q_heads, layer, n_chunks;
-    uint32_t mtw;          // 16-row query tiles per workgroup: 1, 2 or 4 (set by launch_k4)
+    uint32_t mtw;          // 16-row query tiles per workgroup: 1 or 2 (set by launch_k4)
     float scale_log2;      // sm_scale * log2(e)
     uint32_t split_blocks; // layout blocks per token split
     uint32_t pad;

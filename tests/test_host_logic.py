@@ -782,7 +782,7 @@ def test_attend_workspace_size_and_argument_checks():
     REC = (16 * 128 + 32) * 4
     # records: live chunks x KV heads x token splits x 16-row query tiles.  A split is 2048
     # tokens at most; it is halved (down to 128 tokens) while the call has fewer than 2048
-    # workgroups (live chunks x KV heads x splits x groups of 4 query tiles)
+    # workgroups (live chunks x KV heads x splits x pairs of query tiles)
     assert ctx.attend_workspace_bytes([req([ch(512), ch(100)], 1)], 8) == 2 * 2 * 4 * 1 * REC
     assert ctx.attend_workspace_bytes([req([ch(512), ch(0)], 5)], 8) == 1 * 2 * 4 * 2 * REC
     c2 = B.Context(4, 2, 128, 2000, group_int8=128, group_int4=64, dry_run=True)
