@@ -376,6 +376,25 @@ int ha_rag_attend_workspace_bytes(ha_rag_ctx *ctx, const ha_rag_packed_chunk *ch
                                   const ha_rag_attend_request *reqs, uint32_t n_reqs,
                                   uint32_t n_q_heads, size_t *bytes);
 
+/* The same for chunks of the pool, named by id: ids[] holds the requests' chunk ids one
+ * request after the other (reqs[r].n_chunks each).  Every chunk is read where its fastest
+ * copy lies, which must be in HBM or in pinned memory (the kernel reads pinned memory over the
+ * link); ENOENT for an unknown id and for a chunk whose only copies are in pageable memory or
+ * a file (load or promote it first).  No copy is made and nothing is promoted or evicted:
+ * placement is the business of ha_rag_load_chunks / ha_rag_pool_promote.
+ * flags: HA_RAG_ATTEND_COUNT = count one access per listed chunk (Algorithm 1's AF) and move
+ * it to the recent end of its tier's LRU order, as a load does; a caller that attends layer
+ * after layer sets it for one layer of a step only.  Reads are ordered after writes to the
+ * same slots on other streams like the loads' are. */
+#define HA_RAG_ATTEND_COUNT 1u
+int ha_rag_attend_chunks(ha_rag_ctx *ctx, const uint64_t *ids, const ha_rag_attend_request *reqs,
+                         uint32_t n_reqs, uint32_t layer, uint32_t n_q_heads, float sm_scale,
+                         uint32_t flags, void *workspace, size_t workspace_bytes, void *stream);
+
+int ha_rag_attend_chunks_workspace_bytes(ha_rag_ctx *ctx, const uint64_t *ids,
+                                         const ha_rag_attend_request *reqs, uint32_t n_reqs,
+                                         uint32_t n_q_heads, size_t *bytes);
+
 /* ---- pools (Algorithm 2's queueGPU / queuePIN / queuePAGE and the files) ------- */
 
 /* Gives the context a slab for chunks of tag `prec` in a memory tier: `base` is a

@@ -15,6 +15,7 @@ PREC_16, PREC_INT8, PREC_INT4, PREC_FP8_E4M3, PREC_FP8_E5M2, PREC_GSE8 = 0, 1, 2
 TIER_HBM, TIER_PINNED, TIER_PAGEABLE, TIER_DISK, TIER_NONE = 0, 1, 2, 3, 255
 PART_KV, PART_K, PART_V = 0, 1, 2
 NO_CHUNK = 2**64 - 1
+ATTEND_COUNT = 1
 BITS = {PREC_16: 16, PREC_INT8: 8, PREC_INT4: 4, PREC_FP8_E4M3: 8, PREC_FP8_E5M2: 8,
         PREC_GSE8: 8}  # storage bits
 PREC_OF_BITS = {16: PREC_16, 8: PREC_INT8, 4: PREC_INT4}
@@ -31,7 +32,7 @@ SYMBOLS = [
     "ha_rag_quantize_half", "ha_rag_pool_insert_half", "ha_rag_load_packed_paged",
     "ha_rag_load_chunks_paged", "ha_rag_chunk_sq_error", "ha_rag_pool_save_index",
     "ha_rag_pool_load_index", "ha_rag_pool_remove", "ha_rag_attend_packed",
-    "ha_rag_attend_workspace_bytes",
+    "ha_rag_attend_workspace_bytes", "ha_rag_attend_chunks", "ha_rag_attend_chunks_workspace_bytes",
 ]
 
 
@@ -141,6 +142,10 @@ def lib():
                                                C.c_float, vp, C.c_size_t, vp]),
             "ha_rag_attend_workspace_bytes": (C.c_int, [vp, P(PackedChunk), P(AttendRequest), u32, u32,
                                                         P(C.c_size_t)]),
+            "ha_rag_attend_chunks": (C.c_int, [vp, P(u64), P(AttendRequest), u32, u32, u32, C.c_float,
+                                               u32, vp, C.c_size_t, vp]),
+            "ha_rag_attend_chunks_workspace_bytes": (C.c_int, [vp, P(u64), P(AttendRequest), u32, u32,
+                                                               P(C.c_size_t)]),
             "ha_rag_load_chunks_paged": (C.c_int, [vp, P(u64), P(C.c_uint8), u32, P(PagedCache), u64, vp,
                                                    P(LoadStats), P(ChunkTrace)]),
             "ha_rag_register_slab": (C.c_int, [vp, u32, u32, vp, sz]),
@@ -361,6 +366,35 @@ class Context:
         self._chk(lib().ha_rag_attend_packed(self._h, arr, reqs, n_reqs, layer, n_q_heads,
                                              sm_scale, _addr(workspace), workspace_bytes,
                                              _stream(stream)), "ha_rag_attend_packed")
+
+    @staticmethod
+    def attend_id_lists(requests):
+        """requests: list of (ids, q, out, lse, n_q).  Returns the marshalled lists, which
+        attend_chunks accepts in place of `requests`."""
+        if isinstance(requests, tuple) and len(requests) == 3 and isinstance(requests[2], int):
+            return requests
+        ids = [i for r in requests for i in r[0]]
+        reqs = (AttendRequest * max(len(requests), 1))()
+        for k, (rid, q, out, lse, n_q) in enumerate(requests):
+            reqs[k] = AttendRequest(_addr(q), _addr(out), _addr(lse), n_q, len(rid))
+        return _u64s(ids), reqs, len(requests)
+
+    def attend_chunks_workspace_bytes(self, requests, n_q_heads):
+        ids, reqs, n_reqs = self.attend_id_lists(requests)
+        n = C.c_size_t(0)
+        self._chk(lib().ha_rag_attend_chunks_workspace_bytes(self._h, ids, reqs, n_reqs, n_q_heads,
+                                                             C.byref(n)),
+                  "ha_rag_attend_chunks_workspace_bytes")
+        return n.value
+
+    def attend_chunks(self, requests, layer, n_q_heads, sm_scale, workspace, workspace_bytes=None,
+                      count=False, stream=None):
+        ids, reqs, n_reqs = self.attend_id_lists(requests)
+        if workspace_bytes is None:
+            workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+        self._chk(lib().ha_rag_attend_chunks(self._h, ids, reqs, n_reqs, layer, n_q_heads, sm_scale,
+                                             ATTEND_COUNT if count else 0, _addr(workspace),
+                                             workspace_bytes, _stream(stream)), "ha_rag_attend_chunks")
 
     def load_chunks_paged(self, ids, cache, tok_base=0, tags=None, stream=None, want_trace=False):
         n = len(ids)

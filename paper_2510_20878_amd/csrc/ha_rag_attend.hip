@@ -89,7 +89,8 @@ int ha_rag_attend_workspace_bytes(ha_rag_ctx *c, const ha_rag_packed_chunk *chun
     return HA_RAG_OK;
 }
 
-int ha_rag_attend_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
+// checks, workspace layout and launches; the caller holds the context's lock
+static int attend_locked(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
                          const ha_rag_attend_request *reqs, uint32_t n_reqs, uint32_t layer,
                          uint32_t n_q_heads, float sm_scale, void *workspace, size_t workspace_bytes,
                          void *stream)
@@ -103,7 +104,6 @@ int ha_rag_attend_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
     if (floats && (!workspace || ((uintptr_t)workspace & 15u))) return HA_RAG_EINVAL;
     if (floats * 4ull > workspace_bytes) return HA_RAG_ENOSPC;
     if (c->dry()) return HA_RAG_OK;
-    std::lock_guard<std::mutex> g(c->mu);
     hipStream_t st = (hipStream_t)stream;
     const uint32_t H = c->cfg.n_kv_heads;
     float *ws = static_cast<float *>(workspace);
@@ -158,6 +158,98 @@ int ha_rag_attend_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
     }
     if (mp.n_reqs) HIPCHK(c, launch_k5(mp, st));
     return HA_RAG_OK;
+}
+
+int ha_rag_attend_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
+                         const ha_rag_attend_request *reqs, uint32_t n_reqs, uint32_t layer,
+                         uint32_t n_q_heads, float sm_scale, void *workspace, size_t workspace_bytes,
+                         void *stream)
+{
+    if (!c) return HA_RAG_EINVAL;
+    std::lock_guard<std::mutex> g(c->mu);
+    return attend_locked(c, chunks, reqs, n_reqs, layer, n_q_heads, sm_scale, workspace,
+                         workspace_bytes, stream);
+}
+
+// ids -> descriptors of the copies the kernel can read in place (HBM, else pinned memory)
+static int resolve_ids(ha_rag_ctx *c, const uint64_t *ids, const ha_rag_attend_request *reqs,
+                       uint32_t n_reqs, std::vector<ha_rag_packed_chunk> *out,
+                       std::vector<uint32_t> *cis)
+{
+    if (!c || !reqs || n_reqs == 0 || n_reqs > HA_RAG_MAX_ATTEND_REQUESTS) return HA_RAG_EINVAL;
+    uint64_t n = 0;
+    for (uint32_t r = 0; r < n_reqs; ++r) n += reqs[r].n_chunks;
+    if (n > HA_RAG_MAX_REQUEST_CHUNKS || (n && !ids)) return HA_RAG_EINVAL;
+    out->resize((size_t)n);
+    cis->resize((size_t)n);
+    for (uint64_t i = 0; i < n; ++i) {
+        uint32_t ci = 0;
+        const Chunk *ch = find_chunk(c, ids[i], &ci);
+        if (!ch) return HA_RAG_ENOENT;
+        const int t = ch->fastest();
+        if (t != (int)HA_RAG_TIER_HBM && t != (int)HA_RAG_TIER_PINNED) return HA_RAG_ENOENT;
+        ha_rag_packed_chunk &pc = (*out)[(size_t)i];
+        pc.packed = c->slab[t][ch->prec].ptr(ch->slot[t]);
+        pc.n_tokens = ch->n_tokens;
+        pc.prec = ch->prec;
+        pc.group = c->group_of(ch->prec);
+        pc.part = ch->part;
+        (*cis)[(size_t)i] = ci;
+    }
+    return HA_RAG_OK;
+}
+
+int ha_rag_attend_chunks_workspace_bytes(ha_rag_ctx *c, const uint64_t *ids,
+                                         const ha_rag_attend_request *reqs, uint32_t n_reqs,
+                                         uint32_t n_q_heads, size_t *bytes)
+{
+    if (!c || !bytes) return HA_RAG_EINVAL;
+    std::lock_guard<std::mutex> g(c->mu);
+    std::vector<ha_rag_packed_chunk> chunks;
+    std::vector<uint32_t> cis;
+    int rc = resolve_ids(c, ids, reqs, n_reqs, &chunks, &cis);
+    if (rc) return rc;
+    std::vector<Plan> plans;
+    uint64_t floats = 0;
+    uint32_t split_blocks = 0;
+    rc = plan_attend(c, chunks.data(), reqs, n_reqs, n_q_heads, &plans, &floats, &split_blocks, false);
+    if (rc) return rc;
+    *bytes = (size_t)(floats * 4ull);
+    return HA_RAG_OK;
+}
+
+int ha_rag_attend_chunks(ha_rag_ctx *c, const uint64_t *ids, const ha_rag_attend_request *reqs,
+                         uint32_t n_reqs, uint32_t layer, uint32_t n_q_heads, float sm_scale,
+                         uint32_t flags, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!c || (flags & ~(uint32_t)HA_RAG_ATTEND_COUNT)) return HA_RAG_EINVAL;
+    std::lock_guard<std::mutex> g(c->mu);
+    std::vector<ha_rag_packed_chunk> chunks;
+    std::vector<uint32_t> cis;
+    int rc = resolve_ids(c, ids, reqs, n_reqs, &chunks, &cis);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    // the kernels read the slots where they lie: wait for whoever wrote them on another stream
+    for (size_t i = 0; i < cis.size(); ++i) {
+        const Chunk &ch = c->chunks[cis[i]];
+        const int t = ch.fastest();
+        rc = before_read(c, c->slab[t][ch.prec].use[ch.slot[t]], s);
+        if (rc) return rc;
+    }
+    rc = attend_locked(c, chunks.data(), reqs, n_reqs, layer, n_q_heads, sm_scale, workspace,
+                       workspace_bytes, stream);
+    if (rc) return rc;
+    if (flags & HA_RAG_ATTEND_COUNT) {  // Algorithm 1's access counts and the LRU order of Algorithm 2
+        if (c->cfg.rerank_interval && c->n_loads && (c->n_loads % c->cfg.rerank_interval) == 0)
+            rerank_locked(c);
+        ++c->n_loads;
+        for (uint32_t ci : cis) {
+            Chunk &ch = c->chunks[ci];
+            ch.count += 1;
+            tier_touch(c, (uint32_t)ch.fastest(), ci);
+        }
+    }
+    return mark_stream(c, s);  // a later writer of one of these slots waits for this point
 }
 
 }  // extern "C"

@@ -196,3 +196,93 @@ def test_llama3_8b_request_sampled_heads_match_oracle():
             check(out_d[:, h * G:(h + 1) * G].cpu().numpy(), lse_d[:, h * G:(h + 1) * G].cpu().numpy(),
                   ref_out, ref_lse, spread, score_bound(cache, 0, len(order) * T, qh, scale, 1))
     ctx.destroy()
+
+
+def _pool_case():
+    """Six chunks in a pool: ids 0..2 have an HBM copy, 3..5 only a pinned one."""
+    L, H, D, T, g = 2, 2, 128, 96, 64
+    ORC = {B.PREC_16: 16, B.PREC_INT8: 8, B.PREC_INT4: 4, B.PREC_GSE8: 143}
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g)
+    precs = [B.PREC_INT4, B.PREC_INT8, B.PREC_16, B.PREC_INT4, B.PREC_GSE8, B.PREC_INT8]
+    tokens = [96, 50, 33, 80, 96, 17]
+    keep = []
+    for p in sorted(set(precs)):
+        slot = (ctx.chunk_bytes(p, T) + 255) // 256 * 256
+        hb = torch.zeros(slot * 3, dtype=torch.uint8, device="cuda")
+        pn = torch.zeros(slot * 3, dtype=torch.uint8).pin_memory()
+        ctx.register_slab(B.TIER_HBM, p, hb)
+        ctx.register_slab(B.TIER_PINNED, p, pn)
+        keep += [hb, pn]
+    packs = []
+    for i, (p, t) in enumerate(zip(precs, tokens)):
+        pk = codec.quantize_pack_chunk(wl.kv_chunk(L, H, D, t, 300 + i), ORC[p], g)[0]
+        packs.append(pk)
+        ctx.pool_insert(i, p, t, pk, B.TIER_HBM if i < 3 else B.TIER_PINNED)
+    return ctx, (L, H, D), g, precs, tokens, packs, ORC, keep
+
+
+def test_attend_over_pool_chunks_in_hbm_and_in_pinned_memory():
+    ctx, shape, g, precs, tokens, packs, ORC, keep = _pool_case()
+    L, H, D = shape
+    n_qh, scale, layer = 8, 0.09, 1
+    lists = [[4, 0, 3], [2, 5, 1, 0]]
+    call, refs = [], []
+    for r, ids in enumerate(lists):
+        n_q = 1 + 2 * r
+        qw = q_words(n_q, n_qh, D, 400 + r)
+        q_d = torch.from_numpy(qw.view(np.int16)).cuda()
+        out_d = torch.full((n_q, n_qh, D), float("nan"), dtype=torch.float32, device="cuda")
+        lse_d = torch.full((n_q, n_qh), float("nan"), dtype=torch.float32, device="cuda")
+        call.append((ids, q_d, out_d, lse_d, n_q))
+        refs.append((ids, qw, out_d, lse_d))
+    nb = ctx.attend_chunks_workspace_bytes(call, n_qh)
+    ws = torch.full((nb // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.attend_chunks(call, layer, n_qh, scale, ws, nb, count=True)
+    torch.cuda.synchronize()
+    for ids, qw, out_d, lse_d in refs:
+        cache, _ = codec.load_chunks(packs, shape, tokens, [ORC[p] for p in precs], [g] * len(precs), ids)
+        n_kv = sum(tokens[i] for i in ids)
+        ref_out, ref_lse, spread = A.attend(cache, layer, n_kv, qw, scale)
+        check(out_d.cpu().numpy(), lse_d.cpu().numpy(), ref_out, ref_lse, spread,
+              score_bound(cache, layer, n_kv, qw, scale, H))
+    assert [ctx.pool_query(i).count for i in range(6)] == [2, 1, 1, 1, 1, 1]
+    assert all(not ctx.pool_query(i).in_hbm for i in (3, 4, 5))       # nothing was promoted
+    ctx.destroy()
+
+
+def test_attend_can_be_captured_in_a_hip_graph_and_replayed():
+    """The call only launches kernels, so a per-layer loop can be recorded once and replayed;
+    every replay is checked against the eager result, with eager work in between."""
+    ctx, shape, g, precs, tokens, packs, ORC, keep = _pool_case()
+    L, H, D = shape
+    n_qh, scale = 8, 0.09
+    devs = [dev_u8(p) for p in packs]
+    qw = q_words(2, n_qh, D, 500)
+    q_d = torch.from_numpy(qw.view(np.int16)).cuda()
+    outs = [torch.zeros((2, n_qh, D), dtype=torch.float32, device="cuda") for _ in range(L)]
+    lses = [torch.zeros((2, n_qh), dtype=torch.float32, device="cuda") for _ in range(L)]
+    per_layer = [[([(devs[i], tokens[i], precs[i], g) for i in (1, 3, 0, 4)], q_d, outs[l], lses[l], 2)]
+                 for l in range(L)]
+    nb = ctx.attend_workspace_bytes(per_layer[0], n_qh)
+    ws = torch.zeros(nb // 4, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for l in range(L):
+            ctx.attend_packed(per_layer[l], l, n_qh, scale, ws, nb, stream=stream)
+    torch.cuda.synchronize()
+    eager = [(o.clone(), s.clone()) for o, s in zip(outs, lses)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        for l in range(L):
+            ctx.attend_packed(per_layer[l], l, n_qh, scale, ws, nb, stream=torch.cuda.current_stream())
+    for rep in range(3):
+        for o, s in zip(outs, lses):
+            o.fill_(float("nan"))
+            s.fill_(float("nan"))
+        ws.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for l in range(L):
+            assert torch.equal(outs[l], eager[l][0]) and torch.equal(lses[l], eager[l][1]), (rep, l)
+    ctx.destroy()

@@ -825,3 +825,43 @@ def test_attend_workspace_size_and_argument_checks():
         other.attend_workspace_bytes([req([ch(16, g=64)], 1)], 2)
     assert e.value.code == B.EFORMAT
     other.destroy()
+
+
+def test_attend_chunks_reads_hbm_or_pinned_copies_and_counts_on_request():
+    n = 6
+    ctx = B.Context(2, 2, 128, 128, group_int8=128, group_int4=64, dry_run=True,
+                    tau_gpu_ppm=340_000, tau_pin_ppm=340_000, tau_page_ppm=0)
+    for tier, base, slots in ((B.TIER_HBM, FAKE_HBM, 2), (B.TIER_PINNED, FAKE_PIN, 3),
+                              (B.TIER_PAGEABLE, 0x500000000000, 2)):
+        slot = (ctx.chunk_bytes(B.PREC_INT4, 128) + 255) // 256 * 256
+        ctx.register_slab(tier, B.PREC_INT4, base, slot * slots)
+    ctx.pool_insert(0, B.PREC_INT4, 128, None, B.TIER_HBM)
+    ctx.pool_insert(1, B.PREC_INT4, 100, None, B.TIER_PINNED)
+    ctx.pool_insert(2, B.PREC_INT4, 64, None, B.TIER_PINNED)
+    ctx.pool_insert(3, B.PREC_INT4, 128, None, B.TIER_PAGEABLE)
+    P = 0x7F0000001000
+    reqs = [([1, 0], P, P, None, 1), ([2], P, P, P, 3)]
+    nb = ctx.attend_chunks_workspace_bytes(reqs, 8)
+    packed_view = [([(P, 100, B.PREC_INT4, 64), (P, 128, B.PREC_INT4, 64)], P, P, None, 1),
+                   ([(P, 64, B.PREC_INT4, 64)], P, P, P, 3)]
+    assert nb == ctx.attend_workspace_bytes(packed_view, 8) > 0
+    ctx.attend_chunks(reqs, 1, 8, 0.1, P, nb)                          # no bookkeeping
+    assert [ctx.pool_query(i).count for i in range(4)] == [0, 0, 0, 0]
+    assert ctx.pool_lru(B.TIER_PINNED) == [1, 2]
+    ctx.attend_chunks(reqs, 0, 8, 0.1, P, nb, count=True)
+    assert [ctx.pool_query(i).count for i in range(4)] == [1, 1, 1, 0]
+    ctx.attend_chunks([([1], P, P, None, 1)], 0, 8, 0.1, P, nb, count=True)
+    assert ctx.pool_query(1).count == 2 and ctx.pool_lru(B.TIER_PINNED) == [2, 1]
+    for bad, code in (([([3], P, P, None, 1)], B.ENOENT),             # only a pageable copy
+                      ([([9], P, P, None, 1)], B.ENOENT),             # unknown id
+                      ([([0], P, P, None, 0)], B.EINVAL)):
+        with pytest.raises(B.HaRagError) as e:
+            ctx.attend_chunks(bad, 0, 8, 0.1, P, nb)
+        assert e.value.code == code
+    with pytest.raises(B.HaRagError) as e:
+        ctx.attend_chunks(reqs, 0, 8, 0.1, P, nb - 1)
+    assert e.value.code == B.ENOSPC
+    assert [ctx.pool_query(i).count for i in range(4)] == [1, 2, 1, 0]     # failed calls count nothing
+    rc = B.lib().ha_rag_attend_chunks(ctx._h, None, None, 0, 0, 8, 0.1, 2, None, 0, None)
+    assert rc == B.EINVAL                                              # unknown flag
+    ctx.destroy()
