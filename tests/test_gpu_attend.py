@@ -286,3 +286,51 @@ def test_attend_can_be_captured_in_a_hip_graph_and_replayed():
         for l in range(L):
             assert torch.equal(outs[l], eager[l][0]) and torch.equal(lses[l], eager[l][1]), (rep, l)
     ctx.destroy()
+
+
+def test_llama3_8b_batch_of_32_requests_sampled_heads_match_oracle():
+    """The batch the benchmark times: 32 requests x 10 chunks x 512 tokens of the 8B shape in
+    one call (one partial-attention launch over 320 chunks), one query token each.  Sampled
+    (request, layer, KV head) triples are recomputed by the oracle from the source words."""
+    L, H, D, T, g, n_qh, R = 32, 8, 128, 512, 128, 32, 32
+    G = n_qh // H
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g)
+    mix = [B.PREC_16] * 2 + [B.PREC_INT8] * 3 + [B.PREC_INT4] * 5
+    rng = np.random.default_rng(3)
+    srcs, packs, precs = [], [], []
+    for r in range(R):
+        order = rng.permutation(10)
+        for k in range(10):
+            p = mix[order[k]]
+            s_ = wl.kv_chunk_device(L, H, D, T, 9000 + 10 * r + k)
+            dst = torch.empty(ctx.chunk_bytes(p, T), dtype=torch.uint8, device="cuda")
+            ctx.quantize_chunk(s_, T, p, g, dst)
+            srcs.append(s_)
+            packs.append(dst)
+            precs.append(p)
+    qw = q_words(R, n_qh, D, 901)                                   # one query token per request
+    q_d = torch.from_numpy(qw.view(np.int16)).cuda()
+    out_d = torch.full((R, n_qh, D), float("nan"), dtype=torch.float32, device="cuda")
+    lse_d = torch.full((R, n_qh), float("nan"), dtype=torch.float32, device="cuda")
+    call = [([(packs[10 * r + k], T, precs[10 * r + k], g) for k in range(10)],
+             q_d[r:r + 1], out_d[r:r + 1], lse_d[r:r + 1], 1) for r in range(R)]
+    lists = ctx.attend_lists(call)
+    nbytes = ctx.attend_workspace_bytes(lists, n_qh)
+    ws = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    scale = D ** -0.5
+    for layer in (0, 17, 31):
+        ctx.attend_packed(lists, layer, n_qh, scale, ws, nbytes)
+        torch.cuda.synchronize()
+        assert not torch.isnan(out_d).any() and not torch.isnan(lse_d).any()
+        for r, h in [(0, 0), (R - 1, H - 1), (int(rng.integers(R)), int(rng.integers(H)))]:
+            cache = np.zeros((1, 2, 1, 10 * T, D), np.uint16)
+            for k in range(10):
+                bits = B.BITS[precs[10 * r + k]]
+                src_kv = srcs[10 * r + k][layer, :, h].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+                ref_pack, _ = codec.quantize_pack_chunk(src_kv.reshape(1, 2, 1, T, D), bits, g)
+                codec.dequant_scatter_chunk(ref_pack, (1, 1, D), T, bits, g, cache, k * T)
+            qh = np.ascontiguousarray(qw[r:r + 1, h * G:(h + 1) * G])
+            ref_out, ref_lse, spread = A.attend(cache, 0, 10 * T, qh, scale)
+            check(out_d[r:r + 1, h * G:(h + 1) * G].cpu().numpy(), lse_d[r:r + 1, h * G:(h + 1) * G].cpu().numpy(),
+                  ref_out, ref_lse, spread, score_bound(cache, 0, 10 * T, qh, scale, 1))
+    ctx.destroy()
