@@ -356,14 +356,17 @@ typedef struct ha_rag_attend_request {
  * K and V values are exact; the softmax weights are rounded to BF16 before they multiply V
  * and sums are accumulated in binary32, so out differs from the exact result by about
  * 2^-8 * sum_t softmax(s)[t] * |V[t][d]| at most.
- * chunks[]: host array of whole chunks (part = HA_RAG_PART_KV) in device memory, any mix of
- * tags; reqs[n_reqs]: host array, n_reqs <= HA_RAG_MAX_ATTEND_REQUESTS, all chunks together
+ * chunks[]: host array of chunks in device memory, any mix of tags.  A request may name
+ * whole chunks and keys-only / values-only chunks: its i-th keys-only chunk and its i-th
+ * values-only chunk form one document (their formats may differ) and must hold the same
+ * number of tokens; EINVAL if they do not, or if keys are left without values or the reverse.
+ * reqs[n_reqs]: host array, n_reqs <= HA_RAG_MAX_ATTEND_REQUESTS, all chunks together
  * <= HA_RAG_MAX_REQUEST_CHUNKS.  n_q_heads a multiple of H, at most 64 H.  sm_scale > 0.
  * workspace: device memory, 16-byte aligned, of at least the size
  * ha_rag_attend_workspace_bytes returns for the same lists (it holds partial results and
  * may be reused by the next call on the same stream); ENOSPC if smaller.
- * EFORMAT unless head_dim is 128, and for keys-only / values-only chunks.
- * Like ha_rag_load_packed the call only launches kernels on `stream`: one per 512 chunks
+ * EFORMAT unless head_dim is 128.
+ * Like ha_rag_load_packed the call only launches kernels on `stream`: one per 416 documents
  * plus one per 64 requests. */
 int ha_rag_attend_packed(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks,
                          const ha_rag_attend_request *reqs, uint32_t n_reqs, uint32_t layer,

@@ -1,30 +1,42 @@
 // Host side of attention over packed chunks: argument checks, the workspace layout, and the
-// launches (one partial-attention launch per 512 chunks, one merge launch per 64 requests).
+// launches (one partial-attention launch per 416 documents, one merge launch per 64 requests).
 #include "ha_rag_internal.h"
 
 using namespace ha_rag_host;
 
 namespace {
 
+// One document of a request: keys and values, from one whole chunk or from a keys-only and a
+// values-only chunk (paired in list order).
+struct Doc {
+    const uint8_t *k = nullptr, *v = nullptr;  // packed bytes holding the keys / the values
+    uint64_t k_tile = 0, v_tile = 0;           // bytes of one tile record
+    uint32_t k_first = 0, v_first = 0;         // tile record of (layer 0, head 0): 0, or H for the
+                                               // values of a whole chunk; a layer is k_step records on
+    uint32_t k_step = 0, v_step = 0;
+    uint32_t n_tokens = 0, info = 0;
+};
+
 struct Plan {               // one request
-    uint32_t first = 0;     // its first chunk in the list
-    uint32_t n_live = 0;    // chunks with tokens
+    uint32_t first_doc = 0, n_docs = 0;  // its documents that hold tokens
     uint32_t n_split = 1, n_mt = 1, max_blocks = 0;
     uint64_t part_floats = 0;  // offset of its records in the workspace
 };
 
 // Checks everything and lays the workspace out.  *floats = workspace size in binary32 words.
 int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_attend_request *reqs,
-                uint32_t n_reqs, uint32_t n_q_heads, std::vector<Plan> *plans, uint64_t *floats,
-                uint32_t *split_blocks, bool need_buffers)
+                uint32_t n_reqs, uint32_t n_q_heads, std::vector<Plan> *plans, std::vector<Doc> *docs,
+                uint64_t *floats, uint32_t *split_blocks, bool need_buffers)
 {
     if (!c || !reqs || n_reqs == 0 || n_reqs > HA_RAG_MAX_ATTEND_REQUESTS) return HA_RAG_EINVAL;
     if (c->cfg.head_dim != kAttendHeadDim) return HA_RAG_EFORMAT;
-    const uint32_t H = c->cfg.n_kv_heads;
+    const uint32_t L = c->cfg.n_layers, H = c->cfg.n_kv_heads;
     if (n_q_heads == 0 || n_q_heads % H || n_q_heads / H > 64) return HA_RAG_EINVAL;
     const uint32_t G = n_q_heads / H;
     uint64_t total = 0, n_chunks = 0;
     plans->assign(n_reqs, Plan());
+    docs->clear();
+    std::vector<uint32_t> open_k, open_v;  // documents still waiting for their values / keys
     for (uint32_t r = 0; r < n_reqs; ++r) {
         const ha_rag_attend_request &rq = reqs[r];
         Plan &pl = (*plans)[r];
@@ -33,20 +45,58 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
             return HA_RAG_EINVAL;
         if (n_chunks + rq.n_chunks > HA_RAG_MAX_REQUEST_CHUNKS || (rq.n_chunks && !chunks))
             return HA_RAG_EINVAL;
-        pl.first = (uint32_t)n_chunks;
+        pl.first_doc = (uint32_t)docs->size();
         pl.n_mt = (rq.n_q * G + 15u) / 16u;
         uint32_t max_tokens = 0;
+        open_k.clear();
+        open_v.clear();
+        size_t next_k = 0, next_v = 0;  // first entries of open_k / open_v not yet matched
         for (uint32_t i = 0; i < rq.n_chunks; ++i) {
-            const ha_rag_packed_chunk &pc = chunks[pl.first + i];
-            if (pc.part != HA_RAG_PART_KV) return HA_RAG_EFORMAT;
-            int rc = chunk_bytes_impl(c->cfg.n_layers, H, c->cfg.head_dim, pc.prec, pc.group,
-                                      pc.n_tokens, nullptr, nullptr, nullptr, pc.part);
+            const ha_rag_packed_chunk &pc = chunks[n_chunks + i];
+            size_t bytes = 0;
+            int rc = chunk_bytes_impl(L, H, c->cfg.head_dim, pc.prec, pc.group, pc.n_tokens, nullptr,
+                                      nullptr, &bytes, pc.part);
             if (rc) return rc;
-            if (pc.n_tokens == 0) continue;
+            if (pc.n_tokens == 0) continue;  // holds nothing, pairs with nothing
             if (need_buffers && (!pc.packed || ((uintptr_t)pc.packed & 15u))) return HA_RAG_EINVAL;
-            ++pl.n_live;
+            const uint8_t *ptr = static_cast<const uint8_t *>(pc.packed);
+            const uint32_t fmt = pc.prec | ((has_meta(pc.prec) ? log2u(pc.group) : 0u) << 4);
+            if (pc.part == HA_RAG_PART_KV) {
+                Doc d;
+                d.k = d.v = ptr;
+                d.k_tile = d.v_tile = bytes / (2ull * L * H);
+                d.k_first = 0;
+                d.v_first = H;
+                d.k_step = d.v_step = 2u * H;
+                d.n_tokens = pc.n_tokens;
+                d.info = fmt | (fmt << 8);
+                docs->push_back(d);
+            } else {
+                // the i-th keys-only chunk of the request and its i-th values-only chunk are one
+                // document: they must hold the same tokens
+                const bool is_k = pc.part == HA_RAG_PART_K;
+                std::vector<uint32_t> &mine = is_k ? open_k : open_v, &other = is_k ? open_v : open_k;
+                size_t &other_next = is_k ? next_v : next_k;
+                uint32_t di;
+                if (other_next < other.size()) {
+                    di = other[other_next++];
+                    if ((*docs)[di].n_tokens != pc.n_tokens) return HA_RAG_EINVAL;
+                } else {
+                    di = (uint32_t)docs->size();
+                    docs->push_back(Doc());
+                    (*docs)[di].n_tokens = pc.n_tokens;
+                    mine.push_back(di);
+                }
+                Doc &d = (*docs)[di];
+                (is_k ? d.k : d.v) = ptr;
+                (is_k ? d.k_tile : d.v_tile) = bytes / ((uint64_t)L * H);
+                (is_k ? d.k_step : d.v_step) = H;
+                d.info |= is_k ? fmt : fmt << 8;
+            }
             if (pc.n_tokens > max_tokens) max_tokens = pc.n_tokens;
         }
+        if (next_k != open_k.size() || next_v != open_v.size()) return HA_RAG_EINVAL;  // keys without values or the reverse
+        pl.n_docs = (uint32_t)docs->size() - pl.first_doc;
         pl.max_blocks = (max_tokens + 15u) / 16u;
         n_chunks += rq.n_chunks;
     }
@@ -57,14 +107,14 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
     for (;; sb >>= 1) {
         uint64_t groups = 0;
         for (const Plan &pl : *plans)
-            groups += (uint64_t)pl.n_live * H * ((pl.max_blocks + sb - 1u) / sb) * ((pl.n_mt + 1u) / 2u);
+            groups += (uint64_t)pl.n_docs * H * ((pl.max_blocks + sb - 1u) / sb) * ((pl.n_mt + 1u) / 2u);
         if (groups >= kAttendTargetGroups || sb == kAttendMinSplitBlocks) break;
     }
     *split_blocks = sb;
     for (Plan &pl : *plans) {
         pl.n_split = pl.max_blocks ? (pl.max_blocks + sb - 1u) / sb : 1u;
         pl.part_floats = total;
-        total += (uint64_t)pl.n_live * H * pl.n_split * pl.n_mt * kAttendRecFloats;
+        total += (uint64_t)pl.n_docs * H * pl.n_split * pl.n_mt * kAttendRecFloats;
     }
     if (total * 4ull > (1ull << 40)) return HA_RAG_EINVAL;
     *floats = total;
@@ -81,9 +131,10 @@ int ha_rag_attend_workspace_bytes(ha_rag_ctx *c, const ha_rag_packed_chunk *chun
 {
     if (!bytes) return HA_RAG_EINVAL;
     std::vector<Plan> plans;
+    std::vector<Doc> docs;
     uint64_t floats = 0;
     uint32_t split_blocks = 0;
-    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, &plans, &floats, &split_blocks, false);
+    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, &plans, &docs, &floats, &split_blocks, false);
     if (rc) return rc;
     *bytes = (size_t)(floats * 4ull);
     return HA_RAG_OK;
@@ -96,9 +147,10 @@ static int attend_locked(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
                          void *stream)
 {
     std::vector<Plan> plans;
+    std::vector<Doc> docs;
     uint64_t floats = 0;
     uint32_t split_blocks = 0;
-    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, &plans, &floats, &split_blocks, true);
+    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, &plans, &docs, &floats, &split_blocks, true);
     if (rc) return rc;
     if (layer >= c->cfg.n_layers || !(sm_scale > 0.0f) || !(sm_scale < 1e30f)) return HA_RAG_EINVAL;
     if (floats && (!workspace || ((uintptr_t)workspace & 15u))) return HA_RAG_EINVAL;
@@ -117,20 +169,18 @@ static int attend_locked(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
     for (uint32_t r = 0; r < n_reqs; ++r) {
         const ha_rag_attend_request &rq = reqs[r];
         const Plan &pl = plans[r];
-        const uint64_t per_chunk = (uint64_t)H * pl.n_split * pl.n_mt * kAttendRecFloats;
-        uint32_t live = 0;
-        for (uint32_t i = 0; i < rq.n_chunks; ++i) {
-            const ha_rag_packed_chunk &pc = chunks[pl.first + i];
-            if (pc.n_tokens == 0) continue;
+        const uint64_t per_doc = (uint64_t)H * pl.n_split * pl.n_mt * kAttendRecFloats;
+        for (uint32_t i = 0; i < pl.n_docs; ++i) {
+            const Doc &doc = docs[pl.first_doc + i];
             K4Chunk &d = kp.c[kp.n_chunks++];
-            d.src = static_cast<const uint8_t *>(pc.packed);
+            d.k = doc.k + (uint64_t)(doc.k_first + layer * doc.k_step) * doc.k_tile;
+            d.v = doc.v + (uint64_t)(doc.v_first + layer * doc.v_step) * doc.v_tile;
             d.q = static_cast<const uint16_t *>(rq.q);
-            d.part = ws + pl.part_floats + live * per_chunk;
-            d.n_tokens = pc.n_tokens;
-            d.info = pc.prec | ((has_meta(pc.prec) ? log2u(pc.group) : 0u) << 4);
+            d.part = ws + pl.part_floats + i * per_doc;
+            d.n_tokens = doc.n_tokens;
+            d.info = doc.info;
             d.n_q = rq.n_q;
             d.n_split = pl.n_split;
-            ++live;
             if (kp.n_chunks == kAttendLaunchChunks) {
                 HIPCHK(c, launch_k4(kp, st));
                 kp.n_chunks = 0;
@@ -148,7 +198,7 @@ static int attend_locked(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
         d.out = reqs[r].out;
         d.lse = reqs[r].lse;
         d.n_q = reqs[r].n_q;
-        d.n_chunks = plans[r].n_live;
+        d.n_chunks = plans[r].n_docs;
         d.n_split = plans[r].n_split;
         d.pad = 0;
         if (mp.n_reqs == kMaxMergeReqs) {
@@ -210,9 +260,10 @@ int ha_rag_attend_chunks_workspace_bytes(ha_rag_ctx *c, const uint64_t *ids,
     int rc = resolve_ids(c, ids, reqs, n_reqs, &chunks, &cis);
     if (rc) return rc;
     std::vector<Plan> plans;
+    std::vector<Doc> docs;
     uint64_t floats = 0;
     uint32_t split_blocks = 0;
-    rc = plan_attend(c, chunks.data(), reqs, n_reqs, n_q_heads, &plans, &floats, &split_blocks, false);
+    rc = plan_attend(c, chunks.data(), reqs, n_reqs, n_q_heads, &plans, &docs, &floats, &split_blocks, false);
     if (rc) return rc;
     *bytes = (size_t)(floats * 4ull);
     return HA_RAG_OK;

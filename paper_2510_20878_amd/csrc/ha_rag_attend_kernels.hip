@@ -131,9 +131,9 @@ __device__ __forceinline__ void pin(T *&v)
     v = reinterpret_cast<T *>(a);
 }
 
-template <uint32_t PREC>
+template <uint32_t KP, uint32_t VP>
 struct BlockRegs {  // what a lane loads for one block
-    u32x4 kw[Fmt<PREC>::kWords], vw[Fmt<PREC>::kWords];
+    u32x4 kw[Fmt<KP>::kWords], vw[Fmt<VP>::kWords];
     u32x4 vm;
     uint32_t km;
 };
@@ -145,12 +145,14 @@ struct AttendLds {
     static constexpr uint32_t kBytes = kExchange > kCombine ? kExchange : kCombine;
 };
 
-template <uint32_t PREC, int MTW>
+// KP, VP: the formats of the chunk's keys and of its values (the same for a chunk stored whole)
+template <uint32_t KP, uint32_t VP, int MTW>
 __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K4Chunk &c,
                                             uint32_t h, uint32_t s, uint32_t mtg, uint8_t *lds_all,
                                             float (*sm)[MTW * 16], float (*sl)[MTW * 16])
 {
-    typedef Fmt<PREC> F;
+    typedef Fmt<KP> FK;
+    typedef Fmt<VP> FV;
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t c_ = lane >> 4, n_ = lane & 15u;  // MFMA coordinates: lane group, lane column
@@ -158,13 +160,13 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K4Chunk &c
     const uint32_t H = p.n_kv_heads, G = p.n_q_heads / H, M = c.n_q * G;
     const uint32_t n_mt = (M + 15u) >> 4;
     const uint32_t T = c.n_tokens, nblk = (T + 15u) >> 4;
-    const uint32_t gsh = (c.info >> 4) & 0xFu;
-    const uint32_t meta_blk = F::kMeta ? 8192u >> gsh : 0u;
-    const uint64_t tile_bytes = (uint64_t)nblk * (F::kPayload + meta_blk) + (PREC == kGSE8 ? 16u : 0u);
-    const uint8_t *kt = c.src + (uint64_t)((p.layer * 2u) * H + h) * tile_bytes;
-    const uint8_t *vt = c.src + (uint64_t)((p.layer * 2u + 1u) * H + h) * tile_bytes;
-    const uint8_t *kmeta = kt + (uint64_t)nblk * F::kPayload;
-    const uint8_t *vmeta = vt + (uint64_t)nblk * F::kPayload;
+    const uint32_t kgsh = (c.info >> 4) & 0xFu, vgsh = (c.info >> 12) & 0xFu;
+    const uint32_t kmeta_blk = FK::kMeta ? 8192u >> kgsh : 0u, vmeta_blk = FV::kMeta ? 8192u >> vgsh : 0u;
+    // c.k / c.v point at the layer's tile of head 0; the heads' tile records follow one another
+    const uint8_t *kt = c.k + (uint64_t)h * ((uint64_t)nblk * (FK::kPayload + kmeta_blk) + (KP == kGSE8 ? 16u : 0u));
+    const uint8_t *vt = c.v + (uint64_t)h * ((uint64_t)nblk * (FV::kPayload + vmeta_blk) + (VP == kGSE8 ? 16u : 0u));
+    const uint8_t *kmeta = kt + (uint64_t)nblk * FK::kPayload;
+    const uint8_t *vmeta = vt + (uint64_t)nblk * FV::kPayload;
     float *rec0 = c.part + (uint64_t)((h * c.n_split + s) * n_mt) * kAttendRecFloats;
 
     const uint32_t b0 = s * p.split_blocks;
@@ -182,11 +184,13 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K4Chunk &c
     }
 
     int kbase = 0, ktop = 0, vbase = 0, vtop = 0;
-    if (PREC == kGSE8) {
+    if (KP == kGSE8) {
         const uint32_t kr = *reinterpret_cast<const uint32_t *>(kt + (uint64_t)nblk * 2048u);
-        const uint32_t vr = *reinterpret_cast<const uint32_t *>(vt + (uint64_t)nblk * 2048u);
         kbase = (int)(int8_t)(kr & 0xFFu);
         ktop = (int)(int8_t)((kr >> 8) & 0xFFu) - 2;
+    }
+    if (VP == kGSE8) {
+        const uint32_t vr = *reinterpret_cast<const uint32_t *>(vt + (uint64_t)nblk * 2048u);
         vbase = (int)(int8_t)(vr & 0xFFu);
         vtop = (int)(int8_t)((vr >> 8) & 0xFFu) - 2;
     }
@@ -223,51 +227,51 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K4Chunk &c
     // the octet 4 c_ + y, which lane 16 a_ + 4 c_ + y loaded as its plane x_
     const uint32_t src_lane0 = 16u * a_ + 4u * c_;
     uint32_t k_entry = 0;  // scale/zero entry of (token tk, dims 32 c_ ..) in a meta block
-    if (F::kMeta) {
-        const uint32_t grp = ((4u * x_ + a_) * 128u + 32u * c_) >> gsh;
-        k_entry = (grp & ((512u >> gsh) - 1u)) * 4u + (grp >> (9u - gsh));
+    if (FK::kMeta) {
+        const uint32_t grp = ((4u * x_ + a_) * 128u + 32u * c_) >> kgsh;
+        k_entry = (grp & ((512u >> kgsh) - 1u)) * 4u + (grp >> (9u - kgsh));
     }
     uint8_t *lds = lds_all + wave * 4096u;
     u32x4 *lds_w = reinterpret_cast<u32x4 *>(lds);
 
-    auto load_block = [&](uint32_t b, BlockRegs<PREC> &r) {
+    auto load_block = [&](uint32_t b, BlockRegs<KP, VP> &r) {
 #pragma unroll
-        for (uint32_t a = 0; a < F::kWords; ++a) {
-            r.kw[a] = ld16(kt + (uint64_t)b * F::kPayload + a * 1024u + lane * 16u);
-            r.vw[a] = ld16(vt + (uint64_t)b * F::kPayload + a * 1024u + lane * 16u);
-        }
+        for (uint32_t a = 0; a < FK::kWords; ++a)
+            r.kw[a] = ld16(kt + (uint64_t)b * FK::kPayload + a * 1024u + lane * 16u);
+#pragma unroll
+        for (uint32_t a = 0; a < FV::kWords; ++a)
+            r.vw[a] = ld16(vt + (uint64_t)b * FV::kPayload + a * 1024u + lane * 16u);
         r.km = 0;
         r.vm = u32x4{0u, 0u, 0u, 0u};
-        if (F::kMeta) {
-            r.km = *reinterpret_cast<const uint32_t *>(kmeta + (uint64_t)b * meta_blk + 4u * k_entry);
-            r.vm = ld16(vmeta + (uint64_t)b * meta_blk + ((lane * 8u) >> gsh) * 16u);
-        }
+        if (FK::kMeta)
+            r.km = *reinterpret_cast<const uint32_t *>(kmeta + (uint64_t)b * kmeta_blk + 4u * k_entry);
+        if (FV::kMeta) r.vm = ld16(vmeta + (uint64_t)b * vmeta_blk + ((lane * 8u) >> vgsh) * 16u);
     };
 
     // the waves of the workgroup take the blocks of the split in turn; each wave fetches its
     // next block before it works on the current one
-    auto process = [&](uint32_t b, const BlockRegs<PREC> &cur) {
+    auto process = [&](uint32_t b, const BlockRegs<KP, VP> &cur) {
         const bool ragged = b * 16u + 16u > T;  // only the chunk's last block can be
 
         // ---- K: exchange through LDS, decode, S^T = K Q^T
 #pragma unroll
-        for (uint32_t a = 0; a < F::kWords; ++a) lds_w[a * 64u + lane] = cur.kw[a];
+        for (uint32_t a = 0; a < FK::kWords; ++a) lds_w[a * 64u + lane] = cur.kw[a];
         wave_lds_sync();
         bf16x8 ka[4];
 #pragma unroll
         for (int y = 0; y < 4; ++y) {
             const uint32_t i_src = src_lane0 + y;
             u32x4 raw = {0u, 0u, 0u, 0u};
-            if (PREC == kInt4) {
+            if (KP == kInt4) {
                 raw.x = *reinterpret_cast<const uint32_t *>(lds + 16u * i_src + 4u * x_);
-            } else if (PREC == kP16) {
+            } else if (KP == kP16) {
                 raw = *reinterpret_cast<const u32x4 *>(lds + 1024u * x_ + 16u * i_src);
             } else {
                 const u32x2 t = *reinterpret_cast<const u32x2 *>(lds + 1024u * (x_ >> 1) + 16u * i_src + 8u * (x_ & 1u));
                 raw.x = t.x;
                 raw.y = t.y;
             }
-            ka[y] = __builtin_bit_cast(bf16x8, decode_octet<PREC>(raw, cur.km, kbase, ktop));
+            ka[y] = __builtin_bit_cast(bf16x8, decode_octet<KP>(raw, cur.km, kbase, ktop));
         }
         wave_lds_sync();
 
@@ -314,7 +318,7 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K4Chunk &c
         u32x4 vr[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            vr[j] = decode_octet<PREC>(plane_raw<PREC>(cur.vw, j), cur.vm[j], vbase, vtop);
+            vr[j] = decode_octet<VP>(plane_raw<VP>(cur.vw, j), cur.vm[j], vbase, vtop);
         if (ragged) {  // rows past the chunk's end
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -336,8 +340,9 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K4Chunk &c
     // to cover the memory latency at full bandwidth, and a block of a 4-bit chunk is a quarter
     // of the bytes of a 16-bit one, so narrow formats get a deeper ring.  The loop is unrolled
     // over the ring so that no block is copied from one set to another.
-    constexpr int kStages = MTW > 1 ? 2 : PREC == kInt4 ? 4 : PREC == kP16 ? 2 : 3;  // MTW 2: registers are short
-    BlockRegs<PREC> ring[kStages];
+    constexpr uint32_t kWordsKV = FK::kWords + FV::kWords;
+    constexpr int kStages = MTW > 1 ? 2 : kWordsKV <= 2 ? 4 : kWordsKV <= 4 ? 3 : 2;  // MTW 2: registers are short
+    BlockRegs<KP, VP> ring[kStages];
     uint32_t b = b0 + wave;
 #pragma unroll
     for (int i = 0; i < kStages - 1; ++i)
@@ -422,7 +427,8 @@ __global__ void __launch_bounds__(64 * kAttendWaves, 2) k4_attend_partial(const 
     // the whole descriptor and the header at once, before anything depends on a part of them
     K4Chunk c = p.c[blockIdx.y];
     AttendHdr hdr = {p.n_kv_heads, p.n_q_heads, p.layer, p.split_blocks, p.scale_log2};
-    pin(c.src);
+    pin(c.k);
+    pin(c.v);
     pin(c.q);
     pin(c.part);
     pin(c.n_tokens);
@@ -442,14 +448,25 @@ __global__ void __launch_bounds__(64 * kAttendWaves, 2) k4_attend_partial(const 
     const uint32_t mtg = u % n_mtg;
     const uint32_t hs = u / n_mtg;
     const uint32_t s = hs % c.n_split, h = hs / c.n_split;
-    switch (c.info & 0xFu) {
-    case kP16: attend_unit<kP16, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;
-    case kInt8: attend_unit<kInt8, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;
-    case kInt4: attend_unit<kInt4, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;
-    case kE4M3: attend_unit<kE4M3, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;
-    case kE5M2: attend_unit<kE5M2, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;
-    default: attend_unit<kGSE8, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    // one instance per pair of formats: whole chunks use the six on the diagonal
+#define HA_RAG_ATTEND_V(KP)                                                                         \
+    switch ((c.info >> 8) & 0xFu) {                                                                 \
+    case kP16: attend_unit<KP, kP16, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;                  \
+    case kInt8: attend_unit<KP, kInt8, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;                \
+    case kInt4: attend_unit<KP, kInt4, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;                \
+    case kE4M3: attend_unit<KP, kE4M3, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;                \
+    case kE5M2: attend_unit<KP, kE5M2, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;                \
+    default: attend_unit<KP, kGSE8, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;                   \
     }
+    switch (c.info & 0xFu) {
+    case kP16: HA_RAG_ATTEND_V(kP16) break;
+    case kInt8: HA_RAG_ATTEND_V(kInt8) break;
+    case kInt4: HA_RAG_ATTEND_V(kInt4) break;
+    case kE4M3: HA_RAG_ATTEND_V(kE4M3) break;
+    case kE5M2: HA_RAG_ATTEND_V(kE5M2) break;
+    default: HA_RAG_ATTEND_V(kGSE8) break;
+    }
+#undef HA_RAG_ATTEND_V
 }
 
 hipError_t launch_k4(K4Params &p, hipStream_t stream)
@@ -463,12 +480,14 @@ hipError_t launch_k4(K4Params &p, hipStream_t stream)
     uint32_t max_mt = 1;
     for (uint32_t i = 0; i < p.n_chunks; ++i) {
         const K4Chunk &c = p.c[i];
-        const uint32_t prec = c.info & 0xFu, gsh = (c.info >> 4) & 0xFu;
-        if (prec > kGSE8 || !c.src || !c.q || !c.part || c.n_q == 0 || c.n_split == 0 ||
-            ((uintptr_t)c.src & 15u) || ((uintptr_t)c.q & 15u) || ((uintptr_t)c.part & 15u) ||
-            (uint64_t)c.n_q * G > 0xFFFFFFull || c.n_tokens > 0x7FFFFFFu)
+        const uint32_t kprec = c.info & 0xFu, kgsh = (c.info >> 4) & 0xFu;
+        const uint32_t vprec = (c.info >> 8) & 0xFu, vgsh = (c.info >> 12) & 0xFu;
+        if (kprec > kGSE8 || vprec > kGSE8 || !c.k || !c.v || !c.q || !c.part || c.n_q == 0 ||
+            c.n_split == 0 || ((uintptr_t)c.k & 15u) || ((uintptr_t)c.v & 15u) || ((uintptr_t)c.q & 15u) ||
+            ((uintptr_t)c.part & 15u) || (uint64_t)c.n_q * G > 0xFFFFFFull || c.n_tokens > 0x7FFFFFFu)
             return hipErrorInvalidValue;
-        if ((prec == kInt4 || prec == kInt8) && (gsh < 5 || gsh > 7)) return hipErrorInvalidValue;
+        if ((kprec == kInt4 || kprec == kInt8) && (kgsh < 5 || kgsh > 7)) return hipErrorInvalidValue;
+        if ((vprec == kInt4 || vprec == kInt8) && (vgsh < 5 || vgsh > 7)) return hipErrorInvalidValue;
         // every block of the chunk must belong to one of the request's splits
         if ((uint64_t)c.n_split * p.split_blocks * 16u < c.n_tokens) return hipErrorInvalidValue;
         const uint32_t n_mt = (c.n_q * G + 15u) >> 4;

@@ -104,14 +104,17 @@ constexpr uint32_t kAttendWaves = 2;          // waves of a workgroup; they inte
 // arguments of 32 KiB were checked to work on this runtime).  A workgroup needs exactly one
 // descriptor, which it fetches in one go: the argument buffer may live in host memory, where
 // every dependent read costs a trip over the link.
-constexpr uint32_t kAttendLaunchChunks = 512;  // chunk descriptors per launch
+constexpr uint32_t kAttendLaunchChunks = 416;  // chunk descriptors per launch
 
+// One document of one request: its keys and its values, which may come from one whole chunk
+// or from a keys-only and a values-only chunk of different formats.
 struct K4Chunk {
-    const uint8_t *src;   // packed whole chunk
+    const uint8_t *k;     // tile record of (the launch's layer, KV head 0) of the keys; the
+    const uint8_t *v;     // other heads' records follow.  The same for the values
     const uint16_t *q;    // BF16 [n_q][n_q_heads][128] of the chunk's request
-    float *part;          // this chunk's records [n_kv_heads][n_split][n_mtiles]
+    float *part;          // this document's records [n_kv_heads][n_split][n_mtiles]
     uint32_t n_tokens;
-    uint32_t info;        // Prec | log2(group) << 4
+    uint32_t info;        // keys: Prec | log2(group) << 4; values: the same << 8
     uint32_t n_q;         // query tokens of the request
     uint32_t n_split;     // token splits of the request (the same for all its chunks)
 };

@@ -334,3 +334,73 @@ def test_llama3_8b_batch_of_32_requests_sampled_heads_match_oracle():
             check(out_d[r:r + 1, h * G:(h + 1) * G].cpu().numpy(), lse_d[r:r + 1, h * G:(h + 1) * G].cpu().numpy(),
                   ref_out, ref_lse, spread, score_bound(cache, 0, 10 * T, qh, scale, 1))
     ctx.destroy()
+
+
+def test_documents_stored_as_key_and_value_units_with_their_own_formats():
+    """The paper's 2n units (Alg. 1 counts key chunks and value chunks separately): the i-th
+    keys-only and the i-th values-only chunk of a request are one document; formats differ."""
+    L, H, D, g, n_qh, scale, layer = 2, 2, 128, 64, 8, 0.09, 1
+    ORC = {B.PREC_16: 16, B.PREC_INT8: 8, B.PREC_INT4: 4, B.PREC_FP8_E4M3: 43, B.PREC_FP8_E5M2: 52,
+           B.PREC_GSE8: 143}
+    ctx = B.Context(L, H, D, 128, group_int8=g, group_int4=g)
+    docs = {"A": (70, B.PREC_16, B.PREC_INT4), "C": (128, B.PREC_INT8, B.PREC_GSE8),
+            "D": (17, B.PREC_FP8_E4M3, B.PREC_FP8_E5M2), "E": (96, B.PREC_INT4, B.PREC_16)}
+    src = {k: wl.kv_chunk(L, H, D, t, 600 + i) for i, (k, (t, _, _)) in enumerate(docs.items())}
+    src["B"] = wl.kv_chunk(L, H, D, 33, 650)
+    # the request's list: (name, part); keys and values interleaved, a whole chunk between them
+    order = [("A", 1), ("C", 1), ("A", 2), ("C", 2), ("B", 0), ("D", 2), ("D", 1), ("E", 1), ("E", 2)]
+    packed, tokens, bits, parts, call_chunks = [], [], [], [], []
+    for name, part in order:
+        if part == 0:
+            pk = codec.quantize_pack_chunk(src[name], 8, g)[0]
+            t, prec = 33, B.PREC_INT8
+        else:
+            t, kp, vp = docs[name]
+            prec = kp if part == 1 else vp
+            pk = codec.quantize_pack_half(np.ascontiguousarray(src[name][:, part - 1]), ORC[prec], g)[0]
+        packed.append(pk)
+        tokens.append(t)
+        bits.append(ORC[prec])
+        parts.append(part)
+        call_chunks.append((dev_u8(pk), t, prec, g if prec in (B.PREC_INT8, B.PREC_INT4) else 0, part))
+    n_kv = 70 + 128 + 33 + 17 + 96
+    for n_q in (1, 7):
+        qw = q_words(n_q, n_qh, D, 660 + n_q)
+        q_d = torch.from_numpy(qw.view(np.int16)).cuda()
+        out_d = torch.full((n_q, n_qh, D), float("nan"), dtype=torch.float32, device="cuda")
+        lse_d = torch.full((n_q, n_qh), float("nan"), dtype=torch.float32, device="cuda")
+        call = [(call_chunks, q_d, out_d, lse_d, n_q)]
+        nb = ctx.attend_workspace_bytes(call, n_qh)
+        ws = torch.full((nb // 4,), float("nan"), dtype=torch.float32, device="cuda")
+        ctx.attend_packed(call, layer, n_qh, scale, ws, nb)
+        torch.cuda.synchronize()
+        cache, _ = codec.load_chunks(packed, (L, H, D), tokens, bits, [g] * len(order), list(range(len(order))),
+                                     parts=parts)
+        ref_out, ref_lse, spread = A.attend(cache, layer, n_kv, qw, scale)
+        check(out_d.cpu().numpy(), lse_d.cpu().numpy(), ref_out, ref_lse, spread,
+              score_bound(cache, layer, n_kv, qw, scale, H))
+    ctx.destroy()
+
+
+@pytest.mark.parametrize("kp,vp", [(a, b) for a in range(6) for b in range(6) if a != b])
+def test_every_pair_of_key_and_value_formats(kp, vp):
+    L, H, D, g, T = 1, 1, 128, 128, 40
+    ORC = [16, 8, 4, 43, 52, 143]
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g)
+    src = wl.kv_chunk(L, H, D, T, 700 + 6 * kp + vp)
+    pk = codec.quantize_pack_half(np.ascontiguousarray(src[:, 0]), ORC[kp], g)[0]
+    pv = codec.quantize_pack_half(np.ascontiguousarray(src[:, 1]), ORC[vp], g)[0]
+    qw = q_words(2, 2, D, 770)
+    q_d = torch.from_numpy(qw.view(np.int16)).cuda()
+    out_d = torch.full((2, 2, D), float("nan"), dtype=torch.float32, device="cuda")
+    lse_d = torch.full((2, 2), float("nan"), dtype=torch.float32, device="cuda")
+    grp = lambda p: g if p in (B.PREC_INT8, B.PREC_INT4) else 0
+    call = [([(dev_u8(pk), T, kp, grp(kp), B.PART_K), (dev_u8(pv), T, vp, grp(vp), B.PART_V)], q_d, out_d, lse_d, 2)]
+    nb = ctx.attend_workspace_bytes(call, 2)
+    ws = torch.full((nb // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.attend_packed(call, 0, 2, 0.1, ws, nb)
+    torch.cuda.synchronize()
+    cache, _ = codec.load_chunks([pk, pv], (L, H, D), [T, T], [ORC[kp], ORC[vp]], [g, g], [0, 1], parts=[1, 2])
+    ref_out, ref_lse, spread = A.attend(cache, 0, T, qw, 0.1)
+    check(out_d.cpu().numpy(), lse_d.cpu().numpy(), ref_out, ref_lse, spread, score_bound(cache, 0, T, qw, 0.1, H))
+    ctx.destroy()

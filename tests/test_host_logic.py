@@ -816,7 +816,15 @@ def test_attend_workspace_size_and_argument_checks():
     fails(B.EINVAL, [(([ch(16)]), P + 2, P, None, 1)])              # q misaligned
     fails(B.EINVAL, [(([ch(16)]), P, None, None, 1)])               # no out
     fails(B.EINVAL, [req([(P + 8, 16, B.PREC_INT4, 64, B.PART_KV)], 1)])
-    fails(B.EFORMAT, [req([ch(16, part=B.PART_K)], 1)])
+    fails(B.EINVAL, [req([ch(16, part=B.PART_K)], 1)])                                   # keys without values
+    fails(B.EINVAL, [req([ch(16, part=B.PART_V), ch(16)], 1)])
+    fails(B.EINVAL, [req([ch(16, part=B.PART_K), ch(32, part=B.PART_V)], 1)])            # lengths differ
+    fails(B.EINVAL, [req([ch(16, part=B.PART_K)], 1), req([ch(16, part=B.PART_V)], 1)])  # pairs do not cross requests
+    # keys and values of two documents in any interleaving, formats of their own, next to a whole chunk
+    pairs = [req([ch(64, part=B.PART_V), ch(64, B.PREC_16, 0, B.PART_K), ch(100), ch(40, B.PREC_INT8, 128, B.PART_K),
+                  ch(40, part=B.PART_V)], 2)]
+    assert ctx.attend_workspace_bytes(pairs, 8) == 3 * 2 * 1 * 1 * REC     # three documents, 100 tokens = one split
+    ctx.attend_packed(pairs, 0, 8, 0.1, P, 3 * 2 * REC)
     fails(B.EFORMAT, [req([ch(16, g=48)], 1)])
     fails(B.EFORMAT, [req([ch(16, p=9)], 1)])
     ctx.destroy()
