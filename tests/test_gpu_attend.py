@@ -404,3 +404,22 @@ def test_every_pair_of_key_and_value_formats(kp, vp):
     ref_out, ref_lse, spread = A.attend(cache, 0, T, qw, 0.1)
     check(out_d.cpu().numpy(), lse_d.cpu().numpy(), ref_out, ref_lse, spread, score_bound(cache, 0, T, qw, 0.1, H))
     ctx.destroy()
+
+
+def test_the_most_query_tokens_and_the_widest_head_group_one_call_takes():
+    # 4096 query tokens of one head group member (4096 query rows = 256 tiles over one chunk)
+    run_case((1, 1, 128), [([48], [B.PREC_INT4], 4096)], 0, 1, 0.1, 810)
+    # 64 query heads per KV head, one token
+    run_case((1, 2, 128), [([20, 16], [B.PREC_INT8, B.PREC_16], 1)], 0, 128, 0.1, 811)
+
+
+def test_the_most_requests_one_call_takes_and_one_more():
+    reqs = [([16 + i % 5], [ALL[i % 6]], 1) for i in range(1024)]
+    run_case((1, 1, 128), reqs, 0, 1, 0.1, 820)
+    ctx = B.Context(1, 1, 128, 16, dry_run=True)
+    P = 0x7F0000001000
+    too_many = [([(P, 16, B.PREC_16, 0)], P, P, None, 1)] * 1025
+    with pytest.raises(B.HaRagError) as e:
+        ctx.attend_workspace_bytes(too_many, 1)
+    assert e.value.code == B.EINVAL
+    ctx.destroy()
