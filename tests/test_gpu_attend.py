@@ -364,7 +364,7 @@ def test_documents_stored_as_key_and_value_units_with_their_own_formats():
         parts.append(part)
         call_chunks.append((dev_u8(pk), t, prec, g if prec in (B.PREC_INT8, B.PREC_INT4) else 0, part))
     n_kv = 70 + 128 + 33 + 17 + 96
-    for n_q in (1, 7):
+    for n_q in (1, 7, 20):                                    # 20: the many-rows kernel
         qw = q_words(n_q, n_qh, D, 660 + n_q)
         q_d = torch.from_numpy(qw.view(np.int16)).cuda()
         out_d = torch.full((n_q, n_qh, D), float("nan"), dtype=torch.float32, device="cuda")
@@ -390,12 +390,13 @@ def test_every_pair_of_key_and_value_formats(kp, vp):
     src = wl.kv_chunk(L, H, D, T, 700 + 6 * kp + vp)
     pk = codec.quantize_pack_half(np.ascontiguousarray(src[:, 0]), ORC[kp], g)[0]
     pv = codec.quantize_pack_half(np.ascontiguousarray(src[:, 1]), ORC[vp], g)[0]
-    qw = q_words(2, 2, D, 770)
+    n_q = 2 if (kp + vp) % 2 else 40                            # 40 query tokens: the many-rows kernel
+    qw = q_words(n_q, 2, D, 770)
     q_d = torch.from_numpy(qw.view(np.int16)).cuda()
-    out_d = torch.full((2, 2, D), float("nan"), dtype=torch.float32, device="cuda")
-    lse_d = torch.full((2, 2), float("nan"), dtype=torch.float32, device="cuda")
+    out_d = torch.full((n_q, 2, D), float("nan"), dtype=torch.float32, device="cuda")
+    lse_d = torch.full((n_q, 2), float("nan"), dtype=torch.float32, device="cuda")
     grp = lambda p: g if p in (B.PREC_INT8, B.PREC_INT4) else 0
-    call = [([(dev_u8(pk), T, kp, grp(kp), B.PART_K), (dev_u8(pv), T, vp, grp(vp), B.PART_V)], q_d, out_d, lse_d, 2)]
+    call = [([(dev_u8(pk), T, kp, grp(kp), B.PART_K), (dev_u8(pv), T, vp, grp(vp), B.PART_V)], q_d, out_d, lse_d, n_q)]
     nb = ctx.attend_workspace_bytes(call, 2)
     ws = torch.full((nb // 4,), float("nan"), dtype=torch.float32, device="cuda")
     ctx.attend_packed(call, 0, 2, 0.1, ws, nb)
