@@ -121,27 +121,9 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
     return HA_RAG_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-int ha_rag_attend_workspace_bytes(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
-                                  const ha_rag_attend_request *reqs, uint32_t n_reqs,
-                                  uint32_t n_q_heads, size_t *bytes)
-{
-    if (!bytes) return HA_RAG_EINVAL;
-    std::vector<Plan> plans;
-    std::vector<Doc> docs;
-    uint64_t floats = 0;
-    uint32_t split_blocks = 0;
-    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, &plans, &docs, &floats, &split_blocks, false);
-    if (rc) return rc;
-    *bytes = (size_t)(floats * 4ull);
-    return HA_RAG_OK;
-}
 
 // checks, workspace layout and launches; the caller holds the context's lock
-static int attend_locked(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
+int attend_locked(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
                          const ha_rag_attend_request *reqs, uint32_t n_reqs, uint32_t layer,
                          uint32_t n_q_heads, float sm_scale, void *workspace, size_t workspace_bytes,
                          void *stream)
@@ -210,19 +192,8 @@ static int attend_locked(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
     return HA_RAG_OK;
 }
 
-int ha_rag_attend_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
-                         const ha_rag_attend_request *reqs, uint32_t n_reqs, uint32_t layer,
-                         uint32_t n_q_heads, float sm_scale, void *workspace, size_t workspace_bytes,
-                         void *stream)
-{
-    if (!c) return HA_RAG_EINVAL;
-    std::lock_guard<std::mutex> g(c->mu);
-    return attend_locked(c, chunks, reqs, n_reqs, layer, n_q_heads, sm_scale, workspace,
-                         workspace_bytes, stream);
-}
-
 // ids -> descriptors of the copies the kernel can read in place (HBM, else pinned memory)
-static int resolve_ids(ha_rag_ctx *c, const uint64_t *ids, const ha_rag_attend_request *reqs,
+int resolve_ids(ha_rag_ctx *c, const uint64_t *ids, const ha_rag_attend_request *reqs,
                        uint32_t n_reqs, std::vector<ha_rag_packed_chunk> *out,
                        std::vector<uint32_t> *cis)
 {
@@ -247,6 +218,36 @@ static int resolve_ids(ha_rag_ctx *c, const uint64_t *ids, const ha_rag_attend_r
         (*cis)[(size_t)i] = ci;
     }
     return HA_RAG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ha_rag_attend_workspace_bytes(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
+                                  const ha_rag_attend_request *reqs, uint32_t n_reqs,
+                                  uint32_t n_q_heads, size_t *bytes)
+{
+    if (!bytes) return HA_RAG_EINVAL;
+    std::vector<Plan> plans;
+    std::vector<Doc> docs;
+    uint64_t floats = 0;
+    uint32_t split_blocks = 0;
+    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, &plans, &docs, &floats, &split_blocks, false);
+    if (rc) return rc;
+    *bytes = (size_t)(floats * 4ull);
+    return HA_RAG_OK;
+}
+
+int ha_rag_attend_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
+                         const ha_rag_attend_request *reqs, uint32_t n_reqs, uint32_t layer,
+                         uint32_t n_q_heads, float sm_scale, void *workspace, size_t workspace_bytes,
+                         void *stream)
+{
+    if (!c) return HA_RAG_EINVAL;
+    std::lock_guard<std::mutex> g(c->mu);
+    return attend_locked(c, chunks, reqs, n_reqs, layer, n_q_heads, sm_scale, workspace,
+                         workspace_bytes, stream);
 }
 
 int ha_rag_attend_chunks_workspace_bytes(ha_rag_ctx *c, const uint64_t *ids,
