@@ -853,6 +853,8 @@ def main():
     ap.add_argument("--o-direct", type=int, default=1, help="tiers: open pool files with O_DIRECT")
     ap.add_argument("--disk-dir", default="", help="tiers: directory for the pool files")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-attend", action="store_true",
+                    help="hbm8b: skip the short attention-over-packed-chunks measurement appended to the line")
     ap.add_argument("--no-cold", action="store_true",
                     help="hbm8b: skip the short pinned-host measurement appended to the line")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
@@ -911,6 +913,16 @@ def main():
         dma = run_cold(a2, B, wl, torch)
         res["cold_path"]["pinned_dma"] = {"link_gbps": dma["value"], "ms_per_step": dma["ms_per_step"],
                                           "frac_of_pcie_peak": dma["value"] / PCIE_PEAK_GBPS}
+    if args.workload == "hbm8b" and not args.no_attend and not args.mix and not args.paged:
+        # the same requests consumed without building the cache: attention straight over the packed
+        # chunks (one decode step of a batch of 32 requests, all layers)
+        torch.cuda.empty_cache()
+        a3 = argparse.Namespace(**vars(args))
+        a3.steps, a3.warmup, a3.batch, a3.n_q, a3.chunk_tokens, a3.traffic_bytes = 10, 2, 32, 1, 512, None
+        att, _ = run_attend(a3, B, wl, torch)
+        res["attend_path"] = {k: att[k] for k in ("value", "unit", "ms_per_step", "steps", "kv_tokens_per_s",
+                                                   "equivalent_bf16_cache_read_gbps", "roofline")}
+        res["attend_path"]["workload"] = att["config"]["workload"]
     res["paper_context"] = {
         "note": "context only, not a target: the paper reports end-to-end TTFT ratios, no GB/s",
         "ttft_speedup_vs_turborag": {"average": 2.10, "max": 10.49},
