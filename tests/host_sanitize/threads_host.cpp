@@ -34,7 +34,7 @@ int main(int argc, char **argv)
     std::memset(&cfg, 0, sizeof cfg);
     cfg.n_layers = 2;
     cfg.n_kv_heads = 2;
-    cfg.head_dim = 64;
+    cfg.head_dim = 128;
     cfg.max_chunk_tokens = 64;
     cfg.group_int8 = 64;
     cfg.group_int4 = 64;
@@ -45,7 +45,7 @@ int main(int argc, char **argv)
     ha_rag_ctx *ctx = nullptr;
     REQUIRE(ha_rag_create(&cfg, &ctx) == HA_RAG_OK);
     size_t total = 0;
-    REQUIRE(ha_rag_chunk_bytes(2, 2, 64, HA_RAG_PREC_INT4, 64, 64, nullptr, nullptr, &total) == HA_RAG_OK);
+    REQUIRE(ha_rag_chunk_bytes(2, 2, 128, HA_RAG_PREC_INT4, 64, 64, nullptr, nullptr, &total) == HA_RAG_OK);
     const size_t slot = (total + 4095) & ~(size_t)4095;   // file slots
     const size_t mslot = (total + 255) & ~(size_t)255;     // memory slots
     REQUIRE(ha_rag_register_slab(ctx, HA_RAG_TIER_HBM, HA_RAG_PREC_INT4, (void *)0x100000000000ull, mslot * 6) == HA_RAG_OK);
@@ -61,7 +61,29 @@ int main(int argc, char **argv)
         uint64_t s = 0x9E3779B97F4A7C15ull * (uint64_t)(t + 1);
         for (int op = 0; op < ops; ++op) {
             const uint64_t what = next(s) % 100;
-            if (what < 60) {
+            if (what < 12) {  // attention over pool chunks, counting accesses: only chunks with an
+                              // HBM or pinned copy can be read in place
+                uint64_t ids[4];
+                const uint32_t n = 1 + (uint32_t)(next(s) % 4);
+                for (uint32_t i = 0; i < n; ++i) ids[i] = next(s) % 32;
+                ha_rag_attend_request rq;
+                std::memset(&rq, 0, sizeof rq);
+                rq.q = (const void *)0x600000000000ull;
+                rq.out = (float *)(0x610000000000ull + (uint64_t)t * 0x10000000ull);
+                rq.n_q = 1 + (uint32_t)(next(s) % 3);
+                rq.n_chunks = n;
+                size_t need = 0;
+                int rc = ha_rag_attend_chunks_workspace_bytes(ctx, ids, &rq, 1, 4, &need);
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOENT);
+                if (rc == HA_RAG_OK) {
+                    // another thread may evict a copy between the two calls: ENOENT again, or a
+                    // size that no longer fits is impossible (sizes depend on token counts only)
+                    rc = ha_rag_attend_chunks(ctx, ids, &rq, 1, (uint32_t)(next(s) % 2), 4, 0.1f, HA_RAG_ATTEND_COUNT,
+                                              (void *)(0x620000000000ull + (uint64_t)t * 0x10000000ull), need, nullptr);
+                    REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOENT);
+                    if (rc == HA_RAG_OK) chunks.fetch_add(n);
+                }
+            } else if (what < 60) {
                 uint64_t ids[6];
                 const uint32_t n = 1 + (uint32_t)(next(s) % 6);
                 for (uint32_t i = 0; i < n; ++i) ids[i] = next(s) % 32;
