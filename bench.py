@@ -464,7 +464,7 @@ def run_attend(args, B, wl, torch):
         # the rate at which an attention kernel over that BF16 cache would have to read it to
         # finish the step in the same time
         "equivalent_bf16_cache_read_gbps": step_tokens * L * 2 * H * D * 2 / (ms_per_step * 1e-3) / 1e9,
-        "roofline": {"bound": "hbm", "kernel": "k4_attend_partial (+ k5_attend_merge), one call = one layer",
+        "roofline": {"bound": "hbm", "kernel": "k6_attend_partial (+ k7_attend_merge), one call = one layer",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": args.traffic_bytes or (MEASURED_TRAFFIC["attend8b"]

@@ -182,7 +182,7 @@ int ha_rag_chunk_sq_error(ha_rag_ctx *c, const void *src, const void *packed, ui
     if (rc) return rc;
     if (c->dry()) return HA_RAG_OK;
     std::lock_guard<std::mutex> g(c->mu);
-    HIPCHK(c, launch_k3(src, packed, part == kPartKV ? c->n_tiles : c->n_tiles / 2, c->cfg.head_dim,
+    HIPCHK(c, launch_k8(src, packed, part == kPartKV ? c->n_tiles : c->n_tiles / 2, c->cfg.head_dim,
                         n_tokens, prec, has_meta(prec) ? group : 32u, sum_sq, (hipStream_t)stream));
     return HA_RAG_OK;
 }

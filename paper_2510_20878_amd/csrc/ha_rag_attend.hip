@@ -142,7 +142,7 @@ int attend_locked(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
     const uint32_t H = c->cfg.n_kv_heads;
     float *ws = static_cast<float *>(workspace);
 
-    K4Params kp{};
+    K6Params kp{};
     kp.n_kv_heads = H;
     kp.n_q_heads = n_q_heads;
     kp.layer = layer;
@@ -154,7 +154,7 @@ int attend_locked(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
         const uint64_t per_doc = (uint64_t)H * pl.n_split * pl.n_mt * kAttendRecFloats;
         for (uint32_t i = 0; i < pl.n_docs; ++i) {
             const Doc &doc = docs[pl.first_doc + i];
-            K4Chunk &d = kp.c[kp.n_chunks++];
+            K6Chunk &d = kp.c[kp.n_chunks++];
             d.k = doc.k + (uint64_t)(doc.k_first + layer * doc.k_step) * doc.k_tile;
             d.v = doc.v + (uint64_t)(doc.v_first + layer * doc.v_step) * doc.v_tile;
             d.q = static_cast<const uint16_t *>(rq.q);
@@ -164,18 +164,18 @@ int attend_locked(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
             d.n_q = rq.n_q;
             d.n_split = pl.n_split;
             if (kp.n_chunks == kAttendLaunchChunks) {
-                HIPCHK(c, launch_k4(kp, st));
+                HIPCHK(c, launch_k6(kp, st));
                 kp.n_chunks = 0;
             }
         }
     }
-    if (kp.n_chunks) HIPCHK(c, launch_k4(kp, st));
+    if (kp.n_chunks) HIPCHK(c, launch_k6(kp, st));
 
-    K5Params mp{};
+    K7Params mp{};
     mp.n_kv_heads = H;
     mp.n_q_heads = n_q_heads;
     for (uint32_t r = 0; r < n_reqs; ++r) {
-        K5Req &d = mp.r[mp.n_reqs++];
+        K7Req &d = mp.r[mp.n_reqs++];
         d.part = ws + plans[r].part_floats;
         d.out = reqs[r].out;
         d.lse = reqs[r].lse;
@@ -184,11 +184,11 @@ int attend_locked(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
         d.n_split = plans[r].n_split;
         d.pad = 0;
         if (mp.n_reqs == kMaxMergeReqs) {
-            HIPCHK(c, launch_k5(mp, st));
+            HIPCHK(c, launch_k7(mp, st));
             mp.n_reqs = 0;
         }
     }
-    if (mp.n_reqs) HIPCHK(c, launch_k5(mp, st));
+    if (mp.n_reqs) HIPCHK(c, launch_k7(mp, st));
     return HA_RAG_OK;
 }
 

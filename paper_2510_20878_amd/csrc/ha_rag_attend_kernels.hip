@@ -2,11 +2,11 @@
 // building the BF16 cache first (the prefill of Sec. 2.1 consumes the concatenated chunk KV;
 // here the consumer reads the compressed chunks of Sec. 2.2 itself).
 //
-//  k4_attend_partial   one workgroup of kAttendWaves waves per (chunk, KV head, token split, group of
+//  k6_attend_partial   one workgroup of kAttendWaves waves per (chunk, KV head, token split, group of
 //      query rows); the waves take the layout blocks in turn: each decodes K and V blocks to
 //      BF16 in registers (the values a load would write), scores them with MFMA and keeps a
 //      running softmax; the waves' results are summed in LDS into one unnormalised partial result
-//  k5_attend_merge     one workgroup per (query token, query head): merges the partial
+//  k7_attend_merge     one workgroup per (query token, query head): merges the partial
 //      results of the request's chunks and splits into out and the log-sum-exp
 //
 // head_dim 128 only: a layout block is then 16 tokens x 128 dims, and lane (a = lane/16,
@@ -147,7 +147,7 @@ struct AttendLds {
 
 // KP, VP: the formats of the chunk's keys and of its values (the same for a chunk stored whole)
 template <uint32_t KP, uint32_t VP, int MTW>
-__device__ __forceinline__ void attend_unit(const AttendHdr &p, const K4Chunk &c,
+__device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c,
                                             uint32_t h, uint32_t s, uint32_t mtg, uint8_t *lds_all,
                                             float (*sm)[MTW * 16], float (*sl)[MTW * 16])
 {
@@ -420,12 +420,12 @@ blocks_done:
 // (the second bound is waves per SIMD: with two the accumulators stay in ordinary vector
 // registers, with no copies to and from the accumulation registers around the rescale branch)
 template <int MTW>
-__global__ void __launch_bounds__(64 * kAttendWaves, 2) k4_attend_partial(const K4Params p)
+__global__ void __launch_bounds__(64 * kAttendWaves, 2) k6_attend_partial(const K6Params p)
 {
     __shared__ __attribute__((aligned(16))) uint8_t lds[AttendLds<MTW>::kBytes];
     __shared__ float sm[kAttendWaves][MTW * 16], sl[kAttendWaves][MTW * 16];
     // the whole descriptor and the header at once, before anything depends on a part of them
-    K4Chunk c = p.c[blockIdx.y];
+    K6Chunk c = p.c[blockIdx.y];
     AttendHdr hdr = {p.n_kv_heads, p.n_q_heads, p.layer, p.split_blocks, p.scale_log2};
     pin(c.k);
     pin(c.v);
@@ -469,7 +469,7 @@ __global__ void __launch_bounds__(64 * kAttendWaves, 2) k4_attend_partial(const 
 #undef HA_RAG_ATTEND_V
 }
 
-hipError_t launch_k4(K4Params &p, hipStream_t stream)
+hipError_t launch_k6(K6Params &p, hipStream_t stream)
 {
     if (p.n_chunks == 0) return hipSuccess;
     if (p.n_chunks > kAttendLaunchChunks || p.n_kv_heads == 0 || p.n_q_heads % p.n_kv_heads ||
@@ -479,7 +479,7 @@ hipError_t launch_k4(K4Params &p, hipStream_t stream)
     const uint32_t G = p.n_q_heads / p.n_kv_heads;
     uint32_t max_mt = 1;
     for (uint32_t i = 0; i < p.n_chunks; ++i) {
-        const K4Chunk &c = p.c[i];
+        const K6Chunk &c = p.c[i];
         const uint32_t kprec = c.info & 0xFu, kgsh = (c.info >> 4) & 0xFu;
         const uint32_t vprec = (c.info >> 8) & 0xFu, vgsh = (c.info >> 12) & 0xFu;
         if (kprec > kGSE8 || vprec > kGSE8 || !c.k || !c.v || !c.q || !c.part || c.n_q == 0 ||
@@ -499,7 +499,7 @@ hipError_t launch_k4(K4Params &p, hipStream_t stream)
     p.mtw = max_mt >= 2 ? 2u : 1u;
     uint64_t width = 0;
     for (uint32_t i = 0; i < p.n_chunks; ++i) {
-        const K4Chunk &c = p.c[i];
+        const K6Chunk &c = p.c[i];
         const uint32_t n_mt = (c.n_q * G + 15u) >> 4;
         const uint64_t w = (uint64_t)p.n_kv_heads * c.n_split * ((n_mt + p.mtw - 1u) / p.mtw);
         if (w > width) width = w;
@@ -507,19 +507,19 @@ hipError_t launch_k4(K4Params &p, hipStream_t stream)
     if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
     p.pad = 0;
     dim3 grid((uint32_t)width, p.n_chunks), block(64 * kAttendWaves);
-    if (p.mtw == 1) hipLaunchKernelGGL((k4_attend_partial<1>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((k4_attend_partial<2>), grid, block, 0, stream, p);
+    if (p.mtw == 1) hipLaunchKernelGGL((k6_attend_partial<1>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((k6_attend_partial<2>), grid, block, 0, stream, p);
     return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
-// K5.  One workgroup of 128 threads (one per dim) per (query token, query head).
+// K7.  One workgroup of 128 threads (one per dim) per (query token, query head).
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(128) k5_attend_merge(const K5Params p)
+__global__ void __launch_bounds__(128) k7_attend_merge(const K7Params p)
 {
     // grid: x = row of the request (the grid is as wide as the largest), y = request; the
     // descriptor is fetched at once
-    K5Req r = p.r[blockIdx.y];
+    K7Req r = p.r[blockIdx.y];
     uint32_t n_kv_heads = p.n_kv_heads, n_q_heads = p.n_q_heads;
     pin(r.part);
     pin(r.out);
@@ -575,14 +575,14 @@ __global__ void __launch_bounds__(128) k5_attend_merge(const K5Params p)
         r.lse[o] = l_sum > 0.0f ? (m_max + __builtin_log2f(l_sum)) * 0.69314718055994531f : neg_inf();
 }
 
-hipError_t launch_k5(K5Params &p, hipStream_t stream)
+hipError_t launch_k7(K7Params &p, hipStream_t stream)
 {
     if (p.n_reqs == 0) return hipSuccess;
     if (p.n_reqs > kMaxMergeReqs || p.n_kv_heads == 0 || p.n_q_heads % p.n_kv_heads)
         return hipErrorInvalidValue;
     uint64_t width = 0;
     for (uint32_t i = 0; i < p.n_reqs; ++i) {
-        const K5Req &r = p.r[i];
+        const K7Req &r = p.r[i];
         // a request without a token to attend to (n_chunks 0) gets zeros and lse = -inf
         if ((r.n_chunks && !r.part) || !r.out || r.n_q == 0 || r.n_split == 0)
             return hipErrorInvalidValue;
@@ -590,7 +590,7 @@ hipError_t launch_k5(K5Params &p, hipStream_t stream)
         if (rows > width) width = rows;
     }
     if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(k5_attend_merge, dim3((uint32_t)width, p.n_reqs), dim3(128), 0, stream, p);
+    hipLaunchKernelGGL(k7_attend_merge, dim3((uint32_t)width, p.n_reqs), dim3(128), 0, stream, p);
     return hipGetLastError();
 }
 

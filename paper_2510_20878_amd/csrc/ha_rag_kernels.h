@@ -86,7 +86,7 @@ hipError_t launch_k2(const void *src, void *dst, uint32_t n_tiles, uint32_t head
 
 // Adds to *sum_sq (device, binary64) the squared error between src (BF16 [n_tiles][n_tokens][D])
 // and what `packed` decodes to.
-hipError_t launch_k3(const void *src, const void *packed, uint32_t n_tiles, uint32_t head_dim,
+hipError_t launch_k8(const void *src, const void *packed, uint32_t n_tiles, uint32_t head_dim,
                      uint32_t n_tokens, uint32_t prec, uint32_t group, double *sum_sq,
                      hipStream_t stream);
 
@@ -108,7 +108,7 @@ constexpr uint32_t kAttendLaunchChunks = 416;  // chunk descriptors per launch
 
 // One document of one request: its keys and its values, which may come from one whole chunk
 // or from a keys-only and a values-only chunk of different formats.
-struct K4Chunk {
+struct K6Chunk {
     const uint8_t *k;     // tile record of (the launch's layer, KV head 0) of the keys; the
     const uint8_t *v;     // other heads' records follow.  The same for the values
     const uint16_t *q;    // BF16 [n_q][n_q_heads][128] of the chunk's request
@@ -119,16 +119,16 @@ struct K4Chunk {
     uint32_t n_split;     // token splits of the request (the same for all its chunks)
 };
 
-struct K4Params {
+struct K6Params {
     uint32_t n_kv_heads, n_q_heads, layer, n_chunks;
-    uint32_t mtw;          // 16-row query tiles per workgroup: 1 or 2 (set by launch_k4)
+    uint32_t mtw;          // 16-row query tiles per workgroup: 1 or 2 (set by launch_k6)
     float scale_log2;      // sm_scale * log2(e)
     uint32_t split_blocks; // layout blocks per token split
     uint32_t pad;
-    K4Chunk c[kAttendLaunchChunks];
+    K6Chunk c[kAttendLaunchChunks];
 };
 
-struct K5Req {
+struct K7Req {
     const float *part;    // records [n_chunks][n_kv_heads][n_split][n_mtiles]
     float *out;           // binary32 [n_q][n_q_heads][128]
     float *lse;           // binary32 [n_q][n_q_heads] or null
@@ -136,14 +136,14 @@ struct K5Req {
 };
 
 constexpr uint32_t kMaxMergeReqs = 64;
-struct K5Params {
+struct K7Params {
     uint32_t n_kv_heads, n_q_heads, n_reqs, pad;
-    K5Req r[kMaxMergeReqs];
+    K7Req r[kMaxMergeReqs];
 };
 
 // Partial attention of every chunk of the launch (sets mtw).
-hipError_t launch_k4(K4Params &p, hipStream_t stream);
+hipError_t launch_k6(K6Params &p, hipStream_t stream);
 // Merges the partial results of each request into out and lse.
-hipError_t launch_k5(K5Params &p, hipStream_t stream);
+hipError_t launch_k7(K7Params &p, hipStream_t stream);
 
 }  // namespace ha_rag

@@ -745,7 +745,7 @@ hipError_t launch_k2(const void *src, void *dst, uint32_t n_tiles, uint32_t head
 }
 
 // ---------------------------------------------------------------------------
-// K3.  Squared error between a chunk's source words and what its packed form
+// K8.  Squared error between a chunk's source words and what its packed form
 // decodes to (Eq. 1 before the mean and the root; Sec. 3.2.1 orders the
 // compression schemes by this figure).  One wave per block of 2048 elements:
 // the block is decoded exactly as k1 decodes it, compared with the source
@@ -768,7 +768,7 @@ __device__ __forceinline__ double sq_err8(u32x4 a, u32x4 b)
     return acc;
 }
 
-__global__ void __launch_bounds__(256) k3_sq_error(const uint8_t *__restrict__ src,
+__global__ void __launch_bounds__(256) k8_sq_error(const uint8_t *__restrict__ src,
                                                    const uint8_t *__restrict__ packed,
                                                    uint32_t n_tokens, uint32_t head_dim,
                                                    uint32_t n_tiles, uint32_t prec, uint32_t gsh,
@@ -854,7 +854,7 @@ __global__ void __launch_bounds__(256) k3_sq_error(const uint8_t *__restrict__ s
     }
 }
 
-hipError_t launch_k3(const void *src, const void *packed, uint32_t n_tiles, uint32_t head_dim,
+hipError_t launch_k8(const void *src, const void *packed, uint32_t n_tiles, uint32_t head_dim,
                      uint32_t n_tokens, uint32_t prec, uint32_t group, double *sum_sq,
                      hipStream_t stream)
 {
@@ -870,7 +870,7 @@ hipError_t launch_k3(const void *src, const void *packed, uint32_t n_tiles, uint
         while ((1u << gsh) < group) ++gsh;
         if (gsh < 5 || gsh > 9 || (1u << gsh) != group) return hipErrorInvalidValue;
     }
-    hipLaunchKernelGGL(k3_sq_error, dim3(gx), dim3(256), 0, stream,
+    hipLaunchKernelGGL(k8_sq_error, dim3(gx), dim3(256), 0, stream,
                        static_cast<const uint8_t *>(src), static_cast<const uint8_t *>(packed),
                        n_tokens, head_dim, n_tiles, prec, gsh, sum_sq);
     return hipGetLastError();
