@@ -327,6 +327,25 @@ int ha_rag_load_packed(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks, uint3
 int ha_rag_load_packed_paged(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks, uint32_t n,
                              const ha_rag_paged_cache *cache, uint64_t tok_base, void *stream);
 
+/* Algorithm 2 step 2 without the decode, for consumers that read the packed chunks themselves
+ * (ha_rag_attend_chunks): for every listed chunk, in order, exactly the bookkeeping and the
+ * copies of ha_rag_load_chunks (access count, LRU touch in the tier it is found in, a copy in
+ * the tier its rank's list names if that is faster, evicting the least recently used chunk of
+ * a full slab), but no cache is written and no staging slot is used: a copy booked in HBM is
+ * filled by one host -> device copy on `stream`.  Pageable and file copies are read through a
+ * bounce buffer (ENOSPC without one).
+ * flags: HA_RAG_PLACE_DEVICE_VISIBLE = no chunk is left in pageable memory or a file only:
+ * one that its rank's list would leave there also gets a copy in pinned memory (slot
+ * permitting; see promote_skipped in the trace), so that the kernels can read every chunk of
+ * the list in place afterwards.
+ * stats: hit and placement counters as for a load; the byte counters hold what this call
+ * moved (bytes_h2d: copies into HBM; bytes_disk_read, bytes_host_copied); tokens,
+ * packed_bytes_read, bf16_bytes_written and bytes_d2d are 0. */
+#define HA_RAG_PLACE_DEVICE_VISIBLE 1u
+int ha_rag_place_chunks(ha_rag_ctx *ctx, const uint64_t *ids, const uint8_t *tags, uint32_t n,
+                        uint32_t flags, void *stream, ha_rag_load_stats *stats,
+                        ha_rag_chunk_trace *trace);
+
 /* ---- online, no cache: attention straight over packed chunks ------------------ */
 
 #define HA_RAG_MAX_ATTEND_REQUESTS 1024

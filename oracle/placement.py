@@ -105,10 +105,14 @@ class TierSim:
         for c in ids:
             self.q[tier].put(c)
 
-    def access(self, c):
-        """Returns (tier the chunk was found in, [(tier placed into, evicted id or None)])."""
+    def access(self, c, floor=None):
+        """Returns (tier the chunk was found in, [(tier placed into, evicted id or None)]).
+        floor (an addition to the algorithm, for consumers that read chunks in place): no chunk
+        is left in a tier slower than `floor`; its rank's list then counts as that tier."""
         placed = []
         want = self.list_of(c)
+        if floor is not None and want > floor:
+            want = floor
         if c in self.q[self.GPU]:
             self.q[self.GPU].get(c)
             return self.GPU, placed

@@ -16,6 +16,7 @@ TIER_HBM, TIER_PINNED, TIER_PAGEABLE, TIER_DISK, TIER_NONE = 0, 1, 2, 3, 255
 PART_KV, PART_K, PART_V = 0, 1, 2
 NO_CHUNK = 2**64 - 1
 ATTEND_COUNT = 1
+PLACE_DEVICE_VISIBLE = 1
 BITS = {PREC_16: 16, PREC_INT8: 8, PREC_INT4: 4, PREC_FP8_E4M3: 8, PREC_FP8_E5M2: 8,
         PREC_GSE8: 8}  # storage bits
 PREC_OF_BITS = {16: PREC_16, 8: PREC_INT8, 4: PREC_INT4}
@@ -33,6 +34,7 @@ SYMBOLS = [
     "ha_rag_load_chunks_paged", "ha_rag_chunk_sq_error", "ha_rag_pool_save_index",
     "ha_rag_pool_load_index", "ha_rag_pool_remove", "ha_rag_attend_packed",
     "ha_rag_attend_workspace_bytes", "ha_rag_attend_chunks", "ha_rag_attend_chunks_workspace_bytes",
+    "ha_rag_place_chunks",
 ]
 
 
@@ -166,6 +168,8 @@ def lib():
             "ha_rag_set_counts": (C.c_int, [vp, P(u64), P(u64), sz]),
             "ha_rag_rerank": (C.c_int, [vp]),
             "ha_rag_get_rank": (C.c_int, [vp, u64, P(u32)]),
+            "ha_rag_place_chunks": (C.c_int, [vp, P(u64), P(C.c_uint8), u32, u32, vp, P(LoadStats),
+                                              P(ChunkTrace)]),
             "ha_rag_load_chunks": (C.c_int, [vp, P(u64), P(C.c_uint8), u32, vp, u64, u64, vp,
                                              P(LoadStats), P(ChunkTrace)]),
             "ha_rag_load_batch": (C.c_int, [vp, P(u64), P(C.c_uint8), P(u32), u32, P(vp), P(u64),
@@ -508,6 +512,18 @@ class Context:
         self._chk(lib().ha_rag_load_chunks(self._h, _u64s(ids), tg, n, _addr(out), cap_tokens,
                                            tok_base, _stream(stream), C.byref(st), tr),
                   "ha_rag_load_chunks")
+        return st.as_dict(), (list(tr[:n]) if want_trace else None)
+
+    def place_chunks(self, ids, device_visible=False, tags=None, stream=None, want_trace=False):
+        """Algorithm 2's bookkeeping and copies for `ids` without a decode.  Returns (stats dict,
+        trace list or None)."""
+        n = len(ids)
+        st = LoadStats()
+        tr = (ChunkTrace * max(n, 1))() if want_trace else None
+        tg = (C.c_uint8 * max(n, 1))(*tags) if tags is not None else None
+        self._chk(lib().ha_rag_place_chunks(self._h, _u64s(ids), tg, n,
+                                            PLACE_DEVICE_VISIBLE if device_visible else 0,
+                                            _stream(stream), C.byref(st), tr), "ha_rag_place_chunks")
         return st.as_dict(), (list(tr[:n]) if want_trace else None)
 
     def load_batch(self, requests, outs, cap_tokens, tok_base=None, tags=None, stream=None,

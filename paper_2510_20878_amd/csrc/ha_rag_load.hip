@@ -142,6 +142,82 @@ int fill_bounce(ha_rag_ctx *c, const Chunk &ch, uint32_t tier, int32_t slot, uin
     return read_direct(c, sl.fd, dst, ch.bytes, sl.offset(slot));
 }
 
+// Algorithm 2 step 2 for one chunk of a call: counts the access, touches the LRU order of the
+// tier it is found in, and books a copy in the tier its rank's list names if that tier is
+// faster than the one it was found in (floor_tier: no chunk is left in a tier slower than this;
+// HA_RAG_TIER_DISK asks for nothing beyond the algorithm).  Fills the action, the trace entry and
+// the statistics; moves no byte.
+void alg2_step(ha_rag_ctx *c, uint32_t ci, uint32_t r, uint64_t off, uint64_t call, uint32_t floor_tier,
+               Action &a, ha_rag_chunk_trace &tr, ha_rag_load_stats &st)
+{
+    const uint64_t D = c->cfg.head_dim;
+    Chunk &ch = c->chunks[ci];
+    ch.count += 1;
+    const uint32_t found = (uint32_t)ch.fastest();
+    a = Action{ci, r, off, Action::COLD, (uint8_t)found, ch.slot[found], HA_RAG_TIER_NONE, -1};
+    std::memset(&tr, 0, sizeof tr);
+    tr.tok_off = off;
+    tr.evicted_id = HA_RAG_NO_CHUNK;
+    tr.found_tier = (uint8_t)found;
+    tr.placed_tier = HA_RAG_TIER_NONE;
+    tier_touch(c, found, ci);
+    switch (found) {
+    case HA_RAG_TIER_HBM:
+        a.kind = ch.made_by[HA_RAG_TIER_HBM] == call ? Action::HOT_LATE : Action::HOT_EARLY;
+        ++st.n_hbm_hits;
+        break;
+    case HA_RAG_TIER_PINNED: ++st.n_pinned_hits; break;
+    case HA_RAG_TIER_PAGEABLE:
+        ++st.n_pageable_hits;
+        st.bytes_host_copied += ch.bytes;
+        break;
+    default:
+        ++st.n_disk_hits;
+        st.bytes_disk_read += ch.bytes;
+        break;
+    }
+    if (found != HA_RAG_TIER_HBM) {
+        st.bytes_h2d += ch.bytes;
+        // the list the chunk's rank belongs to says where a copy should be kept;
+        // only a tier faster than the one it was found in gets one
+        uint32_t want = ch.rank == kNoRank ? HA_RAG_TIER_DISK : c->list_of(ch.rank);
+        if (want > floor_tier) want = floor_tier;  // HA_RAG_TIER_DISK = no floor
+        if (want < found && c->slab[want][ch.prec].registered()) {
+            uint64_t ev;
+            const int32_t slot = tier_acquire(c, want, ch.prec, &ev, call);
+            if (slot >= 0) {
+                tier_attach(c, want, ci, slot);
+                ch.made_by[want] = call;
+                a.place_tier = (uint8_t)want;
+                a.place_slot = slot;
+                tr.placed_tier = (uint8_t)want;
+                tr.evicted_id = ev;
+                if (ev != HA_RAG_NO_CHUNK) ++st.n_evicted;
+                if (want == HA_RAG_TIER_HBM) {
+                    tr.promoted = 1;
+                    ++st.n_promoted;
+                    st.bytes_d2d += ch.bytes;
+                } else {
+                    ++st.n_placed_host;
+                    st.bytes_host_copied += ch.bytes;
+                }
+            } else {
+                tr.promote_skipped = 1;
+                ++st.n_promote_skipped;
+            }
+        }
+    }
+    // Pinned copy that stays where it is: unless pinned_dma is set the kernel reads it
+    // over the link itself (no staging, no copy stream).  A pinned copy written by this very
+    // call is read after the transfers, which is when its bytes are in place.
+    if (found == HA_RAG_TIER_PINNED && !c->cfg.pinned_dma && a.place_tier == HA_RAG_TIER_NONE)
+        a.kind = ch.made_by[HA_RAG_TIER_PINNED] == call ? Action::HOT_LATE : Action::HOT_EARLY;
+    if (ch.part != kPartV) st.tokens += ch.n_tokens;  // rows of the key plane
+    st.packed_bytes_read += ch.bytes;
+    st.bf16_bytes_written +=
+        (uint64_t)ch.n_tokens * (ch.part == kPartKV ? c->n_tiles : c->n_tiles / 2) * D * 2ull;
+}
+
 int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Request *reqs,
               uint32_t n_req, uint32_t n, hipStream_t s, ha_rag_load_stats *stats,
               ha_rag_chunk_trace *trace)
@@ -197,73 +273,11 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
         PlaneCursor cur(rq.base);
         for (uint32_t i = rq.begin; i < rq.end; ++i) {
             const uint32_t ci = cis[i];
-            Chunk &ch = c->chunks[ci];
-            ch.count += 1;
             uint64_t off = 0;
-            (void)cur.place(ch.part, ch.n_tokens, &off);  // checked above
-            const uint32_t found = (uint32_t)ch.fastest();
-            Action a{ci, r, off, Action::COLD, (uint8_t)found, ch.slot[found], HA_RAG_TIER_NONE, -1};
+            (void)cur.place(c->chunks[ci].part, c->chunks[ci].n_tokens, &off);  // checked above
+            Action a;
             ha_rag_chunk_trace tr;
-            std::memset(&tr, 0, sizeof tr);
-            tr.tok_off = off;
-            tr.evicted_id = HA_RAG_NO_CHUNK;
-            tr.found_tier = (uint8_t)found;
-            tr.placed_tier = HA_RAG_TIER_NONE;
-            tier_touch(c, found, ci);
-            switch (found) {
-            case HA_RAG_TIER_HBM:
-                a.kind = ch.made_by[HA_RAG_TIER_HBM] == call ? Action::HOT_LATE : Action::HOT_EARLY;
-                ++st.n_hbm_hits;
-                break;
-            case HA_RAG_TIER_PINNED: ++st.n_pinned_hits; break;
-            case HA_RAG_TIER_PAGEABLE:
-                ++st.n_pageable_hits;
-                st.bytes_host_copied += ch.bytes;
-                break;
-            default:
-                ++st.n_disk_hits;
-                st.bytes_disk_read += ch.bytes;
-                break;
-            }
-            if (found != HA_RAG_TIER_HBM) {
-                st.bytes_h2d += ch.bytes;
-                // the list the chunk's rank belongs to says where a copy should be kept;
-                // only a tier faster than the one it was found in gets one
-                const uint32_t want = ch.rank == kNoRank ? HA_RAG_TIER_DISK : c->list_of(ch.rank);
-                if (want < found && c->slab[want][ch.prec].registered()) {
-                    uint64_t ev;
-                    const int32_t slot = tier_acquire(c, want, ch.prec, &ev, call);
-                    if (slot >= 0) {
-                        tier_attach(c, want, ci, slot);
-                        ch.made_by[want] = call;
-                        a.place_tier = (uint8_t)want;
-                        a.place_slot = slot;
-                        tr.placed_tier = (uint8_t)want;
-                        tr.evicted_id = ev;
-                        if (ev != HA_RAG_NO_CHUNK) ++st.n_evicted;
-                        if (want == HA_RAG_TIER_HBM) {
-                            tr.promoted = 1;
-                            ++st.n_promoted;
-                            st.bytes_d2d += ch.bytes;
-                        } else {
-                            ++st.n_placed_host;
-                            st.bytes_host_copied += ch.bytes;
-                        }
-                    } else {
-                        tr.promote_skipped = 1;
-                        ++st.n_promote_skipped;
-                    }
-                }
-            }
-            // Pinned copy that stays where it is: unless pinned_dma is set the kernel reads it
-            // over the link itself (no staging, no copy stream).  A pinned copy written by this very
-            // call is read after the transfers, which is when its bytes are in place.
-            if (found == HA_RAG_TIER_PINNED && !c->cfg.pinned_dma && a.place_tier == HA_RAG_TIER_NONE)
-                a.kind = ch.made_by[HA_RAG_TIER_PINNED] == call ? Action::HOT_LATE : Action::HOT_EARLY;
-            if (ch.part != kPartV) st.tokens += ch.n_tokens;  // rows of the key plane
-            st.packed_bytes_read += ch.bytes;
-            st.bf16_bytes_written +=
-                (uint64_t)ch.n_tokens * (ch.part == kPartKV ? c->n_tiles : c->n_tiles / 2) * D * 2ull;
+            alg2_step(c, ci, r, off, call, HA_RAG_TIER_DISK, a, tr, st);
             acts.push_back(a);
             if (trace) trace[i] = tr;
         }
@@ -433,6 +447,118 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     return HA_RAG_OK;
 }
 
+
+// Algorithm 2 step 2 without the decode: the same bookkeeping as a load, and the bytes of every
+// copy it books are moved, but no cache is written.  A copy booked in HBM is filled by one
+// host -> device copy straight into its slot (from the pinned copy, or from a bounce buffer that
+// a pageable copy or a file was read into), so no staging slot is involved.
+int place_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, uint32_t n, uint32_t floor_tier,
+               hipStream_t s, ha_rag_load_stats *stats, ha_rag_chunk_trace *trace)
+{
+    std::vector<uint32_t> cis(n);
+    for (uint32_t i = 0; i < n; ++i) {
+        Chunk *ch = find_chunk(c, ids[i], &cis[i]);
+        if (!ch) return HA_RAG_ENOENT;
+        if (tags && tags[i] != ch->prec) return HA_RAG_EFORMAT;
+        const int f = ch->fastest();
+        if (f < 0) return HA_RAG_ENOENT;
+        if (f >= (int)HA_RAG_TIER_PAGEABLE &&
+            (c->bnc.size() < 2 || c->io_bytes(ch->bytes) > c->bounce_slot_bytes))
+            return HA_RAG_ENOSPC;
+    }
+    if (c->cfg.rerank_interval && c->n_loads && (c->n_loads % c->cfg.rerank_interval) == 0)
+        rerank_locked(c);
+    ++c->n_loads;
+
+    ha_rag_load_stats st;
+    std::memset(&st, 0, sizeof st);
+    std::vector<Action> acts(n);
+    const uint64_t call = ++c->call_seq;
+    for (uint32_t i = 0; i < n; ++i) {
+        ha_rag_chunk_trace tr;
+        alg2_step(c, cis[i], 0, 0, call, floor_tier, acts[i], tr, st);
+        if (trace) trace[i] = tr;
+    }
+    // the byte counters of a load do not apply: count what this call moves
+    st.n_chunks = n;
+    st.tokens = 0;
+    st.bytes_h2d = st.bytes_d2d = st.packed_bytes_read = st.bf16_bytes_written = 0;
+    st.bytes_disk_read = st.bytes_host_copied = 0;
+
+    struct Undo {  // copies booked above but never written must not stay in the books
+        ha_rag_ctx *c;
+        std::vector<Action> &acts;
+        std::vector<uint8_t> written;
+        bool ok = false;
+        ~Undo()
+        {
+            if (ok) return;
+            for (size_t k = 0; k < acts.size(); ++k) {
+                const Action &a = acts[k];
+                if (a.place_tier == HA_RAG_TIER_NONE || written[k]) continue;
+                if (c->chunks[a.ci].slot[a.place_tier] == a.place_slot) tier_detach(c, a.place_tier, a.ci);
+            }
+        }
+    } undo{c, acts, std::vector<uint8_t>(acts.size(), 0)};
+
+    for (uint32_t k = 0; k < n; ++k) {
+        const Action &a = acts[k];
+        if (a.place_tier == HA_RAG_TIER_NONE) continue;
+        const Chunk &ch = c->chunks[a.ci];
+        const uint8_t *src = nullptr;
+        size_t bidx = 0;
+        bool bounced = false;
+        if (a.src_tier == HA_RAG_TIER_PINNED) {
+            src = c->slab[HA_RAG_TIER_PINNED][ch.prec].ptr(a.src_slot);
+        } else {
+            int rc = acquire_bounce(c, &bidx);
+            if (rc) return rc;
+            uint8_t *bp = c->bounce + bidx * c->bounce_slot_bytes;
+            rc = fill_bounce(c, ch, a.src_tier, a.src_slot, bp);
+            if (rc) return rc;
+            if (a.src_tier == HA_RAG_TIER_PAGEABLE) st.bytes_host_copied += ch.bytes;
+            else st.bytes_disk_read += ch.bytes;
+            bounced = true;
+            src = bp;
+            if (a.place_tier != HA_RAG_TIER_HBM) {
+                Slab &ds = c->slab[a.place_tier][ch.prec];
+                rc = before_host_write(c, ds.use[a.place_slot]);
+                if (rc) return rc;
+                if (!c->dry()) std::memcpy(ds.ptr(a.place_slot), bp, ch.bytes);
+                st.bytes_host_copied += ch.bytes;
+                undo.written[k] = 1;
+            }
+        }
+        if (a.place_tier == HA_RAG_TIER_HBM) {
+            Slab &hs = c->slab[HA_RAG_TIER_HBM][ch.prec];
+            int rc = before_write(c, hs.use[a.place_slot], s);
+            if (rc) return rc;
+            if (a.src_tier == HA_RAG_TIER_PINNED) {
+                SlotUse &pu = c->slab[HA_RAG_TIER_PINNED][ch.prec].use[a.src_slot];
+                if (pu.has_writer) {  // a device -> host copy may still be filling the slot
+                    rc = wait_for(c, s, pu.writer);
+                    if (rc) return rc;
+                }
+                if (std::find(pu.readers.begin(), pu.readers.end(), s) == pu.readers.end()) pu.readers.push_back(s);
+            }
+            if (!c->dry()) {
+                HIPCHK(c, hipMemcpyAsync(hs.ptr(a.place_slot), src, ch.bytes, hipMemcpyHostToDevice, s));
+                if (bounced) {
+                    HIPCHK(c, hipEventRecord(c->bnc[bidx].h2d_done, s));
+                    c->bnc[bidx].busy = true;
+                }
+            }
+            st.bytes_h2d += ch.bytes;
+            undo.written[k] = 1;
+        }
+    }
+    int rc = mark_stream(c, s);
+    if (rc) return rc;
+    undo.ok = true;
+    if (stats) *stats = st;
+    return HA_RAG_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -542,6 +668,18 @@ int ha_rag_load_batch(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags,
     }
     std::lock_guard<std::mutex> g(c->mu);
     return load_impl(c, ids, tags, reqs.data(), n_requests, n, (hipStream_t)stream, stats, trace);
+}
+
+int ha_rag_place_chunks(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, uint32_t n,
+                        uint32_t flags, void *stream, ha_rag_load_stats *stats,
+                        ha_rag_chunk_trace *trace)
+{
+    if (!c || (n && !ids) || n > HA_RAG_MAX_REQUEST_CHUNKS || (flags & ~(uint32_t)HA_RAG_PLACE_DEVICE_VISIBLE))
+        return HA_RAG_EINVAL;
+    std::lock_guard<std::mutex> g(c->mu);
+    return place_impl(c, ids, tags, n,
+                      (flags & HA_RAG_PLACE_DEVICE_VISIBLE) ? HA_RAG_TIER_PINNED : HA_RAG_TIER_DISK,
+                      (hipStream_t)stream, stats, trace);
 }
 
 }  // extern "C"

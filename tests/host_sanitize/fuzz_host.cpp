@@ -181,6 +181,15 @@ int main(int argc, char **argv)
                 REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_EIO || rc == HA_RAG_EFORMAT || rc == HA_RAG_EINVAL);
                 if (rc != HA_RAG_OK) REQUIRE(ha_rag_pool_load_index(other, good, &n_loaded) == HA_RAG_OK);
                 REQUIRE(ha_rag_destroy(other) == HA_RAG_OK);
+            } else if (what < 81 && !known.empty()) {  // Algorithm 2 without the decode
+                uint64_t ids3[5];
+                const uint32_t k = (uint32_t)(rnd() % 6);
+                for (uint32_t i = 0; i < k && i < 5; ++i) ids3[i] = rnd() % 30 == 0 ? 999 : known[rnd() % known.size()];
+                ha_rag_load_stats st;
+                ha_rag_chunk_trace tr[5];
+                int rc = ha_rag_place_chunks(ctx, ids3, nullptr, k < 5 ? k : 5, (uint32_t)(rnd() % 2), nullptr, &st, tr);
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOENT || rc == HA_RAG_ENOSPC);
+                if (rc == HA_RAG_OK) REQUIRE(st.n_kernel_launches == 0 && st.bf16_bytes_written == 0);
             } else if (what < 82 && !known.empty()) {
                 int rc = ha_rag_pool_promote(ctx, known[rnd() % known.size()], nullptr);
                 REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOSPC || rc == HA_RAG_ENOENT);

@@ -83,6 +83,14 @@ int main(int argc, char **argv)
                     REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOENT);
                     if (rc == HA_RAG_OK) chunks.fetch_add(n);
                 }
+            } else if (what < 22) {  // placement without a decode, every chunk ends up device-visible
+                uint64_t ids[3];
+                const uint32_t n = 1 + (uint32_t)(next(s) % 3);
+                for (uint32_t i = 0; i < n; ++i) ids[i] = next(s) % 32;
+                ha_rag_load_stats st;
+                REQUIRE(ha_rag_place_chunks(ctx, ids, nullptr, n, (uint32_t)(next(s) % 2), nullptr, &st, nullptr) == HA_RAG_OK);
+                REQUIRE(st.n_chunks == n);
+                chunks.fetch_add(n);
             } else if (what < 60) {
                 uint64_t ids[6];
                 const uint32_t n = 1 + (uint32_t)(next(s) % 6);

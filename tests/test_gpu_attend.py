@@ -424,3 +424,77 @@ def test_the_most_requests_one_call_takes_and_one_more():
         ctx.attend_workspace_bytes(too_many, 1)
     assert e.value.code == B.EINVAL
     ctx.destroy()
+
+
+@pytest.mark.parametrize("o_direct", [False, True])
+def test_place_then_attend_with_every_chunk_starting_in_a_file(tmp_path, o_direct):
+    """Algorithm 2 without the decode, then attention over the chunks where it left them: HBM
+    copies filled straight from bounce buffers or pinned copies, pinned copies read over the
+    link.  Afterwards a load of the same chunks must still equal the oracle's cache (the copies
+    hold the right bytes)."""
+    L, H, D, T, g = 2, 2, 128, 96, 64
+    ORC = {B.PREC_INT4: 4, B.PREC_FP8_E4M3: 43}
+    n = 10
+    precs_all = [B.PREC_INT4, B.PREC_FP8_E4M3]
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=200_000,
+                    tau_pin_ppm=200_000, tau_page_ppm=200_000, disk_o_direct=o_direct)
+    biggest, keep = 0, []
+    for p in precs_all:
+        slot = (ctx.chunk_bytes(p, T) + 4095) // 4096 * 4096
+        biggest = max(biggest, slot)
+        bufs = [torch.zeros(slot * 1, dtype=torch.uint8, device="cuda"), torch.zeros(slot * 4, dtype=torch.uint8).pin_memory(),
+                torch.zeros(slot * 1, dtype=torch.uint8)]
+        keep += bufs
+        ctx.register_slab(B.TIER_HBM, p, bufs[0])
+        ctx.register_slab(B.TIER_PINNED, p, bufs[1])
+        ctx.register_slab(B.TIER_PAGEABLE, p, bufs[2])
+        try:
+            ctx.register_disk(p, str(tmp_path / f"pool_{p}.bin"), slot * n)
+        except B.HaRagError as e:
+            if o_direct and e.code == B.EIO:
+                pytest.skip("this filesystem refuses O_DIRECT")
+            raise
+    ctx.register_staging(torch.zeros(biggest * 2, dtype=torch.uint8, device="cuda"))
+    ctx.register_bounce(torch.zeros(biggest * 2, dtype=torch.uint8).pin_memory())
+    tokens = [T - 5 * (i % 4) for i in range(n)]
+    precs = [precs_all[i % 2] for i in range(n)]
+    packed = [codec.quantize_pack_chunk(wl.kv_chunk(L, H, D, tokens[i], 1300 + i), ORC[p], g)[0]
+              for i, p in enumerate(precs)]
+    for i in range(n):
+        ctx.pool_insert(i, precs[i], tokens[i], packed[i], B.TIER_DISK)
+    ctx.set_counts(list(range(n)), [100 - i for i in range(n)])
+    ctx.rerank()            # lists: GPU {0,1}, PIN {2,3}, PAGE {4,5}, DISK the rest
+
+    ids = [0, 2, 4, 7, 1, 3, 8]
+    # without the floor the chunks of the PAGE and DISK lists stay out of the kernels' reach
+    st, tr = ctx.place_chunks(ids, want_trace=True)
+    assert [t.found_tier for t in tr] == [3] * 7
+    assert [t.placed_tier for t in tr] == [0, 1, 2, 255, 0, 1, 255]
+    n_qh, scale, layer = 8, 0.09, 1
+    qw = q_words(3, n_qh, D, 1400)
+    q_d = torch.from_numpy(qw.view(np.int16)).cuda()
+    out_d = torch.full((3, n_qh, D), float("nan"), dtype=torch.float32, device="cuda")
+    lse_d = torch.full((3, n_qh), float("nan"), dtype=torch.float32, device="cuda")
+    call = [(ids, q_d, out_d, lse_d, 3)]
+    with pytest.raises(B.HaRagError) as e:
+        ctx.attend_chunks_workspace_bytes(call, n_qh)
+    assert e.value.code == B.ENOENT
+    st, tr = ctx.place_chunks(ids, device_visible=True, want_trace=True)
+    assert [t.found_tier for t in tr] == [0, 1, 2, 3, 0, 1, 3]
+    assert [t.placed_tier for t in tr] == [255, 255, 1, 1, 255, 255, 1]
+    nb = ctx.attend_chunks_workspace_bytes(call, n_qh)
+    ws = torch.full((nb // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.attend_chunks(call, layer, n_qh, scale, ws, nb)
+    torch.cuda.synchronize()
+    cache, _ = codec.load_chunks(packed, (L, H, D), tokens, [ORC[p] for p in precs], [g] * n, ids)
+    n_kv = sum(tokens[i] for i in ids)
+    ref_out, ref_lse, spread = A.attend(cache, layer, n_kv, qw, scale)
+    check(out_d.cpu().numpy(), lse_d.cpu().numpy(), ref_out, ref_lse, spread,
+          score_bound(cache, layer, n_kv, qw, scale, H))
+    # the copies hold the chunks' bytes: a load served from them equals the oracle's cache
+    out = torch.zeros((L, 2, H, n_kv, D), dtype=torch.int16, device="cuda")
+    st, tr = ctx.load_chunks(ids, out, n_kv, want_trace=True)
+    torch.cuda.synchronize()
+    assert all(t.found_tier in (0, 1) for t in tr)
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), cache)
+    ctx.destroy()

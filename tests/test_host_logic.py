@@ -873,3 +873,58 @@ def test_attend_chunks_reads_hbm_or_pinned_copies_and_counts_on_request():
     rc = B.lib().ha_rag_attend_chunks(ctx._h, None, None, 0, 0, 8, 0.1, 2, None, 0, None)
     assert rc == B.EINVAL                                              # unknown flag
     ctx.destroy()
+
+
+def test_place_chunks_is_algorithm_2_without_the_decode():
+    """The same sequence as the four-tier trace test, with placement-only calls and loads
+    mixed, with and without the floor that keeps every chunk device-visible: lookups, placements,
+    evictions and residency equal the oracle's after every call."""
+    taus = [50_000, 50_000, 100_000]
+    n, caps = 100, (3, 4, 6)
+    ctx = _ctx4(n, caps, taus)
+    ctx.set_counts(list(range(n)), [1000 - c for c in range(n)])
+    ctx.rerank()
+    sim = pl.TierSim(list(range(n)), taus, caps)
+    rng = np.random.default_rng(11)
+    hot = rng.integers(0, 25, 500)
+    cold = rng.integers(0, n, 500)
+    seq = np.where(rng.random(500) < 0.8, hot, cold).tolist()
+    tiers = (B.TIER_HBM, B.TIER_PINNED, B.TIER_PAGEABLE)
+    cb = ctx.chunk_bytes(B.PREC_INT4, 128)
+    kinds = set()
+    for k, c in enumerate(seq):
+        mode = k % 3                                           # load, place, place with the floor
+        if mode == 0:
+            st, tr = ctx.load_chunks([c], FAKE_HBM, 128, want_trace=True)
+            found, placed = sim.access(c)
+        else:
+            st, tr = ctx.place_chunks([c], device_visible=(mode == 2), want_trace=True)
+            found, placed = sim.access(c, floor=pl.TierSim.PIN if mode == 2 else None)
+            assert st["n_kernel_launches"] == 0 and st["bf16_bytes_written"] == 0 and st["bytes_d2d"] == 0
+            to = placed[0][0] if placed else None
+            assert st["bytes_h2d"] == (cb if to == 0 else 0)
+            assert st["bytes_disk_read"] == (cb if placed and found == 3 else 0)
+            assert st["bytes_host_copied"] == cb * ((1 if placed and found == 2 else 0) + (1 if to in (1, 2) else 0))
+            if mode == 2:
+                kinds.add((found, to))
+        assert tr[0].found_tier == found, (k, c)
+        if placed:
+            assert tr[0].placed_tier == placed[0][0]
+            assert tr[0].evicted_id == (placed[0][1] if placed[0][1] is not None else B.NO_CHUNK)
+        else:
+            assert tr[0].placed_tier == B.TIER_NONE
+        for t in tiers:
+            assert ctx.pool_lru(t) == sim.resident(t), (k, c, t)
+    # with the floor, chunks of the PAGE and DISK lists found in a file or in pageable memory went to pinned memory
+    assert (3, 1) in kinds and (2, 1) in kinds and (3, 0) in kinds
+    assert sum(ctx.pool_query(c).count for c in range(n)) == sum(1000 - c for c in range(n)) + len(seq)
+    # several chunks in one call, a repeat among them; afterwards every one of them can be attended in place
+    st, tr = ctx.place_chunks([70, 71, 70, 2], device_visible=True, want_trace=True)
+    assert all(ctx.pool_query(c).in_hbm or ctx.pool_query(c).in_pinned for c in (70, 71, 2))
+    assert tr[2].found_tier == B.TIER_PINNED and tr[2].placed_tier == B.TIER_NONE
+    with pytest.raises(B.HaRagError) as e:
+        ctx.place_chunks([1, 1000])
+    assert e.value.code == B.ENOENT
+    rc = B.lib().ha_rag_place_chunks(ctx._h, None, None, 0, 4, None, None, None)
+    assert rc == B.EINVAL
+    ctx.destroy()

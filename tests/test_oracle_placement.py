@@ -92,3 +92,16 @@ def test_zipf_mass_closed_form(golden_dir):
     assert all(len(set(r)) == 8 for r in req.tolist())
     share = float(np.mean(req < 1000))
     assert abs(share - 0.74) < 0.03                   # distinct-per-request trims the head a little
+
+
+def test_floor_option_keeps_every_accessed_chunk_out_of_the_slow_tiers():
+    """Hand-worked: 20 chunks, lists GPU {0,1}, PIN {2,3}, PAGE {4..7}, DISK the rest; queues of 2."""
+    sim = pl.TierSim(list(range(20)), [100_000, 100_000, 200_000], (2, 2, 2))
+    assert sim.access(12) == (pl.TierSim.DISK, [])                         # the algorithm leaves it on disk
+    assert sim.access(12, floor=pl.TierSim.PIN) == (pl.TierSim.DISK, [(pl.TierSim.PIN, None)])
+    assert sim.access(5, floor=pl.TierSim.PIN) == (pl.TierSim.DISK, [(pl.TierSim.PIN, None)])   # PAGE list -> pinned
+    assert sim.access(0, floor=pl.TierSim.PIN) == (pl.TierSim.DISK, [(pl.TierSim.GPU, None)])   # faster lists unchanged
+    assert sim.access(13, floor=pl.TierSim.PIN) == (pl.TierSim.DISK, [(pl.TierSim.PIN, 12)])    # LRU of the full queue
+    assert sim.access(5, floor=pl.TierSim.PIN) == (pl.TierSim.PIN, [])
+    assert sim.access(6, floor=pl.TierSim.PAGE) == (pl.TierSim.DISK, [(pl.TierSim.PAGE, None)])
+    assert sim.resident(pl.TierSim.PIN) == [13, 5] and sim.resident(pl.TierSim.PAGE) == [6]
