@@ -222,7 +222,6 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
               uint32_t n_req, uint32_t n, hipStream_t s, ha_rag_load_stats *stats,
               ha_rag_chunk_trace *trace)
 {
-    const uint64_t D = c->cfg.head_dim;
     // ---- checks: nothing changes before all of them pass --------------------
     std::vector<uint32_t> cis(n);
     for (uint32_t r = 0; r < n_req; ++r) {
