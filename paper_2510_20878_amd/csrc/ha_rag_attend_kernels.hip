@@ -103,8 +103,8 @@ __device__ __forceinline__ u32x4 plane_raw(const u32x4 *w, int j)
 __device__ __forceinline__ float neg_inf() { return -__builtin_huge_valf(); }
 
 // orders the LDS accesses of one wave: what its lanes wrote before is visible to all its
-// lanes after (LDS instructions of a wave execute in issue order; this keeps the compiler
-// from moving them and waits for the writes)
+// lanes after.  The hardware executes the LDS instructions of a wave in issue order, so
+// nothing has to be waited for; the fences keep the compiler from moving accesses across
 __device__ __forceinline__ void wave_lds_sync()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
