@@ -498,3 +498,43 @@ def test_place_then_attend_with_every_chunk_starting_in_a_file(tmp_path, o_direc
     assert all(t.found_tier in (0, 1) for t in tr)
     assert np.array_equal(out.cpu().numpy().view(np.uint16), cache)
     ctx.destroy()
+
+
+def test_extreme_scores_and_values():
+    """Query rows that are zero, tiny and huge; keys that tie, one that dominates, a masked tail;
+    values of both signs up to 1e30: the running maximum, its rescaling and the normaliser must
+    hold up (16-bit chunks, so that the awkward values survive storage unchanged)."""
+    L, H, D, n_qh, T = 1, 1, 128, 4, 70                      # 70 tokens: a ragged fifth block
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal((L, 2, H, T, D)).astype(np.float32)
+    x[0, 0, 0, 10] = x[0, 0, 0, 11]                          # two identical keys
+    x[0, 0, 0, 40] *= 30.0                                   # a key far out
+    x[0, 0, 0, 69] *= 50.0                                   # the last valid token dominates some rows
+    x[0, 1, 0, 5] = 1e30
+    x[0, 1, 0, 6] = -1e30
+    x[0, 1, 0, 20, :64] = 0.0
+    src = wl.f32_to_bf16_words(x)
+    q = rng.standard_normal((4, n_qh, D)).astype(np.float32)
+    q[0, 0] = 0.0
+    q[1, 1] *= 1e-20
+    q[2, 2] *= 40.0
+    q[3, 3] = x[0, 0, 0, 69] / 50.0                          # aligned with the far key
+    qw = wl.f32_to_bf16_words(q)
+    pk = codec.quantize_pack_chunk(src, 16)[0]
+    ctx = B.Context(L, H, D, T)
+    q_d = torch.from_numpy(qw.view(np.int16)).cuda()
+    out_d = torch.full((4, n_qh, D), float("nan"), dtype=torch.float32, device="cuda")
+    lse_d = torch.full((4, n_qh), float("nan"), dtype=torch.float32, device="cuda")
+    call = [([(dev_u8(pk), T, B.PREC_16, 0)], q_d, out_d, lse_d, 4)]
+    nb = ctx.attend_workspace_bytes(call, n_qh)
+    ws = torch.full((nb // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    for scale in (0.088, 3.0):
+        ctx.attend_packed(call, 0, n_qh, scale, ws, nb)
+        torch.cuda.synchronize()
+        cache, _ = codec.load_chunks([pk], (L, H, D), [T], [16], [128], [0])
+        ref_out, ref_lse, spread = A.attend(cache, 0, T, qw, scale)
+        out, lse = out_d.cpu().numpy(), lse_d.cpu().numpy()
+        assert np.all(np.isfinite(out)) and np.all(np.isfinite(lse))
+        check(out, lse, ref_out, ref_lse, spread, score_bound(cache, 0, T, qw, scale, H))
+        assert abs(lse[0, 0] - np.log(T)) < 1e-5              # a zero query: uniform weights
+    ctx.destroy()
