@@ -145,8 +145,9 @@ struct AttendLds {
     static constexpr uint32_t kBytes = kExchange > kCombine ? kExchange : kCombine;
 };
 
-// KP, VP: the formats of the chunk's keys and of its values (the same for a chunk stored whole)
-template <uint32_t KP, uint32_t VP, int MTW>
+// KP, VP: the formats of the chunk's keys and of its values (the same for a chunk stored whole).
+// NARROW: the instance belongs to the kernel that runs three waves per SIMD (168 registers).
+template <uint32_t KP, uint32_t VP, int MTW, bool NARROW>
 __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c,
                                             uint32_t h, uint32_t s, uint32_t mtg, uint8_t *lds_all,
                                             float (*sm)[MTW * 16], float (*sl)[MTW * 16])
@@ -341,7 +342,9 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c
     // of the bytes of a 16-bit one, so narrow formats get a deeper ring.  The loop is unrolled
     // over the ring so that no block is copied from one set to another.
     constexpr uint32_t kWordsKV = FK::kWords + FV::kWords;
-    constexpr int kStages = MTW > 1 ? 2 : kWordsKV <= 2 ? 4 : kWordsKV <= 4 ? 3 : 2;  // MTW 2: registers are short
+    constexpr int kStages = MTW > 1 ? 2  // registers are short
+                            : NARROW ? (kWordsKV <= 2 ? 3 : 2)
+                                     : (kWordsKV <= 2 ? 4 : kWordsKV <= 4 ? 3 : 2);
     BlockRegs<KP, VP> ring[kStages];
     uint32_t b = b0 + wave;
 #pragma unroll
@@ -417,10 +420,40 @@ blocks_done:
     }
 }
 
-// (the second bound is waves per SIMD: with two the accumulators stay in ordinary vector
-// registers, with no copies to and from the accumulation registers around the rescale branch)
-template <int MTW>
-__global__ void __launch_bounds__(64 * kAttendWaves, 2) k6_attend_partial(const K6Params p)
+// One instance per pair of formats (whole chunks use the six on the diagonal).  The kernel for
+// narrow formats leaves out every pair with a 16-bit side: those need more registers than three
+// waves per SIMD leave.
+template <uint32_t KP, uint32_t VP, int MTW, bool NARROW>
+__device__ __forceinline__ void attend_pair(const AttendHdr &hdr, const K6Chunk &c, uint32_t h, uint32_t s,
+                                            uint32_t mtg, uint8_t *lds, float (*sm)[MTW * 16],
+                                            float (*sl)[MTW * 16])
+{
+    if constexpr (!(NARROW && (KP == kP16 || VP == kP16)))
+        attend_unit<KP, VP, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl);
+}
+
+template <uint32_t KP, int MTW, bool NARROW>
+__device__ __forceinline__ void attend_values(const AttendHdr &hdr, const K6Chunk &c, uint32_t h, uint32_t s,
+                                              uint32_t mtg, uint8_t *lds, float (*sm)[MTW * 16],
+                                              float (*sl)[MTW * 16])
+{
+    switch ((c.info >> 8) & 0xFu) {
+    case kP16: attend_pair<KP, kP16, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    case kInt8: attend_pair<KP, kInt8, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    case kInt4: attend_pair<KP, kInt4, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    case kE4M3: attend_pair<KP, kE4M3, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    case kE5M2: attend_pair<KP, kE5M2, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    default: attend_pair<KP, kGSE8, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    }
+}
+
+// The second launch bound is waves per SIMD.  With two (256 registers) the accumulators stay in
+// ordinary vector registers, with no copies to and from the accumulation registers around the
+// rescale branch, and every pair of formats fits.  Without a 16-bit side one query tile fits
+// in the 168 registers of three waves per SIMD, which measured 10 % faster (the kernel is bound
+// by instruction issue); 16-bit pairs spill there and lose a quarter.
+template <int MTW, bool NARROW>
+__global__ void __launch_bounds__(64 * kAttendWaves, NARROW ? 3 : 2) k6_attend_partial(const K6Params p)
 {
     __shared__ __attribute__((aligned(16))) uint8_t lds[AttendLds<MTW>::kBytes];
     __shared__ float sm[kAttendWaves][MTW * 16], sl[kAttendWaves][MTW * 16];
@@ -448,25 +481,14 @@ __global__ void __launch_bounds__(64 * kAttendWaves, 2) k6_attend_partial(const 
     const uint32_t mtg = u % n_mtg;
     const uint32_t hs = u / n_mtg;
     const uint32_t s = hs % c.n_split, h = hs / c.n_split;
-    // one instance per pair of formats: whole chunks use the six on the diagonal
-#define HA_RAG_ATTEND_V(KP)                                                                         \
-    switch ((c.info >> 8) & 0xFu) {                                                                 \
-    case kP16: attend_unit<KP, kP16, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;                  \
-    case kInt8: attend_unit<KP, kInt8, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;                \
-    case kInt4: attend_unit<KP, kInt4, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;                \
-    case kE4M3: attend_unit<KP, kE4M3, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;                \
-    case kE5M2: attend_unit<KP, kE5M2, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;                \
-    default: attend_unit<KP, kGSE8, MTW>(hdr, c, h, s, mtg, lds, sm, sl); break;                   \
-    }
     switch (c.info & 0xFu) {
-    case kP16: HA_RAG_ATTEND_V(kP16) break;
-    case kInt8: HA_RAG_ATTEND_V(kInt8) break;
-    case kInt4: HA_RAG_ATTEND_V(kInt4) break;
-    case kE4M3: HA_RAG_ATTEND_V(kE4M3) break;
-    case kE5M2: HA_RAG_ATTEND_V(kE5M2) break;
-    default: HA_RAG_ATTEND_V(kGSE8) break;
+    case kP16: attend_values<kP16, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    case kInt8: attend_values<kInt8, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    case kInt4: attend_values<kInt4, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    case kE4M3: attend_values<kE4M3, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    case kE5M2: attend_values<kE5M2, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    default: attend_values<kGSE8, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
     }
-#undef HA_RAG_ATTEND_V
 }
 
 hipError_t launch_k6(K6Params &p, hipStream_t stream)
@@ -478,6 +500,7 @@ hipError_t launch_k6(K6Params &p, hipStream_t stream)
         return hipErrorInvalidValue;
     const uint32_t G = p.n_q_heads / p.n_kv_heads;
     uint32_t max_mt = 1;
+    bool narrow = true;  // no 16-bit side in this launch
     for (uint32_t i = 0; i < p.n_chunks; ++i) {
         const K6Chunk &c = p.c[i];
         const uint32_t kprec = c.info & 0xFu, kgsh = (c.info >> 4) & 0xFu;
@@ -492,6 +515,7 @@ hipError_t launch_k6(K6Params &p, hipStream_t stream)
         if ((uint64_t)c.n_split * p.split_blocks * 16u < c.n_tokens) return hipErrorInvalidValue;
         const uint32_t n_mt = (c.n_q * G + 15u) >> 4;
         if (n_mt > max_mt) max_mt = n_mt;
+        if (kprec == kP16 || vprec == kP16) narrow = false;
     }
     // Two tiles (32 query rows) per workgroup is the most that still runs two waves per SIMD
     // (241 vector registers); four tiles at one wave per SIMD measured 35 % slower than two
@@ -507,8 +531,9 @@ hipError_t launch_k6(K6Params &p, hipStream_t stream)
     if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
     p.pad = 0;
     dim3 grid((uint32_t)width, p.n_chunks), block(64 * kAttendWaves);
-    if (p.mtw == 1) hipLaunchKernelGGL((k6_attend_partial<1>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((k6_attend_partial<2>), grid, block, 0, stream, p);
+    if (p.mtw == 2) hipLaunchKernelGGL((k6_attend_partial<2, false>), grid, block, 0, stream, p);
+    else if (narrow) hipLaunchKernelGGL((k6_attend_partial<1, true>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((k6_attend_partial<1, false>), grid, block, 0, stream, p);
     return hipGetLastError();
 }
 

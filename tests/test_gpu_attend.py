@@ -407,6 +407,45 @@ def test_every_pair_of_key_and_value_formats(kp, vp):
     ctx.destroy()
 
 
+@pytest.mark.parametrize("with_16_bit", [True, False])
+def test_every_pair_of_formats_as_documents_of_one_request(with_16_bit):
+    """One launch holds every pair: with 16-bit units among them the launch takes the kernel
+    that fits all pairs, without them the one for narrow formats (launch_k6)."""
+    L, H, D, g, n_qh = 1, 2, 128, 64, 4
+    ORC = [16, 8, 4, 43, 52, 143]
+    precs = range(6) if with_16_bit else range(1, 6)
+    ctx = B.Context(L, H, D, 64, group_int8=g, group_int4=g)
+    grp = lambda p: g if p in (B.PREC_INT8, B.PREC_INT4) else 0
+    packed, tokens, bits, parts, units = [], [], [], [], []
+    for i, (kp, vp) in enumerate((a, b) for a in precs for b in precs):
+        T = 9 + (7 * i) % 40                                     # ragged, one to three blocks
+        src = wl.kv_chunk(L, H, D, T, 900 + i)
+        for part, prec in ((B.PART_K, kp), (B.PART_V, vp)):
+            pk = codec.quantize_pack_half(np.ascontiguousarray(src[:, part - 1]), ORC[prec], g)[0]
+            packed.append(pk)
+            tokens.append(T)
+            bits.append(ORC[prec])
+            parts.append(part)
+            units.append((dev_u8(pk), T, prec, grp(prec), part))
+    n_kv = sum(tokens) // 2
+    for n_q in (1, 5):                                           # 4 and 20 rows: one tile, two tiles
+        qw = q_words(n_q, n_qh, D, 990 + n_q)
+        q_d = torch.from_numpy(qw.view(np.int16)).cuda()
+        out_d = torch.full((n_q, n_qh, D), float("nan"), dtype=torch.float32, device="cuda")
+        lse_d = torch.full((n_q, n_qh), float("nan"), dtype=torch.float32, device="cuda")
+        call = [(units, q_d, out_d, lse_d, n_q)]
+        nb = ctx.attend_workspace_bytes(call, n_qh)
+        ws = torch.full((nb // 4,), float("nan"), dtype=torch.float32, device="cuda")
+        ctx.attend_packed(call, 0, n_qh, 0.1, ws, nb)
+        torch.cuda.synchronize()
+        cache, _ = codec.load_chunks(packed, (L, H, D), tokens, bits, [g] * len(units), list(range(len(units))),
+                                     parts=parts)
+        ref_out, ref_lse, spread = A.attend(cache, 0, n_kv, qw, 0.1)
+        check(out_d.cpu().numpy(), lse_d.cpu().numpy(), ref_out, ref_lse, spread,
+              score_bound(cache, 0, n_kv, qw, 0.1, H))
+    ctx.destroy()
+
+
 def test_the_most_query_tokens_and_the_widest_head_group_one_call_takes():
     # 4096 query tokens of one head group member (4096 query rows = 256 tiles over one chunk)
     run_case((1, 1, 128), [([48], [B.PREC_INT4], 4096)], 0, 1, 0.1, 810)
