@@ -538,10 +538,17 @@ hipError_t launch_k6(K6Params &p, hipStream_t stream)
 }
 
 // ---------------------------------------------------------------------------
-// K7.  One workgroup of 128 threads (one per dim) per (query token, query head).
+// K7.  One workgroup per (query token, query head), made of groups of 32 threads (four dims
+// each).  The groups share the row's records between them, so that a single request with many
+// records (long chunks, fine splits) is merged in one or two rounds of loads instead of record
+// after record; then 128 threads, one per dim, merge the groups' results through LDS.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(128) k7_attend_merge(const K7Params p)
+constexpr uint32_t kMergeGroups = 32;  // at most: 1024 threads
+
+__global__ void __launch_bounds__(32 * kMergeGroups) k7_attend_merge(const K7Params p)
 {
+    __shared__ __attribute__((aligned(16))) float s_acc[kMergeGroups][128];
+    __shared__ float s_m[kMergeGroups], s_l[kMergeGroups];
     // grid: x = row of the request (the grid is as wide as the largest), y = request; the
     // descriptor is fetched at once
     K7Req r = p.r[blockIdx.y];
@@ -555,47 +562,78 @@ __global__ void __launch_bounds__(128) k7_attend_merge(const K7Params p)
     pin(n_kv_heads);
     pin(n_q_heads);
     const uint32_t rr = blockIdx.x;
-    if (rr >= r.n_q * n_q_heads) return;
+    if (rr >= r.n_q * n_q_heads) return;  // the whole workgroup
     const uint32_t qt = rr / n_q_heads, hq = rr - qt * n_q_heads;
     const uint32_t G = n_q_heads / n_kv_heads;
     const uint32_t h = hq / G, gq = hq - h * G;
     const uint32_t mrow = qt * G + gq, mt = mrow >> 4, ri = mrow & 15u;
     const uint32_t n_mt = (r.n_q * G + 15u) >> 4;
-    const uint32_t d = threadIdx.x;
+    const uint32_t d4 = threadIdx.x & 31u, g = threadIdx.x >> 5, n_g = blockDim.x >> 5;  // n_g >= 4
     const uint64_t chunk_stride = (uint64_t)n_kv_heads * r.n_split * n_mt * kAttendRecFloats;
     const float *first = r.part + ((uint64_t)(h * r.n_split) * n_mt + mt) * kAttendRecFloats;
     const uint64_t split_stride = (uint64_t)n_mt * kAttendRecFloats;
 
-    // One pass, eight records at a time: their maxima, sums and this thread's dim are fetched
-    // together (every thread reads the same m and l: broadcast loads), then folded into a
-    // running maximum like the blocks inside a record were.
+    // Group g takes records g, g + n_g, ..., four at a time: their maxima, sums and this
+    // thread's four dims are fetched together (every thread of a group reads the same m and l:
+    // broadcast loads), then folded into a running maximum like the blocks inside a record were.
     const uint32_t n_units = r.n_chunks * r.n_split;  // records are [chunk][head][split][tile]
-    float m_max = neg_inf(), acc = 0.0f, l_sum = 0.0f;
-    for (uint32_t u0 = 0; u0 < n_units; u0 += 8u) {
-        float m[8], l[8], o[8];
+    float m_max = neg_inf(), l_sum = 0.0f;
+    f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (uint32_t u0 = g; u0 < n_units; u0 += 4u * n_g) {
+        float m[4], l[4];
+        f32x4 o[4];
 #pragma unroll
-        for (uint32_t k = 0; k < 8; ++k) {
-            const uint32_t u = u0 + k < n_units ? u0 + k : n_units - 1u;
+        for (uint32_t k = 0; k < 4; ++k) {
+            const bool have = u0 + k * n_g < n_units;
+            const uint32_t u = have ? u0 + k * n_g : n_units - 1u;
             const uint32_t ci = u / r.n_split, sp = u - ci * r.n_split;
             const float *rec = first + ci * chunk_stride + sp * split_stride;
             m[k] = rec[2048 + ri];
-            l[k] = u0 + k < n_units ? rec[2048 + 16 + ri] : 0.0f;
-            o[k] = rec[ri * 128u + d];
+            l[k] = have ? rec[2048 + 16 + ri] : 0.0f;
+            o[k] = *reinterpret_cast<const f32x4 *>(rec + ri * 128u + 4u * d4);
         }
 #pragma unroll
-        for (uint32_t k = 0; k < 8; ++k) {
-            if (l[k] > 0.0f) {  // the same for all threads; an empty record holds no output rows
+        for (uint32_t k = 0; k < 4; ++k) {
+            if (l[k] > 0.0f) {  // the same for the whole group; an empty record holds no output rows
                 const float m_new = __builtin_fmaxf(m_max, m[k]);
                 const float fa = __builtin_amdgcn_exp2f(m_max - m_new);  // 0 at the first record
                 const float fb = __builtin_amdgcn_exp2f(m[k] - m_new);
-                acc = __builtin_fmaf(o[k], fb, acc * fa);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(o[k][e], fb, acc[e] * fa);
                 l_sum = __builtin_fmaf(l[k], fb, l_sum * fa);
                 m_max = m_new;
             }
         }
     }
+    *reinterpret_cast<f32x4 *>(&s_acc[g][4u * d4]) = acc;
+    if (d4 == 0) {
+        s_m[g] = m_max;
+        s_l[g] = l_sum;
+    }
+    __syncthreads();
+    const uint32_t d = threadIdx.x;
+    if (d >= 128u) return;
+    // every group's maximum and sum at once (no branch between the LDS reads), then the weights
+    float gm[kMergeGroups], gl[kMergeGroups];
+#pragma unroll
+    for (uint32_t i = 0; i < kMergeGroups; ++i) {
+        gm[i] = s_m[i];
+        gl[i] = i < n_g ? s_l[i] : 0.0f;  // what lies beyond the launch's groups was never written
+    }
+    m_max = neg_inf();
+#pragma unroll
+    for (uint32_t i = 0; i < kMergeGroups; ++i) m_max = gl[i] > 0.0f ? __builtin_fmaxf(m_max, gm[i]) : m_max;
+    float out = 0.0f;
+    l_sum = 0.0f;
+#pragma unroll
+    for (uint32_t i = 0; i < kMergeGroups; ++i) {
+        const float a = s_acc[i][d];
+        const float w = __builtin_amdgcn_exp2f(gm[i] - m_max);
+        out = gl[i] > 0.0f ? __builtin_fmaf(a, w, out) : out;
+        l_sum = gl[i] > 0.0f ? __builtin_fmaf(gl[i], w, l_sum) : l_sum;
+    }
     const uint64_t o = (uint64_t)qt * n_q_heads + hq;
-    r.out[o * 128u + d] = l_sum > 0.0f ? acc / l_sum : 0.0f;
+    r.out[o * 128u + d] = l_sum > 0.0f ? out / l_sum : 0.0f;
     if (d == 0 && r.lse)
         r.lse[o] = l_sum > 0.0f ? (m_max + __builtin_log2f(l_sum)) * 0.69314718055994531f : neg_inf();
 }
@@ -605,7 +643,7 @@ hipError_t launch_k7(K7Params &p, hipStream_t stream)
     if (p.n_reqs == 0) return hipSuccess;
     if (p.n_reqs > kMaxMergeReqs || p.n_kv_heads == 0 || p.n_q_heads % p.n_kv_heads)
         return hipErrorInvalidValue;
-    uint64_t width = 0;
+    uint64_t width = 0, max_units = 0;
     for (uint32_t i = 0; i < p.n_reqs; ++i) {
         const K7Req &r = p.r[i];
         // a request without a token to attend to (n_chunks 0) gets zeros and lse = -inf
@@ -613,9 +651,17 @@ hipError_t launch_k7(K7Params &p, hipStream_t stream)
             return hipErrorInvalidValue;
         const uint64_t rows = (uint64_t)r.n_q * p.n_q_heads;
         if (rows > width) width = rows;
+        const uint64_t units = (uint64_t)r.n_chunks * r.n_split;
+        if (units > 0xFFFFFFFFull) return hipErrorInvalidValue;
+        if (units > max_units) max_units = units;
     }
     if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(k7_attend_merge, dim3((uint32_t)width, p.n_reqs), dim3(128), 0, stream, p);
+    // one group per two records of the longest row if that fits (a group fetches four at a
+    // time), in whole waves, at least the 128 threads that write the row
+    const uint64_t want = (max_units + 1u) / 2u;
+    uint32_t groups = want < 4u ? 4u : want > kMergeGroups ? kMergeGroups : (uint32_t)want;
+    groups = (groups + 1u) & ~1u;
+    hipLaunchKernelGGL(k7_attend_merge, dim3((uint32_t)width, p.n_reqs), dim3(32 * groups), 0, stream, p);
     return hipGetLastError();
 }
 
