@@ -140,6 +140,16 @@ def test_many_long_chunks_take_coarse_splits():
     run_case((1, 8, 128), reqs, 0, 16, 0.09, 45)
 
 
+@pytest.mark.parametrize("n_docs", [1, 3, 8, 9, 63, 64, 65, 150, 300])
+def test_merge_of_one_request_with_few_and_with_many_records(n_docs):
+    """The merge kernel shares a row's records between groups of threads (launch_k7): one record,
+    fewer than the smallest launch's groups, one or two per group, and more than the largest
+    launch's groups fetch in one round (128), with a ragged last round."""
+    tokens = [5 + (11 * i) % 28 for i in range(n_docs)]
+    precs = [ALL[(i * 5 + 1) % 6] for i in range(n_docs)]
+    run_case((1, 2, 128), [(tokens, precs, 3)], 0, 4, 0.11, 70 + n_docs)
+
+
 def test_batch_of_requests_with_different_shapes_empty_chunks_and_an_empty_request():
     reqs = [([30, 0, 65], [B.PREC_INT4, B.PREC_16, B.PREC_INT8], 1),
             ([], [], 2),
