@@ -37,7 +37,7 @@ MEASURED_TRAFFIC = {"hbm8b": 1_013_000_000,
                     # attention over packed chunks, default batch and one query token, per call
                     # (one layer): partial kernel 328.5 MB read (= the packed bytes) + 21.3 MB of
                     # records written, merge kernel 6.6 MB read + 0.6 MB written
-                    "attend8b": 357_000_000}
+                    "attend8b": 341_600_000}
 PCIE_PEAK_GBPS = 63.0           # PCIe Gen5 x16, one direction, theoretical
 
 

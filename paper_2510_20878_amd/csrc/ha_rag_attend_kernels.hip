@@ -393,6 +393,7 @@ blocks_done:
 #pragma unroll
         for (uint32_t k = 0; k < 512u / (64u * kAttendWaves); ++k) {  // 512 16-byte words of output per tile
             const uint32_t i = threadIdx.x + 64u * kAttendWaves * k, row = mt * 16u + (i >> 5);
+            if (mtile * 16u + (i >> 5) >= M) continue;  // no query in this row: the merge never reads it
             float m_all = sm[0][row];
 #pragma unroll
             for (uint32_t w = 1; w < kAttendWaves; ++w) m_all = __builtin_fmaxf(m_all, sm[w][row]);
