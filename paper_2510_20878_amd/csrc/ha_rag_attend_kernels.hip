@@ -339,12 +339,14 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c
     // A ring of kStages register sets: while a block is worked on, the loads of the next
     // kStages - 1 blocks of this wave are in flight.  What is in flight per compute unit has
     // to cover the memory latency at full bandwidth, and a block of a 4-bit chunk is a quarter
-    // of the bytes of a 16-bit one, so narrow formats get a deeper ring.  The loop is unrolled
-    // over the ring so that no block is copied from one set to another.
+    // of the bytes of a 16-bit one, so narrow formats get a deeper ring; the 16-bit pairs take
+    // the registers that two waves per SIMD leave them (3 sets: 217 registers; 2 sets measured
+    // 6 % slower on 16-bit chunks, 4 the same as 3).  The loop is unrolled over the ring so
+    // that no block is copied from one set to another.
     constexpr uint32_t kWordsKV = FK::kWords + FV::kWords;
     constexpr int kStages = MTW > 1 ? 2  // registers are short
                             : NARROW ? (kWordsKV <= 2 ? 3 : 2)
-                                     : (kWordsKV <= 2 ? 4 : kWordsKV <= 4 ? 3 : 2);
+                                     : (kWordsKV <= 2 ? 4 : 3);
     BlockRegs<KP, VP> ring[kStages];
     uint32_t b = b0 + wave;
 #pragma unroll
