@@ -346,8 +346,9 @@ def run_hbm(args, B, wl, torch, name):
         "data": "synthetic",
         "config": {"workload": desc, "pool_chunks": n_pool, "pool_gib": round(pool_bytes / 2**30, 1),
                    "tokens_per_step": step_tokens, "bytes_per_step": step_bytes,
-                   "launch": {"threads": args.threads, "planes16": args.planes16,
-                              "planes8": args.planes8, "nt_store": bool(args.nt_store),
+                   "launch": {"threads": args.threads,
+                              "planes16": args.planes16 or (4 if args.paged else 1),
+                              "planes8": args.planes8 or (4 if args.paged else 2), "nt_store": bool(args.nt_store),
                               "nt_load": bool(args.nt_load)}},
         "kv_tokens_per_s": step_tokens / (ms_per_step * 1e-3),
         "hbm_fraction_whole_path": value / HBM_PEAK_GBPS,
@@ -865,8 +866,8 @@ def main():
     ap.add_argument("--out-buffers", type=int, default=4)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--threads", type=int, default=64, help="kernel launch shape (see ha_rag.h)")
-    ap.add_argument("--planes16", type=int, default=1)
-    ap.add_argument("--planes8", type=int, default=2)
+    ap.add_argument("--planes16", type=int, default=0, help="0 = the library's choice (1; 4 into a paged cache)")
+    ap.add_argument("--planes8", type=int, default=0, help="0 = the library's choice (2; 4 into a paged cache)")
     ap.add_argument("--nt-store", type=int, default=1)
     ap.add_argument("--nt-load", type=int, default=1)
     ap.add_argument("--staging-slots", type=int, default=8)

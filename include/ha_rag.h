@@ -257,13 +257,15 @@ int ha_rag_destroy(ha_rag_ctx *ctx);
 const char *ha_rag_last_hip_error(ha_rag_ctx *ctx);
 
 /* Launch shape of the gather-dequantize-scatter kernel, for tuning sweeps; the
- * defaults are the measured best.  One wave handles one *item*: some of the four
- * 1024-byte output planes of one 2048-element block. */
+ * defaults (64 threads, 0, 0, 1, 1) are the measured best.  One wave handles one
+ * *item*: some of the four 1024-byte output planes of one 2048-element block. */
 typedef struct ha_rag_launch_params {
     uint32_t threads;   /* per workgroup: 64..1024, multiple of 64 (one item per wave)  */
-    uint32_t planes16;  /* planes per item for 16-bit chunks: 1, 2 or 4                  */
+    uint32_t planes16;  /* planes per item for 16-bit chunks: 1, 2 or 4; 0 = the library
+                           chooses: 1 into a plain cache, 4 into a paged cache            */
     uint32_t planes8;   /* planes per item for the 8-bit tags (INT8, FP8, GSE8): 2 or 4;
-                           INT4, and any chunk read from host memory: always 4          */
+                           0 = the library chooses: 2 into a plain cache, 4 into a paged
+                           one.  INT4, GSE8, and any chunk read from host memory: always 4 */
     uint32_t nt_store;  /* 1 = nontemporal (streaming) stores to the cache              */
     uint32_t nt_load;   /* 1 = nontemporal loads of the packed payload                  */
 } ha_rag_launch_params;

@@ -299,7 +299,7 @@ class Context:
                                    g, n_tokens)[2]
         return whole if part == PART_KV else whole // 2
 
-    def set_launch_params(self, threads=64, planes16=1, planes8=2, nt_store=1, nt_load=1):
+    def set_launch_params(self, threads=64, planes16=0, planes8=0, nt_store=1, nt_load=1):
         lp = LaunchParams(threads, planes16, planes8, int(nt_store), int(nt_load))
         self._chk(lib().ha_rag_set_launch_params(self._h, C.byref(lp)), "ha_rag_set_launch_params")
 

@@ -134,8 +134,8 @@ int ha_rag_set_launch_params(ha_rag_ctx *c, const ha_rag_launch_params *lp)
 {
     if (!c || !lp) return HA_RAG_EINVAL;
     if (lp->threads < 64 || lp->threads > 1024 || (lp->threads & 63u)) return HA_RAG_EINVAL;
-    if (lp->planes16 != 1 && lp->planes16 != 2 && lp->planes16 != 4) return HA_RAG_EINVAL;
-    if (lp->planes8 != 2 && lp->planes8 != 4) return HA_RAG_EINVAL;
+    if (lp->planes16 != 0 && lp->planes16 != 1 && lp->planes16 != 2 && lp->planes16 != 4) return HA_RAG_EINVAL;
+    if (lp->planes8 != 0 && lp->planes8 != 2 && lp->planes8 != 4) return HA_RAG_EINVAL;
     std::lock_guard<std::mutex> g(c->mu);
     c->launch = K1Launch{lp->threads, lp->planes16, lp->planes8, lp->nt_store != 0,
                          lp->nt_load != 0};

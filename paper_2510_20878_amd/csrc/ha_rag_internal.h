@@ -137,7 +137,7 @@ struct ha_rag_ctx {
     uint64_t copy_rr = 0;
     std::unordered_map<hipStream_t, hipEvent_t> stream_done;
 
-    ha_rag::K1Launch launch{64, 1, 2, true, true};
+    ha_rag::K1Launch launch{64, 0, 0, true, true};  // 0: launch_k1 chooses
 
     uint32_t group_of(uint32_t prec) const
     {
