@@ -252,7 +252,8 @@ int ha_rag_create(const ha_rag_config *cfg, ha_rag_ctx **out);
  * first.  The caller's buffers are not touched. */
 int ha_rag_destroy(ha_rag_ctx *ctx);
 
-/* Name of the last failing HIP or file call and its error string ("" if none).
+/* Name of the last failing HIP or file call and its error string, or the limit a call to
+ * ha_rag_attend_packed_static exceeded ("" if none).
  * With ctx == NULL: the reason the calling thread's last ha_rag_create failed. */
 const char *ha_rag_last_hip_error(ha_rag_ctx *ctx);
 
@@ -394,8 +395,32 @@ int ha_rag_attend_packed(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks,
                          uint32_t n_q_heads, float sm_scale, void *workspace,
                          size_t workspace_bytes, void *stream);
 
-/* Workspace size for that call: reads only n_tokens, prec, group, part of the chunks and
- * n_q, n_chunks of the requests. */
+/* ha_rag_attend_packed for callers that cannot allocate device memory or have none to hand
+ * over as a workspace: code running under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation.  The same computation, arguments, checks and kernels, but the partial
+ * results go to an array of HA_RAG_ATTEND_STATIC_SCRATCH_BYTES bytes that is part of the
+ * library's device code (each GPU the library runs on holds its own copy until the process
+ * ends; its address on the current device is looked up once, in ha_rag_create or at the first
+ * call on that device).  The call allocates nothing, neither on the device nor on the host: its
+ * plan lives on the stack, which bounds what one call may hold.
+ * ENOSPC, before anything is enqueued, for more than HA_RAG_ATTEND_STATIC_MAX_REQUESTS requests,
+ * more than HA_RAG_ATTEND_STATIC_MAX_DOCS documents (a whole chunk, or a keys-only chunk with its
+ * values-only partner, that holds tokens), or lists whose partial results
+ * (ha_rag_attend_workspace_bytes) exceed the array; ha_rag_last_hip_error then says which
+ * limit and by how much.
+ * All calls on one GPU share that GPU's array, which keeps the previous call's contents: every
+ * record a call reads it has written first, so nothing needs clearing, but two calls whose
+ * kernels overlap on one GPU (different streams, or different contexts) race on it -- order them
+ * on one stream or by events. */
+#define HA_RAG_ATTEND_STATIC_SCRATCH_BYTES (32u << 20)
+#define HA_RAG_ATTEND_STATIC_MAX_REQUESTS 64
+#define HA_RAG_ATTEND_STATIC_MAX_DOCS 416
+int ha_rag_attend_packed_static(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks,
+                                const ha_rag_attend_request *reqs, uint32_t n_reqs, uint32_t layer,
+                                uint32_t n_q_heads, float sm_scale, void *stream);
+
+/* Workspace size for ha_rag_attend_packed: reads only n_tokens, prec, group, part of the chunks
+ * and n_q, n_chunks of the requests. */
 int ha_rag_attend_workspace_bytes(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks,
                                   const ha_rag_attend_request *reqs, uint32_t n_reqs,
                                   uint32_t n_q_heads, size_t *bytes);

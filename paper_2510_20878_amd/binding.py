@@ -16,6 +16,7 @@ TIER_HBM, TIER_PINNED, TIER_PAGEABLE, TIER_DISK, TIER_NONE = 0, 1, 2, 3, 255
 PART_KV, PART_K, PART_V = 0, 1, 2
 NO_CHUNK = 2**64 - 1
 ATTEND_COUNT = 1
+ATTEND_STATIC_SCRATCH_BYTES, ATTEND_STATIC_MAX_REQUESTS, ATTEND_STATIC_MAX_DOCS = 32 << 20, 64, 416
 PLACE_DEVICE_VISIBLE = 1
 BITS = {PREC_16: 16, PREC_INT8: 8, PREC_INT4: 4, PREC_FP8_E4M3: 8, PREC_FP8_E5M2: 8,
         PREC_GSE8: 8}  # storage bits
@@ -34,7 +35,7 @@ SYMBOLS = [
     "ha_rag_load_chunks_paged", "ha_rag_chunk_sq_error", "ha_rag_pool_save_index",
     "ha_rag_pool_load_index", "ha_rag_pool_remove", "ha_rag_attend_packed",
     "ha_rag_attend_workspace_bytes", "ha_rag_attend_chunks", "ha_rag_attend_chunks_workspace_bytes",
-    "ha_rag_place_chunks",
+    "ha_rag_place_chunks", "ha_rag_attend_packed_static",
 ]
 
 
@@ -142,6 +143,8 @@ def lib():
             "ha_rag_load_packed_paged": (C.c_int, [vp, P(PackedChunk), u32, P(PagedCache), u64, vp]),
             "ha_rag_attend_packed": (C.c_int, [vp, P(PackedChunk), P(AttendRequest), u32, u32, u32,
                                                C.c_float, vp, C.c_size_t, vp]),
+            "ha_rag_attend_packed_static": (C.c_int, [vp, P(PackedChunk), P(AttendRequest), u32, u32,
+                                                      u32, C.c_float, vp]),
             "ha_rag_attend_workspace_bytes": (C.c_int, [vp, P(PackedChunk), P(AttendRequest), u32, u32,
                                                         P(C.c_size_t)]),
             "ha_rag_attend_chunks": (C.c_int, [vp, P(u64), P(AttendRequest), u32, u32, u32, C.c_float,
@@ -370,6 +373,14 @@ class Context:
         self._chk(lib().ha_rag_attend_packed(self._h, arr, reqs, n_reqs, layer, n_q_heads,
                                              sm_scale, _addr(workspace), workspace_bytes,
                                              _stream(stream)), "ha_rag_attend_packed")
+
+    def attend_packed_static(self, requests, layer, n_q_heads, sm_scale, stream=None):
+        arr, reqs, n_reqs = self.attend_lists(requests)
+        rc = lib().ha_rag_attend_packed_static(self._h, arr, reqs, n_reqs, layer, n_q_heads,
+                                               sm_scale, _stream(stream))
+        if rc:
+            detail = lib().ha_rag_last_hip_error(self._h).decode() if rc in (EHIP, ENOSPC) else ""
+            raise HaRagError(rc, "ha_rag_attend_packed_static", detail)
 
     @staticmethod
     def attend_id_lists(requests):

@@ -97,6 +97,12 @@ int ha_rag_create(const ha_rag_config *cfg, ha_rag_ctx **out)
             }
             c->copy_streams.push_back(s);
         }
+        // the library's set-up on this device: where its static scratch array lives here
+        if (attend_static_scratch(nullptr, &g_create_err) != HA_RAG_OK) {
+            for (hipStream_t t : c->copy_streams) (void)hipStreamDestroy(t);
+            delete c;
+            return HA_RAG_EHIP;
+        }
     }
     *out = c;
     return HA_RAG_OK;

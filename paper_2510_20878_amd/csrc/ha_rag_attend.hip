@@ -2,9 +2,31 @@
 // launches (one partial-attention launch per 416 documents, one merge launch per 64 requests).
 #include "ha_rag_internal.h"
 
+#include <cstdio>
+
 using namespace ha_rag_host;
 
 namespace {
+
+// A list in storage its owner provides: the planning below fills such lists, so that one of
+// its callers can keep them on the stack and allocate nothing.
+template <class T>
+struct Fixed {
+    T *data = nullptr;
+    uint32_t cap = 0, n = 0;
+    Fixed() = default;
+    Fixed(T *d, uint32_t c) : data(d), cap(c) {}
+    explicit Fixed(std::vector<T> &v) : data(v.data()), cap((uint32_t)v.size()) {}
+    bool push_back(const T &v)
+    {
+        if (n == cap) return false;
+        data[n++] = v;
+        return true;
+    }
+    T &operator[](size_t i) const { return data[i]; }
+    uint32_t size() const { return n; }
+    void clear() { n = 0; }
+};
 
 // One document of a request: keys and values, from one whole chunk or from a keys-only and a
 // values-only chunk (paired in list order).
@@ -24,9 +46,12 @@ struct Plan {               // one request
 };
 
 // Checks everything and lays the workspace out.  *floats = workspace size in binary32 words.
+// plans: n_reqs entries; docs, open_k, open_v: filled here, ENOSPC if one of them is too small
+// (never with lists as long as the call's chunk list).
 int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_attend_request *reqs,
-                uint32_t n_reqs, uint32_t n_q_heads, std::vector<Plan> *plans, std::vector<Doc> *docs,
-                uint64_t *floats, uint32_t *split_blocks, bool need_buffers)
+                uint32_t n_reqs, uint32_t n_q_heads, Plan *plans, Fixed<Doc> *docs,
+                Fixed<uint32_t> open_k, Fixed<uint32_t> open_v, uint64_t *floats,
+                uint32_t *split_blocks, bool need_buffers)
 {
     if (!c || !reqs || n_reqs == 0 || n_reqs > HA_RAG_MAX_ATTEND_REQUESTS) return HA_RAG_EINVAL;
     if (c->cfg.head_dim != kAttendHeadDim) return HA_RAG_EFORMAT;
@@ -34,12 +59,12 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
     if (n_q_heads == 0 || n_q_heads % H || n_q_heads / H > 64) return HA_RAG_EINVAL;
     const uint32_t G = n_q_heads / H;
     uint64_t total = 0, n_chunks = 0;
-    plans->assign(n_reqs, Plan());
     docs->clear();
-    std::vector<uint32_t> open_k, open_v;  // documents still waiting for their values / keys
+    // open_k / open_v: documents still waiting for their values / keys
     for (uint32_t r = 0; r < n_reqs; ++r) {
         const ha_rag_attend_request &rq = reqs[r];
-        Plan &pl = (*plans)[r];
+        Plan &pl = plans[r];
+        pl = Plan();
         if (rq.n_q == 0 || rq.n_q > HA_RAG_MAX_ATTEND_Q) return HA_RAG_EINVAL;
         if (need_buffers && (!rq.q || !rq.out || ((uintptr_t)rq.q & 15u) || ((uintptr_t)rq.out & 15u)))
             return HA_RAG_EINVAL;
@@ -70,12 +95,12 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
                 d.k_step = d.v_step = 2u * H;
                 d.n_tokens = pc.n_tokens;
                 d.info = fmt | (fmt << 8);
-                docs->push_back(d);
+                if (!docs->push_back(d)) return HA_RAG_ENOSPC;
             } else {
                 // the i-th keys-only chunk of the request and its i-th values-only chunk are one
                 // document: they must hold the same tokens
                 const bool is_k = pc.part == HA_RAG_PART_K;
-                std::vector<uint32_t> &mine = is_k ? open_k : open_v, &other = is_k ? open_v : open_k;
+                Fixed<uint32_t> &mine = is_k ? open_k : open_v, &other = is_k ? open_v : open_k;
                 size_t &other_next = is_k ? next_v : next_k;
                 uint32_t di;
                 if (other_next < other.size()) {
@@ -83,9 +108,8 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
                     if ((*docs)[di].n_tokens != pc.n_tokens) return HA_RAG_EINVAL;
                 } else {
                     di = (uint32_t)docs->size();
-                    docs->push_back(Doc());
+                    if (!docs->push_back(Doc()) || !mine.push_back(di)) return HA_RAG_ENOSPC;
                     (*docs)[di].n_tokens = pc.n_tokens;
-                    mine.push_back(di);
                 }
                 Doc &d = (*docs)[di];
                 (is_k ? d.k : d.v) = ptr;
@@ -106,12 +130,15 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
     uint32_t sb = kAttendMaxSplitBlocks;
     for (;; sb >>= 1) {
         uint64_t groups = 0;
-        for (const Plan &pl : *plans)
+        for (uint32_t r = 0; r < n_reqs; ++r) {
+            const Plan &pl = plans[r];
             groups += (uint64_t)pl.n_docs * H * ((pl.max_blocks + sb - 1u) / sb) * ((pl.n_mt + 1u) / 2u);
+        }
         if (groups >= kAttendTargetGroups || sb == kAttendMinSplitBlocks) break;
     }
     *split_blocks = sb;
-    for (Plan &pl : *plans) {
+    for (uint32_t r = 0; r < n_reqs; ++r) {
+        Plan &pl = plans[r];
         pl.n_split = pl.max_blocks ? (pl.max_blocks + sb - 1u) / sb : 1u;
         pl.part_floats = total;
         total += (uint64_t)pl.n_docs * H * pl.n_split * pl.n_mt * kAttendRecFloats;
@@ -122,18 +149,47 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
 }
 
 
-// checks, workspace layout and launches; the caller holds the context's lock
-int attend_locked(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
-                         const ha_rag_attend_request *reqs, uint32_t n_reqs, uint32_t layer,
-                         uint32_t n_q_heads, float sm_scale, void *workspace, size_t workspace_bytes,
-                         void *stream)
-{
+// Storage of one call's plan.  The ordinary entry points size it for the call on the heap; the
+// entry point that allocates nothing keeps a small one on the stack.
+struct PlanStore {
+    Plan *plans;
+    Fixed<Doc> docs;
+    Fixed<uint32_t> open_k, open_v;
+};
+
+struct HeapPlanStore {
     std::vector<Plan> plans;
     std::vector<Doc> docs;
+    std::vector<uint32_t> open_k, open_v;
+    HeapPlanStore(const ha_rag_attend_request *reqs, uint32_t n_reqs)
+    {
+        uint64_t n = 0;
+        if (reqs && n_reqs <= HA_RAG_MAX_ATTEND_REQUESTS)
+            for (uint32_t r = 0; r < n_reqs; ++r) n += reqs[r].n_chunks;
+        if (n > HA_RAG_MAX_REQUEST_CHUNKS) n = 0;  // the planning refuses the call anyway
+        plans.resize(n_reqs <= HA_RAG_MAX_ATTEND_REQUESTS ? n_reqs : 0);
+        docs.resize((size_t)n);
+        open_k.resize((size_t)n);
+        open_v.resize((size_t)n);
+    }
+    PlanStore store() { return PlanStore{plans.data(), Fixed<Doc>(docs), Fixed<uint32_t>(open_k), Fixed<uint32_t>(open_v)}; }
+};
+
+// checks, workspace layout and launches; the caller holds the context's lock.  *need (nullable)
+// receives the workspace bytes the lists ask for, also when the call then fails with ENOSPC.
+int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks,
+                  const ha_rag_attend_request *reqs, uint32_t n_reqs, uint32_t layer,
+                  uint32_t n_q_heads, float sm_scale, void *workspace, size_t workspace_bytes,
+                  void *stream, uint64_t *need = nullptr)
+{
     uint64_t floats = 0;
     uint32_t split_blocks = 0;
-    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, &plans, &docs, &floats, &split_blocks, true);
+    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, ps.plans, &ps.docs, ps.open_k, ps.open_v,
+                         &floats, &split_blocks, true);
     if (rc) return rc;
+    const Plan *plans = ps.plans;
+    const Fixed<Doc> &docs = ps.docs;
+    if (need) *need = floats * 4ull;
     if (layer >= c->cfg.n_layers || !(sm_scale > 0.0f) || !(sm_scale < 1e30f)) return HA_RAG_EINVAL;
     if (floats && (!workspace || ((uintptr_t)workspace & 15u))) return HA_RAG_EINVAL;
     if (floats * 4ull > workspace_bytes) return HA_RAG_ENOSPC;
@@ -220,7 +276,47 @@ int resolve_ids(ha_rag_ctx *c, const uint64_t *ids, const ha_rag_attend_request 
     return HA_RAG_OK;
 }
 
+// ---- scratch of ha_rag_attend_packed_static ------------------------------------------------
+// The partial results of that entry point live in this array instead of a caller's workspace.
+// Every GPU holds its own copy at its own address, from the moment the code object is loaded
+// there until the process ends.  In host code the name is only a handle for
+// hipGetSymbolAddress: what kernels and copies get is the address that call returned for the
+// current device, kept in g_scratch_ptr.
+constexpr size_t kStaticScratchBytes = (size_t)HA_RAG_ATTEND_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
 }  // namespace
+
+namespace ha_rag_host {
+
+// Address of the scratch array on the current device; looked up once per device.
+int attend_static_scratch(void **ptr, std::string *err)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        if (err) *err = std::string("hipGetDevice: ") + (e != hipSuccess ? hipGetErrorString(e) : "device index out of range");
+        return HA_RAG_EHIP;
+    }
+    std::lock_guard<std::mutex> g(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            if (err) *err = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e);
+            return HA_RAG_EHIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    if (ptr) *ptr = g_scratch_ptr[dev];
+    return HA_RAG_OK;
+}
+
+}  // namespace ha_rag_host
 
 extern "C" {
 
@@ -229,11 +325,12 @@ int ha_rag_attend_workspace_bytes(ha_rag_ctx *c, const ha_rag_packed_chunk *chun
                                   uint32_t n_q_heads, size_t *bytes)
 {
     if (!bytes) return HA_RAG_EINVAL;
-    std::vector<Plan> plans;
-    std::vector<Doc> docs;
+    HeapPlanStore hs(reqs, n_reqs);
+    PlanStore ps = hs.store();
     uint64_t floats = 0;
     uint32_t split_blocks = 0;
-    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, &plans, &docs, &floats, &split_blocks, false);
+    int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, ps.plans, &ps.docs, ps.open_k, ps.open_v,
+                         &floats, &split_blocks, false);
     if (rc) return rc;
     *bytes = (size_t)(floats * 4ull);
     return HA_RAG_OK;
@@ -245,9 +342,53 @@ int ha_rag_attend_packed(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
                          void *stream)
 {
     if (!c) return HA_RAG_EINVAL;
+    HeapPlanStore hs(reqs, n_reqs);
     std::lock_guard<std::mutex> g(c->mu);
-    return attend_locked(c, chunks, reqs, n_reqs, layer, n_q_heads, sm_scale, workspace,
+    return attend_locked(c, hs.store(), chunks, reqs, n_reqs, layer, n_q_heads, sm_scale, workspace,
                          workspace_bytes, stream);
+}
+
+int ha_rag_attend_packed_static(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks,
+                                const ha_rag_attend_request *reqs, uint32_t n_reqs, uint32_t layer,
+                                uint32_t n_q_heads, float sm_scale, void *stream)
+{
+    if (!c || !reqs || n_reqs == 0) return HA_RAG_EINVAL;
+    std::lock_guard<std::mutex> g(c->mu);
+    if (n_reqs > HA_RAG_ATTEND_STATIC_MAX_REQUESTS) {
+        c->err = "ha_rag_attend_packed_static: more than " +
+                 std::to_string(HA_RAG_ATTEND_STATIC_MAX_REQUESTS) + " requests in one call";
+        return HA_RAG_ENOSPC;
+    }
+    // the plan of the call on the stack: no list here grows
+    Plan plans[HA_RAG_ATTEND_STATIC_MAX_REQUESTS];
+    Doc docs[HA_RAG_ATTEND_STATIC_MAX_DOCS];
+    uint32_t open_k[HA_RAG_ATTEND_STATIC_MAX_DOCS], open_v[HA_RAG_ATTEND_STATIC_MAX_DOCS];
+    PlanStore ps{plans, Fixed<Doc>(docs, HA_RAG_ATTEND_STATIC_MAX_DOCS),
+                 Fixed<uint32_t>(open_k, HA_RAG_ATTEND_STATIC_MAX_DOCS),
+                 Fixed<uint32_t>(open_v, HA_RAG_ATTEND_STATIC_MAX_DOCS)};
+    void *ws = nullptr;
+    if (!c->dry()) {
+        int rc = attend_static_scratch(&ws, &c->err);
+        if (rc) return rc;
+    } else {
+        ws = reinterpret_cast<void *>((uintptr_t)256);  // never dereferenced
+    }
+    uint64_t need = 0;
+    int rc = attend_locked(c, ps, chunks, reqs, n_reqs, layer, n_q_heads, sm_scale, ws,
+                           kStaticScratchBytes, stream, &need);
+    if (rc == HA_RAG_ENOSPC) {
+        char msg[192];
+        if (need > kStaticScratchBytes)
+            std::snprintf(msg, sizeof msg,
+                          "ha_rag_attend_packed_static: the call needs %llu bytes of partial results, the scratch array holds %llu",
+                          (unsigned long long)need, (unsigned long long)kStaticScratchBytes);
+        else
+            std::snprintf(msg, sizeof msg,
+                          "ha_rag_attend_packed_static: more than %u documents in one call",
+                          (unsigned)HA_RAG_ATTEND_STATIC_MAX_DOCS);
+        c->err = msg;
+    }
+    return rc;
 }
 
 int ha_rag_attend_chunks_workspace_bytes(ha_rag_ctx *c, const uint64_t *ids,
@@ -260,11 +401,12 @@ int ha_rag_attend_chunks_workspace_bytes(ha_rag_ctx *c, const uint64_t *ids,
     std::vector<uint32_t> cis;
     int rc = resolve_ids(c, ids, reqs, n_reqs, &chunks, &cis);
     if (rc) return rc;
-    std::vector<Plan> plans;
-    std::vector<Doc> docs;
+    HeapPlanStore hs(reqs, n_reqs);
+    PlanStore ps = hs.store();
     uint64_t floats = 0;
     uint32_t split_blocks = 0;
-    rc = plan_attend(c, chunks.data(), reqs, n_reqs, n_q_heads, &plans, &docs, &floats, &split_blocks, false);
+    rc = plan_attend(c, chunks.data(), reqs, n_reqs, n_q_heads, ps.plans, &ps.docs, ps.open_k, ps.open_v,
+                     &floats, &split_blocks, false);
     if (rc) return rc;
     *bytes = (size_t)(floats * 4ull);
     return HA_RAG_OK;
@@ -288,7 +430,8 @@ int ha_rag_attend_chunks(ha_rag_ctx *c, const uint64_t *ids, const ha_rag_attend
         rc = before_read(c, c->slab[t][ch.prec].use[ch.slot[t]], s);
         if (rc) return rc;
     }
-    rc = attend_locked(c, chunks.data(), reqs, n_reqs, layer, n_q_heads, sm_scale, workspace,
+    HeapPlanStore hs(reqs, n_reqs);
+    rc = attend_locked(c, hs.store(), chunks.data(), reqs, n_reqs, layer, n_q_heads, sm_scale, workspace,
                        workspace_bytes, stream);
     if (rc) return rc;
     if (flags & HA_RAG_ATTEND_COUNT) {  // Algorithm 1's access counts and the LRU order of Algorithm 2

@@ -200,4 +200,9 @@ void rerank_locked(ha_rag_ctx *c);
 uint32_t new_chunk_entry(ha_rag_ctx *c);  // index of a fresh entry of ctx->chunks
 int acquire_bounce(ha_rag_ctx *c, size_t *idx);
 
+// ---- attention (ha_rag_attend.hip) ----
+// Address, on the current device, of the scratch array that ha_rag_attend_packed_static uses
+// (looked up once per device; *ptr nullable).
+int attend_static_scratch(void **ptr, std::string *err);
+
 }  // namespace ha_rag_host
