@@ -117,7 +117,11 @@ typedef struct ha_rag_config {
                                   ha_rag_rerank                                            */
     uint32_t n_copy_streams;   /* streams for pinned -> HBM copies (0 = 2, at most 8)      */
     uint32_t dry_run;          /* 1 = host bookkeeping only: no HIP call is ever made, no
-                                  byte is moved (for host-logic tests without a GPU)      */
+                                  byte is moved (for host-logic tests without a GPU).
+                                  2 = no HIP call either, but host copies and file transfers
+                                  are real: slabs, bounce buffers and chunk sources are then
+                                  ordinary host memory (for tests of the host and file tiers
+                                  without a GPU)                                           */
     uint32_t tau_pin_ppm;      /* PIN_LIST = ranks [idx1, idx2), idx2 = idx1 +
                                   floor(tau_pin_ppm * N / 1e6)                             */
     uint32_t tau_page_ppm;     /* PAGE_LIST = ranks [idx2, idx3), idx3 = idx2 +

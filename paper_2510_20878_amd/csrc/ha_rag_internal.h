@@ -143,7 +143,8 @@ struct ha_rag_ctx {
     {
         return prec == HA_RAG_PREC_INT8 ? cfg.group_int8 : prec == HA_RAG_PREC_INT4 ? cfg.group_int4 : 0;
     }
-    bool dry() const { return cfg.dry_run != 0; }
+    bool dry() const { return cfg.dry_run != 0; }    // no HIP call is made
+    bool no_io() const { return cfg.dry_run == 1; }  // nor is any byte moved on the host or to files
     bool direct() const { return cfg.disk_o_direct != 0; }
     size_t io_bytes(uint64_t bytes) const  // what a file transfer of `bytes` moves
     {

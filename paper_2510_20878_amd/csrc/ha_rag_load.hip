@@ -132,7 +132,7 @@ void init_batch(const ha_rag_ctx *c, Batch &b, const ha_rag_paged_cache *pg = nu
 // synchronous).
 int fill_bounce(ha_rag_ctx *c, const Chunk &ch, uint32_t tier, int32_t slot, uint8_t *dst)
 {
-    if (c->dry()) return HA_RAG_OK;
+    if (c->no_io()) return HA_RAG_OK;
     const Slab &sl = c->slab[tier][ch.prec];
     if (tier == HA_RAG_TIER_PAGEABLE) {
         std::memcpy(dst, sl.ptr(slot), ch.bytes);
@@ -335,7 +335,7 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
                 Slab &ds = c->slab[a.place_tier][ch.prec];
                 rc = before_host_write(c, ds.use[a.place_slot]);
                 if (rc) return rc;
-                if (!c->dry()) std::memcpy(ds.ptr(a.place_slot), bp, ch.bytes);
+                if (!c->no_io()) std::memcpy(ds.ptr(a.place_slot), bp, ch.bytes);
                 undo.written[cold[k]] = 1;
             }
             src = bp;
@@ -523,7 +523,7 @@ int place_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, uint32_t
                 Slab &ds = c->slab[a.place_tier][ch.prec];
                 rc = before_host_write(c, ds.use[a.place_slot]);
                 if (rc) return rc;
-                if (!c->dry()) std::memcpy(ds.ptr(a.place_slot), bp, ch.bytes);
+                if (!c->no_io()) std::memcpy(ds.ptr(a.place_slot), bp, ch.bytes);
                 st.bytes_host_copied += ch.bytes;
                 undo.written[k] = 1;
             }
@@ -546,6 +546,14 @@ int place_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, uint32_t
                     HIPCHK(c, hipEventRecord(c->bnc[bidx].h2d_done, s));
                     c->bnc[bidx].busy = true;
                 }
+            }
+            if (a.src_tier == HA_RAG_TIER_PINNED) {
+                // A later chunk of this call may have been given this pinned slot (pass A has
+                // already booked everything): the host write into it waits on the stream's
+                // event, which must therefore be recorded after this copy, not at the end of
+                // the call.
+                rc = mark_stream(c, s);
+                if (rc) return rc;
             }
             st.bytes_h2d += ch.bytes;
             undo.written[k] = 1;

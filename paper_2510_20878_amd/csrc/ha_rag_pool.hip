@@ -276,7 +276,7 @@ int ha_rag_register_disk(ha_rag_ctx *c, uint32_t prec, const char *path, size_t 
     if (sl.registered()) return HA_RAG_EINVAL;
     int rc = register_slab_common(c, sl, prec, bytes, kDirectAlign);
     if (rc) return rc;
-    if (!c->dry()) {
+    if (!c->no_io()) {
         int flags = O_RDWR | O_CREAT;
         if (c->direct()) flags |= O_DIRECT;
         sl.fd = open(path, flags, 0600);
@@ -333,7 +333,7 @@ int ha_rag_register_bounce(ha_rag_ctx *c, void *base, size_t bytes)
     slot = (slot + kDirectAlign - 1) / kDirectAlign * kDirectAlign;
     const size_t n = bytes / slot;
     if (n < 2) return HA_RAG_ENOSPC;
-    if (c->direct() && !c->dry()) {
+    if (c->direct() && !c->no_io()) {
         void *p = nullptr;
         if (posix_memalign(&p, kDirectAlign, slot) != 0) return HA_RAG_ENOSPC;
         c->dio = static_cast<uint8_t *>(p);
@@ -370,7 +370,11 @@ static int insert_impl(ha_rag_ctx *c, uint64_t id, uint32_t part, uint32_t prec,
     }
     // pageable / disk targets fed from device memory or through O_DIRECT need a bounce buffer
     const bool via_bounce = packed && tier >= HA_RAG_TIER_PAGEABLE && packed_is_device;
-    if (packed && tier == HA_RAG_TIER_DISK && c->direct() && !c->dry() && !c->dio) return HA_RAG_ENOSPC;
+    // a direct write passes through the page-aligned buffer, which is as large as the largest
+    // pageable / disk slot that was registered before the bounce buffers
+    if (packed && tier == HA_RAG_TIER_DISK && c->direct() && !c->no_io() &&
+        (!c->dio || c->io_bytes(total) > c->dio_bytes))
+        return HA_RAG_ENOSPC;
     if (via_bounce && (c->bnc.size() < 2 || c->io_bytes(total) > c->bounce_slot_bytes)) return HA_RAG_ENOSPC;
     uint64_t ev;
     const int32_t slot = tier_acquire(c, tier, prec, &ev);
@@ -386,14 +390,16 @@ static int insert_impl(ha_rag_ctx *c, uint64_t id, uint32_t part, uint32_t prec,
         c->index.emplace(id, ci);
     }
     tier_attach(c, tier, ci, slot);
-    if (!packed || c->dry()) return HA_RAG_OK;
+    if (!packed || c->no_io()) return HA_RAG_OK;
     if (tier == HA_RAG_TIER_HBM) {
+        if (c->dry()) return HA_RAG_OK;
         rc = before_write(c, sl.use[slot], s);
         if (rc) return rc;
         HIPCHK(c, hipMemcpyAsync(sl.ptr(slot), packed, total,
                                  packed_is_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, s));
         return mark_stream(c, s);
     }
+    if (packed_is_device && c->dry()) return HA_RAG_OK;  // no device to copy from
     if (tier == HA_RAG_TIER_PINNED) {
         rc = before_host_write(c, sl.use[slot]);
         if (rc) return rc;
@@ -413,15 +419,13 @@ static int insert_impl(ha_rag_ctx *c, uint64_t id, uint32_t part, uint32_t prec,
         rc = acquire_bounce(c, &bidx);
         if (rc) return rc;
         uint8_t *bp = c->bounce + bidx * c->bounce_slot_bytes;
-        if (packed_is_device) {
-            HIPCHK(c, hipMemcpyAsync(bp, packed, total, hipMemcpyDeviceToHost, s));
-            HIPCHK(c, hipStreamSynchronize(s));
-        } else {
-            std::memcpy(bp, packed, total);
-        }
+        HIPCHK(c, hipMemcpyAsync(bp, packed, total, hipMemcpyDeviceToHost, s));
+        HIPCHK(c, hipStreamSynchronize(s));
         host = bp;
     }
     if (tier == HA_RAG_TIER_PAGEABLE) {
+        rc = before_host_write(c, sl.use[slot]);
+        if (rc) return rc;
         std::memcpy(sl.ptr(slot), host, total);
         return HA_RAG_OK;
     }

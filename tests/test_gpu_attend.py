@@ -549,6 +549,50 @@ def test_place_then_attend_with_every_chunk_starting_in_a_file(tmp_path, o_direc
     ctx.destroy()
 
 
+def test_place_more_chunks_than_the_pinned_slab_holds_in_one_call(tmp_path):
+    """One ha_rag_place_chunks call whose later chunks are given the pinned slots that its earlier
+    chunks are still being copied out of: chunks 0 and 1 sit in the two pinned slots and belong
+    in HBM (host -> device copies, queued behind other work on the stream); chunks 2 and 3 come
+    from a file and belong in pinned memory, so they take over those very slots.  The host write
+    into a slot has to wait for the copy that reads it: the HBM copies must hold the bytes the
+    oracle packs for chunks 0 and 1, the pinned slots those of 2 and 3."""
+    L, H, D, T = 8, 8, 128, 1024                              # 32 MiB per 16-bit chunk
+    n = 4
+    ctx = B.Context(L, H, D, T, tau_gpu_ppm=500_000, tau_pin_ppm=500_000)
+    slot = (ctx.chunk_bytes(B.PREC_16, T) + 4095) // 4096 * 4096
+    hbm = torch.zeros(slot * n, dtype=torch.uint8, device="cuda")
+    pin = torch.zeros(slot * 2, dtype=torch.uint8).pin_memory()
+    ctx.register_slab(B.TIER_HBM, B.PREC_16, hbm)
+    ctx.register_slab(B.TIER_PINNED, B.PREC_16, pin)
+    ctx.register_disk(B.PREC_16, str(tmp_path / "pool16.bin"), slot * n)
+    ctx.register_bounce(torch.zeros(slot * 2, dtype=torch.uint8).pin_memory())
+    packed = [codec.quantize_pack_chunk(wl.kv_chunk(L, H, D, T, 1500 + i), 16)[0] for i in range(n)]
+    for i in range(n):
+        ctx.pool_insert(i, B.PREC_16, T, packed[i], B.TIER_DISK)
+    for i in range(2):
+        ctx.pool_insert(i, B.PREC_16, T, packed[i], B.TIER_PINNED)
+    ctx.set_counts(list(range(n)), [100 - i for i in range(n)])
+    ctx.rerank()                                              # GPU list {0, 1}, PIN list {2, 3}
+    stream = torch.cuda.Stream()
+    a = torch.randn((8192, 8192), device="cuda")
+    with torch.cuda.stream(stream):                           # work that the copies queue behind
+        for _ in range(12):
+            a = (a @ a) * 1e-4
+    st, tr = ctx.place_chunks([0, 1, 2, 3], stream=stream, want_trace=True)
+    assert [t.found_tier for t in tr] == [1, 1, 3, 3]
+    assert [t.placed_tier for t in tr] == [0, 0, 1, 1]
+    assert sorted(t.evicted_id for t in tr[2:]) == [0, 1]
+    torch.cuda.synchronize()
+    for i in range(n):
+        tier = B.TIER_HBM if i < 2 else B.TIER_PINNED
+        ptr, nbytes = ctx.pool_slot(i, tier)
+        buf = hbm if i < 2 else pin
+        off = ptr - buf.data_ptr()
+        got = buf[off:off + nbytes].cpu().numpy()
+        assert nbytes == len(packed[i]) and np.array_equal(got, packed[i]), i
+    ctx.destroy()
+
+
 def test_extreme_scores_and_values():
     """Query rows that are zero, tiny and huge; keys that tie, one that dominates, a masked tail;
     values of both signs up to 1e30: the running maximum, its rescaling and the normaliser must

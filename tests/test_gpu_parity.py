@@ -1,6 +1,8 @@
 """Parity of the HIP path against the CPU oracle, through the C ABI, on a real
 MI355X.  Bars: packed bytes (codes, scale, zero, padding) bit-exact; BF16 cache
 within 1 ulp (0 expected); order, offsets and untouched rows exact."""
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -90,6 +92,8 @@ SHAPES = [  # (L, H, D, T, group)
     (1, 2, 128, 272, 64),    # 17 blocks: spans several workgroups
     (1, 1, 256, 24, 256),
     (1, 1, 64, 7, 32),       # less than one block
+    (1, 2, 512, 21, 512),    # the widest group: one per row, one scale/zero entry per plane
+    (1, 1, 512, 5, 256),
 ]
 
 
@@ -194,7 +198,8 @@ def test_load_mixed_tags_ragged_tokens_all_launch_shapes(launch):
 
 
 @pytest.mark.parametrize("shape,g", [((2, 2, 64), 64), ((2, 1, 96), 32), ((1, 1, 256), 256),
-                                     ((1, 2, 128), 128), ((1, 1, 128), 32)])
+                                     ((1, 2, 128), 128), ((1, 1, 128), 32), ((1, 2, 512), 512),
+                                     ((1, 1, 512), 256)])
 def test_load_shapes_and_groups(shape, g):
     tokens = [40, 128, 17]
     precs = [B.PREC_INT4, B.PREC_INT8, B.PREC_INT4]
@@ -817,6 +822,60 @@ def test_cold_stress_shape_through_the_pool(pinned_dma):
     for r in range(2):
         _check_sampled_tiles(ctx, (L, H, D), T, g, [B.PREC_INT4] * n, orders[r], srcs, packs,
                              outs[r], 2, np.random.default_rng(2 + r))
+    ctx.destroy()
+
+
+@pytest.mark.parametrize("pinned_dma", [False, True])
+def test_cold_stress_at_its_full_request_shape(pinned_dma):
+    """The cold-path stress configuration as stated: 4 concurrent requests on 4 streams, each
+    32 chunks x 1024 tokens, int4 with group 64, 8B KV shape, all 128 chunks distinct and in pinned
+    host memory (4.5 GiB), 4 GiB of cache per request.  Three chunks of every request are
+    rebuilt from their seed and tiles sampled from them recomputed by the oracle; the first and
+    the last rows of every chunk of every request are compared with a second, single-stream
+    load of the same chunk."""
+    L, H, D, T, g = 32, 8, 128, 1024, 64
+    n_req, per_req = 4, 32
+    n = n_req * per_req
+    ctx = _pool_ctx(L, H, D, T, g, hbm_slots=0, pin_slots=n, stg_slots=4, tau_gpu_ppm=0,
+                    precs=[B.PREC_INT4], pinned_dma=pinned_dma)
+    nbytes = ctx.chunk_bytes(B.PREC_INT4, T)
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    for i in range(n):
+        ctx.quantize_chunk(wl.kv_chunk_device(L, H, D, T, 4000 + i), T, B.PREC_INT4, g, dst)
+        ctx.pool_insert(i, B.PREC_INT4, T, dst, B.TIER_PINNED, packed_is_device=True)
+        torch.cuda.synchronize()
+    rng = np.random.default_rng(11)
+    perm = rng.permutation(n)
+    orders = [[int(c) for c in perm[r * per_req:(r + 1) * per_req]] for r in range(n_req)]
+    streams = [torch.cuda.Stream() for _ in range(n_req)]
+    outs = [torch.empty((L, 2, H, per_req * T, D), dtype=torch.int16, device="cuda") for _ in range(n_req)]
+    print("four loads on four streams", flush=True)
+    for r in range(n_req):
+        st, _ = ctx.load_chunks(orders[r], outs[r], per_req * T, stream=streams[r])
+        assert st["n_pinned_hits"] == per_req and st["bytes_h2d"] == per_req * nbytes
+        assert st["tokens"] == per_req * T
+    torch.cuda.synchronize()
+    one = torch.empty((L, 2, H, T, D), dtype=torch.int16, device="cuda")
+    for r in range(n_req):
+        print("checking request", r, flush=True)
+        for pos in sorted(rng.choice(per_req, 3, replace=False)):
+            c = orders[r][pos]
+            src = wl.kv_chunk_device(L, H, D, T, 4000 + c)
+            ptr, nb = ctx.pool_slot(c, B.TIER_PINNED)
+            pk = torch.empty(nb, dtype=torch.uint8, device="cuda")
+            ctx.quantize_chunk(src, T, B.PREC_INT4, g, pk)      # the same bytes the pool holds
+            torch.cuda.synchronize()
+            held = np.frombuffer(ctypes.string_at(ptr, nb), np.uint8)
+            assert np.array_equal(held, pk.cpu().numpy()), (r, pos, c)
+            view = outs[r][:, :, :, pos * T:(pos + 1) * T]
+            _check_sampled_tiles(ctx, (L, H, D), T, g, {c: B.PREC_INT4}, [c], {c: src}, {c: pk},
+                                 view, 2, rng)
+        # every chunk: its first and last token rows against a plain single-stream load
+        for pos, c in enumerate(orders[r]):
+            ctx.load_chunks([c], one, T)
+            torch.cuda.synchronize()
+            for row in (0, T - 1):
+                assert torch.equal(outs[r][:, :, :, pos * T + row], one[:, :, :, row]), (r, pos, c)
     ctx.destroy()
 
 

@@ -26,7 +26,8 @@ def dev_u16(a):
 
 
 @pytest.mark.parametrize("prec", sorted(ORC))
-@pytest.mark.parametrize("shape", [(2, 2, 64, 128, 64), (1, 3, 96, 37, 32), (3, 1, 128, 1000, 128)])
+@pytest.mark.parametrize("shape", [(2, 2, 64, 128, 64), (1, 3, 96, 37, 32), (3, 1, 128, 1000, 128),
+                                   (1, 2, 512, 19, 512)])
 def test_sq_error_equals_oracle_rmse(prec, shape):
     L, H, D, T, g = shape
     src = wl.kv_chunk(L, H, D, T, 21)

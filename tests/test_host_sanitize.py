@@ -51,3 +51,28 @@ def test_host_runtime_from_four_threads_under_tsan(tmp_path):
     r = subprocess.run([exe, "2000"], capture_output=True, text=True, env=env, timeout=300)
     assert r.returncode == 0, (r.stdout + r.stderr)[-4000:]
     assert "threads_host ok" in r.stdout
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"),
+                    reason="needs hipcc")
+def test_pageable_and_file_tiers_with_real_files_under_asan_ubsan(tmp_path):
+    """dry_run = 2 contexts: no HIP call, but real host copies and real (also O_DIRECT) files.
+    Covers the direct-I/O buffer that a later, larger file slab must not overrun."""
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    exe = str(tmp_path / "tiers_host")
+    csrc = os.path.join(ROOT, "paper_2510_20878_amd", "csrc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17",
+           "-Xarch_host", "-fsanitize=address,undefined", "-Xarch_host", "-fno-omit-frame-pointer",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Wno-unused-command-line-argument",
+           os.path.join(ROOT, "tests", "host_sanitize", "tiers_host.cpp"),
+           *[os.path.join(csrc, f) for f in SOURCES],
+           "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-3000:]
+    pools = tmp_path / "pools"
+    pools.mkdir()
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="halt_on_error=1")
+    r = subprocess.run([exe, str(pools)], capture_output=True, text=True, env=env, timeout=300)
+    assert r.returncode == 0, (r.stdout + r.stderr)[-4000:]
+    assert "tiers_host ok" in r.stdout

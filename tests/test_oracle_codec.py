@@ -68,11 +68,11 @@ def test_ties_round_to_even_code():
 
 # ---- P1: error bound, directed rounding -----------------------------------------
 @pytest.mark.parametrize("bits", [4, 8])
-@pytest.mark.parametrize("g", [32, 64, 128])
+@pytest.mark.parametrize("g", [32, 64, 128, 512])
 def test_error_bound_half_scale(bits, g):
     rng = np.random.default_rng(10 + bits + g)
     qmax = (1 << bits) - 1
-    n_groups = 3000
+    n_groups = 3000 if g < 512 else 1000
     scales = np.minimum(np.exp(rng.normal(0, 3, n_groups)), 500.0)
     offs = rng.normal(0, 5, n_groups) * scales
     for k in range(n_groups):
@@ -126,11 +126,15 @@ def test_requantising_dequantised_values_with_stored_meta_is_stable(bits):
 
 # ---- P6: reductions to library routines -------------------------------------------
 @pytest.mark.parametrize("bits", [4, 8])
-def test_codes_equal_numpy_expression_given_stored_meta(bits):
-    tiny = wl.tiny_config(0)
-    L, H, D = tiny["shape"]
-    src = tiny["chunks"][1]
-    g = 64
+@pytest.mark.parametrize("g", [64, 512])
+def test_codes_equal_numpy_expression_given_stored_meta(bits, g):
+    if g == 64:
+        tiny = wl.tiny_config(0)
+        L, H, D = tiny["shape"]
+        src = tiny["chunks"][1]
+    else:                                    # the widest group: one per row of a 512-wide head
+        L, H, D = 1, 2, 512
+        src = wl.kv_chunk(L, H, D, 128, 31)
     packed, _ = codec.quantize_pack_chunk(src, bits, g)
     codes, sh, zh = codec.unpack_chunk(packed, (L, H, D), 128, bits, g)
     x = wl.bf16_words_to_f32(src).reshape(L, 2, H, 128, D // g, g)

@@ -119,7 +119,8 @@ def _coded_chunk(bits, g, T, D, rng):
 
 
 @pytest.mark.parametrize("bits,g,D", [(4, 64, 64), (4, 128, 128), (8, 64, 128), (8, 32, 64),
-                                      (8, 256, 256), (4, 32, 96)])
+                                      (8, 256, 256), (4, 32, 96), (4, 256, 256), (8, 512, 512),
+                                      (4, 512, 512)])
 def test_wave_view_consecutive_words_give_consecutive_stores(bits, g, D):
     """Simulate what the layout is for.  Lane i of a 64-lane wave reads 16-byte
     word i of each 1024-byte slab of a block; octet number w of what the lane has
