@@ -458,6 +458,17 @@ int ha_rag_attend_chunks_workspace_bytes(ha_rag_ctx *ctx, const uint64_t *ids,
  * one slot. */
 int ha_rag_register_slab(ha_rag_ctx *ctx, uint32_t tier, uint32_t prec, void *base, size_t bytes);
 
+/* Declares that the pinned-tier copies of chunks of tag `prec` are caller-owned: instead of a
+ * slab that the library cuts into slots, every such chunk names the pinned address its packed
+ * bytes lie at (ha_rag_pool_insert_external).  This is queuePIN of Algorithm 2 for a knowledge
+ * base that the caller already keeps in page-locked memory (Sec. 2.3): the library reads those
+ * bytes (the kernel over the link, or DMA) and never writes, moves or frees them; Algorithm 2
+ * places no new copies in this tier for the tag (a chunk found in pageable memory or a file
+ * keeps going through the bounce buffers), so nothing is ever evicted from it.  Takes the place
+ * of ha_rag_register_slab(TIER_PINNED, prec): EINVAL if either was called before for the tag.
+ * Register before ha_rag_register_staging, which sizes its slots by the tags declared so far. */
+int ha_rag_register_external(ha_rag_ctx *ctx, uint32_t prec);
+
 /* The disk tier for tag `prec`: the file `path` (created and grown if needed) cut
  * into slots rounded up to 4096 bytes.  It is kept open until ha_rag_destroy and
  * is not deleted.  EIO if it cannot be opened or grown. */
@@ -499,8 +510,29 @@ int ha_rag_pool_insert_half(ha_rag_ctx *ctx, uint64_t id, uint32_t part, uint32_
                             uint32_t n_tokens, const void *packed, int packed_is_device,
                             uint32_t tier, void *stream);
 
-/* Address and size of the slot that holds chunk `id` in `tier` (ENOENT if not
- * there). */
+/* Adds chunk `id` (whole, or a keys-only / values-only unit: `part`) with its pinned-tier copy
+ * at the caller's address `pinned` (page-locked, device-visible, 16-byte aligned,
+ * ha_rag_chunk_bytes() bytes in the packed layout; halved for a unit), which must stay valid
+ * and unchanged while the chunk is in the pool.  Several ids may name the same address.
+ * ENOSPC unless ha_rag_register_external was called for the tag; otherwise like
+ * ha_rag_pool_insert (EINVAL duplicate in the tier, EFORMAT if the id exists with another tag,
+ * length or part).  The chunk can get an HBM copy through Algorithm 2 or ha_rag_pool_promote
+ * like any other. */
+int ha_rag_pool_insert_external(ha_rag_ctx *ctx, uint64_t id, uint32_t part, uint32_t prec,
+                                uint32_t n_tokens, const void *pinned);
+
+/* Moves the pinned-tier copies of ids[n] to the addresses pinned[n] (host arrays): later calls
+ * read chunk ids[i] at pinned[i], work already enqueued keeps reading the old address, which the
+ * caller therefore keeps intact until that work has finished.  For a knowledge base whose
+ * pinned window moves over a larger store (Sec. 2.1: chunks are loaded on demand).  An HBM copy
+ * made earlier keeps the bytes it was made from.  Nothing changes unless every entry is good:
+ * ENOENT unknown id, EINVAL for a chunk without a caller-owned pinned copy or a bad address. */
+int ha_rag_pool_repoint_external(ha_rag_ctx *ctx, const uint64_t *ids, const void *const *pinned,
+                                 size_t n);
+
+/* Address and size of the copy of chunk `id` in `tier` (HBM, pinned or pageable; ENOENT if
+ * not there): where Algorithm 1 step 3's Compression writes a chunk whose slot was reserved with
+ * ha_rag_pool_insert(packed = NULL), and where a consumer reads it in place. */
 int ha_rag_pool_slot(ha_rag_ctx *ctx, uint64_t id, uint32_t tier, void **ptr, size_t *bytes);
 
 /* Copies the pinned master of `id` into an HBM slot on `stream` regardless of its
@@ -519,6 +551,9 @@ int ha_rag_pool_evict(ha_rag_ctx *ctx, uint64_t id, uint32_t tier);
  * unknown id. */
 int ha_rag_pool_remove(ha_rag_ctx *ctx, uint64_t id);
 
+/* What the pool knows about chunk `id`: its tag (fixed offline, Algorithm 1 step 3), its access
+ * count and rank (Algorithm 1 step 1, Algorithm 2 step 1) and which of Algorithm 2's queues hold
+ * a copy.  ENOENT unknown id. */
 int ha_rag_pool_query(ha_rag_ctx *ctx, uint64_t id, ha_rag_chunk_info *info);
 
 /* The knowledge base is files (Sec. 2.1: the precomputed KV is stored and loaded on demand);
@@ -535,11 +570,10 @@ int ha_rag_pool_query(ha_rag_ctx *ctx, uint64_t id, ha_rag_chunk_info *info);
 int ha_rag_pool_save_index(ha_rag_ctx *ctx, const char *path);
 int ha_rag_pool_load_index(ha_rag_ctx *ctx, const char *path, size_t *n_loaded);
 
-/* Ids resident in `tier` (HBM, pinned or pageable), least recently used first;
- * returns how many were written (at most `cap`) through *n.  ha_rag_pool_hbm_lru is
- * the same for TIER_HBM. */
+/* The order Algorithm 2's "put C_i in queueX with LRU" evicts in: ids resident in `tier` (HBM,
+ * pinned or pageable), least recently used first; returns how many were written (at most
+ * `cap`) through *n. */
 int ha_rag_pool_lru(ha_rag_ctx *ctx, uint32_t tier, uint64_t *ids, size_t cap, size_t *n);
-int ha_rag_pool_hbm_lru(ha_rag_ctx *ctx, uint64_t *ids, size_t cap, size_t *n);
 
 /* ---- hotness (Algorithm 1 step 1, Algorithm 2 step 1) ------------------------ */
 
@@ -554,6 +588,8 @@ int ha_rag_set_counts(ha_rag_ctx *ctx, const uint64_t *ids, const uint64_t *coun
  * recomputes the list boundaries idx1, idx2, idx3 of Algorithm 2 step 1. */
 int ha_rag_rerank(ha_rag_ctx *ctx);
 
+/* Position of `id` in the sort of Algorithm 1 step 1 as of the last rerank (0 = most frequent;
+ * UINT32_MAX if the chunk was inserted since).  ENOENT unknown id. */
 int ha_rag_get_rank(ha_rag_ctx *ctx, uint64_t id, uint32_t *rank);
 
 /* ---- online: the load (Algorithm 2 step 2 + decompression + concatenation) --- */

@@ -13,14 +13,28 @@ import numpy as np
 from . import build as _build
 
 _lib = None
+_native = False
+
+
+def select_library(native):
+    """Which build of the oracle the calls below use: the -O2 one of the tests (default), or the
+    -O3 -march=native one for the benchmark's timed CPU leg (compiled here, on the machine that
+    times it).  The source is the same."""
+    global _lib, _native
+    if bool(native) != _native:
+        _native = bool(native)
+        _lib = None
 
 
 def lib():
     global _lib
     if _lib is None:
-        path = _build.LIB
-        if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
-            _build.build()
+        if _native:
+            path = _build.build_native(force=False)
+        else:
+            path = _build.LIB
+            if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
+                _build.build()
         L = C.CDLL(path)
         u8p, u16p, f32p = C.POINTER(C.c_uint8), C.POINTER(C.c_uint16), C.POINTER(C.c_float)
         L.orc_bf16_to_f32.restype = C.c_float

@@ -28,14 +28,15 @@ SYMBOLS = [
     "ha_rag_create", "ha_rag_destroy", "ha_rag_last_hip_error", "ha_rag_set_launch_params",
     "ha_rag_quantize_chunk", "ha_rag_load_packed", "ha_rag_register_slab",
     "ha_rag_register_staging", "ha_rag_pool_insert", "ha_rag_pool_slot", "ha_rag_pool_promote",
-    "ha_rag_pool_evict", "ha_rag_pool_query", "ha_rag_pool_hbm_lru", "ha_rag_touch",
+    "ha_rag_pool_evict", "ha_rag_pool_query", "ha_rag_touch",
     "ha_rag_set_counts", "ha_rag_rerank", "ha_rag_get_rank", "ha_rag_load_chunks",
     "ha_rag_load_batch", "ha_rag_register_disk", "ha_rag_register_bounce", "ha_rag_pool_lru",
     "ha_rag_quantize_half", "ha_rag_pool_insert_half", "ha_rag_load_packed_paged",
     "ha_rag_load_chunks_paged", "ha_rag_chunk_sq_error", "ha_rag_pool_save_index",
     "ha_rag_pool_load_index", "ha_rag_pool_remove", "ha_rag_attend_packed",
     "ha_rag_attend_workspace_bytes", "ha_rag_attend_chunks", "ha_rag_attend_chunks_workspace_bytes",
-    "ha_rag_place_chunks", "ha_rag_attend_packed_static",
+    "ha_rag_place_chunks", "ha_rag_attend_packed_static", "ha_rag_register_external",
+    "ha_rag_pool_insert_external", "ha_rag_pool_repoint_external",
 ]
 
 
@@ -166,7 +167,9 @@ def lib():
             "ha_rag_pool_evict": (C.c_int, [vp, u64, u32]),
             "ha_rag_pool_remove": (C.c_int, [vp, u64]),
             "ha_rag_pool_query": (C.c_int, [vp, u64, P(ChunkInfo)]),
-            "ha_rag_pool_hbm_lru": (C.c_int, [vp, P(u64), sz, P(sz)]),
+            "ha_rag_register_external": (C.c_int, [vp, u32]),
+            "ha_rag_pool_insert_external": (C.c_int, [vp, u64, u32, u32, u32, vp]),
+            "ha_rag_pool_repoint_external": (C.c_int, [vp, P(u64), P(vp), sz]),
             "ha_rag_touch": (C.c_int, [vp, P(u64), sz]),
             "ha_rag_set_counts": (C.c_int, [vp, P(u64), P(u64), sz]),
             "ha_rag_rerank": (C.c_int, [vp]),
@@ -493,10 +496,21 @@ class Context:
         return list(ids[:n.value])
 
     def pool_hbm_lru(self, cap=1 << 16):
-        ids = (C.c_uint64 * cap)()
-        n = C.c_size_t()
-        self._chk(lib().ha_rag_pool_hbm_lru(self._h, ids, cap, C.byref(n)), "ha_rag_pool_hbm_lru")
-        return list(ids[:n.value])
+        return self.pool_lru(TIER_HBM, cap)
+
+    def register_external(self, prec):
+        self._chk(lib().ha_rag_register_external(self._h, prec), "ha_rag_register_external")
+
+    def pool_insert_external(self, cid, prec, n_tokens, pinned, part=PART_KV):
+        """pinned: address (int) or pinned tensor holding the packed bytes; stays the caller's."""
+        self._chk(lib().ha_rag_pool_insert_external(self._h, cid, part, prec, n_tokens, _addr(pinned)),
+                  "ha_rag_pool_insert_external")
+
+    def pool_repoint_external(self, ids, addrs):
+        n = len(ids)
+        arr = (C.c_void_p * max(n, 1))(*[int(a) for a in addrs])
+        self._chk(lib().ha_rag_pool_repoint_external(self._h, _u64s(ids), arr, n),
+                  "ha_rag_pool_repoint_external")
 
     def touch(self, ids):
         self._chk(lib().ha_rag_touch(self._h, _u64s(ids), len(ids)), "ha_rag_touch")

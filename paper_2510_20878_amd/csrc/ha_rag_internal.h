@@ -86,11 +86,14 @@ struct Slab {
     size_t slot_bytes = 0;
     uint32_t n_slots = 0;
     bool reg = false;
+    bool external = false;             // pinned tier only: every slot is a caller-owned address
+    std::vector<uint8_t *> ext;        // ... kept here, one per slot; the slab grows on demand
     std::vector<uint32_t> free_slots;  // stack
     std::vector<SlotUse> use;
     std::list<uint32_t> lru;           // chunk indices resident here, least recent first
     bool registered() const { return reg; }
-    uint8_t *ptr(int32_t s) const { return base + (size_t)s * slot_bytes; }
+    bool holds_copies() const { return reg && !external; }  // Algorithm 2 may place copies here
+    uint8_t *ptr(int32_t s) const { return external ? ext[(size_t)s] : base + (size_t)s * slot_bytes; }
     off_t offset(int32_t s) const { return (off_t)((size_t)s * slot_bytes); }
 };
 

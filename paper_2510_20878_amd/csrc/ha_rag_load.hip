@@ -182,7 +182,7 @@ void alg2_step(ha_rag_ctx *c, uint32_t ci, uint32_t r, uint64_t off, uint64_t ca
         // only a tier faster than the one it was found in gets one
         uint32_t want = ch.rank == kNoRank ? HA_RAG_TIER_DISK : c->list_of(ch.rank);
         if (want > floor_tier) want = floor_tier;  // HA_RAG_TIER_DISK = no floor
-        if (want < found && c->slab[want][ch.prec].registered()) {
+        if (want < found && c->slab[want][ch.prec].holds_copies()) {
             uint64_t ev;
             const int32_t slot = tier_acquire(c, want, ch.prec, &ev, call);
             if (slot >= 0) {

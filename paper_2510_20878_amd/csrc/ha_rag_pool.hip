@@ -193,17 +193,21 @@ uint32_t new_chunk_entry(ha_rag_ctx *c)
 
 void rerank_locked(ha_rag_ctx *c)
 {
-    std::vector<uint32_t> order;
+    // the sort keys next to each other (not reached through the chunk table by every comparison)
+    struct Key {
+        uint64_t count, id;
+        uint32_t ci;
+    };
+    std::vector<Key> order;
     order.reserve(c->chunks.size());
     for (size_t i = 0; i < c->chunks.size(); ++i)
-        if (c->chunks[i].id != HA_RAG_NO_CHUNK) order.push_back((uint32_t)i);
+        if (c->chunks[i].id != HA_RAG_NO_CHUNK) order.push_back(Key{c->chunks[i].count, c->chunks[i].id, (uint32_t)i});
     const size_t n = order.size();  // N of Algorithm 2 step 1: the chunks that exist
-    std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
-        const Chunk &x = c->chunks[a], &y = c->chunks[b];
+    std::sort(order.begin(), order.end(), [](const Key &x, const Key &y) {
         if (x.count != y.count) return x.count > y.count;
         return x.id < y.id;
     });
-    for (size_t r = 0; r < n; ++r) c->chunks[order[r]].rank = (uint32_t)r;
+    for (size_t r = 0; r < n; ++r) c->chunks[order[r].ci].rank = (uint32_t)r;
     // idx_1 = tau_GPU * N, idx_2 = tau_PIN * N + idx_1, idx_3 = tau_PAGE * N + idx_2
     const uint32_t tau[3] = {c->cfg.tau_gpu_ppm, c->cfg.tau_pin_ppm, c->cfg.tau_page_ppm};
     uint64_t acc = 0;
@@ -240,6 +244,7 @@ int register_slab_common(ha_rag_ctx *c, Slab &sl, uint32_t prec, size_t bytes, s
     if (rc) return rc;
     const size_t slot = (total + align - 1) / align * align;
     if (bytes < slot) return HA_RAG_EINVAL;
+    if (bytes == SIZE_MAX) bytes = 0;  // a slab of caller-owned addresses: no slots yet
     const size_t n_slots = bytes / slot;
     if (n_slots > 0x7FFFFFFFu) return HA_RAG_EINVAL;
     sl.slot_bytes = slot;
@@ -265,6 +270,19 @@ int ha_rag_register_slab(ha_rag_ctx *c, uint32_t tier, uint32_t prec, void *base
     int rc = register_slab_common(c, sl, prec, bytes, 256);
     if (rc) return rc;
     sl.base = static_cast<uint8_t *>(base);
+    return HA_RAG_OK;
+}
+
+int ha_rag_register_external(ha_rag_ctx *c, uint32_t prec)
+{
+    if (!c || prec >= HA_RAG_N_PREC) return HA_RAG_EINVAL;
+    std::lock_guard<std::mutex> g(c->mu);
+    Slab &sl = c->slab[HA_RAG_TIER_PINNED][prec];
+    if (sl.registered()) return HA_RAG_EINVAL;
+    // a slab without memory of its own: slots are added as chunks are inserted
+    int rc = register_slab_common(c, sl, prec, SIZE_MAX, 256);
+    if (rc) return rc;
+    sl.external = true;
     return HA_RAG_OK;
 }
 
@@ -358,6 +376,7 @@ static int insert_impl(ha_rag_ctx *c, uint64_t id, uint32_t part, uint32_t prec,
     std::lock_guard<std::mutex> g(c->mu);
     Slab &sl = c->slab[tier][prec];
     if (!sl.registered()) return HA_RAG_ENOSPC;
+    if (sl.external) return HA_RAG_EINVAL;  // its slots are the caller's memory: ha_rag_pool_insert_external
     size_t total;
     int rc = chunk_bytes_impl(c->cfg.n_layers, c->cfg.n_kv_heads, c->cfg.head_dim, prec,
                               c->group_of(prec), n_tokens, nullptr, nullptr, &total, part);
@@ -447,6 +466,71 @@ int ha_rag_pool_insert_half(ha_rag_ctx *c, uint64_t id, uint32_t part, uint32_t 
 {
     if (part != kPartK && part != kPartV) return HA_RAG_EINVAL;
     return insert_impl(c, id, part, prec, n_tokens, packed, packed_is_device, tier, stream);
+}
+
+int ha_rag_pool_insert_external(ha_rag_ctx *c, uint64_t id, uint32_t part, uint32_t prec,
+                                uint32_t n_tokens, const void *pinned)
+{
+    if (!c || prec >= HA_RAG_N_PREC || id == HA_RAG_NO_CHUNK || part > kPartV) return HA_RAG_EINVAL;
+    if (!pinned || ((uintptr_t)pinned & 15u)) return HA_RAG_EINVAL;
+    if (n_tokens == 0 || n_tokens > c->cfg.max_chunk_tokens) return HA_RAG_EINVAL;
+    if (part == kPartKV && c->cfg.half_slots) return HA_RAG_EFORMAT;
+    std::lock_guard<std::mutex> g(c->mu);
+    size_t total;
+    int rc = chunk_bytes_impl(c->cfg.n_layers, c->cfg.n_kv_heads, c->cfg.head_dim, prec,
+                              c->group_of(prec), n_tokens, nullptr, nullptr, &total, part);
+    if (rc) return rc;
+    Slab &sl = c->slab[HA_RAG_TIER_PINNED][prec];
+    if (!sl.registered()) return HA_RAG_ENOSPC;  // ha_rag_register_external first
+    if (!sl.external) return HA_RAG_EINVAL;      // the library's own pinned slab holds this tag
+    uint32_t ci;
+    Chunk *ch = find_chunk(c, id, &ci);
+    if (ch) {
+        if (ch->slot[HA_RAG_TIER_PINNED] >= 0) return HA_RAG_EINVAL;
+        if (ch->prec != prec || ch->n_tokens != n_tokens || ch->part != part) return HA_RAG_EFORMAT;
+    }
+    int32_t slot;
+    if (!sl.free_slots.empty()) {
+        slot = (int32_t)sl.free_slots.back();
+        sl.free_slots.pop_back();
+    } else {
+        if (sl.n_slots == 0x7FFFFFFFu) return HA_RAG_ENOSPC;
+        slot = (int32_t)sl.n_slots++;
+        sl.use.emplace_back();
+        sl.ext.push_back(nullptr);
+    }
+    sl.ext[(size_t)slot] = const_cast<uint8_t *>(static_cast<const uint8_t *>(pinned));
+    if (!ch) {
+        ci = new_chunk_entry(c);
+        ch = &c->chunks[ci];
+        ch->id = id;
+        ch->prec = prec;
+        ch->n_tokens = n_tokens;
+        ch->part = part;
+        ch->bytes = total;
+        c->index.emplace(id, ci);
+    }
+    tier_attach(c, HA_RAG_TIER_PINNED, ci, slot);
+    return HA_RAG_OK;
+}
+
+int ha_rag_pool_repoint_external(ha_rag_ctx *c, const uint64_t *ids, const void *const *pinned, size_t n)
+{
+    if (!c || (n && (!ids || !pinned))) return HA_RAG_EINVAL;
+    std::lock_guard<std::mutex> g(c->mu);
+    for (size_t i = 0; i < n; ++i) {  // checks first: nothing changes unless every entry is good
+        const Chunk *ch = find_chunk(c, ids[i]);
+        if (!ch) return HA_RAG_ENOENT;
+        if (ch->slot[HA_RAG_TIER_PINNED] < 0 || !c->slab[HA_RAG_TIER_PINNED][ch->prec].external)
+            return HA_RAG_EINVAL;
+        if (!pinned[i] || ((uintptr_t)pinned[i] & 15u)) return HA_RAG_EINVAL;
+    }
+    for (size_t i = 0; i < n; ++i) {
+        const Chunk *ch = find_chunk(c, ids[i]);
+        c->slab[HA_RAG_TIER_PINNED][ch->prec].ext[(size_t)ch->slot[HA_RAG_TIER_PINNED]] =
+            const_cast<uint8_t *>(static_cast<const uint8_t *>(pinned[i]));
+    }
+    return HA_RAG_OK;
 }
 
 int ha_rag_pool_slot(ha_rag_ctx *c, uint64_t id, uint32_t tier, void **ptr, size_t *bytes)
@@ -558,11 +642,6 @@ int ha_rag_pool_lru(ha_rag_ctx *c, uint32_t tier, uint64_t *ids, size_t cap, siz
     *n = std::min(cap, v.size());
     for (size_t i = 0; i < *n; ++i) ids[i] = v[i]->id;
     return HA_RAG_OK;
-}
-
-int ha_rag_pool_hbm_lru(ha_rag_ctx *c, uint64_t *ids, size_t cap, size_t *n)
-{
-    return ha_rag_pool_lru(c, HA_RAG_TIER_HBM, ids, cap, n);
 }
 
 // ---- the knowledge base survives the process: index of the file tier ---------------

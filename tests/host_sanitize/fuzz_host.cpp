@@ -209,7 +209,7 @@ int main(int argc, char **argv)
             // invariants: residency lists are consistent with per-chunk queries
             uint64_t lru[256];
             size_t n_lru = 0;
-            REQUIRE(ha_rag_pool_hbm_lru(ctx, lru, 256, &n_lru) == HA_RAG_OK);
+            REQUIRE(ha_rag_pool_lru(ctx, HA_RAG_TIER_HBM, lru, 256, &n_lru) == HA_RAG_OK);
             REQUIRE(n_lru <= (size_t)hbm_slots * HA_RAG_N_PREC);
             std::set<uint64_t> seen;
             for (size_t i = 0; i < n_lru; ++i) {

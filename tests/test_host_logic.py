@@ -577,6 +577,70 @@ def test_hundred_thousand_ids_ranks_lists_and_trace_equal_oracle():
     ctx.destroy()
 
 
+def test_caller_owned_pinned_masters_of_a_hundred_thousand_ids():
+    """The Zipf configuration's pool as the benchmark builds it: 100k ids whose pinned copies
+    are caller-owned addresses (a small ring of buffers that many ids share), an HBM slab that
+    holds GPU_LIST, promotion by Algorithm 2.  The trace equals the plain simulation with an
+    unbounded pinned queue that holds every chunk; addresses follow insert and repoint."""
+    N = 100_000
+    taus = [30_000, 970_000, 0]
+    cap = 3000
+    ctx = B.Context(2, 2, 64, 128, group_int8=64, group_int4=64, tau_gpu_ppm=taus[0], tau_pin_ppm=taus[1],
+                    rerank_interval=0, dry_run=True)
+    slot = (ctx.chunk_bytes(B.PREC_16, 128) + 255) // 256 * 256
+    ring = [0x7B0000000000 + 4096 * k for k in range(64)]
+    with pytest.raises(B.HaRagError) as e:
+        ctx.pool_insert_external(0, B.PREC_16, 128, ring[0])
+    assert e.value.code == B.ENOSPC                       # the tag was not declared
+    ctx.register_external(B.PREC_16)
+    with pytest.raises(B.HaRagError) as e:
+        ctx.register_slab(B.TIER_PINNED, B.PREC_16, FAKE_PIN, slot * 4)
+    assert e.value.code == B.EINVAL                       # one pinned tier per tag
+    ctx.register_slab(B.TIER_HBM, B.PREC_16, FAKE_HBM, slot * cap)
+    ctx.register_staging(FAKE_STG, slot * 4)
+    for c in range(N):
+        ctx.pool_insert_external(c, B.PREC_16, 128, ring[c % 64])
+    with pytest.raises(B.HaRagError) as e:
+        ctx.pool_insert_external(5, B.PREC_16, 128, ring[1])
+    assert e.value.code == B.EINVAL                       # already there
+    with pytest.raises(B.HaRagError) as e:
+        ctx.pool_insert(N, B.PREC_16, 128, None, B.TIER_PINNED)
+    assert e.value.code == B.EINVAL                       # that tier's slots are the caller's
+    with pytest.raises(B.HaRagError) as e:
+        ctx.pool_insert_external(N, B.PREC_16, 128, ring[1] + 4)
+    assert e.value.code == B.EINVAL                       # misaligned
+    info = ctx.pool_query(70)
+    assert info.in_pinned and info.pinned_ptr == ring[70 % 64] and not info.in_hbm
+    ctx.pool_repoint_external([70, 71], [ring[3], ring[4]])
+    assert ctx.pool_query(70).pinned_ptr == ring[3] and ctx.pool_slot(71, B.TIER_PINNED)[0] == ring[4]
+    with pytest.raises(B.HaRagError) as e:
+        ctx.pool_repoint_external([70, N + 5], [ring[9], ring[9]])
+    assert e.value.code == B.ENOENT and ctx.pool_query(70).pinned_ptr == ring[3]
+    ctx.rerank()                                          # no counts yet: ranks follow the ids
+    sim = pl.TierSim(list(range(N)), taus, (cap, None, 0))
+    sim.seed(sim.PIN, range(N))
+    hits = 0
+    for k, req in enumerate(wl.zipf_requests(N, 1500, 8, 5)):
+        ids = [int(r) for r in req]
+        st, tr = ctx.load_chunks(ids, FAKE_HBM, 8 * 128, want_trace=True)
+        hits += st["n_hbm_hits"]
+        for c, t in zip(ids, tr):
+            tier, placed = sim.access(c)
+            assert t.found_tier == tier
+            assert t.placed_tier == (placed[0][0] if placed else B.TIER_NONE)
+            assert t.evicted_id == (placed[0][1] if placed and placed[0][1] is not None else B.NO_CHUNK)
+    assert ctx.pool_lru(B.TIER_HBM) == sim.resident(sim.GPU)
+    assert hits / (1500 * 8) > 0.6                        # the top 3 % of ranks draw most accesses
+    # an evicted chunk falls back to the caller's address, and a removed one frees its entry
+    victim = ctx.pool_lru(B.TIER_HBM)[0]
+    ctx.pool_evict(victim, B.TIER_HBM)
+    assert not ctx.pool_query(victim).in_hbm and ctx.pool_query(victim).in_pinned
+    ctx.pool_remove(victim)
+    ctx.pool_insert_external(victim, B.PREC_16, 100, ring[7])
+    assert ctx.pool_query(victim).pinned_ptr == ring[7] and ctx.pool_query(victim).n_tokens == 100
+    ctx.destroy()
+
+
 def test_pinned_only_pool_needs_no_staging_unless_dma_is_asked_for():
     for dma in (False, True):
         ctx = B.Context(2, 2, 64, 128, group_int8=64, group_int4=64, tau_gpu_ppm=500_000, dry_run=True,
