@@ -1064,7 +1064,7 @@ def run_tiers(args, B, wl, torch):
             ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g, tau_gpu_ppm=taus[0],
                             tau_pin_ppm=taus[1], tau_page_ppm=taus[2], rerank_interval=8,
                             disk_o_direct=bool(args.o_direct), n_copy_streams=args.copy_streams,
-                            pinned_dma=bool(args.pinned_dma))
+                            pinned_dma=bool(args.pinned_dma), io_threads=args.io_threads)
             used = sorted(set(precs))
             slot = {p: (ctx.chunk_bytes(p, T) + 4095) // 4096 * 4096 for p in used}
             lists = [t * N // 1_000_000 for t in taus]
@@ -1082,8 +1082,8 @@ def run_tiers(args, B, wl, torch):
                                               pin_memory=(tier == B.TIER_PINNED))
                         ctx.register_slab(tier, p, buf)
                 ctx.register_disk(p, os.path.join(tmpdir, f"{name}_{p}.bin"), slot[p] * n_p)
-            ctx.register_staging(torch.empty(max(slot.values()) * 4, dtype=torch.uint8, device="cuda"))
-            ctx.register_bounce(torch.empty(max(slot.values()) * 4, dtype=torch.uint8, pin_memory=True))
+            ctx.register_staging(torch.empty(max(slot.values()) * 8, dtype=torch.uint8, device="cuda"))
+            ctx.register_bounce(torch.empty(max(slot.values()) * 8, dtype=torch.uint8, pin_memory=True))
             tmp = torch.empty(max(slot.values()), dtype=torch.uint8, device="cuda")
             t0 = time.time()
             for cid in range(N):
@@ -1094,14 +1094,37 @@ def run_tiers(args, B, wl, torch):
             disk_gib = sum(slot[p] * precs.count(p) for p in used) / 2**30
             log(f"{name}: {N} chunks, {disk_gib:.1f} GiB written to {tmpdir} in {time.time() - t0:.1f} s")
             tot = {}
-            times = []
-            for k in range(warmup + steps):
-                t0 = time.perf_counter()
-                st, _ = ctx.load_chunks(draws[k].tolist(), out, cap, stream=stream)
-                torch.cuda.synchronize()
-                dt = time.perf_counter() - t0
-                if k >= warmup:
-                    times.append(dt)
+            n_thr = max(1, args.caller_threads)
+            outs_t = [out] + [torch.empty_like(out) for _ in range(n_thr - 1)]
+            streams_t = [stream] + [torch.cuda.Stream() for _ in range(n_thr - 1)]
+            for k in range(warmup):
+                ctx.load_chunks(draws[k].tolist(), out, cap, stream=stream)
+            torch.cuda.synchronize()
+            # caller threads take the requests in turn, each with a cache and a stream of its own
+            # (the library call releases the interpreter lock, and the context's own lock while
+            # it waits for file reads)
+            import threading
+            stats_t = [[] for _ in range(n_thr)]
+
+            def caller(t):
+                for k in range(warmup + t, warmup + steps, n_thr):
+                    st, _ = ctx.load_chunks(draws[k].tolist(), outs_t[t], cap, stream=streams_t[t])
+                    streams_t[t].synchronize()
+                    stats_t[t].append(st)
+
+            t0 = time.perf_counter()
+            if n_thr == 1:
+                caller(0)
+            else:
+                th = [threading.Thread(target=caller, args=(t,)) for t in range(n_thr)]
+                for x in th:
+                    x.start()
+                for x in th:
+                    x.join()
+            torch.cuda.synchronize()
+            times = [time.perf_counter() - t0]
+            for lst in stats_t:
+                for st in lst:
                     for key, v in st.items():
                         tot[key] = tot.get(key, 0) + v
             ctx.destroy()
@@ -1121,7 +1144,8 @@ def run_tiers(args, B, wl, torch):
         "config": {"workload": f"four tiers (Algorithm 2, thresholds 5/5/10 %): Zipf(1.1) over {N} chunk ids, "
                                "Llama-3-8B KV shape, 512-token chunks, 8 chunks per request, masters in "
                                "files, tags 20 % 16-bit / 30 % int8 / 50 % int4",
-                   "o_direct": bool(args.o_direct), "disk_gib": round(disk_gib, 1)},
+                   "o_direct": bool(args.o_direct), "disk_gib": round(disk_gib, 1),
+                   "caller_threads": max(1, args.caller_threads), "io_threads": args.io_threads or 4},
         "kv_tokens_per_s": tot["tokens"] / wall,
         "tier_hit_rates": {"hbm": tot["n_hbm_hits"] / n_c, "pinned": tot["n_pinned_hits"] / n_c,
                            "pageable": tot["n_pageable_hits"] / n_c, "disk": tot["n_disk_hits"] / n_c},
@@ -1172,6 +1196,10 @@ def main():
                     help="sampled (chunk, layer, head) tile pairs the oracle recomputes after each timed region")
     ap.add_argument("--o-direct", type=int, default=1, help="tiers: open pool files with O_DIRECT")
     ap.add_argument("--disk-dir", default="", help="tiers: directory for the pool files")
+    ap.add_argument("--caller-threads", type=int, default=1,
+                    help="tiers: threads that issue the requests, each with its own cache and stream")
+    ap.add_argument("--io-threads", type=int, default=0,
+                    help="tiers: the context's I/O threads (0 = the library's default, 4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attend", action="store_true",
                     help="hbm8b: skip the short attention-over-packed-chunks measurement appended to the line")

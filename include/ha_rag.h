@@ -47,9 +47,14 @@
  *    position p=r%8; the octet (j,i) starts at byte (j/P)*1024 + i*16 + (j%P)*bits
  *    of its payload block, P = 16/bits; group G=r/group is meta entry
  *    (G % (512/group))*4 + G/(512/group).
- *  - A context is not thread safe against itself: calls on one context are
- *    serialised by an internal mutex; calls that overlap on the GPU are ordered
- *    by the streams and events described at each function.
+ *  - A context may be used from several threads.  Its bookkeeping is guarded by an internal
+ *    mutex, which the online calls (ha_rag_load_chunks, ha_rag_load_batch, ha_rag_place_chunks)
+ *    release while they wait for file reads, host copies or device events, so that requests of
+ *    several threads overlap their I/O with each other and with GPU work (the disk tier is where
+ *    Sec. 3.4 finds the time goes); a copy one call is still writing is passed over by the
+ *    others, which read the chunk from a slower tier.  The offline calls (insert, quantize,
+ *    index) keep it locked.  Work that overlaps on the GPU is ordered by the streams and events
+ *    described at each function.
  */
 #ifndef HA_RAG_H
 #define HA_RAG_H
@@ -144,6 +149,10 @@ typedef struct ha_rag_config {
                                   the compute units free while the link is busy.  Chunks
                                   that are promoted, or come from pageable memory or a
                                   file, always take the DMA route                         */
+    uint32_t io_threads;       /* threads that move chunks from files and pageable memory into
+                                  the bounce buffers, in pieces of 4 MiB: the queue depth the
+                                  file tier sees from one call (0 = 4, at most 64; created at
+                                  the first such transfer)                                 */
 } ha_rag_config;
 
 /* One packed chunk handed to ha_rag_load_packed (no pool involved). */
@@ -260,6 +269,16 @@ int ha_rag_destroy(ha_rag_ctx *ctx);
  * ha_rag_attend_packed_static exceeded ("" if none).
  * With ctx == NULL: the reason the calling thread's last ha_rag_create failed. */
 const char *ha_rag_last_hip_error(ha_rag_ctx *ctx);
+
+/* To be called before the caller destroys a stream it has passed to this context.  The
+ * library orders work across streams (a slot is not overwritten while a load on another
+ * stream may still read it: Algorithm 2's evictions under asynchronous execution) with one
+ * event per stream it has seen, and slots remember their last reader and writer streams by
+ * handle.  This call waits on the host for what the library enqueued on `stream` and drops the
+ * stream from those books, so that a later stream that happens to get the same handle starts
+ * clean and the table of events does not grow with every short-lived stream.  OK for a stream
+ * the context has never seen. */
+int ha_rag_forget_stream(ha_rag_ctx *ctx, void *stream);
 
 /* Launch shape of the gather-dequantize-scatter kernel, for tuning sweeps; the
  * defaults (64 threads, 0, 0, 1, 1) are the measured best.  One wave handles one

@@ -36,7 +36,7 @@ SYMBOLS = [
     "ha_rag_pool_load_index", "ha_rag_pool_remove", "ha_rag_attend_packed",
     "ha_rag_attend_workspace_bytes", "ha_rag_attend_chunks", "ha_rag_attend_chunks_workspace_bytes",
     "ha_rag_place_chunks", "ha_rag_attend_packed_static", "ha_rag_register_external",
-    "ha_rag_pool_insert_external", "ha_rag_pool_repoint_external",
+    "ha_rag_pool_insert_external", "ha_rag_pool_repoint_external", "ha_rag_forget_stream",
 ]
 
 
@@ -44,7 +44,7 @@ class Config(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in (
         "n_layers", "n_kv_heads", "head_dim", "max_chunk_tokens", "group_int8", "group_int4",
         "tau_gpu_ppm", "rerank_interval", "n_copy_streams", "dry_run", "tau_pin_ppm",
-        "tau_page_ppm", "disk_o_direct", "half_slots", "pinned_dma")]
+        "tau_page_ppm", "disk_o_direct", "half_slots", "pinned_dma", "io_threads")]
 
 
 class LaunchParams(C.Structure):
@@ -167,6 +167,7 @@ def lib():
             "ha_rag_pool_evict": (C.c_int, [vp, u64, u32]),
             "ha_rag_pool_remove": (C.c_int, [vp, u64]),
             "ha_rag_pool_query": (C.c_int, [vp, u64, P(ChunkInfo)]),
+            "ha_rag_forget_stream": (C.c_int, [vp, vp]),
             "ha_rag_register_external": (C.c_int, [vp, u32]),
             "ha_rag_pool_insert_external": (C.c_int, [vp, u64, u32, u32, u32, vp]),
             "ha_rag_pool_repoint_external": (C.c_int, [vp, P(u64), P(vp), sz]),
@@ -268,11 +269,11 @@ class Context:
     def __init__(self, n_layers, n_kv_heads, head_dim, max_chunk_tokens, group_int8=128,
                  group_int4=128, tau_gpu_ppm=50_000, rerank_interval=0, n_copy_streams=0,
                  dry_run=False, tau_pin_ppm=0, tau_page_ppm=0, disk_o_direct=False,
-                 half_slots=False, pinned_dma=False):
+                 half_slots=False, pinned_dma=False, io_threads=0):
         self.cfg = Config(n_layers, n_kv_heads, head_dim, max_chunk_tokens, group_int8, group_int4,
-                          tau_gpu_ppm, rerank_interval, n_copy_streams, 1 if dry_run else 0,
+                          tau_gpu_ppm, rerank_interval, n_copy_streams, int(dry_run),
                           tau_pin_ppm, tau_page_ppm, 1 if disk_o_direct else 0,
-                          1 if half_slots else 0, 1 if pinned_dma else 0)
+                          1 if half_slots else 0, 1 if pinned_dma else 0, io_threads)
         self._h = C.c_void_p()
         rc = lib().ha_rag_create(C.byref(self.cfg), C.byref(self._h))
         if rc:
@@ -304,6 +305,9 @@ class Context:
         whole = ha_rag_chunk_bytes(self.cfg.n_layers, self.cfg.n_kv_heads, self.cfg.head_dim, prec,
                                    g, n_tokens)[2]
         return whole if part == PART_KV else whole // 2
+
+    def forget_stream(self, stream):
+        self._chk(lib().ha_rag_forget_stream(self._h, _stream(stream)), "ha_rag_forget_stream")
 
     def set_launch_params(self, threads=64, planes16=0, planes8=0, nt_store=1, nt_load=1):
         lp = LaunchParams(threads, planes16, planes8, int(nt_store), int(nt_load))

@@ -77,7 +77,7 @@ int ha_rag_create(const ha_rag_config *cfg, ha_rag_ctx **out)
     for (uint32_t grp : {cfg->group_int8, cfg->group_int4})
         if (grp != 0 && (!valid_group(grp) || (cfg->head_dim % grp))) return HA_RAG_EFORMAT;
     if (cfg->tau_gpu_ppm > kPPM || cfg->tau_pin_ppm > kPPM || cfg->tau_page_ppm > kPPM ||
-        cfg->n_copy_streams > 8)
+        cfg->n_copy_streams > 8 || cfg->io_threads > 64)
         return HA_RAG_EINVAL;
     if ((uint64_t)cfg->max_chunk_tokens * cfg->head_dim > 0x7FFFFFFFull) return HA_RAG_EINVAL;
     ha_rag_ctx *c = new (std::nothrow) ha_rag_ctx();
@@ -111,6 +111,7 @@ int ha_rag_create(const ha_rag_config *cfg, ha_rag_ctx **out)
 int ha_rag_destroy(ha_rag_ctx *c)
 {
     if (!c) return HA_RAG_EINVAL;
+    if (c->io) io_pool_destroy(c->io);  // joins the I/O threads; no call is running any more
     if (!c->dry()) {
         for (hipStream_t s : c->copy_streams) {
             (void)hipStreamSynchronize(s);

@@ -4,8 +4,11 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <condition_variable>
 #include <cstdint>
+#include <deque>
 #include <list>
+#include <memory>
 #include <mutex>
 #include <string>
 #include <unordered_map>
@@ -53,18 +56,28 @@ struct Chunk {
     uint32_t rank = kNoRank;
     uint64_t last_use[kCacheTiers] = {0, 0, 0};  // sequence number of the last access per tier
     uint64_t made_by[kCacheTiers] = {0, 0, 0};   // load call that created this tier's copy (0: none)
+    // A copy that a running call has booked but whose bytes are not in place yet (the call moves
+    // them with the context unlocked).  Other calls pass such a copy over: they read the chunk
+    // from a slower tier, and neither evict the copy nor book a second one.
+    uint8_t pending[kCacheTiers] = {0, 0, 0};
+    uint32_t in_calls = 0;  // running calls that hold this entry by index: it is not removed meanwhile
     std::list<uint32_t>::iterator lru_it[kCacheTiers];
 
-    int fastest() const
+    bool readable(uint32_t t, uint64_t call) const
+    {
+        return slot[t] >= 0 && (t >= kCacheTiers || !pending[t] || (call && made_by[t] == call));
+    }
+    // fastest tier whose copy can be read; `call`: copies that this call itself booked count
+    int fastest(uint64_t call = 0) const
     {
         for (uint32_t t = 0; t < kTiers; ++t)
-            if (slot[t] >= 0) return (int)t;
+            if (readable(t, call)) return (int)t;
         return -1;
     }
     bool has_slower_copy(uint32_t tier) const
     {
         for (uint32_t t = tier + 1; t < kTiers; ++t)
-            if (slot[t] >= 0) return true;
+            if (readable(t, 0)) return true;
         return false;
     }
 };
@@ -78,6 +91,7 @@ struct SlotUse {
     bool has_writer = false;
     std::vector<hipStream_t> readers;
     std::vector<hipEvent_t> read_events;
+    uint32_t host_readers = 0;  // calls that are reading the slot on the host with the context unlocked
 };
 
 struct Slab {
@@ -104,8 +118,30 @@ struct StagingSlot {
 
 struct BounceSlot {
     hipEvent_t h2d_done = nullptr;
-    bool busy = false;
+    bool busy = false;      // a host -> device copy that reads it may be in flight (h2d_done tells)
+    bool reserved = false;  // a running call owns it: being filled, or waiting for its copy to be enqueued
 };
+
+// One chunk's bytes on their way from a file or from pageable memory into a bounce buffer
+// (and into the host slot Algorithm 2 placed a copy in), cut into pieces that the context's
+// I/O threads move side by side.  Touches no context state.
+struct Transfer {
+    int fd = -1;                  // source: a file ...
+    bool direct = false;
+    off_t off = 0;
+    const uint8_t *src = nullptr; // ... or host memory
+    uint8_t *dst = nullptr;       // bounce buffer
+    uint8_t *dst2 = nullptr;      // placed copy in pinned / pageable memory, or null
+    size_t bytes = 0;
+    std::mutex mu;
+    std::condition_variable cv;
+    size_t pieces_left = 0;
+    int rc = 0;
+    std::string err;
+    int wait();  // blocks until every piece is done; returns the first error
+};
+
+class IoPool;
 
 }  // namespace ha_rag_host
 
@@ -115,7 +151,9 @@ struct ha_rag_ctx {
     std::mutex mu;
     std::string err;  // last failing HIP or I/O call
 
-    std::vector<ha_rag_host::Chunk> chunks;   // entries of removed chunks keep id HA_RAG_NO_CHUNK
+    // entries of removed chunks keep id HA_RAG_NO_CHUNK.  A deque: entries stay where they are
+    // when the table grows, so a call that releases the lock midway may keep references
+    std::deque<ha_rag_host::Chunk> chunks;
     std::vector<uint32_t> dead;                // ... and wait here to be used again
     std::unordered_map<uint64_t, uint32_t> index;
     ha_rag_host::Slab slab[ha_rag_host::kTiers][HA_RAG_N_PREC];
@@ -130,9 +168,11 @@ struct ha_rag_ctx {
 
     uint8_t *bounce = nullptr;  // pinned buffers that pageable / disk chunks pass through
     size_t bounce_slot_bytes = 0;
-    uint8_t *dio = nullptr;     // page-aligned ordinary memory for O_DIRECT transfers: the
+    uint8_t *dio = nullptr;     // page-aligned ordinary memory for O_DIRECT writes: the
                                 // kernel cannot do direct I/O on GPU-pinned host memory
     size_t dio_bytes = 0;
+    std::condition_variable cv; // a bounce buffer was released, a pending copy published, ...
+    ha_rag_host::IoPool *io = nullptr;  // threads that move file / pageable bytes (created on first use)
     std::vector<ha_rag_host::BounceSlot> bnc;
     uint64_t bnc_next = 0;
 
@@ -185,7 +225,11 @@ int chunk_bytes_impl(uint32_t L, uint32_t H, uint32_t D, uint32_t prec, uint32_t
 int io_error(ha_rag_ctx *c, const char *what);
 int read_full(ha_rag_ctx *c, int fd, uint8_t *dst, size_t n, off_t off);
 int write_full(ha_rag_ctx *c, int fd, const uint8_t *src, size_t n, off_t off);
-int read_direct(ha_rag_ctx *c, int fd, uint8_t *dst, size_t bytes, off_t off);
+// The context's I/O threads (queue depth of the file tier).  start() cuts the transfer into
+// pieces and returns at once; Transfer::wait() collects them.
+IoPool *io_pool_create(uint32_t n_threads, bool direct);
+void io_pool_destroy(IoPool *p);
+void io_pool_start(IoPool *p, const std::shared_ptr<Transfer> &t);
 
 // ---- streams, slots, tiers, ranks (ha_rag_pool.hip) ----
 int stream_event(ha_rag_ctx *c, hipStream_t s, hipEvent_t *out);
@@ -202,7 +246,14 @@ int32_t tier_acquire(ha_rag_ctx *c, uint32_t tier, uint32_t prec, uint64_t *evic
                      uint64_t keep_call = 0);
 void rerank_locked(ha_rag_ctx *c);
 uint32_t new_chunk_entry(ha_rag_ctx *c);  // index of a fresh entry of ctx->chunks
-int acquire_bounce(ha_rag_ctx *c, size_t *idx);
+// A bounce buffer of this call's own: *wait_ev is the copy that may still read it (or null).  If
+// all are taken by other calls: waits for one (block) or returns false.
+bool reserve_bounce(ha_rag_ctx *c, std::unique_lock<std::mutex> &lk, bool block, size_t *idx,
+                    hipEvent_t *wait_ev);
+void release_bounce(ha_rag_ctx *c, size_t idx, bool copy_in_flight);
+// Events of the device work that reads or writes a host slot, which the host has to wait for
+// (outside the lock) before it overwrites the slot; the slot's lists are cleared.
+void take_host_write_events(ha_rag_ctx *c, SlotUse &u, std::vector<hipEvent_t> *out);
 
 // ---- attention (ha_rag_attend.hip) ----
 // Address, on the current device, of the scratch array that ha_rag_attend_packed_static uses

@@ -1,11 +1,15 @@
-// File transfers of the disk tier: plain and O_DIRECT reads and writes of whole slots.
+// File transfers of the disk tier: whole-slot reads and writes for the offline calls, and the
+// I/O threads that move pieces of chunks into bounce buffers for the online ones.
 #include "ha_rag_internal.h"
 
 #include <unistd.h>
 
+#include <algorithm>
 #include <cerrno>
 #include <condition_variable>
+#include <cstdlib>
 #include <cstring>
+#include <deque>
 #include <thread>
 
 namespace ha_rag_host {
@@ -50,79 +54,137 @@ int write_full(ha_rag_ctx *c, int fd, const uint8_t *src, size_t n, off_t off)
     return HA_RAG_OK;
 }
 
-// O_DIRECT read of `bytes` at `off` into `dst` (GPU-pinned memory, which direct I/O cannot
-// target): a helper thread reads pieces into the two halves of the page-aligned buffer
-// c->dio while this thread copies the previous piece to dst, so the file read and the
-// host copy overlap.
-int read_direct(ha_rag_ctx *c, int fd, uint8_t *dst, size_t bytes, off_t off)
+// ---- transfers into bounce buffers, in pieces, on the context's I/O threads ----------------
+//
+// A piece is up to kPiece bytes of one chunk: read from the file (through the thread's own
+// page-aligned buffer if the file is open with O_DIRECT, which cannot target GPU-pinned memory)
+// or copied from pageable memory into the bounce buffer, and from there into the host slot that
+// Algorithm 2 placed a copy in, if any.  Pieces of one chunk and of different chunks, from one
+// caller or several, run side by side: that is the queue depth the file sees.
+namespace {
+constexpr size_t kPiece = 4u << 20;
+
+struct Piece {
+    std::shared_ptr<Transfer> t;
+    size_t lo = 0, n = 0;
+};
+
+int move_piece(Transfer &t, size_t lo, size_t n, uint8_t *dio, std::string *err)
 {
-    const size_t half = c->dio_bytes / 2 / kDirectAlign * kDirectAlign;
-    const size_t total = c->io_bytes(bytes);
-    if (half == 0 || total <= half) {  // small: one read, one copy
-        int rc = read_full(c, fd, c->dio, total, off);
-        if (rc) return rc;
-        std::memcpy(dst, c->dio, bytes);
-        return HA_RAG_OK;
-    }
-    const size_t piece = std::min<size_t>(half, 4u << 20);
-    const size_t n_pieces = (total + piece - 1) / piece;
-    std::mutex mu;
-    std::condition_variable cv;
-    size_t produced = 0, consumed = 0;  // pieces read / pieces copied out
-    int rc_reader = HA_RAG_OK;
-    std::string err_reader;
-    std::thread reader([&] {
-        for (size_t i = 0; i < n_pieces; ++i) {
-            {
-                std::unique_lock<std::mutex> lk(mu);
-                cv.wait(lk, [&] { return i < consumed + 2; });  // a free half
+    uint8_t *dst = t.dst + lo;
+    if (t.fd < 0) {
+        std::memcpy(dst, t.src + lo, n);
+    } else {
+        // direct reads are whole 4096-byte units (lo is a multiple of kPiece, which is one)
+        const size_t want = t.direct ? (n + kDirectAlign - 1) / kDirectAlign * kDirectAlign : n;
+        uint8_t *buf = t.direct ? dio : dst;
+        size_t done = 0;
+        while (done < want) {
+            const ssize_t r = pread(t.fd, buf + done, want - done, t.off + (off_t)(lo + done));
+            if (r < 0 && errno == EINTR) continue;
+            if (r < 0) {
+                *err = std::string("pread: ") + std::strerror(errno);
+                return HA_RAG_EIO;
             }
-            const size_t n = std::min(piece, total - i * piece);
-            uint8_t *buf = c->dio + (i & 1) * half;
-            size_t done = 0;
-            int rc = HA_RAG_OK;
-            while (done < n) {
-                const ssize_t r = pread(fd, buf + done, n - done, off + (off_t)(i * piece + done));
-                if (r < 0 && errno == EINTR) continue;
-                if (r <= 0) {
-                    err_reader = r < 0 ? std::string("pread: ") + std::strerror(errno)
-                                       : std::string("pread: unexpected end of file");
-                    rc = HA_RAG_EIO;
-                    break;
-                }
-                done += (size_t)r;
+            if (r == 0) {
+                if (done >= n) break;  // the padding of the last unit lies past the end of the file
+                *err = "pread: unexpected end of file";
+                return HA_RAG_EIO;
             }
-            std::lock_guard<std::mutex> lk(mu);
-            if (rc) rc_reader = rc;
-            produced = i + 1;
-            cv.notify_all();
-            if (rc) return;
+            done += (size_t)r;
         }
-    });
-    int rc = HA_RAG_OK;
-    for (size_t i = 0; i < n_pieces; ++i) {
-        {
-            std::unique_lock<std::mutex> lk(mu);
-            cv.wait(lk, [&] { return produced > i || rc_reader; });
-            if (rc_reader) {
-                rc = rc_reader;
-                break;
-            }
-        }
-        const size_t lo = i * piece;
-        if (lo < bytes) std::memcpy(dst + lo, c->dio + (i & 1) * half, std::min(piece, bytes - lo));
-        std::lock_guard<std::mutex> lk(mu);
-        consumed = i + 1;
-        cv.notify_all();
+        if (t.direct) std::memcpy(dst, dio, n);
     }
-    {
-        std::lock_guard<std::mutex> lk(mu);
-        consumed = n_pieces + 2;  // lets a reader that is still waiting run to its end
-        cv.notify_all();
-    }
-    reader.join();
-    if (rc) c->err = err_reader;
+    if (t.dst2) std::memcpy(t.dst2 + lo, dst, n);
+    return HA_RAG_OK;
+}
+}  // namespace
+
+int Transfer::wait()
+{
+    std::unique_lock<std::mutex> lk(mu);
+    cv.wait(lk, [&] { return pieces_left == 0; });
     return rc;
 }
+
+class IoPool {
+public:
+    IoPool(uint32_t n, bool direct)
+    {
+        for (uint32_t i = 0; i < n; ++i) {
+            uint8_t *buf = nullptr;
+            if (direct) {
+                void *p = nullptr;
+                if (posix_memalign(&p, kDirectAlign, kPiece) == 0) buf = static_cast<uint8_t *>(p);
+            }
+            bufs_.push_back(buf);
+        }
+        for (uint32_t i = 0; i < n; ++i) threads_.emplace_back([this, i] { run(i); });
+    }
+    ~IoPool()
+    {
+        {
+            std::lock_guard<std::mutex> g(mu_);
+            stop_ = true;
+        }
+        cv_.notify_all();
+        for (std::thread &t : threads_) t.join();
+        for (uint8_t *b : bufs_) std::free(b);
+    }
+    void start(const std::shared_ptr<Transfer> &t)
+    {
+        const size_t n_pieces = t->bytes ? (t->bytes + kPiece - 1) / kPiece : 0;
+        {
+            std::lock_guard<std::mutex> g(t->mu);
+            t->pieces_left = n_pieces;
+        }
+        if (n_pieces == 0) return;
+        {
+            std::lock_guard<std::mutex> g(mu_);
+            for (size_t i = 0; i < n_pieces; ++i)
+                q_.push_back(Piece{t, i * kPiece, std::min(kPiece, t->bytes - i * kPiece)});
+        }
+        cv_.notify_all();
+    }
+
+private:
+    void run(uint32_t me)
+    {
+        for (;;) {
+            Piece pc;
+            {
+                std::unique_lock<std::mutex> lk(mu_);
+                cv_.wait(lk, [&] { return stop_ || !q_.empty(); });
+                if (q_.empty()) return;  // stop_, and nothing left to move
+                pc = q_.front();
+                q_.pop_front();
+            }
+            std::string err;
+            int rc = HA_RAG_OK;
+            if (pc.t->direct && !bufs_[me]) {
+                rc = HA_RAG_EIO;
+                err = "no page-aligned buffer for direct I/O";
+            } else {
+                rc = move_piece(*pc.t, pc.lo, pc.n, bufs_[me], &err);
+            }
+            std::lock_guard<std::mutex> g(pc.t->mu);
+            if (rc && !pc.t->rc) {
+                pc.t->rc = rc;
+                pc.t->err = err;
+            }
+            if (--pc.t->pieces_left == 0) pc.t->cv.notify_all();
+        }
+    }
+    std::mutex mu_;
+    std::condition_variable cv_;
+    std::deque<Piece> q_;
+    bool stop_ = false;
+    std::vector<std::thread> threads_;
+    std::vector<uint8_t *> bufs_;
+};
+
+IoPool *io_pool_create(uint32_t n_threads, bool direct) { return new IoPool(n_threads, direct); }
+void io_pool_destroy(IoPool *p) { delete p; }
+void io_pool_start(IoPool *p, const std::shared_ptr<Transfer> &t) { p->start(t); }
 
 }  // namespace ha_rag_host

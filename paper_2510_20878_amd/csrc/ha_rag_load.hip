@@ -1,10 +1,19 @@
 // The online load behind include/ha_rag.h (Algorithm 2 step 2 + decompression +
 // concatenation): per-chunk lookup and placement, then the stream / event pipeline that
 // overlaps file reads, host copies and host -> HBM copies with the dequantize kernel.
+//
+// Locking.  The context's mutex is held for bookkeeping and for enqueueing GPU work (both
+// never block); it is released while the calling thread waits for an event or for its file /
+// pageable bytes, which the context's I/O threads move in pieces.  So calls of several threads
+// overlap their file reads with each other and with GPU work.  What a call has booked but not
+// yet written is marked pending (other calls pass it over), what it reads on the host is
+// counted in the slot (it is not evicted meanwhile), and chunk entries it holds by index are
+// not removed meanwhile.
 #include "ha_rag_internal.h"
 
 #include <algorithm>
 #include <cstring>
+#include <memory>
 
 using namespace ha_rag_host;
 
@@ -128,18 +137,36 @@ void init_batch(const ha_rag_ctx *c, Batch &b, const ha_rag_paged_cache *pg = nu
     }
 }
 
-// Packed bytes of a chunk from its pageable or disk copy into a bounce buffer (host work,
-// synchronous).
-int fill_bounce(ha_rag_ctx *c, const Chunk &ch, uint32_t tier, int32_t slot, uint8_t *dst)
+// The host-side move of a chunk from its pageable or file copy into bounce buffer `bounce`,
+// and on into the host slot a copy was placed in (dst2, nullable).  Called with the lock held:
+// captures the addresses (the source slot's reader was counted when the action was decided).
+std::shared_ptr<Transfer> make_transfer(ha_rag_ctx *c, const Chunk &ch, uint32_t tier, int32_t slot,
+                                        uint8_t *bounce, uint8_t *dst2)
 {
-    if (c->no_io()) return HA_RAG_OK;
-    const Slab &sl = c->slab[tier][ch.prec];
+    auto t = std::make_shared<Transfer>();
+    Slab &sl = c->slab[tier][ch.prec];
     if (tier == HA_RAG_TIER_PAGEABLE) {
-        std::memcpy(dst, sl.ptr(slot), ch.bytes);
-        return HA_RAG_OK;
+        t->src = sl.ptr(slot);
+    } else {
+        t->fd = sl.fd;
+        t->direct = c->direct();
+        t->off = sl.offset(slot);
     }
-    if (!c->direct()) return read_full(c, sl.fd, dst, ch.bytes, sl.offset(slot));
-    return read_direct(c, sl.fd, dst, ch.bytes, sl.offset(slot));
+    t->dst = bounce;
+    t->dst2 = dst2;
+    t->bytes = c->no_io() ? 0 : (size_t)ch.bytes;
+    return t;
+}
+
+void done_reading(ha_rag_ctx *c, const Chunk &ch, uint32_t tier, int32_t slot)
+{
+    if (tier < kCacheTiers) --c->slab[tier][ch.prec].use[(size_t)slot].host_readers;
+}
+
+IoPool *io_pool(ha_rag_ctx *c)
+{
+    if (!c->io) c->io = io_pool_create(c->cfg.io_threads ? c->cfg.io_threads : 4u, c->direct());
+    return c->io;
 }
 
 // Algorithm 2 step 2 for one chunk of a call: counts the access, touches the LRU order of the
@@ -153,7 +180,7 @@ void alg2_step(ha_rag_ctx *c, uint32_t ci, uint32_t r, uint64_t off, uint64_t ca
     const uint64_t D = c->cfg.head_dim;
     Chunk &ch = c->chunks[ci];
     ch.count += 1;
-    const uint32_t found = (uint32_t)ch.fastest();
+    const uint32_t found = (uint32_t)ch.fastest(call);
     a = Action{ci, r, off, Action::COLD, (uint8_t)found, ch.slot[found], HA_RAG_TIER_NONE, -1};
     std::memset(&tr, 0, sizeof tr);
     tr.tok_off = off;
@@ -182,12 +209,14 @@ void alg2_step(ha_rag_ctx *c, uint32_t ci, uint32_t r, uint64_t off, uint64_t ca
         // only a tier faster than the one it was found in gets one
         uint32_t want = ch.rank == kNoRank ? HA_RAG_TIER_DISK : c->list_of(ch.rank);
         if (want > floor_tier) want = floor_tier;  // HA_RAG_TIER_DISK = no floor
-        if (want < found && c->slab[want][ch.prec].holds_copies()) {
+        // a copy there that another running call is still writing: nothing to add
+        if (want < found && c->slab[want][ch.prec].holds_copies() && ch.slot[want] < 0) {
             uint64_t ev;
             const int32_t slot = tier_acquire(c, want, ch.prec, &ev, call);
             if (slot >= 0) {
                 tier_attach(c, want, ci, slot);
                 ch.made_by[want] = call;
+                ch.pending[want] = 1;  // until its bytes are in place (published by the call)
                 a.place_tier = (uint8_t)want;
                 a.place_slot = slot;
                 tr.placed_tier = (uint8_t)want;
@@ -218,8 +247,153 @@ void alg2_step(ha_rag_ctx *c, uint32_t ci, uint32_t r, uint64_t off, uint64_t ca
         (uint64_t)ch.n_tokens * (ch.part == kPartKV ? c->n_tiles : c->n_tiles / 2) * D * 2ull;
 }
 
-int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Request *reqs,
-              uint32_t n_req, uint32_t n, hipStream_t s, ha_rag_load_stats *stats,
+// What a call keeps about the chunks it works on, and how it lets go of them: entries it holds
+// by index, host-side readers it counted, bounce buffers it reserved, copies it booked.  The
+// destructor runs with the lock held; copies booked but never written leave the books again.
+struct CallState {
+    ha_rag_ctx *c;
+    std::vector<Action> acts;
+    std::vector<uint8_t> written;      // per action: its placed copy has been written / enqueued
+    std::vector<uint8_t> reading;      // per action: counted as a host reader of its source slot
+    std::vector<size_t> held_bounce;   // reserved by this call, not yet handed back
+    std::vector<std::shared_ptr<Transfer>> moving;  // started on the I/O threads, not yet waited for
+    explicit CallState(ha_rag_ctx *ctx) : c(ctx) {}
+    void add(const Action &a)
+    {
+        acts.push_back(a);
+        written.push_back(0);
+        reading.push_back(0);
+        Chunk &ch = c->chunks[a.ci];
+        ++ch.in_calls;
+        // A copy in pageable memory that the call will read on the host with the context
+        // unlocked, and a copy that an earlier chunk of this call places and this one reads
+        // afterwards: from now on nobody evicts them, neither another call nor a later chunk of
+        // this one (which takes the next victim in LRU order instead).
+        const bool host_read = a.kind == Action::COLD && a.src_tier == HA_RAG_TIER_PAGEABLE;
+        if (host_read || a.kind == Action::HOT_LATE) {
+            ++c->slab[a.src_tier][ch.prec].use[(size_t)a.src_slot].host_readers;
+            reading.back() = 1;
+        }
+    }
+    void publish(size_t k)  // the placed copy of action k holds its bytes (or its copy is enqueued)
+    {
+        const Action &a = acts[k];
+        if (a.place_tier == HA_RAG_TIER_NONE || written[k]) return;
+        written[k] = 1;
+        Chunk &ch = c->chunks[a.ci];
+        if (ch.slot[a.place_tier] == a.place_slot) ch.pending[a.place_tier] = 0;
+    }
+    void stop_reading(size_t k)
+    {
+        if (!reading[k]) return;
+        reading[k] = 0;
+        done_reading(c, c->chunks[acts[k].ci], acts[k].src_tier, acts[k].src_slot);
+    }
+    void drop_bounce(size_t b, bool copy_in_flight)
+    {
+        for (size_t i = 0; i < held_bounce.size(); ++i)
+            if (held_bounce[i] == b) {
+                held_bounce.erase(held_bounce.begin() + (long)i);
+                break;
+            }
+        release_bounce(c, b, copy_in_flight);
+    }
+    ~CallState()
+    {
+        // a call that ends early: the I/O threads must be done with its buffers before they are
+        // handed on (the transfers touch no context state, so waiting with the lock held is safe)
+        for (const std::shared_ptr<Transfer> &t : moving) (void)t->wait();
+        for (size_t k = 0; k < acts.size(); ++k) {
+            const Action &a = acts[k];
+            stop_reading(k);
+            Chunk &ch = c->chunks[a.ci];
+            if (a.place_tier != HA_RAG_TIER_NONE && !written[k] && ch.slot[a.place_tier] == a.place_slot) {
+                ch.pending[a.place_tier] = 0;
+                tier_detach(c, a.place_tier, a.ci);
+            }
+            --ch.in_calls;
+        }
+        for (size_t b : held_bounce) release_bounce(c, b, false);
+        c->cv.notify_all();
+    }
+};
+
+// A host move that must wait for its turn: it also fills a pinned / pageable slot (an earlier
+// chunk of the call may still have to enqueue its read of the copy that slot held before: pass
+// A has booked everything already), or it reads a copy that an earlier chunk of the call is
+// still writing.
+bool not_ahead(const ha_rag_ctx *c, const Action &a)
+{
+    if (a.place_tier == HA_RAG_TIER_PINNED || a.place_tier == HA_RAG_TIER_PAGEABLE) return true;
+    return a.src_tier < kCacheTiers && c->chunks[a.ci].pending[a.src_tier] != 0;
+}
+
+// A chunk's bytes being moved into a bounce buffer by the I/O threads.
+struct HostMove {
+    size_t bounce = 0;
+    std::shared_ptr<Transfer> t;
+    bool started = false;
+};
+
+// Starts the host-side move of action k (source in pageable memory or a file).  Lock held on
+// entry and on return; released while the calling thread waits for device work that still reads
+// the buffers it is about to overwrite.  block: wait for a bounce buffer if other calls hold them
+// all (otherwise *started stays false).
+int start_host_move(ha_rag_ctx *c, std::unique_lock<std::mutex> &lk, CallState &cs, size_t k, bool block,
+                    HostMove *hm)
+{
+    hipEvent_t bounce_ev = nullptr;
+    if (!reserve_bounce(c, lk, block, &hm->bounce, &bounce_ev)) return HA_RAG_OK;
+    cs.held_bounce.push_back(hm->bounce);
+    const Action a = cs.acts[k];
+    const Chunk &ch = c->chunks[a.ci];
+    uint8_t *bp = c->bounce + hm->bounce * c->bounce_slot_bytes;
+    uint8_t *dst2 = nullptr;
+    std::vector<hipEvent_t> waits;
+    if (bounce_ev) waits.push_back(bounce_ev);
+    if (a.place_tier == HA_RAG_TIER_PINNED || a.place_tier == HA_RAG_TIER_PAGEABLE) {
+        Slab &ds = c->slab[a.place_tier][ch.prec];
+        take_host_write_events(c, ds.use[(size_t)a.place_slot], &waits);
+        dst2 = ds.ptr(a.place_slot);
+    }
+    hm->t = make_transfer(c, ch, a.src_tier, a.src_slot, bp, dst2);
+    IoPool *pool = io_pool(c);
+    lk.unlock();
+    hipError_t e = hipSuccess;
+    if (!c->dry())
+        for (hipEvent_t ev : waits)
+            if (e == hipSuccess) e = hipEventSynchronize(ev);
+    if (e == hipSuccess) io_pool_start(pool, hm->t);
+    lk.lock();
+    if (e != hipSuccess) {
+        c->err = std::string("hipEventSynchronize: ") + hipGetErrorString(e);
+        return HA_RAG_EHIP;
+    }
+    cs.moving.push_back(hm->t);
+    hm->started = true;
+    return HA_RAG_OK;
+}
+
+// Waits (lock released) until the bytes of action k are in its bounce buffer and in the host
+// slot a copy was placed in; then that copy is published and the source slot let go of.
+int finish_host_move(ha_rag_ctx *c, std::unique_lock<std::mutex> &lk, CallState &cs, size_t k, HostMove &hm)
+{
+    lk.unlock();
+    const int rc = hm.t->wait();
+    lk.lock();
+    cs.moving.erase(std::find(cs.moving.begin(), cs.moving.end(), hm.t));
+    cs.stop_reading(k);
+    if (rc) {
+        c->err = hm.t->err;
+        return rc;
+    }
+    const Action &a = cs.acts[k];
+    if (a.place_tier == HA_RAG_TIER_PINNED || a.place_tier == HA_RAG_TIER_PAGEABLE) cs.publish(k);
+    return HA_RAG_OK;
+}
+
+int load_impl(ha_rag_ctx *c, std::unique_lock<std::mutex> &lk, const uint64_t *ids, const uint8_t *tags,
+              const Request *reqs, uint32_t n_req, uint32_t n, hipStream_t s, ha_rag_load_stats *stats,
               ha_rag_chunk_trace *trace)
 {
     // ---- checks: nothing changes before all of them pass --------------------
@@ -263,8 +437,8 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     st.n_chunks = n;
 
     // ---- pass A: Algorithm 2 step 2, chunk by chunk, in request order ---------
-    std::vector<Action> acts;
-    acts.reserve(n);
+    CallState cs(c);
+    cs.acts.reserve(n);
     // copies created by this call carry its number: they are not evicted again by this call
     const uint64_t call = ++c->call_seq;
     for (uint32_t r = 0; r < n_req; ++r) {
@@ -277,91 +451,26 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
             Action a;
             ha_rag_chunk_trace tr;
             alg2_step(c, ci, r, off, call, HA_RAG_TIER_DISK, a, tr, st);
-            acts.push_back(a);
+            cs.add(a);
             if (trace) trace[i] = tr;
         }
     }
+    const std::vector<Action> &acts = cs.acts;
 
     // ---- pass B: enqueue ---------------------------------------------------------
     // 1. one kernel over every chunk that is read where it lies: copies already resident in
     //    HBM, and pinned copies when the kernel reads pinned memory itself
-    // 2. transfers of the first cold chunks (as many as there are staging slots)
-    // 3. per cold chunk: wait for its transfer, kernel, copy into the HBM slab if it was
-    //    placed there, release the staging slot, start the transfer that reuses it
-    // 4. one kernel over chunks whose copy was written in step 2 or 3
-    // A transfer is a host -> HBM copy from the pinned slot, or, for pageable and disk
-    // chunks, a host copy / file read into a pinned bounce buffer (synchronous, on this
-    // thread; also the moment a pinned / pageable copy is written) followed by that copy.
+    // 2. per cold chunk, in order: its bytes reach a staging slot (pinned source: one host ->
+    //    HBM copy on a copy stream; pageable / file source: the I/O threads first move them
+    //    into a bounce buffer, and into the pinned / pageable slot a copy was placed in, while
+    //    this thread waits with the context unlocked), `stream` waits for that copy, kernel,
+    //    copy into the HBM slab if the chunk was placed there, staging slot released.  The
+    //    host moves of the next chunks are started ahead, as far as bounce buffers are free.
+    // 3. one kernel over chunks whose copy was written in step 2
     std::vector<uint32_t> cold;
     for (uint32_t k = 0; k < acts.size(); ++k)
         if (acts[k].kind == Action::COLD) cold.push_back(k);
     const size_t n_stg = c->stg.size();
-    std::vector<size_t> cold_slot(cold.size());
-
-    // If a HIP or file call fails midway, copies that pass A booked but that were never
-    // written must not stay in the books.
-    struct Undo {
-        ha_rag_ctx *c;
-        std::vector<Action> &acts;
-        std::vector<uint8_t> written;  // per action: its placed copy has been written / enqueued
-        bool ok = false;
-        ~Undo()
-        {
-            if (ok) return;
-            for (size_t k = 0; k < acts.size(); ++k) {
-                const Action &a = acts[k];
-                if (a.place_tier == HA_RAG_TIER_NONE || written[k]) continue;
-                if (c->chunks[a.ci].slot[a.place_tier] == a.place_slot) tier_detach(c, a.place_tier, a.ci);
-            }
-        }
-    } undo{c, acts, std::vector<uint8_t>(acts.size(), 0)};
-
-    auto start_transfer = [&](size_t k) -> int {
-        const Action &a = acts[cold[k]];
-        const Chunk &ch = c->chunks[a.ci];
-        const size_t sidx = (size_t)(c->stg_next++ % n_stg);
-        cold_slot[k] = sidx;
-        const uint8_t *src = nullptr;
-        size_t bidx = 0;
-        if (a.src_tier == HA_RAG_TIER_PINNED) {
-            src = c->slab[HA_RAG_TIER_PINNED][ch.prec].ptr(a.src_slot);
-        } else {
-            int rc = acquire_bounce(c, &bidx);
-            if (rc) return rc;
-            uint8_t *bp = c->bounce + bidx * c->bounce_slot_bytes;
-            rc = fill_bounce(c, ch, a.src_tier, a.src_slot, bp);
-            if (rc) return rc;
-            if (a.place_tier == HA_RAG_TIER_PINNED || a.place_tier == HA_RAG_TIER_PAGEABLE) {
-                Slab &ds = c->slab[a.place_tier][ch.prec];
-                rc = before_host_write(c, ds.use[a.place_slot]);
-                if (rc) return rc;
-                if (!c->no_io()) std::memcpy(ds.ptr(a.place_slot), bp, ch.bytes);
-                undo.written[cold[k]] = 1;
-            }
-            src = bp;
-        }
-        if (c->dry()) return HA_RAG_OK;
-        StagingSlot &ss = c->stg[sidx];
-        hipStream_t cs = c->copy_streams[c->copy_rr++ % c->copy_streams.size()];
-        if (ss.consumed_valid) HIPCHK(c, hipStreamWaitEvent(cs, ss.consumed, 0));
-        if (a.src_tier == HA_RAG_TIER_PINNED) {
-            SlotUse &u = c->slab[HA_RAG_TIER_PINNED][ch.prec].use[a.src_slot];
-            if (u.has_writer) {  // a device -> host copy may still be filling the slot
-                int rc = wait_for(c, cs, u.writer);
-                if (rc) return rc;
-            }
-            if (std::find(u.read_events.begin(), u.read_events.end(), ss.filled) == u.read_events.end())
-                u.read_events.push_back(ss.filled);  // at most one per staging slot
-        }
-        HIPCHK(c, hipMemcpyAsync(c->staging + sidx * c->staging_slot_bytes, src, ch.bytes,
-                                 hipMemcpyHostToDevice, cs));
-        HIPCHK(c, hipEventRecord(ss.filled, cs));
-        if (a.src_tier != HA_RAG_TIER_PINNED) {
-            HIPCHK(c, hipEventRecord(c->bnc[bidx].h2d_done, cs));
-            c->bnc[bidx].busy = true;
-        }
-        return HA_RAG_OK;
-    };
 
     // Chunks read where they lie (HBM copies, and pinned copies unless pinned_dma is set) go
     // first: their slots may be handed to other chunks by the transfers below.
@@ -388,18 +497,54 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
         if (rc) return rc;
     }
 
-    size_t started = 0;
-    for (; started < cold.size() && started < n_stg; ++started) {
-        rc = start_transfer(started);
-        if (rc) return rc;
-    }
+    std::vector<HostMove> moves(cold.size());
+    size_t ahead = 0;  // cold chunks up to here have had their host move started (if they need one)
+    auto needs_move = [&](size_t k) { return acts[cold[k]].src_tier >= HA_RAG_TIER_PAGEABLE; };
 
     for (size_t k = 0; k < cold.size(); ++k) {
+        // host side: this chunk's move must run; later ones are started while buffers are free
+        while (ahead < cold.size()) {
+            if (!needs_move(ahead)) {
+                ++ahead;
+                continue;
+            }
+            const bool must = ahead <= k;
+            if (!must && not_ahead(c, acts[cold[ahead]])) break;
+            rc = start_host_move(c, lk, cs, cold[ahead], must, &moves[ahead]);
+            if (rc) return rc;
+            if (!moves[ahead].started) break;  // no free bounce buffer: later
+            ++ahead;
+        }
+        if (needs_move(k)) {
+            rc = finish_host_move(c, lk, cs, cold[k], moves[k]);
+            if (rc) return rc;
+        }
+        // device side, enqueued in one go with the lock held
         const Action &a = acts[cold[k]];
         const Chunk &ch = c->chunks[a.ci];
-        const size_t sidx = cold_slot[k];
+        const size_t sidx = (size_t)(c->stg_next++ % n_stg);
         uint8_t *sp = c->staging + sidx * c->staging_slot_bytes;
-        if (!c->dry()) HIPCHK(c, hipStreamWaitEvent(s, c->stg[sidx].filled, 0));
+        const uint8_t *src = needs_move(k) ? c->bounce + moves[k].bounce * c->bounce_slot_bytes
+                                           : c->slab[HA_RAG_TIER_PINNED][ch.prec].ptr(a.src_slot);
+        if (!c->dry()) {
+            StagingSlot &ss = c->stg[sidx];
+            hipStream_t cps = c->copy_streams[c->copy_rr++ % c->copy_streams.size()];
+            if (ss.consumed_valid) HIPCHK(c, hipStreamWaitEvent(cps, ss.consumed, 0));
+            if (a.src_tier == HA_RAG_TIER_PINNED) {
+                SlotUse &u = c->slab[HA_RAG_TIER_PINNED][ch.prec].use[a.src_slot];
+                if (u.has_writer) {  // a device -> host copy may still be filling the slot
+                    rc = wait_for(c, cps, u.writer);
+                    if (rc) return rc;
+                }
+                if (std::find(u.read_events.begin(), u.read_events.end(), ss.filled) == u.read_events.end())
+                    u.read_events.push_back(ss.filled);  // at most one per staging slot
+            }
+            HIPCHK(c, hipMemcpyAsync(sp, src, ch.bytes, hipMemcpyHostToDevice, cps));
+            HIPCHK(c, hipEventRecord(ss.filled, cps));
+            if (needs_move(k)) HIPCHK(c, hipEventRecord(c->bnc[moves[k].bounce].h2d_done, cps));
+            HIPCHK(c, hipStreamWaitEvent(s, ss.filled, 0));
+        }
+        if (needs_move(k)) cs.drop_bounce(moves[k].bounce, !c->dry());
         rc = push(c, batch, make_desc(c, ch, sp, reqs[a.req], a.tok_off), s, &st.n_kernel_launches);
         if (rc) return rc;
         rc = flush(c, batch, s, &st.n_kernel_launches);
@@ -409,21 +554,20 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
             rc = before_write(c, hs.use[a.place_slot], s);
             if (rc) return rc;
             if (!c->dry())
-                HIPCHK(c, hipMemcpyAsync(hs.ptr(a.place_slot), sp, ch.bytes,
-                                         hipMemcpyDeviceToDevice, s));
-            undo.written[cold[k]] = 1;
+                HIPCHK(c, hipMemcpyAsync(hs.ptr(a.place_slot), sp, ch.bytes, hipMemcpyDeviceToDevice, s));
+            // readers on other streams wait for this stream's event, which must cover the copy
+            rc = mark_stream(c, s);
+            if (rc) return rc;
+            cs.publish(cold[k]);
         }
         if (!c->dry()) {
             HIPCHK(c, hipEventRecord(c->stg[sidx].consumed, s));
             c->stg[sidx].consumed_valid = true;
         }
-        if (started < cold.size()) {
-            rc = start_transfer(started++);
-            if (rc) return rc;
-        }
     }
 
-    for (const Action &a : acts) {
+    for (size_t k = 0; k < acts.size(); ++k) {
+        const Action &a = acts[k];
         if (a.kind != Action::HOT_LATE) continue;
         const Chunk &ch = c->chunks[a.ci];
         // `made_by` in pass A guarantees the copy written by this call is still in its slot
@@ -441,7 +585,6 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
     if (rc) return rc;
     rc = mark_stream(c, s);
     if (rc) return rc;
-    undo.ok = true;
     if (stats) *stats = st;
     return HA_RAG_OK;
 }
@@ -451,8 +594,9 @@ int load_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, const Req
 // copy it books are moved, but no cache is written.  A copy booked in HBM is filled by one
 // host -> device copy straight into its slot (from the pinned copy, or from a bounce buffer that
 // a pageable copy or a file was read into), so no staging slot is involved.
-int place_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, uint32_t n, uint32_t floor_tier,
-               hipStream_t s, ha_rag_load_stats *stats, ha_rag_chunk_trace *trace)
+int place_impl(ha_rag_ctx *c, std::unique_lock<std::mutex> &lk, const uint64_t *ids, const uint8_t *tags,
+               uint32_t n, uint32_t floor_tier, hipStream_t s, ha_rag_load_stats *stats,
+               ha_rag_chunk_trace *trace)
 {
     std::vector<uint32_t> cis(n);
     for (uint32_t i = 0; i < n; ++i) {
@@ -471,66 +615,61 @@ int place_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, uint32_t
 
     ha_rag_load_stats st;
     std::memset(&st, 0, sizeof st);
-    std::vector<Action> acts(n);
+    CallState cs(c);
     const uint64_t call = ++c->call_seq;
     for (uint32_t i = 0; i < n; ++i) {
         ha_rag_chunk_trace tr;
-        alg2_step(c, cis[i], 0, 0, call, floor_tier, acts[i], tr, st);
+        Action a;
+        alg2_step(c, cis[i], 0, 0, call, floor_tier, a, tr, st);
+        cs.add(a);
         if (trace) trace[i] = tr;
     }
+    const std::vector<Action> &acts = cs.acts;
     // the byte counters of a load do not apply: count what this call moves
     st.n_chunks = n;
     st.tokens = 0;
     st.bytes_h2d = st.bytes_d2d = st.packed_bytes_read = st.bf16_bytes_written = 0;
     st.bytes_disk_read = st.bytes_host_copied = 0;
 
-    struct Undo {  // copies booked above but never written must not stay in the books
-        ha_rag_ctx *c;
-        std::vector<Action> &acts;
-        std::vector<uint8_t> written;
-        bool ok = false;
-        ~Undo()
-        {
-            if (ok) return;
-            for (size_t k = 0; k < acts.size(); ++k) {
-                const Action &a = acts[k];
-                if (a.place_tier == HA_RAG_TIER_NONE || written[k]) continue;
-                if (c->chunks[a.ci].slot[a.place_tier] == a.place_slot) tier_detach(c, a.place_tier, a.ci);
-            }
-        }
-    } undo{c, acts, std::vector<uint8_t>(acts.size(), 0)};
+    std::vector<uint32_t> todo;  // actions that place a copy
+    for (uint32_t k = 0; k < n; ++k)
+        if (acts[k].place_tier != HA_RAG_TIER_NONE) todo.push_back(k);
+    std::vector<HostMove> moves(todo.size());
+    size_t ahead = 0;
+    auto needs_move = [&](size_t k) { return acts[todo[k]].src_tier >= HA_RAG_TIER_PAGEABLE; };
 
-    for (uint32_t k = 0; k < n; ++k) {
-        const Action &a = acts[k];
-        if (a.place_tier == HA_RAG_TIER_NONE) continue;
+    for (size_t k = 0; k < todo.size(); ++k) {
+        int rc;
+        while (ahead < todo.size()) {
+            if (!needs_move(ahead)) {
+                ++ahead;
+                continue;
+            }
+            const bool must = ahead <= k;
+            if (!must && not_ahead(c, acts[todo[ahead]])) break;
+            rc = start_host_move(c, lk, cs, todo[ahead], must, &moves[ahead]);
+            if (rc) return rc;
+            if (!moves[ahead].started) break;
+            ++ahead;
+        }
+        const Action &a = acts[todo[k]];
+        if (needs_move(k)) {
+            rc = finish_host_move(c, lk, cs, todo[k], moves[k]);
+            if (rc) return rc;
+        }
         const Chunk &ch = c->chunks[a.ci];
         const uint8_t *src = nullptr;
-        size_t bidx = 0;
-        bool bounced = false;
-        if (a.src_tier == HA_RAG_TIER_PINNED) {
-            src = c->slab[HA_RAG_TIER_PINNED][ch.prec].ptr(a.src_slot);
-        } else {
-            int rc = acquire_bounce(c, &bidx);
-            if (rc) return rc;
-            uint8_t *bp = c->bounce + bidx * c->bounce_slot_bytes;
-            rc = fill_bounce(c, ch, a.src_tier, a.src_slot, bp);
-            if (rc) return rc;
+        if (needs_move(k)) {
             if (a.src_tier == HA_RAG_TIER_PAGEABLE) st.bytes_host_copied += ch.bytes;
             else st.bytes_disk_read += ch.bytes;
-            bounced = true;
-            src = bp;
-            if (a.place_tier != HA_RAG_TIER_HBM) {
-                Slab &ds = c->slab[a.place_tier][ch.prec];
-                rc = before_host_write(c, ds.use[a.place_slot]);
-                if (rc) return rc;
-                if (!c->no_io()) std::memcpy(ds.ptr(a.place_slot), bp, ch.bytes);
-                st.bytes_host_copied += ch.bytes;
-                undo.written[k] = 1;
-            }
+            if (a.place_tier != HA_RAG_TIER_HBM) st.bytes_host_copied += ch.bytes;
+            src = c->bounce + moves[k].bounce * c->bounce_slot_bytes;
+        } else {
+            src = c->slab[HA_RAG_TIER_PINNED][ch.prec].ptr(a.src_slot);
         }
         if (a.place_tier == HA_RAG_TIER_HBM) {
             Slab &hs = c->slab[HA_RAG_TIER_HBM][ch.prec];
-            int rc = before_write(c, hs.use[a.place_slot], s);
+            rc = before_write(c, hs.use[a.place_slot], s);
             if (rc) return rc;
             if (a.src_tier == HA_RAG_TIER_PINNED) {
                 SlotUse &pu = c->slab[HA_RAG_TIER_PINNED][ch.prec].use[a.src_slot];
@@ -542,26 +681,21 @@ int place_impl(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, uint32_t
             }
             if (!c->dry()) {
                 HIPCHK(c, hipMemcpyAsync(hs.ptr(a.place_slot), src, ch.bytes, hipMemcpyHostToDevice, s));
-                if (bounced) {
-                    HIPCHK(c, hipEventRecord(c->bnc[bidx].h2d_done, s));
-                    c->bnc[bidx].busy = true;
-                }
+                if (needs_move(k)) HIPCHK(c, hipEventRecord(c->bnc[moves[k].bounce].h2d_done, s));
             }
-            if (a.src_tier == HA_RAG_TIER_PINNED) {
-                // A later chunk of this call may have been given this pinned slot (pass A has
-                // already booked everything): the host write into it waits on the stream's
-                // event, which must therefore be recorded after this copy, not at the end of
-                // the call.
-                rc = mark_stream(c, s);
-                if (rc) return rc;
-            }
+            // Readers of the new copy on other streams, and the host before it overwrites the
+            // pinned source (a later chunk of this call may have been given that slot: pass A
+            // has already booked everything), wait on the stream's event, which must therefore
+            // be recorded after this copy, not at the end of the call.
+            rc = mark_stream(c, s);
+            if (rc) return rc;
             st.bytes_h2d += ch.bytes;
-            undo.written[k] = 1;
+            cs.publish(todo[k]);
         }
+        if (needs_move(k)) cs.drop_bounce(moves[k].bounce, a.place_tier == HA_RAG_TIER_HBM && !c->dry());
     }
     int rc = mark_stream(c, s);
     if (rc) return rc;
-    undo.ok = true;
     if (stats) *stats = st;
     return HA_RAG_OK;
 }
@@ -640,9 +774,9 @@ int ha_rag_load_chunks(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, 
 {
     if (!c || (n && !ids) || n > HA_RAG_MAX_REQUEST_CHUNKS) return HA_RAG_EINVAL;
     if (cap_tokens * (uint64_t)c->cfg.head_dim > 0x7FFFFFFFFFFFull) return HA_RAG_EINVAL;
-    std::lock_guard<std::mutex> g(c->mu);
+    std::unique_lock<std::mutex> g(c->mu);
     Request rq{0, n, static_cast<uint8_t *>(out), cap_tokens, tok_base, nullptr};
-    return load_impl(c, ids, tags, &rq, 1, n, (hipStream_t)stream, stats, trace);
+    return load_impl(c, g, ids, tags, &rq, 1, n, (hipStream_t)stream, stats, trace);
 }
 
 int ha_rag_load_chunks_paged(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, uint32_t n,
@@ -653,9 +787,9 @@ int ha_rag_load_chunks_paged(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *
     uint64_t cap = 0;
     int rc = check_paged(c, cache, &cap);
     if (rc) return rc;
-    std::lock_guard<std::mutex> g(c->mu);
+    std::unique_lock<std::mutex> g(c->mu);
     Request rq{0, n, nullptr, cap, tok_base, cache};
-    return load_impl(c, ids, tags, &rq, 1, n, (hipStream_t)stream, stats, trace);
+    return load_impl(c, g, ids, tags, &rq, 1, n, (hipStream_t)stream, stats, trace);
 }
 
 int ha_rag_load_batch(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags,
@@ -673,8 +807,8 @@ int ha_rag_load_batch(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags,
         reqs[r] = Request{request_starts[r], request_starts[r + 1], static_cast<uint8_t *>(outs[r]),
                           cap_tokens[r], tok_base ? tok_base[r] : 0, nullptr};
     }
-    std::lock_guard<std::mutex> g(c->mu);
-    return load_impl(c, ids, tags, reqs.data(), n_requests, n, (hipStream_t)stream, stats, trace);
+    std::unique_lock<std::mutex> g(c->mu);
+    return load_impl(c, g, ids, tags, reqs.data(), n_requests, n, (hipStream_t)stream, stats, trace);
 }
 
 int ha_rag_place_chunks(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags, uint32_t n,
@@ -683,8 +817,8 @@ int ha_rag_place_chunks(ha_rag_ctx *c, const uint64_t *ids, const uint8_t *tags,
 {
     if (!c || (n && !ids) || n > HA_RAG_MAX_REQUEST_CHUNKS || (flags & ~(uint32_t)HA_RAG_PLACE_DEVICE_VISIBLE))
         return HA_RAG_EINVAL;
-    std::lock_guard<std::mutex> g(c->mu);
-    return place_impl(c, ids, tags, n,
+    std::unique_lock<std::mutex> g(c->mu);
+    return place_impl(c, g, ids, tags, n,
                       (flags & HA_RAG_PLACE_DEVICE_VISIBLE) ? HA_RAG_TIER_PINNED : HA_RAG_TIER_DISK,
                       (hipStream_t)stream, stats, trace);
 }

@@ -165,8 +165,11 @@ int32_t tier_acquire(ha_rag_ctx *c, uint32_t tier, uint32_t prec, uint64_t *evic
     if (!sl.registered()) return -1;
     if (sl.free_slots.empty() && tier < kCacheTiers) {
         for (uint32_t ci : sl.lru) {
-            if (keep_call && c->chunks[ci].made_by[tier] == keep_call) continue;
-            if (c->chunks[ci].has_slower_copy(tier)) {
+            const Chunk &v = c->chunks[ci];
+            if (keep_call && v.made_by[tier] == keep_call) continue;
+            // a copy that a running call is still writing, or reading on the host, stays
+            if (v.pending[tier] || sl.use[(size_t)v.slot[tier]].host_readers) continue;
+            if (v.has_slower_copy(tier)) {
                 *evicted = c->chunks[ci].id;
                 tier_detach(c, tier, ci);
                 break;
@@ -217,16 +220,48 @@ void rerank_locked(ha_rag_ctx *c)
     }
 }
 
-// Next bounce buffer, once the host -> device copy that last read it has finished.
-int acquire_bounce(ha_rag_ctx *c, size_t *idx)
+bool reserve_bounce(ha_rag_ctx *c, std::unique_lock<std::mutex> &lk, bool block, size_t *idx,
+                    hipEvent_t *wait_ev)
 {
-    const size_t b = (size_t)(c->bnc_next++ % c->bnc.size());
-    if (!c->dry() && c->bnc[b].busy) {
-        HIPCHK(c, hipEventSynchronize(c->bnc[b].h2d_done));
-        c->bnc[b].busy = false;
+    for (;;) {
+        for (size_t k = 0; k < c->bnc.size(); ++k) {
+            const size_t b = (size_t)(c->bnc_next++ % c->bnc.size());
+            BounceSlot &bs = c->bnc[b];
+            if (bs.reserved) continue;
+            bs.reserved = true;
+            *wait_ev = bs.busy ? bs.h2d_done : nullptr;
+            bs.busy = false;
+            *idx = b;
+            return true;
+        }
+        if (!block) return false;
+        c->cv.wait(lk);  // a running call hands one back when its copy is enqueued
     }
-    *idx = b;
-    return HA_RAG_OK;
+}
+
+void release_bounce(ha_rag_ctx *c, size_t idx, bool copy_in_flight)
+{
+    c->bnc[idx].reserved = false;
+    c->bnc[idx].busy = copy_in_flight;
+    c->cv.notify_all();
+}
+
+void take_host_write_events(ha_rag_ctx *c, SlotUse &u, std::vector<hipEvent_t> *out)
+{
+    if (!c->dry()) {
+        for (hipEvent_t ev : u.read_events) out->push_back(ev);
+        if (u.has_writer) {
+            auto it = c->stream_done.find(u.writer);
+            if (it != c->stream_done.end()) out->push_back(it->second);
+        }
+        for (hipStream_t r : u.readers) {
+            auto it = c->stream_done.find(r);
+            if (it != c->stream_done.end()) out->push_back(it->second);
+        }
+    }
+    u.read_events.clear();
+    u.readers.clear();
+    u.has_writer = false;
 }
 
 }  // namespace ha_rag_host
@@ -373,7 +408,7 @@ static int insert_impl(ha_rag_ctx *c, uint64_t id, uint32_t part, uint32_t prec,
     if (n_tokens == 0 || n_tokens > c->cfg.max_chunk_tokens) return HA_RAG_EINVAL;
     if (part == kPartKV && c->cfg.half_slots) return HA_RAG_EFORMAT;  // slots hold halves only
     hipStream_t s = (hipStream_t)stream;
-    std::lock_guard<std::mutex> g(c->mu);
+    std::unique_lock<std::mutex> g(c->mu);
     Slab &sl = c->slab[tier][prec];
     if (!sl.registered()) return HA_RAG_ENOSPC;
     if (sl.external) return HA_RAG_EINVAL;  // its slots are the caller's memory: ha_rag_pool_insert_external
@@ -433,25 +468,35 @@ static int insert_impl(ha_rag_ctx *c, uint64_t id, uint32_t part, uint32_t prec,
     }
     // pageable or disk: the bytes have to be in host memory first
     const uint8_t *host = static_cast<const uint8_t *>(packed);
+    // This is the offline path (the knowledge base is built before it is served): the context
+    // stays locked while the bytes are written.
+    size_t bidx = 0;
     if (via_bounce) {
-        size_t bidx;
-        rc = acquire_bounce(c, &bidx);
-        if (rc) return rc;
+        hipEvent_t ev = nullptr;
+        (void)reserve_bounce(c, g, true, &bidx, &ev);
         uint8_t *bp = c->bounce + bidx * c->bounce_slot_bytes;
-        HIPCHK(c, hipMemcpyAsync(bp, packed, total, hipMemcpyDeviceToHost, s));
-        HIPCHK(c, hipStreamSynchronize(s));
+        hipError_t e = ev ? hipEventSynchronize(ev) : hipSuccess;
+        if (e == hipSuccess) e = hipMemcpyAsync(bp, packed, total, hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) {
+            release_bounce(c, bidx, false);
+            c->err = std::string("device -> bounce buffer copy: ") + hipGetErrorString(e);
+            return HA_RAG_EHIP;
+        }
         host = bp;
     }
     if (tier == HA_RAG_TIER_PAGEABLE) {
         rc = before_host_write(c, sl.use[slot]);
-        if (rc) return rc;
-        std::memcpy(sl.ptr(slot), host, total);
-        return HA_RAG_OK;
+        if (rc == HA_RAG_OK) std::memcpy(sl.ptr(slot), host, total);
+    } else if (!c->direct()) {
+        rc = write_full(c, sl.fd, host, total, sl.offset(slot));
+    } else {
+        std::memcpy(c->dio, host, total);
+        std::memset(c->dio + total, 0, c->io_bytes(total) - total);
+        rc = write_full(c, sl.fd, c->dio, c->io_bytes(total), sl.offset(slot));
     }
-    if (!c->direct()) return write_full(c, sl.fd, host, total, sl.offset(slot));
-    std::memcpy(c->dio, host, total);
-    std::memset(c->dio + total, 0, c->io_bytes(total) - total);
-    return write_full(c, sl.fd, c->dio, c->io_bytes(total), sl.offset(slot));
+    if (via_bounce) release_bounce(c, bidx, false);
+    return rc;
 }
 
 int ha_rag_pool_insert(ha_rag_ctx *c, uint64_t id, uint32_t prec, uint32_t n_tokens,
@@ -580,10 +625,16 @@ int ha_rag_pool_promote(ha_rag_ctx *c, uint64_t id, void *stream)
 int ha_rag_pool_evict(ha_rag_ctx *c, uint64_t id, uint32_t tier)
 {
     if (!c || tier >= kCacheTiers) return HA_RAG_EINVAL;
-    std::lock_guard<std::mutex> g(c->mu);
+    std::unique_lock<std::mutex> g(c->mu);
     uint32_t ci;
     Chunk *ch = find_chunk(c, id, &ci);
     if (!ch || ch->slot[tier] < 0) return HA_RAG_ENOENT;
+    // a running load may be writing this copy or reading it on the host: let it finish
+    while (ch->pending[tier] || c->slab[tier][ch->prec].use[(size_t)ch->slot[tier]].host_readers) {
+        c->cv.wait(g);
+        ch = find_chunk(c, id, &ci);
+        if (!ch || ch->slot[tier] < 0) return HA_RAG_ENOENT;
+    }
     if (!ch->has_slower_copy(tier)) return HA_RAG_EINVAL;
     tier_detach(c, tier, ci);
     return HA_RAG_OK;
@@ -592,10 +643,15 @@ int ha_rag_pool_evict(ha_rag_ctx *c, uint64_t id, uint32_t tier)
 int ha_rag_pool_remove(ha_rag_ctx *c, uint64_t id)
 {
     if (!c) return HA_RAG_EINVAL;
-    std::lock_guard<std::mutex> g(c->mu);
+    std::unique_lock<std::mutex> g(c->mu);
     uint32_t ci;
     Chunk *ch = find_chunk(c, id, &ci);
     if (!ch) return HA_RAG_ENOENT;
+    while (ch->in_calls) {  // a running load holds the entry: let it finish
+        c->cv.wait(g);
+        ch = find_chunk(c, id, &ci);
+        if (!ch) return HA_RAG_ENOENT;
+    }
     for (uint32_t t = 0; t < kTiers; ++t)
         if (ch->slot[t] >= 0) tier_detach(c, t, ci);
     c->index.erase(id);
@@ -785,6 +841,36 @@ int ha_rag_pool_load_index(ha_rag_ctx *c, const char *path, size_t *n_loaded)
             if (!taken[p][i]) sl.free_slots.push_back(i);  // lowest slot on top of the stack
     }
     if (n_loaded) *n_loaded = entries.size();
+    return HA_RAG_OK;
+}
+
+int ha_rag_forget_stream(ha_rag_ctx *c, void *stream)
+{
+    if (!c) return HA_RAG_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    std::unique_lock<std::mutex> g(c->mu);
+    auto it = c->stream_done.find(s);
+    if (it == c->stream_done.end()) return HA_RAG_OK;  // the library never enqueued anything there
+    hipEvent_t ev = it->second;
+    c->stream_done.erase(it);
+    // Slots remember streams by handle, and a handle may come back for a new stream: take the
+    // stream out of every slot's books.  What it enqueued is waited for here instead.
+    for (uint32_t t = 0; t < kCacheTiers; ++t)
+        for (uint32_t p = 0; p < HA_RAG_N_PREC; ++p)
+            for (SlotUse &u : c->slab[t][p].use) {
+                if (u.has_writer && u.writer == s) u.has_writer = false;
+                u.readers.erase(std::remove(u.readers.begin(), u.readers.end(), s), u.readers.end());
+            }
+    g.unlock();
+    if (!c->dry()) {
+        hipError_t e = hipEventSynchronize(ev);
+        (void)hipEventDestroy(ev);
+        if (e != hipSuccess) {
+            std::lock_guard<std::mutex> g2(c->mu);
+            c->err = std::string("hipEventSynchronize: ") + hipGetErrorString(e);
+            return HA_RAG_EHIP;
+        }
+    }
     return HA_RAG_OK;
 }
 

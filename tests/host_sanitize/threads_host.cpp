@@ -1,11 +1,16 @@
-// Several threads call into one dry_run context at once (host bookkeeping only: no HIP call,
-// no byte moved).  Meant to be built with -fsanitize=thread on the host side: the library
-// promises that calls on one context are serialised by its own mutex, so the sanitizer must
-// stay silent, and the pool must be consistent afterwards.
+// Several threads call into one context at once.  Meant to be built with -fsanitize=thread on
+// the host side: the library promises that a context may be used from several threads, so the
+// sanitizer must stay silent, and the pool must be consistent afterwards.
+//   threads_host <ops>          dry_run = 1: host bookkeeping only, no HIP call, no byte moved
+//   threads_host <ops> <dir>    dry_run = 2: no HIP call, but real bytes through pageable memory
+//                               and real pool files in <dir> (also with O_DIRECT), moved by the
+//                               context's I/O threads while the context is unlocked; every copy
+//                               left in pinned or pageable memory must hold its chunk's bytes
 #include <atomic>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <string>
 #include <thread>
 #include <vector>
 
@@ -27,9 +32,126 @@ static uint64_t next(uint64_t &s)
     return s;
 }
 
+static std::vector<uint8_t> random_bytes(size_t n, uint64_t seed)
+{
+    std::vector<uint8_t> v(n);
+    uint64_t s = seed * 0x9E3779B97F4A7C15ull + 1;
+    for (size_t i = 0; i < n; ++i) v[i] = (uint8_t)next(s);
+    return v;
+}
+
+static void *aligned(size_t bytes)
+{
+    void *p = nullptr;
+    REQUIRE(posix_memalign(&p, 4096, bytes) == 0);
+    std::memset(p, 0xEE, bytes);
+    return p;
+}
+
+// Four threads load and place chunks whose masters are in a real file; Algorithm 2 copies them
+// into small pinned and pageable slabs (ordinary memory here), evicting as it goes.
+static void real_tiers(int ops, const std::string &dir, uint32_t direct)
+{
+    ha_rag_config cfg;
+    std::memset(&cfg, 0, sizeof cfg);
+    cfg.n_layers = 4;
+    cfg.n_kv_heads = 4;
+    cfg.head_dim = 128;
+    cfg.max_chunk_tokens = 160;   // up to 5 MiB per 16-bit chunk: more than one piece
+    cfg.group_int8 = 128;
+    cfg.group_int4 = 128;
+    cfg.tau_gpu_ppm = 0;
+    cfg.tau_pin_ppm = 200000;
+    cfg.tau_page_ppm = 300000;
+    cfg.rerank_interval = 7;
+    cfg.disk_o_direct = direct;
+    cfg.io_threads = 3;
+    cfg.dry_run = 2;
+    ha_rag_ctx *ctx = nullptr;
+    REQUIRE(ha_rag_create(&cfg, &ctx) == HA_RAG_OK);
+    const uint32_t n_ids = 24;
+    size_t total = 0;
+    REQUIRE(ha_rag_chunk_bytes(4, 4, 128, HA_RAG_PREC_16, 0, cfg.max_chunk_tokens, nullptr, nullptr, &total) == HA_RAG_OK);
+    const size_t slot = (total + 4095) & ~(size_t)4095;
+    void *pin = aligned(slot * 3), *page = aligned(slot * 4), *bounce = aligned(slot * 3);
+    REQUIRE(ha_rag_register_slab(ctx, HA_RAG_TIER_PINNED, HA_RAG_PREC_16, pin, slot * 3) == HA_RAG_OK);
+    REQUIRE(ha_rag_register_slab(ctx, HA_RAG_TIER_PAGEABLE, HA_RAG_PREC_16, page, slot * 4) == HA_RAG_OK);
+    const std::string path = dir + (direct ? "/threads_d.pool" : "/threads_b.pool");
+    REQUIRE(ha_rag_register_disk(ctx, HA_RAG_PREC_16, path.c_str(), slot * n_ids) == HA_RAG_OK);
+    REQUIRE(ha_rag_register_staging(ctx, (void *)0x300000000000ull, slot * 4) == HA_RAG_OK);
+    REQUIRE(ha_rag_register_bounce(ctx, bounce, slot * 3) == HA_RAG_OK);
+    std::vector<std::vector<uint8_t>> bytes(n_ids);
+    std::vector<uint32_t> tokens(n_ids);
+    for (uint32_t id = 0; id < n_ids; ++id) {
+        tokens[id] = 20 + 6 * id;
+        size_t nb = 0;
+        REQUIRE(ha_rag_chunk_bytes(4, 4, 128, HA_RAG_PREC_16, 0, tokens[id], nullptr, nullptr, &nb) == HA_RAG_OK);
+        bytes[id] = random_bytes(nb, id + 1);
+        REQUIRE(ha_rag_pool_insert(ctx, id, HA_RAG_PREC_16, tokens[id], bytes[id].data(), 0, HA_RAG_TIER_DISK, nullptr) == HA_RAG_OK);
+    }
+    REQUIRE(ha_rag_rerank(ctx) == HA_RAG_OK);
+    std::atomic<uint64_t> chunks{0}, disk_bytes{0};
+    auto worker = [&](int t) {
+        uint64_t s = 0xD1B54A32D192ED03ull * (uint64_t)(t + 1);
+        for (int op = 0; op < ops; ++op) {
+            uint64_t ids[4];
+            const uint32_t n = 1 + (uint32_t)(next(s) % 4);
+            // a skewed choice, so that some chunks are hot enough for the pinned and pageable lists
+            for (uint32_t i = 0; i < n; ++i) ids[i] = (next(s) % 3 ? next(s) % 6 : next(s) % n_ids);
+            ha_rag_load_stats st;
+            const uint64_t what = next(s) % 10;
+            if (what < 5) {
+                REQUIRE(ha_rag_load_chunks(ctx, ids, nullptr, n, (void *)(0x500000000000ull + (uint64_t)t * 0x100000000ull),
+                                           4 * 160, 0, nullptr, &st, nullptr) == HA_RAG_OK);
+            } else if (what < 9) {
+                REQUIRE(ha_rag_place_chunks(ctx, ids, nullptr, n, (uint32_t)(next(s) % 2), nullptr, &st, nullptr) == HA_RAG_OK);
+            } else {
+                int rc = ha_rag_pool_evict(ctx, next(s) % n_ids, 1 + (uint32_t)(next(s) % 2));
+                REQUIRE(rc == HA_RAG_OK || rc == HA_RAG_ENOENT || rc == HA_RAG_EINVAL);
+                continue;
+            }
+            REQUIRE(st.n_chunks == n);
+            chunks.fetch_add(n);
+            disk_bytes.fetch_add(st.bytes_disk_read);
+        }
+    };
+    std::vector<std::thread> th;
+    for (int t = 0; t < 4; ++t) th.emplace_back(worker, t);
+    for (auto &x : th) x.join();
+    uint64_t counted = 0, copies = 0;
+    for (uint32_t id = 0; id < n_ids; ++id) {
+        ha_rag_chunk_info info;
+        REQUIRE(ha_rag_pool_query(ctx, id, &info) == HA_RAG_OK);
+        counted += info.count;
+        for (uint32_t tier : {(uint32_t)HA_RAG_TIER_PINNED, (uint32_t)HA_RAG_TIER_PAGEABLE}) {
+            void *p = nullptr;
+            size_t nb = 0;
+            if (ha_rag_pool_slot(ctx, id, tier, &p, &nb) == HA_RAG_OK) {
+                REQUIRE(nb == bytes[id].size() && std::memcmp(p, bytes[id].data(), nb) == 0);
+                ++copies;
+            }
+        }
+    }
+    REQUIRE(counted == chunks.load());
+    REQUIRE(copies > 0 && disk_bytes.load() > 0);
+    REQUIRE(ha_rag_destroy(ctx) == HA_RAG_OK);
+    std::free(pin);
+    std::free(page);
+    std::free(bounce);
+    std::printf("threads_host real tiers (%s): %llu chunks, %llu bytes from the file, %llu copies checked\n",
+                direct ? "O_DIRECT" : "buffered", (unsigned long long)chunks.load(),
+                (unsigned long long)disk_bytes.load(), (unsigned long long)copies);
+}
+
 int main(int argc, char **argv)
 {
     const int ops = argc > 1 ? std::atoi(argv[1]) : 3000;
+    if (argc > 2) {
+        real_tiers(ops, argv[2], 0);
+        real_tiers(ops, argv[2], 1);
+        std::printf("threads_host ok\n");
+        return 0;
+    }
     ha_rag_config cfg;
     std::memset(&cfg, 0, sizeof cfg);
     cfg.n_layers = 2;

@@ -578,6 +578,32 @@ def test_concurrent_requests_on_separate_streams():
     ctx.destroy()
 
 
+def test_short_lived_streams_are_forgotten():
+    """A caller that makes a stream per request and destroys it afterwards: ha_rag_forget_stream
+    takes the stream out of the library's books before it goes, so that stream after stream
+    (handles come back) promote, evict and load the same few slots correctly."""
+    L, H, D, T, g = 2, 2, 64, 128, 64
+    n = 8
+    ctx = _pool_ctx(L, H, D, T, g, hbm_slots=2, pin_slots=n, stg_slots=2, tau_gpu_ppm=1_000_000,
+                    precs=[B.PREC_INT4])
+    packed = [codec.quantize_pack_chunk(wl.kv_chunk(L, H, D, T, 260 + i), 4, g)[0] for i in range(n)]
+    for i, p in enumerate(packed):
+        ctx.pool_insert(i, B.PREC_INT4, T, p, B.TIER_PINNED)
+    ctx.rerank()                                   # every chunk belongs in HBM: two slots, constant eviction
+    ctx.forget_stream(torch.cuda.Stream())         # a stream the context has never seen: nothing to do
+    for rep in range(12):
+        s_ = torch.cuda.Stream()
+        ids = [(3 * rep + k) % n for k in range(3)]
+        out = torch.zeros((L, 2, H, 3 * T, D), dtype=torch.int16, device="cuda")
+        with torch.cuda.stream(s_):
+            ctx.load_chunks(ids, out, 3 * T, stream=s_)
+        ctx.forget_stream(s_)                      # waits for what the library enqueued there
+        ref, _ = codec.load_chunks(packed, (L, H, D), [T] * n, [4] * n, [g] * n, ids)
+        assert np.array_equal(host_u16(out), ref), rep
+        del s_
+    ctx.destroy()
+
+
 def test_batch_of_requests_one_call():
     L, H, D, T, g = 1, 2, 128, 96, 128
     n = 10

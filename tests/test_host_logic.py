@@ -641,6 +641,14 @@ def test_caller_owned_pinned_masters_of_a_hundred_thousand_ids():
     ctx.destroy()
 
 
+def test_forget_stream_on_a_context_without_a_gpu():
+    ctx = _ctx(2, 4, 500_000)
+    ctx.forget_stream(None)
+    ctx.forget_stream(0x1234)
+    assert B.lib().ha_rag_forget_stream(None, None) == B.EINVAL
+    ctx.destroy()
+
+
 def test_pinned_only_pool_needs_no_staging_unless_dma_is_asked_for():
     for dma in (False, True):
         ctx = B.Context(2, 2, 64, 128, group_int8=64, group_int4=64, tau_gpu_ppm=500_000, dry_run=True,

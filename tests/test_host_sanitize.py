@@ -51,6 +51,13 @@ def test_host_runtime_from_four_threads_under_tsan(tmp_path):
     r = subprocess.run([exe, "2000"], capture_output=True, text=True, env=env, timeout=300)
     assert r.returncode == 0, (r.stdout + r.stderr)[-4000:]
     assert "threads_host ok" in r.stdout
+    # the same four threads over real files and real bytes: the loads release the context's lock
+    # while the I/O threads move the chunks
+    pools = tmp_path / "pools"
+    pools.mkdir()
+    r = subprocess.run([exe, "120", str(pools)], capture_output=True, text=True, env=env, timeout=600)
+    assert r.returncode == 0, (r.stdout + r.stderr)[-4000:]
+    assert "threads_host ok" in r.stdout and "O_DIRECT" in r.stdout
 
 
 @pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"),
