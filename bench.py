@@ -193,18 +193,19 @@ def placed_from_pool(B, ctx, slabs, req, T, seed0=None):
     return out
 
 
-def time_quantize(B, wl, torch, ctx, shape, T, g, tags, reps=40):
+def time_quantize(B, wl, torch, ctx, shape, T, g, tags, reps=40, batch=32):
     """The offline step (Algorithm 1 step 3): quantize-pack kernel time per chunk and tag, HIP
-    events around `reps` launches on distinct sources."""
+    events around `reps` single-chunk launches on distinct sources, and around launches that
+    take a class of `batch` chunks at once (ha_rag_quantize_chunks)."""
     L, H, D = shape
     elems = L * 2 * H * T * D
-    srcs = [wl.kv_chunk_device(L, H, D, T, 777 + i) for i in range(4)]
+    srcs = [wl.kv_chunk_device(L, H, D, T, 777 + i) for i in range(batch)]
     out = {}
     stream = torch.cuda.Stream()
     for tag in tags:
         prec = prec_of(B, tag)
         nb = ctx.chunk_bytes(prec, T, g if prec in (B.PREC_INT8, B.PREC_INT4) else 0)
-        dst = [torch.empty(nb, dtype=torch.uint8, device="cuda") for _ in range(4)]
+        dst = [torch.empty(nb, dtype=torch.uint8, device="cuda") for _ in range(batch)]
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         with torch.cuda.stream(stream):
             for i in range(4):
@@ -212,15 +213,25 @@ def time_quantize(B, wl, torch, ctx, shape, T, g, tags, reps=40):
             torch.cuda.synchronize()
             e0.record(stream)
             for i in range(reps):
-                ctx.quantize_chunk(srcs[i % 4], T, prec, g, dst[i % 4], stream=stream)
+                ctx.quantize_chunk(srcs[i % batch], T, prec, g, dst[i % batch], stream=stream)
             e1.record(stream)
             torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / reps
+            us = e0.elapsed_time(e1) * 1e3 / reps
+            ctx.quantize_chunks(srcs, [T] * batch, prec, g, dst, stream=stream)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for _ in range(4):
+                ctx.quantize_chunks(srcs, [T] * batch, prec, g, dst, stream=stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us_b = e0.elapsed_time(e1) * 1e3 / (4 * batch)
         # Eq. 1 on the synthetic chunk: RMSE between the source and its round trip
         acc = torch.zeros(1, dtype=torch.float64, device="cuda")
         ctx.chunk_sq_error(srcs[0], dst[0], T, prec, g, acc)
         torch.cuda.synchronize()
         out[str(tag)] = {"us_per_chunk": us, "gbps": (elems * 2 + nb) / us / 1e3,
+                         "us_per_chunk_in_a_launch_of_%d" % batch: us_b,
+                         "gbps_in_a_launch_of_%d" % batch: (elems * 2 + nb) / us_b / 1e3,
                          "bytes_per_chunk": elems * 2 + nb,
                          "rmse": (float(acc.item()) / elems) ** 0.5}
     return out

@@ -312,6 +312,16 @@ int ha_rag_set_launch_params(ha_rag_ctx *ctx, const ha_rag_launch_params *lp);
 int ha_rag_quantize_chunk(ha_rag_ctx *ctx, const void *src, uint32_t n_tokens, uint32_t prec,
                           uint32_t group, void *dst, uint32_t *saturated, void *stream);
 
+/* Algorithm 1 step 3 compresses a whole class at once, Compression(S_i, chunks_i): the same
+ * as ha_rag_quantize_chunk for chunks i = 0..n-1 of one tag (srcs, dsts, n_tokens: host arrays;
+ * every srcs[i] / dsts[i] as src / dst above, lengths may differ, a chunk of 0 tokens is
+ * skipped), in one kernel launch per 128 chunks, so that short chunks do not each pay a
+ * launch's ramp and tail.  The bytes written are those of n separate calls; `saturated`
+ * receives the sum.  Nothing is enqueued unless every chunk passes the checks. */
+int ha_rag_quantize_chunks(ha_rag_ctx *ctx, const void *const *srcs, void *const *dsts,
+                           const uint32_t *n_tokens, uint32_t n, uint32_t prec, uint32_t group,
+                           uint32_t *saturated, void *stream);
+
 /* The same for a keys-only or values-only chunk: src is BF16 [L][H][n_tokens][D] (one
  * plane of a document's KV), dst takes half of ha_rag_chunk_bytes().  The bytes do not
  * depend on which of the two planes the chunk is. */

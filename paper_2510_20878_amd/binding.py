@@ -37,6 +37,7 @@ SYMBOLS = [
     "ha_rag_attend_workspace_bytes", "ha_rag_attend_chunks", "ha_rag_attend_chunks_workspace_bytes",
     "ha_rag_place_chunks", "ha_rag_attend_packed_static", "ha_rag_register_external",
     "ha_rag_pool_insert_external", "ha_rag_pool_repoint_external", "ha_rag_forget_stream",
+    "ha_rag_quantize_chunks",
 ]
 
 
@@ -138,6 +139,7 @@ def lib():
             "ha_rag_set_launch_params": (C.c_int, [vp, P(LaunchParams)]),
             "ha_rag_quantize_chunk": (C.c_int, [vp, vp, u32, u32, u32, vp, vp, vp]),
             "ha_rag_quantize_half": (C.c_int, [vp, vp, u32, u32, u32, vp, vp, vp]),
+            "ha_rag_quantize_chunks": (C.c_int, [vp, P(vp), P(vp), P(u32), u32, u32, u32, vp, vp]),
             "ha_rag_pool_insert_half": (C.c_int, [vp, u64, u32, u32, u32, vp, C.c_int, u32, vp]),
             "ha_rag_load_packed": (C.c_int, [vp, P(PackedChunk), u32, vp, u64, u64, vp]),
             "ha_rag_chunk_sq_error": (C.c_int, [vp, vp, vp, u32, u32, u32, u32, vp, vp]),
@@ -317,6 +319,16 @@ class Context:
         self._chk(lib().ha_rag_quantize_chunk(self._h, _addr(src), n_tokens, prec, group, _addr(dst),
                                               _addr(saturated), _stream(stream)),
                   "ha_rag_quantize_chunk")
+
+    def quantize_chunks(self, srcs, n_tokens, prec, group, dsts, saturated=None, stream=None):
+        """One launch for a list of chunks of one tag: srcs / dsts lists of tensors or addresses,
+        n_tokens a list."""
+        n = len(srcs)
+        sp = (C.c_void_p * max(n, 1))(*[_addr(x) for x in srcs])
+        dp = (C.c_void_p * max(n, 1))(*[_addr(x) for x in dsts])
+        nt = (C.c_uint32 * max(n, 1))(*[int(t) for t in n_tokens])
+        self._chk(lib().ha_rag_quantize_chunks(self._h, sp, dp, nt, n, prec, group, _addr(saturated),
+                                               _stream(stream)), "ha_rag_quantize_chunks")
 
     def quantize_half(self, src, n_tokens, prec, group, dst, saturated=None, stream=None):
         self._chk(lib().ha_rag_quantize_half(self._h, _addr(src), n_tokens, prec, group, _addr(dst),

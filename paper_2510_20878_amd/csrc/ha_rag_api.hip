@@ -149,34 +149,56 @@ int ha_rag_set_launch_params(ha_rag_ctx *c, const ha_rag_launch_params *lp)
     return HA_RAG_OK;
 }
 
-static int quantize_impl(ha_rag_ctx *c, const void *src, uint32_t n_tokens, uint32_t prec,
-                         uint32_t group, void *dst, uint32_t *saturated, void *stream, uint32_t part)
+// n chunks of one tag, one launch per kMaxK2Chunks of them
+static int quantize_impl(ha_rag_ctx *c, const void *const *srcs, void *const *dsts, const uint32_t *n_tokens,
+                         uint32_t n, uint32_t prec, uint32_t group, uint32_t *saturated, void *stream,
+                         uint32_t part)
 {
-    if (!c || !src || !dst) return HA_RAG_EINVAL;
-    if (((uintptr_t)src & 15u) || ((uintptr_t)dst & 15u) || ((uintptr_t)saturated & 3u)) return HA_RAG_EINVAL;
-    size_t total;
-    int rc = chunk_bytes_impl(c->cfg.n_layers, c->cfg.n_kv_heads, c->cfg.head_dim, prec, group,
-                              n_tokens, nullptr, nullptr, &total, part);
-    if (rc) return rc;
+    if (!c || (n && (!srcs || !dsts || !n_tokens))) return HA_RAG_EINVAL;
+    if ((uintptr_t)saturated & 3u) return HA_RAG_EINVAL;
+    for (uint32_t i = 0; i < n; ++i) {
+        if (!srcs[i] || !dsts[i] || ((uintptr_t)srcs[i] & 15u) || ((uintptr_t)dsts[i] & 15u)) return HA_RAG_EINVAL;
+        int rc = chunk_bytes_impl(c->cfg.n_layers, c->cfg.n_kv_heads, c->cfg.head_dim, prec, group,
+                                  n_tokens[i], nullptr, nullptr, nullptr, part);
+        if (rc) return rc;
+    }
     if (c->dry()) return HA_RAG_OK;
     std::lock_guard<std::mutex> g(c->mu);
-    HIPCHK(c, launch_k2(src, dst, part == kPartKV ? c->n_tiles : c->n_tiles / 2, c->cfg.head_dim,
-                        n_tokens, prec, has_meta(prec) ? group : 32u, saturated,
-                        (hipStream_t)stream));
+    K2Params p{};
+    p.n_tiles = part == kPartKV ? c->n_tiles : c->n_tiles / 2;
+    p.head_dim = c->cfg.head_dim;
+    p.saturated = saturated;
+    for (uint32_t i = 0; i < n; ++i) {
+        if (n_tokens[i] == 0) continue;  // holds nothing: nothing to write
+        p.c[p.n_chunks++] = K2Chunk{static_cast<const uint8_t *>(srcs[i]), static_cast<uint8_t *>(dsts[i]),
+                                    n_tokens[i], 0};
+        if (p.n_chunks == kMaxK2Chunks) {
+            HIPCHK(c, launch_k2(p, prec, has_meta(prec) ? group : 32u, (hipStream_t)stream));
+            p.n_chunks = 0;
+        }
+    }
+    if (p.n_chunks) HIPCHK(c, launch_k2(p, prec, has_meta(prec) ? group : 32u, (hipStream_t)stream));
     return HA_RAG_OK;
 }
 
 int ha_rag_quantize_chunk(ha_rag_ctx *c, const void *src, uint32_t n_tokens, uint32_t prec,
                           uint32_t group, void *dst, uint32_t *saturated, void *stream)
 {
-    return quantize_impl(c, src, n_tokens, prec, group, dst, saturated, stream, kPartKV);
+    return quantize_impl(c, &src, &dst, &n_tokens, 1, prec, group, saturated, stream, kPartKV);
+}
+
+int ha_rag_quantize_chunks(ha_rag_ctx *c, const void *const *srcs, void *const *dsts,
+                           const uint32_t *n_tokens, uint32_t n, uint32_t prec, uint32_t group,
+                           uint32_t *saturated, void *stream)
+{
+    return quantize_impl(c, srcs, dsts, n_tokens, n, prec, group, saturated, stream, kPartKV);
 }
 
 int ha_rag_quantize_half(ha_rag_ctx *c, const void *src, uint32_t n_tokens, uint32_t prec,
                          uint32_t group, void *dst, uint32_t *saturated, void *stream)
 {
     // the tile records of a half do not depend on which plane it is
-    return quantize_impl(c, src, n_tokens, prec, group, dst, saturated, stream, kPartK);
+    return quantize_impl(c, &src, &dst, &n_tokens, 1, prec, group, saturated, stream, kPartK);
 }
 
 int ha_rag_chunk_sq_error(ha_rag_ctx *c, const void *src, const void *packed, uint32_t n_tokens,

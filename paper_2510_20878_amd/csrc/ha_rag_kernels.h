@@ -79,10 +79,22 @@ struct K1Launch {
 // Enqueues one launch covering p.n_chunks chunks (fills the item fields of p).
 hipError_t launch_k1(K1Params &p, const K1Launch &cfg, hipStream_t stream);
 
-// Quantize + pack one chunk.  src BF16 [n_tiles][n_tokens][D]; dst packed.
-hipError_t launch_k2(const void *src, void *dst, uint32_t n_tiles, uint32_t head_dim,
-                     uint32_t n_tokens, uint32_t prec, uint32_t group, uint32_t *saturated,
-                     hipStream_t stream);
+// Quantize + pack the chunks of one launch (one tag, one group size; any lengths).  Chunk i:
+// src BF16 [n_tiles][n_tokens][D], dst packed.  The descriptors travel in the kernel arguments
+// (blockIdx.y = chunk), so that a whole class of Algorithm 1 is compressed by one launch and a
+// short chunk does not pay for a launch's ramp and tail of its own.
+struct K2Chunk {
+    const uint8_t *src;
+    uint8_t *dst;
+    uint32_t n_tokens, pad;
+};
+constexpr uint32_t kMaxK2Chunks = 128;
+struct K2Params {
+    uint32_t n_chunks, n_tiles, head_dim, pad;
+    uint32_t *saturated;   // device counter the integer tags add to, or null
+    K2Chunk c[kMaxK2Chunks];
+};
+hipError_t launch_k2(const K2Params &p, uint32_t prec, uint32_t group, hipStream_t stream);
 
 // Adds to *sum_sq (device, binary64) the squared error between src (BF16 [n_tiles][n_tokens][D])
 // and what `packed` decodes to.

@@ -10,6 +10,8 @@
 // packed layout (see include/ha_rag.h) is built so that lane i of a 64-lane wave
 // reads 16-byte word i of a 1024-byte run and writes 16-byte word i of four
 // 1024-byte runs: every memory instruction of a wave covers one contiguous KiB.
+#include <algorithm>
+
 #include "ha_rag_kernels.h"
 #include "ha_rag_decode.h"
 
@@ -402,17 +404,19 @@ __device__ __forceinline__ void group_minmax(float &mn, float &mx)
 }
 
 template <int BITS, int GSH>
-__global__ void __launch_bounds__(256) k2_quantize_pack(const uint8_t *__restrict__ src,
-                                                        uint8_t *__restrict__ dst,
-                                                        uint32_t n_tokens, uint32_t head_dim,
-                                                        uint32_t wg_per_tile, uint32_t *saturated)
+__global__ void __launch_bounds__(256) k2_quantize_pack(const K2Params p)
 {
-    const uint32_t n_e = n_tokens * head_dim;
+    const K2Chunk c = p.c[blockIdx.y];
+    const uint8_t *__restrict__ src = c.src;
+    uint8_t *__restrict__ dst = c.dst;
+    uint32_t *saturated = p.saturated;
+    const uint32_t n_e = c.n_tokens * p.head_dim;
     const uint32_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
+    const uint32_t wg_per_tile = (nblk + 3u) / 4u;
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
     const uint32_t tile = blockIdx.x / wg_per_tile;
     const uint32_t blk = (blockIdx.x - tile * wg_per_tile) * 4 + wave;
-    if (blk >= nblk) return;
+    if (tile >= p.n_tiles || blk >= nblk) return;  // the grid is as wide as the longest chunk
 
     const uint8_t *in = src + (uint64_t)tile * n_e * 2u + (uint64_t)blk * 4096u + lane * 16u;
     const uint32_t e = blk * kBlockElems + lane * 8;
@@ -516,12 +520,15 @@ __global__ void __launch_bounds__(256) k2_quantize_pack(const uint8_t *__restric
 
 // The 16-bit tag stores the BF16 words verbatim: one 1024-byte plane per wave (the shape
 // that copies fastest), zero fill behind the last element of a tile.
-__global__ void __launch_bounds__(64) k2_pack16(const uint8_t *__restrict__ src,
-                                                uint8_t *__restrict__ dst, uint32_t n_tokens,
-                                                uint32_t head_dim, uint32_t planes_per_tile)
+__global__ void __launch_bounds__(64) k2_pack16(const K2Params p)
 {
-    const uint32_t n_e = n_tokens * head_dim;
+    const K2Chunk c = p.c[blockIdx.y];
+    const uint8_t *__restrict__ src = c.src;
+    uint8_t *__restrict__ dst = c.dst;
+    const uint32_t n_e = c.n_tokens * p.head_dim;
+    const uint32_t planes_per_tile = (n_e + kBlockElems - 1) / kBlockElems * 4u;
     const uint32_t tile = blockIdx.x / planes_per_tile;
+    if (tile >= p.n_tiles) return;
     const uint32_t pl = blockIdx.x - tile * planes_per_tile;   // plane = 512 elements
     const uint32_t e = pl * 512u + threadIdx.x * 8u;
     u32x4 w = u32x4{0, 0, 0, 0};
@@ -532,16 +539,18 @@ __global__ void __launch_bounds__(64) k2_pack16(const uint8_t *__restrict__ src,
 // FP8 tags: every element is rounded on its own (nearest, ties to even, by the hardware
 // conversion) after clamping to the largest finite value; one wave per block.
 template <bool E5M2>
-__global__ void __launch_bounds__(256) k2_pack_fp8(const uint8_t *__restrict__ src,
-                                                   uint8_t *__restrict__ dst, uint32_t n_tokens,
-                                                   uint32_t head_dim, uint32_t wg_per_tile)
+__global__ void __launch_bounds__(256) k2_pack_fp8(const K2Params p)
 {
-    const uint32_t n_e = n_tokens * head_dim;
+    const K2Chunk c = p.c[blockIdx.y];
+    const uint8_t *__restrict__ src = c.src;
+    uint8_t *__restrict__ dst = c.dst;
+    const uint32_t n_e = c.n_tokens * p.head_dim;
     const uint32_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
+    const uint32_t wg_per_tile = (nblk + 3u) / 4u;
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
     const uint32_t tile = blockIdx.x / wg_per_tile;
     const uint32_t blk = (blockIdx.x - tile * wg_per_tile) * 4 + wave;
-    if (blk >= nblk) return;
+    if (tile >= p.n_tiles || blk >= nblk) return;
     const uint8_t *in = src + (uint64_t)tile * n_e * 2u + (uint64_t)blk * 4096u + lane * 16u;
     const uint32_t e = blk * kBlockElems + lane * 8;
     const float vmax = E5M2 ? 57344.0f : 448.0f;
@@ -589,67 +598,97 @@ __device__ __forceinline__ u16x2 splat16(uint32_t v)
     return u16x2{(uint16_t)v, (uint16_t)v};
 }
 
-// the two codes of one dword of BF16 words, one per 16-bit half (code in the low byte)
-__device__ __forceinline__ uint32_t gse8_encode_pair(uint32_t r, u16x2 lo, u16x2 lo2, u16x2 hi)
+// the two codes of one dword of BF16 words, one per 16-bit half (code in the low byte).
+// lo: biased e_lo; lo7: e_lo + 2 + 5 and hi5: e_hi + 5, the shared exponents with the shift's
+// constant folded in
+__device__ __forceinline__ uint32_t gse8_encode_pair(uint32_t r, u16x2 lo, u16x2 lo7, u16x2 hi5)
 {
-    const u16x2 w = __builtin_bit_cast(u16x2, r);
-    const u16x2 mag = w & splat16(0x7FFFu);
+    const uint32_t magw = r & 0x7FFF7FFFu;
+    const u16x2 mag = __builtin_bit_cast(u16x2, magw);
     const u16x2 eb = __builtin_elementwise_max(mag >> splat16(7), splat16(1));  // subnormal: 1
     const u16x2 rel = __builtin_elementwise_sub_sat(eb, lo);                    // exponent above e_lo
     const u16x2 k = (rel * splat16(171)) >> splat16(9);                         // rel / 3, rel < 254
-    const u16x2 g = __builtin_elementwise_min(k * splat16(3) + lo2, hi);        // k-th shared exponent
+    // G + 5, G the k-th shared exponent min(e_lo + 2 + 3k, e_hi)
+    const u16x2 g5 = __builtin_elementwise_min(k * splat16(3) + lo7, hi5);
     // significand with its leading one (none for subnormals) as an 8-bit integer: |x| =
-    // sig / 128 * 2^(eb - 127), so floor(|x| * 2^(2 - G)) = sig >> (G - eb + 5); G >= eb always
-    const u16x2 sig = (mag & splat16(0x7Fu)) | (__builtin_elementwise_min(mag, splat16(0x80u)) & splat16(0x80u));
-    const u16x2 sh = __builtin_elementwise_min(g - eb + splat16(5), splat16(15));
+    // sig / 128 * 2^(eb - 127), so floor(|x| * 2^(2 - G)) = sig >> (G - eb + 5); G >= eb always.
+    // min(mag, low seven bits | 0x80) is that integer: a normal value is at least 0x80
+    const u16x2 sig = __builtin_elementwise_min(mag, __builtin_bit_cast(u16x2, (magw & 0x007F007Fu) | 0x00800080u));
+    const u16x2 sh = __builtin_elementwise_min(g5 - eb, splat16(15));
     const u16x2 field = sig >> sh;                                               // 0..7
-    const u16x2 code = (k * splat16(8) + field) * __builtin_elementwise_min(field, splat16(1));
-    return __builtin_bit_cast(uint32_t, (u16x2)(code | ((w >> splat16(8)) & splat16(0x80u))));
+    // a zero field is stored with index 0
+    // (0 - min(field, 1)) is all ones in a half with a nonzero field, else zero
+    const uint32_t keep = __builtin_bit_cast(uint32_t, (u16x2)(splat16(0) - __builtin_elementwise_min(field, splat16(1))));
+    const uint32_t k8 = __builtin_bit_cast(uint32_t, (u16x2)(k << splat16(3)));
+    return ((k8 & keep) | __builtin_bit_cast(uint32_t, field)) | ((r >> 8) & 0x00800080u);
 }
 
-__global__ void __launch_bounds__(1024) k2_pack_gse8(const uint8_t *__restrict__ src,
-                                                    uint8_t *__restrict__ dst, uint32_t n_tokens,
-                                                    uint32_t head_dim)
+// HELD: blocks of the tile that every wave keeps in registers between the two passes (the
+// tile is then read once); 0: the tile is longer than 16 waves can hold and pass 2 reads it
+// again.
+template <int HELD>
+__global__ void __launch_bounds__(1024) k2_pack_gse8(const K2Params p)
 {
     __shared__ uint32_t s_lo[16], s_hi[16];
-    const uint32_t n_e = n_tokens * head_dim;
+    const K2Chunk c = p.c[blockIdx.y];
+    const uint8_t *__restrict__ src = c.src;
+    uint8_t *__restrict__ dst = c.dst;
+    const uint32_t n_e = c.n_tokens * p.head_dim;
     const uint32_t nblk = (n_e + kBlockElems - 1) / kBlockElems;
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
     const uint32_t n_waves = blockDim.x >> 6;
     const uint32_t tile = blockIdx.x;
     const uint8_t *in = src + (uint64_t)tile * n_e * 2u;
     uint8_t *rec = dst + (uint64_t)tile * ((uint64_t)nblk * 2048u + 16u);
+    constexpr int kHold = HELD > 0 ? HELD : 1;
+    u32x4 held[kHold][4];
 
-    // biased exponents; a zero contributes 0xFFFF to the minimum and 1 to the maximum, so a
-    // tile without nonzero values ends with lo > hi
-    u16x2 lo2 = splat16(0xFFFFu), hi2 = splat16(0);
-    for (uint32_t blk = wave; blk < nblk; blk += n_waves) {
+    // all four loads of a block are issued before the first use: a lane past the tile's end
+    // re-reads the tile's first words, which changes neither extreme of the range
+    auto load_block = [&](uint32_t blk, u32x4 *planes) {
         const uint32_t e = blk * kBlockElems + lane * 8;
-        // all four loads are issued before the first use: a lane past the tile's end re-reads
-        // the tile's first words and drops them (zeros neither widen the range nor encode)
-        u32x4 planes[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t ej = e + j * 512;
             planes[j] = ld16(in + (uint64_t)(ej < n_e ? ej : 0u) * 2u);
         }
+    };
+    // The range follows from the largest magnitude and the smallest nonzero one (the exponent
+    // is monotonic in the magnitude word).  mag - 1 wraps a zero to 0xFFFF, so zeros drop out of
+    // the minimum; a tile without nonzero values ends with lo > hi.
+    u16x2 lo2 = splat16(0xFFFFu), hi2 = splat16(0);
+    auto range_block = [&](const u32x4 *planes) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const u32x4 raw = e + j * 512 < n_e ? planes[j] : u32x4{0, 0, 0, 0};
+            const u32x4 raw = planes[j];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const uint32_t r = raw[k];  // a copy: bit_cast of the vector element itself reads element 0
-                const u16x2 mag = __builtin_bit_cast(u16x2, r) & splat16(0x7FFFu);
-                const u16x2 eb = __builtin_elementwise_max(mag >> splat16(7), splat16(1));
-                const u16x2 zero_mask = __builtin_elementwise_min(mag, splat16(1)) - splat16(1);
-                lo2 = __builtin_elementwise_min(lo2, eb | zero_mask);
-                hi2 = __builtin_elementwise_max(hi2, eb);
+                const u16x2 mag = __builtin_bit_cast(u16x2, r & 0x7FFF7FFFu);
+                lo2 = __builtin_elementwise_min(lo2, (u16x2)(mag - splat16(1)));
+                hi2 = __builtin_elementwise_max(hi2, mag);
             }
         }
+    };
+    if (HELD > 0) {
+#pragma unroll
+        for (int i = 0; i < kHold; ++i)  // every wave's loads are all in flight together
+            if (wave + i * n_waves < nblk) load_block(wave + i * n_waves, held[i]);
+#pragma unroll
+        for (int i = 0; i < kHold; ++i)
+            if (wave + i * n_waves < nblk) range_block(held[i]);
+    } else {
+        for (uint32_t blk = wave; blk < nblk; blk += n_waves) {
+            load_block(blk, held[0]);
+            range_block(held[0]);
+        }
     }
+    // magnitudes -> biased exponents (a subnormal counts as 1; no nonzero value: 0xFFFF)
     const uint32_t lo_pair = __builtin_bit_cast(uint32_t, lo2), hi_pair = __builtin_bit_cast(uint32_t, hi2);
-    uint32_t lo = (lo_pair & 0xFFFFu) < (lo_pair >> 16) ? (lo_pair & 0xFFFFu) : (lo_pair >> 16);
-    uint32_t hi = (hi_pair & 0xFFFFu) > (hi_pair >> 16) ? (hi_pair & 0xFFFFu) : (hi_pair >> 16);
+    const uint32_t min_m1 = (lo_pair & 0xFFFFu) < (lo_pair >> 16) ? (lo_pair & 0xFFFFu) : (lo_pair >> 16);
+    const uint32_t max_m = (hi_pair & 0xFFFFu) > (hi_pair >> 16) ? (hi_pair & 0xFFFFu) : (hi_pair >> 16);
+    uint32_t lo = min_m1 == 0xFFFFu ? 0xFFFFu : ((min_m1 + 1u) >> 7 ? (min_m1 + 1u) >> 7 : 1u);
+    uint32_t hi = max_m >> 7 ? max_m >> 7 : 1u;
     for (int o = 32; o >= 1; o >>= 1) {
         const uint32_t l2 = (uint32_t)__shfl_xor((int)lo, o), h2 = (uint32_t)__shfl_xor((int)hi, o);
         lo = l2 < lo ? l2 : lo;
@@ -669,29 +708,34 @@ __global__ void __launch_bounds__(1024) k2_pack_gse8(const uint8_t *__restrict__
     if (lo > hi) lo = hi = 127;          // all zero: range (e_lo, e_hi) = (0, 0)
     if (lo + 47 < hi) lo = hi - 47;      // 16 shared exponents, 3 apart, reach 48 binades
 
-    const u16x2 vlo = splat16(lo), vlo2 = splat16(lo + 2u), vhi = splat16(hi);
-    for (uint32_t blk = wave; blk < nblk; blk += n_waves) {
+    const u16x2 vlo = splat16(lo), vlo2 = splat16(lo + 7u), vhi = splat16(hi + 5u);
+    auto encode_block = [&](uint32_t blk, const u32x4 *planes) {
         const uint32_t e = blk * kBlockElems + lane * 8;
         uint32_t code[4][2];
-        u32x4 planes[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const uint32_t ej = e + j * 512;
-            planes[j] = ld16(in + (uint64_t)(ej < n_e ? ej : 0u) * 2u);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const u32x4 raw = e + j * 512 < n_e ? planes[j] : u32x4{0, 0, 0, 0};
+            const u32x4 raw = planes[j];
+            const bool live = e + j * 512 < n_e;  // the padding behind the tile's end is zero bytes
 #pragma unroll
             for (int d = 0; d < 2; ++d) {  // four elements -> one dword of codes
                 const uint32_t c01 = gse8_encode_pair(raw[2 * d], vlo, vlo2, vhi);
                 const uint32_t c23 = gse8_encode_pair(raw[2 * d + 1], vlo, vlo2, vhi);
-                code[j][d] = __builtin_amdgcn_perm(c23, c01, 0x06040200u);  // low bytes of the halves
+                code[j][d] = live ? __builtin_amdgcn_perm(c23, c01, 0x06040200u) : 0u;  // low bytes of the halves
             }
         }
         uint8_t *o = rec + (uint64_t)blk * 2048u + lane * 16u;
         st16<false>(o, u32x4{code[0][0], code[0][1], code[1][0], code[1][1]});
         st16<false>(o + 1024, u32x4{code[2][0], code[2][1], code[3][0], code[3][1]});
+    };
+    if (HELD > 0) {
+#pragma unroll
+        for (int i = 0; i < kHold; ++i)
+            if (wave + i * n_waves < nblk) encode_block(wave + i * n_waves, held[i]);
+    } else {
+        for (uint32_t blk = wave; blk < nblk; blk += n_waves) {
+            load_block(blk, held[0]);
+            encode_block(blk, held[0]);
+        }
     }
     if (threadIdx.x == 0) {
         const uint32_t e_lo = (lo - 127u) & 0xFFu, e_hi = (hi - 127u) & 0xFFu;
@@ -700,55 +744,56 @@ __global__ void __launch_bounds__(1024) k2_pack_gse8(const uint8_t *__restrict__
 }
 
 template <int BITS>
-static void launch_k2_g(uint32_t gsh, dim3 grid, hipStream_t stream, const uint8_t *s, uint8_t *d,
-                        uint32_t n_tokens, uint32_t head_dim, uint32_t wg_per_tile,
-                        uint32_t *saturated)
+static void launch_k2_g(uint32_t gsh, dim3 grid, hipStream_t stream, const K2Params &p)
 {
     dim3 block(256);
     switch (gsh) {
-    case 5: hipLaunchKernelGGL((k2_quantize_pack<BITS, 5>), grid, block, 0, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated); break;
-    case 6: hipLaunchKernelGGL((k2_quantize_pack<BITS, 6>), grid, block, 0, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated); break;
-    case 7: hipLaunchKernelGGL((k2_quantize_pack<BITS, 7>), grid, block, 0, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated); break;
-    case 8: hipLaunchKernelGGL((k2_quantize_pack<BITS, 8>), grid, block, 0, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated); break;
-    default: hipLaunchKernelGGL((k2_quantize_pack<BITS, 9>), grid, block, 0, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated); break;
+    case 5: hipLaunchKernelGGL((k2_quantize_pack<BITS, 5>), grid, block, 0, stream, p); break;
+    case 6: hipLaunchKernelGGL((k2_quantize_pack<BITS, 6>), grid, block, 0, stream, p); break;
+    case 7: hipLaunchKernelGGL((k2_quantize_pack<BITS, 7>), grid, block, 0, stream, p); break;
+    case 8: hipLaunchKernelGGL((k2_quantize_pack<BITS, 8>), grid, block, 0, stream, p); break;
+    default: hipLaunchKernelGGL((k2_quantize_pack<BITS, 9>), grid, block, 0, stream, p); break;
     }
 }
 
-hipError_t launch_k2(const void *src, void *dst, uint32_t n_tiles, uint32_t head_dim,
-                     uint32_t n_tokens, uint32_t prec, uint32_t group, uint32_t *saturated,
-                     hipStream_t stream)
+hipError_t launch_k2(const K2Params &p, uint32_t prec, uint32_t group, hipStream_t stream)
 {
     const uint32_t bits = prec == kP16 ? 16u : prec == kInt4 ? 4u : 8u;
-    if (n_tokens == 0 || n_tiles == 0) return hipSuccess;
-    const uint64_t n_e = (uint64_t)n_tokens * head_dim;
-    if (n_e > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    const uint32_t nblk = (uint32_t)((n_e + kBlockElems - 1) / kBlockElems);
-    const uint32_t wg_per_tile = (nblk + 3) / 4;
-    const uint64_t gx = (uint64_t)n_tiles * wg_per_tile;
+    if (p.n_chunks == 0 || p.n_tiles == 0) return hipSuccess;
+    if (p.n_chunks > kMaxK2Chunks) return hipErrorInvalidValue;
+    uint32_t max_blk = 0;  // blocks per tile of the longest chunk: the grid's width follows it
+    for (uint32_t i = 0; i < p.n_chunks; ++i) {
+        const K2Chunk &c = p.c[i];
+        if (!c.src || !c.dst || c.n_tokens == 0) return hipErrorInvalidValue;
+        const uint64_t n_e = (uint64_t)c.n_tokens * p.head_dim;
+        if (n_e > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        max_blk = std::max(max_blk, (uint32_t)((n_e + kBlockElems - 1) / kBlockElems));
+    }
+    const uint64_t gx = (uint64_t)p.n_tiles * ((max_blk + 3) / 4);
     if (gx > 0x7FFFFFFFull) return hipErrorInvalidValue;
     uint32_t gsh = 0;
     while ((1u << gsh) < group) ++gsh;
-    const uint8_t *s = static_cast<const uint8_t *>(src);
-    uint8_t *d = static_cast<uint8_t *>(dst);
-    dim3 grid((uint32_t)gx);
+    dim3 grid((uint32_t)gx, p.n_chunks);
     if (prec == kGSE8) {
-        const uint32_t waves = nblk < 16u ? (nblk < 1u ? 1u : nblk) : 16u;  // one block per wave and pass
-        hipLaunchKernelGGL(k2_pack_gse8, dim3(n_tiles), dim3(waves * 64u), 0, stream, s, d, n_tokens,
-                           head_dim);
+        const uint32_t waves = max_blk < 16u ? max_blk : 16u;
+        const dim3 g2(p.n_tiles, p.n_chunks), b2(waves * 64u);
+        // up to four blocks per wave stay in registers between the passes (tiles of up to 1024
+        // tokens x 128 dims); longer tiles are read twice
+        if (max_blk <= 16u) hipLaunchKernelGGL(k2_pack_gse8<1>, g2, b2, 0, stream, p);
+        else if (max_blk <= 32u) hipLaunchKernelGGL(k2_pack_gse8<2>, g2, b2, 0, stream, p);
+        else if (max_blk <= 64u) hipLaunchKernelGGL(k2_pack_gse8<4>, g2, b2, 0, stream, p);
+        else hipLaunchKernelGGL(k2_pack_gse8<0>, g2, b2, 0, stream, p);
     } else if (prec == kE4M3 || prec == kE5M2) {
-        if (prec == kE5M2)
-            hipLaunchKernelGGL(k2_pack_fp8<true>, grid, dim3(256), 0, stream, s, d, n_tokens, head_dim, wg_per_tile);
-        else
-            hipLaunchKernelGGL(k2_pack_fp8<false>, grid, dim3(256), 0, stream, s, d, n_tokens, head_dim, wg_per_tile);
+        if (prec == kE5M2) hipLaunchKernelGGL(k2_pack_fp8<true>, grid, dim3(256), 0, stream, p);
+        else hipLaunchKernelGGL(k2_pack_fp8<false>, grid, dim3(256), 0, stream, p);
     } else if (bits == 16) {
-        const uint64_t planes = (uint64_t)n_tiles * nblk * 4u;
+        const uint64_t planes = (uint64_t)p.n_tiles * max_blk * 4u;
         if (planes > 0x7FFFFFFFull) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(k2_pack16, dim3((uint32_t)planes), dim3(64), 0, stream, s, d, n_tokens,
-                           head_dim, nblk * 4u);
+        hipLaunchKernelGGL(k2_pack16, dim3((uint32_t)planes, p.n_chunks), dim3(64), 0, stream, p);
     } else {
         if (gsh < 5 || gsh > 9 || (1u << gsh) != group) return hipErrorInvalidValue;
-        if (prec == kInt8) launch_k2_g<8>(gsh, grid, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated);
-        else if (prec == kInt4) launch_k2_g<4>(gsh, grid, stream, s, d, n_tokens, head_dim, wg_per_tile, saturated);
+        if (prec == kInt8) launch_k2_g<8>(gsh, grid, stream, p);
+        else if (prec == kInt4) launch_k2_g<4>(gsh, grid, stream, p);
         else return hipErrorInvalidValue;
     }
     return hipGetLastError();

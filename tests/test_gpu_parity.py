@@ -136,6 +136,49 @@ def test_quantize_codes_bit_exact_on_tens_of_millions_of_elements(prec, g):
     ctx.destroy()
 
 
+@pytest.mark.parametrize("prec", sorted(ORC))
+def test_a_class_of_chunks_in_one_launch_equals_chunk_by_chunk_oracle(prec):
+    """ha_rag_quantize_chunks: ragged lengths in one launch, bytes equal to the oracle's for
+    every chunk, nothing written past any chunk, the saturation count summed."""
+    L, H, D, g = 2, 2, 128, 64
+    tokens = [1, 40, 16, 77, 130, 5, 64]
+    ctx = B.Context(L, H, D, max(tokens), group_int8=g, group_int4=g)
+    srcs = [special_values_chunk(L, H, D, t, 50 + i) if i % 3 == 0 else wl.kv_chunk(L, H, D, t, 60 + i)
+            for i, t in enumerate(tokens)]
+    refs = [codec.quantize_pack_chunk(s_, ORC[prec], g) for s_ in srcs]
+    dsrc = [dev_u16(s_) for s_ in srcs]
+    ddst = [torch.full((len(r[0]) + 64,), 0xAB, dtype=torch.uint8, device="cuda") for r in refs]
+    sat = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ctx.quantize_chunks(dsrc, tokens, prec, g, ddst, saturated=sat)
+    torch.cuda.synchronize()
+    for i, (ref, _) in enumerate(refs):
+        got = ddst[i].cpu().numpy()
+        assert np.array_equal(got[:len(ref)], ref), i
+        assert np.all(got[len(ref):] == 0xAB), i
+    if prec in (B.PREC_INT8, B.PREC_INT4):
+        assert int(sat.item()) == sum(r[1] for r in refs)
+    ctx.destroy()
+
+
+def test_more_chunks_than_one_quantize_launch_holds():
+    L, H, D, T, g = 1, 1, 64, 20, 64
+    n = 150                                              # two launches of at most 128 descriptors
+    ctx = B.Context(L, H, D, T, group_int8=g, group_int4=g)
+    srcs = [wl.kv_chunk(L, H, D, T - i % 7, 900 + i) for i in range(n)]
+    tokens = [T - i % 7 for i in range(n)]
+    dsrc = [dev_u16(s_) for s_ in srcs]
+    ddst = [torch.zeros(ctx.chunk_bytes(B.PREC_INT4, t), dtype=torch.uint8, device="cuda") for t in tokens]
+    ctx.quantize_chunks(dsrc, tokens, B.PREC_INT4, g, ddst)
+    torch.cuda.synchronize()
+    for i in range(n):
+        assert np.array_equal(ddst[i].cpu().numpy(), codec.quantize_pack_chunk(srcs[i], 4, g)[0]), i
+    # a bad chunk anywhere in the list: nothing is enqueued
+    with pytest.raises(B.HaRagError) as e:
+        ctx.quantize_chunks(dsrc[:3], [T, T + 100000000, T], B.PREC_INT4, g, ddst[:3])
+    assert e.value.code in (B.EINVAL, B.EFORMAT)
+    ctx.destroy()
+
+
 def _load_case(shape, tokens, precs, g, order, seed, cap_extra=0, tok_base=0, launch=None):
     L, H, D = shape
     ctx = B.Context(L, H, D, max(tokens), group_int8=g, group_int4=g)
