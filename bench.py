@@ -638,6 +638,7 @@ def run_attend(args, B, wl, torch):
     per = sorted(a.elapsed_time(b) for a, b in evs)
     call_ms = ev_ms / (args.steps * L)
     achieved = step_bytes / L / (call_ms * 1e-3) / 1e9
+    log(f"attend8b: {call_ms * 1e3:.1f} us per layer call (events), {ms_per_step:.3f} ms per step")
     verified = verify_attend(torch, ctx, slabs, set_chunks[0], sets[0], q, out, lse, shape, g, n_qh,
                              scale, ws, ws_bytes, stream, args.verify_samples, args.seed)
     # the other route, measured in the same run: build each request's BF16 cache once (the load

@@ -42,8 +42,16 @@ struct Doc {
 struct Plan {               // one request
     uint32_t first_doc = 0, n_docs = 0;  // its documents that hold tokens
     uint32_t n_split = 1, n_mt = 1, max_blocks = 0;
+    uint32_t shared = 0;       // more than two query tiles: the kernel whose waves share each decoded block
+    uint32_t run_len = 1, n_runs = 0;  // documents per workgroup (shared kernel only) and runs of the request
     uint64_t part_floats = 0;  // offset of its records in the workspace
 };
+
+// workgroups per (document or run, KV head, split) of a request
+uint32_t tile_groups(const Plan &pl, uint32_t waves)
+{
+    return pl.shared ? (pl.n_mt + 2u * waves - 1u) / (2u * waves) : (pl.n_mt + 1u) / 2u;
+}
 
 // Checks everything and lays the workspace out.  *floats = workspace size in binary32 words.
 // plans: n_reqs entries; docs, open_k, open_v: filled here, ENOSPC if one of them is too small
@@ -51,7 +59,7 @@ struct Plan {               // one request
 int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_attend_request *reqs,
                 uint32_t n_reqs, uint32_t n_q_heads, Plan *plans, Fixed<Doc> *docs,
                 Fixed<uint32_t> open_k, Fixed<uint32_t> open_v, uint64_t *floats,
-                uint32_t *split_blocks, bool need_buffers)
+                uint32_t *split_blocks, uint32_t *shared_waves, bool need_buffers)
 {
     if (!c || !reqs || n_reqs == 0 || n_reqs > HA_RAG_MAX_ATTEND_REQUESTS) return HA_RAG_EINVAL;
     if (c->cfg.head_dim != kAttendHeadDim) return HA_RAG_EFORMAT;
@@ -72,6 +80,7 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
             return HA_RAG_EINVAL;
         pl.first_doc = (uint32_t)docs->size();
         pl.n_mt = (rq.n_q * G + 15u) / 16u;
+        pl.shared = pl.n_mt > 2u;
         uint32_t max_tokens = 0;
         open_k.clear();
         open_v.clear();
@@ -124,24 +133,44 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
         pl.max_blocks = (max_tokens + 15u) / 16u;
         n_chunks += rq.n_chunks;
     }
+    // The shared kernel runs with four waves (eight tiles a workgroup) as soon as one request
+    // has more than four tiles, else with two.
+    uint32_t waves = 2;
+    for (uint32_t r = 0; r < n_reqs; ++r)
+        if (plans[r].shared && plans[r].n_mt > 4u) waves = 4;
+    *shared_waves = waves;
     // Tokens per workgroup: as many as possible (every workgroup pays for fetching the queries
     // and for writing a record), but fine enough that the launch fills the chip a few times
     // over, since workgroups of one size finish in rounds.
     uint32_t sb = kAttendMaxSplitBlocks;
+    uint64_t groups = 0;
     for (;; sb >>= 1) {
-        uint64_t groups = 0;
+        groups = 0;
         for (uint32_t r = 0; r < n_reqs; ++r) {
             const Plan &pl = plans[r];
-            groups += (uint64_t)pl.n_docs * H * ((pl.max_blocks + sb - 1u) / sb) * ((pl.n_mt + 1u) / 2u);
+            groups += (uint64_t)pl.n_docs * H * ((pl.max_blocks + sb - 1u) / sb) * tile_groups(pl, waves);
         }
         if (groups >= kAttendTargetGroups || sb == kAttendMinSplitBlocks) break;
     }
     *split_blocks = sb;
+    // With workgroups to spare, a workgroup of the shared kernel takes a run of consecutive
+    // documents of its request instead of one: a record per run, not per document, is written
+    // and merged (records rival the packed bytes once a request has hundreds of query rows).
+    const uint64_t per_run = groups / kAttendTargetGroups;  // documents a run may hold
     for (uint32_t r = 0; r < n_reqs; ++r) {
         Plan &pl = plans[r];
         pl.n_split = pl.max_blocks ? (pl.max_blocks + sb - 1u) / sb : 1u;
+        pl.run_len = 1;
+        pl.n_runs = pl.n_docs;
+        if (pl.shared && per_run >= 2 && pl.n_docs > 1) {
+            uint32_t most = per_run < pl.n_docs ? (uint32_t)per_run : pl.n_docs;
+            if (most > kAttendLaunchChunks) most = kAttendLaunchChunks;  // a run lies within one launch
+            const uint32_t n_runs = (pl.n_docs + most - 1u) / most;
+            pl.run_len = (pl.n_docs + n_runs - 1u) / n_runs;  // runs of equal length, the last may be shorter
+            pl.n_runs = (pl.n_docs + pl.run_len - 1u) / pl.run_len;
+        }
         pl.part_floats = total;
-        total += (uint64_t)pl.n_docs * H * pl.n_split * pl.n_mt * kAttendRecFloats;
+        total += (uint64_t)pl.n_runs * H * pl.n_split * pl.n_mt * kAttendRecFloats;
     }
     if (total * 4ull > (1ull << 40)) return HA_RAG_EINVAL;
     *floats = total;
@@ -183,9 +212,9 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
                   void *stream, uint64_t *need = nullptr)
 {
     uint64_t floats = 0;
-    uint32_t split_blocks = 0;
+    uint32_t split_blocks = 0, waves = 2;
     int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, ps.plans, &ps.docs, ps.open_k, ps.open_v,
-                         &floats, &split_blocks, true);
+                         &floats, &split_blocks, &waves, true);
     if (rc) return rc;
     const Plan *plans = ps.plans;
     const Fixed<Doc> &docs = ps.docs;
@@ -198,27 +227,32 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
     const uint32_t H = c->cfg.n_kv_heads;
     float *ws = static_cast<float *>(workspace);
 
-    K6Params kp{};
-    kp.n_kv_heads = H;
-    kp.n_q_heads = n_q_heads;
-    kp.layer = layer;
-    kp.scale_log2 = sm_scale * 1.44269504088896341f;
-    kp.split_blocks = split_blocks;
+    // two launches in the making: requests of at most two query tiles, and the others
+    K6Params kp{}, ks{};
+    for (K6Params *q : {&kp, &ks}) {
+        q->n_kv_heads = H;
+        q->n_q_heads = n_q_heads;
+        q->layer = layer;
+        q->scale_log2 = sm_scale * 1.44269504088896341f;
+        q->split_blocks = split_blocks;
+    }
+    auto fill = [&](K6Chunk &d, const ha_rag_attend_request &rq, const Plan &pl, const Doc &doc, uint32_t run_no) {
+        d.k = doc.k + (uint64_t)(doc.k_first + layer * doc.k_step) * doc.k_tile;
+        d.v = doc.v + (uint64_t)(doc.v_first + layer * doc.v_step) * doc.v_tile;
+        d.q = static_cast<const uint16_t *>(rq.q);
+        d.part = ws + pl.part_floats + (uint64_t)run_no * H * pl.n_split * pl.n_mt * kAttendRecFloats;
+        d.n_tokens = doc.n_tokens;
+        d.info = doc.info;
+        d.n_q = rq.n_q;
+        d.n_split = pl.n_split;
+        d.run = 1;
+        d.more = 0;
+    };
     for (uint32_t r = 0; r < n_reqs; ++r) {
-        const ha_rag_attend_request &rq = reqs[r];
         const Plan &pl = plans[r];
-        const uint64_t per_doc = (uint64_t)H * pl.n_split * pl.n_mt * kAttendRecFloats;
+        if (pl.shared) continue;
         for (uint32_t i = 0; i < pl.n_docs; ++i) {
-            const Doc &doc = docs[pl.first_doc + i];
-            K6Chunk &d = kp.c[kp.n_chunks++];
-            d.k = doc.k + (uint64_t)(doc.k_first + layer * doc.k_step) * doc.k_tile;
-            d.v = doc.v + (uint64_t)(doc.v_first + layer * doc.v_step) * doc.v_tile;
-            d.q = static_cast<const uint16_t *>(rq.q);
-            d.part = ws + pl.part_floats + i * per_doc;
-            d.n_tokens = doc.n_tokens;
-            d.info = doc.info;
-            d.n_q = rq.n_q;
-            d.n_split = pl.n_split;
+            fill(kp.c[kp.n_chunks++], reqs[r], pl, docs[pl.first_doc + i], i);
             if (kp.n_chunks == kAttendLaunchChunks) {
                 HIPCHK(c, launch_k6(kp, st));
                 kp.n_chunks = 0;
@@ -226,6 +260,44 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
         }
     }
     if (kp.n_chunks) HIPCHK(c, launch_k6(kp, st));
+    // The shared kernel's launch lists the runs' first documents, then the other documents run
+    // by run.  A run never straddles two launches: first count the runs that fit, then fill.
+    struct RunPos {
+        uint32_t r, i;  // request, first document of the run
+    };
+    auto settle = [&](RunPos &p) {  // moves p to the next run there is; false at the end
+        while (p.r < n_reqs && (!plans[p.r].shared || p.i >= plans[p.r].n_docs)) {
+            ++p.r;
+            p.i = 0;
+        }
+        return p.r < n_reqs;
+    };
+    auto run_docs = [&](const RunPos &p) {
+        const Plan &pl = plans[p.r];
+        return pl.n_docs - p.i < pl.run_len ? pl.n_docs - p.i : pl.run_len;
+    };
+    RunPos at = {0, 0};
+    while (settle(at)) {
+        uint32_t n_runs = 0, n_all = 0;
+        for (RunPos p = at; settle(p) && n_all + run_docs(p) <= kAttendLaunchChunks; p.i += plans[p.r].run_len) {
+            ++n_runs;
+            n_all += run_docs(p);
+        }
+        uint32_t later = n_runs;  // where the next run's other documents go
+        for (uint32_t k = 0; k < n_runs; ++k, at.i += plans[at.r].run_len) {
+            settle(at);
+            const Plan &pl = plans[at.r];
+            const uint32_t len = run_docs(at), run_no = at.i / pl.run_len;
+            K6Chunk &head = ks.c[k];
+            fill(head, reqs[at.r], pl, docs[pl.first_doc + at.i], run_no);
+            head.run = len;
+            head.more = later;
+            for (uint32_t d = 1; d < len; ++d)
+                fill(ks.c[later++], reqs[at.r], pl, docs[pl.first_doc + at.i + d], run_no);
+        }
+        ks.n_chunks = n_all;
+        HIPCHK(c, launch_k6_shared(ks, n_runs, waves, st));
+    }
 
     K7Params mp{};
     mp.n_kv_heads = H;
@@ -236,7 +308,7 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
         d.out = reqs[r].out;
         d.lse = reqs[r].lse;
         d.n_q = reqs[r].n_q;
-        d.n_chunks = plans[r].n_docs;
+        d.n_chunks = plans[r].n_runs;
         d.n_split = plans[r].n_split;
         d.pad = 0;
         if (mp.n_reqs == kMaxMergeReqs) {
@@ -328,9 +400,9 @@ int ha_rag_attend_workspace_bytes(ha_rag_ctx *c, const ha_rag_packed_chunk *chun
     HeapPlanStore hs(reqs, n_reqs);
     PlanStore ps = hs.store();
     uint64_t floats = 0;
-    uint32_t split_blocks = 0;
+    uint32_t split_blocks = 0, waves = 0;
     int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, ps.plans, &ps.docs, ps.open_k, ps.open_v,
-                         &floats, &split_blocks, false);
+                         &floats, &split_blocks, &waves, false);
     if (rc) return rc;
     *bytes = (size_t)(floats * 4ull);
     return HA_RAG_OK;
@@ -404,9 +476,9 @@ int ha_rag_attend_chunks_workspace_bytes(ha_rag_ctx *c, const uint64_t *ids,
     HeapPlanStore hs(reqs, n_reqs);
     PlanStore ps = hs.store();
     uint64_t floats = 0;
-    uint32_t split_blocks = 0;
+    uint32_t split_blocks = 0, waves = 0;
     rc = plan_attend(c, chunks.data(), reqs, n_reqs, n_q_heads, ps.plans, &ps.docs, ps.open_k, ps.open_v,
-                     &floats, &split_blocks, false);
+                     &floats, &split_blocks, &waves, false);
     if (rc) return rc;
     *bytes = (size_t)(floats * 4ull);
     return HA_RAG_OK;

@@ -1,0 +1,116 @@
+// Device-side pieces shared by the attention kernels over packed chunks: the per-format block
+// geometry, the decoders that give the BF16 values a load would write, and small helpers.
+#pragma once
+#include "ha_rag_kernels.h"
+#include "ha_rag_decode.h"
+
+namespace ha_rag {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <uint32_t PREC>
+struct Fmt {
+    static constexpr uint32_t kWords = PREC == kInt4 ? 1u : PREC == kP16 ? 4u : 2u;  // 16-byte words per lane and block
+    static constexpr uint32_t kPayload = 1024u * kWords;
+    static constexpr bool kMeta = PREC == kInt4 || PREC == kInt8;
+};
+
+// byte K of a dword -> float in one instruction.  Written as asm because the compiler
+// otherwise folds the nibble mask into a bit-field extract per code and then converts byte 0
+// (two instructions per code instead of one).
+template <int K>
+__device__ __forceinline__ float ubyte_f(uint32_t w)
+{
+    float r;
+    if (K == 0) asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(r) : "v"(w));
+    else if (K == 1) asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(r) : "v"(w));
+    else if (K == 2) asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(r) : "v"(w));
+    else asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(r) : "v"(w));
+    return r;
+}
+
+// the same values as dequant_octet4 / dequant_octet8: bf16_rne(fma(code, scale, zero))
+__device__ __forceinline__ u32x4 attend_octet4(uint32_t c, uint32_t m)
+{
+    const float s = h2f(m & 0xFFFFu), z = h2f(m >> 16);
+    const uint32_t ev = c & 0x0F0F0F0Fu, od = (c >> 4) & 0x0F0F0F0Fu;
+    u32x4 r;
+    r.x = pack_bf16(__builtin_fmaf(ubyte_f<0>(ev), s, z), __builtin_fmaf(ubyte_f<0>(od), s, z));
+    r.y = pack_bf16(__builtin_fmaf(ubyte_f<1>(ev), s, z), __builtin_fmaf(ubyte_f<1>(od), s, z));
+    r.z = pack_bf16(__builtin_fmaf(ubyte_f<2>(ev), s, z), __builtin_fmaf(ubyte_f<2>(od), s, z));
+    r.w = pack_bf16(__builtin_fmaf(ubyte_f<3>(ev), s, z), __builtin_fmaf(ubyte_f<3>(od), s, z));
+    return r;
+}
+
+__device__ __forceinline__ u32x4 attend_octet8(uint32_t c0, uint32_t c1, uint32_t m)
+{
+    const float s = h2f(m & 0xFFFFu), z = h2f(m >> 16);
+    u32x4 r;
+    r.x = pack_bf16(__builtin_fmaf(ubyte_f<0>(c0), s, z), __builtin_fmaf(ubyte_f<1>(c0), s, z));
+    r.y = pack_bf16(__builtin_fmaf(ubyte_f<2>(c0), s, z), __builtin_fmaf(ubyte_f<3>(c0), s, z));
+    r.z = pack_bf16(__builtin_fmaf(ubyte_f<0>(c1), s, z), __builtin_fmaf(ubyte_f<1>(c1), s, z));
+    r.w = pack_bf16(__builtin_fmaf(ubyte_f<2>(c1), s, z), __builtin_fmaf(ubyte_f<3>(c1), s, z));
+    return r;
+}
+
+// the raw codes of one octet (x: int4; x, y: 8-bit formats; all four: 16-bit) -> 8 BF16
+template <uint32_t PREC>
+__device__ __forceinline__ u32x4 decode_octet(u32x4 raw, uint32_t meta, int base, int top)
+{
+    if (PREC == kInt4) return attend_octet4(raw.x, meta);
+    if (PREC == kInt8) return attend_octet8(raw.x, raw.y, meta);
+    if (PREC == kE4M3) return decode_octet_fp8<false>(raw.x, raw.y);
+    if (PREC == kE5M2) return decode_octet_fp8<true>(raw.x, raw.y);
+    if (PREC == kGSE8) return decode_octet_gse8(raw.x, raw.y, base, top);
+    return raw;
+}
+
+// plane j of the words a lane loaded from a payload block
+template <uint32_t PREC>
+__device__ __forceinline__ u32x4 plane_raw(const u32x4 *w, int j)
+{
+    u32x4 r = {0u, 0u, 0u, 0u};
+    if (PREC == kInt4) r.x = w[0][j];
+    else if (PREC == kP16) r = w[j];
+    else {
+        r.x = w[j >> 1][(j & 1) * 2];
+        r.y = w[j >> 1][(j & 1) * 2 + 1];
+    }
+    return r;
+}
+
+__device__ __forceinline__ float neg_inf() { return -__builtin_huge_valf(); }
+
+// orders the LDS accesses of one wave: what its lanes wrote before is visible to all its
+// lanes after.  The hardware executes the LDS instructions of a wave in issue order, so
+// nothing has to be waited for; the fences keep the compiler from moving accesses across
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// the launch-wide scalars a workgroup needs, read from the argument buffer once
+struct AttendHdr {
+    uint32_t n_kv_heads, n_q_heads, layer, split_blocks;
+    float scale_log2;
+};
+
+// keeps a value in a scalar register from here on: everything pinned at the top of the kernel
+// is fetched from the argument buffer by loads issued together, not one by one where the
+// values are first used
+__device__ __forceinline__ void pin(uint32_t &v) { asm volatile("" : "+s"(v)); }
+__device__ __forceinline__ void pin(float &v) { asm volatile("" : "+s"(v)); }
+template <class T>
+__device__ __forceinline__ void pin(T *&v)
+{
+    uint64_t a = reinterpret_cast<uint64_t>(v);
+    asm volatile("" : "+s"(a));
+    v = reinterpret_cast<T *>(a);
+}
+
+}  // namespace ha_rag

@@ -19,117 +19,10 @@
 // words go through LDS once (as codes, before decoding) and come back with token and dim
 // roles of the lane index exchanged.  The score tile is computed transposed (tokens x query
 // rows) so that its register layout is already the one P needs as an MFMA operand.
-#include "ha_rag_kernels.h"
-#include "ha_rag_decode.h"
+#include "ha_rag_attend_dev.h"
 
 namespace ha_rag {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-template <uint32_t PREC>
-struct Fmt {
-    static constexpr uint32_t kWords = PREC == kInt4 ? 1u : PREC == kP16 ? 4u : 2u;  // 16-byte words per lane and block
-    static constexpr uint32_t kPayload = 1024u * kWords;
-    static constexpr bool kMeta = PREC == kInt4 || PREC == kInt8;
-};
-
-// byte K of a dword -> float in one instruction.  Written as asm because the compiler
-// otherwise folds the nibble mask into a bit-field extract per code and then converts byte 0
-// (two instructions per code instead of one).
-template <int K>
-__device__ __forceinline__ float ubyte_f(uint32_t w)
-{
-    float r;
-    if (K == 0) asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(r) : "v"(w));
-    else if (K == 1) asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(r) : "v"(w));
-    else if (K == 2) asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(r) : "v"(w));
-    else asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(r) : "v"(w));
-    return r;
-}
-
-// the same values as dequant_octet4 / dequant_octet8: bf16_rne(fma(code, scale, zero))
-__device__ __forceinline__ u32x4 attend_octet4(uint32_t c, uint32_t m)
-{
-    const float s = h2f(m & 0xFFFFu), z = h2f(m >> 16);
-    const uint32_t ev = c & 0x0F0F0F0Fu, od = (c >> 4) & 0x0F0F0F0Fu;
-    u32x4 r;
-    r.x = pack_bf16(__builtin_fmaf(ubyte_f<0>(ev), s, z), __builtin_fmaf(ubyte_f<0>(od), s, z));
-    r.y = pack_bf16(__builtin_fmaf(ubyte_f<1>(ev), s, z), __builtin_fmaf(ubyte_f<1>(od), s, z));
-    r.z = pack_bf16(__builtin_fmaf(ubyte_f<2>(ev), s, z), __builtin_fmaf(ubyte_f<2>(od), s, z));
-    r.w = pack_bf16(__builtin_fmaf(ubyte_f<3>(ev), s, z), __builtin_fmaf(ubyte_f<3>(od), s, z));
-    return r;
-}
-
-__device__ __forceinline__ u32x4 attend_octet8(uint32_t c0, uint32_t c1, uint32_t m)
-{
-    const float s = h2f(m & 0xFFFFu), z = h2f(m >> 16);
-    u32x4 r;
-    r.x = pack_bf16(__builtin_fmaf(ubyte_f<0>(c0), s, z), __builtin_fmaf(ubyte_f<1>(c0), s, z));
-    r.y = pack_bf16(__builtin_fmaf(ubyte_f<2>(c0), s, z), __builtin_fmaf(ubyte_f<3>(c0), s, z));
-    r.z = pack_bf16(__builtin_fmaf(ubyte_f<0>(c1), s, z), __builtin_fmaf(ubyte_f<1>(c1), s, z));
-    r.w = pack_bf16(__builtin_fmaf(ubyte_f<2>(c1), s, z), __builtin_fmaf(ubyte_f<3>(c1), s, z));
-    return r;
-}
-
-// the raw codes of one octet (x: int4; x, y: 8-bit formats; all four: 16-bit) -> 8 BF16
-template <uint32_t PREC>
-__device__ __forceinline__ u32x4 decode_octet(u32x4 raw, uint32_t meta, int base, int top)
-{
-    if (PREC == kInt4) return attend_octet4(raw.x, meta);
-    if (PREC == kInt8) return attend_octet8(raw.x, raw.y, meta);
-    if (PREC == kE4M3) return decode_octet_fp8<false>(raw.x, raw.y);
-    if (PREC == kE5M2) return decode_octet_fp8<true>(raw.x, raw.y);
-    if (PREC == kGSE8) return decode_octet_gse8(raw.x, raw.y, base, top);
-    return raw;
-}
-
-// plane j of the words a lane loaded from a payload block
-template <uint32_t PREC>
-__device__ __forceinline__ u32x4 plane_raw(const u32x4 *w, int j)
-{
-    u32x4 r = {0u, 0u, 0u, 0u};
-    if (PREC == kInt4) r.x = w[0][j];
-    else if (PREC == kP16) r = w[j];
-    else {
-        r.x = w[j >> 1][(j & 1) * 2];
-        r.y = w[j >> 1][(j & 1) * 2 + 1];
-    }
-    return r;
-}
-
-__device__ __forceinline__ float neg_inf() { return -__builtin_huge_valf(); }
-
-// orders the LDS accesses of one wave: what its lanes wrote before is visible to all its
-// lanes after.  The hardware executes the LDS instructions of a wave in issue order, so
-// nothing has to be waited for; the fences keep the compiler from moving accesses across
-__device__ __forceinline__ void wave_lds_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// the launch-wide scalars a workgroup needs, read from the argument buffer once
-struct AttendHdr {
-    uint32_t n_kv_heads, n_q_heads, layer, split_blocks;
-    float scale_log2;
-};
-
-// keeps a value in a scalar register from here on: everything pinned at the top of the kernel
-// is fetched from the argument buffer by loads issued together, not one by one where the
-// values are first used
-__device__ __forceinline__ void pin(uint32_t &v) { asm volatile("" : "+s"(v)); }
-__device__ __forceinline__ void pin(float &v) { asm volatile("" : "+s"(v)); }
-template <class T>
-__device__ __forceinline__ void pin(T *&v)
-{
-    uint64_t a = reinterpret_cast<uint64_t>(v);
-    asm volatile("" : "+s"(a));
-    v = reinterpret_cast<T *>(a);
-}
 
 template <uint32_t KP, uint32_t VP>
 struct BlockRegs {  // what a lane loads for one block
@@ -641,12 +534,91 @@ __global__ void __launch_bounds__(32 * kMergeGroups) k7_attend_merge(const K7Par
         r.lse[o] = l_sum > 0.0f ? (m_max + __builtin_log2f(l_sum)) * 0.69314718055994531f : neg_inf();
 }
 
+// The merge for requests with many query rows: one workgroup per (request, KV head, 16-row
+// query tile), 16 threads a row, 8 dims a thread.  A record is then read as the contiguous
+// 8 KiB it is, by one workgroup, and a request of hundreds of rows needs hundreds of workgroups
+// instead of one for each of its rows.
+__global__ void __launch_bounds__(256) k7_attend_merge_tiles(const K7Params p)
+{
+    typedef const float __attribute__((address_space(1))) *gfloats;
+    typedef const f32x4 __attribute__((address_space(1))) *gquads;
+    K7Req r = p.r[blockIdx.y];
+    uint32_t n_kv_heads = p.n_kv_heads, n_q_heads = p.n_q_heads;
+    pin(r.part);
+    pin(r.out);
+    pin(r.lse);
+    pin(r.n_q);
+    pin(r.n_chunks);
+    pin(r.n_split);
+    pin(n_kv_heads);
+    pin(n_q_heads);
+    const uint32_t G = n_q_heads / n_kv_heads, M = r.n_q * G;
+    const uint32_t n_mt = (M + 15u) >> 4;
+    if (blockIdx.x >= n_kv_heads * n_mt) return;  // the grid is as wide as the largest request
+    const uint32_t h = blockIdx.x / n_mt, mt = blockIdx.x - h * n_mt;
+    const uint32_t ri = threadIdx.x >> 4, d8 = threadIdx.x & 15u;
+    const uint32_t mrow = mt * 16u + ri;
+    if (mrow >= M) return;  // rows without a query are not in the records either
+    const uint64_t split_stride = (uint64_t)n_mt * kAttendRecFloats;
+    const uint64_t chunk_stride = (uint64_t)n_kv_heads * r.n_split * split_stride;
+    gfloats first = (gfloats)r.part + ((uint64_t)(h * r.n_split) * n_mt + mt) * kAttendRecFloats;
+    const uint32_t n_units = r.n_chunks * r.n_split;  // records are [run][head][split][tile]
+    float m_max = neg_inf(), l_sum = 0.0f;
+    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+    for (uint32_t u0 = 0; u0 < n_units; u0 += 4u) {
+        float m[4], l[4];
+        f32x4 o[4][2];
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) {  // four records under way at a time
+            const bool have = u0 + k < n_units;
+            const uint32_t u = have ? u0 + k : n_units - 1u;
+            const uint32_t ci = u / r.n_split, sp = u - ci * r.n_split;
+            gfloats rec = first + ci * chunk_stride + sp * split_stride;
+            m[k] = rec[2048 + ri];
+            l[k] = have ? rec[2048 + 16 + ri] : 0.0f;
+            o[k][0] = ((gquads)(rec + ri * 128u + 8u * d8))[0];
+            o[k][1] = ((gquads)(rec + ri * 128u + 8u * d8))[1];
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) {
+            if (l[k] > 0.0f) {  // an empty record holds no output rows
+                const float m_new = __builtin_fmaxf(m_max, m[k]);
+                const float fa = __builtin_amdgcn_exp2f(m_max - m_new);  // 0 at the first record
+                const float fb = __builtin_amdgcn_exp2f(m[k] - m_new);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc[0][e] = __builtin_fmaf(o[k][0][e], fb, acc[0][e] * fa);
+                    acc[1][e] = __builtin_fmaf(o[k][1][e], fb, acc[1][e] * fa);
+                }
+                l_sum = __builtin_fmaf(l[k], fb, l_sum * fa);
+                m_max = m_new;
+            }
+        }
+    }
+    const uint32_t qt = mrow / G, gq = mrow - qt * G;
+    const uint64_t orow = (uint64_t)qt * n_q_heads + h * G + gq;
+    f32x4 __attribute__((address_space(1))) *dst =
+        (f32x4 __attribute__((address_space(1))) *)((float __attribute__((address_space(1))) *)r.out + orow * 128u + 8u * d8);
+    f32x4 w0, w1;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        w0[e] = l_sum > 0.0f ? acc[0][e] / l_sum : 0.0f;
+        w1[e] = l_sum > 0.0f ? acc[1][e] / l_sum : 0.0f;
+    }
+    dst[0] = w0;
+    dst[1] = w1;
+    if (d8 == 0 && r.lse)
+        r.lse[orow] = l_sum > 0.0f ? (m_max + __builtin_log2f(l_sum)) * 0.69314718055994531f : neg_inf();
+}
+
 hipError_t launch_k7(K7Params &p, hipStream_t stream)
 {
     if (p.n_reqs == 0) return hipSuccess;
     if (p.n_reqs > kMaxMergeReqs || p.n_kv_heads == 0 || p.n_q_heads % p.n_kv_heads)
         return hipErrorInvalidValue;
-    uint64_t width = 0, max_units = 0;
+    uint64_t width = 0, max_units = 0, tile_width = 0;
+    const uint32_t G = p.n_q_heads / p.n_kv_heads;
+    uint32_t max_mt = 0;
     for (uint32_t i = 0; i < p.n_reqs; ++i) {
         const K7Req &r = p.r[i];
         // a request without a token to attend to (n_chunks 0) gets zeros and lse = -inf
@@ -654,11 +626,18 @@ hipError_t launch_k7(K7Params &p, hipStream_t stream)
             return hipErrorInvalidValue;
         const uint64_t rows = (uint64_t)r.n_q * p.n_q_heads;
         if (rows > width) width = rows;
+        const uint64_t n_mt = ((uint64_t)r.n_q * G + 15u) >> 4;
+        if (n_mt > max_mt) max_mt = (uint32_t)(n_mt > 0xFFFFFFFFull ? 0xFFFFFFFFull : n_mt);
+        if (n_mt * p.n_kv_heads > tile_width) tile_width = n_mt * p.n_kv_heads;
         const uint64_t units = (uint64_t)r.n_chunks * r.n_split;
         if (units > 0xFFFFFFFFull) return hipErrorInvalidValue;
         if (units > max_units) max_units = units;
     }
     if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    if (max_mt > 2u) {  // the requests of the shared kernel: merge tile by tile
+        hipLaunchKernelGGL(k7_attend_merge_tiles, dim3((uint32_t)tile_width, p.n_reqs), dim3(256), 0, stream, p);
+        return hipGetLastError();
+    }
     // one group per two records of the longest row if that fits (a group fetches four at a
     // time), in whole waves, at least the 128 threads that write the row
     const uint64_t want = (max_units + 1u) / 2u;

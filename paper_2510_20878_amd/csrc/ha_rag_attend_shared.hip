@@ -1,0 +1,438 @@
+// gfx950 kernel for attention over packed chunks when a request has more query rows than one
+// wave can keep (more than two 16-row tiles: the question's prefill of Sec. 2.1, tens of query
+// tokens times the query heads of a KV head).
+//
+//  k6_attend_shared<W>   one workgroup of W waves per (run of documents, KV head, token split,
+//      group of 2 W query tiles).  Every wave owns two query tiles for the whole run: their
+//      queries, running maxima, sums and output rows stay in its registers.  The layout blocks
+//      are taken W at a time: wave w decodes block w of the round to BF16 (the values a load
+//      would write) and leaves it in LDS in the form the MFMAs take their operands in; after one
+//      barrier every wave scores all W blocks against its own tiles.  A block is therefore
+//      fetched and decoded once per 32 W query rows.  The rounds alternate between two sets of
+//      LDS buffers, so one barrier per round is enough: a wave that writes round r + 1 has
+//      passed barrier r, which every wave reaches only after it has read all of round r - 1.
+//
+// Block geometry as for k6_attend_partial: lane (c = lane / 16, n = lane % 16) of the wave that
+// reads a block holds, in plane j, token 4 j + c, dims 8 n .. 8 n + 7.
+//   V: that is what the product P V takes from a lane, so the decoding wave stores its eight
+//      operand words lane by lane and every wave reads them back lane by lane.
+//   K: the score MFMA wants, per lane, 8 dims of the token of its column; the decoding wave
+//      stores octet o of token t at 16-byte slot (o ^ t) of row t (256 bytes a row), which
+//      both its own stores and the readers' loads reach without bank conflicts.
+#include "ha_rag_attend_dev.h"
+
+namespace ha_rag {
+
+namespace {
+
+// Everything the kernel reads or writes outside LDS lies in global memory; saying so lets the
+// loads run as global instructions (scalar base, 32-bit lane offset), which do not count
+// against the LDS counter the way loads through generic pointers do.
+typedef const uint8_t __attribute__((address_space(1))) *gbytes;
+typedef float __attribute__((address_space(1))) *gfloats;
+
+__device__ __forceinline__ u32x4 ldg16(gbytes p)
+{
+    return *(const u32x4 __attribute__((address_space(1))) *)p;
+}
+
+constexpr uint32_t kSharedBlockLds = 8192;  // K operands 4 KiB, then V operands 4 KiB
+
+struct SharedState {  // a wave's two query tiles
+    bf16x8 qb[2][4];
+    float m_run[2], l_run[2];
+    f32x4 O[2][8];
+};
+
+struct SharedSide {  // the keys or the values of one document's (layer, head) tile (uniform values)
+    gbytes tile, meta;
+    uint32_t meta_blk, gsh;
+    int base, top;
+};
+
+struct SharedLane {
+    uint32_t lane, c_, n_;  // MFMA coordinates: lane group, lane column
+    uint32_t k_rd;          // where the lane reads its K operand 0 inside a block's buffer; operand y: ^ 16 y
+    uint32_t k_wr;          // where it writes the keys of its plane 0; plane j: (^ 64 j) + 1024 j
+};
+
+// a fresh copy of a lane constant: what is derived from it is computed where it is used and
+// does not occupy registers across the whole loop
+__device__ __forceinline__ uint32_t fresh(uint32_t v)
+{
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
+// max of a value over the four lanes l, l ^ 16, l ^ 32, l ^ 48 (one per lane group), in every
+// lane.  The row swaps exchange registers between lane rows without a trip through LDS: after
+// swapping the odd rows of one copy with the even rows of another, the two copies hold the
+// value of rows r and r ^ 1 side by side; the same with halves of 32 lanes.
+__device__ __forceinline__ float max_over_lane_groups(float x)
+{
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    const unsigned xi = __builtin_bit_cast(unsigned, x);
+    const u2 r = __builtin_amdgcn_permlane16_swap(xi, xi, false, false);
+    const unsigned r0 = r.x, r1 = r.y;  // copied out first: a bit cast of a vector element reads element 0
+    const float y = __builtin_fmaxf(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
+    const unsigned yi = __builtin_bit_cast(unsigned, y);
+    const u2 t = __builtin_amdgcn_permlane32_swap(yi, yi, false, false);
+    const unsigned t0 = t.x, t1 = t.y;
+    return __builtin_fmaxf(__builtin_bit_cast(float, t0), __builtin_bit_cast(float, t1));
+}
+
+// One block against the wave's two tiles: S^T = K Q^T, running softmax, O += P V.
+__device__ __forceinline__ void shared_score(const uint8_t *src, uint32_t b, uint32_t T, float scale_log2,
+                                             const SharedLane &ln, SharedState &st)
+{
+    const uint32_t c_ = ln.c_;
+    const bool ragged = b * 16u + 16u > T;  // only the document's last block can be
+    const uint32_t k_rd = fresh(ln.k_rd), v_rd = fresh(ln.lane) * 16u;
+    bf16x8 ka[4];
+#pragma unroll
+    for (uint32_t y = 0; y < 4; ++y)
+        ka[y] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(src + (k_rd ^ (16u * y))));
+    u32x4 vq[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) vq[q] = *reinterpret_cast<const u32x4 *>(src + 4096u + q * 1024u + v_rd);
+    // both tiles side by side, so that their MFMA chains and reductions overlap
+    f32x4 S[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) S[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int y = 0; y < 4; ++y)
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+            S[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[y], st.qb[mt][y], S[mt], 0, 0, 0);
+    // S[mt][jj] = score of token 4 jj + c_ of the block against query row n_ of tile mt
+    float sc[2][4], m_new[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) sc[mt][jj] = S[mt][jj] * scale_log2;
+        if (ragged) {
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                if (b * 16u + 4u * jj + c_ >= T) sc[mt][jj] = neg_inf();
+        }
+        const float mx = __builtin_fmaxf(__builtin_fmaxf(sc[mt][0], sc[mt][1]), __builtin_fmaxf(sc[mt][2], sc[mt][3]));
+        m_new[mt] = __builtin_fmaxf(st.m_run[mt], max_over_lane_groups(mx));
+    }
+    if (__any(m_new[0] > st.m_run[0] || m_new[1] > st.m_run[1])) {
+        // rare after the first blocks: rescale what is accumulated (a tile whose maximum stays
+        // is multiplied by exactly 1)
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            const float alpha = __builtin_amdgcn_exp2f(st.m_run[mt] - m_new[mt]);  // 0 at the first block
+            st.l_run[mt] *= alpha;
+            st.m_run[mt] = m_new[mt];
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const float ar = __shfl(alpha, (int)(4u * c_ + jj));  // factor of output row 4 c_ + jj
+#pragma unroll
+                for (int pp = 0; pp < 8; ++pp) st.O[mt][pp][jj] *= ar;
+            }
+        }
+    }
+    s16x4 pa[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        float pr[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) pr[jj] = __builtin_amdgcn_exp2f(sc[mt][jj] - st.m_run[mt]);
+        st.l_run[mt] += (pr[0] + pr[1]) + (pr[2] + pr[3]);
+        const u32x2 pk = {pack_bf16(pr[0], pr[1]), pack_bf16(pr[2], pr[3])};
+        pa[mt] = __builtin_bit_cast(s16x4, pk);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const s16x4 v0 = __builtin_bit_cast(s16x4, u32x2{vq[q].x, vq[q].y});
+        const s16x4 v1 = __builtin_bit_cast(s16x4, u32x2{vq[q].z, vq[q].w});
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            st.O[mt][2 * q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa[mt], v0, st.O[mt][2 * q], 0, 0, 0);
+            st.O[mt][2 * q + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa[mt], v1, st.O[mt][2 * q + 1], 0, 0, 0);
+        }
+    }
+}
+
+// The rounds of one document for a wave that decodes one side (IS_K: the keys) of format P:
+// decoder number r of its side takes blocks 2 r and 2 r + 1 of every round of W blocks.
+template <uint32_t P, bool IS_K, int W>
+__device__ __forceinline__ void shared_rounds(const SharedSide &sd, uint32_t T, uint32_t b0, uint32_t b1,
+                                              float scale_log2, uint32_t r, bool active, const SharedLane &ln,
+                                              uint8_t (*lds)[W][kSharedBlockLds], uint32_t &set, SharedState &st)
+{
+    typedef Fmt<P> F;
+    const uint32_t lane = ln.lane, c_ = ln.c_;
+    u32x4 w[2][F::kWords], m[2];
+    m[0] = m[1] = u32x4{0u, 0u, 0u, 0u};
+    // the block is clamped to the split's last one instead of skipping the loads: no branch
+    // around them, so nothing waits for them before they are needed
+    auto fetch = [&](int e, uint32_t b) {
+        b = b < b1 ? b : b1 - 1u;
+#pragma unroll
+        for (uint32_t a = 0; a < F::kWords; ++a)
+            w[e][a] = ldg16(sd.tile + ((uint64_t)b * F::kPayload + a * 1024u + lane * 16u));
+        if (F::kMeta) m[e] = ldg16(sd.meta + ((uint64_t)b * sd.meta_blk + ((lane * 8u) >> sd.gsh) * 16u));
+    };
+    fetch(0, b0 + 2u * r);
+    fetch(1, b0 + 2u * r + 1u);
+    for (uint32_t rb = b0; rb < b1; rb += W) {  // a round: blocks rb .. rb + W - 1
+        // ---- this wave's two blocks of the round: decode into the round's buffers
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const uint32_t blk = rb + 2u * r + e;
+            if (blk >= b1) continue;
+            uint8_t *dst = lds[set][2u * r + e];
+            u32x4 o[4];  // o[j] = token 4 j + c_, dims 8 n_ .. 8 n_ + 7 as BF16
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[j] = decode_octet<P>(plane_raw<P>(w[e], j), m[e][j], sd.base, sd.top);
+            if (IS_K) {
+                // token t = 4 j + c_, octet n_: slot (n_ ^ t) of row t
+                const uint32_t k_wr = fresh(ln.k_wr);
+#pragma unroll
+                for (uint32_t j = 0; j < 4; ++j)
+                    *reinterpret_cast<u32x4 *>(dst + ((k_wr ^ (64u * j)) + 1024u * j)) = o[j];
+            } else {
+                if (blk * 16u + 16u > T) {  // rows past the document's end
+#pragma unroll
+                    for (uint32_t j = 0; j < 4; ++j)
+                        if (blk * 16u + 4u * j + c_ >= T) o[j] = u32x4{0u, 0u, 0u, 0u};
+                }
+                // operand pp of P V: value pp of the octet of each of the lane's four tokens
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    u32x4 t;
+                    t.x = __builtin_amdgcn_perm(o[1][q], o[0][q], 0x05040100u);
+                    t.y = __builtin_amdgcn_perm(o[3][q], o[2][q], 0x05040100u);
+                    t.z = __builtin_amdgcn_perm(o[1][q], o[0][q], 0x07060302u);
+                    t.w = __builtin_amdgcn_perm(o[3][q], o[2][q], 0x07060302u);
+                    *reinterpret_cast<u32x4 *>(dst + 4096u + q * 1024u + fresh(lane) * 16u) = t;
+                }
+            }
+        }
+        __syncthreads();
+        // the wave's blocks of the next round: in flight while this round is scored.  Issued
+        // after the barrier, which waits for every memory access of the wave still under way
+        fetch(0, rb + W + 2u * r);
+        fetch(1, rb + W + 2u * r + 1u);
+
+        // ---- every wave: its two tiles against the round's blocks
+        if (active) {
+            const uint32_t nb = b1 - rb;
+#pragma unroll 1
+            for (uint32_t i = 0; i < (uint32_t)W; ++i)
+                if (i < nb) shared_score(lds[set][i], rb + i, T, scale_log2, ln, st);
+        }
+        set ^= 1u;
+    }
+}
+
+template <bool IS_K, int W>
+__device__ __forceinline__ void shared_rounds_any(uint32_t prec, const SharedSide &sd, uint32_t T, uint32_t b0,
+                                                  uint32_t b1, float scale_log2, uint32_t r, bool active,
+                                                  const SharedLane &ln, uint8_t (*lds)[W][kSharedBlockLds],
+                                                  uint32_t &set, SharedState &st)
+{
+    switch (prec) {
+    case kP16: shared_rounds<kP16, IS_K, W>(sd, T, b0, b1, scale_log2, r, active, ln, lds, set, st); break;
+    case kInt8: shared_rounds<kInt8, IS_K, W>(sd, T, b0, b1, scale_log2, r, active, ln, lds, set, st); break;
+    case kInt4: shared_rounds<kInt4, IS_K, W>(sd, T, b0, b1, scale_log2, r, active, ln, lds, set, st); break;
+    case kE4M3: shared_rounds<kE4M3, IS_K, W>(sd, T, b0, b1, scale_log2, r, active, ln, lds, set, st); break;
+    case kE5M2: shared_rounds<kE5M2, IS_K, W>(sd, T, b0, b1, scale_log2, r, active, ln, lds, set, st); break;
+    default: shared_rounds<kGSE8, IS_K, W>(sd, T, b0, b1, scale_log2, r, active, ln, lds, set, st); break;
+    }
+}
+
+__device__ __forceinline__ SharedSide shared_side(const uint8_t *first, uint32_t prec, uint32_t gsh, uint32_t h,
+                                                  uint32_t nblk, bool wanted)
+{
+    SharedSide sd;
+    const bool has_meta = prec == kInt4 || prec == kInt8;
+    const uint32_t pay = prec == kInt4 ? 1024u : prec == kP16 ? 4096u : 2048u;
+    sd.gsh = gsh;
+    sd.meta_blk = has_meta ? 8192u >> gsh : 0u;
+    // `first` points at the layer's tile of head 0; the heads' tile records follow one another
+    sd.tile = (gbytes)first + (uint64_t)h * ((uint64_t)nblk * (pay + sd.meta_blk) + (prec == kGSE8 ? 16u : 0u));
+    sd.meta = sd.tile + (uint64_t)nblk * pay;
+    sd.base = sd.top = 0;
+    if (wanted && prec == kGSE8) {  // the tile's exponent range follows its payload
+        const uint32_t rg = *(const uint32_t __attribute__((address_space(1))) *)(sd.tile + (uint64_t)nblk * 2048u);
+        sd.base = (int)(int8_t)(rg & 0xFFu);
+        sd.top = (int)(int8_t)((rg >> 8) & 0xFFu) - 2;
+    }
+    return sd;
+}
+
+}  // namespace
+
+// W waves, half of them decoding keys and half values; two waves per SIMD keep 256 registers
+// each (two tiles of output, their queries, the raw words of two blocks).
+template <int W>
+__global__ void __launch_bounds__(64 * W, 2) k6_attend_shared(const K6Params p)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2][W][kSharedBlockLds];
+    K6Chunk c = p.c[blockIdx.y];
+    AttendHdr hdr = {p.n_kv_heads, p.n_q_heads, p.layer, p.split_blocks, p.scale_log2};
+    pin(c.k);
+    pin(c.v);
+    pin(c.q);
+    pin(c.part);
+    pin(c.n_tokens);
+    pin(c.info);
+    pin(c.n_q);
+    pin(c.n_split);
+    pin(hdr.n_kv_heads);
+    pin(hdr.n_q_heads);
+    pin(hdr.split_blocks);
+    pin(hdr.scale_log2);
+    uint32_t run = c.run, more = c.more;  // the run's documents: this one, then descriptors more, more + 1, ..
+    pin(run);
+    pin(more);
+    const uint32_t H = hdr.n_kv_heads, G = hdr.n_q_heads / H, M = c.n_q * G;
+    const uint32_t n_mt = (M + 15u) >> 4;
+    const uint32_t n_mtg = (n_mt + 2u * W - 1u) / (2u * W);
+    const uint32_t u = blockIdx.x;
+    if (u >= H * c.n_split * n_mtg) return;  // the grid is as wide as the widest run
+    const uint32_t mtg = u % n_mtg, hs = u / n_mtg;
+    const uint32_t s = hs % c.n_split, h = hs / c.n_split;
+
+    SharedLane ln;
+    ln.lane = threadIdx.x & 63u;
+    ln.c_ = ln.lane >> 4;
+    ln.n_ = ln.lane & 15u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t tile0 = (mtg * W + wave) * 2u;  // this wave's tiles: tile0, tile0 + 1
+    const bool active = tile0 < n_mt;              // a wave without a tile still decodes
+    const bool is_k = wave < (uint32_t)W / 2u;
+    const uint32_t r = is_k ? wave : wave - (uint32_t)W / 2u;
+    // where this lane reads its K operands: the token of MFMA row n_ is 4 (n_ % 4) + n_ / 4, so
+    // that score register jj of lane group c_ belongs to token 4 jj + c_, the token whose values
+    // the lane group's plane jj holds
+    {
+        const uint32_t tau = 4u * (ln.n_ & 3u) + (ln.n_ >> 2);
+        ln.k_rd = tau * 256u + (((4u * ln.c_) ^ tau) & 15u) * 16u;  // octet 4 c_ + y of token tau: slot (4 c_ ^ tau) ^ y
+        ln.k_wr = ln.c_ * 256u + ((ln.n_ ^ ln.c_) & 15u) * 16u;     // n_ ^ (4 j + c_) = (n_ ^ c_) ^ 4 j
+    }
+
+    // Q as the B operand of S^T = K Q^T: lane (c_, n_) holds, for MFMA y, dims
+    // 32 c_ + 8 y .. + 7 of query row n_ of the tile (zero rows beyond M)
+    SharedState st;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        const uint32_t row = (tile0 + mt) * 16u + ln.n_;
+        u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int y = 0; y < 4; ++y) st.qb[mt][y] = __builtin_bit_cast(bf16x8, z);
+        if (row < M) {
+            const uint32_t qt = row / G, gq = row - qt * G;
+            gbytes qp = (gbytes)c.q + ((uint64_t)(qt * hdr.n_q_heads + h * G + gq) * 128u + 32u * ln.c_) * 2u;
+#pragma unroll
+            for (int y = 0; y < 4; ++y) st.qb[mt][y] = __builtin_bit_cast(bf16x8, ldg16(qp + 16 * y));
+        }
+        st.m_run[mt] = neg_inf();
+        st.l_run[mt] = 0.0f;
+#pragma unroll
+        for (int pp = 0; pp < 8; ++pp) st.O[mt][pp] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    uint32_t set = 0;
+    for (uint32_t d = 0; d < run; ++d) {
+        // ---- the document: descriptor d of the run (its first is already here)
+        const uint8_t *dk = c.k, *dv = c.v;
+        uint32_t T = c.n_tokens, dinfo = c.info;
+        if (d) {
+            const K6Chunk &cd = p.c[more + d - 1u];
+            dk = cd.k;
+            dv = cd.v;
+            T = cd.n_tokens;
+            dinfo = cd.info;
+        }
+        const uint32_t nblk = (T + 15u) >> 4;
+        const uint32_t b0 = s * hdr.split_blocks;
+        const uint32_t b1 = b0 + hdr.split_blocks < nblk ? b0 + hdr.split_blocks : nblk;
+        if (b0 >= b1) continue;  // nothing of this document in this split
+        if (is_k) {
+            const uint32_t prec = dinfo & 0xFu;
+            const SharedSide sd = shared_side(dk, prec, (dinfo >> 4) & 0xFu, h, nblk, true);
+            shared_rounds_any<true, W>(prec, sd, T, b0, b1, hdr.scale_log2, r, active, ln, lds, set, st);
+        } else {
+            const uint32_t prec = (dinfo >> 8) & 0xFu;
+            const SharedSide sd = shared_side(dv, prec, (dinfo >> 12) & 0xFu, h, nblk, true);
+            shared_rounds_any<false, W>(prec, sd, T, b0, b1, hdr.scale_log2, r, active, ln, lds, set, st);
+        }
+    }
+
+    // ---- the wave's records, straight from its registers: lane (c_, n_) holds rows
+    // 4 c_ + jj, dims 8 n_ + pp of each tile
+    if (!active) return;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        const uint32_t tile = tile0 + mt;
+        if (tile >= n_mt) continue;
+        float l_tot = st.l_run[mt];
+        l_tot += __shfl_xor(l_tot, 16);
+        l_tot += __shfl_xor(l_tot, 32);
+        gfloats rec = (gfloats)c.part + ((uint64_t)(h * c.n_split + s) * n_mt + tile) * kAttendRecFloats;
+#pragma unroll
+        for (uint32_t jj = 0; jj < 4; ++jj) {
+            const uint32_t row = 4u * ln.c_ + jj;
+            if (tile * 16u + row >= M) continue;  // no query in this row: the merge never reads it
+            f32x4 __attribute__((address_space(1))) *dst =
+                (f32x4 __attribute__((address_space(1))) *)(rec + row * 128u + 8u * ln.n_);
+            dst[0] = f32x4{st.O[mt][0][jj], st.O[mt][1][jj], st.O[mt][2][jj], st.O[mt][3][jj]};
+            dst[1] = f32x4{st.O[mt][4][jj], st.O[mt][5][jj], st.O[mt][6][jj], st.O[mt][7][jj]};
+        }
+        if (ln.c_ == 0) {
+            rec[2048 + ln.n_] = st.m_run[mt];
+            rec[2048 + 16 + ln.n_] = l_tot;
+        }
+    }
+}
+
+hipError_t launch_k6_shared(K6Params &p, uint32_t n_runs, uint32_t waves, hipStream_t stream)
+{
+    if (p.n_chunks == 0) return hipSuccess;
+    if (p.n_chunks > kAttendLaunchChunks || n_runs == 0 || n_runs > p.n_chunks || p.n_kv_heads == 0 ||
+        p.n_q_heads % p.n_kv_heads || p.split_blocks < kAttendMinSplitBlocks ||
+        p.split_blocks > kAttendMaxSplitBlocks || (p.split_blocks & (p.split_blocks - 1u)) ||
+        (waves != 2u && waves != 4u))
+        return hipErrorInvalidValue;
+    const uint32_t G = p.n_q_heads / p.n_kv_heads;
+    uint64_t width = 0, followers = 0;
+    for (uint32_t i = 0; i < p.n_chunks; ++i) {
+        const K6Chunk &c = p.c[i];
+        const uint32_t kprec = c.info & 0xFu, kgsh = (c.info >> 4) & 0xFu;
+        const uint32_t vprec = (c.info >> 8) & 0xFu, vgsh = (c.info >> 12) & 0xFu;
+        if (c.info >> 16 || kprec > kGSE8 || vprec > kGSE8 || !c.k || !c.v || ((uintptr_t)c.k & 15u) ||
+            ((uintptr_t)c.v & 15u) || c.n_tokens > 0x7FFFFFFu)
+            return hipErrorInvalidValue;
+        if ((kprec == kInt4 || kprec == kInt8) && (kgsh < 5 || kgsh > 7)) return hipErrorInvalidValue;
+        if ((vprec == kInt4 || vprec == kInt8) && (vgsh < 5 || vgsh > 7)) return hipErrorInvalidValue;
+        if (i >= n_runs) continue;  // a run's later document: read by the workgroups of its first
+        if (c.run == 0 || !c.q || !c.part || c.n_q == 0 || c.n_split == 0 || ((uintptr_t)c.q & 15u) ||
+            ((uintptr_t)c.part & 15u) || (uint64_t)c.n_q * G > 0xFFFFFFull)
+            return hipErrorInvalidValue;
+        if (c.run > 1u && (c.more < n_runs || c.more > p.n_chunks || c.run - 1u > p.n_chunks - c.more))
+            return hipErrorInvalidValue;
+        // every block of every document of the run must belong to one of the request's splits
+        for (uint32_t d = 0; d < c.run; ++d) {
+            const K6Chunk &cd = d ? p.c[c.more + d - 1u] : c;
+            if ((uint64_t)c.n_split * p.split_blocks * 16u < cd.n_tokens) return hipErrorInvalidValue;
+        }
+        followers += c.run - 1u;
+        const uint32_t n_mt = (c.n_q * G + 15u) >> 4;
+        const uint64_t w = (uint64_t)p.n_kv_heads * c.n_split * ((n_mt + 2u * waves - 1u) / (2u * waves));
+        if (w > width) width = w;
+    }
+    if (followers != p.n_chunks - n_runs || width > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    p.mtw = 2;
+    p.pad = 0;
+    dim3 grid((uint32_t)width, n_runs);
+    if (waves == 2u) hipLaunchKernelGGL((k6_attend_shared<2>), grid, dim3(128), 0, stream, p);
+    else hipLaunchKernelGGL((k6_attend_shared<4>), grid, dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace ha_rag

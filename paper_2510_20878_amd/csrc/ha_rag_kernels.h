@@ -112,7 +112,7 @@ constexpr uint32_t kAttendMinSplitBlocks = 8;   // a workgroup takes split_block
 constexpr uint32_t kAttendMaxSplitBlocks = 128; // tokens each) of one chunk: a power of two in this range
 constexpr uint32_t kAttendTargetGroups = 2048;  // the host splits finer while a launch has fewer workgroups
 constexpr uint32_t kAttendWaves = 2;          // waves of a workgroup; they interleave its blocks
-// Descriptors travel in the kernel argument buffer (about 20 KiB when full; launches with
+// Descriptors travel in the kernel argument buffer (about 23 KiB when full; launches with
 // arguments of 32 KiB were checked to work on this runtime).  A workgroup needs exactly one
 // descriptor, which it fetches in one go: the argument buffer may live in host memory, where
 // every dependent read costs a trip over the link.
@@ -129,6 +129,9 @@ struct K6Chunk {
     uint32_t info;        // keys: Prec | log2(group) << 4; values: the same << 8
     uint32_t n_q;         // query tokens of the request
     uint32_t n_split;     // token splits of the request (the same for all its chunks)
+    uint32_t run;         // launch_k6_shared: documents of the run this descriptor starts (1 = itself only)
+    uint32_t more;        // launch_k6_shared: index of the descriptor of the run's second document;
+                          // the third and later ones follow it
 };
 
 struct K6Params {
@@ -141,7 +144,7 @@ struct K6Params {
 };
 
 struct K7Req {
-    const float *part;    // records [n_chunks][n_kv_heads][n_split][n_mtiles]
+    const float *part;    // records [n_chunks][n_kv_heads][n_split][n_mtiles]; n_chunks counts runs
     float *out;           // binary32 [n_q][n_q_heads][128]
     float *lse;           // binary32 [n_q][n_q_heads] or null
     uint32_t n_q, n_chunks, n_split, pad;
@@ -155,6 +158,13 @@ struct K7Params {
 
 // Partial attention of every chunk of the launch (sets mtw).
 hipError_t launch_k6(K6Params &p, hipStream_t stream);
+// The same for requests with more than two query tiles: the `waves` (2 or 4) waves of a
+// workgroup share every decoded block, each wave with two tiles of its own.  A workgroup takes
+// a run of documents of one request: descriptors 0 .. n_runs - 1 are the runs' first documents
+// (request, records in `part`, `run`, `more`), the runs' other documents come after them
+// (k, v, n_tokens, info only).  The grid has no row without work: rows of workgroups that
+// exit at once, in a regular pattern, were measured to halve the workgroups a CU runs side by side.
+hipError_t launch_k6_shared(K6Params &p, uint32_t n_runs, uint32_t waves, hipStream_t stream);
 // Merges the partial results of each request into out and lse.
 hipError_t launch_k7(K7Params &p, hipStream_t stream);
 

@@ -165,6 +165,30 @@ def test_more_chunks_and_requests_than_one_launch_holds():
     run_case((1, 1, 128), reqs, 0, 2, 0.1, 60)
 
 
+def test_runs_of_documents_per_workgroup_across_launches_of_the_many_rows_kernel():
+    """Requests with more than two query tiles go to the kernel whose waves share each decoded
+    block.  With workgroups to spare (here 2 x 270 documents x 8 heads x 2 tile groups = 8640,
+    four times the target) a workgroup takes a run of consecutive documents (4 here, the last
+    run of a request shorter) and writes one record per run; 540 documents also need two
+    launches, and no run straddles them.  Formats change inside a run and documents end
+    ragged."""
+    n_docs = 270
+    reqs = [([3 + (7 * i + 5 * r) % 41 for i in range(n_docs)], [ALL[(i * 5 + r) % 6] for i in range(n_docs)],
+             40 - 7 * r) for r in range(2)]
+    run_case((1, 8, 128), reqs, 0, 32, 0.1, 90)
+
+
+def test_one_call_with_requests_for_both_attention_kernels():
+    """One query token next to 24 and 70 of them: the first request takes the kernel of at most
+    two query tiles, the others the many-rows kernel (3 and 9 tiles, so one workgroup of four
+    waves has idle waves for the former); one merge launch serves all of them."""
+    reqs = [([50, 33], [B.PREC_INT4, B.PREC_16], 1),
+            ([70, 16, 129], [B.PREC_INT8, B.PREC_GSE8, B.PREC_INT4], 24),
+            ([300, 45], [B.PREC_FP8_E4M3, B.PREC_16], 70),
+            ([20], [B.PREC_FP8_E5M2], 2)]
+    run_case((2, 2, 128), reqs, 1, 4, 0.09, 95)
+
+
 def test_llama3_8b_request_sampled_heads_match_oracle():
     """One request of the headline workload (32 layers, 8 KV heads, head_dim 128, ten
     512-token chunks: 2 x 16-bit, 3 x int8, 5 x int4, group 128; 32 query heads, one and
