@@ -57,11 +57,11 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c
     const uint32_t kgsh = (c.info >> 4) & 0xFu, vgsh = (c.info >> 12) & 0xFu;
     const uint32_t kmeta_blk = FK::kMeta ? 8192u >> kgsh : 0u, vmeta_blk = FV::kMeta ? 8192u >> vgsh : 0u;
     // c.k / c.v point at the layer's tile of head 0; the heads' tile records follow one another
-    const uint8_t *kt = c.k + (uint64_t)h * ((uint64_t)nblk * (FK::kPayload + kmeta_blk) + (KP == kGSE8 ? 16u : 0u));
-    const uint8_t *vt = c.v + (uint64_t)h * ((uint64_t)nblk * (FV::kPayload + vmeta_blk) + (VP == kGSE8 ? 16u : 0u));
-    const uint8_t *kmeta = kt + (uint64_t)nblk * FK::kPayload;
-    const uint8_t *vmeta = vt + (uint64_t)nblk * FV::kPayload;
-    float *rec0 = c.part + (uint64_t)((h * c.n_split + s) * n_mt) * kAttendRecFloats;
+    gbytes kt = (gbytes)c.k + (uint64_t)h * ((uint64_t)nblk * (FK::kPayload + kmeta_blk) + (KP == kGSE8 ? 16u : 0u));
+    gbytes vt = (gbytes)c.v + (uint64_t)h * ((uint64_t)nblk * (FV::kPayload + vmeta_blk) + (VP == kGSE8 ? 16u : 0u));
+    gbytes kmeta = kt + (uint64_t)nblk * FK::kPayload;
+    gbytes vmeta = vt + (uint64_t)nblk * FV::kPayload;
+    gfloats rec0 = (gfloats)c.part + (uint64_t)((h * c.n_split + s) * n_mt) * kAttendRecFloats;
 
     const uint32_t b0 = s * p.split_blocks;
     const uint32_t b1 = b0 + p.split_blocks < nblk ? b0 + p.split_blocks : nblk;
@@ -69,7 +69,7 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c
         if (threadIdx.x < MTW * 16u) {
             const uint32_t mtile = mtg * MTW + (threadIdx.x >> 4);
             if (mtile < n_mt) {
-                float *rec = rec0 + (uint64_t)mtile * kAttendRecFloats;
+                gfloats rec = rec0 + (uint64_t)mtile * kAttendRecFloats;
                 rec[2048 + n_] = neg_inf();
                 rec[2048 + 16 + n_] = 0.0f;
             }
@@ -79,12 +79,12 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c
 
     int kbase = 0, ktop = 0, vbase = 0, vtop = 0;
     if (KP == kGSE8) {
-        const uint32_t kr = *reinterpret_cast<const uint32_t *>(kt + (uint64_t)nblk * 2048u);
+        const uint32_t kr = *(const uint32_t __attribute__((address_space(1))) *)(kt + (uint64_t)nblk * 2048u);
         kbase = (int)(int8_t)(kr & 0xFFu);
         ktop = (int)(int8_t)((kr >> 8) & 0xFFu) - 2;
     }
     if (VP == kGSE8) {
-        const uint32_t vr = *reinterpret_cast<const uint32_t *>(vt + (uint64_t)nblk * 2048u);
+        const uint32_t vr = *(const uint32_t __attribute__((address_space(1))) *)(vt + (uint64_t)nblk * 2048u);
         vbase = (int)(int8_t)(vr & 0xFFu);
         vtop = (int)(int8_t)((vr >> 8) & 0xFFu) - 2;
     }
@@ -100,10 +100,10 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c
         for (int y = 0; y < 4; ++y) qb[mt][y] = __builtin_bit_cast(bf16x8, z);
         if (row < M) {
             const uint32_t qt = row / G, gq = row - qt * G;
-            const uint8_t *qp = reinterpret_cast<const uint8_t *>(c.q) +
+            gbytes qp = (gbytes)c.q +
                                 ((uint64_t)(qt * p.n_q_heads + h * G + gq) * 128u + 32u * c_) * 2u;
 #pragma unroll
-            for (int y = 0; y < 4; ++y) qb[mt][y] = __builtin_bit_cast(bf16x8, ld16(qp + 16 * y));
+            for (int y = 0; y < 4; ++y) qb[mt][y] = __builtin_bit_cast(bf16x8, ldg16(qp + 16 * y));
         }
     }
 
@@ -131,15 +131,15 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c
     auto load_block = [&](uint32_t b, BlockRegs<KP, VP> &r) {
 #pragma unroll
         for (uint32_t a = 0; a < FK::kWords; ++a)
-            r.kw[a] = ld16(kt + (uint64_t)b * FK::kPayload + a * 1024u + lane * 16u);
+            r.kw[a] = ldg16(kt + ((uint64_t)b * FK::kPayload + a * 1024u + lane * 16u));
 #pragma unroll
         for (uint32_t a = 0; a < FV::kWords; ++a)
-            r.vw[a] = ld16(vt + (uint64_t)b * FV::kPayload + a * 1024u + lane * 16u);
+            r.vw[a] = ldg16(vt + ((uint64_t)b * FV::kPayload + a * 1024u + lane * 16u));
         r.km = 0;
         r.vm = u32x4{0u, 0u, 0u, 0u};
         if (FK::kMeta)
-            r.km = *reinterpret_cast<const uint32_t *>(kmeta + (uint64_t)b * kmeta_blk + 4u * k_entry);
-        if (FV::kMeta) r.vm = ld16(vmeta + (uint64_t)b * vmeta_blk + ((lane * 8u) >> vgsh) * 16u);
+            r.km = *(const uint32_t __attribute__((address_space(1))) *)(kmeta + ((uint64_t)b * kmeta_blk + 4u * k_entry));
+        if (FV::kMeta) r.vm = ldg16(vmeta + ((uint64_t)b * vmeta_blk + ((lane * 8u) >> vgsh) * 16u));
     };
 
     // the waves of the workgroup take the blocks of the split in turn; each wave fetches its
@@ -186,8 +186,7 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c
                     if (b * 16u + 4u * jj + c_ >= T) sc[jj] = neg_inf();
             }
             float mx = __builtin_fmaxf(__builtin_fmaxf(sc[0], sc[1]), __builtin_fmaxf(sc[2], sc[3]));
-            mx = __builtin_fmaxf(mx, __shfl_xor(mx, 16));
-            mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));
+            mx = max_over_lane_groups(mx);
             const float m_new = __builtin_fmaxf(m_run[mt], mx);
             if (__any(m_new > m_run[mt])) {  // rare after the first blocks: rescale what is accumulated
                 const float alpha = __builtin_amdgcn_exp2f(m_run[mt] - m_new);  // 0 at the first block
@@ -242,15 +241,21 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c
                                      : (kWordsKV <= 2 ? 4 : 3);
     BlockRegs<KP, VP> ring[kStages];
     uint32_t b = b0 + wave;
+    // Every load below is issued whether or not its block exists (a block past the split's end
+    // is replaced by one this wave has already fetched, a hit in the cache): with a branch
+    // around the loads the compiler has to wait as if they had not been issued, which then
+    // waits for part of the block just requested - a full memory latency per block.
 #pragma unroll
-    for (int i = 0; i < kStages - 1; ++i)
-        if (b + i * kAttendWaves < b1) load_block(b + i * kAttendWaves, ring[i]);
+    for (int i = 0; i < kStages - 1; ++i) {
+        const uint32_t first = b + i * kAttendWaves;
+        load_block(first < b1 ? first : b1 - 1u, ring[i]);
+    }
     if (b < b1) {
         for (;;) {
 #pragma unroll
             for (int i = 0; i < kStages; ++i) {
                 const uint32_t ahead = b + (kStages - 1) * kAttendWaves;
-                if (ahead < b1) load_block(ahead, ring[(i + kStages - 1) % kStages]);
+                load_block(ahead < b1 ? ahead : b, ring[(i + kStages - 1) % kStages]);
                 process(b, ring[i]);
                 b += kAttendWaves;
                 if (b >= b1) goto blocks_done;
@@ -284,7 +289,7 @@ blocks_done:
         __syncthreads();
         const uint32_t mtile = mtg * MTW + mt;
         if (mtile >= n_mt) continue;
-        float *rec = rec0 + (uint64_t)mtile * kAttendRecFloats;
+        gfloats rec = rec0 + (uint64_t)mtile * kAttendRecFloats;
 #pragma unroll
         for (uint32_t k = 0; k < 512u / (64u * kAttendWaves); ++k) {  // 512 16-byte words of output per tile
             const uint32_t i = threadIdx.x + 64u * kAttendWaves * k, row = mt * 16u + (i >> 5);
@@ -299,7 +304,7 @@ blocks_done:
                 const float f = sl[w][row] > 0.0f ? __builtin_amdgcn_exp2f(sm[w][row] - m_all) : 0.0f;
                 sum += reinterpret_cast<const f32x4 *>(acc + w * 2048u)[i] * f;
             }
-            reinterpret_cast<f32x4 *>(rec)[i] = sum;
+            ((f32x4 __attribute__((address_space(1))) *)rec)[i] = sum;
         }
         if (threadIdx.x < 16u) {
             const uint32_t row = mt * 16u + threadIdx.x;

@@ -25,17 +25,6 @@ namespace ha_rag {
 
 namespace {
 
-// Everything the kernel reads or writes outside LDS lies in global memory; saying so lets the
-// loads run as global instructions (scalar base, 32-bit lane offset), which do not count
-// against the LDS counter the way loads through generic pointers do.
-typedef const uint8_t __attribute__((address_space(1))) *gbytes;
-typedef float __attribute__((address_space(1))) *gfloats;
-
-__device__ __forceinline__ u32x4 ldg16(gbytes p)
-{
-    return *(const u32x4 __attribute__((address_space(1))) *)p;
-}
-
 constexpr uint32_t kSharedBlockLds = 8192;  // K operands 4 KiB, then V operands 4 KiB
 
 struct SharedState {  // a wave's two query tiles
@@ -62,23 +51,6 @@ __device__ __forceinline__ uint32_t fresh(uint32_t v)
 {
     asm volatile("" : "+v"(v));
     return v;
-}
-
-// max of a value over the four lanes l, l ^ 16, l ^ 32, l ^ 48 (one per lane group), in every
-// lane.  The row swaps exchange registers between lane rows without a trip through LDS: after
-// swapping the odd rows of one copy with the even rows of another, the two copies hold the
-// value of rows r and r ^ 1 side by side; the same with halves of 32 lanes.
-__device__ __forceinline__ float max_over_lane_groups(float x)
-{
-    typedef unsigned u2 __attribute__((ext_vector_type(2)));
-    const unsigned xi = __builtin_bit_cast(unsigned, x);
-    const u2 r = __builtin_amdgcn_permlane16_swap(xi, xi, false, false);
-    const unsigned r0 = r.x, r1 = r.y;  // copied out first: a bit cast of a vector element reads element 0
-    const float y = __builtin_fmaxf(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
-    const unsigned yi = __builtin_bit_cast(unsigned, y);
-    const u2 t = __builtin_amdgcn_permlane32_swap(yi, yi, false, false);
-    const unsigned t0 = t.x, t1 = t.y;
-    return __builtin_fmaxf(__builtin_bit_cast(float, t0), __builtin_bit_cast(float, t1));
 }
 
 // One block against the wave's two tiles: S^T = K Q^T, running softmax, O += P V.
