@@ -153,18 +153,40 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
         if (groups >= kAttendTargetGroups || sb == kAttendMinSplitBlocks) break;
     }
     *split_blocks = sb;
-    // With workgroups to spare, a workgroup of the shared kernel takes a run of consecutive
-    // documents of its request instead of one: a record per run, not per document, is written
+    // A workgroup of the shared kernel takes a run of consecutive documents of its request
+    // instead of one where that costs no time: a record per run, not per document, is written
     // and merged (records rival the packed bytes once a request has hundreds of query rows).
-    const uint64_t per_run = groups / kAttendTargetGroups;  // documents a run may hold
+    // Workgroups of one size finish in rounds of as many as the chip holds side by side, so a
+    // launch of documents of similar length takes rounds x documents per run; the longest run
+    // with the least of that is taken, but never so long that the first round is not full.
+    const uint64_t side_by_side = (uint64_t)kChipCUs * (waves == 4 ? 2u : 4u);
+    uint32_t most_docs = 0;
+    for (uint32_t r = 0; r < n_reqs; ++r)
+        if (plans[r].shared && plans[r].n_docs > most_docs) most_docs = plans[r].n_docs;
+    if (most_docs > kAttendLaunchChunks) most_docs = kAttendLaunchChunks;  // a run lies within one launch
+    uint32_t run_docs = 1;
+    uint64_t least = ~0ull;
+    for (uint32_t len = 1; len <= most_docs; ++len) {
+        uint64_t wgs = 0;
+        for (uint32_t r = 0; r < n_reqs; ++r) {
+            const Plan &pl = plans[r];
+            if (pl.shared)
+                wgs += (uint64_t)((pl.n_docs + len - 1u) / len) * H * ((pl.max_blocks + sb - 1u) / sb) * tile_groups(pl, waves);
+        }
+        if (len > 1 && wgs < side_by_side) break;
+        const uint64_t cost = (wgs + side_by_side - 1u) / side_by_side * len;
+        if (cost <= least) {
+            least = cost;
+            run_docs = len;
+        }
+    }
     for (uint32_t r = 0; r < n_reqs; ++r) {
         Plan &pl = plans[r];
         pl.n_split = pl.max_blocks ? (pl.max_blocks + sb - 1u) / sb : 1u;
         pl.run_len = 1;
         pl.n_runs = pl.n_docs;
-        if (pl.shared && per_run >= 2 && pl.n_docs > 1) {
-            uint32_t most = per_run < pl.n_docs ? (uint32_t)per_run : pl.n_docs;
-            if (most > kAttendLaunchChunks) most = kAttendLaunchChunks;  // a run lies within one launch
+        if (pl.shared && run_docs > 1 && pl.n_docs > 1) {
+            const uint32_t most = run_docs < pl.n_docs ? run_docs : pl.n_docs;
             const uint32_t n_runs = (pl.n_docs + most - 1u) / most;
             pl.run_len = (pl.n_docs + n_runs - 1u) / n_runs;  // runs of equal length, the last may be shorter
             pl.n_runs = (pl.n_docs + pl.run_len - 1u) / pl.run_len;

@@ -25,6 +25,7 @@ namespace ha_rag {
 
 namespace {
 
+constexpr float kLazyMaxSlack = 8.0f;  // in units of log2
 constexpr uint32_t kSharedBlockLds = 8192;  // K operands 4 KiB, then V operands 4 KiB
 
 struct SharedState {  // a wave's two query tiles
@@ -67,7 +68,7 @@ __device__ __forceinline__ void shared_score(const uint8_t *src, uint32_t b, uin
     u32x4 vq[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) vq[q] = *reinterpret_cast<const u32x4 *>(src + 4096u + q * 1024u + v_rd);
-    // both tiles side by side, so that their MFMA chains and reductions overlap
+    // both tiles side by side, so that their MFMA chains overlap
     f32x4 S[2];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) S[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -76,28 +77,31 @@ __device__ __forceinline__ void shared_score(const uint8_t *src, uint32_t b, uin
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
             S[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[y], st.qb[mt][y], S[mt], 0, 0, 0);
-    // S[mt][jj] = score of token 4 jj + c_ of the block against query row n_ of tile mt
-    float sc[2][4], m_new[2];
+    // S[mt][jj] = q k (unscaled) of token 4 jj + c_ of the block and query row n_ of tile mt
+    if (ragged) {
+        const uint32_t tok = b * 16u + fresh(c_);  // computed only here
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) sc[mt][jj] = S[mt][jj] * scale_log2;
-        if (ragged) {
+        for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj)
-                if (b * 16u + 4u * jj + c_ >= T) sc[mt][jj] = neg_inf();
-        }
-        const float mx = __builtin_fmaxf(__builtin_fmaxf(sc[mt][0], sc[mt][1]), __builtin_fmaxf(sc[mt][2], sc[mt][3]));
-        m_new[mt] = __builtin_fmaxf(st.m_run[mt], max_over_lane_groups(mx));
+                if (tok + 4u * jj >= T) S[mt][jj] = neg_inf();
     }
-    if (__any(m_new[0] > st.m_run[0] || m_new[1] > st.m_run[1])) {
-        // rare after the first blocks: rescale what is accumulated (a tile whose maximum stays
-        // is multiplied by exactly 1)
+    // The running maximum of a row is only a reference point for the exponentials, so it need
+    // not be the true maximum: it is brought up to date (a reduction over the lane groups and a
+    // rescaling of what is accumulated) only when some lane meets a score more than 8 above
+    // it, which bounds every weight by 2^8.  After the first blocks that almost never happens,
+    // and a block costs one comparison instead of the reduction.
+    float mx[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+        mx[mt] = __builtin_fmaxf(__builtin_fmaxf(S[mt][0], S[mt][1]), __builtin_fmaxf(S[mt][2], S[mt][3])) * scale_log2;
+    if (__any(mx[0] > st.m_run[0] + kLazyMaxSlack || mx[1] > st.m_run[1] + kLazyMaxSlack)) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
-            const float alpha = __builtin_amdgcn_exp2f(st.m_run[mt] - m_new[mt]);  // 0 at the first block
+            const float m_new = __builtin_fmaxf(st.m_run[mt], max_over_lane_groups(mx[mt]));
+            const float alpha = __builtin_amdgcn_exp2f(st.m_run[mt] - m_new);  // 0 at the first block, 1 if nothing moved
             st.l_run[mt] *= alpha;
-            st.m_run[mt] = m_new[mt];
+            st.m_run[mt] = m_new;
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
                 const float ar = __shfl(alpha, (int)(4u * c_ + jj));  // factor of output row 4 c_ + jj
@@ -111,7 +115,8 @@ __device__ __forceinline__ void shared_score(const uint8_t *src, uint32_t b, uin
     for (int mt = 0; mt < 2; ++mt) {
         float pr[4];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) pr[jj] = __builtin_amdgcn_exp2f(sc[mt][jj] - st.m_run[mt]);
+        for (int jj = 0; jj < 4; ++jj)
+            pr[jj] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mt][jj], scale_log2, -st.m_run[mt]));
         st.l_run[mt] += (pr[0] + pr[1]) + (pr[2] + pr[3]);
         const u32x2 pk = {pack_bf16(pr[0], pr[1]), pack_bf16(pr[2], pr[3])};
         pa[mt] = __builtin_bit_cast(s16x4, pk);

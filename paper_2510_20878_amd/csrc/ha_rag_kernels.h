@@ -111,6 +111,7 @@ constexpr uint32_t kAttendRecFloats = 16 * 128 + 32;
 constexpr uint32_t kAttendMinSplitBlocks = 8;   // a workgroup takes split_blocks layout blocks (16
 constexpr uint32_t kAttendMaxSplitBlocks = 128; // tokens each) of one chunk: a power of two in this range
 constexpr uint32_t kAttendTargetGroups = 2048;  // the host splits finer while a launch has fewer workgroups
+constexpr uint32_t kChipCUs = 256;            // compute units of the one GPU this library is built for
 constexpr uint32_t kAttendWaves = 2;          // waves of a workgroup; they interleave its blocks
 // Descriptors travel in the kernel argument buffer (about 23 KiB when full; launches with
 // arguments of 32 KiB were checked to work on this runtime).  A workgroup needs exactly one
