@@ -82,6 +82,22 @@ __device__ __forceinline__ u32x4 plane_raw(const u32x4 *w, int j)
     return r;
 }
 
+// The first instruction that reads an MFMA result has to come a fixed number of cycles after
+// the MFMA (11 for the 8-pass 16x16x32).  The compiler inserts that wait where both are in one
+// basic block; with a branch between them it was found to leave the wait out, and the reader
+// then sees what the registers held before.  Called right after a chain whose result is first
+// read behind a branch: nothing is scheduled across it, and it idles for 12 cycles.
+__device__ __forceinline__ void mfma_result_wait()
+{
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 7\n\ts_nop 3");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// how far a score may exceed a row's running maximum before that maximum is brought up to
+// date, in units of log2: weights stay below 2^8
+constexpr float kLazyMaxSlack = 8.0f;
+
 __device__ __forceinline__ float neg_inf() { return -__builtin_huge_valf(); }
 
 // orders the LDS accesses of one wave: what its lanes wrote before is visible to all its

@@ -176,19 +176,21 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c
 #pragma unroll
             for (int y = 0; y < 4; ++y)
                 S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[y], qb[mt][y], S, 0, 0, 0);
-            // S[jj] = score of token 4 jj + c_ of the block against query row n_
-            float sc[4];
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) sc[jj] = S[jj] * p.scale_log2;
+            mfma_result_wait();  // S is first read behind the branch below
+            // S[jj] = q k (unscaled) of token 4 jj + c_ of the block and query row n_
             if (ragged) {
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj)
-                    if (b * 16u + 4u * jj + c_ >= T) sc[jj] = neg_inf();
+                    if (b * 16u + 4u * jj + c_ >= T) S[jj] = neg_inf();
             }
-            float mx = __builtin_fmaxf(__builtin_fmaxf(sc[0], sc[1]), __builtin_fmaxf(sc[2], sc[3]));
-            mx = max_over_lane_groups(mx);
-            const float m_new = __builtin_fmaxf(m_run[mt], mx);
-            if (__any(m_new > m_run[mt])) {  // rare after the first blocks: rescale what is accumulated
+            const float mx = __builtin_fmaxf(__builtin_fmaxf(S[0], S[1]), __builtin_fmaxf(S[2], S[3])) * p.scale_log2;
+            // The running maximum of a row is only a reference point for the exponentials: it
+            // is brought up to date (a reduction over the lane groups and a rescaling of what is
+            // accumulated) only when some lane meets a score more than kLazyMaxSlack above it,
+            // which bounds every weight by 2^kLazyMaxSlack.  After the first blocks that almost
+            // never happens, and a block costs one comparison instead of the reduction.
+            if (__any(mx > m_run[mt] + kLazyMaxSlack)) {
+                const float m_new = __builtin_fmaxf(m_run[mt], max_over_lane_groups(mx));
                 const float alpha = __builtin_amdgcn_exp2f(m_run[mt] - m_new);  // 0 at the first block
                 l_run[mt] *= alpha;
                 m_run[mt] = m_new;
@@ -201,7 +203,8 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c
             }
             float pr[4];
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) pr[jj] = __builtin_amdgcn_exp2f(sc[jj] - m_run[mt]);
+            for (int jj = 0; jj < 4; ++jj)
+                pr[jj] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], p.scale_log2, -m_run[mt]));
             l_run[mt] += (pr[0] + pr[1]) + (pr[2] + pr[3]);
             const u32x2 pk = {pack_bf16(pr[0], pr[1]), pack_bf16(pr[2], pr[3])};
             pa[mt] = __builtin_bit_cast(s16x4, pk);

@@ -25,7 +25,6 @@ namespace ha_rag {
 
 namespace {
 
-constexpr float kLazyMaxSlack = 8.0f;  // in units of log2
 constexpr uint32_t kSharedBlockLds = 8192;  // K operands 4 KiB, then V operands 4 KiB
 
 struct SharedState {  // a wave's two query tiles
@@ -77,6 +76,7 @@ __device__ __forceinline__ void shared_score(const uint8_t *src, uint32_t b, uin
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
             S[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[y], st.qb[mt][y], S[mt], 0, 0, 0);
+    mfma_result_wait();  // S is first read behind the branch below
     // S[mt][jj] = q k (unscaled) of token 4 jj + c_ of the block and query row n_ of tile mt
     if (ragged) {
         const uint32_t tok = b * 16u + fresh(c_);  // computed only here
@@ -86,15 +86,15 @@ __device__ __forceinline__ void shared_score(const uint8_t *src, uint32_t b, uin
             for (int jj = 0; jj < 4; ++jj)
                 if (tok + 4u * jj >= T) S[mt][jj] = neg_inf();
     }
-    // The running maximum of a row is only a reference point for the exponentials, so it need
-    // not be the true maximum: it is brought up to date (a reduction over the lane groups and a
-    // rescaling of what is accumulated) only when some lane meets a score more than 8 above
-    // it, which bounds every weight by 2^8.  After the first blocks that almost never happens,
-    // and a block costs one comparison instead of the reduction.
     float mx[2];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
         mx[mt] = __builtin_fmaxf(__builtin_fmaxf(S[mt][0], S[mt][1]), __builtin_fmaxf(S[mt][2], S[mt][3])) * scale_log2;
+    // The running maximum of a row is only a reference point for the exponentials, so it need
+    // not be the true maximum: it is brought up to date (a reduction over the lane groups and a
+    // rescaling of what is accumulated) only when some lane meets a score more than
+    // kLazyMaxSlack above it, which bounds every weight by 2^kLazyMaxSlack.  After the first
+    // blocks that almost never happens, and a block costs one comparison instead of the reduction.
     if (__any(mx[0] > st.m_run[0] + kLazyMaxSlack || mx[1] > st.m_run[1] + kLazyMaxSlack)) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
