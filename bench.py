@@ -32,7 +32,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+HBM_PEAK_GBPS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense BF16, MI355X's published figure
 # HBM bytes per launch of the gather-dequantize-scatter kernel on the hbm8b workload, from
 # rocprofv3 FETCH_SIZE / WRITE_SIZE runs (one counter per run) scaled by an elementwise
 # kernel of known size (--calibrate): 1.015 x the algorithmic bytes.
@@ -423,9 +424,11 @@ def run_hbm(args, B, wl, torch, name, with_k2=True):
         # the same bytes as n_out page pools; a fresh random page table per buffer
         P = args.paged
         n_pages = cap // P
-        tables = [torch.from_numpy(rng.permutation(n_pages).astype(np.int32)).cuda() for _ in range(n_out)]
-        caches = [B.paged_cache(outs[i], tables[i], P, n_pages, "page_major", L, H, D) for i in range(n_out)]
-        desc += f"; paged cache, {P}-token pages, page-major pool, random page table"
+        tables = [torch.from_numpy((np.arange(n_pages) if args.paged_identity else rng.permutation(n_pages))
+                                   .astype(np.int32)).cuda() for _ in range(n_out)]
+        caches = [B.paged_cache(outs[i], tables[i], P, n_pages, args.paged_layout, L, H, D) for i in range(n_out)]
+        desc += (f"; paged cache, {P}-token pages, {args.paged_layout.replace('_', '-')} pool, "
+                 f"{'identity' if args.paged_identity else 'random'} page table")
 
         cache_of = {o.data_ptr(): c for o, c in zip(outs, caches)}
 
@@ -639,6 +642,31 @@ def run_attend(args, B, wl, torch):
     call_ms = ev_ms / (args.steps * L)
     achieved = step_bytes / L / (call_ms * 1e-3) / 1e9
     log(f"attend8b: {call_ms * 1e3:.1f} us per layer call (events), {ms_per_step:.3f} ms per step")
+    # Which roofline bounds a call: the packed bytes at the HBM peak, or the two contractions
+    # (Q K^T and P V: 4 flops per query row, key token and dim) at the dense BF16 MFMA peak,
+    # whichever takes longer.  Query rows are counted in whole 16-row MFMA tiles per KV head.
+    G = n_qh // H
+    rows = (n_q * G + 15) // 16 * 16
+    call_flops = 4.0 * rows * D * H * sum(sum(c[1] for c in rc) for rc in set_chunks[0])
+    t_hbm, t_mfma = step_bytes / L / (HBM_PEAK_GBPS * 1e9), call_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    kname = ("k6_attend_shared" if (n_q * G + 15) // 16 > 2 else "k6_attend_partial")
+    stored = (R, n_q, T) == (32, 1, 512) and not args.mix
+    if t_mfma > t_hbm:
+        tf = call_flops / (call_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "kernel": f"{kname} (+ merge), one call = one layer", "achieved": tf,
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": None, "traffic_source": None,
+                "kernel_ms": call_ms, "kernel_ms_median": per[len(per) // 2], "kernel_ms_best": per[0],
+                "algorithmic_flops_per_launch": call_flops, "algorithmic_bytes_per_launch": step_bytes // L,
+                "hbm_frac_of_the_same_call": achieved / HBM_PEAK_GBPS}
+    else:
+        roof = {"bound": "hbm", "kernel": f"{kname} (+ merge), one call = one layer",
+                "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                "traffic": args.traffic_bytes or (MEASURED_TRAFFIC["attend8b"] if stored else None),
+                "traffic_source": "--traffic-bytes" if args.traffic_bytes else (TRAFFIC_SOURCE["attend8b"] if stored else None),
+                "kernel_ms": call_ms, "kernel_ms_median": per[len(per) // 2], "kernel_ms_best": per[0],
+                "algorithmic_bytes_per_launch": step_bytes // L, "algorithmic_flops_per_launch": call_flops,
+                "mfma_frac_of_the_same_call": call_flops / (call_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
     verified = verify_attend(torch, ctx, slabs, set_chunks[0], sets[0], q, out, lse, shape, g, n_qh,
                              scale, ws, ws_bytes, stream, args.verify_samples, args.seed)
     # the other route, measured in the same run: build each request's BF16 cache once (the load
@@ -691,15 +719,7 @@ def run_attend(args, B, wl, torch):
         # the rate at which an attention kernel over that BF16 cache would have to read it to
         # finish the step in the same time
         "equivalent_bf16_cache_read_gbps": step_tokens * L * 2 * H * D * 2 / (ms_per_step * 1e-3) / 1e9,
-        "roofline": {"bound": "hbm", "kernel": "k6_attend_partial (+ k7_attend_merge), one call = one layer",
-                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": args.traffic_bytes or (MEASURED_TRAFFIC["attend8b"]
-                                                       if (R, n_q, T) == (32, 1, 512) and not args.mix else None),
-                     "traffic_source": "--traffic-bytes" if args.traffic_bytes else
-                                       (TRAFFIC_SOURCE["attend8b"] if (R, n_q, T) == (32, 1, 512) and not args.mix else None),
-                     "kernel_ms": call_ms, "kernel_ms_median": per[len(per) // 2], "kernel_ms_best": per[0],
-                     "algorithmic_bytes_per_launch": step_bytes // L},
+        "roofline": roof,
     }
     return res, (shape, T, g, mix)
 
@@ -1187,6 +1207,9 @@ def main():
     ap.add_argument("--out-buffers", type=int, default=4)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--threads", type=int, default=64, help="kernel launch shape (see ha_rag.h)")
+    ap.add_argument("--paged-layout", default="page_major", choices=["page_major", "tile_major"],
+                    help="--paged: the pool's layout (tile_major with --paged-identity has the plain cache's addresses)")
+    ap.add_argument("--paged-identity", action="store_true", help="--paged: page i of the table is page i of the pool")
     ap.add_argument("--planes16", type=int, default=0, help="0 = the library's choice (1; 4 into a paged cache)")
     ap.add_argument("--planes8", type=int, default=0, help="0 = the library's choice (2; 4 into a paged cache)")
     ap.add_argument("--nt-store", type=int, default=1)
