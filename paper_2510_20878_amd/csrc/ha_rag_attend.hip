@@ -133,11 +133,13 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
         pl.max_blocks = (max_tokens + 15u) / 16u;
         n_chunks += rq.n_chunks;
     }
-    // The shared kernel runs with four waves (eight tiles a workgroup) as soon as one request
-    // has more than four tiles, else with two.
+    // The shared kernel runs with as many waves (two tiles each) as the call's largest request
+    // has use for: 2, 4 or 8.
     uint32_t waves = 2;
     for (uint32_t r = 0; r < n_reqs; ++r)
-        if (plans[r].shared && plans[r].n_mt > 4u) waves = 4;
+        if (plans[r].shared && plans[r].n_mt > 4u && waves < 4u) waves = 4;
+    for (uint32_t r = 0; r < n_reqs; ++r)
+        if (plans[r].shared && plans[r].n_mt > 8u) waves = 8;
     *shared_waves = waves;
     // Tokens per workgroup: as many as possible (every workgroup pays for fetching the queries
     // and for writing a record), but fine enough that the launch fills the chip a few times
@@ -159,7 +161,7 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
     // Workgroups of one size finish in rounds of as many as the chip holds side by side, so a
     // launch of documents of similar length takes rounds x documents per run; the longest run
     // with the least of that is taken, but never so long that the first round is not full.
-    const uint64_t side_by_side = (uint64_t)kChipCUs * (waves == 4 ? 2u : 4u);
+    const uint64_t side_by_side = (uint64_t)kChipCUs * (8u / waves);  // two waves per SIMD: eight per CU
     uint32_t most_docs = 0;
     for (uint32_t r = 0; r < n_reqs; ++r)
         if (plans[r].shared && plans[r].n_docs > most_docs) most_docs = plans[r].n_docs;

@@ -20,6 +20,7 @@
 //      stores octet o of token t at 16-byte slot (o ^ t) of row t (256 bytes a row), which
 //      both its own stores and the readers' loads reach without bank conflicts.
 #include "ha_rag_attend_dev.h"
+#include <atomic>
 
 namespace ha_rag {
 
@@ -53,22 +54,20 @@ __device__ __forceinline__ uint32_t fresh(uint32_t v)
     return v;
 }
 
-// One block against the wave's two tiles: S^T = K Q^T, running softmax, O += P V.
-__device__ __forceinline__ void shared_score(const uint8_t *src, uint32_t b, uint32_t T, float scale_log2,
-                                             const SharedLane &ln, SharedState &st)
+// One block against the wave's two tiles, in three steps that the round loop below interleaves
+// across blocks: S^T = K Q^T (shared_qk), the running softmax (shared_softmax), O += P V
+// (shared_pv).
+
+// S[mt][jj] = q k (unscaled) of token 4 jj + c_ of the block and query row n_ of tile mt
+__device__ __forceinline__ void shared_qk(const uint8_t *src, const SharedLane &ln, const SharedState &st,
+                                          f32x4 (&S)[2])
 {
-    const uint32_t c_ = ln.c_;
-    const bool ragged = b * 16u + 16u > T;  // only the document's last block can be
-    const uint32_t k_rd = fresh(ln.k_rd), v_rd = fresh(ln.lane) * 16u;
+    const uint32_t k_rd = fresh(ln.k_rd);
     bf16x8 ka[4];
 #pragma unroll
     for (uint32_t y = 0; y < 4; ++y)
         ka[y] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(src + (k_rd ^ (16u * y))));
-    u32x4 vq[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) vq[q] = *reinterpret_cast<const u32x4 *>(src + 4096u + q * 1024u + v_rd);
     // both tiles side by side, so that their MFMA chains overlap
-    f32x4 S[2];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) S[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -76,9 +75,15 @@ __device__ __forceinline__ void shared_score(const uint8_t *src, uint32_t b, uin
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
             S[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[y], st.qb[mt][y], S[mt], 0, 0, 0);
-    mfma_result_wait();  // S is first read behind the branch below
-    // S[mt][jj] = q k (unscaled) of token 4 jj + c_ of the block and query row n_ of tile mt
-    if (ragged) {
+}
+
+// From the scores of block b to the weights pa (the A operands of P V).  The caller sees to it
+// that S is not read too early after its MFMAs (mfma_result_wait, or other MFMAs in between).
+__device__ __forceinline__ void shared_softmax(f32x4 (&S)[2], uint32_t b, uint32_t T, float scale_log2,
+                                               const SharedLane &ln, SharedState &st, s16x4 (&pa)[2])
+{
+    const uint32_t c_ = ln.c_;
+    if (b * 16u + 16u > T) {  // ragged: only the document's last block can be
         const uint32_t tok = b * 16u + fresh(c_);  // computed only here
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
@@ -110,7 +115,6 @@ __device__ __forceinline__ void shared_score(const uint8_t *src, uint32_t b, uin
             }
         }
     }
-    s16x4 pa[2];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
         float pr[4];
@@ -121,6 +125,15 @@ __device__ __forceinline__ void shared_score(const uint8_t *src, uint32_t b, uin
         const u32x2 pk = {pack_bf16(pr[0], pr[1]), pack_bf16(pr[2], pr[3])};
         pa[mt] = __builtin_bit_cast(s16x4, pk);
     }
+}
+
+__device__ __forceinline__ void shared_pv(const uint8_t *src, const SharedLane &ln, SharedState &st,
+                                          const s16x4 (&pa)[2])
+{
+    const uint32_t v_rd = fresh(ln.lane) * 16u;
+    u32x4 vq[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) vq[q] = *reinterpret_cast<const u32x4 *>(src + 4096u + q * 1024u + v_rd);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const s16x4 v0 = __builtin_bit_cast(s16x4, u32x2{vq[q].x, vq[q].y});
@@ -196,11 +209,26 @@ __device__ __forceinline__ void shared_rounds(const SharedSide &sd, uint32_t T, 
         fetch(1, rb + W + 2u * r + 1u);
 
         // ---- every wave: its two tiles against the round's blocks
+        // The blocks of the round are staggered: the score MFMAs of block i + 1 are issued
+        // before the P V MFMAs of block i, and the softmax of block i + 1 (vector work) runs
+        // while those drain.  Between the score MFMAs and the first read of their result lie
+        // the 16 P V MFMAs, more than the cycles that read has to wait.
         if (active) {
-            const uint32_t nb = b1 - rb;
-#pragma unroll 1
-            for (uint32_t i = 0; i < (uint32_t)W; ++i)
-                if (i < nb) shared_score(lds[set][i], rb + i, T, scale_log2, ln, st);
+            const uint32_t nb = b1 - rb < (uint32_t)W ? b1 - rb : (uint32_t)W;
+            f32x4 S[2];
+            s16x4 pa[2];
+            shared_qk(lds[set][0], ln, st, S);
+            mfma_result_wait();
+            shared_softmax(S, rb, T, scale_log2, ln, st, pa);
+#pragma unroll
+            for (uint32_t i = 0; i + 1u < (uint32_t)W; ++i) {
+                if (i + 1u < nb) {
+                    shared_qk(lds[set][i + 1u], ln, st, S);
+                    shared_pv(lds[set][i], ln, st, pa);
+                    shared_softmax(S, rb + i + 1u, T, scale_log2, ln, st, pa);
+                }
+            }
+            shared_pv(lds[set][nb - 1u], ln, st, pa);
         }
         set ^= 1u;
     }
@@ -244,12 +272,15 @@ __device__ __forceinline__ SharedSide shared_side(const uint8_t *first, uint32_t
 
 }  // namespace
 
-// W waves, half of them decoding keys and half values; two waves per SIMD keep 256 registers
+// W = 2, 4 or 8 waves, half of them decoding keys and half values; two waves per SIMD keep 256 registers
 // each (two tiles of output, their queries, the raw words of two blocks).
 template <int W>
 __global__ void __launch_bounds__(64 * W, 2) k6_attend_shared(const K6Params p)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[2][W][kSharedBlockLds];
+    // two sets of W block buffers; dynamic, because eight waves need 128 KiB (a workgroup may
+    // declare 64 KiB at most statically)
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_bytes[];
+    uint8_t (*lds)[W][kSharedBlockLds] = reinterpret_cast<uint8_t (*)[W][kSharedBlockLds]>(lds_bytes);
     K6Chunk c = p.c[blockIdx.y];
     AttendHdr hdr = {p.n_kv_heads, p.n_q_heads, p.layer, p.split_blocks, p.scale_log2};
     pin(c.k);
@@ -374,7 +405,7 @@ hipError_t launch_k6_shared(K6Params &p, uint32_t n_runs, uint32_t waves, hipStr
     if (p.n_chunks > kAttendLaunchChunks || n_runs == 0 || n_runs > p.n_chunks || p.n_kv_heads == 0 ||
         p.n_q_heads % p.n_kv_heads || p.split_blocks < kAttendMinSplitBlocks ||
         p.split_blocks > kAttendMaxSplitBlocks || (p.split_blocks & (p.split_blocks - 1u)) ||
-        (waves != 2u && waves != 4u))
+        (waves != 2u && waves != 4u && waves != 8u))
         return hipErrorInvalidValue;
     const uint32_t G = p.n_q_heads / p.n_kv_heads;
     uint64_t width = 0, followers = 0;
@@ -407,8 +438,24 @@ hipError_t launch_k6_shared(K6Params &p, uint32_t n_runs, uint32_t waves, hipStr
     p.mtw = 2;
     p.pad = 0;
     dim3 grid((uint32_t)width, n_runs);
-    if (waves == 2u) hipLaunchKernelGGL((k6_attend_shared<2>), grid, dim3(128), 0, stream, p);
-    else hipLaunchKernelGGL((k6_attend_shared<4>), grid, dim3(256), 0, stream, p);
+    const uint32_t lds_bytes = 2u * waves * kSharedBlockLds;
+    if (waves == 2u) hipLaunchKernelGGL((k6_attend_shared<2>), grid, dim3(128), lds_bytes, stream, p);
+    else if (waves == 4u) hipLaunchKernelGGL((k6_attend_shared<4>), grid, dim3(256), lds_bytes, stream, p);
+    else {
+        // more than 64 KiB of LDS per workgroup has to be asked for once per device
+        static std::atomic<uint64_t> asked{0};
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        if (!(asked.load(std::memory_order_acquire) >> dev & 1u)) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k6_attend_shared<8>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            if (e != hipSuccess) return e;
+            asked.fetch_or(1ull << dev, std::memory_order_release);
+        }
+        hipLaunchKernelGGL((k6_attend_shared<8>), grid, dim3(512), lds_bytes, stream, p);
+    }
     return hipGetLastError();
 }
 

@@ -159,7 +159,7 @@ struct K7Params {
 
 // Partial attention of every chunk of the launch (sets mtw).
 hipError_t launch_k6(K6Params &p, hipStream_t stream);
-// The same for requests with more than two query tiles: the `waves` (2 or 4) waves of a
+// The same for requests with more than two query tiles: the `waves` (2, 4 or 8) waves of a
 // workgroup share every decoded block, each wave with two tiles of its own.  A workgroup takes
 // a run of documents of one request: descriptors 0 .. n_runs - 1 are the runs' first documents
 // (request, records in `part`, `run`, `more`), the runs' other documents come after them

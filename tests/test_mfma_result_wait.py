@@ -1,6 +1,6 @@
 """Host-side check of the attention kernels' machine code (no GPU): the first instruction that
-reads an MFMA result must come at least 11 issue slots after the MFMA (8-pass 16x16x32; the
-shorter MFMAs need fewer).  The compiler inserts that wait inside a basic block; behind a
+reads an MFMA result must come a number of issue slots after the MFMA: its passes + 3, i.e. 11
+for the 8-pass 16x16x32 and 7 for the 4-pass 16x16x16.  The compiler inserts that wait inside a basic block; behind a
 branch it was seen to leave it out, which is why the kernels idle explicitly
 (mfma_result_wait in csrc/ha_rag_attend_dev.h).  This test compiles the two kernel sources to
 assembly with the library's flags and follows every path from every MFMA, taken branches
@@ -15,7 +15,16 @@ import pytest
 
 from paper_2510_20878_amd import build
 
-NEED = 11
+NEED = {"16x16x32": 11, "16x16x16": 7}  # 8-pass and 4-pass MFMAs: passes + 3
+
+
+def _need(instr, need):
+    if need is not None:
+        return need
+    for shape, n in NEED.items():
+        if shape in instr:
+            return n
+    return max(NEED.values())
 
 
 def _regs(text):
@@ -36,7 +45,7 @@ def _split(instr):
     return ops[0], ops[1] if len(ops) > 1 else ""
 
 
-def early_readers(asm_text, need=NEED):
+def early_readers(asm_text, need=None):
     lines = asm_text.split("\n")
     label = {l.split(":")[0]: i for i, l in enumerate(lines) if re.match(r"\.LBB\d+_\d+:", l)}
     found, n_mfma = [], 0
@@ -45,11 +54,12 @@ def early_readers(asm_text, need=NEED):
         if not m:
             continue
         n_mfma += 1
+        limit = _need(l, need)
         dst = set(range(int(m.group(1)), int(m.group(2)) + 1))
         work, seen = [(i + 1, 0)], set()
         while work:
             j, slots = work.pop()
-            while j < len(lines) and slots < need and j not in seen:
+            while j < len(lines) and slots < limit and j not in seen:
                 seen.add(j)
                 t = lines[j].strip()
                 if not t or t[0] in ";.":
