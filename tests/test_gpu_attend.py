@@ -178,6 +178,16 @@ def test_runs_of_documents_per_workgroup_across_launches_of_the_many_rows_kernel
     run_case((1, 8, 128), reqs, 0, 32, 0.1, 90)
 
 
+@pytest.mark.parametrize("n_q,n_qh,H", [(12, 4, 1), (40, 4, 1), (9, 32, 2)])
+def test_many_rows_kernel_with_token_splits(n_q, n_qh, H):
+    """Few, long documents and many query rows: the call has few workgroups, so the host cuts
+    the tokens into splits (128-token splits here) and every (document, split) writes its own
+    record for the tile-wise merge; 3, 10 and 9 query tiles take workgroups of 2, 8 and 8 waves.
+    The second document's last block is ragged and its last split short."""
+    reqs = [([2500, 700], [B.PREC_INT4, B.PREC_INT8], n_q), ([1333], [B.PREC_16], n_q)]
+    run_case((1, H, 128), reqs, 0, n_qh, 0.07, 110 + n_q)
+
+
 def test_one_call_with_requests_for_both_attention_kernels():
     """One query token next to 24 and 70 of them: the first request takes the kernel of at most
     two query tiles, the others the many-rows kernel (3 and 9 tiles, so one workgroup of four
