@@ -43,7 +43,9 @@ struct Plan {               // one request
     uint32_t first_doc = 0, n_docs = 0;  // its documents that hold tokens
     uint32_t n_split = 1, n_mt = 1, max_blocks = 0;
     uint32_t shared = 0;       // more than two query tiles: the kernel whose waves share each decoded block
-    uint32_t run_len = 1, n_runs = 0;  // documents per workgroup (shared kernel only) and runs of the request
+    uint32_t run_blocks = 0;   // shared kernel: layout blocks per workgroup (a run of blocks across documents)
+    uint64_t all_blocks = 0;   // shared kernel: layout blocks of all its documents
+    uint32_t n_runs = 0;       // records per (KV head, split, tile): runs, or documents of the other kernel
     uint64_t part_floats = 0;  // offset of its records in the workspace
 };
 
@@ -51,6 +53,47 @@ struct Plan {               // one request
 uint32_t tile_groups(const Plan &pl, uint32_t waves)
 {
     return pl.shared ? (pl.n_mt + 2u * waves - 1u) / (2u * waves) : (pl.n_mt + 1u) / 2u;
+}
+
+// A run: the blocks one workgroup of the shared kernel takes, a range of the request's blocks in
+// list order that may start and end inside a document.
+struct Run {
+    uint32_t doc, first_block;  // first document (index into the request's documents) and block in it
+    uint32_t n_docs, end_block; // documents touched; end of the range in the last of them
+};
+constexpr uint32_t kMaxRunDocs = 128;  // a run's documents are descriptors of one launch
+
+// The run that starts at block `blk` of document `doc` of the request (both moved to the next
+// run's start); false when the request has no block left.
+bool next_run(const Plan &pl, const Doc *docs, uint32_t &doc, uint32_t &blk, Run *out)
+{
+    if (doc >= pl.n_docs) return false;
+    out->doc = doc;
+    out->first_block = blk;
+    out->n_docs = 0;
+    uint32_t left = pl.run_blocks;
+    for (;;) {
+        const uint32_t nb = (docs[doc].n_tokens + 15u) / 16u;
+        ++out->n_docs;
+        if (nb - blk > left) {  // the run ends inside this document
+            blk += left;
+            out->end_block = blk;
+            return true;
+        }
+        left -= nb - blk;
+        out->end_block = nb;
+        ++doc;
+        blk = 0;
+        if (left == 0 || doc >= pl.n_docs || out->n_docs == kMaxRunDocs) return true;
+    }
+}
+
+uint32_t count_runs(const Plan &pl, const Doc *docs)
+{
+    uint32_t doc = 0, blk = 0, n = 0;
+    Run r;
+    while (next_run(pl, docs, doc, blk, &r)) ++n;
+    return n;
 }
 
 // Checks everything and lays the workspace out.  *floats = workspace size in binary32 words.
@@ -135,11 +178,10 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
     }
     // The shared kernel runs with as many waves (two tiles each) as the call's largest request
     // has use for: 2, 4 or 8.
-    uint32_t waves = 2;
+    uint32_t most_mt = 0;
     for (uint32_t r = 0; r < n_reqs; ++r)
-        if (plans[r].shared && plans[r].n_mt > 4u && waves < 4u) waves = 4;
-    for (uint32_t r = 0; r < n_reqs; ++r)
-        if (plans[r].shared && plans[r].n_mt > 8u) waves = 8;
+        if (plans[r].shared && plans[r].n_mt > most_mt) most_mt = plans[r].n_mt;
+    const uint32_t waves = most_mt > 8u ? 8u : most_mt > 4u ? 4u : 2u;
     *shared_waves = waves;
     // Tokens per workgroup: as many as possible (every workgroup pays for fetching the queries
     // and for writing a record), but fine enough that the launch fills the chip a few times
@@ -150,48 +192,51 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
         groups = 0;
         for (uint32_t r = 0; r < n_reqs; ++r) {
             const Plan &pl = plans[r];
-            groups += (uint64_t)pl.n_docs * H * ((pl.max_blocks + sb - 1u) / sb) * tile_groups(pl, waves);
+            if (!pl.shared) groups += (uint64_t)pl.n_docs * H * ((pl.max_blocks + sb - 1u) / sb) * tile_groups(pl, waves);
         }
         if (groups >= kAttendTargetGroups || sb == kAttendMinSplitBlocks) break;
     }
     *split_blocks = sb;
-    // A workgroup of the shared kernel takes a run of consecutive documents of its request
-    // instead of one where that costs no time: a record per run, not per document, is written
-    // and merged (records rival the packed bytes once a request has hundreds of query rows).
-    // Workgroups of one size finish in rounds of as many as the chip holds side by side, so a
-    // launch of documents of similar length takes rounds x documents per run; the longest run
-    // with the least of that is taken, but never so long that the first round is not full.
+    // A workgroup of the shared kernel takes a run of the request's blocks in list order, across
+    // document boundaries, and writes one record per run (records rival the packed bytes once a
+    // request has hundreds of query rows; equal runs also finish together whatever the documents'
+    // lengths).  Workgroups of one size finish in rounds of as many as the chip holds side by
+    // side, so a launch takes rounds x blocks per run: the longest run with the least of that
+    // is taken; a run is at least kAttendMinSplitBlocks long.  Token splits do not apply here.
     const uint64_t side_by_side = (uint64_t)kChipCUs * (8u / waves);  // two waves per SIMD: eight per CU
-    uint32_t most_docs = 0;
-    for (uint32_t r = 0; r < n_reqs; ++r)
-        if (plans[r].shared && plans[r].n_docs > most_docs) most_docs = plans[r].n_docs;
-    if (most_docs > kAttendLaunchChunks) most_docs = kAttendLaunchChunks;  // a run lies within one launch
-    uint32_t run_docs = 1;
-    uint64_t least = ~0ull;
-    for (uint32_t len = 1; len <= most_docs; ++len) {
+    uint64_t most_blocks = 0;
+    for (uint32_t r = 0; r < n_reqs; ++r) {
+        Plan &pl = plans[r];
+        if (!pl.shared) continue;
+        pl.all_blocks = 0;
+        for (uint32_t i = 0; i < pl.n_docs; ++i) pl.all_blocks += ((*docs)[pl.first_doc + i].n_tokens + 15u) / 16u;
+        if (pl.all_blocks > most_blocks) most_blocks = pl.all_blocks;
+    }
+    uint64_t run_blocks = most_blocks, least = ~0ull;
+    for (uint64_t n = 1; n <= most_blocks; ++n) {  // n runs for the largest request
+        const uint64_t len = (most_blocks + n - 1u) / n;
+        if (n > 1 && len < kAttendMinSplitBlocks) break;
         uint64_t wgs = 0;
         for (uint32_t r = 0; r < n_reqs; ++r) {
             const Plan &pl = plans[r];
-            if (pl.shared)
-                wgs += (uint64_t)((pl.n_docs + len - 1u) / len) * H * ((pl.max_blocks + sb - 1u) / sb) * tile_groups(pl, waves);
+            if (pl.shared) wgs += (pl.all_blocks + len - 1u) / len * H * tile_groups(pl, waves);
         }
-        if (len > 1 && wgs < side_by_side) break;
         const uint64_t cost = (wgs + side_by_side - 1u) / side_by_side * len;
-        if (cost <= least) {
+        if (cost < least) {
             least = cost;
-            run_docs = len;
+            run_blocks = len;
         }
+        if (wgs >= 64u * side_by_side) break;  // finer than this gains nothing
     }
     for (uint32_t r = 0; r < n_reqs; ++r) {
         Plan &pl = plans[r];
-        pl.n_split = pl.max_blocks ? (pl.max_blocks + sb - 1u) / sb : 1u;
-        pl.run_len = 1;
-        pl.n_runs = pl.n_docs;
-        if (pl.shared && run_docs > 1 && pl.n_docs > 1) {
-            const uint32_t most = run_docs < pl.n_docs ? run_docs : pl.n_docs;
-            const uint32_t n_runs = (pl.n_docs + most - 1u) / most;
-            pl.run_len = (pl.n_docs + n_runs - 1u) / n_runs;  // runs of equal length, the last may be shorter
-            pl.n_runs = (pl.n_docs + pl.run_len - 1u) / pl.run_len;
+        if (pl.shared) {
+            pl.n_split = 1;
+            pl.run_blocks = run_blocks > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)(run_blocks ? run_blocks : 1u);
+            pl.n_runs = count_runs(pl, docs->data + pl.first_doc);
+        } else {
+            pl.n_split = pl.max_blocks ? (pl.max_blocks + sb - 1u) / sb : 1u;
+            pl.n_runs = pl.n_docs;
         }
         pl.part_floats = total;
         total += (uint64_t)pl.n_runs * H * pl.n_split * pl.n_mt * kAttendRecFloats;
@@ -271,6 +316,7 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
         d.n_split = pl.n_split;
         d.run = 1;
         d.more = 0;
+        d.first_block = d.end_block = 0;
     };
     for (uint32_t r = 0; r < n_reqs; ++r) {
         const Plan &pl = plans[r];
@@ -287,37 +333,45 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
     // The shared kernel's launch lists the runs' first documents, then the other documents run
     // by run.  A run never straddles two launches: first count the runs that fit, then fill.
     struct RunPos {
-        uint32_t r, i;  // request, first document of the run
+        uint32_t r, doc, blk, run_no;  // request, start of the next run in it, number of that run
     };
     auto settle = [&](RunPos &p) {  // moves p to the next run there is; false at the end
-        while (p.r < n_reqs && (!plans[p.r].shared || p.i >= plans[p.r].n_docs)) {
+        while (p.r < n_reqs && (!plans[p.r].shared || p.doc >= plans[p.r].n_docs)) {
             ++p.r;
-            p.i = 0;
+            p.doc = p.blk = p.run_no = 0;
         }
         return p.r < n_reqs;
     };
-    auto run_docs = [&](const RunPos &p) {
+    auto take = [&](RunPos &p, Run *run) {  // the run at p; p moves behind it
         const Plan &pl = plans[p.r];
-        return pl.n_docs - p.i < pl.run_len ? pl.n_docs - p.i : pl.run_len;
+        next_run(pl, docs.data + pl.first_doc, p.doc, p.blk, run);
+        ++p.run_no;
     };
-    RunPos at = {0, 0};
+    RunPos at = {0, 0, 0, 0};
     while (settle(at)) {
         uint32_t n_runs = 0, n_all = 0;
-        for (RunPos p = at; settle(p) && n_all + run_docs(p) <= kAttendLaunchChunks; p.i += plans[p.r].run_len) {
+        for (RunPos p = at; settle(p);) {
+            Run run;
+            take(p, &run);
+            if (n_all + run.n_docs > kAttendLaunchChunks) break;
             ++n_runs;
-            n_all += run_docs(p);
+            n_all += run.n_docs;
         }
         uint32_t later = n_runs;  // where the next run's other documents go
-        for (uint32_t k = 0; k < n_runs; ++k, at.i += plans[at.r].run_len) {
+        for (uint32_t k = 0; k < n_runs; ++k) {
             settle(at);
             const Plan &pl = plans[at.r];
-            const uint32_t len = run_docs(at), run_no = at.i / pl.run_len;
+            const uint32_t run_no = at.run_no, r = at.r;
+            Run run;
+            take(at, &run);
             K6Chunk &head = ks.c[k];
-            fill(head, reqs[at.r], pl, docs[pl.first_doc + at.i], run_no);
-            head.run = len;
+            fill(head, reqs[r], pl, docs[pl.first_doc + run.doc], run_no);
+            head.run = run.n_docs;
             head.more = later;
-            for (uint32_t d = 1; d < len; ++d)
-                fill(ks.c[later++], reqs[at.r], pl, docs[pl.first_doc + at.i + d], run_no);
+            head.first_block = run.first_block;
+            head.end_block = run.end_block;
+            for (uint32_t d = 1; d < run.n_docs; ++d)
+                fill(ks.c[later++], reqs[r], pl, docs[pl.first_doc + run.doc + d], run_no);
         }
         ks.n_chunks = n_all;
         HIPCHK(c, launch_k6_shared(ks, n_runs, waves, st));

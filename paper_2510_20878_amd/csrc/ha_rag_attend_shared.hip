@@ -2,15 +2,16 @@
 // wave can keep (more than two 16-row tiles: the question's prefill of Sec. 2.1, tens of query
 // tokens times the query heads of a KV head).
 //
-//  k6_attend_shared<W>   one workgroup of W waves per (run of documents, KV head, token split,
-//      group of 2 W query tiles).  Every wave owns two query tiles for the whole run: their
-//      queries, running maxima, sums and output rows stay in its registers.  The layout blocks
-//      are taken W at a time: wave w decodes block w of the round to BF16 (the values a load
-//      would write) and leaves it in LDS in the form the MFMAs take their operands in; after one
-//      barrier every wave scores all W blocks against its own tiles.  A block is therefore
-//      fetched and decoded once per 32 W query rows.  The rounds alternate between two sets of
-//      LDS buffers, so one barrier per round is enough: a wave that writes round r + 1 has
-//      passed barrier r, which every wave reaches only after it has read all of round r - 1.
+//  k6_attend_shared<W>   one workgroup of W waves (2, 4 or 8) per (run of blocks across a request's
+//      documents in list order, KV head, group of 2 W query tiles).  Every wave owns two query
+//      tiles for the whole run: their queries, reference maxima, sums and output rows stay in its
+//      registers.  The layout blocks are taken W at a time: half the waves decode the keys and
+//      half the values of the round, two blocks each, to BF16 (the values a load would write)
+//      and leave them in LDS in the form the MFMAs take their operands in; after one barrier
+//      every wave scores all W blocks against its own tiles.  A block is therefore fetched and
+//      decoded once per 32 W query rows.  The rounds alternate between two sets of LDS buffers,
+//      so one barrier per round is enough: a wave that writes round r + 1 has passed barrier r,
+//      which every wave reaches only after it has read all of round r - 1.
 //
 // Block geometry as for k6_attend_partial: lane (c = lane / 16, n = lane % 16) of the wave that
 // reads a block holds, in plane j, token 4 j + c, dims 8 n .. 8 n + 7.
@@ -296,8 +297,11 @@ __global__ void __launch_bounds__(64 * W, 2) k6_attend_shared(const K6Params p)
     pin(hdr.split_blocks);
     pin(hdr.scale_log2);
     uint32_t run = c.run, more = c.more;  // the run's documents: this one, then descriptors more, more + 1, ..
+    uint32_t first_block = c.first_block, end_block = c.end_block;  // where the run starts in its first and ends in its last
     pin(run);
     pin(more);
+    pin(first_block);
+    pin(end_block);
     const uint32_t H = hdr.n_kv_heads, G = hdr.n_q_heads / H, M = c.n_q * G;
     const uint32_t n_mt = (M + 15u) >> 4;
     const uint32_t n_mtg = (n_mt + 2u * W - 1u) / (2u * W);
@@ -358,9 +362,9 @@ __global__ void __launch_bounds__(64 * W, 2) k6_attend_shared(const K6Params p)
             dinfo = cd.info;
         }
         const uint32_t nblk = (T + 15u) >> 4;
-        const uint32_t b0 = s * hdr.split_blocks;
-        const uint32_t b1 = b0 + hdr.split_blocks < nblk ? b0 + hdr.split_blocks : nblk;
-        if (b0 >= b1) continue;  // nothing of this document in this split
+        const uint32_t b0 = d ? 0u : first_block;
+        const uint32_t b1 = d + 1u == run ? end_block : nblk;
+        if (b0 >= b1) continue;  // cannot happen with a checked launch
         if (is_k) {
             const uint32_t prec = dinfo & 0xFu;
             const SharedSide sd = shared_side(dk, prec, (dinfo >> 4) & 0xFu, h, nblk, true);
@@ -424,10 +428,14 @@ hipError_t launch_k6_shared(K6Params &p, uint32_t n_runs, uint32_t waves, hipStr
             return hipErrorInvalidValue;
         if (c.run > 1u && (c.more < n_runs || c.more > p.n_chunks || c.run - 1u > p.n_chunks - c.more))
             return hipErrorInvalidValue;
-        // every block of every document of the run must belong to one of the request's splits
-        for (uint32_t d = 0; d < c.run; ++d) {
-            const K6Chunk &cd = d ? p.c[c.more + d - 1u] : c;
-            if ((uint64_t)c.n_split * p.split_blocks * 16u < cd.n_tokens) return hipErrorInvalidValue;
+        // the run's block range: starts inside its first document, ends inside its last, not empty
+        if (c.n_split != 1u) return hipErrorInvalidValue;
+        {
+            const K6Chunk &last = c.run > 1u ? p.c[c.more + c.run - 2u] : c;
+            const uint32_t nb_first = (c.n_tokens + 15u) >> 4, nb_last = (last.n_tokens + 15u) >> 4;
+            if (c.first_block >= nb_first || c.end_block > nb_last || c.end_block == 0 ||
+                (c.run == 1u && c.end_block <= c.first_block))
+                return hipErrorInvalidValue;
         }
         followers += c.run - 1u;
         const uint32_t n_mt = (c.n_q * G + 15u) >> 4;

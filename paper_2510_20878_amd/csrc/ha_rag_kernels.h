@@ -113,7 +113,7 @@ constexpr uint32_t kAttendMaxSplitBlocks = 128; // tokens each) of one chunk: a 
 constexpr uint32_t kAttendTargetGroups = 2048;  // the host splits finer while a launch has fewer workgroups
 constexpr uint32_t kChipCUs = 256;            // compute units of the one GPU this library is built for
 constexpr uint32_t kAttendWaves = 2;          // waves of a workgroup; they interleave its blocks
-// Descriptors travel in the kernel argument buffer (about 23 KiB when full; launches with
+// Descriptors travel in the kernel argument buffer (about 26 KiB when full; launches with
 // arguments of 32 KiB were checked to work on this runtime).  A workgroup needs exactly one
 // descriptor, which it fetches in one go: the argument buffer may live in host memory, where
 // every dependent read costs a trip over the link.
@@ -133,6 +133,8 @@ struct K6Chunk {
     uint32_t run;         // launch_k6_shared: documents of the run this descriptor starts (1 = itself only)
     uint32_t more;        // launch_k6_shared: index of the descriptor of the run's second document;
                           // the third and later ones follow it
+    uint32_t first_block; // launch_k6_shared: the run starts at this layout block of its first document
+    uint32_t end_block;   // and ends before this one of its last document (all documents between whole)
 };
 
 struct K6Params {
@@ -161,7 +163,8 @@ struct K7Params {
 hipError_t launch_k6(K6Params &p, hipStream_t stream);
 // The same for requests with more than two query tiles: the `waves` (2, 4 or 8) waves of a
 // workgroup share every decoded block, each wave with two tiles of its own.  A workgroup takes
-// a run of documents of one request: descriptors 0 .. n_runs - 1 are the runs' first documents
+// a run of blocks of one request, across its documents in list order (first_block, end_block;
+// n_split must be 1): descriptors 0 .. n_runs - 1 are the runs' first documents
 // (request, records in `part`, `run`, `more`), the runs' other documents come after them
 // (k, v, n_tokens, info only).  The grid has no row without work: rows of workgroups that
 // exit at once, in a regular pattern, were measured to halve the workgroups a CU runs side by side.

@@ -167,11 +167,11 @@ def test_more_chunks_and_requests_than_one_launch_holds():
 
 def test_runs_of_documents_per_workgroup_across_launches_of_the_many_rows_kernel():
     """Requests with more than two query tiles go to the kernel whose waves share each decoded
-    block.  With workgroups to spare (here 2 x 270 documents x 8 heads x 2 tile groups = 8640,
-    four times the target) a workgroup takes a run of consecutive documents (4 here, the last
-    run of a request shorter) and writes one record per run; 540 documents also need two
-    launches, and no run straddles them.  Formats change inside a run and documents end
-    ragged."""
+    block.  A workgroup takes a run of the request's blocks in list order, across documents
+    (here 2 x 270 short documents of 1 to 3 blocks x 8 heads x 2 tile groups: runs of several
+    documents, cut where the blocks run out, not at document ends), and writes one record per
+    run; 540 documents also need two launches, and no run straddles them.  Formats change inside
+    a run and documents end ragged."""
     n_docs = 270
     reqs = [([3 + (7 * i + 5 * r) % 41 for i in range(n_docs)], [ALL[(i * 5 + r) % 6] for i in range(n_docs)],
              40 - 7 * r) for r in range(2)]
@@ -180,10 +180,11 @@ def test_runs_of_documents_per_workgroup_across_launches_of_the_many_rows_kernel
 
 @pytest.mark.parametrize("n_q,n_qh,H", [(12, 4, 1), (40, 4, 1), (9, 32, 2)])
 def test_many_rows_kernel_with_token_splits(n_q, n_qh, H):
-    """Few, long documents and many query rows: the call has few workgroups, so the host cuts
-    the tokens into splits (128-token splits here) and every (document, split) writes its own
-    record for the tile-wise merge; 3, 10 and 9 query tiles take workgroups of 2, 8 and 8 waves.
-    The second document's last block is ragged and its last split short."""
+    """Few, long documents and many query rows: the call has few workgroups, so the runs are
+    the shortest there are (8 blocks = 128 tokens) and most of them start and end inside a
+    document; every run writes its own record for the tile-wise merge; 3, 10 and 9 query tiles
+    take workgroups of 2, 8 and 8 waves.  The second document's last block is ragged and the
+    last run of each request short."""
     reqs = [([2500, 700], [B.PREC_INT4, B.PREC_INT8], n_q), ([1333], [B.PREC_16], n_q)]
     run_case((1, H, 128), reqs, 0, n_qh, 0.07, 110 + n_q)
 
