@@ -97,8 +97,12 @@ int ha_rag_create(const ha_rag_config *cfg, ha_rag_ctx **out)
             }
             c->copy_streams.push_back(s);
         }
-        // the library's set-up on this device: where its static scratch array lives here
-        if (attend_static_scratch(nullptr, &g_create_err) != HA_RAG_OK) {
+        // the library's set-up on this device: where its static scratch array lives here, and
+        // the LDS allowance of the eight-wave attention kernel
+        hipError_t pe = hipSuccess;
+        if (attend_static_scratch(nullptr, &g_create_err) != HA_RAG_OK ||
+            (pe = ha_rag::prepare_k6_shared()) != hipSuccess) {
+            if (pe != hipSuccess) g_create_err = std::string("hipFuncSetAttribute(k6_attend_shared): ") + hipGetErrorString(pe);
             for (hipStream_t t : c->copy_streams) (void)hipStreamDestroy(t);
             delete c;
             return HA_RAG_EHIP;

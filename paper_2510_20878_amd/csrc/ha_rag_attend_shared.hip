@@ -403,6 +403,24 @@ __global__ void __launch_bounds__(64 * W, 2) k6_attend_shared(const K6Params p)
     }
 }
 
+// The eight-wave build takes 128 KiB of LDS per workgroup; more than 64 KiB has to be asked for
+// once per device.  Called when a context is created on the device (not from inside a launch
+// that a caller may be capturing into a graph) and, as a fallback, before the first such launch.
+hipError_t prepare_k6_shared()
+{
+    static std::atomic<uint64_t> asked{0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (asked.load(std::memory_order_acquire) >> dev & 1u) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k6_attend_shared<8>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)(2u * 8u * kSharedBlockLds));
+    if (e != hipSuccess) return e;
+    asked.fetch_or(1ull << dev, std::memory_order_release);
+    return hipSuccess;
+}
+
 hipError_t launch_k6_shared(K6Params &p, uint32_t n_runs, uint32_t waves, hipStream_t stream)
 {
     if (p.n_chunks == 0) return hipSuccess;
@@ -450,18 +468,8 @@ hipError_t launch_k6_shared(K6Params &p, uint32_t n_runs, uint32_t waves, hipStr
     if (waves == 2u) hipLaunchKernelGGL((k6_attend_shared<2>), grid, dim3(128), lds_bytes, stream, p);
     else if (waves == 4u) hipLaunchKernelGGL((k6_attend_shared<4>), grid, dim3(256), lds_bytes, stream, p);
     else {
-        // more than 64 KiB of LDS per workgroup has to be asked for once per device
-        static std::atomic<uint64_t> asked{0};
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
+        const hipError_t e = prepare_k6_shared();  // done at ha_rag_create; a no-op from then on
         if (e != hipSuccess) return e;
-        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-        if (!(asked.load(std::memory_order_acquire) >> dev & 1u)) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k6_attend_shared<8>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-            if (e != hipSuccess) return e;
-            asked.fetch_or(1ull << dev, std::memory_order_release);
-        }
         hipLaunchKernelGGL((k6_attend_shared<8>), grid, dim3(512), lds_bytes, stream, p);
     }
     return hipGetLastError();

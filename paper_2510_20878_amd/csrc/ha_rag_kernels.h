@@ -169,6 +169,8 @@ hipError_t launch_k6(K6Params &p, hipStream_t stream);
 // (k, v, n_tokens, info only).  The grid has no row without work: rows of workgroups that
 // exit at once, in a regular pattern, were measured to halve the workgroups a CU runs side by side.
 hipError_t launch_k6_shared(K6Params &p, uint32_t n_runs, uint32_t waves, hipStream_t stream);
+// Once per device, before the first launch of the eight-wave build (its LDS allowance).
+hipError_t prepare_k6_shared();
 // Merges the partial results of each request into out and lse.
 hipError_t launch_k7(K7Params &p, hipStream_t stream);
 

@@ -295,18 +295,21 @@ def test_attend_over_pool_chunks_in_hbm_and_in_pinned_memory():
     ctx.destroy()
 
 
-def test_attend_can_be_captured_in_a_hip_graph_and_replayed():
+@pytest.mark.parametrize("n_q", [2, 40])
+def test_attend_can_be_captured_in_a_hip_graph_and_replayed(n_q):
     """The call only launches kernels, so a per-layer loop can be recorded once and replayed;
-    every replay is checked against the eager result, with eager work in between."""
+    every replay is checked against the eager result, with eager work in between.  2 query
+    tokens take the kernel of at most two query tiles, 40 the many-rows kernel with eight
+    waves (whose LDS allowance was set when the context was created, not inside the capture)."""
     ctx, shape, g, precs, tokens, packs, ORC, keep = _pool_case()
     L, H, D = shape
     n_qh, scale = 8, 0.09
     devs = [dev_u8(p) for p in packs]
-    qw = q_words(2, n_qh, D, 500)
+    qw = q_words(n_q, n_qh, D, 500)
     q_d = torch.from_numpy(qw.view(np.int16)).cuda()
-    outs = [torch.zeros((2, n_qh, D), dtype=torch.float32, device="cuda") for _ in range(L)]
-    lses = [torch.zeros((2, n_qh), dtype=torch.float32, device="cuda") for _ in range(L)]
-    per_layer = [[([(devs[i], tokens[i], precs[i], g) for i in (1, 3, 0, 4)], q_d, outs[l], lses[l], 2)]
+    outs = [torch.zeros((n_q, n_qh, D), dtype=torch.float32, device="cuda") for _ in range(L)]
+    lses = [torch.zeros((n_q, n_qh), dtype=torch.float32, device="cuda") for _ in range(L)]
+    per_layer = [[([(devs[i], tokens[i], precs[i], g) for i in (1, 3, 0, 4)], q_d, outs[l], lses[l], n_q)]
                  for l in range(L)]
     nb = ctx.attend_workspace_bytes(per_layer[0], n_qh)
     ws = torch.zeros(nb // 4, dtype=torch.float32, device="cuda")
