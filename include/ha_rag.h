@@ -435,7 +435,8 @@ int ha_rag_attend_packed(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks,
  * library's device code (each GPU the library runs on holds its own copy until the process
  * ends; its address on the current device is looked up once, in ha_rag_create or at the first
  * call on that device).  The call allocates nothing, neither on the device nor on the host: its
- * plan lives on the stack, which bounds what one call may hold.
+ * plan lives on the stack (about 100 KiB with the launch descriptors), which bounds what one
+ * call may hold.
  * ENOSPC, before anything is enqueued, for more than HA_RAG_ATTEND_STATIC_MAX_REQUESTS requests,
  * more than HA_RAG_ATTEND_STATIC_MAX_DOCS documents (a whole chunk, or a keys-only chunk with its
  * values-only partner, that holds tokens), or lists whose partial results
