@@ -601,7 +601,8 @@ def run_attend(args, B, wl, torch):
             set_chunks[-1].append(chunks)
             reqs.append((chunks, q[r], out[r], lse[r], n_q))
         sets.append(ctx.attend_lists(reqs))
-    ws_bytes = ctx.attend_workspace_bytes(sets[0], n_qh)
+    # what a call needs depends on the order of its documents' formats: size for the largest
+    ws_bytes = max(ctx.attend_workspace_bytes(s, n_qh) for s in sets)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     scale = D ** -0.5
     packed_bytes = sum(ctx.chunk_bytes(prec_of(B, b), T) for b in mix) * R

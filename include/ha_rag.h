@@ -421,8 +421,9 @@ typedef struct ha_rag_attend_request {
  * ha_rag_attend_workspace_bytes returns for the same lists (it holds partial results and
  * may be reused by the next call on the same stream); ENOSPC if smaller.
  * EFORMAT unless head_dim is 128.
- * Like ha_rag_load_packed the call only launches kernels on `stream`: one per 416 documents
- * plus one per 64 requests. */
+ * Like ha_rag_load_packed the call only launches kernels on `stream`: one per 480 runs of
+ * blocks (a workgroup's share of a request: a piece of a document, or for requests of many
+ * query rows a range of blocks across documents) plus one per 64 requests. */
 int ha_rag_attend_packed(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks,
                          const ha_rag_attend_request *reqs, uint32_t n_reqs, uint32_t layer,
                          uint32_t n_q_heads, float sm_scale, void *workspace,

@@ -41,22 +41,23 @@ struct Doc {
 
 struct Plan {               // one request
     uint32_t first_doc = 0, n_docs = 0;  // its documents that hold tokens
-    uint32_t n_split = 1, n_mt = 1, max_blocks = 0;
+    uint32_t n_mt = 1;
     uint32_t shared = 0;       // more than two query tiles: the kernel whose waves share each decoded block
-    uint32_t run_blocks = 0;   // shared kernel: layout blocks per workgroup (a run of blocks across documents)
-    uint64_t all_blocks = 0;   // shared kernel: layout blocks of all its documents
-    uint32_t n_runs = 0;       // records per (KV head, split, tile): runs, or documents of the other kernel
+    uint32_t run_blocks = 0;   // layout blocks per run (what one workgroup takes)
+    uint64_t all_blocks = 0;   // layout blocks of all its documents
+    uint32_t n_runs = 0;       // records per (KV head, tile)
     uint64_t part_floats = 0;  // offset of its records in the workspace
 };
 
-// workgroups per (document or run, KV head, split) of a request
+// workgroups per (run, KV head) of a request
 uint32_t tile_groups(const Plan &pl, uint32_t waves)
 {
     return pl.shared ? (pl.n_mt + 2u * waves - 1u) / (2u * waves) : (pl.n_mt + 1u) / 2u;
 }
 
-// A run: the blocks one workgroup of the shared kernel takes, a range of the request's blocks in
-// list order that may start and end inside a document.
+// A run: the blocks one workgroup takes, a range of the request's blocks in list order.  For the
+// shared kernel it may start and end inside a document and span several; for the kernel of at
+// most two query tiles it is a piece of one document.
 struct Run {
     uint32_t doc, first_block;  // first document (index into the request's documents) and block in it
     uint32_t n_docs, end_block; // documents touched; end of the range in the last of them
@@ -70,6 +71,18 @@ bool next_run(const Plan &pl, const Doc *docs, uint32_t &doc, uint32_t &blk, Run
     if (doc >= pl.n_docs) return false;
     out->doc = doc;
     out->first_block = blk;
+    if (!pl.shared) {  // equal pieces of one document, none longer than run_blocks
+        const uint32_t nb = (docs[doc].n_tokens + 15u) / 16u;
+        const uint32_t n = (nb + pl.run_blocks - 1u) / pl.run_blocks, len = (nb + n - 1u) / n;
+        out->n_docs = 1;
+        out->end_block = nb - blk > len ? blk + len : nb;
+        blk = out->end_block;
+        if (blk == nb) {
+            ++doc;
+            blk = 0;
+        }
+        return true;
+    }
     out->n_docs = 0;
     uint32_t left = pl.run_blocks;
     for (;;) {
@@ -102,7 +115,7 @@ uint32_t count_runs(const Plan &pl, const Doc *docs)
 int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_attend_request *reqs,
                 uint32_t n_reqs, uint32_t n_q_heads, Plan *plans, Fixed<Doc> *docs,
                 Fixed<uint32_t> open_k, Fixed<uint32_t> open_v, uint64_t *floats,
-                uint32_t *split_blocks, uint32_t *shared_waves, bool need_buffers)
+                uint32_t *shared_waves, bool need_buffers)
 {
     if (!c || !reqs || n_reqs == 0 || n_reqs > HA_RAG_MAX_ATTEND_REQUESTS) return HA_RAG_EINVAL;
     if (c->cfg.head_dim != kAttendHeadDim) return HA_RAG_EFORMAT;
@@ -124,7 +137,6 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
         pl.first_doc = (uint32_t)docs->size();
         pl.n_mt = (rq.n_q * G + 15u) / 16u;
         pl.shared = pl.n_mt > 2u;
-        uint32_t max_tokens = 0;
         open_k.clear();
         open_v.clear();
         size_t next_k = 0, next_v = 0;  // first entries of open_k / open_v not yet matched
@@ -169,11 +181,9 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
                 (is_k ? d.k_step : d.v_step) = H;
                 d.info |= is_k ? fmt : fmt << 8;
             }
-            if (pc.n_tokens > max_tokens) max_tokens = pc.n_tokens;
         }
         if (next_k != open_k.size() || next_v != open_v.size()) return HA_RAG_EINVAL;  // keys without values or the reverse
         pl.n_docs = (uint32_t)docs->size() - pl.first_doc;
-        pl.max_blocks = (max_tokens + 15u) / 16u;
         n_chunks += rq.n_chunks;
     }
     // The shared kernel runs with as many waves (two tiles each) as the call's largest request
@@ -183,39 +193,42 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
         if (plans[r].shared && plans[r].n_mt > most_mt) most_mt = plans[r].n_mt;
     const uint32_t waves = most_mt > 8u ? 8u : most_mt > 4u ? 4u : 2u;
     *shared_waves = waves;
-    // Tokens per workgroup: as many as possible (every workgroup pays for fetching the queries
-    // and for writing a record), but fine enough that the launch fills the chip a few times
-    // over, since workgroups of one size finish in rounds.
-    uint32_t sb = kAttendMaxSplitBlocks;
-    uint64_t groups = 0;
-    for (;; sb >>= 1) {
-        groups = 0;
-        for (uint32_t r = 0; r < n_reqs; ++r) {
-            const Plan &pl = plans[r];
-            if (!pl.shared) groups += (uint64_t)pl.n_docs * H * ((pl.max_blocks + sb - 1u) / sb) * tile_groups(pl, waves);
-        }
-        if (groups >= kAttendTargetGroups || sb == kAttendMinSplitBlocks) break;
-    }
-    *split_blocks = sb;
-    // A workgroup of the shared kernel takes a run of the request's blocks in list order, across
-    // document boundaries, and writes one record per run (records rival the packed bytes once a
-    // request has hundreds of query rows; equal runs also finish together whatever the documents'
-    // lengths).  Workgroups of one size finish in rounds of as many as the chip holds side by
-    // side, so a launch takes rounds x blocks per run: the longest run with the least of that
-    // is taken; a run is at least kAttendMinSplitBlocks long.  Token splits do not apply here.
-    const uint64_t side_by_side = (uint64_t)kChipCUs * (8u / waves);  // two waves per SIMD: eight per CU
-    uint64_t most_blocks = 0;
+    // A workgroup takes a run of its request's blocks and writes one record per query tile for
+    // it.  Requests of at most two query tiles: a run is a piece of one document, as long as
+    // possible (every workgroup pays for fetching the queries and for writing a record), but
+    // short enough that the launch fills the chip a few times over, since the hardware then
+    // evens out what documents of different formats and lengths take.
     for (uint32_t r = 0; r < n_reqs; ++r) {
         Plan &pl = plans[r];
-        if (!pl.shared) continue;
         pl.all_blocks = 0;
         for (uint32_t i = 0; i < pl.n_docs; ++i) pl.all_blocks += ((*docs)[pl.first_doc + i].n_tokens + 15u) / 16u;
-        if (pl.all_blocks > most_blocks) most_blocks = pl.all_blocks;
     }
+    uint32_t piece = kAttendMaxRunBlocks;
+    for (;; piece >>= 1) {
+        uint64_t groups = 0;
+        for (uint32_t r = 0; r < n_reqs; ++r) {
+            const Plan &pl = plans[r];
+            if (pl.shared) continue;
+            uint64_t runs = 0;
+            for (uint32_t i = 0; i < pl.n_docs; ++i)
+                runs += (((*docs)[pl.first_doc + i].n_tokens + 15u) / 16u + piece - 1u) / piece;
+            groups += runs * H * tile_groups(pl, waves);
+        }
+        if (groups >= kAttendTargetGroups || piece == kAttendMinRunBlocks) break;
+    }
+    // The shared kernel: a run crosses document boundaries (records rival the packed bytes once
+    // a request has hundreds of query rows; equal runs also finish together whatever the
+    // documents' lengths).  Workgroups of one size finish in rounds of as many as the chip holds
+    // side by side, so a launch takes rounds x blocks per run: the longest run with the least
+    // of that is taken; a run is at least kAttendMinRunBlocks long.
+    const uint64_t side_by_side = (uint64_t)kChipCUs * (8u / waves);  // two waves per SIMD: eight per CU
+    uint64_t most_blocks = 0;
+    for (uint32_t r = 0; r < n_reqs; ++r)
+        if (plans[r].shared && plans[r].all_blocks > most_blocks) most_blocks = plans[r].all_blocks;
     uint64_t run_blocks = most_blocks, least = ~0ull;
     for (uint64_t n = 1; n <= most_blocks; ++n) {  // n runs for the largest request
         const uint64_t len = (most_blocks + n - 1u) / n;
-        if (n > 1 && len < kAttendMinSplitBlocks) break;
+        if (n > 1 && len < kAttendMinRunBlocks) break;
         uint64_t wgs = 0;
         for (uint32_t r = 0; r < n_reqs; ++r) {
             const Plan &pl = plans[r];
@@ -230,16 +243,10 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
     }
     for (uint32_t r = 0; r < n_reqs; ++r) {
         Plan &pl = plans[r];
-        if (pl.shared) {
-            pl.n_split = 1;
-            pl.run_blocks = run_blocks > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)(run_blocks ? run_blocks : 1u);
-            pl.n_runs = count_runs(pl, docs->data + pl.first_doc);
-        } else {
-            pl.n_split = pl.max_blocks ? (pl.max_blocks + sb - 1u) / sb : 1u;
-            pl.n_runs = pl.n_docs;
-        }
+        pl.run_blocks = !pl.shared ? piece : run_blocks > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)(run_blocks ? run_blocks : 1u);
+        pl.n_runs = count_runs(pl, docs->data + pl.first_doc);
         pl.part_floats = total;
-        total += (uint64_t)pl.n_runs * H * pl.n_split * pl.n_mt * kAttendRecFloats;
+        total += (uint64_t)pl.n_runs * H * pl.n_mt * kAttendRecFloats;
     }
     if (total * 4ull > (1ull << 40)) return HA_RAG_EINVAL;
     *floats = total;
@@ -281,9 +288,9 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
                   void *stream, uint64_t *need = nullptr)
 {
     uint64_t floats = 0;
-    uint32_t split_blocks = 0, waves = 2;
+    uint32_t waves = 2;
     int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, ps.plans, &ps.docs, ps.open_k, ps.open_v,
-                         &floats, &split_blocks, &waves, true);
+                         &floats, &waves, true);
     if (rc) return rc;
     const Plan *plans = ps.plans;
     const Fixed<Doc> &docs = ps.docs;
@@ -303,78 +310,70 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
         q->n_q_heads = n_q_heads;
         q->layer = layer;
         q->scale_log2 = sm_scale * 1.44269504088896341f;
-        q->split_blocks = split_blocks;
     }
-    auto fill = [&](K6Chunk &d, const ha_rag_attend_request &rq, const Plan &pl, const Doc &doc, uint32_t run_no) {
-        d.k = doc.k + (uint64_t)(doc.k_first + layer * doc.k_step) * doc.k_tile;
-        d.v = doc.v + (uint64_t)(doc.v_first + layer * doc.v_step) * doc.v_tile;
-        d.q = static_cast<const uint16_t *>(rq.q);
-        d.part = ws + pl.part_floats + (uint64_t)run_no * H * pl.n_split * pl.n_mt * kAttendRecFloats;
-        d.n_tokens = doc.n_tokens;
-        d.info = doc.info;
-        d.n_q = rq.n_q;
-        d.n_split = pl.n_split;
-        d.run = 1;
-        d.more = 0;
-        d.first_block = d.end_block = 0;
-    };
-    for (uint32_t r = 0; r < n_reqs; ++r) {
-        const Plan &pl = plans[r];
-        if (pl.shared) continue;
-        for (uint32_t i = 0; i < pl.n_docs; ++i) {
-            fill(kp.c[kp.n_chunks++], reqs[r], pl, docs[pl.first_doc + i], i);
-            if (kp.n_chunks == kAttendLaunchChunks) {
-                HIPCHK(c, launch_k6(kp, st));
-                kp.n_chunks = 0;
-            }
-        }
-    }
-    if (kp.n_chunks) HIPCHK(c, launch_k6(kp, st));
-    // The shared kernel's launch lists the runs' first documents, then the other documents run
-    // by run.  A run never straddles two launches: first count the runs that fit, then fill.
+    auto doc_k = [&](const Doc &doc) { return doc.k + (uint64_t)(doc.k_first + layer * doc.k_step) * doc.k_tile; };
+    auto doc_v = [&](const Doc &doc) { return doc.v + (uint64_t)(doc.v_first + layer * doc.v_step) * doc.v_tile; };
+    // A launch lists its runs (one grid row each), then the runs' further documents run by run.
+    // A run never straddles two launches: first count the runs that fit, then fill.
     struct RunPos {
         uint32_t r, doc, blk, run_no;  // request, start of the next run in it, number of that run
     };
-    auto settle = [&](RunPos &p) {  // moves p to the next run there is; false at the end
-        while (p.r < n_reqs && (!plans[p.r].shared || p.doc >= plans[p.r].n_docs)) {
-            ++p.r;
-            p.doc = p.blk = p.run_no = 0;
+    for (uint32_t sh = 0; sh < 2u; ++sh) {  // the kernel of at most two tiles, then the shared one
+        K6Params &kq = sh ? ks : kp;
+        auto settle = [&](RunPos &p) {  // moves p to the next run there is; false at the end
+            while (p.r < n_reqs && (plans[p.r].shared != sh || p.doc >= plans[p.r].n_docs)) {
+                ++p.r;
+                p.doc = p.blk = p.run_no = 0;
+            }
+            return p.r < n_reqs;
+        };
+        auto take = [&](RunPos &p, Run *run) {  // the run at p; p moves behind it
+            const Plan &pl = plans[p.r];
+            next_run(pl, docs.data + pl.first_doc, p.doc, p.blk, run);
+            ++p.run_no;
+        };
+        RunPos at = {0, 0, 0, 0};
+        while (settle(at)) {
+            uint32_t n_runs = 0, n_more = 0;
+            for (RunPos p = at; settle(p);) {
+                Run run;
+                take(p, &run);
+                if ((uint64_t)(K6Params::docs_behind(n_runs + 1u) + n_more + run.n_docs - 1u) > kAttendMaxDocs) break;
+                ++n_runs;
+                n_more += run.n_docs - 1u;
+            }
+            kq.n_chunks = n_runs;
+            kq.d_first = K6Params::docs_behind(n_runs);
+            uint32_t later = kq.d_first;  // where the next run's further documents go
+            for (uint32_t k = 0; k < n_runs; ++k) {
+                settle(at);
+                const Plan &pl = plans[at.r];
+                const ha_rag_attend_request &rq = reqs[at.r];
+                const uint32_t run_no = at.run_no;
+                Run run;
+                take(at, &run);
+                const Doc &first = docs[pl.first_doc + run.doc];
+                K6Chunk &d = kq.c[k];
+                d.k = doc_k(first);
+                d.v = doc_v(first);
+                d.q = static_cast<const uint16_t *>(rq.q);
+                d.part = ws + pl.part_floats + (uint64_t)run_no * H * pl.n_mt * kAttendRecFloats;
+                d.n_tokens = first.n_tokens;
+                d.info = first.info;
+                d.n_q = rq.n_q;
+                d.pad = 0;
+                d.run = run.n_docs;
+                d.more = later;
+                d.first_block = run.first_block;
+                d.end_block = run.end_block;
+                for (uint32_t i = 1; i < run.n_docs; ++i) {
+                    const Doc &doc = docs[pl.first_doc + run.doc + i];
+                    kq.d[later++] = K6Doc{doc_k(doc), doc_v(doc), doc.n_tokens, doc.info};
+                }
+            }
+            kq.d_end = later;
+            HIPCHK(c, sh ? launch_k6_shared(kq, waves, st) : launch_k6(kq, st));
         }
-        return p.r < n_reqs;
-    };
-    auto take = [&](RunPos &p, Run *run) {  // the run at p; p moves behind it
-        const Plan &pl = plans[p.r];
-        next_run(pl, docs.data + pl.first_doc, p.doc, p.blk, run);
-        ++p.run_no;
-    };
-    RunPos at = {0, 0, 0, 0};
-    while (settle(at)) {
-        uint32_t n_runs = 0, n_all = 0;
-        for (RunPos p = at; settle(p);) {
-            Run run;
-            take(p, &run);
-            if (n_all + run.n_docs > kAttendLaunchChunks) break;
-            ++n_runs;
-            n_all += run.n_docs;
-        }
-        uint32_t later = n_runs;  // where the next run's other documents go
-        for (uint32_t k = 0; k < n_runs; ++k) {
-            settle(at);
-            const Plan &pl = plans[at.r];
-            const uint32_t run_no = at.run_no, r = at.r;
-            Run run;
-            take(at, &run);
-            K6Chunk &head = ks.c[k];
-            fill(head, reqs[r], pl, docs[pl.first_doc + run.doc], run_no);
-            head.run = run.n_docs;
-            head.more = later;
-            head.first_block = run.first_block;
-            head.end_block = run.end_block;
-            for (uint32_t d = 1; d < run.n_docs; ++d)
-                fill(ks.c[later++], reqs[r], pl, docs[pl.first_doc + run.doc + d], run_no);
-        }
-        ks.n_chunks = n_all;
-        HIPCHK(c, launch_k6_shared(ks, n_runs, waves, st));
     }
 
     K7Params mp{};
@@ -387,8 +386,7 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
         d.lse = reqs[r].lse;
         d.n_q = reqs[r].n_q;
         d.n_chunks = plans[r].n_runs;
-        d.n_split = plans[r].n_split;
-        d.pad = 0;
+        d.pad[0] = d.pad[1] = 0;
         if (mp.n_reqs == kMaxMergeReqs) {
             HIPCHK(c, launch_k7(mp, st));
             mp.n_reqs = 0;
@@ -478,9 +476,9 @@ int ha_rag_attend_workspace_bytes(ha_rag_ctx *c, const ha_rag_packed_chunk *chun
     HeapPlanStore hs(reqs, n_reqs);
     PlanStore ps = hs.store();
     uint64_t floats = 0;
-    uint32_t split_blocks = 0, waves = 0;
+    uint32_t waves = 0;
     int rc = plan_attend(c, chunks, reqs, n_reqs, n_q_heads, ps.plans, &ps.docs, ps.open_k, ps.open_v,
-                         &floats, &split_blocks, &waves, false);
+                         &floats, &waves, false);
     if (rc) return rc;
     *bytes = (size_t)(floats * 4ull);
     return HA_RAG_OK;
@@ -554,9 +552,9 @@ int ha_rag_attend_chunks_workspace_bytes(ha_rag_ctx *c, const uint64_t *ids,
     HeapPlanStore hs(reqs, n_reqs);
     PlanStore ps = hs.store();
     uint64_t floats = 0;
-    uint32_t split_blocks = 0, waves = 0;
+    uint32_t waves = 0;
     rc = plan_attend(c, chunks.data(), reqs, n_reqs, n_q_heads, ps.plans, &ps.docs, ps.open_k, ps.open_v,
-                     &floats, &split_blocks, &waves, false);
+                     &floats, &waves, false);
     if (rc) return rc;
     *bytes = (size_t)(floats * 4ull);
     return HA_RAG_OK;

@@ -112,7 +112,7 @@ __device__ __forceinline__ void wave_lds_sync()
 
 // the launch-wide scalars a workgroup needs, read from the argument buffer once
 struct AttendHdr {
-    uint32_t n_kv_heads, n_q_heads, layer, split_blocks;
+    uint32_t n_kv_heads, n_q_heads, layer;
     float scale_log2;
 };
 

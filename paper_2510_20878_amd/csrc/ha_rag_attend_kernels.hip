@@ -2,12 +2,12 @@
 // building the BF16 cache first (the prefill of Sec. 2.1 consumes the concatenated chunk KV;
 // here the consumer reads the compressed chunks of Sec. 2.2 itself).
 //
-//  k6_attend_partial   one workgroup of kAttendWaves waves per (chunk, KV head, token split, group of
-//      query rows); the waves take the layout blocks in turn: each decodes K and V blocks to
+//  k6_attend_partial   one workgroup of kAttendWaves waves per (run of blocks of one document, KV
+//      head, group of query rows); the waves take the layout blocks in turn: each decodes K and V blocks to
 //      BF16 in registers (the values a load would write), scores them with MFMA and keeps a
 //      running softmax; the waves' results are summed in LDS into one unnormalised partial result
 //  k7_attend_merge     one workgroup per (query token, query head): merges the partial
-//      results of the request's chunks and splits into out and the log-sum-exp
+//      results of the request's runs into out and the log-sum-exp
 //
 // head_dim 128 only: a layout block is then 16 tokens x 128 dims, and lane (a = lane/16,
 // o = lane%16) of the wave that reads it holds, in plane j, token 4j + a, dims 8o .. 8o+7.
@@ -42,7 +42,7 @@ struct AttendLds {
 // NARROW: the instance belongs to the kernel that runs three waves per SIMD (168 registers).
 template <uint32_t KP, uint32_t VP, int MTW, bool NARROW>
 __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c,
-                                            uint32_t h, uint32_t s, uint32_t mtg, uint8_t *lds_all,
+                                            uint32_t h, uint32_t mtg, uint8_t *lds_all,
                                             float (*sm)[MTW * 16], float (*sl)[MTW * 16])
 {
     typedef Fmt<KP> FK;
@@ -61,21 +61,9 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c
     gbytes vt = (gbytes)c.v + (uint64_t)h * ((uint64_t)nblk * (FV::kPayload + vmeta_blk) + (VP == kGSE8 ? 16u : 0u));
     gbytes kmeta = kt + (uint64_t)nblk * FK::kPayload;
     gbytes vmeta = vt + (uint64_t)nblk * FV::kPayload;
-    gfloats rec0 = (gfloats)c.part + (uint64_t)((h * c.n_split + s) * n_mt) * kAttendRecFloats;
+    gfloats rec0 = (gfloats)c.part + (uint64_t)(h * n_mt) * kAttendRecFloats;
 
-    const uint32_t b0 = s * p.split_blocks;
-    const uint32_t b1 = b0 + p.split_blocks < nblk ? b0 + p.split_blocks : nblk;
-    if (b0 >= b1) {  // nothing of this chunk in this split: empty records (l = 0)
-        if (threadIdx.x < MTW * 16u) {
-            const uint32_t mtile = mtg * MTW + (threadIdx.x >> 4);
-            if (mtile < n_mt) {
-                gfloats rec = rec0 + (uint64_t)mtile * kAttendRecFloats;
-                rec[2048 + n_] = neg_inf();
-                rec[2048 + 16 + n_] = 0.0f;
-            }
-        }
-        return;
-    }
+    const uint32_t b0 = c.first_block, b1 = c.end_block;  // the run: blocks of this one document
 
     int kbase = 0, ktop = 0, vbase = 0, vtop = 0;
     if (KP == kGSE8) {
@@ -142,7 +130,7 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c
         if (FV::kMeta) r.vm = ldg16(vmeta + ((uint64_t)b * vmeta_blk + ((lane * 8u) >> vgsh) * 16u));
     };
 
-    // the waves of the workgroup take the blocks of the split in turn; each wave fetches its
+    // the waves of the workgroup take the blocks of the run in turn; each wave fetches its
     // next block before it works on the current one
     auto process = [&](uint32_t b, const BlockRegs<KP, VP> &cur) {
         const bool ragged = b * 16u + 16u > T;  // only the chunk's last block can be
@@ -244,7 +232,7 @@ __device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c
                                      : (kWordsKV <= 2 ? 4 : 3);
     BlockRegs<KP, VP> ring[kStages];
     uint32_t b = b0 + wave;
-    // Every load below is issued whether or not its block exists (a block past the split's end
+    // Every load below is issued whether or not its block exists (a block past the run's end
     // is replaced by one this wave has already fetched, a hit in the cache): with a branch
     // around the loads the compiler has to wait as if they had not been issued, which then
     // waits for part of the block just requested - a full memory latency per block.
@@ -328,26 +316,26 @@ blocks_done:
 // narrow formats leaves out every pair with a 16-bit side: those need more registers than three
 // waves per SIMD leave.
 template <uint32_t KP, uint32_t VP, int MTW, bool NARROW>
-__device__ __forceinline__ void attend_pair(const AttendHdr &hdr, const K6Chunk &c, uint32_t h, uint32_t s,
+__device__ __forceinline__ void attend_pair(const AttendHdr &hdr, const K6Chunk &c, uint32_t h,
                                             uint32_t mtg, uint8_t *lds, float (*sm)[MTW * 16],
                                             float (*sl)[MTW * 16])
 {
     if constexpr (!(NARROW && (KP == kP16 || VP == kP16)))
-        attend_unit<KP, VP, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl);
+        attend_unit<KP, VP, MTW, NARROW>(hdr, c, h, mtg, lds, sm, sl);
 }
 
 template <uint32_t KP, int MTW, bool NARROW>
-__device__ __forceinline__ void attend_values(const AttendHdr &hdr, const K6Chunk &c, uint32_t h, uint32_t s,
+__device__ __forceinline__ void attend_values(const AttendHdr &hdr, const K6Chunk &c, uint32_t h,
                                               uint32_t mtg, uint8_t *lds, float (*sm)[MTW * 16],
                                               float (*sl)[MTW * 16])
 {
     switch ((c.info >> 8) & 0xFu) {
-    case kP16: attend_pair<KP, kP16, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
-    case kInt8: attend_pair<KP, kInt8, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
-    case kInt4: attend_pair<KP, kInt4, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
-    case kE4M3: attend_pair<KP, kE4M3, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
-    case kE5M2: attend_pair<KP, kE5M2, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
-    default: attend_pair<KP, kGSE8, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    case kP16: attend_pair<KP, kP16, MTW, NARROW>(hdr, c, h, mtg, lds, sm, sl); break;
+    case kInt8: attend_pair<KP, kInt8, MTW, NARROW>(hdr, c, h, mtg, lds, sm, sl); break;
+    case kInt4: attend_pair<KP, kInt4, MTW, NARROW>(hdr, c, h, mtg, lds, sm, sl); break;
+    case kE4M3: attend_pair<KP, kE4M3, MTW, NARROW>(hdr, c, h, mtg, lds, sm, sl); break;
+    case kE5M2: attend_pair<KP, kE5M2, MTW, NARROW>(hdr, c, h, mtg, lds, sm, sl); break;
+    default: attend_pair<KP, kGSE8, MTW, NARROW>(hdr, c, h, mtg, lds, sm, sl); break;
     }
 }
 
@@ -363,7 +351,7 @@ __global__ void __launch_bounds__(64 * kAttendWaves, NARROW ? 3 : 2) k6_attend_p
     __shared__ float sm[kAttendWaves][MTW * 16], sl[kAttendWaves][MTW * 16];
     // the whole descriptor and the header at once, before anything depends on a part of them
     K6Chunk c = p.c[blockIdx.y];
-    AttendHdr hdr = {p.n_kv_heads, p.n_q_heads, p.layer, p.split_blocks, p.scale_log2};
+    AttendHdr hdr = {p.n_kv_heads, p.n_q_heads, p.layer, p.scale_log2};
     pin(c.k);
     pin(c.v);
     pin(c.q);
@@ -371,69 +359,87 @@ __global__ void __launch_bounds__(64 * kAttendWaves, NARROW ? 3 : 2) k6_attend_p
     pin(c.n_tokens);
     pin(c.info);
     pin(c.n_q);
-    pin(c.n_split);
+    pin(c.first_block);
+    pin(c.end_block);
     pin(hdr.n_kv_heads);
     pin(hdr.n_q_heads);
     pin(hdr.layer);
-    pin(hdr.split_blocks);
     pin(hdr.scale_log2);
     const uint32_t G = hdr.n_q_heads / hdr.n_kv_heads;
     const uint32_t n_mt = (c.n_q * G + 15u) >> 4;
     const uint32_t n_mtg = (n_mt + MTW - 1u) / MTW;
     const uint32_t u = blockIdx.x;
-    if (u >= hdr.n_kv_heads * c.n_split * n_mtg) return;  // the grid is as wide as the widest chunk
+    if (u >= hdr.n_kv_heads * n_mtg) return;  // the grid is as wide as the widest run
     const uint32_t mtg = u % n_mtg;
-    const uint32_t hs = u / n_mtg;
-    const uint32_t s = hs % c.n_split, h = hs / c.n_split;
+    const uint32_t h = u / n_mtg;
     switch (c.info & 0xFu) {
-    case kP16: attend_values<kP16, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
-    case kInt8: attend_values<kInt8, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
-    case kInt4: attend_values<kInt4, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
-    case kE4M3: attend_values<kE4M3, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
-    case kE5M2: attend_values<kE5M2, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
-    default: attend_values<kGSE8, MTW, NARROW>(hdr, c, h, s, mtg, lds, sm, sl); break;
+    case kP16: attend_values<kP16, MTW, NARROW>(hdr, c, h, mtg, lds, sm, sl); break;
+    case kInt8: attend_values<kInt8, MTW, NARROW>(hdr, c, h, mtg, lds, sm, sl); break;
+    case kInt4: attend_values<kInt4, MTW, NARROW>(hdr, c, h, mtg, lds, sm, sl); break;
+    case kE4M3: attend_values<kE4M3, MTW, NARROW>(hdr, c, h, mtg, lds, sm, sl); break;
+    case kE5M2: attend_values<kE5M2, MTW, NARROW>(hdr, c, h, mtg, lds, sm, sl); break;
+    default: attend_values<kGSE8, MTW, NARROW>(hdr, c, h, mtg, lds, sm, sl); break;
     }
+}
+
+// Checks what both attention launches assume of their arguments: the runs, their further
+// documents in rows behind them, every run's block range.  *max_mt receives the most query tiles
+// of a run's request, *narrow whether no document has a 16-bit side.
+hipError_t check_k6_args(const K6Params &p, uint32_t *max_mt, bool *narrow)
+{
+    if (p.n_chunks == 0 || p.n_chunks > kAttendMaxRuns || p.n_kv_heads == 0 || p.n_q_heads % p.n_kv_heads ||
+        p.d_first != K6Params::docs_behind(p.n_chunks) || p.d_end < p.d_first || p.d_end > kAttendMaxDocs)
+        return hipErrorInvalidValue;
+    const uint32_t G = p.n_q_heads / p.n_kv_heads;
+    auto doc_ok = [&](const uint8_t *k, const uint8_t *v, uint32_t n_tokens, uint32_t info) {
+        const uint32_t kprec = info & 0xFu, kgsh = (info >> 4) & 0xFu;
+        const uint32_t vprec = (info >> 8) & 0xFu, vgsh = (info >> 12) & 0xFu;
+        if (info >> 16 || kprec > kGSE8 || vprec > kGSE8 || !k || !v || ((uintptr_t)k & 15u) ||
+            ((uintptr_t)v & 15u) || n_tokens == 0 || n_tokens > 0x7FFFFFFu)
+            return false;
+        if ((kprec == kInt4 || kprec == kInt8) && (kgsh < 5 || kgsh > 7)) return false;
+        if ((vprec == kInt4 || vprec == kInt8) && (vgsh < 5 || vgsh > 7)) return false;
+        if (kprec == kP16 || vprec == kP16) *narrow = false;
+        return true;
+    };
+    *max_mt = 1;
+    *narrow = true;
+    for (uint32_t i = p.d_first; i < p.d_end; ++i)
+        if (!doc_ok(p.d[i].k, p.d[i].v, p.d[i].n_tokens, p.d[i].info)) return hipErrorInvalidValue;
+    uint32_t next = p.d_first;  // the runs' further documents lie in the runs' order, without gaps
+    for (uint32_t i = 0; i < p.n_chunks; ++i) {
+        const K6Chunk &c = p.c[i];
+        if (!doc_ok(c.k, c.v, c.n_tokens, c.info) || c.run == 0 || !c.q || !c.part || c.n_q == 0 ||
+            ((uintptr_t)c.q & 15u) || ((uintptr_t)c.part & 15u) || (uint64_t)c.n_q * G > 0xFFFFFFull)
+            return hipErrorInvalidValue;
+        if (c.run > 1u && (c.more != next || c.run - 1u > p.d_end - next)) return hipErrorInvalidValue;
+        next += c.run - 1u;
+        // the run's block range: starts inside its first document, ends inside its last, not empty
+        const uint32_t nb_first = (c.n_tokens + 15u) >> 4;
+        const uint32_t nb_last = c.run > 1u ? (p.d[next - 1u].n_tokens + 15u) >> 4 : nb_first;
+        if (c.first_block >= nb_first || c.end_block > nb_last || c.end_block == 0 ||
+            (c.run == 1u && c.end_block <= c.first_block))
+            return hipErrorInvalidValue;
+        const uint32_t n_mt = (c.n_q * G + 15u) >> 4;
+        if (n_mt > *max_mt) *max_mt = n_mt;
+    }
+    return next == p.d_end ? hipSuccess : hipErrorInvalidValue;
 }
 
 hipError_t launch_k6(K6Params &p, hipStream_t stream)
 {
     if (p.n_chunks == 0) return hipSuccess;
-    if (p.n_chunks > kAttendLaunchChunks || p.n_kv_heads == 0 || p.n_q_heads % p.n_kv_heads ||
-        p.split_blocks < kAttendMinSplitBlocks || p.split_blocks > kAttendMaxSplitBlocks ||
-        (p.split_blocks & (p.split_blocks - 1u)))
-        return hipErrorInvalidValue;
-    const uint32_t G = p.n_q_heads / p.n_kv_heads;
     uint32_t max_mt = 1;
     bool narrow = true;  // no 16-bit side in this launch
-    for (uint32_t i = 0; i < p.n_chunks; ++i) {
-        const K6Chunk &c = p.c[i];
-        const uint32_t kprec = c.info & 0xFu, kgsh = (c.info >> 4) & 0xFu;
-        const uint32_t vprec = (c.info >> 8) & 0xFu, vgsh = (c.info >> 12) & 0xFu;
-        if (kprec > kGSE8 || vprec > kGSE8 || !c.k || !c.v || !c.q || !c.part || c.n_q == 0 ||
-            c.n_split == 0 || ((uintptr_t)c.k & 15u) || ((uintptr_t)c.v & 15u) || ((uintptr_t)c.q & 15u) ||
-            ((uintptr_t)c.part & 15u) || (uint64_t)c.n_q * G > 0xFFFFFFull || c.n_tokens > 0x7FFFFFFu)
-            return hipErrorInvalidValue;
-        if ((kprec == kInt4 || kprec == kInt8) && (kgsh < 5 || kgsh > 7)) return hipErrorInvalidValue;
-        if ((vprec == kInt4 || vprec == kInt8) && (vgsh < 5 || vgsh > 7)) return hipErrorInvalidValue;
-        // every block of the chunk must belong to one of the request's splits
-        if ((uint64_t)c.n_split * p.split_blocks * 16u < c.n_tokens) return hipErrorInvalidValue;
-        const uint32_t n_mt = (c.n_q * G + 15u) >> 4;
-        if (n_mt > max_mt) max_mt = n_mt;
-        if (kprec == kP16 || vprec == kP16) narrow = false;
-    }
-    // Two tiles (32 query rows) per workgroup is the most that still runs two waves per SIMD
-    // (241 vector registers); four tiles at one wave per SIMD measured 35 % slower than two
-    // passes of two.
+    const hipError_t e = check_k6_args(p, &max_mt, &narrow);
+    if (e != hipSuccess) return e;
+    for (uint32_t i = 0; i < p.n_chunks; ++i)
+        if (p.c[i].run != 1u) return hipErrorInvalidValue;  // this kernel's runs stay inside one document
+    // Two tiles (32 query rows) per workgroup is the most that still runs two waves per SIMD;
+    // four tiles at one wave per SIMD measured 35 % slower than two passes of two.
     p.mtw = max_mt >= 2 ? 2u : 1u;
-    uint64_t width = 0;
-    for (uint32_t i = 0; i < p.n_chunks; ++i) {
-        const K6Chunk &c = p.c[i];
-        const uint32_t n_mt = (c.n_q * G + 15u) >> 4;
-        const uint64_t w = (uint64_t)p.n_kv_heads * c.n_split * ((n_mt + p.mtw - 1u) / p.mtw);
-        if (w > width) width = w;
-    }
+    const uint64_t width = (uint64_t)p.n_kv_heads * ((max_mt + p.mtw - 1u) / p.mtw);
     if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    p.pad = 0;
     dim3 grid((uint32_t)width, p.n_chunks), block(64 * kAttendWaves);
     if (p.mtw == 2) hipLaunchKernelGGL((k6_attend_partial<2, false>), grid, block, 0, stream, p);
     else if (narrow) hipLaunchKernelGGL((k6_attend_partial<1, true>), grid, block, 0, stream, p);
@@ -444,7 +450,7 @@ hipError_t launch_k6(K6Params &p, hipStream_t stream)
 // ---------------------------------------------------------------------------
 // K7.  One workgroup per (query token, query head), made of groups of 32 threads (four dims
 // each).  The groups share the row's records between them, so that a single request with many
-// records (long chunks, fine splits) is merged in one or two rounds of loads instead of record
+// records (long chunks cut into many runs) is merged in one or two rounds of loads instead of record
 // after record; then 128 threads, one per dim, merge the groups' results through LDS.
 // ---------------------------------------------------------------------------
 constexpr uint32_t kMergeGroups = 32;  // at most: 1024 threads
@@ -462,7 +468,6 @@ __global__ void __launch_bounds__(32 * kMergeGroups) k7_attend_merge(const K7Par
     pin(r.lse);
     pin(r.n_q);
     pin(r.n_chunks);
-    pin(r.n_split);
     pin(n_kv_heads);
     pin(n_q_heads);
     const uint32_t rr = blockIdx.x;
@@ -473,14 +478,13 @@ __global__ void __launch_bounds__(32 * kMergeGroups) k7_attend_merge(const K7Par
     const uint32_t mrow = qt * G + gq, mt = mrow >> 4, ri = mrow & 15u;
     const uint32_t n_mt = (r.n_q * G + 15u) >> 4;
     const uint32_t d4 = threadIdx.x & 31u, g = threadIdx.x >> 5, n_g = blockDim.x >> 5;  // n_g >= 4
-    const uint64_t chunk_stride = (uint64_t)n_kv_heads * r.n_split * n_mt * kAttendRecFloats;
-    const float *first = r.part + ((uint64_t)(h * r.n_split) * n_mt + mt) * kAttendRecFloats;
-    const uint64_t split_stride = (uint64_t)n_mt * kAttendRecFloats;
+    const uint64_t run_stride = (uint64_t)n_kv_heads * n_mt * kAttendRecFloats;  // records are [run][head][tile]
+    const float *first = r.part + ((uint64_t)h * n_mt + mt) * kAttendRecFloats;
 
     // Group g takes records g, g + n_g, ..., four at a time: their maxima, sums and this
     // thread's four dims are fetched together (every thread of a group reads the same m and l:
     // broadcast loads), then folded into a running maximum like the blocks inside a record were.
-    const uint32_t n_units = r.n_chunks * r.n_split;  // records are [chunk][head][split][tile]
+    const uint32_t n_units = r.n_chunks;
     float m_max = neg_inf(), l_sum = 0.0f;
     f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
     for (uint32_t u0 = g; u0 < n_units; u0 += 4u * n_g) {
@@ -490,8 +494,7 @@ __global__ void __launch_bounds__(32 * kMergeGroups) k7_attend_merge(const K7Par
         for (uint32_t k = 0; k < 4; ++k) {
             const bool have = u0 + k * n_g < n_units;
             const uint32_t u = have ? u0 + k * n_g : n_units - 1u;
-            const uint32_t ci = u / r.n_split, sp = u - ci * r.n_split;
-            const float *rec = first + ci * chunk_stride + sp * split_stride;
+            const float *rec = first + u * run_stride;
             m[k] = rec[2048 + ri];
             l[k] = have ? rec[2048 + 16 + ri] : 0.0f;
             o[k] = *reinterpret_cast<const f32x4 *>(rec + ri * 128u + 4u * d4);
@@ -557,7 +560,6 @@ __global__ void __launch_bounds__(256) k7_attend_merge_tiles(const K7Params p)
     pin(r.lse);
     pin(r.n_q);
     pin(r.n_chunks);
-    pin(r.n_split);
     pin(n_kv_heads);
     pin(n_q_heads);
     const uint32_t G = n_q_heads / n_kv_heads, M = r.n_q * G;
@@ -567,10 +569,9 @@ __global__ void __launch_bounds__(256) k7_attend_merge_tiles(const K7Params p)
     const uint32_t ri = threadIdx.x >> 4, d8 = threadIdx.x & 15u;
     const uint32_t mrow = mt * 16u + ri;
     if (mrow >= M) return;  // rows without a query are not in the records either
-    const uint64_t split_stride = (uint64_t)n_mt * kAttendRecFloats;
-    const uint64_t chunk_stride = (uint64_t)n_kv_heads * r.n_split * split_stride;
-    gfloats first = (gfloats)r.part + ((uint64_t)(h * r.n_split) * n_mt + mt) * kAttendRecFloats;
-    const uint32_t n_units = r.n_chunks * r.n_split;  // records are [run][head][split][tile]
+    const uint64_t run_stride = (uint64_t)n_kv_heads * n_mt * kAttendRecFloats;  // records are [run][head][tile]
+    gfloats first = (gfloats)r.part + ((uint64_t)h * n_mt + mt) * kAttendRecFloats;
+    const uint32_t n_units = r.n_chunks;
     float m_max = neg_inf(), l_sum = 0.0f;
     f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
     for (uint32_t u0 = 0; u0 < n_units; u0 += 4u) {
@@ -580,8 +581,7 @@ __global__ void __launch_bounds__(256) k7_attend_merge_tiles(const K7Params p)
         for (uint32_t k = 0; k < 4; ++k) {  // four records under way at a time
             const bool have = u0 + k < n_units;
             const uint32_t u = have ? u0 + k : n_units - 1u;
-            const uint32_t ci = u / r.n_split, sp = u - ci * r.n_split;
-            gfloats rec = first + ci * chunk_stride + sp * split_stride;
+            gfloats rec = first + u * run_stride;
             m[k] = rec[2048 + ri];
             l[k] = have ? rec[2048 + 16 + ri] : 0.0f;
             o[k][0] = ((gquads)(rec + ri * 128u + 8u * d8))[0];
@@ -630,16 +630,14 @@ hipError_t launch_k7(K7Params &p, hipStream_t stream)
     for (uint32_t i = 0; i < p.n_reqs; ++i) {
         const K7Req &r = p.r[i];
         // a request without a token to attend to (n_chunks 0) gets zeros and lse = -inf
-        if ((r.n_chunks && !r.part) || !r.out || r.n_q == 0 || r.n_split == 0)
+        if ((r.n_chunks && !r.part) || !r.out || r.n_q == 0)
             return hipErrorInvalidValue;
         const uint64_t rows = (uint64_t)r.n_q * p.n_q_heads;
         if (rows > width) width = rows;
         const uint64_t n_mt = ((uint64_t)r.n_q * G + 15u) >> 4;
         if (n_mt > max_mt) max_mt = (uint32_t)(n_mt > 0xFFFFFFFFull ? 0xFFFFFFFFull : n_mt);
         if (n_mt * p.n_kv_heads > tile_width) tile_width = n_mt * p.n_kv_heads;
-        const uint64_t units = (uint64_t)r.n_chunks * r.n_split;
-        if (units > 0xFFFFFFFFull) return hipErrorInvalidValue;
-        if (units > max_units) max_units = units;
+        if (r.n_chunks > max_units) max_units = r.n_chunks;
     }
     if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
     if (max_mt > 2u) {  // the requests of the shared kernel: merge tile by tile

@@ -158,7 +158,7 @@ __device__ __forceinline__ void shared_rounds(const SharedSide &sd, uint32_t T, 
     const uint32_t lane = ln.lane, c_ = ln.c_;
     u32x4 w[2][F::kWords], m[2];
     m[0] = m[1] = u32x4{0u, 0u, 0u, 0u};
-    // the block is clamped to the split's last one instead of skipping the loads: no branch
+    // the block is clamped to the range's last one instead of skipping the loads: no branch
     // around them, so nothing waits for them before they are needed
     auto fetch = [&](int e, uint32_t b) {
         b = b < b1 ? b : b1 - 1u;
@@ -283,7 +283,7 @@ __global__ void __launch_bounds__(64 * W, 2) k6_attend_shared(const K6Params p)
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_bytes[];
     uint8_t (*lds)[W][kSharedBlockLds] = reinterpret_cast<uint8_t (*)[W][kSharedBlockLds]>(lds_bytes);
     K6Chunk c = p.c[blockIdx.y];
-    AttendHdr hdr = {p.n_kv_heads, p.n_q_heads, p.layer, p.split_blocks, p.scale_log2};
+    AttendHdr hdr = {p.n_kv_heads, p.n_q_heads, p.layer, p.scale_log2};
     pin(c.k);
     pin(c.v);
     pin(c.q);
@@ -291,10 +291,8 @@ __global__ void __launch_bounds__(64 * W, 2) k6_attend_shared(const K6Params p)
     pin(c.n_tokens);
     pin(c.info);
     pin(c.n_q);
-    pin(c.n_split);
     pin(hdr.n_kv_heads);
     pin(hdr.n_q_heads);
-    pin(hdr.split_blocks);
     pin(hdr.scale_log2);
     uint32_t run = c.run, more = c.more;  // the run's documents: this one, then descriptors more, more + 1, ..
     uint32_t first_block = c.first_block, end_block = c.end_block;  // where the run starts in its first and ends in its last
@@ -306,9 +304,8 @@ __global__ void __launch_bounds__(64 * W, 2) k6_attend_shared(const K6Params p)
     const uint32_t n_mt = (M + 15u) >> 4;
     const uint32_t n_mtg = (n_mt + 2u * W - 1u) / (2u * W);
     const uint32_t u = blockIdx.x;
-    if (u >= H * c.n_split * n_mtg) return;  // the grid is as wide as the widest run
-    const uint32_t mtg = u % n_mtg, hs = u / n_mtg;
-    const uint32_t s = hs % c.n_split, h = hs / c.n_split;
+    if (u >= H * n_mtg) return;  // the grid is as wide as the widest run
+    const uint32_t mtg = u % n_mtg, h = u / n_mtg;
 
     SharedLane ln;
     ln.lane = threadIdx.x & 63u;
@@ -355,7 +352,7 @@ __global__ void __launch_bounds__(64 * W, 2) k6_attend_shared(const K6Params p)
         const uint8_t *dk = c.k, *dv = c.v;
         uint32_t T = c.n_tokens, dinfo = c.info;
         if (d) {
-            const K6Chunk &cd = p.c[more + d - 1u];
+            const K6Doc &cd = p.d[more + d - 1u];
             dk = cd.k;
             dv = cd.v;
             T = cd.n_tokens;
@@ -386,7 +383,7 @@ __global__ void __launch_bounds__(64 * W, 2) k6_attend_shared(const K6Params p)
         float l_tot = st.l_run[mt];
         l_tot += __shfl_xor(l_tot, 16);
         l_tot += __shfl_xor(l_tot, 32);
-        gfloats rec = (gfloats)c.part + ((uint64_t)(h * c.n_split + s) * n_mt + tile) * kAttendRecFloats;
+        gfloats rec = (gfloats)c.part + ((uint64_t)h * n_mt + tile) * kAttendRecFloats;
 #pragma unroll
         for (uint32_t jj = 0; jj < 4; ++jj) {
             const uint32_t row = 4u * ln.c_ + jj;
@@ -421,54 +418,23 @@ hipError_t prepare_k6_shared()
     return hipSuccess;
 }
 
-hipError_t launch_k6_shared(K6Params &p, uint32_t n_runs, uint32_t waves, hipStream_t stream)
+hipError_t launch_k6_shared(K6Params &p, uint32_t waves, hipStream_t stream)
 {
     if (p.n_chunks == 0) return hipSuccess;
-    if (p.n_chunks > kAttendLaunchChunks || n_runs == 0 || n_runs > p.n_chunks || p.n_kv_heads == 0 ||
-        p.n_q_heads % p.n_kv_heads || p.split_blocks < kAttendMinSplitBlocks ||
-        p.split_blocks > kAttendMaxSplitBlocks || (p.split_blocks & (p.split_blocks - 1u)) ||
-        (waves != 2u && waves != 4u && waves != 8u))
-        return hipErrorInvalidValue;
-    const uint32_t G = p.n_q_heads / p.n_kv_heads;
-    uint64_t width = 0, followers = 0;
-    for (uint32_t i = 0; i < p.n_chunks; ++i) {
-        const K6Chunk &c = p.c[i];
-        const uint32_t kprec = c.info & 0xFu, kgsh = (c.info >> 4) & 0xFu;
-        const uint32_t vprec = (c.info >> 8) & 0xFu, vgsh = (c.info >> 12) & 0xFu;
-        if (c.info >> 16 || kprec > kGSE8 || vprec > kGSE8 || !c.k || !c.v || ((uintptr_t)c.k & 15u) ||
-            ((uintptr_t)c.v & 15u) || c.n_tokens > 0x7FFFFFFu)
-            return hipErrorInvalidValue;
-        if ((kprec == kInt4 || kprec == kInt8) && (kgsh < 5 || kgsh > 7)) return hipErrorInvalidValue;
-        if ((vprec == kInt4 || vprec == kInt8) && (vgsh < 5 || vgsh > 7)) return hipErrorInvalidValue;
-        if (i >= n_runs) continue;  // a run's later document: read by the workgroups of its first
-        if (c.run == 0 || !c.q || !c.part || c.n_q == 0 || c.n_split == 0 || ((uintptr_t)c.q & 15u) ||
-            ((uintptr_t)c.part & 15u) || (uint64_t)c.n_q * G > 0xFFFFFFull)
-            return hipErrorInvalidValue;
-        if (c.run > 1u && (c.more < n_runs || c.more > p.n_chunks || c.run - 1u > p.n_chunks - c.more))
-            return hipErrorInvalidValue;
-        // the run's block range: starts inside its first document, ends inside its last, not empty
-        if (c.n_split != 1u) return hipErrorInvalidValue;
-        {
-            const K6Chunk &last = c.run > 1u ? p.c[c.more + c.run - 2u] : c;
-            const uint32_t nb_first = (c.n_tokens + 15u) >> 4, nb_last = (last.n_tokens + 15u) >> 4;
-            if (c.first_block >= nb_first || c.end_block > nb_last || c.end_block == 0 ||
-                (c.run == 1u && c.end_block <= c.first_block))
-                return hipErrorInvalidValue;
-        }
-        followers += c.run - 1u;
-        const uint32_t n_mt = (c.n_q * G + 15u) >> 4;
-        const uint64_t w = (uint64_t)p.n_kv_heads * c.n_split * ((n_mt + 2u * waves - 1u) / (2u * waves));
-        if (w > width) width = w;
-    }
-    if (followers != p.n_chunks - n_runs || width > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    if (waves != 2u && waves != 4u && waves != 8u) return hipErrorInvalidValue;
+    uint32_t max_mt = 1;
+    bool narrow = true;
+    hipError_t e = check_k6_args(p, &max_mt, &narrow);
+    if (e != hipSuccess) return e;
+    const uint64_t width = (uint64_t)p.n_kv_heads * ((max_mt + 2u * waves - 1u) / (2u * waves));
+    if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
     p.mtw = 2;
-    p.pad = 0;
-    dim3 grid((uint32_t)width, n_runs);
+    dim3 grid((uint32_t)width, p.n_chunks);
     const uint32_t lds_bytes = 2u * waves * kSharedBlockLds;
     if (waves == 2u) hipLaunchKernelGGL((k6_attend_shared<2>), grid, dim3(128), lds_bytes, stream, p);
     else if (waves == 4u) hipLaunchKernelGGL((k6_attend_shared<4>), grid, dim3(256), lds_bytes, stream, p);
     else {
-        const hipError_t e = prepare_k6_shared();  // done at ha_rag_create; a no-op from then on
+        e = prepare_k6_shared();  // done at ha_rag_create; a no-op from then on
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL((k6_attend_shared<8>), grid, dim3(512), lds_bytes, stream, p);
     }

@@ -108,49 +108,68 @@ hipError_t launch_k8(const void *src, const void *packed, uint32_t n_tiles, uint
 // sum l[16] of 2^(score - m).
 constexpr uint32_t kAttendHeadDim = 128;
 constexpr uint32_t kAttendRecFloats = 16 * 128 + 32;
-constexpr uint32_t kAttendMinSplitBlocks = 8;   // a workgroup takes split_blocks layout blocks (16
-constexpr uint32_t kAttendMaxSplitBlocks = 128; // tokens each) of one chunk: a power of two in this range
-constexpr uint32_t kAttendTargetGroups = 2048;  // the host splits finer while a launch has fewer workgroups
+constexpr uint32_t kAttendMinRunBlocks = 8;    // a workgroup takes at least this many layout blocks (16 tokens each),
+constexpr uint32_t kAttendMaxRunBlocks = 128;  // and a piece of one document is at most this long (a power of two)
+constexpr uint32_t kAttendTargetGroups = 2048; // pieces are halved while a launch has fewer workgroups
 constexpr uint32_t kChipCUs = 256;            // compute units of the one GPU this library is built for
 constexpr uint32_t kAttendWaves = 2;          // waves of a workgroup; they interleave its blocks
-// Descriptors travel in the kernel argument buffer (about 26 KiB when full; launches with
-// arguments of 32 KiB were checked to work on this runtime).  A workgroup needs exactly one
-// descriptor, which it fetches in one go: the argument buffer may live in host memory, where
-// every dependent read costs a trip over the link.
-constexpr uint32_t kAttendLaunchChunks = 416;  // chunk descriptors per launch
+// Descriptors travel in the kernel argument buffer (30 KiB; launches with arguments of 32 KiB
+// were checked to work on this runtime).  A workgroup fetches its run's descriptor in one go
+// and one short descriptor per further document: the argument buffer may live in host memory,
+// where every dependent read costs a trip over the link.
+constexpr uint32_t kAttendArgBytes = 30720;
 
-// One document of one request: its keys and its values, which may come from one whole chunk
-// or from a keys-only and a values-only chunk of different formats.
-struct K6Chunk {
+// One document: its keys and its values, which may come from one whole chunk or from a
+// keys-only and a values-only chunk of different formats.
+struct K6Doc {
     const uint8_t *k;     // tile record of (the launch's layer, KV head 0) of the keys; the
     const uint8_t *v;     // other heads' records follow.  The same for the values
-    const uint16_t *q;    // BF16 [n_q][n_q_heads][128] of the chunk's request
-    float *part;          // this document's records [n_kv_heads][n_split][n_mtiles]
     uint32_t n_tokens;
     uint32_t info;        // keys: Prec | log2(group) << 4; values: the same << 8
-    uint32_t n_q;         // query tokens of the request
-    uint32_t n_split;     // token splits of the request (the same for all its chunks)
-    uint32_t run;         // launch_k6_shared: documents of the run this descriptor starts (1 = itself only)
-    uint32_t more;        // launch_k6_shared: index of the descriptor of the run's second document;
-                          // the third and later ones follow it
-    uint32_t first_block; // launch_k6_shared: the run starts at this layout block of its first document
-    uint32_t end_block;   // and ends before this one of its last document (all documents between whole)
 };
 
+// A run: layout blocks first_block .. of its first document (described here), then `run` - 2
+// whole documents, then the blocks before end_block of its last one, all of one request.  One
+// row of workgroups takes a run and writes one record per (KV head, query tile) for it.
+struct K6Chunk {
+    const uint8_t *k;
+    const uint8_t *v;
+    const uint16_t *q;    // BF16 [n_q][n_q_heads][128] of the request
+    float *part;          // the run's records [n_kv_heads][n_mtiles]
+    uint32_t n_tokens;
+    uint32_t info;
+    uint32_t n_q;         // query tokens of the request
+    uint32_t pad;
+    uint32_t run;         // documents of the run (1 = this one only)
+    uint32_t more;        // index in K6Params::d of the run's second document; the third and
+                          // later ones follow it
+    uint32_t first_block;
+    uint32_t end_block;   // of the run's last document; with run == 1 that is this one
+};
+
+constexpr uint32_t kAttendMaxRuns = kAttendArgBytes / sizeof(K6Chunk);
+constexpr uint32_t kAttendMaxDocs = kAttendArgBytes / sizeof(K6Doc);
+
 struct K6Params {
-    uint32_t n_kv_heads, n_q_heads, layer, n_chunks;
+    uint32_t n_kv_heads, n_q_heads, layer;
+    uint32_t n_chunks;     // runs: c[0 .. n_chunks)
     uint32_t mtw;          // 16-row query tiles per workgroup: 1 or 2 (set by launch_k6)
     float scale_log2;      // sm_scale * log2(e)
-    uint32_t split_blocks; // layout blocks per token split
-    uint32_t pad;
-    K6Chunk c[kAttendLaunchChunks];
+    uint32_t d_first;      // the runs' further documents: d[d_first .. d_end), behind the runs
+    uint32_t d_end;
+    union {                // two views of the same bytes
+        K6Chunk c[kAttendMaxRuns];
+        K6Doc d[kAttendMaxDocs];
+    };
+    // index in d of the first short descriptor behind n runs
+    static constexpr uint32_t docs_behind(uint32_t n) { return (n * (uint32_t)sizeof(K6Chunk) + (uint32_t)sizeof(K6Doc) - 1u) / (uint32_t)sizeof(K6Doc); }
 };
 
 struct K7Req {
-    const float *part;    // records [n_chunks][n_kv_heads][n_split][n_mtiles]; n_chunks counts runs
+    const float *part;    // records [n_chunks][n_kv_heads][n_mtiles]; n_chunks counts runs
     float *out;           // binary32 [n_q][n_q_heads][128]
     float *lse;           // binary32 [n_q][n_q_heads] or null
-    uint32_t n_q, n_chunks, n_split, pad;
+    uint32_t n_q, n_chunks, pad[2];
 };
 
 constexpr uint32_t kMaxMergeReqs = 64;
@@ -159,16 +178,18 @@ struct K7Params {
     K7Req r[kMaxMergeReqs];
 };
 
-// Partial attention of every chunk of the launch (sets mtw).
+// Partial attention of every run of the launch: runs c[0 .. n_chunks), their further documents
+// d[d_first .. d_end) with d_first = docs_behind(n_chunks), each run's in a row (`more`).  The
+// grid has one row of workgroups per run and none without work: rows of workgroups that exit
+// at once, in a regular pattern, were measured to halve the workgroups a CU runs side by side.
+// launch_k6 is for requests of at most two query tiles (sets mtw): a workgroup's two waves take
+// the run's blocks in turn.
 hipError_t launch_k6(K6Params &p, hipStream_t stream);
 // The same for requests with more than two query tiles: the `waves` (2, 4 or 8) waves of a
-// workgroup share every decoded block, each wave with two tiles of its own.  A workgroup takes
-// a run of blocks of one request, across its documents in list order (first_block, end_block;
-// n_split must be 1): descriptors 0 .. n_runs - 1 are the runs' first documents
-// (request, records in `part`, `run`, `more`), the runs' other documents come after them
-// (k, v, n_tokens, info only).  The grid has no row without work: rows of workgroups that
-// exit at once, in a regular pattern, were measured to halve the workgroups a CU runs side by side.
-hipError_t launch_k6_shared(K6Params &p, uint32_t n_runs, uint32_t waves, hipStream_t stream);
+// workgroup share every decoded block, each wave with two tiles of its own.
+hipError_t launch_k6_shared(K6Params &p, uint32_t waves, hipStream_t stream);
+// What both check of their arguments (max_mt: most query tiles of a run's request; narrow: no 16-bit side).
+hipError_t check_k6_args(const K6Params &p, uint32_t *max_mt, bool *narrow);
 // Once per device, before the first launch of the eight-wave build (its LDS allowance).
 hipError_t prepare_k6_shared();
 // Merges the partial results of each request into out and lse.

@@ -128,15 +128,17 @@ def test_smaller_groups(g):
     run_case((1, 2, 128), [([70, 30], [B.PREC_INT4, B.PREC_INT8], 2)], 0, 4, 0.09, 30, g8=g, g4=g)
 
 
-def test_a_chunk_longer_than_one_split_and_a_sharp_softmax():
-    # 1100 tokens = 9 splits of 128 tokens (few workgroups, so the finest split); a large scale makes few keys dominate, so the running maximum
-    # keeps moving and accumulated sums are rescaled many times
+def test_a_chunk_cut_into_pieces_and_a_sharp_softmax():
+    # few workgroups, so the shortest pieces: 1100 tokens = 69 blocks = 8 pieces of 8 blocks and one of 5,
+    # 513 tokens = 33 blocks = 4 pieces of 7 and one of 5, a record each; a large scale makes few keys
+    # dominate, so the running maximum keeps moving and accumulated sums are rescaled many times
     run_case((1, 1, 128), [([1100, 513], [B.PREC_INT4, B.PREC_INT8], 4)], 0, 4, 0.5, 40)
 
 
-def test_many_long_chunks_take_coarse_splits():
-    # 40 chunks x 8 heads: 1300 tokens in 2 splits of 1024 give 640 workgroups, 4 of 512 give 1280, 6 of 256 2560
-    reqs = [([1300, 700], [B.PREC_INT4, B.PREC_INT8], 2) for _ in range(20)]
+def test_many_long_chunks_take_long_pieces():
+    # 120 chunks x 8 heads: pieces of at most 64 blocks (82 blocks in 2, 44 in 1) give 1440 workgroups,
+    # of at most 32 blocks (3 of 28, 28, 26 and 2 of 22) 2400, which is enough: no shorter ones
+    reqs = [([1300, 700], [B.PREC_INT4, B.PREC_INT8], 2) for _ in range(60)]
     run_case((1, 8, 128), reqs, 0, 16, 0.09, 45)
 
 
@@ -161,7 +163,7 @@ def test_batch_of_requests_with_different_shapes_empty_chunks_and_an_empty_reque
 
 def test_more_chunks_and_requests_than_one_launch_holds():
     reqs = [([16 + (3 * i + j) % 20 for j in range(8)], [ALL[(i + j) % 6] for j in range(8)], 1 + i % 3)
-            for i in range(140)]                     # 1120 chunks, 140 requests: two launches each
+            for i in range(140)]                     # 1120 chunks, 140 requests: three launches of runs, three of merges
     run_case((1, 1, 128), reqs, 0, 2, 0.1, 60)
 
 
@@ -179,7 +181,7 @@ def test_runs_of_documents_per_workgroup_across_launches_of_the_many_rows_kernel
 
 
 @pytest.mark.parametrize("n_q,n_qh,H", [(12, 4, 1), (40, 4, 1), (9, 32, 2)])
-def test_many_rows_kernel_with_token_splits(n_q, n_qh, H):
+def test_many_rows_kernel_with_runs_inside_long_documents(n_q, n_qh, H):
     """Few, long documents and many query rows: the call has few workgroups, so the runs are
     the shortest there are (8 blocks = 128 tokens) and most of them start and end inside a
     document; every run writes its own record for the tile-wise merge; 3, 10 and 9 query tiles
