@@ -298,7 +298,8 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
     if (layer >= c->cfg.n_layers || !(sm_scale > 0.0f) || !(sm_scale < 1e30f)) return HA_RAG_EINVAL;
     if (floats && (!workspace || ((uintptr_t)workspace & 15u))) return HA_RAG_EINVAL;
     if (floats * 4ull > workspace_bytes) return HA_RAG_ENOSPC;
-    if (c->dry()) return HA_RAG_OK;
+    // a context without a device fills and checks the launches' descriptors all the same
+    const bool dry = c->dry();
     hipStream_t st = (hipStream_t)stream;
     const uint32_t H = c->cfg.n_kv_heads;
     float *ws = static_cast<float *>(workspace);
@@ -372,7 +373,7 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
                 }
             }
             kq.d_end = later;
-            HIPCHK(c, sh ? launch_k6_shared(kq, waves, st) : launch_k6(kq, st));
+            HIPCHK(c, sh ? launch_k6_shared(kq, waves, st, dry) : launch_k6(kq, st, dry));
         }
     }
 
@@ -388,11 +389,11 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
         d.n_chunks = plans[r].n_runs;
         d.pad[0] = d.pad[1] = 0;
         if (mp.n_reqs == kMaxMergeReqs) {
-            HIPCHK(c, launch_k7(mp, st));
+            HIPCHK(c, launch_k7(mp, st, dry));
             mp.n_reqs = 0;
         }
     }
-    if (mp.n_reqs) HIPCHK(c, launch_k7(mp, st));
+    if (mp.n_reqs) HIPCHK(c, launch_k7(mp, st, dry));
     return HA_RAG_OK;
 }
 

@@ -426,7 +426,7 @@ hipError_t check_k6_args(const K6Params &p, uint32_t *max_mt, bool *narrow)
     return next == p.d_end ? hipSuccess : hipErrorInvalidValue;
 }
 
-hipError_t launch_k6(K6Params &p, hipStream_t stream)
+hipError_t launch_k6(K6Params &p, hipStream_t stream, bool check_only)
 {
     if (p.n_chunks == 0) return hipSuccess;
     uint32_t max_mt = 1;
@@ -440,6 +440,7 @@ hipError_t launch_k6(K6Params &p, hipStream_t stream)
     p.mtw = max_mt >= 2 ? 2u : 1u;
     const uint64_t width = (uint64_t)p.n_kv_heads * ((max_mt + p.mtw - 1u) / p.mtw);
     if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    if (check_only) return hipSuccess;
     dim3 grid((uint32_t)width, p.n_chunks), block(64 * kAttendWaves);
     if (p.mtw == 2) hipLaunchKernelGGL((k6_attend_partial<2, false>), grid, block, 0, stream, p);
     else if (narrow) hipLaunchKernelGGL((k6_attend_partial<1, true>), grid, block, 0, stream, p);
@@ -619,7 +620,7 @@ __global__ void __launch_bounds__(256) k7_attend_merge_tiles(const K7Params p)
         r.lse[orow] = l_sum > 0.0f ? (m_max + __builtin_log2f(l_sum)) * 0.69314718055994531f : neg_inf();
 }
 
-hipError_t launch_k7(K7Params &p, hipStream_t stream)
+hipError_t launch_k7(K7Params &p, hipStream_t stream, bool check_only)
 {
     if (p.n_reqs == 0) return hipSuccess;
     if (p.n_reqs > kMaxMergeReqs || p.n_kv_heads == 0 || p.n_q_heads % p.n_kv_heads)
@@ -640,6 +641,7 @@ hipError_t launch_k7(K7Params &p, hipStream_t stream)
         if (r.n_chunks > max_units) max_units = r.n_chunks;
     }
     if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    if (check_only) return hipSuccess;
     if (max_mt > 2u) {  // the requests of the shared kernel: merge tile by tile
         hipLaunchKernelGGL(k7_attend_merge_tiles, dim3((uint32_t)tile_width, p.n_reqs), dim3(256), 0, stream, p);
         return hipGetLastError();

@@ -418,7 +418,7 @@ hipError_t prepare_k6_shared()
     return hipSuccess;
 }
 
-hipError_t launch_k6_shared(K6Params &p, uint32_t waves, hipStream_t stream)
+hipError_t launch_k6_shared(K6Params &p, uint32_t waves, hipStream_t stream, bool check_only)
 {
     if (p.n_chunks == 0) return hipSuccess;
     if (waves != 2u && waves != 4u && waves != 8u) return hipErrorInvalidValue;
@@ -429,6 +429,7 @@ hipError_t launch_k6_shared(K6Params &p, uint32_t waves, hipStream_t stream)
     const uint64_t width = (uint64_t)p.n_kv_heads * ((max_mt + 2u * waves - 1u) / (2u * waves));
     if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
     p.mtw = 2;
+    if (check_only) return hipSuccess;
     dim3 grid((uint32_t)width, p.n_chunks);
     const uint32_t lds_bytes = 2u * waves * kSharedBlockLds;
     if (waves == 2u) hipLaunchKernelGGL((k6_attend_shared<2>), grid, dim3(128), lds_bytes, stream, p);

@@ -183,16 +183,17 @@ struct K7Params {
 // grid has one row of workgroups per run and none without work: rows of workgroups that exit
 // at once, in a regular pattern, were measured to halve the workgroups a CU runs side by side.
 // launch_k6 is for requests of at most two query tiles (sets mtw): a workgroup's two waves take
-// the run's blocks in turn.
-hipError_t launch_k6(K6Params &p, hipStream_t stream);
+// the run's blocks in turn.  check_only (here and below): every check, no launch -- what a
+// context without a device does with the descriptors it has filled.
+hipError_t launch_k6(K6Params &p, hipStream_t stream, bool check_only = false);
 // The same for requests with more than two query tiles: the `waves` (2, 4 or 8) waves of a
 // workgroup share every decoded block, each wave with two tiles of its own.
-hipError_t launch_k6_shared(K6Params &p, uint32_t waves, hipStream_t stream);
+hipError_t launch_k6_shared(K6Params &p, uint32_t waves, hipStream_t stream, bool check_only = false);
 // What both check of their arguments (max_mt: most query tiles of a run's request; narrow: no 16-bit side).
 hipError_t check_k6_args(const K6Params &p, uint32_t *max_mt, bool *narrow);
 // Once per device, before the first launch of the eight-wave build (its LDS allowance).
 hipError_t prepare_k6_shared();
 // Merges the partial results of each request into out and lse.
-hipError_t launch_k7(K7Params &p, hipStream_t stream);
+hipError_t launch_k7(K7Params &p, hipStream_t stream, bool check_only = false);
 
 }  // namespace ha_rag

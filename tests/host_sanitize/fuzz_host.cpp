@@ -67,6 +67,42 @@ int main(int argc, char **argv)
         }
         REQUIRE(ha_rag_register_staging(ctx, (void *)0x300000000000ull, (slot[0] + 4096) * (2 + rnd() % 3)) == HA_RAG_OK);
         REQUIRE(ha_rag_register_bounce(ctx, (void *)0x600000000000ull, (slot[0] + 8192) * (2 + rnd() % 2)) == HA_RAG_OK);
+        // Attention over well-formed lists of any shape: a context without a device still cuts the
+        // requests' blocks into runs, fills every launch's descriptors and runs the launches' own
+        // checks on them, so an inconsistent descriptor shows as a HIP error here.
+        for (int k = 0; k < 3; ++k) {
+            const uint32_t n_reqs = 1 + (uint32_t)(rnd() % 5);
+            std::vector<ha_rag_attend_request> rq(n_reqs);
+            std::vector<ha_rag_packed_chunk> ch;
+            const uint32_t n_qh = cfg.n_kv_heads * (1 + (uint32_t)(rnd() % 8));
+            for (uint32_t r = 0; r < n_reqs; ++r) {
+                std::memset(&rq[r], 0, sizeof rq[r]);
+                rq[r].q = (const void *)0x720000000000ull;
+                rq[r].out = (float *)0x730000000000ull;
+                rq[r].lse = rnd() % 2 ? nullptr : (float *)0x740000000000ull;
+                const uint64_t kind = rnd() % 4;
+                rq[r].n_q = kind == 0 ? 1 : kind == 1 ? 1 + (uint32_t)(rnd() % 8) : 1 + (uint32_t)(rnd() % 300);
+                const uint64_t many = rnd() % 4;
+                rq[r].n_chunks = many == 0 ? 100 + (uint32_t)(rnd() % 500) : (uint32_t)(rnd() % 12);
+                for (uint32_t i = 0; i < rq[r].n_chunks; ++i) {
+                    ha_rag_packed_chunk pc;
+                    pc.packed = (const void *)(0x750000000000ull + 16 * (rnd() % 100000));
+                    pc.n_tokens = many == 0 ? (uint32_t)(rnd() % 60) : (uint32_t)(rnd() % 4000);
+                    pc.prec = (uint32_t)(rnd() % HA_RAG_N_PREC);
+                    pc.group = pc.prec == HA_RAG_PREC_INT8 ? 128 : pc.prec == HA_RAG_PREC_INT4 ? 64 : 0;
+                    pc.part = HA_RAG_PART_KV;
+                    ch.push_back(pc);
+                }
+            }
+            size_t need = 0;
+            REQUIRE(ha_rag_attend_workspace_bytes(ctx, ch.data(), rq.data(), n_reqs, n_qh, &need) == HA_RAG_OK);
+            const int rc = ha_rag_attend_packed(ctx, ch.data(), rq.data(), n_reqs, 0, n_qh, 0.1f,
+                                                (void *)0x760000000000ull, need, nullptr);
+            if (rc != HA_RAG_OK) std::fprintf(stderr, "fuzz_host: attend_packed %d: %s\n", rc, ha_rag_last_hip_error(ctx));
+            REQUIRE(rc == HA_RAG_OK);
+            const int rs = ha_rag_attend_packed_static(ctx, ch.data(), rq.data(), n_reqs, 0, n_qh, 0.1f, nullptr);
+            REQUIRE(rs == HA_RAG_OK || rs == HA_RAG_ENOSPC);
+        }
         std::vector<uint64_t> known;
         for (int op = 0; op < 400; ++op) {
             const uint64_t what = rnd() % 100;

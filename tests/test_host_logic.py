@@ -846,6 +846,33 @@ def _attend_ctx(D=128, L=4, H=2):
     return B.Context(L, H, D, 512, group_int8=min(D, 128), group_int4=min(D, 64), dry_run=True)
 
 
+def test_attend_launch_descriptors_are_filled_and_checked_without_a_device():
+    """A dry-run context cuts the requests' blocks into runs, fills every launch's descriptors and
+    runs the launches' own argument checks (only the launch itself is left out), so lists of any
+    shape must come back OK: more runs than one launch holds, runs that span more documents than
+    a run may (128), requests for both kernels in one call, the workspace exactly as large as
+    asked for."""
+    ctx = _attend_ctx(H=8)
+    P = 0x7F0000001000
+    ch = lambda t, p=B.PREC_INT4, g=64: (P, t, p, g, B.PART_KV)
+    req = lambda chunks, n_q: (chunks, P, P, P, n_q)
+    precs = [(B.PREC_INT4, 64), (B.PREC_INT8, 128), (B.PREC_16, 0), (B.PREC_FP8_E4M3, 0), (B.PREC_GSE8, 0)]
+    lists = [
+        [req([ch(1, *precs[i % 5]) for i in range(600)], 40)],                        # one block per document
+        [req([ch(3 + 7 * i % 50, *precs[i % 5]) for i in range(700)], 1)],             # 700 runs: two launches
+        [req([ch(2000)] * 40, 1), req([ch(2000)] * 40, 64), req([ch(17)], 9), req([], 3)],
+        [req([ch(16 * (1 + i % 9), *precs[(i + r) % 5]) for i in range(60)], 1 + 13 * r) for r in range(20)],
+    ]
+    for reqs in lists:
+        n = ctx.attend_workspace_bytes(reqs, 32)
+        ctx.attend_packed(reqs, 1, 32, 0.088, P, n)
+        if n:
+            with pytest.raises(B.HaRagError) as e:
+                ctx.attend_packed(reqs, 1, 32, 0.088, P, n - 4)
+            assert e.value.code == B.ENOSPC
+    ctx.destroy()
+
+
 def test_attend_workspace_size_and_argument_checks():
     ctx = _attend_ctx()
     P = 0x7F0000001000
