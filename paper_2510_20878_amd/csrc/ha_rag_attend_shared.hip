@@ -8,18 +8,22 @@
 //      registers.  The layout blocks are taken W at a time: half the waves decode the keys and
 //      half the values of the round, two blocks each, to BF16 (the values a load would write)
 //      and leave them in LDS in the form the MFMAs take their operands in; after one barrier
-//      every wave scores all W blocks against its own tiles.  A block is therefore fetched and
-//      decoded once per 32 W query rows.  The rounds alternate between two sets of LDS buffers,
-//      so one barrier per round is enough: a wave that writes round r + 1 has passed barrier r,
-//      which every wave reaches only after it has read all of round r - 1.
+//      every wave scores all W blocks against its own tiles, two blocks (a pair) at a time.  A
+//      block is therefore fetched and decoded once per 32 W query rows.  The rounds alternate
+//      between two sets of LDS buffers, so one barrier per round is enough: a wave that writes
+//      round r + 1 has passed barrier r, which every wave reaches only after it has read all of
+//      round r - 1.
 //
 // Block geometry as for k6_attend_partial: lane (c = lane / 16, n = lane % 16) of the wave that
 // reads a block holds, in plane j, token 4 j + c, dims 8 n .. 8 n + 7.
 //   V: that is what the product P V takes from a lane, so the decoding wave stores its eight
-//      operand words lane by lane and every wave reads them back lane by lane.
+//      operand words lane by lane, those of a pair's first and second block side by side (16
+//      bytes per lane and operand), and every wave reads them back lane by lane: one 16x16x32
+//      MFMA then contracts over the 32 tokens of the pair.
 //   K: the score MFMA wants, per lane, 8 dims of the token of its column; the decoding wave
 //      stores octet o of token t at 16-byte slot (o ^ t) of row t (256 bytes a row), which
 //      both its own stores and the readers' loads reach without bank conflicts.
+// A pair's buffer is 16 KiB: K of its first block, K of its second block, V of both.
 #include "ha_rag_attend_dev.h"
 #include <atomic>
 
@@ -27,7 +31,7 @@ namespace ha_rag {
 
 namespace {
 
-constexpr uint32_t kSharedBlockLds = 8192;  // K operands 4 KiB, then V operands 4 KiB
+constexpr uint32_t kSharedBlockLds = 8192;  // LDS per block: K operands 4 KiB, V operands 4 KiB (laid out per pair)
 
 struct SharedState {  // a wave's two query tiles
     bf16x8 qb[2][4];
@@ -55,52 +59,69 @@ __device__ __forceinline__ uint32_t fresh(uint32_t v)
     return v;
 }
 
-// One block against the wave's two tiles, in three steps that the round loop below interleaves
-// across blocks: S^T = K Q^T (shared_qk), the running softmax (shared_softmax), O += P V
-// (shared_pv).
+// Two blocks (a pair) against the wave's two tiles, in three steps: S^T = K Q^T of both blocks
+// (shared_qk_pair), the running softmax (shared_softmax_pair), O += P V (shared_pv_pair).
+//
+// The product P V contracts over tokens, 16 per block; the 16x16x32 MFMA contracts over 32, so
+// the two blocks of a pair share one: contraction index 8 c_ + i is token 4 i + c_ of the pair's
+// first block for i < 4 and token 4 (i - 4) + c_ of its second block for i >= 4.  For the lane
+// that is the weights of the first block next to those of the second (P8) and, per dim, the
+// values of the first block next to those of the second, which is how the decoding waves lay
+// the pair's V operands out (16 bytes per lane and operand: first block, second block).  Half
+// the MFMAs of the 16x16x16 form, which is no faster per instruction.
 
-// S[mt][jj] = q k (unscaled) of token 4 jj + c_ of the block and query row n_ of tile mt
-__device__ __forceinline__ void shared_qk(const uint8_t *src, const SharedLane &ln, const SharedState &st,
-                                          f32x4 (&S)[2])
+// S[e][mt][jj] = q k (unscaled) of token 4 jj + c_ of block e of the pair and query row n_ of tile mt
+__device__ __forceinline__ void shared_qk_pair(const uint8_t *pair, const SharedLane &ln, const SharedState &st,
+                                               f32x4 (&S)[2][2])
 {
     const uint32_t k_rd = fresh(ln.k_rd);
-    bf16x8 ka[4];
 #pragma unroll
-    for (uint32_t y = 0; y < 4; ++y)
-        ka[y] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(src + (k_rd ^ (16u * y))));
-    // both tiles side by side, so that their MFMA chains overlap
+    for (int e = 0; e < 2; ++e) {
+        bf16x8 ka[4];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) S[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (uint32_t y = 0; y < 4; ++y)
+            ka[y] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pair + e * 4096u + (k_rd ^ (16u * y))));
+        // both tiles side by side, so that their MFMA chains overlap
 #pragma unroll
-    for (int y = 0; y < 4; ++y)
+        for (int mt = 0; mt < 2; ++mt) S[e][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-            S[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[y], st.qb[mt][y], S[mt], 0, 0, 0);
+        for (int y = 0; y < 4; ++y)
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+                S[e][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[y], st.qb[mt][y], S[e][mt], 0, 0, 0);
+    }
 }
 
-// From the scores of block b to the weights pa (the A operands of P V).  The caller sees to it
-// that S is not read too early after its MFMAs (mfma_result_wait, or other MFMAs in between).
-__device__ __forceinline__ void shared_softmax(f32x4 (&S)[2], uint32_t b, uint32_t T, float scale_log2,
-                                               const SharedLane &ln, SharedState &st, s16x4 (&pa)[2])
+// From the scores of the pair that starts at block b to the weights P8 (the A operands of P V).
+// `end` = the first token that does not count: the document's end, or the end of the run's last
+// block; only a pair that reaches beyond it is masked.  The caller sees to it that S is not read
+// too early after its MFMAs (mfma_result_wait).
+__device__ __forceinline__ void shared_softmax_pair(f32x4 (&S)[2][2], uint32_t b, uint32_t end, float scale_log2,
+                                                    const SharedLane &ln, SharedState &st, bf16x8 (&P8)[2])
 {
     const uint32_t c_ = ln.c_;
-    if (b * 16u + 16u > T) {  // ragged: only the document's last block can be
+    if (b * 16u + 32u > end) {  // a ragged last block, or a last block without a partner
         const uint32_t tok = b * 16u + fresh(c_);  // computed only here
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int e = 0; e < 2; ++e)
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj)
-                if (tok + 4u * jj >= T) S[mt][jj] = neg_inf();
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+                    if (tok + 16u * e + 4u * jj >= end) S[e][mt][jj] = neg_inf();
     }
     float mx[2];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-        mx[mt] = __builtin_fmaxf(__builtin_fmaxf(S[mt][0], S[mt][1]), __builtin_fmaxf(S[mt][2], S[mt][3])) * scale_log2;
+    for (int mt = 0; mt < 2; ++mt) {
+        const float a = __builtin_fmaxf(__builtin_fmaxf(S[0][mt][0], S[0][mt][1]), __builtin_fmaxf(S[0][mt][2], S[0][mt][3]));
+        const float bb = __builtin_fmaxf(__builtin_fmaxf(S[1][mt][0], S[1][mt][1]), __builtin_fmaxf(S[1][mt][2], S[1][mt][3]));
+        mx[mt] = __builtin_fmaxf(a, bb) * scale_log2;
+    }
     // The running maximum of a row is only a reference point for the exponentials, so it need
     // not be the true maximum: it is brought up to date (a reduction over the lane groups and a
     // rescaling of what is accumulated) only when some lane meets a score more than
     // kLazyMaxSlack above it, which bounds every weight by 2^kLazyMaxSlack.  After the first
-    // blocks that almost never happens, and a block costs one comparison instead of the reduction.
+    // blocks that almost never happens, and a pair costs one comparison instead of the reduction.
     if (__any(mx[0] > st.m_run[0] + kLazyMaxSlack || mx[1] > st.m_run[1] + kLazyMaxSlack)) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
@@ -118,32 +139,33 @@ __device__ __forceinline__ void shared_softmax(f32x4 (&S)[2], uint32_t b, uint32
     }
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
-        float pr[4];
+        float pr[2][4];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj)
-            pr[jj] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mt][jj], scale_log2, -st.m_run[mt]));
-        st.l_run[mt] += (pr[0] + pr[1]) + (pr[2] + pr[3]);
-        const u32x2 pk = {pack_bf16(pr[0], pr[1]), pack_bf16(pr[2], pr[3])};
-        pa[mt] = __builtin_bit_cast(s16x4, pk);
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                pr[e][jj] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[e][mt][jj], scale_log2, -st.m_run[mt]));
+        st.l_run[mt] += ((pr[0][0] + pr[0][1]) + (pr[0][2] + pr[0][3])) + ((pr[1][0] + pr[1][1]) + (pr[1][2] + pr[1][3]));
+        const u32x4 pk = {pack_bf16(pr[0][0], pr[0][1]), pack_bf16(pr[0][2], pr[0][3]),
+                          pack_bf16(pr[1][0], pr[1][1]), pack_bf16(pr[1][2], pr[1][3])};
+        P8[mt] = __builtin_bit_cast(bf16x8, pk);
     }
 }
 
-__device__ __forceinline__ void shared_pv(const uint8_t *src, const SharedLane &ln, SharedState &st,
-                                          const s16x4 (&pa)[2])
+// O += P V of a pair; `vsrc` = its V operands
+__device__ __forceinline__ void shared_pv_pair(const uint8_t *vsrc, const SharedLane &ln, SharedState &st,
+                                               const bf16x8 (&P8)[2])
 {
     const uint32_t v_rd = fresh(ln.lane) * 16u;
-    u32x4 vq[4];
+    u32x4 vq[8];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) vq[q] = *reinterpret_cast<const u32x4 *>(src + 4096u + q * 1024u + v_rd);
+    for (int pp = 0; pp < 8; ++pp) vq[pp] = *reinterpret_cast<const u32x4 *>(vsrc + pp * 1024u + v_rd);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const s16x4 v0 = __builtin_bit_cast(s16x4, u32x2{vq[q].x, vq[q].y});
-        const s16x4 v1 = __builtin_bit_cast(s16x4, u32x2{vq[q].z, vq[q].w});
+    for (int pp = 0; pp < 8; ++pp) {
+        const bf16x8 v = __builtin_bit_cast(bf16x8, vq[pp]);
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-            st.O[mt][2 * q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa[mt], v0, st.O[mt][2 * q], 0, 0, 0);
-            st.O[mt][2 * q + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa[mt], v1, st.O[mt][2 * q + 1], 0, 0, 0);
-        }
+        for (int mt = 0; mt < 2; ++mt)
+            st.O[mt][pp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(P8[mt], v, st.O[mt][pp], 0, 0, 0);
     }
 }
 
@@ -174,8 +196,19 @@ __device__ __forceinline__ void shared_rounds(const SharedSide &sd, uint32_t T, 
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
             const uint32_t blk = rb + 2u * r + e;
-            if (blk >= b1) continue;
-            uint8_t *dst = lds[set][2u * r + e];
+            uint8_t *pair = lds[set][2u * r];  // this decoder's pair of the round: K 4 KiB + 4 KiB, then V 8 KiB
+            if (blk >= b1) {
+                // no such block.  If its partner exists, the pair's MFMAs still take this half of
+                // the V operands, with weight zero: it must hold numbers (what the keys' half
+                // holds does not matter, its scores are replaced)
+                if (!IS_K && e == 1 && blk - 1u < b1) {
+#pragma unroll
+                    for (int pp = 0; pp < 8; ++pp)
+                        *reinterpret_cast<u32x2 *>(pair + 8192u + pp * 1024u + fresh(lane) * 16u + 8u) = u32x2{0u, 0u};
+                }
+                continue;
+            }
+            uint8_t *dst = pair + e * 4096u;
             u32x4 o[4];  // o[j] = token 4 j + c_, dims 8 n_ .. 8 n_ + 7 as BF16
 #pragma unroll
             for (int j = 0; j < 4; ++j) o[j] = decode_octet<P>(plane_raw<P>(w[e], j), m[e][j], sd.base, sd.top);
@@ -191,15 +224,18 @@ __device__ __forceinline__ void shared_rounds(const SharedSide &sd, uint32_t T, 
                     for (uint32_t j = 0; j < 4; ++j)
                         if (blk * 16u + 4u * j + c_ >= T) o[j] = u32x4{0u, 0u, 0u, 0u};
                 }
-                // operand pp of P V: value pp of the octet of each of the lane's four tokens
+                // operand pp of P V: value pp of the octet of each of the lane's four tokens; the
+                // pair's second block fills the second half of the lane's 16 bytes
+                uint8_t *vdst = pair + 8192u + fresh(lane) * 16u + e * 8u;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    u32x4 t;
-                    t.x = __builtin_amdgcn_perm(o[1][q], o[0][q], 0x05040100u);
-                    t.y = __builtin_amdgcn_perm(o[3][q], o[2][q], 0x05040100u);
-                    t.z = __builtin_amdgcn_perm(o[1][q], o[0][q], 0x07060302u);
-                    t.w = __builtin_amdgcn_perm(o[3][q], o[2][q], 0x07060302u);
-                    *reinterpret_cast<u32x4 *>(dst + 4096u + q * 1024u + fresh(lane) * 16u) = t;
+                    u32x2 lo, hi;
+                    lo.x = __builtin_amdgcn_perm(o[1][q], o[0][q], 0x05040100u);
+                    lo.y = __builtin_amdgcn_perm(o[3][q], o[2][q], 0x05040100u);
+                    hi.x = __builtin_amdgcn_perm(o[1][q], o[0][q], 0x07060302u);
+                    hi.y = __builtin_amdgcn_perm(o[3][q], o[2][q], 0x07060302u);
+                    *reinterpret_cast<u32x2 *>(vdst + (2 * q) * 1024u) = lo;
+                    *reinterpret_cast<u32x2 *>(vdst + (2 * q + 1) * 1024u) = hi;
                 }
             }
         }
@@ -209,30 +245,32 @@ __device__ __forceinline__ void shared_rounds(const SharedSide &sd, uint32_t T, 
         fetch(0, rb + W + 2u * r);
         fetch(1, rb + W + 2u * r + 1u);
 
-        // ---- every wave: its two tiles against the round's blocks
-        // The blocks of the round are staggered: the score MFMAs of block i + 1 are issued
-        // before the P V MFMAs of block i, and the softmax of block i + 1 (vector work) runs
-        // while those drain.  Between the score MFMAs and the first read of their result lie
-        // the 16 P V MFMAs, more than the cycles that read has to wait.
+        // ---- every wave: its two tiles against the round's blocks, two blocks at a time.  The
+        // loop over the pairs is kept a loop: unrolled, the pairs' operand loads and temporaries
+        // overlap and the registers do not reach (the 16-bit instances then spill into the path
+        // of the prefetch, whose wait a reload shares).
         if (active) {
             const uint32_t nb = b1 - rb < (uint32_t)W ? b1 - rb : (uint32_t)W;
-            f32x4 S[2];
-            s16x4 pa[2];
-            shared_qk(lds[set][0], ln, st, S);
-            mfma_result_wait();
-            shared_softmax(S, rb, T, scale_log2, ln, st, pa);
-#pragma unroll
-            for (uint32_t i = 0; i + 1u < (uint32_t)W; ++i) {
-                if (i + 1u < nb) {
-                    shared_qk(lds[set][i + 1u], ln, st, S);
-                    shared_pv(lds[set][i], ln, st, pa);
-                    shared_softmax(S, rb + i + 1u, T, scale_log2, ln, st, pa);
+            const uint32_t end = b1 * 16u < T ? b1 * 16u : T;  // the first token that does not count
+            const uint8_t *base = lds[set][0];
+#pragma unroll 1
+            for (uint32_t pr = 0; 2u * pr < nb; ++pr) {
+                {
+                    const uint8_t *pair = base + pr * (2u * kSharedBlockLds);
+                    f32x4 S[2][2];
+                    bf16x8 P8[2];
+                    shared_qk_pair(pair, ln, st, S);
+                    mfma_result_wait();
+                    shared_softmax_pair(S, rb + 2u * pr, end, scale_log2, ln, st, P8);
+                    shared_pv_pair(pair + 8192u, ln, st, P8);
                 }
             }
-            shared_pv(lds[set][nb - 1u], ln, st, pa);
         }
         set ^= 1u;
     }
+    // what follows the document's last P V MFMAs (moves of the output rows between registers, the
+    // records) lies behind branches
+    mfma_result_wait();
 }
 
 template <bool IS_K, int W>
