@@ -191,6 +191,16 @@ def test_many_rows_kernel_with_runs_inside_long_documents(n_q, n_qh, H):
     run_case((1, H, 128), reqs, 0, n_qh, 0.07, 110 + n_q)
 
 
+@pytest.mark.parametrize("tokens", [[1], [16], [48], [33, 16, 1, 80], [15, 17, 31, 47, 49]])
+def test_many_rows_kernel_with_blocks_that_have_no_partner(tokens):
+    """The many-rows kernel scores two blocks per step.  Documents of one block, of an odd number
+    of whole blocks, and ragged ones whose last block opens a pair: the missing half of a pair
+    must not count (its keys are whatever the buffer held, its values are written as zeros), in
+    the first round of a workgroup (nothing decoded yet) and in later ones."""
+    precs = [ALL[(3 * i + len(tokens)) % 6] for i in range(len(tokens))]
+    run_case((1, 2, 128), [(tokens, precs, 40), (tokens[::-1], precs[::-1], 9)], 0, 8, 0.1, 130 + len(tokens))
+
+
 def test_one_call_with_requests_for_both_attention_kernels():
     """One query token next to 24 and 70 of them: the first request takes the kernel of at most
     two query tiles, the others the many-rows kernel (3 and 9 tiles, so one workgroup of four
