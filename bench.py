@@ -16,7 +16,8 @@ The default line also carries one short leg per other configuration, each with i
 roofline object: `llama70b` (the 70B shape, pool of about 200 GB), `zipf` (Zipf(1.1) over 100k
 chunk ids, batch of 32 requests x 8 chunks, HBM hot tier + pinned cold tier with promotion),
 `cold_path` (all chunks in pinned host memory, both transfer routes, against the PCIe peak) and
-`attend_path` (attention straight over the packed chunks).  After each timed region, outside
+`attend_path` / `attend_prefill_path` (attention straight over the packed chunks, 1 and 64 query
+tokens per request).  After each timed region, outside
 the timing, tiles sampled from the last outputs are recomputed by the CPU oracle from the very
 packed bytes the kernels read and compared bit for bit (`verified_tiles`; attention:
 `verified_rows`, within the tolerance of its parity tests).  A mismatch ends the run with an
@@ -1344,6 +1345,15 @@ def main():
         res["attend_path"] = {k: att[k] for k in ("value", "unit", "ms_per_step", "steps", "kv_tokens_per_s",
                                                    "equivalent_bf16_cache_read_gbps", "verified_rows", "roofline")}
         res["attend_path"]["workload"] = att["config"]["workload"]
+        release()
+        # and with the query tokens of a question (its prefill, Sec. 2.1): 64 per request, where the
+        # two contractions at the MFMA peak are the longer floor
+        a4 = argparse.Namespace(**vars(a3))
+        a4.steps, a4.warmup, a4.n_q = 10, 3, 64
+        pre, _ = run_attend(a4, B, wl, torch)
+        res["attend_prefill_path"] = {k: pre[k] for k in ("value", "unit", "ms_per_step", "steps", "kv_tokens_per_s",
+                                                           "verified_rows", "roofline")}
+        res["attend_prefill_path"]["workload"] = pre["config"]["workload"]
         release()
     res["paper_context"] = {
         "note": "context only, not a target: the paper reports end-to-end TTFT ratios, no GB/s",
