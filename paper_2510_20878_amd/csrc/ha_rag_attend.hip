@@ -343,9 +343,9 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
                 ++n_runs;
                 n_more += run.n_docs - 1u;
             }
-            kq.n_chunks = n_runs;
-            kq.d_first = K6Params::docs_behind(n_runs);
-            uint32_t later = kq.d_first;  // where the next run's further documents go
+            kq.n_runs = n_runs;
+            kq.doc_first = K6Params::docs_behind(n_runs);
+            uint32_t later = kq.doc_first;  // where the next run's further documents go
             for (uint32_t k = 0; k < n_runs; ++k) {
                 settle(at);
                 const Plan &pl = plans[at.r];
@@ -354,7 +354,7 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
                 Run run;
                 take(at, &run);
                 const Doc &first = docs[pl.first_doc + run.doc];
-                K6Chunk &d = kq.c[k];
+                K6Run &d = kq.run[k];
                 d.k = doc_k(first);
                 d.v = doc_v(first);
                 d.q = static_cast<const uint16_t *>(rq.q);
@@ -363,16 +363,16 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
                 d.info = first.info;
                 d.n_q = rq.n_q;
                 d.pad = 0;
-                d.run = run.n_docs;
+                d.n_docs = run.n_docs;
                 d.more = later;
                 d.first_block = run.first_block;
                 d.end_block = run.end_block;
                 for (uint32_t i = 1; i < run.n_docs; ++i) {
                     const Doc &doc = docs[pl.first_doc + run.doc + i];
-                    kq.d[later++] = K6Doc{doc_k(doc), doc_v(doc), doc.n_tokens, doc.info};
+                    kq.doc[later++] = K6Doc{doc_k(doc), doc_v(doc), doc.n_tokens, doc.info};
                 }
             }
-            kq.d_end = later;
+            kq.doc_end = later;
             HIPCHK(c, sh ? launch_k6_shared(kq, waves, st, dry) : launch_k6(kq, st, dry));
         }
     }
@@ -386,7 +386,7 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
         d.out = reqs[r].out;
         d.lse = reqs[r].lse;
         d.n_q = reqs[r].n_q;
-        d.n_chunks = plans[r].n_runs;
+        d.n_runs = plans[r].n_runs;
         d.pad[0] = d.pad[1] = 0;
         if (mp.n_reqs == kMaxMergeReqs) {
             HIPCHK(c, launch_k7(mp, st, dry));

@@ -41,7 +41,7 @@ struct AttendLds {
 // KP, VP: the formats of the chunk's keys and of its values (the same for a chunk stored whole).
 // NARROW: the instance belongs to the kernel that runs three waves per SIMD (168 registers).
 template <uint32_t KP, uint32_t VP, int MTW, bool NARROW>
-__device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Chunk &c,
+__device__ __forceinline__ void attend_unit(const AttendHdr &p, const K6Run &c,
                                             uint32_t h, uint32_t mtg, uint8_t *lds_all,
                                             float (*sm)[MTW * 16], float (*sl)[MTW * 16])
 {
@@ -316,7 +316,7 @@ blocks_done:
 // narrow formats leaves out every pair with a 16-bit side: those need more registers than three
 // waves per SIMD leave.
 template <uint32_t KP, uint32_t VP, int MTW, bool NARROW>
-__device__ __forceinline__ void attend_pair(const AttendHdr &hdr, const K6Chunk &c, uint32_t h,
+__device__ __forceinline__ void attend_pair(const AttendHdr &hdr, const K6Run &c, uint32_t h,
                                             uint32_t mtg, uint8_t *lds, float (*sm)[MTW * 16],
                                             float (*sl)[MTW * 16])
 {
@@ -325,7 +325,7 @@ __device__ __forceinline__ void attend_pair(const AttendHdr &hdr, const K6Chunk 
 }
 
 template <uint32_t KP, int MTW, bool NARROW>
-__device__ __forceinline__ void attend_values(const AttendHdr &hdr, const K6Chunk &c, uint32_t h,
+__device__ __forceinline__ void attend_values(const AttendHdr &hdr, const K6Run &c, uint32_t h,
                                               uint32_t mtg, uint8_t *lds, float (*sm)[MTW * 16],
                                               float (*sl)[MTW * 16])
 {
@@ -350,7 +350,7 @@ __global__ void __launch_bounds__(64 * kAttendWaves, NARROW ? 3 : 2) k6_attend_p
     __shared__ __attribute__((aligned(16))) uint8_t lds[AttendLds<MTW>::kBytes];
     __shared__ float sm[kAttendWaves][MTW * 16], sl[kAttendWaves][MTW * 16];
     // the whole descriptor and the header at once, before anything depends on a part of them
-    K6Chunk c = p.c[blockIdx.y];
+    K6Run c = p.run[blockIdx.y];
     AttendHdr hdr = {p.n_kv_heads, p.n_q_heads, p.layer, p.scale_log2};
     pin(c.k);
     pin(c.v);
@@ -387,8 +387,8 @@ __global__ void __launch_bounds__(64 * kAttendWaves, NARROW ? 3 : 2) k6_attend_p
 // of a run's request, *narrow whether no document has a 16-bit side.
 hipError_t check_k6_args(const K6Params &p, uint32_t *max_mt, bool *narrow)
 {
-    if (p.n_chunks == 0 || p.n_chunks > kAttendMaxRuns || p.n_kv_heads == 0 || p.n_q_heads % p.n_kv_heads ||
-        p.d_first != K6Params::docs_behind(p.n_chunks) || p.d_end < p.d_first || p.d_end > kAttendMaxDocs)
+    if (p.n_runs == 0 || p.n_runs > kAttendMaxRuns || p.n_kv_heads == 0 || p.n_q_heads % p.n_kv_heads ||
+        p.doc_first != K6Params::docs_behind(p.n_runs) || p.doc_end < p.doc_first || p.doc_end > kAttendMaxDocs)
         return hipErrorInvalidValue;
     const uint32_t G = p.n_q_heads / p.n_kv_heads;
     auto doc_ok = [&](const uint8_t *k, const uint8_t *v, uint32_t n_tokens, uint32_t info) {
@@ -404,44 +404,44 @@ hipError_t check_k6_args(const K6Params &p, uint32_t *max_mt, bool *narrow)
     };
     *max_mt = 1;
     *narrow = true;
-    for (uint32_t i = p.d_first; i < p.d_end; ++i)
-        if (!doc_ok(p.d[i].k, p.d[i].v, p.d[i].n_tokens, p.d[i].info)) return hipErrorInvalidValue;
-    uint32_t next = p.d_first;  // the runs' further documents lie in the runs' order, without gaps
-    for (uint32_t i = 0; i < p.n_chunks; ++i) {
-        const K6Chunk &c = p.c[i];
-        if (!doc_ok(c.k, c.v, c.n_tokens, c.info) || c.run == 0 || !c.q || !c.part || c.n_q == 0 ||
+    for (uint32_t i = p.doc_first; i < p.doc_end; ++i)
+        if (!doc_ok(p.doc[i].k, p.doc[i].v, p.doc[i].n_tokens, p.doc[i].info)) return hipErrorInvalidValue;
+    uint32_t next = p.doc_first;  // the runs' further documents lie in the runs' order, without gaps
+    for (uint32_t i = 0; i < p.n_runs; ++i) {
+        const K6Run &c = p.run[i];
+        if (!doc_ok(c.k, c.v, c.n_tokens, c.info) || c.n_docs == 0 || !c.q || !c.part || c.n_q == 0 ||
             ((uintptr_t)c.q & 15u) || ((uintptr_t)c.part & 15u) || (uint64_t)c.n_q * G > 0xFFFFFFull)
             return hipErrorInvalidValue;
-        if (c.run > 1u && (c.more != next || c.run - 1u > p.d_end - next)) return hipErrorInvalidValue;
-        next += c.run - 1u;
+        if (c.n_docs > 1u && (c.more != next || c.n_docs - 1u > p.doc_end - next)) return hipErrorInvalidValue;
+        next += c.n_docs - 1u;
         // the run's block range: starts inside its first document, ends inside its last, not empty
         const uint32_t nb_first = (c.n_tokens + 15u) >> 4;
-        const uint32_t nb_last = c.run > 1u ? (p.d[next - 1u].n_tokens + 15u) >> 4 : nb_first;
+        const uint32_t nb_last = c.n_docs > 1u ? (p.doc[next - 1u].n_tokens + 15u) >> 4 : nb_first;
         if (c.first_block >= nb_first || c.end_block > nb_last || c.end_block == 0 ||
-            (c.run == 1u && c.end_block <= c.first_block))
+            (c.n_docs == 1u && c.end_block <= c.first_block))
             return hipErrorInvalidValue;
         const uint32_t n_mt = (c.n_q * G + 15u) >> 4;
         if (n_mt > *max_mt) *max_mt = n_mt;
     }
-    return next == p.d_end ? hipSuccess : hipErrorInvalidValue;
+    return next == p.doc_end ? hipSuccess : hipErrorInvalidValue;
 }
 
 hipError_t launch_k6(K6Params &p, hipStream_t stream, bool check_only)
 {
-    if (p.n_chunks == 0) return hipSuccess;
+    if (p.n_runs == 0) return hipSuccess;
     uint32_t max_mt = 1;
     bool narrow = true;  // no 16-bit side in this launch
     const hipError_t e = check_k6_args(p, &max_mt, &narrow);
     if (e != hipSuccess) return e;
-    for (uint32_t i = 0; i < p.n_chunks; ++i)
-        if (p.c[i].run != 1u) return hipErrorInvalidValue;  // this kernel's runs stay inside one document
+    for (uint32_t i = 0; i < p.n_runs; ++i)
+        if (p.run[i].n_docs != 1u) return hipErrorInvalidValue;  // this kernel's runs stay inside one document
     // Two tiles (32 query rows) per workgroup is the most that still runs two waves per SIMD;
     // four tiles at one wave per SIMD measured 35 % slower than two passes of two.
     p.mtw = max_mt >= 2 ? 2u : 1u;
     const uint64_t width = (uint64_t)p.n_kv_heads * ((max_mt + p.mtw - 1u) / p.mtw);
     if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
     if (check_only) return hipSuccess;
-    dim3 grid((uint32_t)width, p.n_chunks), block(64 * kAttendWaves);
+    dim3 grid((uint32_t)width, p.n_runs), block(64 * kAttendWaves);
     if (p.mtw == 2) hipLaunchKernelGGL((k6_attend_partial<2, false>), grid, block, 0, stream, p);
     else if (narrow) hipLaunchKernelGGL((k6_attend_partial<1, true>), grid, block, 0, stream, p);
     else hipLaunchKernelGGL((k6_attend_partial<1, false>), grid, block, 0, stream, p);
@@ -468,7 +468,7 @@ __global__ void __launch_bounds__(32 * kMergeGroups) k7_attend_merge(const K7Par
     pin(r.out);
     pin(r.lse);
     pin(r.n_q);
-    pin(r.n_chunks);
+    pin(r.n_runs);
     pin(n_kv_heads);
     pin(n_q_heads);
     const uint32_t rr = blockIdx.x;
@@ -485,7 +485,7 @@ __global__ void __launch_bounds__(32 * kMergeGroups) k7_attend_merge(const K7Par
     // Group g takes records g, g + n_g, ..., four at a time: their maxima, sums and this
     // thread's four dims are fetched together (every thread of a group reads the same m and l:
     // broadcast loads), then folded into a running maximum like the blocks inside a record were.
-    const uint32_t n_units = r.n_chunks;
+    const uint32_t n_units = r.n_runs;
     float m_max = neg_inf(), l_sum = 0.0f;
     f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
     for (uint32_t u0 = g; u0 < n_units; u0 += 4u * n_g) {
@@ -560,7 +560,7 @@ __global__ void __launch_bounds__(256) k7_attend_merge_tiles(const K7Params p)
     pin(r.out);
     pin(r.lse);
     pin(r.n_q);
-    pin(r.n_chunks);
+    pin(r.n_runs);
     pin(n_kv_heads);
     pin(n_q_heads);
     const uint32_t G = n_q_heads / n_kv_heads, M = r.n_q * G;
@@ -572,7 +572,7 @@ __global__ void __launch_bounds__(256) k7_attend_merge_tiles(const K7Params p)
     if (mrow >= M) return;  // rows without a query are not in the records either
     const uint64_t run_stride = (uint64_t)n_kv_heads * n_mt * kAttendRecFloats;  // records are [run][head][tile]
     gfloats first = (gfloats)r.part + ((uint64_t)h * n_mt + mt) * kAttendRecFloats;
-    const uint32_t n_units = r.n_chunks;
+    const uint32_t n_units = r.n_runs;
     float m_max = neg_inf(), l_sum = 0.0f;
     f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
     for (uint32_t u0 = 0; u0 < n_units; u0 += 4u) {
@@ -630,15 +630,15 @@ hipError_t launch_k7(K7Params &p, hipStream_t stream, bool check_only)
     uint32_t max_mt = 0;
     for (uint32_t i = 0; i < p.n_reqs; ++i) {
         const K7Req &r = p.r[i];
-        // a request without a token to attend to (n_chunks 0) gets zeros and lse = -inf
-        if ((r.n_chunks && !r.part) || !r.out || r.n_q == 0)
+        // a request without a token to attend to (n_runs 0) gets zeros and lse = -inf
+        if ((r.n_runs && !r.part) || !r.out || r.n_q == 0)
             return hipErrorInvalidValue;
         const uint64_t rows = (uint64_t)r.n_q * p.n_q_heads;
         if (rows > width) width = rows;
         const uint64_t n_mt = ((uint64_t)r.n_q * G + 15u) >> 4;
         if (n_mt > max_mt) max_mt = (uint32_t)(n_mt > 0xFFFFFFFFull ? 0xFFFFFFFFull : n_mt);
         if (n_mt * p.n_kv_heads > tile_width) tile_width = n_mt * p.n_kv_heads;
-        if (r.n_chunks > max_units) max_units = r.n_chunks;
+        if (r.n_runs > max_units) max_units = r.n_runs;
     }
     if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
     if (check_only) return hipSuccess;

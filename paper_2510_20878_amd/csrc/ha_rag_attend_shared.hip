@@ -320,7 +320,7 @@ __global__ void __launch_bounds__(64 * W, 2) k6_attend_shared(const K6Params p)
     // declare 64 KiB at most statically)
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_bytes[];
     uint8_t (*lds)[W][kSharedBlockLds] = reinterpret_cast<uint8_t (*)[W][kSharedBlockLds]>(lds_bytes);
-    K6Chunk c = p.c[blockIdx.y];
+    K6Run c = p.run[blockIdx.y];
     AttendHdr hdr = {p.n_kv_heads, p.n_q_heads, p.layer, p.scale_log2};
     pin(c.k);
     pin(c.v);
@@ -332,7 +332,7 @@ __global__ void __launch_bounds__(64 * W, 2) k6_attend_shared(const K6Params p)
     pin(hdr.n_kv_heads);
     pin(hdr.n_q_heads);
     pin(hdr.scale_log2);
-    uint32_t run = c.run, more = c.more;  // the run's documents: this one, then descriptors more, more + 1, ..
+    uint32_t run = c.n_docs, more = c.more;  // the run's documents: this one, then descriptors more, more + 1, ..
     uint32_t first_block = c.first_block, end_block = c.end_block;  // where the run starts in its first and ends in its last
     pin(run);
     pin(more);
@@ -390,7 +390,7 @@ __global__ void __launch_bounds__(64 * W, 2) k6_attend_shared(const K6Params p)
         const uint8_t *dk = c.k, *dv = c.v;
         uint32_t T = c.n_tokens, dinfo = c.info;
         if (d) {
-            const K6Doc &cd = p.d[more + d - 1u];
+            const K6Doc &cd = p.doc[more + d - 1u];
             dk = cd.k;
             dv = cd.v;
             T = cd.n_tokens;
@@ -458,7 +458,7 @@ hipError_t prepare_k6_shared()
 
 hipError_t launch_k6_shared(K6Params &p, uint32_t waves, hipStream_t stream, bool check_only)
 {
-    if (p.n_chunks == 0) return hipSuccess;
+    if (p.n_runs == 0) return hipSuccess;
     if (waves != 2u && waves != 4u && waves != 8u) return hipErrorInvalidValue;
     uint32_t max_mt = 1;
     bool narrow = true;
@@ -468,7 +468,7 @@ hipError_t launch_k6_shared(K6Params &p, uint32_t waves, hipStream_t stream, boo
     if (width > 0x7FFFFFFFull) return hipErrorInvalidValue;
     p.mtw = 2;
     if (check_only) return hipSuccess;
-    dim3 grid((uint32_t)width, p.n_chunks);
+    dim3 grid((uint32_t)width, p.n_runs);
     const uint32_t lds_bytes = 2u * waves * kSharedBlockLds;
     if (waves == 2u) hipLaunchKernelGGL((k6_attend_shared<2>), grid, dim3(128), lds_bytes, stream, p);
     else if (waves == 4u) hipLaunchKernelGGL((k6_attend_shared<4>), grid, dim3(256), lds_bytes, stream, p);

@@ -128,10 +128,10 @@ struct K6Doc {
     uint32_t info;        // keys: Prec | log2(group) << 4; values: the same << 8
 };
 
-// A run: layout blocks first_block .. of its first document (described here), then `run` - 2
+// A run: layout blocks first_block .. of its first document (described here), then n_docs - 2
 // whole documents, then the blocks before end_block of its last one, all of one request.  One
 // row of workgroups takes a run and writes one record per (KV head, query tile) for it.
-struct K6Chunk {
+struct K6Run {
     const uint8_t *k;
     const uint8_t *v;
     const uint16_t *q;    // BF16 [n_q][n_q_heads][128] of the request
@@ -140,36 +140,36 @@ struct K6Chunk {
     uint32_t info;
     uint32_t n_q;         // query tokens of the request
     uint32_t pad;
-    uint32_t run;         // documents of the run (1 = this one only)
-    uint32_t more;        // index in K6Params::d of the run's second document; the third and
+    uint32_t n_docs;      // documents of the run (1 = this one only)
+    uint32_t more;        // index in K6Params::doc of the run's second document; the third and
                           // later ones follow it
     uint32_t first_block;
-    uint32_t end_block;   // of the run's last document; with run == 1 that is this one
+    uint32_t end_block;   // of the run's last document; with n_docs == 1 that is this one
 };
 
-constexpr uint32_t kAttendMaxRuns = kAttendArgBytes / sizeof(K6Chunk);
+constexpr uint32_t kAttendMaxRuns = kAttendArgBytes / sizeof(K6Run);
 constexpr uint32_t kAttendMaxDocs = kAttendArgBytes / sizeof(K6Doc);
 
 struct K6Params {
     uint32_t n_kv_heads, n_q_heads, layer;
-    uint32_t n_chunks;     // runs: c[0 .. n_chunks)
+    uint32_t n_runs;       // run[0 .. n_runs)
     uint32_t mtw;          // 16-row query tiles per workgroup: 1 or 2 (set by launch_k6)
     float scale_log2;      // sm_scale * log2(e)
-    uint32_t d_first;      // the runs' further documents: d[d_first .. d_end), behind the runs
-    uint32_t d_end;
+    uint32_t doc_first;    // the runs' further documents: doc[doc_first .. doc_end), behind the runs
+    uint32_t doc_end;
     union {                // two views of the same bytes
-        K6Chunk c[kAttendMaxRuns];
-        K6Doc d[kAttendMaxDocs];
+        K6Run run[kAttendMaxRuns];
+        K6Doc doc[kAttendMaxDocs];
     };
-    // index in d of the first short descriptor behind n runs
-    static constexpr uint32_t docs_behind(uint32_t n) { return (n * (uint32_t)sizeof(K6Chunk) + (uint32_t)sizeof(K6Doc) - 1u) / (uint32_t)sizeof(K6Doc); }
+    // index in doc of the first short descriptor behind n runs
+    static constexpr uint32_t docs_behind(uint32_t n) { return (n * (uint32_t)sizeof(K6Run) + (uint32_t)sizeof(K6Doc) - 1u) / (uint32_t)sizeof(K6Doc); }
 };
 
 struct K7Req {
-    const float *part;    // records [n_chunks][n_kv_heads][n_mtiles]; n_chunks counts runs
+    const float *part;    // records [n_runs][n_kv_heads][n_mtiles]
     float *out;           // binary32 [n_q][n_q_heads][128]
     float *lse;           // binary32 [n_q][n_q_heads] or null
-    uint32_t n_q, n_chunks, pad[2];
+    uint32_t n_q, n_runs, pad[2];
 };
 
 constexpr uint32_t kMaxMergeReqs = 64;
@@ -178,8 +178,8 @@ struct K7Params {
     K7Req r[kMaxMergeReqs];
 };
 
-// Partial attention of every run of the launch: runs c[0 .. n_chunks), their further documents
-// d[d_first .. d_end) with d_first = docs_behind(n_chunks), each run's in a row (`more`).  The
+// Partial attention of every run of the launch: run[0 .. n_runs), their further documents
+// doc[doc_first .. doc_end) with doc_first = docs_behind(n_runs), each run's in a row (`more`).  The
 // grid has one row of workgroups per run and none without work: rows of workgroups that exit
 // at once, in a regular pattern, were measured to halve the workgroups a CU runs side by side.
 // launch_k6 is for requests of at most two query tiles (sets mtw): a workgroup's two waves take
