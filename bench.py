@@ -339,6 +339,7 @@ def cpu_baseline_attend(T, g, mix, n_q, n_qh, H, min_seconds, seed):
     from paper_2510_20878_amd import workloads as wl
 
     D, G, n = 128, n_qh // H, len(mix)
+    tags, mix = list(mix), [orc_name(b) for b in mix]
     slices, dt, nbytes = 0, 0.0, 0
     rng = np.random.Generator(np.random.PCG64(seed))
     while dt < min_seconds and slices < 64:
@@ -352,7 +353,7 @@ def cpu_baseline_attend(T, g, mix, n_q, n_qh, H, min_seconds, seed):
         nbytes += sum(len(p) for p in packed) + q.size * 2 + n_q * G * (D + 1) * 4
         slices += 1
     return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"{slices} (layer, KV head) slices of one request ({n} chunks x {T} tokens, bits {mix}): "
+            "sample": f"{slices} (layer, KV head) slices of one request ({n} chunks x {T} tokens, tags {tags}): "
                       f"oracle dequantize + oracle attention for {G} query heads x {n_q} token(s), "
                       f"{dt:.1f} s of one host core (numpy may use more for its products)",
             "kv_tokens_per_s": slices * n * T / (H * 32) / dt}
