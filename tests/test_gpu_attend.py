@@ -350,7 +350,7 @@ def test_attend_can_be_captured_in_a_hip_graph_and_replayed(n_q):
 
 def test_llama3_8b_batch_of_32_requests_sampled_heads_match_oracle():
     """The batch the benchmark times: 32 requests x 10 chunks x 512 tokens of the 8B shape in
-    one call (one partial-attention launch over 320 chunks), one query token each.  Sampled
+    one call (one partial-attention launch over 320 chunks), one query token each, then 64 each.  Sampled
     (request, layer, KV head) triples are recomputed by the oracle from the source words."""
     L, H, D, T, g, n_qh, R = 32, 8, 128, 512, 128, 32, 32
     G = n_qh // H
@@ -393,6 +393,33 @@ def test_llama3_8b_batch_of_32_requests_sampled_heads_match_oracle():
             ref_out, ref_lse, spread = A.attend(cache, 0, 10 * T, qh, scale)
             check(out_d[r:r + 1, h * G:(h + 1) * G].cpu().numpy(), lse_d[r:r + 1, h * G:(h + 1) * G].cpu().numpy(),
                   ref_out, ref_lse, spread, score_bound(cache, 0, 10 * T, qh, scale, 1))
+    # the same batch with the 64 query tokens of a question per request (the benchmark's other
+    # attention leg): 256 query rows per KV head, eight-wave workgroups, one run per request and head
+    n_q = 64
+    qw = q_words(R * n_q, n_qh, D, 902).reshape(R, n_q, n_qh, D)
+    q_d = torch.from_numpy(qw.view(np.int16)).cuda()
+    out_d = torch.full((R, n_q, n_qh, D), float("nan"), dtype=torch.float32, device="cuda")
+    lse_d = torch.full((R, n_q, n_qh), float("nan"), dtype=torch.float32, device="cuda")
+    call = [([(packs[10 * r + k], T, precs[10 * r + k], g) for k in range(10)], q_d[r], out_d[r], lse_d[r], n_q)
+            for r in range(R)]
+    lists = ctx.attend_lists(call)
+    nbytes = ctx.attend_workspace_bytes(lists, n_qh)
+    ws = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    layer = 23
+    ctx.attend_packed(lists, layer, n_qh, scale, ws, nbytes)
+    torch.cuda.synchronize()
+    assert not torch.isnan(out_d).any() and not torch.isnan(lse_d).any()
+    for r, h in [(0, H - 1), (int(rng.integers(R)), int(rng.integers(H)))]:
+        cache = np.zeros((1, 2, 1, 10 * T, D), np.uint16)
+        for k in range(10):
+            bits = B.BITS[precs[10 * r + k]]
+            src_kv = srcs[10 * r + k][layer, :, h].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+            ref_pack, _ = codec.quantize_pack_chunk(src_kv.reshape(1, 2, 1, T, D), bits, g)
+            codec.dequant_scatter_chunk(ref_pack, (1, 1, D), T, bits, g, cache, k * T)
+        qh = np.ascontiguousarray(qw[r, :, h * G:(h + 1) * G])
+        ref_out, ref_lse, spread = A.attend(cache, 0, 10 * T, qh, scale)
+        check(out_d[r, :, h * G:(h + 1) * G].cpu().numpy(), lse_d[r, :, h * G:(h + 1) * G].cpu().numpy(),
+              ref_out, ref_lse, spread, score_bound(cache, 0, 10 * T, qh, scale, 1))
     ctx.destroy()
 
 
