@@ -419,9 +419,10 @@ typedef struct ha_rag_attend_request {
  * <= HA_RAG_MAX_REQUEST_CHUNKS.  n_q_heads a multiple of H, at most 64 H.  sm_scale > 0.
  * workspace: device memory, 16-byte aligned, of at least the size
  * ha_rag_attend_workspace_bytes returns for the same lists (it holds partial results and
- * may be reused by the next call on the same stream); ENOSPC if smaller.
+ * may be reused by the next call on the same stream; the size may be 0, and the pointer then
+ * null, when no request needs a partial result); ENOSPC if smaller.
  * EFORMAT unless head_dim is 128.
- * Like ha_rag_load_packed the call only launches kernels on `stream`: one per 480 runs of
+ * Like ha_rag_load_packed the call only launches kernels on `stream`: one per 512 runs of
  * blocks (a workgroup's share of a request: a piece of a document, or for requests of many
  * query rows a range of blocks across documents) plus one per 64 requests. */
 int ha_rag_attend_packed(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks,
@@ -436,7 +437,7 @@ int ha_rag_attend_packed(ha_rag_ctx *ctx, const ha_rag_packed_chunk *chunks,
  * library's device code (each GPU the library runs on holds its own copy until the process
  * ends; its address on the current device is looked up once, in ha_rag_create or at the first
  * call on that device).  The call allocates nothing, neither on the device nor on the host: its
- * plan lives on the stack (about 100 KiB with the launch descriptors), which bounds what one
+ * plan lives on the stack (about 120 KiB with the launch descriptors), which bounds what one
  * call may hold.
  * ENOSPC, before anything is enqueued, for more than HA_RAG_ATTEND_STATIC_MAX_REQUESTS requests,
  * more than HA_RAG_ATTEND_STATIC_MAX_DOCS documents (a whole chunk, or a keys-only chunk with its

@@ -46,6 +46,7 @@ struct Plan {               // one request
     uint32_t run_blocks = 0;   // layout blocks per run (what one workgroup takes)
     uint64_t all_blocks = 0;   // layout blocks of all its documents
     uint32_t n_runs = 0;       // records per (KV head, tile)
+    uint32_t final = 0;        // one run of the shared kernel is all there is: it writes the output itself
     uint64_t part_floats = 0;  // offset of its records in the workspace
 };
 
@@ -245,8 +246,9 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
         Plan &pl = plans[r];
         pl.run_blocks = !pl.shared ? piece : run_blocks > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)(run_blocks ? run_blocks : 1u);
         pl.n_runs = count_runs(pl, docs->data + pl.first_doc);
+        pl.final = pl.shared && pl.n_runs == 1u;  // no record, no merge
         pl.part_floats = total;
-        total += (uint64_t)pl.n_runs * H * pl.n_mt * kAttendRecFloats;
+        if (!pl.final) total += (uint64_t)pl.n_runs * H * pl.n_mt * kAttendRecFloats;
     }
     if (total * 4ull > (1ull << 40)) return HA_RAG_EINVAL;
     *floats = total;
@@ -358,11 +360,12 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
                 d.k = doc_k(first);
                 d.v = doc_v(first);
                 d.q = static_cast<const uint16_t *>(rq.q);
-                d.part = ws + pl.part_floats + (uint64_t)run_no * H * pl.n_mt * kAttendRecFloats;
+                d.part = pl.final ? rq.out : ws + pl.part_floats + (uint64_t)run_no * H * pl.n_mt * kAttendRecFloats;
+                d.final = pl.final;
+                d.lse = pl.final ? rq.lse : nullptr;
                 d.n_tokens = first.n_tokens;
                 d.info = first.info;
                 d.n_q = rq.n_q;
-                d.pad = 0;
                 d.n_docs = run.n_docs;
                 d.more = later;
                 d.first_block = run.first_block;
@@ -381,6 +384,7 @@ int attend_locked(ha_rag_ctx *c, PlanStore ps, const ha_rag_packed_chunk *chunks
     mp.n_kv_heads = H;
     mp.n_q_heads = n_q_heads;
     for (uint32_t r = 0; r < n_reqs; ++r) {
+        if (plans[r].final) continue;  // written by the run's own workgroups
         K7Req &d = mp.r[mp.n_reqs++];
         d.part = ws + plans[r].part_floats;
         d.out = reqs[r].out;

@@ -410,7 +410,8 @@ hipError_t check_k6_args(const K6Params &p, uint32_t *max_mt, bool *narrow)
     for (uint32_t i = 0; i < p.n_runs; ++i) {
         const K6Run &c = p.run[i];
         if (!doc_ok(c.k, c.v, c.n_tokens, c.info) || c.n_docs == 0 || !c.q || !c.part || c.n_q == 0 ||
-            ((uintptr_t)c.q & 15u) || ((uintptr_t)c.part & 15u) || (uint64_t)c.n_q * G > 0xFFFFFFull)
+            ((uintptr_t)c.q & 15u) || ((uintptr_t)c.part & 15u) || (uint64_t)c.n_q * G > 0xFFFFFFull ||
+            c.final > 1u || (!c.final && c.lse) || ((uintptr_t)c.lse & 3u))
             return hipErrorInvalidValue;
         if (c.n_docs > 1u && (c.more != next || c.n_docs - 1u > p.doc_end - next)) return hipErrorInvalidValue;
         next += c.n_docs - 1u;
@@ -434,7 +435,7 @@ hipError_t launch_k6(K6Params &p, hipStream_t stream, bool check_only)
     const hipError_t e = check_k6_args(p, &max_mt, &narrow);
     if (e != hipSuccess) return e;
     for (uint32_t i = 0; i < p.n_runs; ++i)
-        if (p.run[i].n_docs != 1u) return hipErrorInvalidValue;  // this kernel's runs stay inside one document
+        if (p.run[i].n_docs != 1u || p.run[i].final) return hipErrorInvalidValue;  // this kernel's runs stay inside one document and always leave records
     // Two tiles (32 query rows) per workgroup is the most that still runs two waves per SIMD;
     // four tiles at one wave per SIMD measured 35 % slower than two passes of two.
     p.mtw = max_mt >= 2 ? 2u : 1u;

@@ -411,9 +411,13 @@ __global__ void __launch_bounds__(64 * W, 2) k6_attend_shared(const K6Params p)
         }
     }
 
-    // ---- the wave's records, straight from its registers: lane (c_, n_) holds rows
+    // ---- the wave's results, straight from its registers: lane (c_, n_) holds rows
     // 4 c_ + jj, dims 8 n_ + pp of each tile
     if (!active) return;
+    uint32_t final = c.final;
+    pin(final);
+    const float *lse_ptr = c.lse;
+    pin(lse_ptr);
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
         const uint32_t tile = tile0 + mt;
@@ -421,6 +425,36 @@ __global__ void __launch_bounds__(64 * W, 2) k6_attend_shared(const K6Params p)
         float l_tot = st.l_run[mt];
         l_tot += __shfl_xor(l_tot, 16);
         l_tot += __shfl_xor(l_tot, 32);
+        if (final) {
+            // The run is everything the request attends to: what the merge would do with its one
+            // record is done here.  l_tot of row n_ is in every lane of column n_; the rows this
+            // lane holds are 4 c_ + jj.
+            gfloats out = (gfloats)c.part;
+#pragma unroll
+            for (uint32_t jj = 0; jj < 4; ++jj) {
+                const uint32_t row = 4u * ln.c_ + jj, mrow = tile * 16u + row;
+                const float l_row = __shfl(l_tot, (int)row);
+                if (mrow >= M) continue;
+                const uint32_t qt = mrow / G, gq = mrow - qt * G;
+                f32x4 __attribute__((address_space(1))) *dst = (f32x4 __attribute__((address_space(1))) *)(
+                    out + ((uint64_t)qt * hdr.n_q_heads + h * G + gq) * 128u + 8u * ln.n_);
+                f32x4 w0, w1;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    w0[e] = l_row > 0.0f ? st.O[mt][e][jj] / l_row : 0.0f;
+                    w1[e] = l_row > 0.0f ? st.O[mt][4 + e][jj] / l_row : 0.0f;
+                }
+                dst[0] = w0;
+                dst[1] = w1;
+            }
+            const uint32_t mrow = tile * 16u + ln.n_;
+            if (ln.c_ == 0 && lse_ptr && mrow < M) {
+                const uint32_t qt = mrow / G, gq = mrow - qt * G;
+                ((gfloats)lse_ptr)[(uint64_t)qt * hdr.n_q_heads + h * G + gq] =
+                    l_tot > 0.0f ? (st.m_run[mt] + __builtin_log2f(l_tot)) * 0.69314718055994531f : neg_inf();
+            }
+            continue;
+        }
         gfloats rec = (gfloats)c.part + ((uint64_t)h * n_mt + tile) * kAttendRecFloats;
 #pragma unroll
         for (uint32_t jj = 0; jj < 4; ++jj) {

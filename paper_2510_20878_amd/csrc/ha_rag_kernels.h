@@ -113,11 +113,11 @@ constexpr uint32_t kAttendMaxRunBlocks = 128;  // and a piece of one document is
 constexpr uint32_t kAttendTargetGroups = 2048; // pieces are halved while a launch has fewer workgroups
 constexpr uint32_t kChipCUs = 256;            // compute units of the one GPU this library is built for
 constexpr uint32_t kAttendWaves = 2;          // waves of a workgroup; they interleave its blocks
-// Descriptors travel in the kernel argument buffer (30 KiB; launches with arguments of 32 KiB
-// were checked to work on this runtime).  A workgroup fetches its run's descriptor in one go
+// Descriptors travel in the kernel argument buffer (36 KiB; launches with arguments of up to
+// 62.5 KiB were checked to work on this runtime).  A workgroup fetches its run's descriptor in one go
 // and one short descriptor per further document: the argument buffer may live in host memory,
 // where every dependent read costs a trip over the link.
-constexpr uint32_t kAttendArgBytes = 30720;
+constexpr uint32_t kAttendArgBytes = 36864;
 
 // One document: its keys and its values, which may come from one whole chunk or from a
 // keys-only and a values-only chunk of different formats.
@@ -135,16 +135,19 @@ struct K6Run {
     const uint8_t *k;
     const uint8_t *v;
     const uint16_t *q;    // BF16 [n_q][n_q_heads][128] of the request
-    float *part;          // the run's records [n_kv_heads][n_mtiles]
+    float *part;          // the run's records [n_kv_heads][n_mtiles]; or, if `final`, the request's
+                          // output, binary32 [n_q][n_q_heads][128]
     uint32_t n_tokens;
     uint32_t info;
     uint32_t n_q;         // query tokens of the request
-    uint32_t pad;
+    uint32_t final;       // the run is all the request has (launch_k6_shared only): the workgroups
+                          // normalise and write out and lse themselves, no record, no merge
     uint32_t n_docs;      // documents of the run (1 = this one only)
     uint32_t more;        // index in K6Params::doc of the run's second document; the third and
                           // later ones follow it
     uint32_t first_block;
     uint32_t end_block;   // of the run's last document; with n_docs == 1 that is this one
+    float *lse;           // final runs: binary32 [n_q][n_q_heads] or null
 };
 
 constexpr uint32_t kAttendMaxRuns = kAttendArgBytes / sizeof(K6Run);

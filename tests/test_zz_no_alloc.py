@@ -92,7 +92,9 @@ def test_static_scratch_entry_refuses_what_exceeds_its_limits():
     shape = (1, 1, 128)
     ctx = B.Context(*shape, 4096)
     pk = torch.zeros(ctx.chunk_bytes(B.PREC_INT4, 4096), dtype=torch.uint8, device="cuda")
-    n_q, n_qh = 2048, 64
+    # 2,048 query tiles in 128 groups of eight-wave workgroups: two runs of the document's 256 blocks
+    # fill the chip's 256 places, and two records per tile are 34 MB (one run would need no record at all)
+    n_q, n_qh = 1024, 32
     q = torch.zeros((n_q, n_qh, 128), dtype=torch.int16, device="cuda")
     out = torch.zeros((n_q, n_qh, 128), dtype=torch.float32, device="cuda")
     big = [([(pk, 4096, B.PREC_INT4, 128)], q, out, None, n_q)]
