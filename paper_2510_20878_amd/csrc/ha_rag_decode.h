@@ -107,8 +107,11 @@ __device__ __forceinline__ float decode_gse8(uint32_t w, uint32_t fields, int b,
 template <int B>
 __device__ __forceinline__ uint32_t decode_pair_gse8(uint32_t w, uint32_t fields, int base, int top)
 {
-    const uint32_t mag = pack_bf16(decode_gse8(w, fields, B, base, top),
-                                   decode_gse8(w, fields, B + 1, base, top));
+    // field * 2^n has three significant bits: the upper halves of the two binary32 results are
+    // the BF16 values, no rounding conversion needed
+    const uint32_t mag = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, decode_gse8(w, fields, B + 1, base, top)),
+                                               __builtin_bit_cast(uint32_t, decode_gse8(w, fields, B, base, top)),
+                                               0x07060302u);
     constexpr uint32_t sel = 0x0Cu | (uint32_t(B) << 8) | (0x0Cu << 16) | (uint32_t(B + 1) << 24);
     return mag | (__builtin_amdgcn_perm(0u, w, sel) & 0x80008000u);
 }
