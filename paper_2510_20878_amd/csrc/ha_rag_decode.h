@@ -68,7 +68,7 @@ __device__ __forceinline__ u32x4 dequant_octet8(uint32_t c0, uint32_t c1, uint32
 }
 
 // 8 FP8 codes (two dwords) of one plane -> 8 BF16.  The hardware conversion to fp32 is
-// exact and every FP8 value is a BF16 value, so the BF16 rounding changes nothing.
+// exact and every FP8 value is a BF16 value, so no rounding conversion is needed.
 template <bool E5M2>
 __device__ __forceinline__ u32x4 decode_octet_fp8(uint32_t c0, uint32_t c1)
 {
@@ -84,11 +84,17 @@ __device__ __forceinline__ u32x4 decode_octet_fp8(uint32_t c0, uint32_t c1)
         c = __builtin_amdgcn_cvt_pk_f32_fp8(c1, false);
         d = __builtin_amdgcn_cvt_pk_f32_fp8(c1, true);
     }
+    // the upper halves of the binary32 results are the BF16 values: a byte permute per pair
+    // (the elements are copied to scalars first: a bit cast of a vector element reads element 0)
+    auto upper = [](f32x2 v) {
+        const float lo = v.x, hi = v.y;
+        return __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, hi), __builtin_bit_cast(uint32_t, lo), 0x07060302u);
+    };
     u32x4 r;
-    r.x = pack_bf16(a.x, a.y);
-    r.y = pack_bf16(b.x, b.y);
-    r.z = pack_bf16(c.x, c.y);
-    r.w = pack_bf16(d.x, d.y);
+    r.x = upper(a);
+    r.y = upper(b);
+    r.z = upper(c);
+    r.w = upper(d);
     return r;
 }
 
