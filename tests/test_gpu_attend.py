@@ -62,8 +62,9 @@ def score_bound(cache, layer, n_kv, qw, scale, H):
     return out
 
 
-def run_case(shape, reqs, layer, n_qh, scale, seed, g8=128, g4=128, max_tokens=None):
-    """reqs: list of (tokens list, precs list, n_q).  Chunk i of a request is drawn from seed."""
+def run_case(shape, reqs, layer, n_qh, scale, seed, g8=128, g4=128, max_tokens=None, want_lse=True):
+    """reqs: list of (tokens list, precs list, n_q).  Chunk i of a request is drawn from seed.
+    want_lse=False: the requests ask for no log-sum-exp (a null pointer); only out is checked."""
     L, H, D = shape
     T_max = max_tokens or max([t for r in reqs for t in r[0]] + [16])
     ctx = B.Context(L, H, D, T_max, group_int8=g8, group_int4=g4)
@@ -86,7 +87,7 @@ def run_case(shape, reqs, layer, n_qh, scale, seed, g8=128, g4=128, max_tokens=N
         packs_d = [dev_u8(p) if len(p) else None for p in packs]
         keep += [q_d, out_d, lse_d, packs_d]
         call.append(([(pd, t, p, grp.get(p, 0)) for pd, t, p in zip(packs_d, tokens, precs)],
-                     q_d, out_d, lse_d, n_q))
+                     q_d, out_d, lse_d if want_lse else None, n_q))
         refs.append((packs, tokens, precs, qw, out_d, lse_d))
     nbytes = ctx.attend_workspace_bytes(call, n_qh)
     ws = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device="cuda")
@@ -97,12 +98,15 @@ def run_case(shape, reqs, layer, n_qh, scale, seed, g8=128, g4=128, max_tokens=N
         n_kv = sum(tokens)
         out, lse = out_d.cpu().numpy(), lse_d.cpu().numpy()
         if n_kv == 0:
-            assert np.all(out == 0) and np.all(np.isneginf(lse))
+            assert np.all(out == 0) and (np.all(np.isneginf(lse)) if want_lse else np.all(np.isnan(lse)))
             continue
         live = [i for i, t in enumerate(tokens) if t]
         cache, _ = codec.load_chunks(packs, shape, tokens, [ORC[p] for p in precs],
                                      [grp.get(p, 128) for p in precs], live)
         ref_out, ref_lse, spread = A.attend(cache, layer, n_kv, qw, scale)
+        if not want_lse:
+            assert np.all(np.isnan(lse))  # untouched
+            lse = ref_lse
         w = check(out, lse, ref_out, ref_lse, spread, score_bound(cache, layer, n_kv, qw, scale, H))
         worst = (max(worst[0], w[0]), max(worst[1], w[1]))
     ctx.destroy()
@@ -199,6 +203,17 @@ def test_many_rows_kernel_with_blocks_that_have_no_partner(tokens):
     the first round of a workgroup (nothing decoded yet) and in later ones."""
     precs = [ALL[(3 * i + len(tokens)) % 6] for i in range(len(tokens))]
     run_case((1, 2, 128), [(tokens, precs, 40), (tokens[::-1], precs[::-1], 9)], 0, 8, 0.1, 130 + len(tokens))
+
+
+def test_requests_that_ask_for_no_log_sum_exp():
+    """lse may be null: in the merge kernels (a decode request, a many-rows request of several
+    runs) and in the many-rows workgroups that write their request's output themselves (one run),
+    next to an empty request."""
+    reqs = [([50, 33], [B.PREC_INT4, B.PREC_16], 1),
+            ([700, 260], [B.PREC_INT8, B.PREC_GSE8], 24),
+            ([40], [B.PREC_FP8_E4M3], 30),
+            ([], [], 2)]
+    run_case((1, 2, 128), reqs, 0, 4, 0.09, 140, want_lse=False)
 
 
 def test_one_call_with_requests_for_both_attention_kernels():
