@@ -204,8 +204,7 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
         pl.all_blocks = 0;
         for (uint32_t i = 0; i < pl.n_docs; ++i) pl.all_blocks += ((*docs)[pl.first_doc + i].n_tokens + 15u) / 16u;
     }
-    uint32_t piece = kAttendMaxRunBlocks;
-    for (;; piece >>= 1) {
+    auto groups_at = [&](uint32_t piece) {  // workgroups of the one/two-tile kernel with pieces this long
         uint64_t groups = 0;
         for (uint32_t r = 0; r < n_reqs; ++r) {
             const Plan &pl = plans[r];
@@ -215,8 +214,14 @@ int plan_attend(ha_rag_ctx *c, const ha_rag_packed_chunk *chunks, const ha_rag_a
                 runs += (((*docs)[pl.first_doc + i].n_tokens + 15u) / 16u + piece - 1u) / piece;
             groups += runs * H * tile_groups(pl, waves);
         }
-        if (groups >= kAttendTargetGroups || piece == kAttendMinRunBlocks) break;
-    }
+        return groups;
+    };
+    uint32_t piece = kAttendMaxRunBlocks;
+    while (piece > kAttendMinRunBlocks && groups_at(piece) < kAttendTargetGroups) piece >>= 1;
+    // A call of so few workgroups that even twice as many run side by side (four per CU) is
+    // bound by how long one of them takes: halve once more (one request of 10 x 512 tokens:
+    // 13.7 against 14.7 us; with two requests, 1,280 workgroups, it would cost 1.5 us).
+    if (piece == kAttendMinRunBlocks && groups_at(piece / 2u) <= 4ull * kChipCUs) piece /= 2u;
     // The shared kernel: a run crosses document boundaries (records rival the packed bytes once
     // a request has hundreds of query rows; equal runs also finish together whatever the
     // documents' lengths).  Workgroups of one size finish in rounds of as many as the chip holds

@@ -108,7 +108,8 @@ hipError_t launch_k8(const void *src, const void *packed, uint32_t n_tiles, uint
 // sum l[16] of 2^(score - m).
 constexpr uint32_t kAttendHeadDim = 128;
 constexpr uint32_t kAttendRecFloats = 16 * 128 + 32;
-constexpr uint32_t kAttendMinRunBlocks = 8;    // a workgroup takes at least this many layout blocks (16 tokens each),
+constexpr uint32_t kAttendMinRunBlocks = 8;    // a workgroup takes at least this many layout blocks (16 tokens each;
+                                               // half as many in a call of very few workgroups),
 constexpr uint32_t kAttendMaxRunBlocks = 128;  // and a piece of one document is at most this long (a power of two)
 constexpr uint32_t kAttendTargetGroups = 2048; // pieces are halved while a launch has fewer workgroups
 constexpr uint32_t kChipCUs = 256;            // compute units of the one GPU this library is built for

@@ -133,8 +133,8 @@ def test_smaller_groups(g):
 
 
 def test_a_chunk_cut_into_pieces_and_a_sharp_softmax():
-    # few workgroups, so the shortest pieces: 1100 tokens = 69 blocks = 8 pieces of 8 blocks and one of 5,
-    # 513 tokens = 33 blocks = 4 pieces of 7 and one of 5, a record each; a large scale makes few keys
+    # few workgroups, so the shortest pieces: 1100 tokens = 69 blocks = 17 pieces of 4 blocks and one of 1,
+    # 513 tokens = 33 blocks = 8 pieces of 4 and one of 1, a record each; a large scale makes few keys
     # dominate, so the running maximum keeps moving and accumulated sums are rescaled many times
     run_case((1, 1, 128), [([1100, 513], [B.PREC_INT4, B.PREC_INT8], 4)], 0, 4, 0.5, 40)
 

@@ -882,13 +882,13 @@ def test_attend_workspace_size_and_argument_checks():
     # records: runs x KV heads x 16-row query tiles.  With at most two query tiles a run is a
     # piece of one document: equal pieces, none longer than 2048 tokens; that bound is halved
     # (down to 128 tokens) while the call has fewer than 2048 workgroups (runs x KV heads x pairs
-    # of query tiles)
-    assert ctx.attend_workspace_bytes([req([ch(512), ch(100)], 1)], 8) == (4 + 1) * 2 * 1 * REC
-    assert ctx.attend_workspace_bytes([req([ch(512), ch(0)], 5)], 8) == 4 * 2 * 2 * REC
+    # of query tiles), and once more (64 tokens) if the call then still has at most 1024
+    assert ctx.attend_workspace_bytes([req([ch(512), ch(100)], 1)], 8) == (8 + 2) * 2 * 1 * REC
+    assert ctx.attend_workspace_bytes([req([ch(512), ch(0)], 5)], 8) == 8 * 2 * 2 * REC
     c2 = B.Context(4, 2, 128, 2000, group_int8=128, group_int4=64, dry_run=True)
-    # 1100 tokens = 69 blocks: nine pieces of 8 blocks (the last one 5)
+    # 1100 tokens = 69 blocks: 18 pieces of 4 blocks (the last one 1)
     assert c2.attend_workspace_bytes([req([ch(1100), ch(10)], 4), req([], 1), req([ch(16)], 9)], 4) == \
-        ((9 + 1) * 2 * 1 + 0 + 1 * 2 * 2) * REC
+        ((18 + 1) * 2 * 1 + 0 + 1 * 2 * 2) * REC
     # 300 chunks x 2 heads x 4 pieces of at most 512 tokens make 2400 workgroups: no finer pieces
     big = [req([ch(2000)] * 100, 1) for _ in range(3)]
     assert c2.attend_workspace_bytes(big, 4) == 300 * 4 * 2 * 1 * REC
@@ -924,8 +924,8 @@ def test_attend_workspace_size_and_argument_checks():
     # keys and values of two documents in any interleaving, formats of their own, next to a whole chunk
     pairs = [req([ch(64, part=B.PART_V), ch(64, B.PREC_16, 0, B.PART_K), ch(100), ch(40, B.PREC_INT8, 128, B.PART_K),
                   ch(40, part=B.PART_V)], 2)]
-    assert ctx.attend_workspace_bytes(pairs, 8) == 3 * 2 * 1 * REC     # three documents, one run each
-    ctx.attend_packed(pairs, 0, 8, 0.1, P, 3 * 2 * REC)
+    assert ctx.attend_workspace_bytes(pairs, 8) == 4 * 2 * 1 * REC     # three documents, the one of 7 blocks in two pieces
+    ctx.attend_packed(pairs, 0, 8, 0.1, P, 4 * 2 * REC)
     fails(B.EFORMAT, [req([ch(16, g=48)], 1)])
     fails(B.EFORMAT, [req([ch(16, p=9)], 1)])
     ctx.destroy()
